@@ -1,0 +1,215 @@
+"""ctypes view of libpsb_oracle.so (TEST INFRASTRUCTURE ONLY).
+
+numpy in, numpy out; no arithmetic of the method happens here.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build_oracle
+
+ZERO, NORMAL, SUBNORMAL, NONFINITE = 0, 1, 2, 3
+OK, ERR_ARG, ERR_VALUE, ERR_OVERFLOW_UNSAFE = 0, -1, -3, -4
+
+
+class WInfo(C.Structure):
+    _fields_ = [("e_top", C.c_int32), ("e_min", C.c_int32),
+                ("n_zero", C.c_int64), ("n_flushed", C.c_int64), ("n_live", C.c_int64)]
+
+
+class Weights(C.Structure):
+    _fields_ = [("oc", C.c_int32), ("K", C.c_int32),
+                ("sign", C.POINTER(C.c_int8)), ("shift", C.POINTER(C.c_int32)),
+                ("p", C.POINTER(C.c_double)), ("info", WInfo)]
+
+
+class WShape(C.Structure):
+    _fields_ = [("oc", C.c_int32), ("cin", C.c_int32), ("kh", C.c_int32),
+                ("kw", C.c_int32), ("groups", C.c_int32)]
+
+
+class Geom(C.Structure):
+    _fields_ = [("n", C.c_int32), ("h", C.c_int32), ("w", C.c_int32),
+                ("stride_h", C.c_int32), ("stride_w", C.c_int32),
+                ("pad_h", C.c_int32), ("pad_w", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = build_oracle.ensure_built()
+        L = C.CDLL(path)
+        L.psbo_decode.argtypes = [C.c_float, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
+        L.psbo_decode.restype = C.c_int
+        L.psbo_philox4x32_10.argtypes = [C.POINTER(C.c_uint32)] * 3
+        L.psbo_philox4x32_10.restype = None
+        L.psbo_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
+        L.psbo_uniform.restype = C.c_uint32
+        L.psbo_quantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                    C.POINTER(Weights)]
+        L.psbo_quantize.restype = C.c_int
+        L.psbo_weights_free.argtypes = [C.POINTER(Weights)]
+        L.psbo_weights_free.restype = None
+        L.psbo_linear.argtypes = [C.POINTER(Weights), C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, C.c_uint32,
+                                  C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
+        L.psbo_linear.restype = C.c_int
+        L.psbo_conv2d.argtypes = [C.POINTER(Weights), C.POINTER(WShape), C.c_void_p, C.POINTER(Geom),
+                                  C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32,
+                                  C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        L.psbo_conv2d.restype = C.c_int
+        L.psbo_rescale.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                   C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.psbo_rescale.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code):
+        super().__init__(f"oracle status {code}")
+        self.code = code
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def decode(w):
+    """(class, s, e, p) of one binary32 weight."""
+    s, e, p = C.c_int32(0), C.c_int32(0), C.c_double(0.0)
+    cls = lib().psbo_decode(C.c_float(float(np.float32(w))), C.byref(s), C.byref(e), C.byref(p))
+    return cls, s.value, e.value, p.value
+
+
+def philox(ctr, key):
+    c = (C.c_uint32 * 4)(*[int(v) & 0xFFFFFFFF for v in ctr])
+    k = (C.c_uint32 * 2)(*[int(v) & 0xFFFFFFFF for v in key])
+    out = (C.c_uint32 * 4)()
+    lib().psbo_philox4x32_10(c, k, out)
+    return [int(v) for v in out]
+
+
+def uniform(seed, layer_id, o, k, s):
+    return int(lib().psbo_uniform(int(seed), int(layer_id), int(o), int(k), int(s)))
+
+
+class QWeights:
+    """Quantised layer held by the oracle; arrays are numpy views, [oc, K]."""
+
+    def __init__(self, w, exp_bits=0, x_absmax=127, s_max=16):
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        oc = w.shape[0]
+        K = int(np.prod(w.shape[1:]))
+        self._q = Weights()
+        rc = lib().psbo_quantize(_ptr(w), oc, K, exp_bits, x_absmax, s_max, C.byref(self._q))
+        if rc != OK:
+            self._q = None
+            raise OracleError(rc)
+        n = oc * K
+        self.oc, self.K = oc, K
+        self.sign = np.ctypeslib.as_array(self._q.sign, shape=(n,)).reshape(oc, K)
+        self.shift = np.ctypeslib.as_array(self._q.shift, shape=(n,)).reshape(oc, K)
+        self.p = np.ctypeslib.as_array(self._q.p, shape=(n,)).reshape(oc, K)
+        i = self._q.info
+        self.e_top, self.e_min = i.e_top, i.e_min
+        self.n_zero, self.n_flushed, self.n_live = i.n_zero, i.n_flushed, i.n_live
+        self.s_max = s_max
+        self.shape = w.shape
+
+    def __del__(self):
+        if getattr(self, "_q", None) is not None:
+            self.sign = self.shift = self.p = None
+            lib().psbo_weights_free(C.byref(self._q))
+            self._q = None
+
+    def represented(self):
+        """The real numbers the encoding stands for: s 2^e (1+p); 0 when not live."""
+        return self.sign.astype(np.float64) * np.ldexp(1.0 + self.p, self.shift + self.e_min)
+
+
+def linear(q, x, S, seed=0, layer_id=0, u_table=None):
+    """acc[B, OC] (int32), number of outputs whose exact sum leaves int32."""
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    B = x.shape[0]
+    assert x.shape[1] == q.K
+    acc = np.zeros((B, q.oc), dtype=np.int32)
+    over = C.c_int64(0)
+    if u_table is not None:
+        u_table = np.ascontiguousarray(u_table, dtype=np.uint32)
+        assert u_table.size == B * q.oc * q.K * S
+    rc = lib().psbo_linear(C.byref(q._q), _ptr(x), B, S, int(seed), int(layer_id), _ptr(u_table), _ptr(acc),
+                           C.byref(over))
+    if rc != OK:
+        raise OracleError(rc)
+    return acc, over.value
+
+
+def out_hw(h, w, kh, kw, stride, pad):
+    sh, sw = stride
+    ph, pw = pad
+    return (h + 2 * ph - kh) // sh + 1, (w + 2 * pw - kw) // sw + 1
+
+
+def conv2d(q, wshape, x, stride=(1, 1), pad=(0, 0), S=None, s_max=None, budget_to=None, budget_from=None,
+           seed=0, layer_id=0, points=None, acc_in=None):
+    """wshape = (oc, cin, kh, kw, groups); x int8 [n, cin, h, w].
+
+    Returns (acc, overflow_count, n_smac).  acc is [n, oc, oh, ow], or [len(points)] when points is given.
+    """
+    oc, cin, kh, kw, groups = wshape
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    n, c, h, w = x.shape
+    assert c == cin
+    ws = WShape(oc, cin, kh, kw, groups)
+    g = Geom(n, h, w, stride[0], stride[1], pad[0], pad[1])
+    oh, ow = out_hw(h, w, kh, kw, stride, pad)
+    if s_max is None:
+        s_max = q.s_max
+    if budget_to is not None:
+        budget_to = np.ascontiguousarray(budget_to, dtype=np.uint8)
+        assert budget_to.shape == (n, oh, ow)
+    if budget_from is not None:
+        budget_from = np.ascontiguousarray(budget_from, dtype=np.uint8)
+        assert budget_from.shape == (n, oh, ow)
+    if points is not None:
+        points = np.ascontiguousarray(points, dtype=np.int64)
+        shape = (points.size,)
+    else:
+        shape = (n, oc, oh, ow)
+    if budget_from is not None:
+        assert acc_in is not None
+        acc = np.ascontiguousarray(acc_in, dtype=np.int32).copy().reshape(shape)
+    else:
+        acc = np.zeros(shape, dtype=np.int32)
+    over, smac = C.c_int64(0), C.c_int64(0)
+    rc = lib().psbo_conv2d(C.byref(q._q), C.byref(ws), _ptr(x), C.byref(g), 0 if S is None else int(S),
+                           int(s_max), _ptr(budget_to), _ptr(budget_from), int(seed), int(layer_id),
+                           _ptr(points), 0 if points is None else points.size, _ptr(acc),
+                           C.byref(over), C.byref(smac))
+    if rc != OK:
+        raise OracleError(rc)
+    return acc, over.value, smac.value
+
+
+def rescale(acc, e_min, S=None, s_max=255, budget_to=None, mult=None, bias=None):
+    """acc [n, oc, ...] int32 -> y float32 of the same shape."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    n, oc = acc.shape[0], acc.shape[1]
+    spatial = int(np.prod(acc.shape[2:])) if acc.ndim > 2 else 1
+    y = np.zeros(acc.shape, dtype=np.float32)
+    if budget_to is not None:
+        budget_to = np.ascontiguousarray(budget_to, dtype=np.uint8)
+        assert budget_to.size == n * spatial
+    if mult is not None:
+        mult = np.ascontiguousarray(mult, dtype=np.float32)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    rc = lib().psbo_rescale(_ptr(acc), n, oc, spatial, 0 if S is None else int(S), int(s_max), _ptr(budget_to),
+                            int(e_min), _ptr(mult), _ptr(bias), _ptr(y))
+    if rc != OK:
+        raise OracleError(rc)
+    return y

@@ -1,0 +1,119 @@
+/*
+ * psb_oracle.h -- CPU oracle for the stochastically binarized scalar-product
+ * layer of Progressive Stochastic Binarization (Hartmann & Wand).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, slow, sequential-by-definition
+ * implementation whose only purpose is to define, for every (inputs, seed),
+ * the single bit pattern the GPU library has to reproduce.  It shares no code
+ * with the HIP path; nothing in the product imports, links or calls it.
+ *
+ * Every function names the passage of the paper it follows.  Where the paper
+ * is silent the reading is stated next to the code (and listed in the design
+ * document of the repository).
+ *
+ * Parity status: every function below is pinned by CPU tests (closed forms,
+ * published known-answer vectors, brute-force enumeration, statistical bounds,
+ * reduction to a textbook integer convolution).  No function is
+ * "parity unpinned".
+ */
+#ifndef PSB_ORACLE_H
+#define PSB_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* weight classes */
+enum { PSBO_ZERO = 0, PSBO_NORMAL = 1, PSBO_SUBNORMAL = 2, PSBO_NONFINITE = 3 };
+
+/* status codes (oracle-local; the GPU library has its own) */
+enum { PSBO_OK = 0, PSBO_ERR_ARG = -1, PSBO_ERR_VALUE = -3, PSBO_ERR_OVERFLOW_UNSAFE = -4 };
+
+typedef struct {
+    int32_t e_top;      /* largest exponent e over normal non-zero weights      */
+    int32_t e_min;      /* exponent that maps to shift 0                         */
+    int64_t n_zero;     /* weights equal to +-0                                  */
+    int64_t n_flushed;  /* non-zero weights below the window (incl. subnormals)  */
+    int64_t n_live;     /* weights that are sampled                              */
+} psbo_winfo;
+
+/* Quantised layer as the oracle keeps it: one entry per weight, [oc][K].       */
+typedef struct {
+    int32_t  oc, K;         /* K = (cin/groups)*kh*kw                            */
+    int8_t*  sign;          /* -1, +1; 0 = not live (zero or flushed)            */
+    int32_t* shift;         /* e - e_min >= 0 for live weights                   */
+    double*  p;             /* probability of the larger shift, in [0,1)         */
+    psbo_winfo info;
+} psbo_weights;
+
+typedef struct { int32_t oc, cin, kh, kw, groups; } psbo_wshape;
+typedef struct { int32_t n, h, w, stride_h, stride_w, pad_h, pad_w; } psbo_geom;
+
+/* Sect. 3.1 "Value-based importance sampling", Eq. (numbersystem) and the
+ * three definitions below it: s = sign(w), e = floor(log2|w|), p = |w|/2^e-1.
+ * Computed on the VALUE (frexp/ldexp), not on the bit pattern.  Returns the
+ * class of w; s,e,p are written for NORMAL and SUBNORMAL inputs.               */
+int psbo_decode(float w, int32_t* s, int32_t* e, double* p);
+
+/* Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).  The paper
+ * only asks for "sufficiently independent and evenly distributed" numbers
+ * (suppl. "Random number generation"); the counter-based generator is what
+ * makes one result per (inputs, seed) well defined.                            */
+void psbo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/* The uniform 32-bit integer of product (o,k), sample s: word (s mod 4) of
+ * Philox4x32-10 with key (seed mod 2^32, seed div 2^32) and counter
+ * (o, k, floor(s/4), layer_id).                                                 */
+uint32_t psbo_uniform(uint64_t seed, uint32_t layer_id, uint32_t o, uint32_t k, uint32_t s);
+
+/* Encode a layer.  exp_bits<=0 selects 4 (Sect. 4.4: 4-bit exponents).  The
+ * window and the overflow rule are described at the definition.  Allocates the
+ * arrays of *out with malloc; release with psbo_weights_free.                   */
+int  psbo_quantize(const float* w, int32_t oc, int32_t K, int32_t exp_bits,
+                   int32_t x_absmax, int32_t s_max, psbo_weights* out);
+void psbo_weights_free(psbo_weights* q);
+
+/* Sect. 3.1, unnumbered equation after Eq. (numbersystem:simulation):
+ * acc[b][oc] = sum_k sum_{s<S} sigma_k * ( x[b][k] << (shift_k + B^(s)) ).
+ * u_table: optional replacement of the generator for enumeration tests,
+ * u(o,k,s) = u_table[(o*K + k)*S + s]; NULL = Philox.
+ * overflow (nullable) receives the number of outputs whose exact (int64) sum
+ * does not fit int32.                                                           */
+int psbo_linear(const psbo_weights* q, const int8_t* x, int32_t B, int32_t S,
+                uint64_t seed, uint32_t layer_id, const uint32_t* u_table,
+                int32_t* acc, int64_t* overflow);
+
+/* Same sum for a convolution (Sect. 3: "the same basic computational structure
+ * except they reuse weights and limit their support"), NCHW / OIHW, with a
+ * per-output-pixel sample range [from,to) (Sect. 4.5: spatially adaptive
+ * sample counts whose first-pass samples are reused).
+ *   budget_to   [n][oh][ow] or NULL (=> S_uniform everywhere)
+ *   budget_from [n][oh][ow] or NULL (=> 0 and acc is overwritten;
+ *               non-NULL => acc is read-modify-write)
+ * Both maps are clamped: to' = min(to, s_max), from' = min(from, to').
+ * points: optional list of n_points flat output indices; when non-NULL only
+ * those outputs are computed and written to acc[0..n_points) (compact).
+ * n_smac (nullable): number of sampled MACs = sum over computed outputs of
+ * (to'-from') * #(live taps inside the image).                                 */
+int psbo_conv2d(const psbo_weights* q, const psbo_wshape* ws, const int8_t* x,
+                const psbo_geom* g, int32_t S_uniform, int32_t s_max,
+                const uint8_t* budget_to, const uint8_t* budget_from,
+                uint64_t seed, uint32_t layer_id,
+                const int64_t* points, int64_t n_points,
+                int32_t* acc, int64_t* overflow, int64_t* n_smac);
+
+/* Final rescale: y = fl( fl( float(acc) * mult[oc] ) * inv_S ) + bias[oc],
+ * every fl one binary32 round-to-nearest-even operation, no fused
+ * multiply-add.  inv_S = 1/to' (0 when to' = 0).  mult NULL => 2^e_min;
+ * bias NULL => no addition.  budget_to NULL => S_uniform.  spatial = oh*ow
+ * (1 for a linear layer); acc is [n][oc][spatial].                              */
+int psbo_rescale(const int32_t* acc, int32_t n, int32_t oc, int32_t spatial,
+                 int32_t S_uniform, int32_t s_max, const uint8_t* budget_to,
+                 int32_t e_min, const float* mult, const float* bias, float* y);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
