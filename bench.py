@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the PSB layer hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path over one batch of synthetic input that is already resident in
+HBM: the layer call(s) of the workload through the C-ABI (zero-fill, sampling kernel, fp32 rescale).  The
+default workload is BASELINE config 2 (3x3 conv 64->64 on 1x64x56x56, S=16), the ResNet-shaped layer the
+metric is quoted on.  Prints ONE JSON line.
+
+metric  sampled MACs/s: one sampled MAC = one (output element, live tap inside the image, sample)
+        shift-add; taps whose activation is 0 are counted (the method as stated samples them), so `value` is
+        comparable between implementations whether or not they skip such taps.
+roofline  bound "alu": the sampling kernel is limited by integer VALU issue.  `achieved` is the
+        algorithmic instruction work of the products that need sampling (live weight, tap inside the image,
+        activation != 0) in full-rate int32 lane-operations per second; `peak` = 256 CUs x 64 lanes x 2.4 GHz.
+        Per generator call (4 samples) that cannot be hoisted or done on the scalar unit: 15 32x32->64
+        multiplies (v_mad_u64_u32, 4 issue slots of a full-rate instruction each, measured), 31 two-input
+        xors (gfx950 has no three-input xor), 4 compares and 4 carry-adds; per product 2 more.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# ---- ALU roofline constants (derivation in the design doc, measured by csrc/valu_rates.hip) -----------------
+CUS, LANES_PER_CU_CLK, CLOCK_HZ = 256, 64, 2.4e9
+PEAK_TIOPS = CUS * LANES_PER_CU_CLK * CLOCK_HZ / 1e12          # 39.32 T full-rate int32 lane-ops/s
+MAD64_SLOTS = 4.0          # v_mad_u64_u32 occupies the issue slots of 4 full-rate instructions
+CALL_MAD64, CALL_XOR, CALL_CMP_ADD = 15, 31, 8                  # per generator call (4 samples)
+PRODUCT_OPS = 2                                                 # v_mul_i32_i24 + v_mad_i32_i24 per product
+
+
+def lane_ops(n_calls, n_products):
+    """Full-rate-equivalent int32 lane-operations of n_calls generator calls and n_products products."""
+    return n_calls * (CALL_MAD64 * MAD64_SLOTS + CALL_XOR + CALL_CMP_ADD) + n_products * PRODUCT_OPS
+
+
+def workload_layers(name):
+    from paper_1904_02205_amd import synth
+    if name == "c1":
+        return [synth.config1()], "config1: linear 512->256, batch 64, uint4 activations, S=8"
+    if name == "c2":
+        return [synth.config2()], "config2: conv3x3 s1 p1 64->64 on 1x64x56x56 int8 (50% zeros), S=16"
+    if name == "c3":
+        return [synth.config3()], "config3: progressive conv3x3 128->128 on 8x128x28x28, blob budgets {2..32}"
+    if name == "c4":
+        return synth.config4_layers(), "config4: 20 convs + FC of a ResNet-18 shape, batch 32, S=8 (layer inputs synthetic)"
+    if name == "c5":
+        return synth.config5(), "config5: MobileNet-v2 block at 14x14, batch 64: pruned 1x1 576->160 + depthwise 3x3, S=16"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def count_work(L, packed, torch, device):
+    """(sampled MACs, generator calls needed, products needed) of one layer call, from the exported weights.
+
+    sampled MACs: sum over outputs of budget x #(live taps inside the image).
+    needed: the same restricted to taps whose activation is not 0; calls = ceil(budget/4) per such product.
+    """
+    oc, cin, kh, kw, groups = L.wshape
+    cg = cin // groups
+    live = ((packed >> 23) & 0xFF) != 0xFF                       # [oc, K]
+    live = live.reshape(groups, oc // groups, cg, kh, kw).sum(axis=1).astype(np.float64)   # [g, cg, kh, kw]
+    wt = torch.from_numpy(live).to(device)
+    x = torch.from_numpy(L.x).to(device)
+    ones = torch.ones_like(x, dtype=torch.float64)
+    nz = (x != 0).to(torch.float64)
+    conv = torch.nn.functional.conv2d
+    taps_all = conv(ones, wt, stride=L.stride, padding=L.pad, groups=groups).sum(dim=1)     # [n, oh, ow]
+    taps_nz = conv(nz, wt, stride=L.stride, padding=L.pad, groups=groups).sum(dim=1)
+    if L.budget_to is not None:
+        b = torch.from_numpy(np.minimum(L.budget_to, L.s_max).astype(np.float64)).to(device)
+    else:
+        b = torch.full_like(taps_all, float(L.S))
+    smac = float((taps_all * b).sum().item())
+    calls = float((taps_nz * torch.ceil(b / 4)).sum().item())
+    products = float((taps_nz * (b > 0)).sum().item())
+    return smac, calls, products
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--mapping", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-y", action="store_true", help="skip the fp32 rescale output")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every box has one); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    from paper_1904_02205_amd import psb
+    psb.lib()
+    psb.set_mapping(args.mapping)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    layers, desc = workload_layers(args.workload)
+    calls = []
+    smac = n_calls = n_prod = 0.0
+    for L in layers:
+        w = torch.from_numpy(L.w).to(dev)
+        q = psb.Weights(w, groups=L.groups, x_absmax=L.x_absmax, s_max=L.s_max)
+        x = torch.from_numpy(L.x).to(dev)
+        n, oc = L.x.shape[0], L.w.shape[0]
+        oh, ow = L.out_hw
+        acc = torch.empty((n, oc, oh, ow), dtype=torch.int32, device=dev)
+        y = None if args.no_y else torch.empty((n, oc, oh, ow), dtype=torch.float32, device=dev)
+        bt = None if L.budget_to is None else torch.from_numpy(L.budget_to).to(dev)
+        a, b, c = count_work(L, q.export(), torch, dev)
+        smac += a
+        n_calls += b
+        n_prod += c
+        calls.append((L, q, x, acc, y, bt))
+    torch.cuda.synchronize()
+
+    def step():
+        for L, q, x, acc, y, bt in calls:
+            if bt is not None:
+                psb.conv2d_progressive(q, x, bt, None, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id,
+                                       acc=acc, y=y)
+            elif L.linear:
+                psb.linear(q, x.reshape(x.shape[0], -1), L.S, seed=L.seed, layer_id=L.layer_id,
+                           acc=acc.reshape(acc.shape[0], -1), y=None if y is None else y.reshape(y.shape[0], -1))
+            else:
+                psb.conv2d(q, x, L.S, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id, acc=acc, y=y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    psb.profile_enable(True)
+    psb.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms, n_launch = psb.profile_read()
+    psb.profile_enable(False)
+
+    sec_per_step = (t1 - t0) / args.steps
+    value = smac / sec_per_step
+    kern_s = kernel_ms * 1e-3 / max(n_launch, 1)                 # average sampling-kernel launch
+    launches_per_step = n_launch / args.steps
+    ops_per_launch = lane_ops(n_calls, n_prod) / launches_per_step
+    achieved = ops_per_launch / kern_s / 1e12
+    out = {
+        "metric": "sampled MACs/sec (int shift-adds/s) on 1 MI355X",
+        "value": value, "unit": "sampled MAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": desc, "sampled_macs_per_step": smac,
+                   "sampled_macs_needing_work_per_step": n_calls * 4, "generator_calls_per_step": n_calls,
+                   "kernel_launches_per_step": launches_per_step, "mapping": args.mapping,
+                   "rescale_output": not args.no_y},
+        "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_TIOPS,
+                     "unit": "TIOP/s (full-rate int32 lane-ops)", "frac": achieved / PEAK_TIOPS, "traffic": None,
+                     "kernel": "k_layer_oc_lane" if args.mapping != 1 else "k_layer_pixel_lane",
+                     "kernel_ms_avg": kern_s * 1e3, "lane_ops_per_launch": ops_per_launch},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import binding as orc          # the oracle is only timed here, never used for results
+        orc.lib()
+        L = layers[0]
+        qo = orc.QWeights(L.w.reshape(L.w.shape[0], -1), x_absmax=L.x_absmax, s_max=L.s_max)
+        total = int(np.prod((L.x.shape[0], L.w.shape[0]) + L.out_hw))
+        # bounded sample: as many output elements as about 8e9 sampled MACs need, at most all of them
+        per_out = smac / sum(np.prod((l.x.shape[0], l.w.shape[0]) + l.out_hw) for l in layers)
+        n_pts = int(min(total, max(1000, 8e9 / max(per_out, 1))))
+        pts = None if n_pts >= total else np.random.default_rng(0).choice(total, n_pts, replace=False).astype(np.int64)
+        c0 = time.perf_counter()
+        _, _, cpu_smac = orc.conv2d(qo, L.wshape, L.x, L.stride, L.pad, S=None if L.budget_to is not None else L.S,
+                                    s_max=L.s_max, budget_to=L.budget_to, seed=L.seed, layer_id=L.layer_id, points=pts)
+        c1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": cpu_smac / (c1 - c0), "unit": "sampled MAC/s",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": (f"{'all' if pts is None else n_pts} of {total} output elements of "
+                                          f"{L.name}, {cpu_smac} sampled MACs, {c1 - c0:.2f} s")}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,189 @@
+/*
+ * psb.h -- C-ABI of the MI355X (gfx950) library for the stochastically
+ * binarized scalar-product layer of Progressive Stochastic Binarization
+ * (Hartmann & Wand, "Progressive Stochastic Binarization of Deep Networks").
+ *
+ * What the layer computes (paper, Sect. 3 and 3.1): the pre-activation
+ * sum_k x_k * w_k of a linear or convolutional layer, in which every weight w
+ * is replaced, for every sample, by the random power of two
+ *     w_bar = s * 2^(e + B),  s = sign(w), e = floor(log2|w|),
+ *     Pr(B = 1) = p = |w| / 2^e - 1                       (Eq. "numbersystem")
+ * so that x * w_bar is a shift of the integer activation x, and S samples are
+ * accumulated in an integer register (unnumbered equation after Eq.
+ * "numbersystem:simulation"):
+ *     acc = sum_k s_k * sum_{i < S} ( x_k << (e_k - e_min + B_k^(i)) ).
+ * One random bit is drawn per shift (Sect. 2, last paragraph of "Hardware
+ * optimized architectures"): B^(i) is independent for every (output element,
+ * tap, sample).  Sample counts may differ per output pixel, and a pixel with a
+ * larger count reuses the samples of the smaller one (Sect. 4.5).
+ *
+ * Conventions
+ *  - All data pointers named *_dev are DEVICE pointers (HIP global memory of
+ *    the current device); pointers named *_host are host pointers.  The caller
+ *    owns every buffer; the library owns only psb_weights_t handles.
+ *  - Layouts: activations NCHW int8, weights OIHW float32 (O = output channel,
+ *    I = input channels per group), accumulators and outputs NCHW.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the null stream).
+ *    Layer calls are asynchronous on that stream and never synchronise.
+ *    psb_quantize_weights synchronises the stream twice (it reads back the
+ *    largest exponent and a per-channel exponent histogram).
+ *  - Every function returns PSB_OK (0) or a negative psb_status; nothing
+ *    throws, aborts or prints.  Arguments are validated on the host before any
+ *    device work is started; on error nothing has been launched.
+ *  - The random bit of (output element o, tap k, sample i) is
+ *        B = [ u < p * 2^32 ],
+ *    u = word (i mod 4) of Philox4x32-10 with key (seed mod 2^32, seed div 2^32)
+ *    and counter (o, k, i div 4, layer_id);  o is the flat NCHW index of the
+ *    output element ((n*OC + oc)*OH + oy)*OW + ox (linear: b*OC + oc) and
+ *    k = (ci*KH + kh)*KW + kw with ci counted inside the group.  The result is
+ *    therefore a pure function of (inputs, seed, layer_id): independent of
+ *    tiling, launch geometry and call order.
+ */
+#ifndef PSB_H
+#define PSB_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PSB_OK = 0,
+    PSB_ERR_NULL = -1,            /* a required pointer is NULL                                  */
+    PSB_ERR_SHAPE = -2,           /* non-positive or inconsistent dimension                      */
+    PSB_ERR_VALUE = -3,           /* NaN/Inf weight, S <= 0, S > s_max, unsupported bit width    */
+    PSB_ERR_OVERFLOW_UNSAFE = -4, /* no exponent window keeps the worst case inside int32        */
+    PSB_ERR_TOO_LARGE = -5,       /* N*OC*OH*OW or K does not fit the 32-bit counter words       */
+    PSB_ERR_DEVICE = -6,          /* a HIP call failed; see psb_last_device_error()              */
+    PSB_ERR_ALLOC = -7            /* host or device allocation failed                            */
+} psb_status;
+
+typedef struct psb_weights psb_weights_t;   /* opaque, created by psb_quantize_weights */
+
+/* Weight tensor [oc][cin/groups][kh][kw].  A linear layer is kh = kw = groups = 1. */
+typedef struct { int32_t oc, cin, kh, kw, groups; } psb_wshape;
+
+/* Input batch and convolution geometry.  OH = (h + 2*pad_h - kh)/stride_h + 1,
+ * OW likewise; no dilation.                                                        */
+typedef struct { int32_t n, h, w, stride_h, stride_w, pad_h, pad_w; } psb_conv_geom;
+
+typedef struct {
+    int32_t e_top;      /* largest exponent of a normal non-zero weight             */
+    int32_t e_min;      /* exponent that maps to shift 0; acc is in units 2^e_min   */
+    int64_t n_zero;     /* weights equal to +-0: never sampled                      */
+    int64_t n_flushed;  /* non-zero weights below the window, and subnormals        */
+    int64_t n_live;     /* weights that are sampled                                 */
+} psb_winfo;
+
+/*
+ * Encode a layer's weights as (sign, shift = e - e_min, 23-bit mantissa = p*2^23)
+ * [Sect. 3.1, definitions of s, e, p below Eq. "numbersystem"; for a normal
+ * binary32 number these are its three bit fields].
+ *
+ * Exponent window [Sect. 4.4: 4-bit exponents suffice; caption of the stochastic-
+ * multiplier figure: the width of the integers restricts the exponents; caption of
+ * Fig. "numbersystem": too many shifts of an integer give 0]:
+ * e_top = largest e in the layer; e_min = the smallest integer in
+ * [e_top - (2^exp_bits - 1), e_top] such that
+ *   x_absmax * s_max * max_oc sum_{k: e_k >= e_min} 2^(e_k - e_min + 1) <= 2^31 - 1,
+ * which makes int32 wrap-around impossible for |x| <= x_absmax and up to s_max
+ * samples.  Weights below e_min, subnormals and zeros are not live.
+ *
+ *  w_dev      device, float32 [oc][cin/groups][kh][kw], read only during the call
+ *  prob_bits  must be 23 (the full binary32 mantissa)
+ *  exp_bits   1..5; <= 0 selects 4
+ *  x_absmax   1..128, largest |activation| the caller will pass
+ *  s_max      1..255, largest sample count / budget the caller will use
+ *  out        receives the handle (device memory owned by the library)
+ * Errors: NULL, SHAPE, VALUE (NaN/Inf weight, bad widths), OVERFLOW_UNSAFE,
+ * TOO_LARGE, DEVICE, ALLOC.
+ */
+int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t prob_bits, int32_t exp_bits,
+                         int32_t x_absmax, int32_t s_max, void* hip_stream, psb_weights_t** out);
+
+/* Copy the summary of the encoding to *info (host). */
+int psb_weights_info(const psb_weights_t* q, psb_winfo* info);
+
+/* Copy the encoded weights to host memory: packed_host[oc*K + k] =
+ * sign<<31 | shift<<23 | mantissa, with shift = 0xFF for a weight that is not live.
+ * Synchronous. */
+int psb_weights_export(const psb_weights_t* q, uint32_t* packed_host);
+
+/* Release a handle (NULL is allowed).  The caller must make sure no layer call
+ * using it is still running. */
+void psb_weights_destroy(psb_weights_t* q);
+
+/* Output height/width of a convolution, on the host, with the validation every
+ * conv entry point applies (SHAPE, TOO_LARGE).  oh/ow may be NULL. */
+int psb_conv2d_out_dims(const psb_wshape* shape, const psb_conv_geom* geom, int32_t* oh, int32_t* ow);
+
+/*
+ * Linear layer [Sect. 3, Eq. 1, with every product replaced per Sect. 3.1]:
+ *   acc[b][oc] = sum_{k live} sigma_k * sum_{i<S} ( x[b][k] << (shift_k + B(o,k,i)) ),  o = b*OC + oc.
+ *  x_dev    device, int8 [B][K], K = cin
+ *  acc_dev  device, int32 [B][OC], overwritten
+ *  y_dev    device, float32 [B][OC] or NULL.  y = fl(fl(float(acc) * mult[oc]) * fl(1/S)) + bias[oc],
+ *           every fl one binary32 round-to-nearest operation, no fused multiply-add
+ *           [the ">> n" normalisation of the shift form, Sect. 3.1; the affine map of a
+ *           folded batch normalisation, Sect. 3, Eq. 2]
+ *  mult_dev device, float32 [OC] or NULL (= 2^e_min for every channel)
+ *  bias_dev device, float32 [OC] or NULL (= no addition)
+ * Errors: NULL, SHAPE, VALUE (S <= 0 or S > s_max), TOO_LARGE, DEVICE.
+ */
+int psb_linear(const psb_weights_t* q, const int8_t* x_dev, int32_t B, int32_t S, uint64_t seed,
+               uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev,
+               const float* bias_dev, void* hip_stream);
+
+/*
+ * Convolution with the same sample count S at every output [Sect. 3: convolutions
+ * "reuse weights and limit their support"; otherwise as psb_linear].  Taps that fall
+ * into the padding contribute 0 and are not sampled.
+ *  x_dev    device, int8 [N][C][H][W]
+ *  acc_dev  device, int32 [N][OC][OH][OW], overwritten
+ *  y_dev, mult_dev, bias_dev as in psb_linear, shaped [N][OC][OH][OW] / [OC].
+ */
+int psb_conv2d(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S,
+               uint64_t seed, uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev,
+               const float* bias_dev, void* hip_stream);
+
+/*
+ * Convolution with a per-output-pixel sample range [Sect. 4.5: a low-precision pass
+ * everywhere, more samples only where needed, the first samples being reused].
+ * Pixel (n,oy,ox), all output channels alike, draws samples from'..to'-1 with
+ *   to' = min(budget_to, s_max), from' = min(budget_from, to')   (0 if budget_from is NULL).
+ *  budget_to_dev    device, uint8 [N][OH][OW]
+ *  budget_from_dev  device, uint8 [N][OH][OW] or NULL.
+ *                   NULL: acc is overwritten.  Non-NULL: acc is read-modify-write; it must
+ *                   hold the result of samples 0..from'-1 of the same (seed, layer_id), and
+ *                   afterwards holds the result of samples 0..to'-1, bit-identical to a
+ *                   single call with budget_from NULL.
+ *  y_dev            uses fl(1/to') per pixel (0 where to' = 0).
+ */
+int psb_conv2d_progressive(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom,
+                           const uint8_t* budget_to_dev, const uint8_t* budget_from_dev, uint64_t seed,
+                           uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev,
+                           const float* bias_dev, void* hip_stream);
+
+/* The hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
+int psb_last_device_error(void);
+
+/* Select the kernel mapping for subsequent layer calls of this process:
+ * 0 = automatic, 1 = one output pixel per lane (any layer), 2 = one output channel
+ * per lane (groups = 1 only).  Results are bit-identical for every mapping; the
+ * switch exists for tests and benchmarks.  Returns the previous value. */
+int psb_set_mapping(int mapping);
+
+/* Timing of the sampling kernels, for benchmarks.  While enabled, every layer call
+ * brackets its sampling kernel (not the zero-fill or the separate rescale kernel) with a
+ * pair of HIP events on the caller's stream; at most 4096 pairs are kept between reads.
+ * psb_profile_read waits for the recorded events, adds up their elapsed times, returns
+ * the sum in milliseconds and the number of launches, and clears the record.  Not
+ * thread-safe; enable/disable only while no layer call is in flight. */
+int psb_profile_enable(int on);
+int psb_profile_read(double* kernel_ms_sum, int64_t* n_launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -64,6 +64,8 @@ def lib():
         L.psbo_rescale.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.psbo_rescale.restype = C.c_int
+        L.psbo_num_threads.argtypes = []
+        L.psbo_num_threads.restype = C.c_int
         _lib = L
     return _lib
 
@@ -76,6 +78,10 @@ class OracleError(RuntimeError):
 
 def _ptr(a):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def num_threads():
+    return int(lib().psbo_num_threads())
 
 
 def decode(w):

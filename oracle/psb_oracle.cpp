@@ -11,6 +11,9 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 /* ---------------------------------------------------------------------------
  * Number system: Sect. 3.1, Eq. (numbersystem) and the definitions of s, e, p.
@@ -329,4 +332,13 @@ extern "C" int psbo_rescale(const int32_t* acc, int32_t n, int32_t oc, int32_t s
                 y[i] = r;
             }
     return PSBO_OK;
+}
+
+extern "C" int psbo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
 }

@@ -113,6 +113,9 @@ int psbo_rescale(const int32_t* acc, int32_t n, int32_t oc, int32_t spatial,
                  int32_t S_uniform, int32_t s_max, const uint8_t* budget_to,
                  int32_t e_min, const float* mult, const float* bias, float* y);
 
+/* Number of host threads the layer functions spread output elements over. */
+int psbo_num_threads(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,0 +1,45 @@
+"""Build the HIP library paper_1904_02205_amd/libpsb_hip.so for gfx950 (in-tree).
+
+Usage: python -m paper_1904_02205_amd.build
+"""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB = os.path.join(HERE, "libpsb_hip.so")
+SRC = os.path.join(HERE, "csrc", "psb_api.hip")
+DEPS = [SRC,
+        os.path.join(HERE, "csrc", "psb_kernels.hip.h"),
+        os.path.join(HERE, "csrc", "psb_kernels_oc.hip.h"),
+        os.path.join(HERE, "csrc", "psb_philox.hip.h"),
+        os.path.join(os.path.dirname(HERE), "include", "psb.h")]
+
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+         # packed FP32 instructions are disabled on purpose (see the build notes of this machine pool)
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-ffp-contract=off", "-Wall", "-Wno-unused-function"]
+
+
+def build(verbose: bool = False, extra=()) -> str:
+    cmd = ["hipcc", *FLAGS, *extra, SRC, "-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True, cwd=HERE)
+    return LIB
+
+
+def ensure_built() -> str:
+    """Build only when the library is missing; a present library is used as it is."""
+    if not os.path.exists(LIB):
+        build()
+    return LIB
+
+
+def stale() -> bool:
+    return (not os.path.exists(LIB)) or any(os.path.getmtime(d) > os.path.getmtime(LIB) for d in DEPS)
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))
+    sys.exit(0)

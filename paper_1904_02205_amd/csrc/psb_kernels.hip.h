@@ -1,0 +1,213 @@
+// Device kernels of the PSB layer library (gfx950, wave64).
+//
+//  - weight encoding: exponent scan, per-channel exponent histogram, packing
+//  - "pixel-lane" layer kernel: one output element per lane, one output channel per
+//    workgroup; works for every layer shape (groups, strides, pruned weights)
+//
+// The packed weight word is  sign<<31 | shift<<23 | mantissa(23 bit);  a weight that is
+// not sampled (zero, subnormal, below the exponent window) has shift = 0xFF.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "psb_philox.hip.h"
+
+namespace psb {
+
+constexpr uint32_t kDeadWord = 0x7F800000u;  // shift field 0xFF, nothing else
+constexpr int kHistBins = 32;                // exponent window is at most 2^5 wide
+
+// ---------------------------------------------------------------------------------
+// Weight encoding (Sect. 3.1: s = sign w, e = floor(log2|w|), p = |w|/2^e - 1; for a
+// normal binary32 these are its sign bit, exponent field - 127 and mantissa / 2^23).
+// ---------------------------------------------------------------------------------
+
+// scan[0] = largest exponent field among normal non-zero weights (0 if none)
+// scan[1] = 1 if any weight is NaN or Inf
+__global__ void __launch_bounds__(256) k_exponent_scan(const uint32_t* __restrict__ w_bits, int64_t n,
+                                                       uint32_t* __restrict__ scan)
+{
+    uint32_t best = 0, bad = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const uint32_t f = (w_bits[i] >> 23) & 0xFFu;
+        if (f == 0xFFu) bad = 1;
+        else if (f > best) best = f;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        best = max(best, (uint32_t)__shfl_xor((int)best, off, 64));
+        bad |= (uint32_t)__shfl_xor((int)bad, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        if (best) atomicMax(&scan[0], best);
+        if (bad) atomicOr(&scan[1], 1u);
+    }
+}
+
+// hist[oc][b] = number of normal weights of channel oc whose exponent is e_top - b,
+// b = 0 .. window.  One workgroup per output channel.
+__global__ void __launch_bounds__(256) k_exponent_hist(const uint32_t* __restrict__ w_bits, int K, int field_top,
+                                                       int window, uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t bins[kHistBins];
+    if (threadIdx.x < kHistBins) bins[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t* row = w_bits + (int64_t)blockIdx.x * K;
+    for (int k = threadIdx.x; k < K; k += blockDim.x) {
+        const int f = (int)((row[k] >> 23) & 0xFFu);
+        const int b = field_top - f;
+        if (f != 0 && b >= 0 && b <= window) atomicAdd(&bins[b], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x < kHistBins) hist[(int64_t)blockIdx.x * kHistBins + threadIdx.x] = bins[threadIdx.x];
+}
+
+// packed[oc][k] (row-major, the export format) and tile[k][oc_pad] (transposed, padded
+// with dead entries to a multiple of 64 channels, for the channel-lane kernel):
+// tile entry = { threshold = mantissa << 9,  unit = +-2^shift (0 when not live) }.
+// counts[0..2] = zero, flushed, live.
+__global__ void __launch_bounds__(256) k_pack(const uint32_t* __restrict__ w_bits, int OC, int K, int oc_pad,
+                                              int field_min /* exponent field of e_min */,
+                                              uint32_t* __restrict__ packed, uint2* __restrict__ tile,
+                                              unsigned long long* __restrict__ counts)
+{
+    const int64_t total = (int64_t)oc_pad * K;
+    unsigned long long n_zero = 0, n_flush = 0, n_live = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        // i enumerates the transposed array so that its writes are coalesced
+        const int k = (int)(i / oc_pad);
+        const int oc = (int)(i - (int64_t)k * oc_pad);
+        uint2 entry = make_uint2(0u, 0u);
+        if (oc < OC) {
+            uint32_t word = kDeadWord;
+            const uint32_t bits = w_bits[(int64_t)oc * K + k];
+            const int f = (int)((bits >> 23) & 0xFFu);
+            const uint32_t mant = bits & 0x7FFFFFu;
+            if (f == 0 && mant == 0) n_zero++;
+            else if (f == 0 || f < field_min) n_flush++;
+            else {
+                n_live++;
+                const uint32_t shift = (uint32_t)(f - field_min);
+                word = (bits & 0x80000000u) | (shift << 23) | mant;
+                const uint32_t unit = 1u << shift;              // shift <= 30 by the overflow rule
+                entry = make_uint2(mant << 9, (bits & 0x80000000u) ? (0u - unit) : unit);
+            }
+            packed[(int64_t)oc * K + k] = word;
+        }
+        tile[i] = entry;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        n_zero += __shfl_xor(n_zero, off, 64);
+        n_flush += __shfl_xor(n_flush, off, 64);
+        n_live += __shfl_xor(n_live, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        if (n_zero) atomicAdd(&counts[0], n_zero);
+        if (n_flush) atomicAdd(&counts[1], n_flush);
+        if (n_live) atomicAdd(&counts[2], n_live);
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Layer kernels
+// ---------------------------------------------------------------------------------
+
+struct LayerParams {
+    // tensors
+    const uint32_t* packed;    // [OC][K]
+    const uint2* tile;         // [K][oc_pad] {threshold, unit}
+    const int8_t* x;           // [N][C][H][W]
+    const uint8_t* budget_to;  // [N][OH][OW] or null
+    const uint8_t* budget_from;  // [N][OH][OW] or null (non-null: acc is read-modify-write)
+    int32_t* acc;              // [N][OC][OH][OW]
+    float* y;                  // same shape or null
+    const float* mult;         // [OC] or null
+    const float* bias;         // [OC] or null
+    // geometry
+    int N, C, H, W, OC, OH, OW, KH, KW, Cg, OCg, K, oc_pad;
+    int stride_h, stride_w, pad_h, pad_w;
+    // sampling
+    int S, s_max;
+    uint32_t key0, key1, layer_id;
+    float default_mult;        // 2^e_min
+    int max_shift;             // largest shift of a live weight
+};
+
+// Number of samples i in [from,to) of product (o,k) whose uniform is below thr.
+// Block j of the generator serves samples 4j .. 4j+3.
+__device__ __forceinline__ uint32_t count_below(uint32_t o, uint32_t k, uint32_t layer, uint32_t key0,
+                                                uint32_t key1, uint32_t thr, int from, int to)
+{
+    uint32_t n = 0;
+    for (int j = from >> 2; 4 * j < to; ++j) {
+        const u32x4 r = philox4x32_10(u32x4{o, k, (uint32_t)j, layer}, key0, key1);
+        const int s0 = 4 * j;
+        n += (s0 + 0 >= from && s0 + 0 < to && r.x < thr) ? 1u : 0u;
+        n += (s0 + 1 >= from && s0 + 1 < to && r.y < thr) ? 1u : 0u;
+        n += (s0 + 2 >= from && s0 + 2 < to && r.z < thr) ? 1u : 0u;
+        n += (s0 + 3 >= from && s0 + 3 < to && r.w < thr) ? 1u : 0u;
+    }
+    return n;
+}
+
+// Final rescale: four separately rounded binary32 operations.
+__device__ __forceinline__ float rescale(int32_t acc, float mult, int to, const float* bias, int oc)
+{
+    const float inv_s = (to > 0) ? __fdiv_rn(1.0f, (float)to) : 0.0f;
+    float r = __fmul_rn(__fmul_rn(__int2float_rn(acc), mult), inv_s);
+    if (bias) r = __fadd_rn(r, bias[oc]);
+    return r;
+}
+
+// One output element per lane; blockIdx.y = output channel, so the weight word and the
+// tap position are wave-uniform (scalar loads, scalar branches on dead weights) and the
+// activation reads of neighbouring lanes are neighbouring bytes.
+__global__ void __launch_bounds__(256) k_layer_pixel_lane(const LayerParams p)
+{
+    const int oc = blockIdx.y;
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int64_t pix = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pix >= npix) return;
+    const int ox = (int)(pix % p.OW);
+    const int oy = (int)((pix / p.OW) % p.OH);
+    const int n = (int)(pix / ((int64_t)p.OW * p.OH));
+
+    int to = p.budget_to ? (int)p.budget_to[pix] : p.S;
+    to = min(to, p.s_max);
+    int from = p.budget_from ? (int)p.budget_from[pix] : 0;
+    from = min(from, to);
+
+    const uint32_t o = (uint32_t)((((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox);
+    const int grp = oc / p.OCg;
+    const uint32_t* wrow = p.packed + (int64_t)oc * p.K;
+    const int8_t* xn = p.x + ((int64_t)n * p.C + (int64_t)grp * p.Cg) * p.H * p.W;
+    const int iy0 = oy * p.stride_h - p.pad_h;
+    const int ix0 = ox * p.stride_w - p.pad_w;
+
+    int32_t acc = 0;
+    if (to > from) {
+        int k = 0;
+        for (int ci = 0; ci < p.Cg; ++ci) {
+            for (int kh = 0; kh < p.KH; ++kh) {
+                for (int kw = 0; kw < p.KW; ++kw, ++k) {
+                    const uint32_t word = wrow[k];
+                    if ((word & 0x7F800000u) == kDeadWord) continue;
+                    const int iy = iy0 + kh, ix = ix0 + kw;
+                    if (iy < 0 || iy >= p.H || ix < 0 || ix >= p.W) continue;
+                    const int32_t xv = xn[((int64_t)ci * p.H + iy) * p.W + ix];
+                    if (xv == 0) continue;
+                    const uint32_t cnt = count_below(o, (uint32_t)k, p.layer_id, p.key0, p.key1, word << 9, from, to);
+                    const int32_t shifted = (int32_t)((uint32_t)xv << ((word >> 23) & 0xFFu));
+                    const int32_t term = shifted * (int32_t)((uint32_t)(to - from) + cnt);
+                    acc += (word & 0x80000000u) ? -term : term;
+                }
+            }
+        }
+    }
+    if (p.budget_from) acc += p.acc[o];
+    p.acc[o] = acc;
+    if (p.y) p.y[o] = rescale(acc, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+}
+
+}  // namespace psb

@@ -1,0 +1,368 @@
+// "Channel-lane" layer kernel for dense layers with groups = 1 (gfx950, wave64).
+//
+// Mapping: lane = output channel inside a block of 64, wave = one output pixel at a
+// time.  The activation of a tap is then the same for all lanes, so
+//   - taps whose activation is 0 (about half after a ReLU, and all padding) are removed
+//     before the sampling loop by a wave-level compaction (ballot + prefix count) into a
+//     per-wave list in LDS: no lane ever idles on a zero product;
+//   - the sample range [from,to) of a progressive call is wave-uniform: no divergence;
+//   - everything of the Philox counter that depends on the tap only is scalar work.
+// The weights of one tile of taps x 64 channels are staged in LDS once per workgroup as
+// {threshold, +-2^shift} pairs and read conflict-free (one ds_read_b64 per product).
+//
+// The reduction over taps is split into chunks; with more than one chunk the partial
+// sums are combined with int32 atomic adds, which is exact in any order because the
+// accumulator arithmetic is modulo 2^32.
+//
+// Philox work saved without changing a bit of the result.  Counter = (o, k, j, layer).
+// Round 0 multiplies o and j; o is fixed per lane and pixel, j is a literal.  Round 1
+// multiplies a scalar (a function of k and j) and a per-lane value that depends on o
+// only.  Round 2 multiplies a value that depends on (o, j) only and one that depends on
+// everything.  So of the 20 wide multiplies of a call only 15 are per-product vector
+// work; the other five are hoisted to per-pixel set-up or to the scalar unit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "psb_kernels.hip.h"
+
+namespace psb {
+
+constexpr int kOcWaves = 4;     // waves per workgroup
+constexpr int kOcMaxTaps = 64;  // taps per LDS tile: 64 * 64 channels * 8 B = 32 KB
+
+__device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+
+// a*b + c with 24-bit signed a, b (full-rate v_mad_i32_i24)
+__device__ __forceinline__ int32_t mad24(int32_t a, int32_t b, int32_t c) { return __mul24(a, b) + c; }
+
+struct PixelHoist {
+    uint32_t lo_a;    // low half of MulA * o                          (round 0, word 3)
+    uint32_t hi_b1;   // high half of MulB * (state word 2 after round 0)
+    uint32_t y2k;     // low half of the same product, xor round-2 key 0
+};
+
+struct Keys { uint32_t k0[10], k1[10]; };
+
+// Count, for one product, how many of the samples of block j are below thr, and add to n.
+// s_* arguments are wave-uniform.
+template <bool FULL>
+__device__ __forceinline__ uint32_t sample_block(uint32_t n, uint32_t thr, uint32_t s_x1 /* state word 0 after round 0 */,
+                                                 const PixelHoist& h, uint32_t hz, uint32_t lo2, const Keys& key,
+                                                 int j, int from, int to)
+{
+    // round 1, scalar half: MulA * (word 0)
+    uint32_t s_hi, s_lo;
+    mulhilo(kMulA, s_x1, s_hi, s_lo);
+    // state after round 1: (.., .., s_hi ^ lo_a ^ k1[1], s_lo); words 0 and 1 were used in the set-up
+    const uint32_t z2 = (s_hi ^ key.k1[1]) ^ h.lo_a;
+    // round 2: only MulB * z2 is new
+    uint32_t hi_b2, lo_b2;
+    mulhilo(kMulB, z2, hi_b2, lo_b2);
+    u32x4 c;
+    c.x = hi_b2 ^ h.y2k;
+    c.y = lo_b2;
+    c.z = hz ^ s_lo;
+    c.w = lo2;
+    c = philox_rounds_from<3>(c, key.k0[0], key.k1[0]);
+    if (FULL) {
+        n += (c.x < thr) ? 1u : 0u;
+        n += (c.y < thr) ? 1u : 0u;
+        n += (c.z < thr) ? 1u : 0u;
+        n += (c.w < thr) ? 1u : 0u;
+    } else {
+        const int s0 = 4 * j;
+        n += (s0 + 0 >= from && s0 + 0 < to && c.x < thr) ? 1u : 0u;
+        n += (s0 + 1 >= from && s0 + 1 < to && c.y < thr) ? 1u : 0u;
+        n += (s0 + 2 >= from && s0 + 2 < to && c.z < thr) ? 1u : 0u;
+        n += (s0 + 3 >= from && s0 + 3 < to && c.w < thr) ? 1u : 0u;
+    }
+    return n;
+}
+
+// Per-(pixel, block j) set-up: the part of rounds 0..2 that does not depend on the tap.
+__device__ __forceinline__ void block_setup(const PixelHoist& h, const Keys& key, int j, uint32_t& s_hib /* scalar */,
+                                            uint32_t& hz, uint32_t& lo2)
+{
+    uint32_t hi_bj, lo_bj;
+    mulhilo(kMulB, (uint32_t)j, hi_bj, lo_bj);          // round 0: MulB * j (scalar)
+    s_hib = hi_bj ^ key.k0[0];                          // state word 0 after round 0 is s_hib ^ k
+    const uint32_t x2 = h.hi_b1 ^ lo_bj ^ key.k0[1];    // state word 0 after round 1
+    uint32_t hi_a2, lo_a2;
+    mulhilo(kMulA, x2, hi_a2, lo_a2);                   // round 2: MulA * x2
+    hz = hi_a2 ^ key.k1[2];
+    lo2 = lo_a2;
+}
+
+// All products of one pixel's compacted tap list, NB generator blocks per product
+// (NB = 0: run-time number of blocks).  Returns this lane's partial accumulator.
+template <int NB, bool FULL>
+__device__ __forceinline__ int32_t process_list(const uint32_t* __restrict__ list, int cnt,
+                                                const uint2* __restrict__ w_tile, int lane, uint32_t k0,
+                                                int j0, int nb_rt, int from, int to, const PixelHoist& h,
+                                                const Keys& key)
+{
+    const uint32_t nsamp = (uint32_t)(to - from);
+    int32_t acc = 0;
+    if constexpr (NB == 0) {
+        for (int i = 0; i < cnt; ++i) {
+            const uint32_t entry = uniform_u32(list[i]);
+            const uint32_t kl = entry >> 8;
+            const int32_t xs = (int32_t)(int8_t)(entry & 0xFFu);
+            const uint2 wt = w_tile[kl * 64 + lane];
+            uint32_t n = nsamp;
+            for (int jj = 0; jj < nb_rt; ++jj) {
+                uint32_t s_hib, hz, lo2;
+                block_setup(h, key, j0 + jj, s_hib, hz, lo2);
+                n = sample_block<false>(n, wt.x, s_hib ^ (k0 + kl), h, hz, lo2, key, j0 + jj, from, to);
+            }
+            acc = mad24(__mul24(xs, (int32_t)n), (int32_t)wt.y, acc);
+        }
+        return acc;
+    } else {
+        constexpr int E = (NB >= 4) ? 1 : 4 / NB;   // products in flight: keep four generator calls independent
+        uint32_t s_hib[NB], hz[NB], lo2[NB];
+#pragma unroll
+        for (int jj = 0; jj < NB; ++jj) block_setup(h, key, j0 + jj, s_hib[jj], hz[jj], lo2[jj]);
+
+        int i = 0;
+        for (; i + E <= cnt; i += E) {
+            uint32_t n[E];
+            uint2 wt[E];
+            int32_t xs[E];
+            uint32_t kk[E];
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const uint32_t entry = uniform_u32(list[i + e]);
+                const uint32_t kl = entry >> 8;
+                xs[e] = (int32_t)(int8_t)(entry & 0xFFu);
+                wt[e] = w_tile[kl * 64 + lane];
+                kk[e] = k0 + kl;
+                n[e] = nsamp;
+            }
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+#pragma unroll
+                for (int jj = 0; jj < NB; ++jj)
+                    n[e] = sample_block<FULL>(n[e], wt[e].x, s_hib[jj] ^ kk[e], h, hz[jj], lo2[jj], key, j0 + jj,
+                                              from, to);
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc = mad24(__mul24(xs[e], (int32_t)n[e]), (int32_t)wt[e].y, acc);
+        }
+        for (; i < cnt; ++i) {
+            const uint32_t entry = uniform_u32(list[i]);
+            const uint32_t kl = entry >> 8;
+            const int32_t xs = (int32_t)(int8_t)(entry & 0xFFu);
+            const uint2 wt = w_tile[kl * 64 + lane];
+            uint32_t n = nsamp;
+#pragma unroll
+            for (int jj = 0; jj < NB; ++jj)
+                n = sample_block<FULL>(n, wt.x, s_hib[jj] ^ (k0 + kl), h, hz[jj], lo2[jj], key, j0 + jj, from, to);
+            acc = mad24(__mul24(xs, (int32_t)n), (int32_t)wt.y, acc);
+        }
+        return acc;
+    }
+}
+
+// grid.x = pixel groups (kOcWaves * ppw pixels each), grid.y = n_chunks * (oc_pad / 64).
+__global__ void __launch_bounds__(kOcWaves * 64) k_layer_oc_lane(const LayerParams p, int n_chunks, int kc, int ppw)
+{
+    __shared__ uint2 w_tile[kOcMaxTaps * 64];
+    __shared__ int2 tap_tab[kOcMaxTaps];
+    __shared__ uint32_t lists[kOcWaves][kOcMaxTaps];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = (int)uniform_u32(threadIdx.x >> 6);
+    const int chunk = blockIdx.y % n_chunks;
+    const int ocb = blockIdx.y / n_chunks;
+    const int k0 = chunk * kc;
+    const int kn = min(kc, p.K - k0);
+    if (kn <= 0) return;   // only possible when n_chunks > 1: nothing to add
+
+    // stage this chunk's weights (taps k0..k0+kn-1, channels ocb*64..+63): coalesced 512 B rows
+    for (int i = threadIdx.x; i < kn * 64; i += kOcWaves * 64)
+        w_tile[i] = p.tile[(int64_t)(k0 + (i >> 6)) * p.oc_pad + ocb * 64 + (i & 63)];
+    // tap table: offset of the tap inside one image relative to (iy0, ix0), and (kh, kw)
+    for (int t = threadIdx.x; t < kn; t += kOcWaves * 64) {
+        const int k = k0 + t;
+        const int khw = p.KH * p.KW;
+        const int ci = k / khw;
+        const int r = k - ci * khw;
+        const int kh = r / p.KW;
+        const int kw = r - kh * p.KW;
+        tap_tab[t] = make_int2((ci * p.H + kh) * p.W + kw, kh | (kw << 16));
+    }
+    __syncthreads();
+
+    Keys key;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        key.k0[r] = p.key0 + (uint32_t)r * kWeyl0;
+        key.k1[r] = p.key1 + (uint32_t)r * kWeyl1;
+    }
+
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int oc = ocb * 64 + lane;
+    uint32_t* list = lists[wave];
+
+    for (int it = 0; it < ppw; ++it) {
+        const int64_t pix = ((int64_t)blockIdx.x * ppw + it) * kOcWaves + wave;
+        if (pix >= npix) break;   // wave-uniform
+        const int ox = (int)(pix % p.OW);
+        const int oy = (int)((pix / p.OW) % p.OH);
+        const int n = (int)(pix / ((int64_t)p.OW * p.OH));
+
+        int to = p.budget_to ? (int)p.budget_to[pix] : p.S;
+        to = min(to, p.s_max);
+        int from = p.budget_from ? (int)p.budget_from[pix] : 0;
+        from = min(from, to);
+        to = (int)uniform_u32((uint32_t)to);
+        from = (int)uniform_u32((uint32_t)from);
+
+        const uint32_t o = (uint32_t)((((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox);
+        int32_t total = 0;
+
+        if (to > from) {
+            // gather this pixel's taps of the chunk and keep the non-zero ones
+            const int iy0 = oy * p.stride_h - p.pad_h;
+            const int ix0 = ox * p.stride_w - p.pad_w;
+            const int8_t* xb = p.x + (int64_t)n * p.C * p.H * p.W + (int64_t)iy0 * p.W + ix0;
+            int cnt = 0;
+            for (int t0 = 0; t0 < kn; t0 += 64) {
+                const int t = t0 + lane;
+                int32_t xv = 0;
+                if (t < kn) {
+                    const int2 info = tap_tab[t];
+                    const int iy = iy0 + (info.y & 0xFFFF);
+                    const int ix = ix0 + (info.y >> 16);
+                    if ((unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W) xv = xb[info.x];
+                }
+                const unsigned long long mask = __ballot(xv != 0);
+                const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                if (xv != 0) list[pos] = ((uint32_t)t << 8) | ((uint32_t)xv & 0xFFu);
+                cnt += __popcll(mask);
+            }
+            // the list is written and read by this wave only: order the LDS accesses
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+            if (cnt > 0) {
+                PixelHoist h;
+                uint32_t hi_a;
+                mulhilo(kMulA, o, hi_a, h.lo_a);                       // round 0: MulA * o
+                const uint32_t z1 = hi_a ^ p.layer_id ^ key.k1[0];      // state word 2 after round 0
+                uint32_t lo_b1;
+                mulhilo(kMulB, z1, h.hi_b1, lo_b1);                    // round 1: MulB * z1
+                h.y2k = lo_b1 ^ key.k0[2];
+
+                const int j0 = from >> 2;
+                const int nb = ((to + 3) >> 2) - j0;
+                const bool full = ((from | to) & 3) == 0;
+                const uint32_t kbase = (uint32_t)k0;
+                if (full) {
+                    switch (nb) {
+                        case 1: total = process_list<1, true>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                        case 2: total = process_list<2, true>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                        case 4: total = process_list<4, true>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                        case 8: total = process_list<8, true>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                        default: total = process_list<0, false>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                    }
+                } else if (nb == 1) {
+                    total = process_list<1, false>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key);
+                } else {
+                    total = process_list<0, false>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key);
+                }
+            }
+            // the next pixel overwrites the list: all reads of it must have completed
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        if (oc < p.OC) {
+            if (n_chunks == 1) {
+                if (p.budget_from) total += p.acc[o];
+                p.acc[o] = total;
+                if (p.y) p.y[o] = rescale(total, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+            } else if (total != 0) {
+                atomicAdd(&p.acc[o], total);
+            }
+        }
+    }
+}
+
+// acc[i] = 0  (a plain store kernel: safe inside a captured graph, unlike a memset node)
+__global__ void __launch_bounds__(256) k_fill_zero(int32_t* __restrict__ acc, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        acc[i] = 0;
+}
+
+// y = rescale(acc) for layers whose accumulators were combined with atomics.
+__global__ void __launch_bounds__(256) k_rescale(const LayerParams p)
+{
+    const int64_t total = (int64_t)p.N * p.OC * p.OH * p.OW;
+    const int64_t hw = (int64_t)p.OH * p.OW;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int oc = (int)((i / hw) % p.OC);
+        const int64_t pix = (i / (hw * p.OC)) * hw + (i % hw);
+        int to = p.budget_to ? (int)p.budget_to[pix] : p.S;
+        to = min(to, p.s_max);
+        p.y[i] = rescale(p.acc[i], p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+    }
+}
+
+// The channel-lane kernel needs groups = 1 and products that fit the 24-bit multiplier
+// (|x * count| < 2^17, unit <= 2^22).
+inline bool oc_lane_supported(const LayerParams& p) { return p.Cg == p.C && p.max_shift <= 22; }
+
+inline bool oc_lane_preferred(const LayerParams& p)
+{
+    // at least half of the 64 lanes of the last channel block must be real channels
+    return oc_lane_supported(p) && (p.OC % 64 == 0 || p.OC % 64 >= 32 || p.OC >= 256);
+}
+
+// Returns 0 or a hipError_t.
+typedef bool (*ProfileBegin)(hipStream_t, int*);
+typedef void (*ProfileEnd)(hipStream_t, int);
+
+inline int launch_oc_lane(const LayerParams& p, hipStream_t stream, ProfileBegin prof_begin, ProfileEnd prof_end)
+{
+    if (!oc_lane_supported(p)) return (int)hipErrorInvalidValue;
+    const int n_chunks = (p.K + kOcMaxTaps - 1) / kOcMaxTaps;
+    const int kc = (p.K + n_chunks - 1) / n_chunks;
+    const int n_ocb = p.oc_pad / 64;
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    // pixels per wave: enough wave-level work items to balance 1024 SIMDs, few enough
+    // weight-tile loads
+    const int64_t items = npix * n_chunks * n_ocb;
+    int ppw = (int)std::min<int64_t>(8, std::max<int64_t>(1, items / 65536));
+    const int64_t groups = (npix + (int64_t)kOcWaves * ppw - 1) / ((int64_t)kOcWaves * ppw);
+    const int64_t gy = (int64_t)n_chunks * n_ocb;
+    if (groups > 2147483647ll || gy > 65535) return (int)hipErrorInvalidValue;
+    const int64_t total = npix * p.OC;
+
+    if (n_chunks > 1 && !p.budget_from) {
+        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
+        hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, stream, p.acc, total);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return (int)e;
+    }
+    int slot = 0;
+    const bool timed = prof_begin(stream, &slot);
+    hipLaunchKernelGGL(k_layer_oc_lane, dim3((unsigned)groups, (unsigned)gy), dim3(kOcWaves * 64), 0, stream, p,
+                       n_chunks, kc, ppw);
+    if (timed) prof_end(stream, slot);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+    if (n_chunks > 1 && p.y) {
+        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
+        hipLaunchKernelGGL(k_rescale, dim3(blocks), dim3(256), 0, stream, p);
+        e = hipGetLastError();
+        if (e != hipSuccess) return (int)e;
+    }
+    return 0;
+}
+
+}  // namespace psb

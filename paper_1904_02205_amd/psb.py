@@ -1,0 +1,211 @@
+"""Thin Python binding of the C-ABI library (include/psb.h).
+
+Argument marshalling only: every step of the layer runs in the HIP kernels of
+libpsb_hip.so.  PyTorch supplies device memory (tensor.data_ptr()) and the stream.
+There is no fallback: if the library is missing or a call fails, PsbError is raised.
+"""
+import ctypes as C
+import os
+
+import torch
+
+from . import build as _build
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_VALUE, ERR_OVERFLOW_UNSAFE, ERR_TOO_LARGE, ERR_DEVICE, ERR_ALLOC = -1, -2, -3, -4, -5, -6, -7
+_NAMES = {0: "PSB_OK", -1: "PSB_ERR_NULL", -2: "PSB_ERR_SHAPE", -3: "PSB_ERR_VALUE",
+          -4: "PSB_ERR_OVERFLOW_UNSAFE", -5: "PSB_ERR_TOO_LARGE", -6: "PSB_ERR_DEVICE", -7: "PSB_ERR_ALLOC"}
+
+MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE = 0, 1, 2
+
+SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
+           "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
+           "psb_last_device_error", "psb_set_mapping", "psb_profile_enable", "psb_profile_read"]
+
+
+class PsbError(RuntimeError):
+    def __init__(self, code, where=""):
+        self.code = code
+        dev = ""
+        if code == ERR_DEVICE and _lib is not None:
+            dev = f" (hipError {_lib.psb_last_device_error()})"
+        super().__init__(f"{where}: {_NAMES.get(code, code)}{dev}")
+
+
+class WShape(C.Structure):
+    _fields_ = [("oc", C.c_int32), ("cin", C.c_int32), ("kh", C.c_int32), ("kw", C.c_int32), ("groups", C.c_int32)]
+
+
+class ConvGeom(C.Structure):
+    _fields_ = [("n", C.c_int32), ("h", C.c_int32), ("w", C.c_int32), ("stride_h", C.c_int32),
+                ("stride_w", C.c_int32), ("pad_h", C.c_int32), ("pad_w", C.c_int32)]
+
+
+class WInfo(C.Structure):
+    _fields_ = [("e_top", C.c_int32), ("e_min", C.c_int32), ("n_zero", C.c_int64), ("n_flushed", C.c_int64),
+                ("n_live", C.c_int64)]
+
+
+_lib = None
+
+
+def library_path():
+    return _build.LIB
+
+
+def lib():
+    """Load libpsb_hip.so (built in-tree; built here only if it does not exist)."""
+    global _lib
+    if _lib is None:
+        path = _build.ensure_built()
+        if not os.path.exists(path):
+            raise PsbError(ERR_DEVICE, f"HIP library {path} is missing")
+        L = C.CDLL(path)
+        vp, i32, u32, u64 = C.c_void_p, C.c_int32, C.c_uint32, C.c_uint64
+        L.psb_quantize_weights.argtypes = [vp, C.POINTER(WShape), i32, i32, i32, i32, vp, C.POINTER(vp)]
+        L.psb_weights_info.argtypes = [vp, C.POINTER(WInfo)]
+        L.psb_weights_export.argtypes = [vp, vp]
+        L.psb_weights_destroy.argtypes = [vp]
+        L.psb_weights_destroy.restype = None
+        L.psb_conv2d_out_dims.argtypes = [C.POINTER(WShape), C.POINTER(ConvGeom), C.POINTER(i32), C.POINTER(i32)]
+        L.psb_linear.argtypes = [vp, vp, i32, i32, u64, u32, vp, vp, vp, vp, vp]
+        L.psb_conv2d.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, u64, u32, vp, vp, vp, vp, vp]
+        L.psb_conv2d_progressive.argtypes = [vp, vp, C.POINTER(ConvGeom), vp, vp, u64, u32, vp, vp, vp, vp, vp]
+        L.psb_last_device_error.argtypes = []
+        L.psb_set_mapping.argtypes = [C.c_int]
+        L.psb_profile_enable.argtypes = [C.c_int]
+        L.psb_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        for name in SYMBOLS:
+            if name != "psb_weights_destroy":
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise PsbError(rc, where)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t, dtype, name):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{name}: expected a contiguous CUDA tensor of dtype {dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def set_mapping(mapping):
+    return lib().psb_set_mapping(int(mapping))
+
+
+def profile_enable(on=True):
+    _check(lib().psb_profile_enable(1 if on else 0), "psb_profile_enable")
+
+
+def profile_read():
+    """(sum of sampling-kernel milliseconds, number of launches) since the last read."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    _check(lib().psb_profile_read(C.byref(ms), C.byref(n)), "psb_profile_read")
+    return ms.value, n.value
+
+
+def conv2d_out_dims(wshape, geom):
+    """wshape = (oc, cin, kh, kw, groups); geom = (n, h, w, stride_h, stride_w, pad_h, pad_w)."""
+    oh, ow = C.c_int32(0), C.c_int32(0)
+    rc = lib().psb_conv2d_out_dims(C.byref(WShape(*wshape)), C.byref(ConvGeom(*geom)), C.byref(oh), C.byref(ow))
+    _check(rc, "psb_conv2d_out_dims")
+    return oh.value, ow.value
+
+
+class Weights:
+    """Handle returned by psb_quantize_weights."""
+
+    def __init__(self, w, groups=1, exp_bits=0, x_absmax=127, s_max=16, prob_bits=23):
+        """w: CUDA float32 [oc, cin/groups, kh, kw] (a 2-D [oc, k] tensor is a linear layer)."""
+        if w.dim() == 2:
+            w = w.reshape(w.shape[0], w.shape[1], 1, 1)
+        oc, cg, kh, kw = w.shape
+        self.wshape = (oc, cg * groups, kh, kw, groups)
+        self.K = cg * kh * kw
+        self.s_max = s_max
+        self._h = C.c_void_p(None)
+        shape = WShape(*self.wshape)
+        rc = lib().psb_quantize_weights(_ptr(w, torch.float32, "w"), C.byref(shape), prob_bits, exp_bits, x_absmax,
+                                        s_max, _stream(), C.byref(self._h))
+        _check(rc, "psb_quantize_weights")
+        info = WInfo()
+        _check(lib().psb_weights_info(self._h, C.byref(info)), "psb_weights_info")
+        self.e_top, self.e_min = info.e_top, info.e_min
+        self.n_zero, self.n_flushed, self.n_live = info.n_zero, info.n_flushed, info.n_live
+
+    def export(self):
+        """numpy uint32 [oc, K]: sign<<31 | shift<<23 | mantissa; shift 0xFF = not live."""
+        import numpy as np
+        out = np.empty((self.wshape[0], self.K), dtype=np.uint32)
+        _check(lib().psb_weights_export(self._h, out.ctypes.data_as(C.c_void_p)), "psb_weights_export")
+        return out
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib().psb_weights_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def linear(q, x, S, seed=0, layer_id=0, acc=None, y=None, mult=None, bias=None):
+    """x int8 [B, K] -> acc int32 [B, OC] (and y float32 if given)."""
+    B = x.shape[0]
+    oc = q.wshape[0]
+    if acc is None:
+        acc = torch.empty((B, oc), dtype=torch.int32, device=x.device)
+    rc = lib().psb_linear(q._h, _ptr(x, torch.int8, "x"), B, S, seed, layer_id, _ptr(acc, torch.int32, "acc"),
+                          _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"),
+                          _ptr(bias, torch.float32, "bias"), _stream())
+    _check(rc, "psb_linear")
+    return acc
+
+
+def _geom(x, stride, pad):
+    n, _, h, w = x.shape
+    return ConvGeom(n, h, w, stride[0], stride[1], pad[0], pad[1])
+
+
+def conv2d(q, x, S, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, acc=None, y=None, mult=None, bias=None):
+    """x int8 [N, C, H, W] -> acc int32 [N, OC, OH, OW]."""
+    g = _geom(x, stride, pad)
+    if acc is None:
+        oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
+        acc = torch.empty((g.n, q.wshape[0], oh, ow), dtype=torch.int32, device=x.device)
+    rc = lib().psb_conv2d(q._h, _ptr(x, torch.int8, "x"), C.byref(g), S, seed, layer_id,
+                          _ptr(acc, torch.int32, "acc"), _ptr(y, torch.float32, "y"),
+                          _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
+    _check(rc, "psb_conv2d")
+    return acc
+
+
+def conv2d_progressive(q, x, budget_to, budget_from=None, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, acc=None,
+                       y=None, mult=None, bias=None):
+    """budget_to / budget_from uint8 [N, OH, OW]; with budget_from, acc is updated in place."""
+    g = _geom(x, stride, pad)
+    if acc is None:
+        if budget_from is not None:
+            raise ValueError("a refinement call needs the accumulators of the first pass")
+        oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
+        acc = torch.empty((g.n, q.wshape[0], oh, ow), dtype=torch.int32, device=x.device)
+    rc = lib().psb_conv2d_progressive(q._h, _ptr(x, torch.int8, "x"), C.byref(g),
+                                      _ptr(budget_to, torch.uint8, "budget_to"),
+                                      _ptr(budget_from, torch.uint8, "budget_from"), seed, layer_id,
+                                      _ptr(acc, torch.int32, "acc"), _ptr(y, torch.float32, "y"),
+                                      _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
+    _check(rc, "psb_conv2d_progressive")
+    return acc

@@ -1,0 +1,87 @@
+"""The C-ABI library loads without a GPU, exports what include/psb.h declares, and rejects bad
+arguments on the host before any device work."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def psb():
+    from paper_1904_02205_amd import psb as m
+    m.lib()
+    return m
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "psb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(psb_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_library_agree(psb):
+    names = _declared()
+    assert set(names) == set(psb.SYMBOLS)
+    L = C.CDLL(psb.library_path())
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_out_dims_and_shape_errors(psb):
+    assert psb.conv2d_out_dims((64, 64, 3, 3, 1), (1, 56, 56, 1, 1, 1, 1)) == (56, 56)
+    assert psb.conv2d_out_dims((64, 3, 7, 7, 1), (32, 224, 224, 2, 2, 3, 3)) == (112, 112)
+    assert psb.conv2d_out_dims((128, 64, 1, 1, 1), (2, 56, 56, 2, 2, 0, 0)) == (28, 28)
+    assert psb.conv2d_out_dims((8, 8, 2, 3, 2), (1, 6, 8, 1, 2, 0, 2)) == (5, 5)
+    bad = [((0, 64, 3, 3, 1), (1, 8, 8, 1, 1, 1, 1), psb.ERR_SHAPE),
+           ((64, 64, 3, 3, 3), (1, 8, 8, 1, 1, 1, 1), psb.ERR_SHAPE),       # groups do not divide
+           ((64, 64, 3, 3, 1), (1, 8, 8, 0, 1, 1, 1), psb.ERR_SHAPE),       # stride 0
+           ((64, 64, 3, 3, 1), (1, 8, 8, 1, 1, -1, 1), psb.ERR_SHAPE),
+           ((64, 64, 9, 9, 1), (1, 4, 4, 1, 1, 1, 1), psb.ERR_SHAPE),       # kernel larger than padded input
+           ((64, 64, 3, 3, 1), (0, 8, 8, 1, 1, 1, 1), psb.ERR_SHAPE),
+           ((1024, 64, 1, 1, 1), (4096, 64, 64, 1, 1, 0, 0), psb.ERR_TOO_LARGE),   # 2^34 outputs
+           ((64, 1 << 22, 3, 3, 1), (1, 8, 8, 1, 1, 1, 1), psb.ERR_TOO_LARGE)]     # K >= 2^24
+    for ws, g, code in bad:
+        with pytest.raises(psb.PsbError) as ei:
+            psb.conv2d_out_dims(ws, g)
+        assert ei.value.code == code
+    L = psb.lib()
+    assert L.psb_conv2d_out_dims(None, None, None, None) == psb.ERR_NULL
+
+
+def test_null_arguments_are_rejected_before_any_device_work(psb):
+    L = psb.lib()
+    g = psb.ConvGeom(1, 8, 8, 1, 1, 1, 1)
+    ws = psb.WShape(4, 4, 3, 3, 1)
+    h = C.c_void_p(None)
+    assert L.psb_quantize_weights(None, C.byref(ws), 23, 0, 127, 8, None, C.byref(h)) == psb.ERR_NULL
+    assert L.psb_quantize_weights(C.c_void_p(16), None, 23, 0, 127, 8, None, C.byref(h)) == psb.ERR_NULL
+    assert L.psb_quantize_weights(C.c_void_p(16), C.byref(ws), 23, 0, 127, 8, None, None) == psb.ERR_NULL
+    # value errors are found before the pointer is ever dereferenced
+    for prob_bits, exp_bits, xmax, smax in ((8, 0, 127, 8), (23, 6, 127, 8), (23, 0, 0, 8), (23, 0, 129, 8),
+                                            (23, 0, 127, 0), (23, 0, 127, 256)):
+        assert L.psb_quantize_weights(C.c_void_p(16), C.byref(ws), prob_bits, exp_bits, xmax, smax, None,
+                                      C.byref(h)) == psb.ERR_VALUE
+    bad_ws = psb.WShape(4, 4, 0, 3, 1)
+    assert L.psb_quantize_weights(C.c_void_p(16), C.byref(bad_ws), 23, 0, 127, 8, None, C.byref(h)) == psb.ERR_SHAPE
+    assert L.psb_weights_info(None, None) == psb.ERR_NULL
+    assert L.psb_weights_export(None, None) == psb.ERR_NULL
+    L.psb_weights_destroy(None)
+    assert L.psb_linear(None, None, 1, 1, 0, 0, None, None, None, None, None) == psb.ERR_NULL
+    assert L.psb_conv2d(None, None, C.byref(g), 1, 0, 0, None, None, None, None, None) == psb.ERR_NULL
+    assert L.psb_conv2d_progressive(None, None, C.byref(g), None, None, 0, 0, None, None, None, None, None) == psb.ERR_NULL
+    assert L.psb_last_device_error() == 0
+
+
+def test_mapping_switch(psb):
+    prev = psb.set_mapping(psb.MAPPING_PIXEL_LANE)
+    assert psb.set_mapping(99) == psb.MAPPING_PIXEL_LANE      # out of range: ignored
+    assert psb.set_mapping(prev) == psb.MAPPING_PIXEL_LANE
+
+
+def test_binding_refuses_cpu_tensors(psb):
+    import torch
+    with pytest.raises(TypeError):
+        psb.Weights(torch.zeros(4, 4, 3, 3))

@@ -1,0 +1,77 @@
+"""BASELINE configurations at full size, in the launch configuration bench.py times (needs an MI355X).
+
+Configs 1, 2, 3 and 5 are compared with the oracle on every output element; the ResNet-18-shaped layers of
+config 4 (batch 32) on 20,000 randomly chosen output elements per layer, which the oracle computes one by
+one (possible because the random bits are keyed by output coordinate).
+"""
+import numpy as np
+import pytest
+
+import helpers
+from paper_1904_02205_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def psb():
+    from paper_1904_02205_amd import psb as m
+    m.lib()
+    m.set_mapping(m.MAPPING_AUTO)
+    return m
+
+
+def _full(psb, orc, L, **kw):
+    print(f"[config] {L.name} x{L.x.shape} w{L.w.shape} S={L.S} seed={L.seed}", flush=True)
+    qo = helpers.oracle_quantize(orc, L)
+    ref, over, smac = helpers.oracle_layer(orc, L, qo, **kw)
+    acc, y = helpers.gpu_layer(psb, L, want_y=True, **kw)
+    assert over == 0
+    assert np.array_equal(acc, ref)
+    ref_y = orc.rescale(ref, qo.e_min, S=None if L.budget_to is not None else L.S, s_max=L.s_max,
+                        budget_to=L.budget_to)
+    np.testing.assert_allclose(y, ref_y, rtol=1e-6, atol=0)
+    return smac
+
+
+def test_config1_linear(psb, orc):
+    assert _full(psb, orc, synth.config1()) == 64 * 8 * (256 * 512 - 6)
+
+
+def test_config2_conv3x3(psb, orc):
+    _full(psb, orc, synth.config2())
+
+
+def test_config3_progressive(psb, orc):
+    L = synth.config3()
+    _full(psb, orc, L)
+    # the incremental pair: 8 samples first (where the budget allows), then up to the budget
+    qo = helpers.oracle_quantize(orc, L)
+    qg = helpers.gpu_quantize(psb, L)
+    first = np.minimum(L.budget_to, 8).astype(np.uint8)
+    a1, _ = helpers.gpu_layer(psb, L, qg, budget_to=first)
+    a2, _ = helpers.gpu_layer(psb, L, qg, budget_to=L.budget_to, budget_from=first, acc_in=a1)
+    ref, _, _ = helpers.oracle_layer(orc, L, qo)
+    assert np.array_equal(a2, ref)
+
+
+def test_config5_mobilenet_block(psb, orc):
+    for L in synth.config5():
+        _full(psb, orc, L)
+
+
+def test_config4_resnet18_layers_sampled(psb, orc):
+    rng = np.random.default_rng(4040)
+    for L in synth.config4_layers():
+        print(f"[config4] {L.name} x{L.x.shape} w{L.w.shape}", flush=True)
+        qo = helpers.oracle_quantize(orc, L)
+        acc, y = helpers.gpu_layer(psb, L, want_y=True)
+        pts = rng.choice(acc.size, size=min(20000, acc.size), replace=False).astype(np.int64)
+        ref, over, _ = helpers.oracle_layer(orc, L, qo, points=pts)
+        assert over == 0
+        assert np.array_equal(acc.ravel()[pts], ref), L.name
+        ref_y = orc.rescale(ref.reshape(1, 1, -1), qo.e_min, S=L.S).ravel()
+        np.testing.assert_allclose(y.ravel()[pts], ref_y, rtol=1e-6, atol=0)
+        # properties that hold at any size: zero input rows give zero, and the call is repeatable
+        acc2, _ = helpers.gpu_layer(psb, L)
+        assert np.array_equal(acc, acc2)

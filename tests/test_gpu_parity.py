@@ -1,0 +1,269 @@
+"""HIP library vs CPU oracle, element by element, through the C-ABI (needs an MI355X).
+
+Bar: int32 accumulators and packed weights bit-exact; fp32 rescale bit-exact in practice, asserted to
+1e-6 relative as the contract states.
+"""
+import numpy as np
+import pytest
+
+import helpers
+from paper_1904_02205_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def psb():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_1904_02205_amd import psb as m
+    m.lib()                      # raises if the HIP library cannot be loaded: no fallback
+    yield m
+    m.set_mapping(m.MAPPING_AUTO)
+
+
+def _layer(rng, n, c, oc, hw, k, stride=1, pad=0, groups=1, S=8, s_max=None, std=None, xkind="relu", seed=11,
+           layer_id=3, prune=0.0):
+    h, w = hw if isinstance(hw, tuple) else (hw, hw)
+    kh, kw = k if isinstance(k, tuple) else (k, k)
+    wt = synth.he_normal((oc, c // groups, kh, kw), rng) if std is None else synth.normal_weights(
+        (oc, c // groups, kh, kw), std, rng)
+    if prune:
+        wt = synth.prune_by_magnitude(wt, prune)
+    if xkind == "relu":
+        x = synth.sparse_relu_int8((n, c, h, w), rng)
+    elif xkind == "signed":
+        x = rng.integers(-128, 128, size=(n, c, h, w)).astype(np.int8)
+    else:
+        x = synth.uniform_uint4((n, c, h, w), rng)
+    st = stride if isinstance(stride, tuple) else (stride, stride)
+    pd = pad if isinstance(pad, tuple) else (pad, pad)
+    return synth.Layer("t", wt, x, groups=groups, stride=st, pad=pd, S=S, s_max=s_max or S,
+                       x_absmax=128 if xkind == "signed" else 127, seed=seed, layer_id=layer_id)
+
+
+# ------------------------------------------------------------------ weight encoding
+
+def _weight_sets():
+    rng = np.random.default_rng(100)
+    sets = []
+    sets.append(("he", synth.he_normal((70, 20, 3, 3), rng), 127, 16, 0))
+    sets.append(("wide", (rng.standard_normal((5, 300)) * 10.0 ** rng.uniform(-8, 1, size=(5, 300))).astype(np.float32),
+                 127, 8, 0))
+    w = synth.prune_by_magnitude(synth.he_normal((160, 576, 1, 1), rng), 0.9)
+    sets.append(("pruned", w, 127, 16, 0))
+    w = synth.he_normal((9, 64), rng)
+    w[0, :] = 0.0
+    w[1, :5] = [1e-40, -1e-42, 2.0 ** -126, -0.0, 2.0 ** -140]
+    sets.append(("zeros_subnormals", w, 128, 4, 0))
+    sets.append(("exp3", synth.he_normal((33, 17, 3, 3), rng), 15, 32, 3))
+    sets.append(("exp5", synth.he_normal((33, 17, 3, 3), rng), 15, 2, 5))
+    sets.append(("exp1", synth.he_normal((4, 3, 3, 3), rng), 127, 255, 1))
+    sets.append(("tiny_all", (synth.he_normal((4, 8), rng) * 1e-37).astype(np.float32), 127, 8, 0))
+    sets.append(("only_subnormal", np.full((2, 3), 1e-41, np.float32), 127, 8, 0))
+    sets.append(("all_zero", np.zeros((3, 5), np.float32), 127, 8, 0))
+    return sets
+
+
+@pytest.mark.parametrize("case", _weight_sets(), ids=lambda c: c[0])
+def test_quantize_matches_oracle(psb, orc, case):
+    import torch
+    _, w, xmax, smax, eb = case
+    qo = orc.QWeights(w.reshape(w.shape[0], -1), exp_bits=eb, x_absmax=xmax, s_max=smax)
+    qg = psb.Weights(torch.from_numpy(w).cuda(), exp_bits=eb, x_absmax=xmax, s_max=smax)
+    assert (qg.n_zero, qg.n_flushed, qg.n_live) == (qo.n_zero, qo.n_flushed, qo.n_live)
+    if qo.n_live:
+        assert (qg.e_top, qg.e_min) == (qo.e_top, qo.e_min)
+    assert np.array_equal(qg.export(), helpers.pack_from_oracle(qo))
+
+
+def test_quantize_error_codes(psb, orc):
+    import torch
+    for bad in (np.nan, np.inf, -np.inf):
+        w = np.ones((2, 40), np.float32)
+        w[1, 17] = bad
+        with pytest.raises(psb.PsbError) as ei:
+            psb.Weights(torch.from_numpy(w).cuda())
+        assert ei.value.code == psb.ERR_VALUE
+    w = np.ones((1, 2 ** 16), np.float32)
+    with pytest.raises(psb.PsbError) as ei:
+        psb.Weights(torch.from_numpy(w).cuda(), x_absmax=128, s_max=255)
+    assert ei.value.code == psb.ERR_OVERFLOW_UNSAFE
+    with pytest.raises(orc.OracleError) as eo:
+        orc.QWeights(w, x_absmax=128, s_max=255)
+    assert eo.value.code == orc.ERR_OVERFLOW_UNSAFE
+    q = psb.Weights(torch.from_numpy(np.ones((4, 8), np.float32)).cuda(), s_max=8)
+    x = torch.zeros((2, 8), dtype=torch.int8, device="cuda")
+    for S in (0, -1, 9):
+        with pytest.raises(psb.PsbError) as ei:
+            psb.linear(q, x, S)
+        assert ei.value.code == psb.ERR_VALUE
+    with pytest.raises(psb.PsbError) as ei:         # a conv handle is not a linear layer
+        psb.linear(psb.Weights(torch.ones((4, 2, 3, 3), device="cuda")), x, 1)
+    assert ei.value.code == psb.ERR_SHAPE
+
+
+# ------------------------------------------------------------------ layers, both mappings
+
+def _cases():
+    rng = np.random.default_rng(200)
+    c = []
+    # (id, layer, mappings)
+    both = (1, 2)
+    c.append(("linear_small", _layer(rng, 5, 37, 9, 1, 1, S=8, xkind="u4", std=0.05), both))
+    c.append(("linear_ragged_oc", _layer(rng, 3, 130, 100, 1, 1, S=5, xkind="signed", std=0.05), both))
+    c.append(("conv3x3_multi_chunk", _layer(rng, 2, 20, 70, (9, 11), 3, pad=1, S=8), both))
+    c.append(("conv3x3_s16", _layer(rng, 1, 16, 64, 7, 3, pad=1, S=16), both))
+    c.append(("conv3x3_s32_signed", _layer(rng, 1, 8, 32, 6, 3, pad=1, S=32, xkind="signed"), both))
+    c.append(("conv7x7_s2_p3", _layer(rng, 2, 3, 16, (23, 19), 7, stride=2, pad=3, S=8, xkind="signed"), both))
+    c.append(("conv1x1_s2", _layer(rng, 2, 24, 40, 9, 1, stride=2, S=4), both))
+    c.append(("conv_rect_kernel", _layer(rng, 1, 6, 12, (6, 8), (2, 3), stride=(1, 2), pad=(0, 2), S=3), both))
+    c.append(("conv_s1", _layer(rng, 1, 5, 7, 5, 3, pad=1, S=1), both))
+    c.append(("conv_s2samples", _layer(rng, 1, 9, 66, 6, 3, pad=1, S=2), both))
+    c.append(("conv_s12", _layer(rng, 1, 9, 10, 6, 3, pad=1, S=12), both))
+    c.append(("conv_pad3_tiny_image", _layer(rng, 1, 4, 8, 2, 3, pad=3, S=4), both))
+    c.append(("pruned_pointwise", _layer(rng, 2, 96, 40, 5, 1, S=16, prune=0.9), both))
+    c.append(("grouped", _layer(rng, 2, 8, 12, 7, 3, pad=1, groups=4, S=8), (1,)))
+    c.append(("depthwise", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), (1,)))
+    c.append(("depthwise_s2", _layer(rng, 1, 10, 10, 8, 3, stride=2, pad=1, groups=10, S=4, xkind="signed"), (1,)))
+    return c
+
+
+@pytest.mark.parametrize("case", _cases(), ids=lambda c: c[0])
+def test_layer_bit_exact(psb, orc, case):
+    _, L, mappings = case
+    ref, over, _ = helpers.oracle_layer(orc, L)
+    assert over == 0
+    for m in mappings:
+        psb.set_mapping(m)
+        acc, _ = helpers.gpu_layer(psb, L)
+        assert np.array_equal(acc, ref), f"mapping {m}"
+    psb.set_mapping(psb.MAPPING_AUTO)
+    acc, _ = helpers.gpu_layer(psb, L)
+    assert np.array_equal(acc, ref)
+    acc2, _ = helpers.gpu_layer(psb, L)          # same call again: same bits
+    assert np.array_equal(acc2, ref)
+
+
+def test_channel_lane_refuses_grouped_layers(psb):
+    rng = np.random.default_rng(201)
+    L = _layer(rng, 1, 8, 8, 5, 3, pad=1, groups=2, S=4)
+    psb.set_mapping(psb.MAPPING_CHANNEL_LANE)
+    with pytest.raises(psb.PsbError) as ei:
+        helpers.gpu_layer(psb, L)
+    assert ei.value.code == psb.ERR_SHAPE
+    psb.set_mapping(psb.MAPPING_AUTO)
+
+
+def test_seed_and_layer_id_select_the_stream(psb, orc):
+    rng = np.random.default_rng(202)
+    L = _layer(rng, 1, 8, 64, 5, 3, pad=1, S=8)
+    outs = []
+    for seed, lid in ((0, 0), (2 ** 63 + 12345, 0), (0, 7), (0xFFFFFFFFFFFFFFFF, 0xFFFFFFFF)):
+        L.seed, L.layer_id = seed, lid
+        ref, _, _ = helpers.oracle_layer(orc, L)
+        for m in (1, 2):
+            psb.set_mapping(m)
+            acc, _ = helpers.gpu_layer(psb, L)
+            assert np.array_equal(acc, ref)
+        outs.append(ref)
+    psb.set_mapping(psb.MAPPING_AUTO)
+    assert not np.array_equal(outs[0], outs[1]) and not np.array_equal(outs[0], outs[2])
+
+
+# ------------------------------------------------------------------ progressive budgets
+
+@pytest.mark.parametrize("mapping", [1, 2])
+def test_progressive_bit_exact_and_incremental(psb, orc, mapping):
+    rng = np.random.default_rng(300)
+    L = _layer(rng, 3, 12, 70, (9, 8), 3, pad=1, S=32, s_max=32)
+    oh, ow = L.out_hw
+    to = rng.choice([0, 1, 2, 3, 4, 7, 8, 16, 31, 32, 40], size=(3, oh, ow)).astype(np.uint8)   # 40 is clamped to 32
+    qo = helpers.oracle_quantize(orc, L)
+    ref, over, _ = helpers.oracle_layer(orc, L, qo, budget_to=to)
+    assert over == 0
+    psb.set_mapping(mapping)
+    qg = helpers.gpu_quantize(psb, L)
+    acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to)
+    assert np.array_equal(acc, ref)
+    # two-call form: first min(to, m) samples, then the rest on top, for aligned and unaligned splits
+    for m in (8, 2, 5):
+        first = np.minimum(to, m).astype(np.uint8)
+        a1, _ = helpers.gpu_layer(psb, L, qg, budget_to=first)
+        r1, _, _ = helpers.oracle_layer(orc, L, qo, budget_to=first)
+        assert np.array_equal(a1, r1)
+        a2, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, budget_from=first, acc_in=a1)
+        assert np.array_equal(a2, ref)
+    # from > to is clamped to an empty range: accumulators unchanged
+    a3, _ = helpers.gpu_layer(psb, L, qg, budget_to=first, budget_from=to, acc_in=a1)
+    assert np.array_equal(a3, a1)
+    psb.set_mapping(psb.MAPPING_AUTO)
+
+
+def test_progressive_constant_map_equals_plain_call(psb):
+    rng = np.random.default_rng(301)
+    L = _layer(rng, 2, 10, 64, 6, 3, pad=1, S=8, s_max=16)
+    oh, ow = L.out_hw
+    q = helpers.gpu_quantize(psb, L)
+    plain, _ = helpers.gpu_layer(psb, L, q)
+    prog, _ = helpers.gpu_layer(psb, L, q, budget_to=np.full((2, oh, ow), 8, np.uint8))
+    assert np.array_equal(plain, prog)
+
+
+# ------------------------------------------------------------------ fp32 rescale
+
+@pytest.mark.parametrize("mapping", [1, 2])
+def test_rescale_matches_oracle(psb, orc, mapping):
+    rng = np.random.default_rng(400)
+    psb.set_mapping(mapping)
+    for S, prog in ((8, False), (7, False), (16, True)):
+        L = _layer(rng, 2, 20, 70, 6, 3, pad=1, S=S, s_max=32)          # 3 chunks: rescale runs as its own kernel
+        oh, ow = L.out_hw
+        to = rng.choice([0, 2, 3, 8, 16, 32], size=(2, oh, ow)).astype(np.uint8) if prog else None
+        qo = helpers.oracle_quantize(orc, L)
+        mult = (np.ldexp(1.0, qo.e_min) * rng.uniform(0.5, 2.0, size=70)).astype(np.float32)
+        bias = rng.standard_normal(70).astype(np.float32)
+        for mu, bi in ((None, None), (mult, bias)):
+            acc, y = helpers.gpu_layer(psb, L, budget_to=to, want_y=True, mult=mu, bias=bi)
+            ref_acc, _, _ = helpers.oracle_layer(orc, L, qo, budget_to=to)
+            ref_y = orc.rescale(ref_acc, qo.e_min, S=None if prog else S, s_max=32, budget_to=to, mult=mu, bias=bi)
+            assert np.array_equal(acc, ref_acc)
+            assert np.array_equal(y, ref_y)                       # in practice: 0 ulp
+            np.testing.assert_allclose(y, ref_y, rtol=1e-6, atol=0)
+    # single chunk: rescale fused into the layer kernel
+    L = _layer(rng, 3, 40, 64, 1, 1, S=5, s_max=8, xkind="u4", std=0.05)
+    L.linear = True
+    qo = helpers.oracle_quantize(orc, L)
+    acc, y = helpers.gpu_layer(psb, L, want_y=True)
+    ref_acc, _, _ = helpers.oracle_layer(orc, L, qo)
+    assert np.array_equal(acc, ref_acc)
+    assert np.array_equal(y, orc.rescale(ref_acc, qo.e_min, S=5))
+    psb.set_mapping(psb.MAPPING_AUTO)
+
+
+# ------------------------------------------------------------------ generator cross-check on the box
+
+def test_oracle_philox_against_rocrand_host_generator(orc):
+    """An independent implementation of Philox4x32-10 (rocRAND's host generator, if the library is there)."""
+    import ctypes as C
+    try:
+        R = C.CDLL("librocrand.so")
+    except OSError:
+        pytest.skip("rocRAND not installed")
+    gen = C.c_void_p()
+    if R.rocrand_create_generator_host(C.byref(gen), 404) != 0:      # ROCRAND_RNG_PSEUDO_PHILOX4_32_10
+        pytest.skip("rocRAND host generator unavailable")
+    R.rocrand_set_seed.argtypes = [C.c_void_p, C.c_ulonglong]
+    R.rocrand_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+    seed = 0x0123456789ABCDEF
+    assert R.rocrand_set_seed(gen, seed) == 0
+    out = np.zeros(64, dtype=np.uint32)
+    if R.rocrand_generate(gen, out.ctypes.data_as(C.c_void_p), out.size) != 0:
+        pytest.skip("rocRAND host generation failed")
+    R.rocrand_destroy_generator(gen)
+    # whatever order the library emits its blocks in, the first 64 words must be made of the blocks of
+    # counters 0..15 under key (seed lo, seed hi)
+    key = [seed & 0xFFFFFFFF, seed >> 32]
+    blocks = {tuple(orc.philox([c, 0, 0, 0], key)) for c in range(16)}
+    got = {tuple(int(v) for v in out[i:i + 4]) for i in range(0, 64, 4)}
+    assert got == blocks
