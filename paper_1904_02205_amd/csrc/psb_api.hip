@@ -22,6 +22,7 @@ struct psb_weights {
     int device;
     uint32_t* packed_dev;    // [OC][K]
     uint2* tile_dev;         // [K][oc_pad] {threshold, unit}
+    uint32_t* sched_dev;     // ticket counter and finish counter of the persistent kernel (both 0 between calls)
 };
 
 namespace {
@@ -143,7 +144,7 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
     if (mapping == 0) mapping = psb::oc_lane_preferred(p) ? 2 : 1;
 
     if (mapping == 2) {
-        rc = psb::launch_oc_lane(p, stream, profile_begin, profile_end);
+        rc = psb::launch_oc_lane(p, q->sched_dev, stream, profile_begin, profile_end);
         if (rc != 0) { tl_last_device_error = rc; return PSB_ERR_DEVICE; }
     } else {
         const int64_t npix = (int64_t)p.N * OH * OW;
@@ -244,7 +245,9 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     if (hipMalloc(&q->packed_dev, (size_t)nw * sizeof(uint32_t)) != hipSuccess) return fail(PSB_ERR_ALLOC, hipSuccess);
     if (hipMalloc(&q->tile_dev, (size_t)oc_pad * K * sizeof(uint2)) != hipSuccess)
         return fail(PSB_ERR_ALLOC, hipSuccess);
+    if (hipMalloc(&q->sched_dev, 2 * sizeof(uint32_t)) != hipSuccess) return fail(PSB_ERR_ALLOC, hipSuccess);
     QTRY(hipMemsetAsync(scratch, 0, scratch_words * sizeof(uint32_t), stream));
+    QTRY(hipMemsetAsync(q->sched_dev, 0, 2 * sizeof(uint32_t), stream));
 
     // 1. largest exponent, NaN/Inf detection
     {
@@ -318,6 +321,7 @@ void psb_weights_destroy(psb_weights_t* q)
     if (!q) return;
     if (q->packed_dev) (void)hipFree(q->packed_dev);
     if (q->tile_dev) (void)hipFree(q->tile_dev);
+    if (q->sched_dev) (void)hipFree(q->sched_dev);
     delete q;
 }
 

@@ -24,11 +24,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cstdlib>
+
 #include "psb_kernels.hip.h"
 
 namespace psb {
 
-constexpr int kOcWaves = 4;     // waves per workgroup
+constexpr int kOcWaves = 4;     // default waves per workgroup (the kernel is also built for 8)
 constexpr int kOcMaxTaps = 64;  // taps per LDS tile: 64 * 64 channels * 8 B = 32 KB
 
 __device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
@@ -42,7 +44,41 @@ struct PixelHoist {
     uint32_t y2k;     // low half of the same product, xor round-2 key 0
 };
 
-struct Keys { uint32_t k0[10], k1[10]; };
+// Round keys as the scalar unit sees them, plus copies of the keys of rounds 3..9 and of the
+// two multipliers that are pinned to vector registers: on gfx950 a two-operand VALU
+// instruction with a scalar-register source issues at half the rate of one whose sources
+// are both vector registers (4.2 vs 2.4 cycles per wave64, measured), and fourteen of the
+// xors of a call have a round key as operand.
+struct Keys {
+    uint32_t k0[10], k1[10];
+    uint32_t vk0[7], vk1[7];   // rounds 3..9, in VGPRs
+    uint32_t vmul_a, vmul_b;   // kMulA, kMulB in VGPRs
+};
+
+__device__ __forceinline__ uint32_t pin_to_vgpr(uint32_t s)
+{
+    uint32_t v;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(v) : "s"(s));
+    return v;
+}
+
+// Rounds 3..9 with every operand in a vector register.
+__device__ __forceinline__ u32x4 philox_rounds_3_to_9(u32x4 c, const Keys& key)
+{
+#pragma unroll
+    for (int r = 0; r < 7; ++r) {
+        uint32_t hi_a, lo_a, hi_b, lo_b;
+        mulhilo(key.vmul_a, c.x, hi_a, lo_a);
+        mulhilo(key.vmul_b, c.z, hi_b, lo_b);
+        u32x4 t;
+        t.x = hi_b ^ c.y ^ key.vk0[r];
+        t.y = lo_b;
+        t.z = hi_a ^ c.w ^ key.vk1[r];
+        t.w = lo_a;
+        c = t;
+    }
+    return c;
+}
 
 // Count, for one product, how many of the samples of block j are below thr, and add to n.
 // s_* arguments are wave-uniform.
@@ -58,13 +94,13 @@ __device__ __forceinline__ uint32_t sample_block(uint32_t n, uint32_t thr, uint3
     const uint32_t z2 = (s_hi ^ key.k1[1]) ^ h.lo_a;
     // round 2: only MulB * z2 is new
     uint32_t hi_b2, lo_b2;
-    mulhilo(kMulB, z2, hi_b2, lo_b2);
+    mulhilo(key.vmul_b, z2, hi_b2, lo_b2);
     u32x4 c;
     c.x = hi_b2 ^ h.y2k;
     c.y = lo_b2;
     c.z = hz ^ s_lo;
     c.w = lo2;
-    c = philox_rounds_from<3>(c, key.k0[0], key.k1[0]);
+    c = philox_rounds_3_to_9(c, key);
     if (FULL) {
         n += (c.x < thr) ? 1u : 0u;
         n += (c.y < thr) ? 1u : 0u;
@@ -94,19 +130,26 @@ __device__ __forceinline__ void block_setup(const PixelHoist& h, const Keys& key
     lo2 = lo_a2;
 }
 
+// Entry i of the wave's compacted tap list; the list lives in one VGPR (lane i = entry i).
+__device__ __forceinline__ uint32_t list_entry(uint32_t mylist, int i)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)mylist, i);
+}
+
 // All products of one pixel's compacted tap list, NB generator blocks per product
 // (NB = 0: run-time number of blocks).  Returns this lane's partial accumulator.
+// mylist: lane i holds entry i = (tap index inside the tile << 8) | activation byte, and 0
+// beyond cnt (entry 0 addresses tile row 0, so reading one group ahead is always in bounds).
 template <int NB, bool FULL>
-__device__ __forceinline__ int32_t process_list(const uint32_t* __restrict__ list, int cnt,
-                                                const uint2* __restrict__ w_tile, int lane, uint32_t k0,
-                                                int j0, int nb_rt, int from, int to, const PixelHoist& h,
-                                                const Keys& key)
+__device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const uint2* __restrict__ w_tile,
+                                                int lane, uint32_t k0, int j0, int nb_rt, int from, int to,
+                                                const PixelHoist& h, const Keys& key)
 {
     const uint32_t nsamp = (uint32_t)(to - from);
     int32_t acc = 0;
     if constexpr (NB == 0) {
         for (int i = 0; i < cnt; ++i) {
-            const uint32_t entry = uniform_u32(list[i]);
+            const uint32_t entry = list_entry(mylist, i);
             const uint32_t kl = entry >> 8;
             const int32_t xs = (int32_t)(int8_t)(entry & 0xFFu);
             const uint2 wt = w_tile[kl * 64 + lane];
@@ -125,20 +168,30 @@ __device__ __forceinline__ int32_t process_list(const uint32_t* __restrict__ lis
 #pragma unroll
         for (int jj = 0; jj < NB; ++jj) block_setup(h, key, j0 + jj, s_hib[jj], hz[jj], lo2[jj]);
 
+        // software pipeline: the weights of group g+1 are read from LDS while group g is sampled
+        uint32_t ent_next[E];
+        uint2 wt_next[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            ent_next[e] = list_entry(mylist, e);
+            wt_next[e] = w_tile[(ent_next[e] >> 8) * 64 + lane];
+        }
         int i = 0;
         for (; i + E <= cnt; i += E) {
-            uint32_t n[E];
+            uint32_t n[E], kk[E];
             uint2 wt[E];
             int32_t xs[E];
-            uint32_t kk[E];
 #pragma unroll
             for (int e = 0; e < E; ++e) {
-                const uint32_t entry = uniform_u32(list[i + e]);
-                const uint32_t kl = entry >> 8;
-                xs[e] = (int32_t)(int8_t)(entry & 0xFFu);
-                wt[e] = w_tile[kl * 64 + lane];
-                kk[e] = k0 + kl;
+                xs[e] = (int32_t)(int8_t)(ent_next[e] & 0xFFu);
+                kk[e] = k0 + (ent_next[e] >> 8);
+                wt[e] = wt_next[e];
                 n[e] = nsamp;
+            }
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                ent_next[e] = list_entry(mylist, (i + E + e) & 63);
+                wt_next[e] = w_tile[(ent_next[e] >> 8) * 64 + lane];
             }
 #pragma unroll
             for (int e = 0; e < E; ++e)
@@ -149,50 +202,41 @@ __device__ __forceinline__ int32_t process_list(const uint32_t* __restrict__ lis
 #pragma unroll
             for (int e = 0; e < E; ++e) acc = mad24(__mul24(xs[e], (int32_t)n[e]), (int32_t)wt[e].y, acc);
         }
-        for (; i < cnt; ++i) {
-            const uint32_t entry = uniform_u32(list[i]);
-            const uint32_t kl = entry >> 8;
-            const int32_t xs = (int32_t)(int8_t)(entry & 0xFFu);
-            const uint2 wt = w_tile[kl * 64 + lane];
-            uint32_t n = nsamp;
+        if constexpr (E > 1) {
+            for (; i < cnt; ++i) {      // fewer than E products left
+                const uint32_t entry = list_entry(mylist, i);
+                const uint2 wt = w_tile[(entry >> 8) * 64 + lane];
+                uint32_t n = nsamp;
 #pragma unroll
-            for (int jj = 0; jj < NB; ++jj)
-                n = sample_block<FULL>(n, wt.x, s_hib[jj] ^ (k0 + kl), h, hz[jj], lo2[jj], key, j0 + jj, from, to);
-            acc = mad24(__mul24(xs, (int32_t)n), (int32_t)wt.y, acc);
+                for (int jj = 0; jj < NB; ++jj)
+                    n = sample_block<FULL>(n, wt.x, s_hib[jj] ^ (k0 + (entry >> 8)), h, hz[jj], lo2[jj], key, j0 + jj,
+                                           from, to);
+                acc = mad24(__mul24((int32_t)(int8_t)(entry & 0xFFu), (int32_t)n), (int32_t)wt.y, acc);
+            }
         }
         return acc;
     }
 }
 
-// grid.x = pixel groups (kOcWaves * ppw pixels each), grid.y = n_chunks * (oc_pad / 64).
-__global__ void __launch_bounds__(kOcWaves * 64) k_layer_oc_lane(const LayerParams p, int n_chunks, int kc, int ppw)
+// Persistent kernel.  A ticket is one (channel block, tap chunk, group of WAVES pixels);
+// tickets are numbered so that consecutive tickets are consecutive pixel groups of the same
+// (channel block, chunk).  Workgroups draw tickets from a device counter until none is left:
+// the grid is only as large as the chip can hold at once, there is no launch gap between
+// work items, and the tail at the end of the kernel is at most one ticket long.
+//   sched[0] = next ticket, sched[1] = number of workgroups that have finished.  Both are 0
+//   before the launch; the last workgroup to finish sets them back to 0.
+template <int WAVES>
+__global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams p, int n_chunks, int kc,
+                                                              uint32_t pixel_groups, uint32_t n_tickets,
+                                                              uint32_t* __restrict__ sched)
 {
     __shared__ uint2 w_tile[kOcMaxTaps * 64];
     __shared__ int2 tap_tab[kOcMaxTaps];
-    __shared__ uint32_t lists[kOcWaves][kOcMaxTaps];
+    __shared__ uint32_t lists[WAVES][kOcMaxTaps];
+    __shared__ uint32_t s_ticket;
 
     const int lane = threadIdx.x & 63;
     const int wave = (int)uniform_u32(threadIdx.x >> 6);
-    const int chunk = blockIdx.y % n_chunks;
-    const int ocb = blockIdx.y / n_chunks;
-    const int k0 = chunk * kc;
-    const int kn = min(kc, p.K - k0);
-    if (kn <= 0) return;   // only possible when n_chunks > 1: nothing to add
-
-    // stage this chunk's weights (taps k0..k0+kn-1, channels ocb*64..+63): coalesced 512 B rows
-    for (int i = threadIdx.x; i < kn * 64; i += kOcWaves * 64)
-        w_tile[i] = p.tile[(int64_t)(k0 + (i >> 6)) * p.oc_pad + ocb * 64 + (i & 63)];
-    // tap table: offset of the tap inside one image relative to (iy0, ix0), and (kh, kw)
-    for (int t = threadIdx.x; t < kn; t += kOcWaves * 64) {
-        const int k = k0 + t;
-        const int khw = p.KH * p.KW;
-        const int ci = k / khw;
-        const int r = k - ci * khw;
-        const int kh = r / p.KW;
-        const int kw = r - kh * p.KW;
-        tap_tab[t] = make_int2((ci * p.H + kh) * p.W + kw, kh | (kw << 16));
-    }
-    __syncthreads();
 
     Keys key;
 #pragma unroll
@@ -200,94 +244,141 @@ __global__ void __launch_bounds__(kOcWaves * 64) k_layer_oc_lane(const LayerPara
         key.k0[r] = p.key0 + (uint32_t)r * kWeyl0;
         key.k1[r] = p.key1 + (uint32_t)r * kWeyl1;
     }
+#pragma unroll
+    for (int r = 0; r < 7; ++r) {
+        key.vk0[r] = pin_to_vgpr(key.k0[r + 3]);
+        key.vk1[r] = pin_to_vgpr(key.k1[r + 3]);
+    }
+    key.vmul_a = pin_to_vgpr(kMulA);
+    key.vmul_b = pin_to_vgpr(kMulB);
 
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
-    const int oc = ocb * 64 + lane;
     uint32_t* list = lists[wave];
+    uint32_t staged = 0xFFFFFFFFu;   // (channel block, chunk) whose weights are in w_tile
 
-    for (int it = 0; it < ppw; ++it) {
-        const int64_t pix = ((int64_t)blockIdx.x * ppw + it) * kOcWaves + wave;
-        if (pix >= npix) break;   // wave-uniform
-        const int ox = (int)(pix % p.OW);
-        const int oy = (int)((pix / p.OW) % p.OH);
-        const int n = (int)(pix / ((int64_t)p.OW * p.OH));
+    for (;;) {
+        if (threadIdx.x == 0) s_ticket = atomicAdd(&sched[0], 1u);
+        __syncthreads();
+        const uint32_t ticket = s_ticket;
+        if (ticket >= n_tickets) break;   // uniform over the workgroup
+        const uint32_t combo = ticket / pixel_groups;
+        const uint32_t pgroup = ticket - combo * pixel_groups;
+        const int chunk = (int)(combo % (uint32_t)n_chunks);
+        const int ocb = (int)(combo / (uint32_t)n_chunks);
+        const int k0 = chunk * kc;
+        const int kn = min(kc, p.K - k0);   // > 0: the launcher sizes n_chunks so that no chunk is empty
 
-        int to = p.budget_to ? (int)p.budget_to[pix] : p.S;
-        to = min(to, p.s_max);
-        int from = p.budget_from ? (int)p.budget_from[pix] : 0;
-        from = min(from, to);
-        to = (int)uniform_u32((uint32_t)to);
-        from = (int)uniform_u32((uint32_t)from);
-
-        const uint32_t o = (uint32_t)((((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox);
-        int32_t total = 0;
-
-        if (to > from) {
-            // gather this pixel's taps of the chunk and keep the non-zero ones
-            const int iy0 = oy * p.stride_h - p.pad_h;
-            const int ix0 = ox * p.stride_w - p.pad_w;
-            const int8_t* xb = p.x + (int64_t)n * p.C * p.H * p.W + (int64_t)iy0 * p.W + ix0;
-            int cnt = 0;
-            for (int t0 = 0; t0 < kn; t0 += 64) {
-                const int t = t0 + lane;
-                int32_t xv = 0;
-                if (t < kn) {
-                    const int2 info = tap_tab[t];
-                    const int iy = iy0 + (info.y & 0xFFFF);
-                    const int ix = ix0 + (info.y >> 16);
-                    if ((unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W) xv = xb[info.x];
-                }
-                const unsigned long long mask = __ballot(xv != 0);
-                const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-                if (xv != 0) list[pos] = ((uint32_t)t << 8) | ((uint32_t)xv & 0xFFu);
-                cnt += __popcll(mask);
+        if (combo != staged) {
+            // stage this chunk's weights (taps k0..k0+kn-1, channels ocb*64..+63): coalesced 512 B rows
+            for (int i = threadIdx.x; i < kn * 64; i += WAVES * 64)
+                w_tile[i] = p.tile[(int64_t)(k0 + (i >> 6)) * p.oc_pad + ocb * 64 + (i & 63)];
+            // tap table: offset of the tap inside one image relative to (iy0, ix0), and (kh, kw)
+            for (int t = threadIdx.x; t < kn; t += WAVES * 64) {
+                const int k = k0 + t;
+                const int khw = p.KH * p.KW;
+                const int ci = k / khw;
+                const int r = k - ci * khw;
+                const int kh = r / p.KW;
+                const int kw = r - kh * p.KW;
+                tap_tab[t] = make_int2((ci * p.H + kh) * p.W + kw, kh | (kw << 16));
             }
-            // the list is written and read by this wave only: order the LDS accesses
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-            if (cnt > 0) {
-                PixelHoist h;
-                uint32_t hi_a;
-                mulhilo(kMulA, o, hi_a, h.lo_a);                       // round 0: MulA * o
-                const uint32_t z1 = hi_a ^ p.layer_id ^ key.k1[0];      // state word 2 after round 0
-                uint32_t lo_b1;
-                mulhilo(kMulB, z1, h.hi_b1, lo_b1);                    // round 1: MulB * z1
-                h.y2k = lo_b1 ^ key.k0[2];
-
-                const int j0 = from >> 2;
-                const int nb = ((to + 3) >> 2) - j0;
-                const bool full = ((from | to) & 3) == 0;
-                const uint32_t kbase = (uint32_t)k0;
-                if (full) {
-                    switch (nb) {
-                        case 1: total = process_list<1, true>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
-                        case 2: total = process_list<2, true>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
-                        case 4: total = process_list<4, true>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
-                        case 8: total = process_list<8, true>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
-                        default: total = process_list<0, false>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
-                    }
-                } else if (nb == 1) {
-                    total = process_list<1, false>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key);
-                } else {
-                    total = process_list<0, false>(list, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key);
-                }
-            }
-            // the next pixel overwrites the list: all reads of it must have completed
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+            staged = combo;
         }
+        __syncthreads();
 
-        if (oc < p.OC) {
-            if (n_chunks == 1) {
-                if (p.budget_from) total += p.acc[o];
-                p.acc[o] = total;
-                if (p.y) p.y[o] = rescale(total, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
-            } else if (total != 0) {
-                atomicAdd(&p.acc[o], total);
+        const int oc = ocb * 64 + lane;
+        const int64_t pix = (int64_t)pgroup * WAVES + wave;
+        if (pix < npix) {   // wave-uniform
+            const int ox = (int)(pix % p.OW);
+            const int oy = (int)((pix / p.OW) % p.OH);
+            const int n = (int)(pix / ((int64_t)p.OW * p.OH));
+
+            int to = p.budget_to ? (int)p.budget_to[pix] : p.S;
+            to = min(to, p.s_max);
+            int from = p.budget_from ? (int)p.budget_from[pix] : 0;
+            from = min(from, to);
+            to = (int)uniform_u32((uint32_t)to);
+            from = (int)uniform_u32((uint32_t)from);
+
+            const uint32_t o = (uint32_t)((((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox);
+            int32_t total = 0;
+
+            if (to > from) {
+                // gather this pixel's taps of the chunk and keep the non-zero ones
+                const int iy0 = oy * p.stride_h - p.pad_h;
+                const int ix0 = ox * p.stride_w - p.pad_w;
+                const int8_t* xb = p.x + (int64_t)n * p.C * p.H * p.W + (int64_t)iy0 * p.W + ix0;
+                int cnt = 0;
+                for (int t0 = 0; t0 < kn; t0 += 64) {
+                    const int t = t0 + lane;
+                    int32_t xv = 0;
+                    if (t < kn) {
+                        const int2 info = tap_tab[t];
+                        const int iy = iy0 + (info.y & 0xFFFF);
+                        const int ix = ix0 + (info.y >> 16);
+                        if ((unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W) xv = xb[info.x];
+                    }
+                    const unsigned long long mask = __ballot(xv != 0);
+                    const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                    if (xv != 0) list[pos] = ((uint32_t)t << 8) | ((uint32_t)xv & 0xFFu);
+                    cnt += __popcll(mask);
+                }
+                // the list is written and read by this wave only: order the LDS accesses
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+                if (cnt > 0) {
+                    const uint32_t mylist = (lane < cnt) ? list[lane] : 0u;
+                    PixelHoist h;
+                    uint32_t hi_a;
+                    mulhilo(kMulA, o, hi_a, h.lo_a);                       // round 0: MulA * o
+                    const uint32_t z1 = hi_a ^ p.layer_id ^ key.k1[0];      // state word 2 after round 0
+                    uint32_t lo_b1;
+                    mulhilo(kMulB, z1, h.hi_b1, lo_b1);                    // round 1: MulB * z1
+                    h.y2k = lo_b1 ^ key.k0[2];
+
+                    const int j0 = from >> 2;
+                    const int nb = ((to + 3) >> 2) - j0;
+                    const bool full = ((from | to) & 3) == 0;
+                    const uint32_t kbase = (uint32_t)k0;
+                    if (full) {
+                        switch (nb) {
+                            case 1: total = process_list<1, true>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                            case 2: total = process_list<2, true>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                            case 4: total = process_list<4, true>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                            case 8: total = process_list<8, true>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                            default: total = process_list<0, false>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                        }
+                    } else if (nb == 1) {
+                        total = process_list<1, false>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key);
+                    } else {
+                        total = process_list<0, false>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key);
+                    }
+                }
             }
+
+            if (oc < p.OC) {
+                if (n_chunks == 1) {
+                    if (p.budget_from) total += p.acc[o];
+                    p.acc[o] = total;
+                    if (p.y) p.y[o] = rescale(total, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+                } else if (total != 0) {
+                    atomicAdd(&p.acc[o], total);
+                }
+            }
+        }
+        // all waves are done with the tile, the lists and s_ticket before the next ticket is drawn
+        __syncthreads();
+    }
+
+    if (threadIdx.x == 0) {
+        __threadfence();
+        if (atomicAdd(&sched[1], 1u) == gridDim.x - 1) {   // every workgroup has drawn its last ticket
+            sched[0] = 0;
+            sched[1] = 0;
+            __threadfence();
         }
     }
 }
@@ -327,21 +418,37 @@ inline bool oc_lane_preferred(const LayerParams& p)
 typedef bool (*ProfileBegin)(hipStream_t, int*);
 typedef void (*ProfileEnd)(hipStream_t, int);
 
-inline int launch_oc_lane(const LayerParams& p, hipStream_t stream, ProfileBegin prof_begin, ProfileEnd prof_end)
+inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t stream, ProfileBegin prof_begin,
+                          ProfileEnd prof_end)
 {
     if (!oc_lane_supported(p)) return (int)hipErrorInvalidValue;
-    const int n_chunks = (p.K + kOcMaxTaps - 1) / kOcMaxTaps;
+    int max_taps = kOcMaxTaps;
+    int waves = kOcWaves;
+    // benchmark overrides (results do not depend on either)
+    if (const char* v = std::getenv("PSB_OC_TAPS")) { const int t = std::atoi(v); if (t >= 1 && t <= kOcMaxTaps) max_taps = t; }
+    if (const char* v = std::getenv("PSB_OC_WAVES")) { const int t = std::atoi(v); if (t == 4 || t == 8) waves = t; }
+    // chunks of at most max_taps taps, as equal as possible, none empty
+    int n_chunks = (p.K + max_taps - 1) / max_taps;
     const int kc = (p.K + n_chunks - 1) / n_chunks;
+    n_chunks = (p.K + kc - 1) / kc;
     const int n_ocb = p.oc_pad / 64;
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
-    // pixels per wave: enough wave-level work items to balance 1024 SIMDs, few enough
-    // weight-tile loads
-    const int64_t items = npix * n_chunks * n_ocb;
-    int ppw = (int)std::min<int64_t>(8, std::max<int64_t>(1, items / 65536));
-    const int64_t groups = (npix + (int64_t)kOcWaves * ppw - 1) / ((int64_t)kOcWaves * ppw);
-    const int64_t gy = (int64_t)n_chunks * n_ocb;
-    if (groups > 2147483647ll || gy > 65535) return (int)hipErrorInvalidValue;
+    const int64_t pixel_groups = (npix + waves - 1) / waves;
+    const int64_t n_tickets = pixel_groups * n_chunks * n_ocb;
+    if (n_tickets >= (1ll << 32) - 65536) return (int)hipErrorInvalidValue;
     const int64_t total = npix * p.OC;
+
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    // resident workgroups: 160 KB of LDS hold four tiles; 512 VGPRs per lane hold four (8: three) waves per SIMD
+    const int wg_per_cu = (waves == 8) ? 2 : 4;
+    const int64_t grid = std::min<int64_t>(n_tickets, (int64_t)cus * wg_per_cu);
 
     if (n_chunks > 1 && !p.budget_from) {
         const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
@@ -351,8 +458,12 @@ inline int launch_oc_lane(const LayerParams& p, hipStream_t stream, ProfileBegin
     }
     int slot = 0;
     const bool timed = prof_begin(stream, &slot);
-    hipLaunchKernelGGL(k_layer_oc_lane, dim3((unsigned)groups, (unsigned)gy), dim3(kOcWaves * 64), 0, stream, p,
-                       n_chunks, kc, ppw);
+    if (waves == 8)
+        hipLaunchKernelGGL(k_layer_oc_lane<8>, dim3((unsigned)grid), dim3(512), 0, stream, p, n_chunks, kc,
+                           (uint32_t)pixel_groups, (uint32_t)n_tickets, sched);
+    else
+        hipLaunchKernelGGL(k_layer_oc_lane<4>, dim3((unsigned)grid), dim3(256), 0, stream, p, n_chunks, kc,
+                           (uint32_t)pixel_groups, (uint32_t)n_tickets, sched);
     if (timed) prof_end(stream, slot);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;

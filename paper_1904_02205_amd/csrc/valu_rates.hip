@@ -15,6 +15,8 @@
 #include <string>
 #include <vector>
 
+#include "psb_philox.hip.h"
+
 #define CHECK(x)                                                                      \
     do {                                                                              \
         hipError_t e_ = (x);                                                          \
@@ -32,7 +34,7 @@ enum Op {
     OP_XOR_E32, OP_XOR_E64, OP_ADD, OP_ADD3, OP_LSHL_ADD, OP_AND_OR, OP_XAD, OP_BFI, OP_ALIGNBIT, OP_LSHR,
     OP_MAD64, OP_MULHI, OP_MULLO, OP_MAD24, OP_MUL24, OP_MULHI24,
     OP_CMP_VCC, OP_CMP_SGPR, OP_ADDC, OP_CMP_ADDC, OP_SUB_LSHR_ADD, OP_CNDMASK,
-    OP_PHILOX_ROUND, OP_COUNT
+    OP_PHILOX_ROUND, OP_MAD64_SGPR, OP_XOR_SGPR, OP_PHILOX7_COUNT, OP_PHILOX10, OP_COUNT
 };
 static const char* kNames[OP_COUNT] = {
     "v_xor_b32 (VOP2)", "v_xor_b32_e64 (VOP3)", "v_add_u32", "v_add3_u32", "v_lshl_add_u32", "v_and_or_b32",
@@ -40,7 +42,8 @@ static const char* kNames[OP_COUNT] = {
     "v_mad_u64_u32", "v_mul_hi_u32", "v_mul_lo_u32", "v_mad_i32_i24", "v_mul_i32_i24", "v_mul_hi_u32_u24",
     "v_cmp_lt_u32 -> vcc", "v_cmp_lt_u32_e64 -> sgpr", "v_addc_co_u32", "v_cmp_lt_u32 + v_addc_co_u32",
     "v_sub_u32 + v_lshrrev_b32 + v_add_u32", "v_cndmask_b32",
-    "philox round: 2 mad_u64_u32 + 4 xor"};
+    "philox round: 2 mad_u64_u32 + 4 xor", "v_mad_u64_u32 v, s[..], v, sgpr, 0", "v_xor_b32 v, sgpr, v",
+    "compiled: 7 philox rounds + 4 compare/count (= 1/8 op)", "compiled: philox4x32-10 (= 1/8 op)"};
 
 template <int OP>
 __device__ __forceinline__ void step(uint32_t& a, uint32_t& b, uint32_t m)
@@ -107,6 +110,59 @@ __device__ __forceinline__ void step(uint32_t& a, uint32_t& b, uint32_t m)
         asm volatile("v_xor_b32_e32 %0, %1, %0" : "+v"(y) : "v"(m));
         a = x;
         b = y;
+    } else if constexpr (OP == OP_MAD64_SGPR) {
+        uint64_t d;
+        uint64_t carry;
+        asm volatile("v_mad_u64_u32 %0, %1, %2, %3, 0" : "=v"(d), "=s"(carry) : "v"(a), "s"(m));
+        a = (uint32_t)d ^ (uint32_t)(d >> 32);   // one extra xor, subtracted in the table below is not attempted
+    } else if constexpr (OP == OP_XOR_SGPR) {
+        asm volatile("v_xor_b32_e32 %0, %1, %0" : "+v"(a) : "s"(m));
+    }
+}
+
+// One "operation" = what the layer kernel does per generator call after its hoisting:
+// seven full rounds and four compare/count steps, on four independent states per lane.
+template <int OP>
+__device__ __forceinline__ void step4(psb::u32x4 (&c)[4], uint32_t (&n)[4], uint32_t thr, uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if constexpr (OP == OP_PHILOX7_COUNT) {
+            c[i] = psb::philox_rounds_from<3>(c[i], k0, k1);
+            n[i] += (c[i].x < thr) ? 1u : 0u;
+            n[i] += (c[i].y < thr) ? 1u : 0u;
+            n[i] += (c[i].z < thr) ? 1u : 0u;
+            n[i] += (c[i].w < thr) ? 1u : 0u;
+        } else {
+            c[i] = psb::philox4x32_10(c[i], k0, k1);
+        }
+    }
+}
+
+template <int OP>
+__global__ void __launch_bounds__(256) k_rate_compiled(uint32_t* out, uint32_t m, int iters, unsigned long long* ticks)
+{
+    psb::u32x4 c[4];
+    uint32_t n[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        c[i] = psb::u32x4{threadIdx.x * 2654435761u + i, blockIdx.x * 40503u + i, m + i, m ^ (uint32_t)i};
+        n[i] = 0;
+    }
+    const uint32_t thr = threadIdx.x * 0x01010101u + m;
+    const unsigned long long c0 = __builtin_readcyclecounter();
+    const unsigned long long w0 = wall_clock64();
+    // same operation count as k_rate: kUnroll * kChains "operations" per iteration, here 1/8 call each
+    for (int it = 0; it < iters * 2; ++it) step4<OP>(c, n, thr, m, m * 3u);
+    const unsigned long long c1 = __builtin_readcyclecounter();
+    const unsigned long long w1 = wall_clock64();
+    uint32_t r = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r ^= c[i].x ^ c[i].y ^ c[i].z ^ c[i].w ^ n[i];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = r;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ticks[0] = c1 - c0;
+        ticks[1] = w1 - w0;
     }
 }
 
@@ -148,12 +204,13 @@ static int run(uint32_t* out, unsigned long long* ticks_dev, int blocks, int wav
     hipEvent_t e0, e1;
     CHECK(hipEventCreate(&e0));
     CHECK(hipEventCreate(&e1));
-    hipLaunchKernelGGL(k_rate<OP>, dim3(blocks), dim3(256), 0, 0, out, 0x9E3779B9u, 16, ticks_dev);   // warm-up
+    auto kernel = (OP == OP_PHILOX7_COUNT || OP == OP_PHILOX10) ? k_rate_compiled<OP> : k_rate<OP>;
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, 0, out, 0x9E3779B9u, 16, ticks_dev);   // warm-up
     CHECK(hipDeviceSynchronize());
     float best = 1e30f;
     for (int rep = 0; rep < 5; ++rep) {
         CHECK(hipEventRecord(e0, 0));
-        hipLaunchKernelGGL(k_rate<OP>, dim3(blocks), dim3(256), 0, 0, out, 0x9E3779B9u, kIters, ticks_dev);
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, 0, out, 0x9E3779B9u, kIters, ticks_dev);
         CHECK(hipEventRecord(e1, 0));
         CHECK(hipEventSynchronize(e1));
         float ms = 0;
