@@ -11,12 +11,15 @@ metric is quoted on.  Prints ONE JSON line.
 metric  sampled MACs/s: one sampled MAC = one (output element, live tap inside the image, sample)
         shift-add; taps whose activation is 0 are counted (the method as stated samples them), so `value` is
         comparable between implementations whether or not they skip such taps.
-roofline  bound "alu": the sampling kernel is limited by integer VALU issue.  `achieved` is the
-        algorithmic instruction work of the products that need sampling (live weight, tap inside the image,
-        activation != 0) in full-rate int32 lane-operations per second; `peak` = 256 CUs x 64 lanes x 2.4 GHz.
-        Per generator call (4 samples) that cannot be hoisted or done on the scalar unit: 15 32x32->64
-        multiplies (v_mad_u64_u32, 4 issue slots of a full-rate instruction each, measured), 31 two-input
-        xors (gfx950 has no three-input xor), 4 compares and 4 carry-adds; per product 2 more.
+roofline  bound "alu": the sampling kernel is limited by integer VALU issue.  Unit: simple int32 lane-operations
+        (a two-operand VALU instruction on vector registers, e.g. v_xor_b32, v_add_u32).  peak = 256 CUs x 4 SIMDs
+        x 32 lanes/clock x 2.4 GHz = 78.6 T lane-ops/s (the integer twin of the 157.3 TFLOP/s fp32 vector figure;
+        measured: 2.4 cycles per wave64).  Instructions that multiply, take three operands or produce/consume a lane
+        mask (v_mad_u64_u32, v_mul_*, v_cmp, v_addc_co) issue at half that rate (measured 4.2-4.5 cycles) and
+        count as 2 units.  `achieved` prices only what the method cannot avoid under this keying: per generator
+        call (4 samples) 15 wide multiplies, 31 two-input xors (gfx950 has no three-input xor), 4 compares and
+        4 carry-adds = 77 units; per product a 24-bit multiply and multiply-add = 4 units; and only for products
+        that need sampling (live weight, tap inside the image, activation != 0).
 """
 import argparse
 import json
@@ -29,17 +32,21 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the sampling kernel (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc, scaled by a 64 MiB copy;
+# profiles/k_layer_oc_lane_config2.md).  Measured for the default workload and mapping only.
+MEASURED_TRAFFIC_BYTES = {("c2", 0): int((3.9 + 55.4) * (1 << 20))}
+
 # ---- ALU roofline constants (derivation in the design doc, measured by csrc/valu_rates.hip) -----------------
-CUS, LANES_PER_CU_CLK, CLOCK_HZ = 256, 64, 2.4e9
-PEAK_TIOPS = CUS * LANES_PER_CU_CLK * CLOCK_HZ / 1e12          # 39.32 T full-rate int32 lane-ops/s
-MAD64_SLOTS = 4.0          # v_mad_u64_u32 occupies the issue slots of 4 full-rate instructions
-CALL_MAD64, CALL_XOR, CALL_CMP_ADD = 15, 31, 8                  # per generator call (4 samples)
-PRODUCT_OPS = 2                                                 # v_mul_i32_i24 + v_mad_i32_i24 per product
+CUS, SIMDS_PER_CU, LANES_PER_SIMD_CLK, CLOCK_HZ = 256, 4, 32, 2.4e9
+PEAK_TIOPS = CUS * SIMDS_PER_CU * LANES_PER_SIMD_CLK * CLOCK_HZ / 1e12     # 78.64 T simple int32 lane-ops/s
+WIDE = 2                   # units of a half-rate instruction (multiply, three operands, lane-mask producer/consumer)
+CALL_UNITS = 15 * WIDE + 31 + 4 * WIDE + 4 * WIDE                          # 77 per generator call (4 samples)
+PRODUCT_UNITS = 2 * WIDE                                                   # v_mul_i32_i24 + v_mad_i32_i24
 
 
 def lane_ops(n_calls, n_products):
-    """Full-rate-equivalent int32 lane-operations of n_calls generator calls and n_products products."""
-    return n_calls * (CALL_MAD64 * MAD64_SLOTS + CALL_XOR + CALL_CMP_ADD) + n_products * PRODUCT_OPS
+    """Simple-int32-lane-operation units of n_calls generator calls and n_products products (per lane)."""
+    return n_calls * CALL_UNITS + n_products * PRODUCT_UNITS
 
 
 def workload_layers(name):
@@ -93,6 +100,8 @@ def main():
     ap.add_argument("--mapping", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-y", action="store_true", help="skip the fp32 rescale output")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 64 MiB device-to-device copy (reference dispatch for FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one); use --gpus 1", file=sys.stderr)
@@ -138,6 +147,11 @@ def main():
             else:
                 psb.conv2d(q, x, L.S, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id, acc=acc, y=y)
 
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -167,7 +181,8 @@ def main():
                    "kernel_launches_per_step": launches_per_step, "mapping": args.mapping,
                    "rescale_output": not args.no_y},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_TIOPS,
-                     "unit": "TIOP/s (full-rate int32 lane-ops)", "frac": achieved / PEAK_TIOPS, "traffic": None,
+                     "unit": "TIOP/s (simple int32 lane-ops)", "frac": achieved / PEAK_TIOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mapping)),
                      "kernel": "k_layer_oc_lane" if args.mapping != 1 else "k_layer_pixel_lane",
                      "kernel_ms_avg": kern_s * 1e3, "lane_ops_per_launch": ops_per_launch},
     }

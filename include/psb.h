@@ -111,7 +111,11 @@ int psb_weights_info(const psb_weights_t* q, psb_winfo* info);
 int psb_weights_export(const psb_weights_t* q, uint32_t* packed_host);
 
 /* Release a handle (NULL is allowed).  The caller must make sure no layer call
- * using it is still running. */
+ * using it is still running.
+ * A handle also owns two device words with which the layer kernel hands out work to its
+ * workgroups; they are zero between calls.  Layer calls that use the SAME handle must
+ * therefore not overlap in time (same stream, or ordered by events); calls on different
+ * handles may run concurrently. */
 void psb_weights_destroy(psb_weights_t* q);
 
 /* Output height/width of a convolution, on the host, with the validation every
