@@ -256,10 +256,19 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
     uint32_t* list = lists[wave];
     uint32_t staged = 0xFFFFFFFFu;   // (channel block, chunk) whose weights are in w_tile
 
+    // The first ticket of a workgroup is its index (the grid never exceeds the number of tickets); only
+    // later ones come from the counter, so the launch does not start with every workgroup hitting one address.
+    bool first = true;
     for (;;) {
-        if (threadIdx.x == 0) s_ticket = atomicAdd(&sched[0], 1u);
-        __syncthreads();
-        const uint32_t ticket = s_ticket;
+        uint32_t ticket;
+        if (first) {
+            ticket = blockIdx.x;
+            first = false;
+        } else {
+            if (threadIdx.x == 0) s_ticket = gridDim.x + atomicAdd(&sched[0], 1u);
+            __syncthreads();
+            ticket = s_ticket;
+        }
         if (ticket >= n_tickets) break;   // uniform over the workgroup
         const uint32_t combo = ticket / pixel_groups;
         const uint32_t pgroup = ticket - combo * pixel_groups;
