@@ -44,22 +44,29 @@ struct PixelHoist {
     uint32_t y2k;     // low half of the same product, xor round-2 key 0
 };
 
-// Round keys as the scalar unit sees them, plus copies of the keys of rounds 3..9 and of the
-// two multipliers that are pinned to vector registers: on gfx950 a two-operand VALU
-// instruction with a scalar-register source issues at half the rate of one whose sources
-// are both vector registers (4.2 vs 2.4 cycles per wave64, measured), and fourteen of the
-// xors of a call have a round key as operand.
+// Round keys and multipliers.  vk0/vk1/vmul_* are the operands of rounds 3..9; with PSB_PIN_KEYS=1 they are
+// pinned to vector registers.  (An instruction stream in which EVERY two-operand VALU instruction has a
+// scalar-register source issues at half rate on gfx950 - 4.2 vs 2.4 cycles per wave64 - but in this loop
+// only 14 of 58 instructions per call do, and pinning them measured no gain while costing 16 VGPRs, so
+// the default leaves them in scalar registers.)
 struct Keys {
     uint32_t k0[10], k1[10];
     uint32_t vk0[7], vk1[7];   // rounds 3..9, in VGPRs
     uint32_t vmul_a, vmul_b;   // kMulA, kMulB in VGPRs
 };
 
+#ifndef PSB_PIN_KEYS
+#define PSB_PIN_KEYS 0
+#endif
 __device__ __forceinline__ uint32_t pin_to_vgpr(uint32_t s)
 {
+#if PSB_PIN_KEYS
     uint32_t v;
     asm volatile("v_mov_b32 %0, %1" : "=v"(v) : "s"(s));
     return v;
+#else
+    return s;
+#endif
 }
 
 // Rounds 3..9 with every operand in a vector register.
@@ -80,27 +87,33 @@ __device__ __forceinline__ u32x4 philox_rounds_3_to_9(u32x4 c, const Keys& key)
     return c;
 }
 
-// Count, for one product, how many of the samples of block j are below thr, and add to n.
-// s_* arguments are wave-uniform.
-template <bool FULL>
-__device__ __forceinline__ uint32_t sample_block(uint32_t n, uint32_t thr, uint32_t s_x1 /* state word 0 after round 0 */,
-                                                 const PixelHoist& h, uint32_t hz, uint32_t lo2, const Keys& key,
-                                                 int j, int from, int to)
+// Scalar half of round 1 for one (tap, block): word 0 of the state after round 0 is s_x1 = s_hib ^ k.
+// Returns the two scalars the vector part needs.
+struct TapScalars { uint32_t sz, s_lo; };
+__device__ __forceinline__ TapScalars tap_scalars(uint32_t s_x1, const Keys& key)
 {
-    // round 1, scalar half: MulA * (word 0)
     uint32_t s_hi, s_lo;
     mulhilo(kMulA, s_x1, s_hi, s_lo);
-    // state after round 1: (.., .., s_hi ^ lo_a ^ k1[1], s_lo); words 0 and 1 were used in the set-up
-    const uint32_t z2 = (s_hi ^ key.k1[1]) ^ h.lo_a;
+    return TapScalars{s_hi ^ key.k1[1], s_lo};
+}
+
+// Number of samples of block j of one product that are below thr.
+// state after round 1: (.., .., ts.sz ^ lo_a, ts.s_lo); words 0 and 1 were used in the per-pixel set-up.
+template <bool FULL>
+__device__ __forceinline__ uint32_t sample_block(uint32_t thr, TapScalars ts, const PixelHoist& h, uint32_t hz,
+                                                 uint32_t lo2, const Keys& key, int j, int from, int to)
+{
+    const uint32_t z2 = ts.sz ^ h.lo_a;
     // round 2: only MulB * z2 is new
     uint32_t hi_b2, lo_b2;
     mulhilo(key.vmul_b, z2, hi_b2, lo_b2);
     u32x4 c;
     c.x = hi_b2 ^ h.y2k;
     c.y = lo_b2;
-    c.z = hz ^ s_lo;
+    c.z = hz ^ ts.s_lo;
     c.w = lo2;
     c = philox_rounds_3_to_9(c, key);
+    uint32_t n = 0;
     if (FULL) {
         n += (c.x < thr) ? 1u : 0u;
         n += (c.y < thr) ? 1u : 0u;
@@ -157,7 +170,7 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
             for (int jj = 0; jj < nb_rt; ++jj) {
                 uint32_t s_hib, hz, lo2;
                 block_setup(h, key, j0 + jj, s_hib, hz, lo2);
-                n = sample_block<false>(n, wt.x, s_hib ^ (k0 + kl), h, hz, lo2, key, j0 + jj, from, to);
+                n += sample_block<false>(wt.x, tap_scalars(s_hib ^ (k0 + kl), key), h, hz, lo2, key, j0 + jj, from, to);
             }
             acc = mad24(__mul24(xs, (int32_t)n), (int32_t)wt.y, acc);
         }
@@ -168,39 +181,52 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
 #pragma unroll
         for (int jj = 0; jj < NB; ++jj) block_setup(h, key, j0 + jj, s_hib[jj], hz[jj], lo2[jj]);
 
-        // software pipeline: the weights of group g+1 are read from LDS while group g is sampled
+        // Software pipeline: while group g is sampled, the list entries of group g+1 are read, their
+        // weights fetched from LDS and the scalar half of their generator calls computed.
         uint32_t ent_next[E];
         uint2 wt_next[E];
+        TapScalars ts_next[E][NB];
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             ent_next[e] = list_entry(mylist, e);
             wt_next[e] = w_tile[(ent_next[e] >> 8) * 64 + lane];
+#pragma unroll
+            for (int jj = 0; jj < NB; ++jj) ts_next[e][jj] = tap_scalars(s_hib[jj] ^ (k0 + (ent_next[e] >> 8)), key);
         }
         int i = 0;
         for (; i + E <= cnt; i += E) {
-            uint32_t n[E], kk[E];
             uint2 wt[E];
             int32_t xs[E];
+            TapScalars ts[E][NB];
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 xs[e] = (int32_t)(int8_t)(ent_next[e] & 0xFFu);
-                kk[e] = k0 + (ent_next[e] >> 8);
                 wt[e] = wt_next[e];
-                n[e] = nsamp;
+#pragma unroll
+                for (int jj = 0; jj < NB; ++jj) ts[e][jj] = ts_next[e][jj];
             }
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 ent_next[e] = list_entry(mylist, (i + E + e) & 63);
                 wt_next[e] = w_tile[(ent_next[e] >> 8) * 64 + lane];
+#pragma unroll
+                for (int jj = 0; jj < NB; ++jj)
+                    ts_next[e][jj] = tap_scalars(s_hib[jj] ^ (k0 + (ent_next[e] >> 8)), key);
             }
+            // the counts of the blocks are independent of each other: no serial chain over the samples
+            uint32_t cnt_b[E][NB];
 #pragma unroll
             for (int e = 0; e < E; ++e)
 #pragma unroll
                 for (int jj = 0; jj < NB; ++jj)
-                    n[e] = sample_block<FULL>(n[e], wt[e].x, s_hib[jj] ^ kk[e], h, hz[jj], lo2[jj], key, j0 + jj,
-                                              from, to);
+                    cnt_b[e][jj] = sample_block<FULL>(wt[e].x, ts[e][jj], h, hz[jj], lo2[jj], key, j0 + jj, from, to);
 #pragma unroll
-            for (int e = 0; e < E; ++e) acc = mad24(__mul24(xs[e], (int32_t)n[e]), (int32_t)wt[e].y, acc);
+            for (int e = 0; e < E; ++e) {
+                uint32_t n = nsamp;
+#pragma unroll
+                for (int jj = 0; jj < NB; ++jj) n += cnt_b[e][jj];
+                acc = mad24(__mul24(xs[e], (int32_t)n), (int32_t)wt[e].y, acc);
+            }
         }
         if constexpr (E > 1) {
             for (; i < cnt; ++i) {      // fewer than E products left
@@ -209,8 +235,8 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
                 uint32_t n = nsamp;
 #pragma unroll
                 for (int jj = 0; jj < NB; ++jj)
-                    n = sample_block<FULL>(n, wt.x, s_hib[jj] ^ (k0 + (entry >> 8)), h, hz[jj], lo2[jj], key, j0 + jj,
-                                           from, to);
+                    n += sample_block<FULL>(wt.x, tap_scalars(s_hib[jj] ^ (k0 + (entry >> 8)), key), h, hz[jj], lo2[jj],
+                                            key, j0 + jj, from, to);
                 acc = mad24(__mul24((int32_t)(int8_t)(entry & 0xFFu), (int32_t)n), (int32_t)wt.y, acc);
             }
         }
