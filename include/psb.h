@@ -173,9 +173,11 @@ int psb_conv2d_progressive(const psb_weights_t* q, const int8_t* x_dev, const ps
 int psb_last_device_error(void);
 
 /* Select the kernel mapping for subsequent layer calls of this process:
- * 0 = automatic, 1 = one output pixel per lane (any layer), 2 = one output channel
- * per lane (groups = 1 only).  Results are bit-identical for every mapping; the
- * switch exists for tests and benchmarks.  Returns the previous value. */
+ * 0 = automatic, 1 = one output pixel per lane (any layer; the simplest kernel), 2 = one output
+ * channel per lane (groups = 1 only; made for dense layers), 3 = compacted product list per
+ * (channel, 256 pixels) (any layer; made for grouped, depthwise and pruned layers).
+ * Results are bit-identical for every mapping; the switch exists for tests and benchmarks.
+ * Returns the previous value. */
 int psb_set_mapping(int mapping);
 
 /* Timing of the sampling kernels, for benchmarks.  While enabled, every layer call

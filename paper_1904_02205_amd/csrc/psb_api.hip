@@ -12,6 +12,7 @@
 
 #include "psb_kernels.hip.h"
 #include "psb_kernels_oc.hip.h"
+#include "psb_kernels_list.hip.h"
 
 struct psb_weights {
     psb_wshape shape;
@@ -22,6 +23,8 @@ struct psb_weights {
     int device;
     uint32_t* packed_dev;    // [OC][K]
     uint2* tile_dev;         // [K][oc_pad] {threshold, unit}
+    uint32_t* live_idx_dev;  // [OC][K]: live taps of each channel first, any order
+    uint32_t* live_cnt_dev;  // [OC]
     uint32_t* sched_dev;     // ticket counter and finish counter of the persistent kernel (both 0 between calls)
 };
 
@@ -141,10 +144,18 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
 
     int mapping = g_mapping;
     if (mapping == 2 && q->shape.groups != 1) return PSB_ERR_SHAPE;
-    if (mapping == 0) mapping = psb::oc_lane_preferred(p) ? 2 : 1;
+    if (mapping == 0) {
+        // channel lanes pay for every (tap, channel) pair of a tile, live or not: only for mostly dense layers
+        const int64_t n_weights = (int64_t)q->shape.oc * q->K;
+        const bool dense = 2 * q->info.n_live >= n_weights;
+        mapping = (dense && psb::oc_lane_preferred(p)) ? 2 : 3;
+    }
 
     if (mapping == 2) {
         rc = psb::launch_oc_lane(p, q->sched_dev, stream, profile_begin, profile_end);
+        if (rc != 0) { tl_last_device_error = rc; return PSB_ERR_DEVICE; }
+    } else if (mapping == 3) {
+        rc = psb::launch_product_list(p, q->live_idx_dev, q->live_cnt_dev, stream, profile_begin, profile_end);
         if (rc != 0) { tl_last_device_error = rc; return PSB_ERR_DEVICE; }
     } else {
         const int64_t npix = (int64_t)p.N * OH * OW;
@@ -168,7 +179,7 @@ int psb_last_device_error(void) { return tl_last_device_error; }
 int psb_set_mapping(int mapping)
 {
     const int prev = g_mapping;
-    if (mapping >= 0 && mapping <= 2) g_mapping = mapping;
+    if (mapping >= 0 && mapping <= 3) g_mapping = mapping;
     return prev;
 }
 
@@ -246,6 +257,8 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     if (hipMalloc(&q->tile_dev, (size_t)oc_pad * K * sizeof(uint2)) != hipSuccess)
         return fail(PSB_ERR_ALLOC, hipSuccess);
     if (hipMalloc(&q->sched_dev, 2 * sizeof(uint32_t)) != hipSuccess) return fail(PSB_ERR_ALLOC, hipSuccess);
+    if (hipMalloc(&q->live_idx_dev, (size_t)nw * sizeof(uint32_t)) != hipSuccess) return fail(PSB_ERR_ALLOC, hipSuccess);
+    if (hipMalloc(&q->live_cnt_dev, (size_t)OC * sizeof(uint32_t)) != hipSuccess) return fail(PSB_ERR_ALLOC, hipSuccess);
     QTRY(hipMemsetAsync(scratch, 0, scratch_words * sizeof(uint32_t), stream));
     QTRY(hipMemsetAsync(q->sched_dev, 0, 2 * sizeof(uint32_t), stream));
 
@@ -288,6 +301,9 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
         hipLaunchKernelGGL(psb::k_pack, dim3(blocks), dim3(256), 0, stream, w_bits, OC, (int)K, oc_pad, field_min,
                            q->packed_dev, q->tile_dev, reinterpret_cast<unsigned long long*>(scratch + 2));
         QTRY(hipGetLastError());
+        hipLaunchKernelGGL(psb::k_live_index, dim3(OC), dim3(256), 0, stream, q->packed_dev, (int)K, q->live_idx_dev,
+                           q->live_cnt_dev);
+        QTRY(hipGetLastError());
     }
     unsigned long long counts[3] = {0, 0, 0};
     QTRY(hipMemcpyAsync(counts, scratch + 2, sizeof(counts), hipMemcpyDeviceToHost, stream));
@@ -322,6 +338,8 @@ void psb_weights_destroy(psb_weights_t* q)
     if (q->packed_dev) (void)hipFree(q->packed_dev);
     if (q->tile_dev) (void)hipFree(q->tile_dev);
     if (q->sched_dev) (void)hipFree(q->sched_dev);
+    if (q->live_idx_dev) (void)hipFree(q->live_idx_dev);
+    if (q->live_cnt_dev) (void)hipFree(q->live_cnt_dev);
     delete q;
 }
 

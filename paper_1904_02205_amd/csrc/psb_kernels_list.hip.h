@@ -1,0 +1,222 @@
+// "Product-list" layer kernel: any layer shape, made for the ones the channel-lane kernel cannot
+// serve well - grouped and depthwise convolutions, and layers whose weights are mostly pruned.
+//
+// A workgroup owns one output channel and 256 consecutive output pixels.  For a chunk of up to 32 LIVE
+// taps of that channel (a per-channel index of live taps is built when the weights are encoded, so dead
+// weights cost nothing) it first builds, in LDS, the list of all products that need sampling - live
+// weight, tap inside the image, activation != 0 - by ballot/prefix compaction over the pixels, then the
+// 256 lanes take list entries round-robin, sample them, and add the result to the pixel's accumulator in
+// LDS (ds_add, exact in any order).  Every lane therefore always has a product to work on, whatever the
+// sparsity pattern; the price is that output index and tap differ per lane, so nothing of the Philox
+// counter can be hoisted (20 wide multiplies per call instead of 15).  No global atomics, no zero-fill:
+// the accumulators leave LDS once, with the fp32 epilogue fused.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "psb_kernels.hip.h"
+
+namespace psb {
+
+constexpr int kListPixels = 256;                       // pixels per workgroup = threads per workgroup
+constexpr int kListTaps = 32;                          // live taps per chunk
+constexpr int kListCap = kListPixels * kListTaps;      // list entries (32 KB)
+
+// live_idx[oc][0 .. live_cnt[oc]) = taps k of channel oc whose weight is sampled (any order).
+// One workgroup per output channel.
+__global__ void __launch_bounds__(256) k_live_index(const uint32_t* __restrict__ packed, int K,
+                                                    uint32_t* __restrict__ live_idx, uint32_t* __restrict__ live_cnt)
+{
+    __shared__ uint32_t count;
+    if (threadIdx.x == 0) count = 0;
+    __syncthreads();
+    const int oc = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    for (int k0 = 0; k0 < K; k0 += 256) {
+        const int k = k0 + threadIdx.x;
+        const bool live = k < K && (packed[(int64_t)oc * K + k] & 0x7F800000u) != kDeadWord;
+        const unsigned long long mask = __ballot(live);
+        uint32_t base = 0;
+        if (lane == 0 && mask) base = atomicAdd(&count, (uint32_t)__popcll(mask));
+        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+        if (live) {
+            const uint32_t pos = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            live_idx[(int64_t)oc * K + pos] = (uint32_t)k;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) live_cnt[oc] = count;
+}
+
+// Samples of block j of product (o, k) that are below thr; all arguments per lane.
+__device__ __forceinline__ uint32_t count_block_full(uint32_t o, uint32_t k, uint32_t j, uint32_t layer, uint32_t key0,
+                                                     uint32_t key1, uint32_t thr)
+{
+    const u32x4 r = philox4x32_10(u32x4{o, k, j, layer}, key0, key1);
+    return (r.x < thr ? 1u : 0u) + (r.y < thr ? 1u : 0u) + (r.z < thr ? 1u : 0u) + (r.w < thr ? 1u : 0u);
+}
+
+// NB > 0: every pixel draws samples 0 .. 4*NB-1 (a call with the same S everywhere, S = 4*NB).
+// NB = 0: per-pixel ranges [from, to), any values.
+template <int NB>
+__global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerParams p,
+                                                                    const uint32_t* __restrict__ live_idx,
+                                                                    const uint32_t* __restrict__ live_cnt)
+{
+    __shared__ uint32_t list[kListCap];          // pixel | tap slot << 8 | activation byte << 16
+    __shared__ int32_t acc_s[kListPixels];
+    __shared__ uint32_t o_s[kListPixels];        // flat output index of the pixel for this channel
+    __shared__ uint32_t range_s[kListPixels];    // from | to << 8
+    __shared__ uint32_t ktab[kListTaps];         // tap index k
+    __shared__ uint2 wtab[kListTaps];            // {threshold, +-2^shift}
+    __shared__ int2 tapinfo[kListTaps];          // {offset inside the image group, kh | kw << 16}
+    __shared__ uint32_t count;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int oc = blockIdx.y;
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int64_t pix = (int64_t)blockIdx.x * kListPixels + tid;
+    const bool valid = pix < npix;
+    const int64_t pixc = valid ? pix : npix - 1;
+    const int ox = (int)(pixc % p.OW);
+    const int oy = (int)((pixc / p.OW) % p.OH);
+    const int n = (int)(pixc / ((int64_t)p.OW * p.OH));
+    int to = p.budget_to ? (int)p.budget_to[pixc] : p.S;
+    to = min(to, p.s_max);
+    int from = p.budget_from ? (int)p.budget_from[pixc] : 0;
+    from = min(from, to);
+    const uint32_t o = (uint32_t)((((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox);
+    const int grp = oc / p.OCg;
+    const int iy0 = oy * p.stride_h - p.pad_h;
+    const int ix0 = ox * p.stride_w - p.pad_w;
+    // index of x[n][grp*Cg][iy0][ix0]; only dereferenced with an in-bounds tap offset added
+    const int64_t xbase = (((int64_t)n * p.C + (int64_t)grp * p.Cg) * p.H + iy0) * p.W + ix0;
+    const bool wants = valid && to > from;
+
+    acc_s[tid] = 0;
+    o_s[tid] = o;
+    range_s[tid] = (uint32_t)from | ((uint32_t)to << 8);
+
+    const uint32_t nlive = live_cnt[oc];
+    for (uint32_t c0 = 0; c0 < nlive; c0 += kListTaps) {
+        const int nk = (int)min((uint32_t)kListTaps, nlive - c0);
+        if (tid < nk) {
+            const uint32_t k = live_idx[(int64_t)oc * p.K + c0 + tid];
+            const uint32_t word = p.packed[(int64_t)oc * p.K + k];
+            const uint32_t unit = 1u << ((word >> 23) & 0xFFu);
+            ktab[tid] = k;
+            wtab[tid] = make_uint2(word << 9, (word & 0x80000000u) ? (0u - unit) : unit);
+            const int khw = p.KH * p.KW;
+            const int ci = (int)k / khw;
+            const int r = (int)k - ci * khw;
+            const int kh = r / p.KW;
+            const int kw = r - kh * p.KW;
+            tapinfo[tid] = make_int2((ci * p.H + kh) * p.W + kw, kh | (kw << 16));
+        }
+        if (tid == 0) count = 0;
+        __syncthreads();
+
+        // build the list of products that need sampling
+        for (int i = 0; i < nk; ++i) {
+            const int2 info = tapinfo[i];
+            const int iy = iy0 + (info.y & 0xFFFF);
+            const int ix = ix0 + (info.y >> 16);
+            int32_t xv = 0;
+            if (wants && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W) xv = p.x[xbase + info.x];
+            const unsigned long long mask = __ballot(xv != 0);
+            uint32_t base = 0;
+            if (lane == 0 && mask) base = atomicAdd(&count, (uint32_t)__popcll(mask));
+            base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+            if (xv != 0) {
+                const uint32_t pos = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                list[pos] = (uint32_t)tid | ((uint32_t)i << 8) | (((uint32_t)xv & 0xFFu) << 16);
+            }
+        }
+        __syncthreads();
+
+        // sample the products, lanes taking entries round-robin
+        const uint32_t total = count;
+        if constexpr (NB > 0) {
+            constexpr int U = (NB >= 4) ? 1 : 4 / NB;      // entries in flight per lane: four independent calls
+            for (uint32_t e0 = (uint32_t)tid; e0 < total; e0 += (uint32_t)(U * kListPixels)) {
+                uint32_t cnt[U];
+                uint32_t ent[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t e = e0 + (uint32_t)(u * kListPixels);
+                    ent[u] = (e < total) ? list[e] : 0xFFFFFFFFu;
+                    cnt[u] = 0;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (ent[u] == 0xFFFFFFFFu) continue;
+                    const uint32_t slot = (ent[u] >> 8) & 0xFFu;
+                    const uint32_t ou = o_s[ent[u] & 0xFFu];
+                    const uint32_t ku = ktab[slot];
+                    const uint32_t thr = wtab[slot].x;
+#pragma unroll
+                    for (int j = 0; j < NB; ++j)
+                        cnt[u] += count_block_full(ou, ku, (uint32_t)j, p.layer_id, p.key0, p.key1, thr);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (ent[u] == 0xFFFFFFFFu) continue;
+                    const int32_t xs = (int32_t)(int8_t)((ent[u] >> 16) & 0xFFu);
+                    const int32_t unit = (int32_t)wtab[(ent[u] >> 8) & 0xFFu].y;
+                    const int32_t term = (int32_t)((uint32_t)xs * ((uint32_t)(4 * NB) + cnt[u]) * (uint32_t)unit);   // modulo 2^32
+                    atomicAdd(&acc_s[ent[u] & 0xFFu], term);
+                }
+            }
+        } else {
+            for (uint32_t e = (uint32_t)tid; e < total; e += (uint32_t)kListPixels) {
+                const uint32_t entry = list[e];
+                const uint32_t pl = entry & 0xFFu;
+                const uint32_t slot = (entry >> 8) & 0xFFu;
+                const uint32_t rg = range_s[pl];
+                const int f = (int)(rg & 0xFFu), t = (int)(rg >> 8);
+                const uint32_t c = count_below(o_s[pl], ktab[slot], p.layer_id, p.key0, p.key1, wtab[slot].x, f, t);
+                const int32_t xs = (int32_t)(int8_t)((entry >> 16) & 0xFFu);
+                const int32_t term = (int32_t)((uint32_t)xs * ((uint32_t)(t - f) + c) * wtab[slot].y);   // modulo 2^32
+                atomicAdd(&acc_s[pl], term);
+            }
+        }
+        __syncthreads();   // the tables and the list are rewritten by the next chunk
+    }
+    __syncthreads();       // acc_s is complete (also when the channel has no live tap at all)
+
+    if (valid) {
+        int32_t total = acc_s[tid];
+        if (p.budget_from) total += p.acc[o];
+        p.acc[o] = total;
+        if (p.y) p.y[o] = rescale(total, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+    }
+}
+
+// Returns 0 or a hipError_t.
+inline int launch_product_list(const LayerParams& p, const uint32_t* live_idx, const uint32_t* live_cnt,
+                               hipStream_t stream, bool (*prof_begin)(hipStream_t, int*),
+                               void (*prof_end)(hipStream_t, int))
+{
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int64_t gx = (npix + kListPixels - 1) / kListPixels;
+    if (gx > 2147483647ll || p.OC > 65535) return (int)hipErrorInvalidValue;
+    const dim3 grid((unsigned)gx, (unsigned)p.OC), block(kListPixels);
+    int nb = 0;   // compile-time block count only for a uniform S that is a multiple of 4
+    if (!p.budget_to && (p.S & 3) == 0) nb = p.S / 4;
+    int slot = 0;
+    const bool timed = prof_begin(stream, &slot);
+    switch (nb) {
+        case 1: hipLaunchKernelGGL(k_layer_product_list<1>, grid, block, 0, stream, p, live_idx, live_cnt); break;
+        case 2: hipLaunchKernelGGL(k_layer_product_list<2>, grid, block, 0, stream, p, live_idx, live_cnt); break;
+        case 4: hipLaunchKernelGGL(k_layer_product_list<4>, grid, block, 0, stream, p, live_idx, live_cnt); break;
+        case 8: hipLaunchKernelGGL(k_layer_product_list<8>, grid, block, 0, stream, p, live_idx, live_cnt); break;
+        default: hipLaunchKernelGGL(k_layer_product_list<0>, grid, block, 0, stream, p, live_idx, live_cnt); break;
+    }
+    if (timed) prof_end(stream, slot);
+    return (int)hipGetLastError();
+}
+
+}  // namespace psb

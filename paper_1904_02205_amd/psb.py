@@ -16,7 +16,7 @@ ERR_NULL, ERR_SHAPE, ERR_VALUE, ERR_OVERFLOW_UNSAFE, ERR_TOO_LARGE, ERR_DEVICE, 
 _NAMES = {0: "PSB_OK", -1: "PSB_ERR_NULL", -2: "PSB_ERR_SHAPE", -3: "PSB_ERR_VALUE",
           -4: "PSB_ERR_OVERFLOW_UNSAFE", -5: "PSB_ERR_TOO_LARGE", -6: "PSB_ERR_DEVICE", -7: "PSB_ERR_ALLOC"}
 
-MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE = 0, 1, 2
+MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE, MAPPING_PRODUCT_LIST = 0, 1, 2, 3
 
 SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",

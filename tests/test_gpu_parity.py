@@ -109,7 +109,7 @@ def _cases():
     rng = np.random.default_rng(200)
     c = []
     # (id, layer, mappings)
-    both = (1, 2)
+    both = (1, 2, 3)
     c.append(("linear_small", _layer(rng, 5, 37, 9, 1, 1, S=8, xkind="u4", std=0.05), both))
     c.append(("linear_ragged_oc", _layer(rng, 3, 130, 100, 1, 1, S=5, xkind="signed", std=0.05), both))
     c.append(("conv3x3_multi_chunk", _layer(rng, 2, 20, 70, (9, 11), 3, pad=1, S=8), both))
@@ -123,9 +123,9 @@ def _cases():
     c.append(("conv_s12", _layer(rng, 1, 9, 10, 6, 3, pad=1, S=12), both))
     c.append(("conv_pad3_tiny_image", _layer(rng, 1, 4, 8, 2, 3, pad=3, S=4), both))
     c.append(("pruned_pointwise", _layer(rng, 2, 96, 40, 5, 1, S=16, prune=0.9), both))
-    c.append(("grouped", _layer(rng, 2, 8, 12, 7, 3, pad=1, groups=4, S=8), (1,)))
-    c.append(("depthwise", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), (1,)))
-    c.append(("depthwise_s2", _layer(rng, 1, 10, 10, 8, 3, stride=2, pad=1, groups=10, S=4, xkind="signed"), (1,)))
+    c.append(("grouped", _layer(rng, 2, 8, 12, 7, 3, pad=1, groups=4, S=8), (1, 3)))
+    c.append(("depthwise", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), (1, 3)))
+    c.append(("depthwise_s2", _layer(rng, 1, 10, 10, 8, 3, stride=2, pad=1, groups=10, S=4, xkind="signed"), (1, 3)))
     return c
 
 
@@ -162,7 +162,7 @@ def test_seed_and_layer_id_select_the_stream(psb, orc):
     for seed, lid in ((0, 0), (2 ** 63 + 12345, 0), (0, 7), (0xFFFFFFFFFFFFFFFF, 0xFFFFFFFF)):
         L.seed, L.layer_id = seed, lid
         ref, _, _ = helpers.oracle_layer(orc, L)
-        for m in (1, 2):
+        for m in (1, 2, 3):
             psb.set_mapping(m)
             acc, _ = helpers.gpu_layer(psb, L)
             assert np.array_equal(acc, ref)
@@ -173,7 +173,7 @@ def test_seed_and_layer_id_select_the_stream(psb, orc):
 
 # ------------------------------------------------------------------ progressive budgets
 
-@pytest.mark.parametrize("mapping", [1, 2])
+@pytest.mark.parametrize("mapping", [1, 2, 3])
 def test_progressive_bit_exact_and_incremental(psb, orc, mapping):
     rng = np.random.default_rng(300)
     L = _layer(rng, 3, 12, 70, (9, 8), 3, pad=1, S=32, s_max=32)
@@ -212,7 +212,7 @@ def test_progressive_constant_map_equals_plain_call(psb):
 
 # ------------------------------------------------------------------ fp32 rescale
 
-@pytest.mark.parametrize("mapping", [1, 2])
+@pytest.mark.parametrize("mapping", [1, 2, 3])
 def test_rescale_matches_oracle(psb, orc, mapping):
     rng = np.random.default_rng(400)
     psb.set_mapping(mapping)
