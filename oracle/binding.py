@@ -21,7 +21,7 @@ class WInfo(C.Structure):
 class Weights(C.Structure):
     _fields_ = [("oc", C.c_int32), ("K", C.c_int32),
                 ("sign", C.POINTER(C.c_int8)), ("shift", C.POINTER(C.c_int32)),
-                ("p", C.POINTER(C.c_double)), ("info", WInfo)]
+                ("p", C.POINTER(C.c_double)), ("prob_bits", C.c_int32), ("info", WInfo)]
 
 
 class WShape(C.Structure):
@@ -49,8 +49,10 @@ def lib():
         L.psbo_philox4x32_10.restype = None
         L.psbo_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
         L.psbo_uniform.restype = C.c_uint32
-        L.psbo_quantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+        L.psbo_quantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                     C.POINTER(Weights)]
+        L.psbo_uniform7.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
+        L.psbo_uniform7.restype = C.c_uint32
         L.psbo_quantize.restype = C.c_int
         L.psbo_weights_free.argtypes = [C.POINTER(Weights)]
         L.psbo_weights_free.restype = None
@@ -103,15 +105,20 @@ def uniform(seed, layer_id, o, k, s):
     return int(lib().psbo_uniform(int(seed), int(layer_id), int(o), int(k), int(s)))
 
 
+def uniform7(seed, layer_id, o, k, s):
+    return int(lib().psbo_uniform7(int(seed), int(layer_id), int(o), int(k), int(s)))
+
+
 class QWeights:
     """Quantised layer held by the oracle; arrays are numpy views, [oc, K]."""
 
-    def __init__(self, w, exp_bits=0, x_absmax=127, s_max=16):
+    def __init__(self, w, exp_bits=0, x_absmax=127, s_max=16, prob_bits=23):
         w = np.ascontiguousarray(w, dtype=np.float32)
         oc = w.shape[0]
         K = int(np.prod(w.shape[1:]))
         self._q = Weights()
-        rc = lib().psbo_quantize(_ptr(w), oc, K, exp_bits, x_absmax, s_max, C.byref(self._q))
+        rc = lib().psbo_quantize(_ptr(w), oc, K, prob_bits, exp_bits, x_absmax, s_max, C.byref(self._q))
+        self.prob_bits = prob_bits
         if rc != OK:
             self._q = None
             raise OracleError(rc)

@@ -73,6 +73,17 @@ extern "C" uint32_t psbo_uniform(uint64_t seed, uint32_t layer_id, uint32_t o, u
     return block[s % 4u];
 }
 
+extern "C" uint32_t psbo_uniform7(uint64_t seed, uint32_t layer_id, uint32_t o, uint32_t k, uint32_t s)
+{
+    const uint32_t key[2] = { (uint32_t)(seed & 0xFFFFFFFFull), (uint32_t)(seed >> 32) };
+    const uint32_t ctr[4] = { o, k, s / 16u, layer_id };
+    uint32_t block[4];
+    psbo_philox4x32_10(ctr, key, block);
+    const uint32_t byte_index = s % 16u;
+    const uint32_t byte = (block[byte_index / 4u] >> (8u * (byte_index % 4u))) & 0xFFu;
+    return byte & 0x7Fu;
+}
+
 /* ---------------------------------------------------------------------------
  * Encoding of a layer.
  *
@@ -92,17 +103,18 @@ extern "C" uint32_t psbo_uniform(uint64_t seed, uint32_t layer_id, uint32_t o, u
  * Weights with e_k < e_min, and all subnormal weights, are flushed to zero.
  * Zero weights are not live either and are never sampled.
  * ------------------------------------------------------------------------- */
-extern "C" int psbo_quantize(const float* w, int32_t oc, int32_t K, int32_t exp_bits,
+extern "C" int psbo_quantize(const float* w, int32_t oc, int32_t K, int32_t prob_bits, int32_t exp_bits,
                              int32_t x_absmax, int32_t s_max, psbo_weights* out)
 {
     if (!w || !out || oc <= 0 || K <= 0) return PSBO_ERR_ARG;
+    if (prob_bits != 23 && (prob_bits < 1 || prob_bits > 7)) return PSBO_ERR_VALUE;
     if (exp_bits <= 0) exp_bits = 4;
     if (exp_bits > 5 || x_absmax <= 0 || x_absmax > 128 || s_max <= 0 || s_max > 255) return PSBO_ERR_VALUE;
 
     const int64_t nw = (int64_t)oc * K;
     int32_t* e_all = (int32_t*)std::malloc(sizeof(int32_t) * nw);
     int*     cls   = (int*)std::malloc(sizeof(int) * nw);
-    out->oc = oc; out->K = K;
+    out->oc = oc; out->K = K; out->prob_bits = prob_bits;
     out->sign  = (int8_t*)std::calloc(nw, sizeof(int8_t));
     out->shift = (int32_t*)std::calloc(nw, sizeof(int32_t));
     out->p     = (double*)std::calloc(nw, sizeof(double));
@@ -115,6 +127,18 @@ extern "C" int psbo_quantize(const float* w, int32_t oc, int32_t K, int32_t exp_
         if (cls[i] == PSBO_NONFINITE) {
             std::free(e_all); std::free(cls); psbo_weights_free(out);
             return PSBO_ERR_VALUE;
+        }
+        if (prob_bits < 23 && cls[i] == PSBO_NORMAL) {
+            /* Sect. 4.4: regular grid with p = 0, without p = 1 ("the right boundary would result
+             * in a higher exponent"); nearbyint rounds half to even in the default rounding mode */
+            const double scale = std::ldexp(1.0, prob_bits);
+            double P = std::nearbyint(p * scale);
+            if (P >= scale) { P = 0.0; e += 1; }
+            p = P / scale;
+            if (e > 127) {             /* rounded past the largest binary32 exponent */
+                std::free(e_all); std::free(cls); psbo_weights_free(out);
+                return PSBO_ERR_VALUE;
+            }
         }
         e_all[i] = e;
         out->sign[i] = (int8_t)s;      /* provisional; cleared below if not live */
@@ -182,15 +206,21 @@ extern "C" void psbo_weights_free(psbo_weights* q)
  * Returned exactly (int64); negative x is handled as a multiplication by the
  * power of two, which is what a left shift means on a two's complement value.
  * ------------------------------------------------------------------------- */
-static int64_t product_samples(int32_t x, int sigma, int32_t shift, double p,
+static int64_t product_samples(int32_t x, int sigma, int32_t shift, double p, int32_t prob_bits,
                                int32_t from, int32_t to,
                                uint64_t seed, uint32_t layer_id, uint32_t o, uint32_t k,
                                const uint32_t* u_row /* [S] or NULL */)
 {
     int64_t sum = 0;
     for (int32_t s = from; s < to; ++s) {
-        const uint32_t u = u_row ? u_row[s] : psbo_uniform(seed, layer_id, o, k, (uint32_t)s);
-        const double U = (double)u / 4294967296.0;
+        double U;                                   /* uniform on [0,1) */
+        if (prob_bits == 23) {
+            const uint32_t u = u_row ? u_row[s] : psbo_uniform(seed, layer_id, o, k, (uint32_t)s);
+            U = (double)u / 4294967296.0;
+        } else {
+            const uint32_t u7 = u_row ? u_row[s] : psbo_uniform7(seed, layer_id, o, k, (uint32_t)s);
+            U = (double)u7 / 128.0;
+        }
         const int B = (U < p) ? 1 : 0;
         sum += (int64_t)sigma * (int64_t)x * ((int64_t)1 << (shift + B));
     }
@@ -215,7 +245,7 @@ extern "C" int psbo_linear(const psbo_weights* q, const int8_t* x, int32_t B, in
                 if (q->sign[wi] == 0) continue;           /* not live: never sampled */
                 const uint32_t* u_row = u_table ? u_table + ((int64_t)o * K + k) * S : nullptr;
                 const int64_t t = product_samples(x[(int64_t)b * K + k], q->sign[wi], q->shift[wi],
-                                                  q->p[wi], 0, S, seed, layer_id, o, (uint32_t)k, u_row);
+                                                  q->p[wi], q->prob_bits, 0, S, seed, layer_id, o, (uint32_t)k, u_row);
                 exact += t;
                 wrapped += (uint32_t)t;
             }
@@ -284,7 +314,7 @@ extern "C" int psbo_conv2d(const psbo_weights* q, const psbo_wshape* ws, const i
                     if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;   /* padding: x = 0 */
                     const int32_t c = grp * Cg + ci;
                     const int32_t xv = x[(((int64_t)n * C + c) * H + iy) * W + ix];
-                    const int64_t t = product_samples(xv, q->sign[wi], q->shift[wi], q->p[wi],
+                    const int64_t t = product_samples(xv, q->sign[wi], q->shift[wi], q->p[wi], q->prob_bits,
                                                       from, to, seed, layer_id, o, (uint32_t)k, nullptr);
                     exact += t;
                     wrapped += (uint32_t)t;

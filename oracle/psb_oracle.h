@@ -45,6 +45,8 @@ typedef struct {
     int8_t*  sign;          /* -1, +1; 0 = not live (zero or flushed)            */
     int32_t* shift;         /* e - e_min >= 0 for live weights                   */
     double*  p;             /* probability of the larger shift, in [0,1)         */
+    int32_t  prob_bits;     /* 23: p is the full mantissa; 1..7: p is a multiple
+                               of 2^-prob_bits and samples use 7-bit uniforms     */
     psbo_winfo info;
 } psbo_weights;
 
@@ -68,17 +70,28 @@ void psbo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t o
  * (o, k, floor(s/4), layer_id).                                                 */
 uint32_t psbo_uniform(uint64_t seed, uint32_t layer_id, uint32_t o, uint32_t k, uint32_t s);
 
-/* Encode a layer.  exp_bits<=0 selects 4 (Sect. 4.4: 4-bit exponents).  The
+/* The 7-bit uniform used with discretised probabilities (Sect. 4.4; suppl.
+ * "Stochastic multiplier": a k_p-bit probability needs a k_p-bit comparator):
+ * the low 7 bits of byte (s mod 16) of the Philox block with counter
+ * (o, k, floor(s/16), layer_id); byte b of a block is bits 8*(b mod 4) .. +7 of
+ * word floor(b/4).  One block serves 16 samples instead of 4.                     */
+uint32_t psbo_uniform7(uint64_t seed, uint32_t layer_id, uint32_t o, uint32_t k, uint32_t s);
+
+/* Encode a layer.  exp_bits<=0 selects 4 (Sect. 4.4: 4-bit exponents).
+ * prob_bits = 23 keeps p exactly; prob_bits = 1..7 discretises it to a regular
+ * grid that includes 0 and excludes 1 (Sect. 4.4): P = round-half-even(p * 2^prob_bits),
+ * and P = 2^prob_bits moves the weight to the next exponent with p = 0.  The
  * window and the overflow rule are described at the definition.  Allocates the
  * arrays of *out with malloc; release with psbo_weights_free.                   */
-int  psbo_quantize(const float* w, int32_t oc, int32_t K, int32_t exp_bits,
+int  psbo_quantize(const float* w, int32_t oc, int32_t K, int32_t prob_bits, int32_t exp_bits,
                    int32_t x_absmax, int32_t s_max, psbo_weights* out);
 void psbo_weights_free(psbo_weights* q);
 
 /* Sect. 3.1, unnumbered equation after Eq. (numbersystem:simulation):
  * acc[b][oc] = sum_k sum_{s<S} sigma_k * ( x[b][k] << (shift_k + B^(s)) ).
  * u_table: optional replacement of the generator for enumeration tests,
- * u(o,k,s) = u_table[(o*K + k)*S + s]; NULL = Philox.
+ * u(o,k,s) = u_table[(o*K + k)*S + s] (a 32-bit uniform, or a 7-bit one when the
+ * layer was encoded with prob_bits < 23); NULL = Philox.
  * overflow (nullable) receives the number of outputs whose exact (int64) sum
  * does not fit int32.                                                           */
 int psbo_linear(const psbo_weights* q, const int8_t* x, int32_t B, int32_t S,

@@ -468,3 +468,90 @@ def test_rescale_is_four_separately_rounded_operations(orc):
     y2 = orc.rescale(acc, e_min=-12, S=16)
     exact = acc.astype(np.float64) * 2.0 ** -12 / 16
     assert np.allclose(y2, exact, rtol=1e-6, atol=0)
+
+
+# ------------------------------------------------------------------ discretised probabilities (Sect. 4.4)
+
+def test_probability_grid_includes_zero_excludes_one(orc):
+    # p = 0.99 with 2 bits rounds to 4/4: the weight moves to the next exponent with p = 0
+    q = orc.QWeights(np.array([[1.99, 1.0]], np.float32), x_absmax=1, s_max=1, prob_bits=2)
+    assert q.e_top == 1 and list(q.p[0]) == [0.0, 0.0] and list(q.shift[0] + q.e_min) == [1, 0]
+    # ties go to the even grid point: 1.125 -> p = 1/8 -> P = 0.5 -> 0;  1.375 -> P = 1.5 -> 2
+    q = orc.QWeights(np.array([[1.125, 1.375, 1.625, 1.875]], np.float32), x_absmax=1, s_max=1, prob_bits=2)
+    assert list(q.p[0][:3]) == [0.0, 0.5, 0.5] and q.p[0][3] == 0.0 and q.shift[0][3] + q.e_min == 1
+    rng = np.random.default_rng(71)
+    w = (rng.standard_normal((6, 200)) * 0.1).astype(np.float32)
+    for kp in (1, 2, 3, 4, 6, 7):
+        q = orc.QWeights(w, x_absmax=1, s_max=1, prob_bits=kp)
+        live = q.sign != 0
+        grid = q.p[live] * 2 ** kp
+        assert np.all(grid == np.rint(grid)) and grid.min() >= 0 and grid.max() <= 2 ** kp - 1
+        rep = q.represented()
+        e = np.floor(np.log2(np.abs(w.astype(np.float64))))
+        assert np.all(np.abs(rep - w)[live] <= 2.0 ** e[live] * 2.0 ** -(kp + 1) + 1e-18)
+    full = orc.QWeights(w, x_absmax=1, s_max=1, prob_bits=23)
+    assert np.all(full.represented()[full.sign != 0] == w[full.sign != 0])
+    for bad in (0, 8, 16, 22, 24):
+        with pytest.raises(orc.OracleError) as ei:
+            orc.QWeights(w, prob_bits=bad)
+        assert ei.value.code == orc.ERR_VALUE
+
+
+def test_uniform7_keying(orc):
+    # byte b of a block = bits 8*(b mod 4)..+7 of word b div 4; the 7-bit uniform is its low 7 bits
+    ctr, key, out = _kat()[0]                     # all-zero counter and key: block 0 of product (0,0), layer 0
+    for b in range(16):
+        assert orc.uniform7(0, 0, 0, 0, b) == (out[b // 4] >> (8 * (b % 4))) & 0x7F
+    # counter positions, through the generator that the known answers pin
+    seed, layer, o, k = 0xA4093822299F31D0, 0x03707344, 0x243F6A88, 0x85A308D3
+    for j in (0, 1, 5):
+        blk = orc.philox([o, k, j, layer], [seed & 0xFFFFFFFF, seed >> 32])
+        for b in range(16):
+            assert orc.uniform7(seed, layer, o, k, 16 * j + b) == (blk[b // 4] >> (8 * (b % 4))) & 0x7F
+    u = np.array([orc.uniform7(9, 0, o, 1, s) for o in range(300) for s in range(40)])
+    hist = np.bincount(u, minlength=128)
+    assert len(hist) == 128 and stats.chisquare(hist).pvalue > 1e-4
+
+
+def test_discretised_enumeration_gives_exact_expectation(orc):
+    # 2-bit probabilities, all 128 values of the 7-bit uniform for each of K*S = 2 draws
+    w = np.array([[1.25, -0.875]], dtype=np.float32)          # p = 1/4 ; -0.875 = -(1/2)(1 + 3/4): p = 3/4
+    x = np.array([[5, -9]], dtype=np.int8)
+    q = orc.QWeights(w, x_absmax=16, s_max=1, prob_bits=2)
+    total = 0
+    for a in range(128):
+        for b in range(128):
+            acc, over = orc.linear(q, x, 1, u_table=np.array([a, b], dtype=np.uint32))
+            total += int(acc[0, 0])
+    unit = 2.0 ** -q.e_min
+    assert total == 128 * 128 * (5 * 1.25 * unit + (-9) * (-0.875) * unit)
+    # threshold is strict: p = 1/4 means u7 in 0..31
+    one = orc.QWeights(np.array([[1.25]], np.float32), x_absmax=1, s_max=1, prob_bits=2, exp_bits=1)
+    lo, _ = orc.linear(one, np.array([[1]], np.int8), 1, u_table=np.array([31], dtype=np.uint32))
+    hi, _ = orc.linear(one, np.array([[1]], np.int8), 1, u_table=np.array([32], dtype=np.uint32))
+    assert int(lo[0, 0]) == 2 * int(hi[0, 0])
+
+
+def test_discretised_mean_converges_to_quantised_weights(orc):
+    rng = np.random.default_rng(72)
+    K, OC, B, S, T = 64, 5, 3, 16, 300
+    w = (rng.standard_normal((OC, K)) * 0.05).astype(np.float32)
+    x = rng.integers(0, 16, size=(B, K)).astype(np.int8)
+    q = orc.QWeights(w, x_absmax=15, s_max=S, prob_bits=4)
+    what = q.represented()
+    exact = x.astype(np.float64) @ what.T
+    aw = np.abs(what)
+    e = np.floor(np.log2(np.where(aw > 0, aw, 1.0)))
+    var_w = np.where(aw > 0, (2.0 ** (e + 1) - aw) * (aw - 2.0 ** e), 0.0)
+    sigma = np.sqrt((x.astype(np.float64) ** 2) @ var_w.T / S)
+    mean = np.zeros((B, OC))
+    for t in range(T):
+        acc, over = orc.linear(q, x, S, seed=500 + t)
+        assert over == 0
+        mean += acc.astype(np.float64) * 2.0 ** q.e_min / S
+    mean /= T
+    assert np.all(np.abs(mean - exact) < 6 * sigma / np.sqrt(T) + 1e-12)
+    # the convolution path uses the same draws as the linear path
+    a, _ = orc.linear(q, x, S, seed=3, layer_id=2)
+    b, _, _ = orc.conv2d(q, (OC, K, 1, 1, 1), x.reshape(B, K, 1, 1), S=S, seed=3, layer_id=2)
+    assert np.array_equal(a, b.reshape(B, OC))
