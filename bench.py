@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the PSB layer hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5] [--prob-bits 23|1..7]
+                    [--no-cpu-baseline]
 
 A step is one pass of the whole hot path over one batch of synthetic input that is already resident in
 HBM: the layer call(s) of the workload through the C-ABI (zero-fill, sampling kernel, fp32 rescale).  The
@@ -19,7 +20,9 @@ roofline  bound "alu": the sampling kernel is limited by integer VALU issue.  Un
         count as 2 units.  `achieved` prices only what the method cannot avoid under this keying: per generator
         call (4 samples) 15 wide multiplies, 31 two-input xors (gfx950 has no three-input xor), 4 compares and
         4 carry-adds = 77 units; per product a 24-bit multiply and multiply-add = 4 units; and only for products
-        that need sampling (live weight, tap inside the image, activation != 0).
+        that need sampling (live weight, tap inside the image, activation != 0).  With --prob-bits 1..7 a
+        generator call serves 16 samples and its counting is 4 x (or, subtract, and, bit count) + 1 = 17 units
+        instead of 16: 78 units per call.
 """
 import argparse
 import json
@@ -41,12 +44,14 @@ CUS, SIMDS_PER_CU, LANES_PER_SIMD_CLK, CLOCK_HZ = 256, 4, 32, 2.4e9
 PEAK_TIOPS = CUS * SIMDS_PER_CU * LANES_PER_SIMD_CLK * CLOCK_HZ / 1e12     # 78.64 T simple int32 lane-ops/s
 WIDE = 2                   # units of a half-rate instruction (multiply, three operands, lane-mask producer/consumer)
 CALL_UNITS = 15 * WIDE + 31 + 4 * WIDE + 4 * WIDE                          # 77 per generator call (4 samples)
+CALL_UNITS_7BIT = 15 * WIDE + 31 + 4 * 4 + 1                               # 78 per generator call (16 samples)
 PRODUCT_UNITS = 2 * WIDE                                                   # v_mul_i32_i24 + v_mad_i32_i24
+KERNEL_NAMES = {1: "k_layer_pixel_lane", 2: "k_layer_oc_lane", 3: "k_layer_product_list"}
 
 
-def lane_ops(n_calls, n_products):
+def lane_ops(n_calls, n_products, prob_bits=23):
     """Simple-int32-lane-operation units of n_calls generator calls and n_products products (per lane)."""
-    return n_calls * CALL_UNITS + n_products * PRODUCT_UNITS
+    return n_calls * (CALL_UNITS if prob_bits == 23 else CALL_UNITS_7BIT) + n_products * PRODUCT_UNITS
 
 
 def workload_layers(name):
@@ -64,11 +69,11 @@ def workload_layers(name):
     raise SystemExit(f"unknown workload {name}")
 
 
-def count_work(L, packed, torch, device):
+def count_work(L, packed, torch, device, per_call=4):
     """(sampled MACs, generator calls needed, products needed) of one layer call, from the exported weights.
 
     sampled MACs: sum over outputs of budget x #(live taps inside the image).
-    needed: the same restricted to taps whose activation is not 0; calls = ceil(budget/4) per such product.
+    needed: the same restricted to taps whose activation is not 0; calls = ceil(budget/per_call) per such product.
     """
     oc, cin, kh, kw, groups = L.wshape
     cg = cin // groups
@@ -86,7 +91,7 @@ def count_work(L, packed, torch, device):
     else:
         b = torch.full_like(taps_all, float(L.S))
     smac = float((taps_all * b).sum().item())
-    calls = float((taps_nz * torch.ceil(b / 4)).sum().item())
+    calls = float((taps_nz * torch.ceil(b / per_call)).sum().item())
     products = float((taps_nz * (b > 0)).sum().item())
     return smac, calls, products
 
@@ -98,6 +103,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--mapping", type=int, default=0)
+    ap.add_argument("--prob-bits", type=int, default=23,
+                    help="23 = exact probabilities (the headline metric); 1..7 = discretised, 7-bit uniforms")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-y", action="store_true", help="skip the fp32 rescale output")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -118,18 +125,23 @@ def main():
     torch.cuda.set_device(0)
 
     layers, desc = workload_layers(args.workload)
+    per_call = 4 if args.prob_bits == 23 else 16
     calls = []
+    kernels = []
     smac = n_calls = n_prod = 0.0
     for L in layers:
         w = torch.from_numpy(L.w).to(dev)
-        q = psb.Weights(w, groups=L.groups, x_absmax=L.x_absmax, s_max=L.s_max)
+        q = psb.Weights(w, groups=L.groups, x_absmax=L.x_absmax, s_max=L.s_max, prob_bits=args.prob_bits)
+        name = KERNEL_NAMES[psb.query_mapping(q, (L.x.shape[0], L.x.shape[2], L.x.shape[3]) + L.stride + L.pad)]
+        if name not in kernels:
+            kernels.append(name)
         x = torch.from_numpy(L.x).to(dev)
         n, oc = L.x.shape[0], L.w.shape[0]
         oh, ow = L.out_hw
         acc = torch.empty((n, oc, oh, ow), dtype=torch.int32, device=dev)
         y = None if args.no_y else torch.empty((n, oc, oh, ow), dtype=torch.float32, device=dev)
         bt = None if L.budget_to is None else torch.from_numpy(L.budget_to).to(dev)
-        a, b, c = count_work(L, q.export(), torch, dev)
+        a, b, c = count_work(L, q.export(), torch, dev, per_call)
         smac += a
         n_calls += b
         n_prod += c
@@ -169,7 +181,7 @@ def main():
     value = smac / sec_per_step
     kern_s = kernel_ms * 1e-3 / max(n_launch, 1)                 # average sampling-kernel launch
     launches_per_step = n_launch / args.steps
-    ops_per_launch = lane_ops(n_calls, n_prod) / launches_per_step
+    ops_per_launch = lane_ops(n_calls, n_prod, args.prob_bits) / launches_per_step
     achieved = ops_per_launch / kern_s / 1e12
     out = {
         "metric": "sampled MACs/sec (int shift-adds/s) on 1 MI355X",
@@ -177,13 +189,15 @@ def main():
         "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": desc, "sampled_macs_per_step": smac,
-                   "sampled_macs_needing_work_per_step": n_calls * 4, "generator_calls_per_step": n_calls,
+                   "generator_calls_per_step": n_calls, "samples_per_generator_call": per_call,
+                   "prob_bits": args.prob_bits,
                    "kernel_launches_per_step": launches_per_step, "mapping": args.mapping,
                    "rescale_output": not args.no_y},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_TIOPS,
                      "unit": "TIOP/s (simple int32 lane-ops)", "frac": achieved / PEAK_TIOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mapping)),
-                     "kernel": "k_layer_oc_lane" if args.mapping != 1 else "k_layer_pixel_lane",
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mapping))
+                     if args.prob_bits == 23 else None,
+                     "kernel": "+".join(kernels),
                      "kernel_ms_avg": kern_s * 1e3, "lane_ops_per_launch": ops_per_launch},
     }
 
@@ -191,7 +205,8 @@ def main():
         from oracle import binding as orc          # the oracle is only timed here, never used for results
         orc.lib()
         L = layers[0]
-        qo = orc.QWeights(L.w.reshape(L.w.shape[0], -1), x_absmax=L.x_absmax, s_max=L.s_max)
+        qo = orc.QWeights(L.w.reshape(L.w.shape[0], -1), x_absmax=L.x_absmax, s_max=L.s_max,
+                          prob_bits=args.prob_bits)
         total = int(np.prod((L.x.shape[0], L.w.shape[0]) + L.out_hw))
         # bounded sample: as many output elements as about 8e9 sampled MACs need, at most all of them
         per_out = smac / sum(np.prod((l.x.shape[0], l.w.shape[0]) + l.out_hw) for l in layers)

@@ -38,6 +38,12 @@
  *    k = (ci*KH + kh)*KW + kw with ci counted inside the group.  The result is
  *    therefore a pure function of (inputs, seed, layer_id): independent of
  *    tiling, launch geometry and call order.
+ *  - With discretised probabilities (prob_bits = 1..7, Sect. 4.4) p is a multiple of
+ *    2^-prob_bits and a 7-bit uniform decides the bit:
+ *        B = [ u7 < p * 128 ],
+ *    u7 = the low 7 bits of byte (i mod 16) of the Philox block with counter
+ *    (o, k, i div 16, layer_id), byte b of a block being bits 8*(b mod 4) .. +7 of
+ *    word b div 4.  One generator block then serves 16 samples instead of 4.
  */
 #ifndef PSB_H
 #define PSB_H
@@ -81,6 +87,13 @@ typedef struct {
  * [Sect. 3.1, definitions of s, e, p below Eq. "numbersystem"; for a normal
  * binary32 number these are its three bit fields].
  *
+ * Discretised probabilities [Sect. 4.4: probabilities on a regular grid that contains
+ * p = 0 but not p = 1, because p = 1 is the next exponent]: with prob_bits = 1..7, p is
+ * rounded to the nearest multiple of 2^-prob_bits, ties to the even multiple; a p that
+ * rounds to 1 becomes p = 0 with e + 1.  The rounding comes first: e_top, the window and
+ * the overflow rule below see the rounded weights.  A weight that rounds past the largest
+ * binary32 exponent is refused (VALUE).  The exported mantissa is the rounded one.
+ *
  * Exponent window [Sect. 4.4: 4-bit exponents suffice; caption of the stochastic-
  * multiplier figure: the width of the integers restricts the exponents; caption of
  * Fig. "numbersystem": too many shifts of an integer give 0]:
@@ -91,12 +104,12 @@ typedef struct {
  * samples.  Weights below e_min, subnormals and zeros are not live.
  *
  *  w_dev      device, float32 [oc][cin/groups][kh][kw], read only during the call
- *  prob_bits  must be 23 (the full binary32 mantissa)
+ *  prob_bits  23 (p exact: the full binary32 mantissa, 32-bit uniforms) or 1..7
  *  exp_bits   1..5; <= 0 selects 4
  *  x_absmax   1..128, largest |activation| the caller will pass
  *  s_max      1..255, largest sample count / budget the caller will use
  *  out        receives the handle (device memory owned by the library)
- * Errors: NULL, SHAPE, VALUE (NaN/Inf weight, bad widths), OVERFLOW_UNSAFE,
+ * Errors: NULL, SHAPE, VALUE (NaN/Inf weight, bad widths, rounded out of range), OVERFLOW_UNSAFE,
  * TOO_LARGE, DEVICE, ALLOC.
  */
 int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t prob_bits, int32_t exp_bits,
@@ -179,6 +192,11 @@ int psb_last_device_error(void);
  * Results are bit-identical for every mapping; the switch exists for tests and benchmarks.
  * Returns the previous value. */
 int psb_set_mapping(int mapping);
+
+/* The mapping (1, 2 or 3) a layer call with this handle and geometry would run with under the
+ * current psb_set_mapping value; negative psb_status on invalid arguments (NULL, SHAPE,
+ * TOO_LARGE; SHAPE also when mapping 2 is forced on a grouped layer).  Host only: no device work. */
+int psb_query_mapping(const psb_weights_t* q, const psb_conv_geom* geom);
 
 /* Timing of the sampling kernels, for benchmarks.  While enabled, every layer call
  * brackets its sampling kernel (not the zero-fill or the separate rescale kernel) with a

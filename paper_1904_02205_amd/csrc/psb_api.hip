@@ -18,7 +18,7 @@ struct psb_weights {
     psb_wshape shape;
     int32_t K;         // taps per output channel
     int32_t oc_pad;    // OC rounded up to a multiple of 64
-    int32_t exp_bits, x_absmax, s_max;
+    int32_t prob_bits, exp_bits, x_absmax, s_max;
     psb_winfo info;
     int device;
     uint32_t* packed_dev;    // [OC][K]
@@ -115,6 +115,33 @@ bool choose_window(const std::vector<uint32_t>& hist, int OC, int window, int x_
     return false;
 }
 
+// Which kernel serves this layer under the current mapping switch (1, 2, 3), or a psb_status.
+int pick_mapping(const psb_weights* q, const psb::LayerParams& p)
+{
+    int mapping = g_mapping;
+    if (mapping == 2 && q->shape.groups != 1) return PSB_ERR_SHAPE;
+    if (mapping == 0) {
+        // channel lanes pay for every (tap, channel) pair of a tile, live or not: only for mostly dense layers
+        const int64_t n_weights = (int64_t)q->shape.oc * q->K;
+        const bool dense = 2 * q->info.n_live >= n_weights;
+        mapping = (dense && psb::oc_lane_preferred(p)) ? 2 : 3;
+    }
+    return mapping;
+}
+
+void fill_geometry(const psb_weights* q, const psb_conv_geom* g, int32_t OH, int32_t OW, psb::LayerParams& p)
+{
+    std::memset(&p, 0, sizeof(p));
+    p.N = g->n; p.C = q->shape.cin; p.H = g->h; p.W = g->w;
+    p.OC = q->shape.oc; p.OH = OH; p.OW = OW; p.KH = q->shape.kh; p.KW = q->shape.kw;
+    p.Cg = q->shape.cin / q->shape.groups; p.OCg = q->shape.oc / q->shape.groups;
+    p.K = q->K; p.oc_pad = q->oc_pad;
+    p.stride_h = g->stride_h; p.stride_w = g->stride_w; p.pad_h = g->pad_h; p.pad_w = g->pad_w;
+    p.s_max = q->s_max; p.prob_bits = q->prob_bits;
+    p.default_mult = std::ldexp(1.0f, q->info.e_min);
+    p.max_shift = q->info.e_top - q->info.e_min;
+}
+
 int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, int32_t S,
                  const uint8_t* budget_to, const uint8_t* budget_from, uint64_t seed, uint32_t layer_id,
                  int32_t* acc, float* y, const float* mult, const float* bias, hipStream_t stream)
@@ -124,32 +151,19 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
     if (rc != PSB_OK) return rc;
 
     psb::LayerParams p;
-    std::memset(&p, 0, sizeof(p));
+    fill_geometry(q, g, OH, OW, p);
     p.packed = q->packed_dev; p.tile = q->tile_dev; p.x = x;
     p.budget_to = budget_to; p.budget_from = budget_from;
     p.acc = acc; p.y = y; p.mult = mult; p.bias = bias;
-    p.N = g->n; p.C = q->shape.cin; p.H = g->h; p.W = g->w;
-    p.OC = q->shape.oc; p.OH = OH; p.OW = OW; p.KH = q->shape.kh; p.KW = q->shape.kw;
-    p.Cg = q->shape.cin / q->shape.groups; p.OCg = q->shape.oc / q->shape.groups;
-    p.K = q->K; p.oc_pad = q->oc_pad;
-    p.stride_h = g->stride_h; p.stride_w = g->stride_w; p.pad_h = g->pad_h; p.pad_w = g->pad_w;
-    p.S = S; p.s_max = q->s_max;
+    p.S = S;
     p.key0 = (uint32_t)(seed & 0xFFFFFFFFull); p.key1 = (uint32_t)(seed >> 32); p.layer_id = layer_id;
-    p.default_mult = std::ldexp(1.0f, q->info.e_min);
-    p.max_shift = q->info.e_top - q->info.e_min;
 
     int dev = 0;
     PSB_HIP_TRY(hipGetDevice(&dev));
     if (dev != q->device) return PSB_ERR_DEVICE;
 
-    int mapping = g_mapping;
-    if (mapping == 2 && q->shape.groups != 1) return PSB_ERR_SHAPE;
-    if (mapping == 0) {
-        // channel lanes pay for every (tap, channel) pair of a tile, live or not: only for mostly dense layers
-        const int64_t n_weights = (int64_t)q->shape.oc * q->K;
-        const bool dense = 2 * q->info.n_live >= n_weights;
-        mapping = (dense && psb::oc_lane_preferred(p)) ? 2 : 3;
-    }
+    const int mapping = pick_mapping(q, p);
+    if (mapping < 0) return mapping;
 
     if (mapping == 2) {
         rc = psb::launch_oc_lane(p, q->sched_dev, stream, profile_begin, profile_end);
@@ -181,6 +195,17 @@ int psb_set_mapping(int mapping)
     const int prev = g_mapping;
     if (mapping >= 0 && mapping <= 3) g_mapping = mapping;
     return prev;
+}
+
+int psb_query_mapping(const psb_weights_t* q, const psb_conv_geom* geom)
+{
+    if (!q || !geom) return PSB_ERR_NULL;
+    int32_t OH = 0, OW = 0;
+    const int rc = check_geom(&q->shape, geom, &OH, &OW);
+    if (rc != PSB_OK) return rc;
+    psb::LayerParams p;
+    fill_geometry(q, geom, OH, OW, p);
+    return pick_mapping(q, p);
 }
 
 int psb_profile_enable(int on)
@@ -220,7 +245,7 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     int64_t K = 0;
     int rc = check_wshape(shape, &K);
     if (rc != PSB_OK) return rc;
-    if (prob_bits != 23) return PSB_ERR_VALUE;
+    if (prob_bits != 23 && (prob_bits < 1 || prob_bits > 7)) return PSB_ERR_VALUE;
     if (exp_bits <= 0) exp_bits = 4;
     if (exp_bits > 5 || x_absmax <= 0 || x_absmax > 128 || s_max <= 0 || s_max > 255) return PSB_ERR_VALUE;
 
@@ -234,7 +259,7 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     if (!q) return PSB_ERR_ALLOC;
     std::memset(q, 0, sizeof(*q));
     q->shape = *shape; q->K = (int32_t)K; q->oc_pad = oc_pad;
-    q->exp_bits = exp_bits; q->x_absmax = x_absmax; q->s_max = s_max;
+    q->prob_bits = prob_bits; q->exp_bits = exp_bits; q->x_absmax = x_absmax; q->s_max = s_max;
 
     // scratch: [0]=max field, [1]=non-finite flag, then 3 64-bit counters, then the histogram
     uint32_t* scratch = nullptr;
@@ -265,7 +290,7 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     // 1. largest exponent, NaN/Inf detection
     {
         const int blocks = (int)std::min<int64_t>((nw + 255) / 256, 2048);
-        hipLaunchKernelGGL(psb::k_exponent_scan, dim3(blocks), dim3(256), 0, stream, w_bits, nw, scratch);
+        hipLaunchKernelGGL(psb::k_exponent_scan, dim3(blocks), dim3(256), 0, stream, w_bits, nw, (int)prob_bits, scratch);
         QTRY(hipGetLastError());
     }
     uint32_t scan[2] = {0, 0};
@@ -278,7 +303,7 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     int field_min = field_top;
     if (field_top != 0) {
         // 2. per-channel exponent histogram over the window, then the host picks e_min
-        hipLaunchKernelGGL(psb::k_exponent_hist, dim3(OC), dim3(256), 0, stream, w_bits, (int)K, field_top, window,
+        hipLaunchKernelGGL(psb::k_exponent_hist, dim3(OC), dim3(256), 0, stream, w_bits, (int)K, (int)prob_bits, field_top, window,
                            scratch + 8);
         QTRY(hipGetLastError());
         std::vector<uint32_t> hist((size_t)OC * psb::kHistBins);
@@ -298,7 +323,8 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     {
         const int64_t total = (int64_t)oc_pad * K;
         const int blocks = (int)std::min<int64_t>((total + 255) / 256, 4096);
-        hipLaunchKernelGGL(psb::k_pack, dim3(blocks), dim3(256), 0, stream, w_bits, OC, (int)K, oc_pad, field_min,
+        hipLaunchKernelGGL(psb::k_pack, dim3(blocks), dim3(256), 0, stream, w_bits, OC, (int)K, oc_pad, (int)prob_bits,
+                           field_min,
                            q->packed_dev, q->tile_dev, reinterpret_cast<unsigned long long*>(scratch + 2));
         QTRY(hipGetLastError());
         hipLaunchKernelGGL(psb::k_live_index, dim3(OC), dim3(256), 0, stream, q->packed_dev, (int)K, q->live_idx_dev,

@@ -22,14 +22,32 @@ constexpr int kHistBins = 32;                // exponent window is at most 2^5 w
 // normal binary32 these are its sign bit, exponent field - 127 and mantissa / 2^23).
 // ---------------------------------------------------------------------------------
 
-// scan[0] = largest exponent field among normal non-zero weights (0 if none)
-// scan[1] = 1 if any weight is NaN or Inf
+// Discretised probabilities (Sect. 4.4): p is rounded, ties to even, to a multiple of 2^-prob_bits;
+// the grid holds 0 but not 1, so a p that rounds to 1 becomes p = 0 at the next exponent.  On the bit
+// pattern this is one integer addition into the exponent|mantissa field, whose carry does the exponent
+// step.  A weight pushed past the largest finite exponent comes out with the exponent field of an
+// infinity and is reported like one.  Zeros, subnormals, NaN and Inf are returned unchanged.
+__device__ __forceinline__ uint32_t round_probability(uint32_t bits, int prob_bits)
+{
+    const uint32_t f = (bits >> 23) & 0xFFu;
+    if (prob_bits >= 23 || f == 0u || f == 0xFFu) return bits;
+    const int drop = 23 - prob_bits;
+    const uint32_t em = bits & 0x7FFFFFFFu;
+    const uint32_t q = em >> drop;
+    const uint32_t rem = em & ((1u << drop) - 1u);
+    const uint32_t half = 1u << (drop - 1);
+    const uint32_t up = (rem > half || (rem == half && (q & 1u))) ? 1u : 0u;
+    return (bits & 0x80000000u) | ((q + up) << drop);
+}
+
+// scan[0] = largest exponent field among normal non-zero weights after rounding (0 if none)
+// scan[1] = 1 if any weight is NaN or Inf, or is rounded past the largest finite exponent
 __global__ void __launch_bounds__(256) k_exponent_scan(const uint32_t* __restrict__ w_bits, int64_t n,
-                                                       uint32_t* __restrict__ scan)
+                                                       int prob_bits, uint32_t* __restrict__ scan)
 {
     uint32_t best = 0, bad = 0;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        const uint32_t f = (w_bits[i] >> 23) & 0xFFu;
+        const uint32_t f = (round_probability(w_bits[i], prob_bits) >> 23) & 0xFFu;
         if (f == 0xFFu) bad = 1;
         else if (f > best) best = f;
     }
@@ -46,15 +64,15 @@ __global__ void __launch_bounds__(256) k_exponent_scan(const uint32_t* __restric
 
 // hist[oc][b] = number of normal weights of channel oc whose exponent is e_top - b,
 // b = 0 .. window.  One workgroup per output channel.
-__global__ void __launch_bounds__(256) k_exponent_hist(const uint32_t* __restrict__ w_bits, int K, int field_top,
-                                                       int window, uint32_t* __restrict__ hist)
+__global__ void __launch_bounds__(256) k_exponent_hist(const uint32_t* __restrict__ w_bits, int K, int prob_bits,
+                                                       int field_top, int window, uint32_t* __restrict__ hist)
 {
     __shared__ uint32_t bins[kHistBins];
     if (threadIdx.x < kHistBins) bins[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t* row = w_bits + (int64_t)blockIdx.x * K;
     for (int k = threadIdx.x; k < K; k += blockDim.x) {
-        const int f = (int)((row[k] >> 23) & 0xFFu);
+        const int f = (int)((round_probability(row[k], prob_bits) >> 23) & 0xFFu);
         const int b = field_top - f;
         if (f != 0 && b >= 0 && b <= window) atomicAdd(&bins[b], 1u);
     }
@@ -64,10 +82,16 @@ __global__ void __launch_bounds__(256) k_exponent_hist(const uint32_t* __restric
 
 // packed[oc][k] (row-major, the export format) and tile[k][oc_pad] (transposed, padded
 // with dead entries to a multiple of 64 channels, for the channel-lane kernel):
-// tile entry = { threshold = mantissa << 9,  unit = +-2^shift (0 when not live) }.
+// tile entry = { threshold,  unit = +-2^shift (0 when not live) }; the threshold is mantissa << 9 for
+// 32-bit uniforms and the 7-bit numerator of p in each of the four bytes for 7-bit uniforms.
 // counts[0..2] = zero, flushed, live.
+__device__ __forceinline__ uint32_t threshold_of(uint32_t mant, int prob_bits)
+{
+    return prob_bits < 23 ? (mant >> 16) * 0x01010101u : mant << 9;
+}
+
 __global__ void __launch_bounds__(256) k_pack(const uint32_t* __restrict__ w_bits, int OC, int K, int oc_pad,
-                                              int field_min /* exponent field of e_min */,
+                                              int prob_bits, int field_min /* exponent field of e_min */,
                                               uint32_t* __restrict__ packed, uint2* __restrict__ tile,
                                               unsigned long long* __restrict__ counts)
 {
@@ -80,7 +104,7 @@ __global__ void __launch_bounds__(256) k_pack(const uint32_t* __restrict__ w_bit
         uint2 entry = make_uint2(0u, 0u);
         if (oc < OC) {
             uint32_t word = kDeadWord;
-            const uint32_t bits = w_bits[(int64_t)oc * K + k];
+            const uint32_t bits = round_probability(w_bits[(int64_t)oc * K + k], prob_bits);
             const int f = (int)((bits >> 23) & 0xFFu);
             const uint32_t mant = bits & 0x7FFFFFu;
             if (f == 0 && mant == 0) n_zero++;
@@ -90,7 +114,7 @@ __global__ void __launch_bounds__(256) k_pack(const uint32_t* __restrict__ w_bit
                 const uint32_t shift = (uint32_t)(f - field_min);
                 word = (bits & 0x80000000u) | (shift << 23) | mant;
                 const uint32_t unit = 1u << shift;              // shift <= 30 by the overflow rule
-                entry = make_uint2(mant << 9, (bits & 0x80000000u) ? (0u - unit) : unit);
+                entry = make_uint2(threshold_of(mant, prob_bits), (bits & 0x80000000u) ? (0u - unit) : unit);
             }
             packed[(int64_t)oc * K + k] = word;
         }
@@ -129,6 +153,7 @@ struct LayerParams {
     int stride_h, stride_w, pad_h, pad_w;
     // sampling
     int S, s_max;
+    int prob_bits;             // 23: 32-bit uniforms, 4 per generator block; 1..7: 7-bit uniforms, 16 per block
     uint32_t key0, key1, layer_id;
     float default_mult;        // 2^e_min
     int max_shift;             // largest shift of a live weight
@@ -149,6 +174,43 @@ __device__ __forceinline__ uint32_t count_below(uint32_t o, uint32_t k, uint32_t
         n += (s0 + 3 >= from && s0 + 3 < to && r.w < thr) ? 1u : 0u;
     }
     return n;
+}
+
+// 7-bit uniforms (Sect. 4.4: a k_p-bit probability needs k_p random bits per sample): sample i of a
+// product is the low 7 bits of byte i mod 16 of generator block i div 16, bytes numbered from the
+// least significant byte of word 0.  thr4 holds the 7-bit threshold in each byte.
+//
+// Bytes of one word whose 7-bit uniform is NOT below the threshold, among the bytes selected by
+// valid (0x80 in each selected byte): with bit 7 forced to one no byte borrows from its neighbour,
+// and bit 7 of (0x80 + u) - t survives exactly when u >= t.
+__device__ __forceinline__ uint32_t not_below7(uint32_t word, uint32_t thr4, uint32_t valid)
+{
+    return (uint32_t)__popc(((word | 0x80808080u) - thr4) & valid);
+}
+
+// 0x80 in byte b of word w of block j for every sample 16j + 4w + b inside [from, to)
+__device__ __forceinline__ uint32_t valid_bytes7(int j, int w, int from, int to)
+{
+    const int base = 16 * j + 4 * w;
+    const int lo = min(max(from - base, 0), 4), hi = min(max(to - base, 0), 4);
+    const uint32_t below_hi = hi >= 4 ? 0xFFFFFFFFu : (1u << (8 * hi)) - 1u;
+    const uint32_t below_lo = lo >= 4 ? 0xFFFFFFFFu : (1u << (8 * lo)) - 1u;
+    return below_hi & ~below_lo & 0x80808080u;
+}
+
+// Number of samples i in [from,to) of product (o,k) whose 7-bit uniform is below the threshold.
+__device__ __forceinline__ uint32_t count_below7(uint32_t o, uint32_t k, uint32_t layer, uint32_t key0,
+                                                 uint32_t key1, uint32_t thr4, int from, int to)
+{
+    uint32_t not_below = 0;
+    for (int j = from >> 4; 16 * j < to; ++j) {
+        const u32x4 r = philox4x32_10(u32x4{o, k, (uint32_t)j, layer}, key0, key1);
+        not_below += not_below7(r.x, thr4, valid_bytes7(j, 0, from, to));
+        not_below += not_below7(r.y, thr4, valid_bytes7(j, 1, from, to));
+        not_below += not_below7(r.z, thr4, valid_bytes7(j, 2, from, to));
+        not_below += not_below7(r.w, thr4, valid_bytes7(j, 3, from, to));
+    }
+    return (uint32_t)(to - from) - not_below;
 }
 
 // Final rescale: four separately rounded binary32 operations.
@@ -197,7 +259,10 @@ __global__ void __launch_bounds__(256) k_layer_pixel_lane(const LayerParams p)
                     if (iy < 0 || iy >= p.H || ix < 0 || ix >= p.W) continue;
                     const int32_t xv = xn[((int64_t)ci * p.H + iy) * p.W + ix];
                     if (xv == 0) continue;
-                    const uint32_t cnt = count_below(o, (uint32_t)k, p.layer_id, p.key0, p.key1, word << 9, from, to);
+                    const uint32_t thr = threshold_of(word & 0x7FFFFFu, p.prob_bits);
+                    const uint32_t cnt = p.prob_bits < 23
+                        ? count_below7(o, (uint32_t)k, p.layer_id, p.key0, p.key1, thr, from, to)
+                        : count_below(o, (uint32_t)k, p.layer_id, p.key0, p.key1, thr, from, to);
                     const int32_t shifted = (int32_t)((uint32_t)xv << ((word >> 23) & 0xFFu));
                     const int32_t term = shifted * (int32_t)((uint32_t)(to - from) + cnt);
                     acc += (word & 0x80000000u) ? -term : term;

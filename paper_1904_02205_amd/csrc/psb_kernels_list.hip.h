@@ -57,9 +57,21 @@ __device__ __forceinline__ uint32_t count_block_full(uint32_t o, uint32_t k, uin
     return (r.x < thr ? 1u : 0u) + (r.y < thr ? 1u : 0u) + (r.z < thr ? 1u : 0u) + (r.w < thr ? 1u : 0u);
 }
 
-// NB > 0: every pixel draws samples 0 .. 4*NB-1 (a call with the same S everywhere, S = 4*NB).
+// Same with sixteen 7-bit uniforms per block, thr4 = the 7-bit threshold in each byte.
+__device__ __forceinline__ uint32_t count_block_full7(uint32_t o, uint32_t k, uint32_t j, uint32_t layer, uint32_t key0,
+                                                      uint32_t key1, uint32_t thr4)
+{
+    const u32x4 r = philox4x32_10(u32x4{o, k, j, layer}, key0, key1);
+    const uint32_t all = 0x80808080u;
+    return 16u - (not_below7(r.x, thr4, all) + not_below7(r.y, thr4, all) + not_below7(r.z, thr4, all) +
+                  not_below7(r.w, thr4, all));
+}
+
+// NB > 0: every pixel draws the samples of generator blocks 0 .. NB-1, all of them (a call with the
+//         same S everywhere, S = NB * samples per block).
 // NB = 0: per-pixel ranges [from, to), any values.
-template <int NB>
+// P7: 7-bit uniforms, 16 samples per block; otherwise 32-bit uniforms, 4 per block.
+template <int NB, bool P7>
 __global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerParams p,
                                                                     const uint32_t* __restrict__ live_idx,
                                                                     const uint32_t* __restrict__ live_cnt)
@@ -107,7 +119,7 @@ __global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerP
             const uint32_t word = p.packed[(int64_t)oc * p.K + k];
             const uint32_t unit = 1u << ((word >> 23) & 0xFFu);
             ktab[tid] = k;
-            wtab[tid] = make_uint2(word << 9, (word & 0x80000000u) ? (0u - unit) : unit);
+            wtab[tid] = make_uint2(threshold_of(word & 0x7FFFFFu, P7 ? 7 : 23), (word & 0x80000000u) ? (0u - unit) : unit);
             const int khw = p.KH * p.KW;
             const int ci = (int)k / khw;
             const int r = (int)k - ci * khw;
@@ -159,14 +171,15 @@ __global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerP
                     const uint32_t thr = wtab[slot].x;
 #pragma unroll
                     for (int j = 0; j < NB; ++j)
-                        cnt[u] += count_block_full(ou, ku, (uint32_t)j, p.layer_id, p.key0, p.key1, thr);
+                        cnt[u] += P7 ? count_block_full7(ou, ku, (uint32_t)j, p.layer_id, p.key0, p.key1, thr)
+                                     : count_block_full(ou, ku, (uint32_t)j, p.layer_id, p.key0, p.key1, thr);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     if (ent[u] == 0xFFFFFFFFu) continue;
                     const int32_t xs = (int32_t)(int8_t)((ent[u] >> 16) & 0xFFu);
                     const int32_t unit = (int32_t)wtab[(ent[u] >> 8) & 0xFFu].y;
-                    const int32_t term = (int32_t)((uint32_t)xs * ((uint32_t)(4 * NB) + cnt[u]) * (uint32_t)unit);   // modulo 2^32
+                    const int32_t term = (int32_t)((uint32_t)xs * ((uint32_t)((P7 ? 16 : 4) * NB) + cnt[u]) * (uint32_t)unit);   // modulo 2^32
                     atomicAdd(&acc_s[ent[u] & 0xFFu], term);
                 }
             }
@@ -177,7 +190,8 @@ __global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerP
                 const uint32_t slot = (entry >> 8) & 0xFFu;
                 const uint32_t rg = range_s[pl];
                 const int f = (int)(rg & 0xFFu), t = (int)(rg >> 8);
-                const uint32_t c = count_below(o_s[pl], ktab[slot], p.layer_id, p.key0, p.key1, wtab[slot].x, f, t);
+                const uint32_t c = P7 ? count_below7(o_s[pl], ktab[slot], p.layer_id, p.key0, p.key1, wtab[slot].x, f, t)
+                                      : count_below(o_s[pl], ktab[slot], p.layer_id, p.key0, p.key1, wtab[slot].x, f, t);
                 const int32_t xs = (int32_t)(int8_t)((entry >> 16) & 0xFFu);
                 const int32_t term = (int32_t)((uint32_t)xs * ((uint32_t)(t - f) + c) * wtab[slot].y);   // modulo 2^32
                 atomicAdd(&acc_s[pl], term);
@@ -204,17 +218,31 @@ inline int launch_product_list(const LayerParams& p, const uint32_t* live_idx, c
     const int64_t gx = (npix + kListPixels - 1) / kListPixels;
     if (gx > 2147483647ll || p.OC > 65535) return (int)hipErrorInvalidValue;
     const dim3 grid((unsigned)gx, (unsigned)p.OC), block(kListPixels);
-    int nb = 0;   // compile-time block count only for a uniform S that is a multiple of 4
-    if (!p.budget_to && (p.S & 3) == 0) nb = p.S / 4;
+    // compile-time block count only for a uniform S that is a whole number of generator blocks
+    const bool p7 = p.prob_bits < 23;
+    const int per_block = p7 ? 16 : 4;
+    int nb = 0;
+    if (!p.budget_to && p.S % per_block == 0) nb = p.S / per_block;
     int slot = 0;
     const bool timed = prof_begin(stream, &slot);
-    switch (nb) {
-        case 1: hipLaunchKernelGGL(k_layer_product_list<1>, grid, block, 0, stream, p, live_idx, live_cnt); break;
-        case 2: hipLaunchKernelGGL(k_layer_product_list<2>, grid, block, 0, stream, p, live_idx, live_cnt); break;
-        case 4: hipLaunchKernelGGL(k_layer_product_list<4>, grid, block, 0, stream, p, live_idx, live_cnt); break;
-        case 8: hipLaunchKernelGGL(k_layer_product_list<8>, grid, block, 0, stream, p, live_idx, live_cnt); break;
-        default: hipLaunchKernelGGL(k_layer_product_list<0>, grid, block, 0, stream, p, live_idx, live_cnt); break;
+#define PSB_LAUNCH(NB_, P7_) \
+    hipLaunchKernelGGL((k_layer_product_list<NB_, P7_>), grid, block, 0, stream, p, live_idx, live_cnt)
+    if (p7) {
+        switch (nb) {
+            case 1: PSB_LAUNCH(1, true); break;
+            case 2: PSB_LAUNCH(2, true); break;
+            default: PSB_LAUNCH(0, true); break;
+        }
+    } else {
+        switch (nb) {
+            case 1: PSB_LAUNCH(1, false); break;
+            case 2: PSB_LAUNCH(2, false); break;
+            case 4: PSB_LAUNCH(4, false); break;
+            case 8: PSB_LAUNCH(8, false); break;
+            default: PSB_LAUNCH(0, false); break;
+        }
     }
+#undef PSB_LAUNCH
     if (timed) prof_end(stream, slot);
     return (int)hipGetLastError();
 }

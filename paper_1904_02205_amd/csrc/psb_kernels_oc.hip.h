@@ -97,9 +97,10 @@ __device__ __forceinline__ TapScalars tap_scalars(uint32_t s_x1, const Keys& key
     return TapScalars{s_hi ^ key.k1[1], s_lo};
 }
 
-// Number of samples of block j of one product that are below thr.
+// Number of samples of block j of one product that are below thr.  P7: the block holds sixteen 7-bit
+// uniforms and thr the 7-bit threshold in each byte; otherwise four 32-bit uniforms.
 // state after round 1: (.., .., ts.sz ^ lo_a, ts.s_lo); words 0 and 1 were used in the per-pixel set-up.
-template <bool FULL>
+template <bool FULL, bool P7>
 __device__ __forceinline__ uint32_t sample_block(uint32_t thr, TapScalars ts, const PixelHoist& h, uint32_t hz,
                                                  uint32_t lo2, const Keys& key, int j, int from, int to)
 {
@@ -114,7 +115,17 @@ __device__ __forceinline__ uint32_t sample_block(uint32_t thr, TapScalars ts, co
     c.w = lo2;
     c = philox_rounds_3_to_9(c, key);
     uint32_t n = 0;
-    if (FULL) {
+    if constexpr (P7) {
+        if (FULL) {
+            const uint32_t all = 0x80808080u;
+            return 16u - (not_below7(c.x, thr, all) + not_below7(c.y, thr, all) + not_below7(c.z, thr, all) +
+                          not_below7(c.w, thr, all));
+        }
+        const int lo = max(from, 16 * j), hi = min(to, 16 * j + 16);
+        return (uint32_t)(hi - lo) -
+               (not_below7(c.x, thr, valid_bytes7(j, 0, from, to)) + not_below7(c.y, thr, valid_bytes7(j, 1, from, to)) +
+                not_below7(c.z, thr, valid_bytes7(j, 2, from, to)) + not_below7(c.w, thr, valid_bytes7(j, 3, from, to)));
+    } else if (FULL) {
         n += (c.x < thr) ? 1u : 0u;
         n += (c.y < thr) ? 1u : 0u;
         n += (c.z < thr) ? 1u : 0u;
@@ -153,7 +164,7 @@ __device__ __forceinline__ uint32_t list_entry(uint32_t mylist, int i)
 // (NB = 0: run-time number of blocks).  Returns this lane's partial accumulator.
 // mylist: lane i holds entry i = (tap index inside the tile << 8) | activation byte, and 0
 // beyond cnt (entry 0 addresses tile row 0, so reading one group ahead is always in bounds).
-template <int NB, bool FULL>
+template <int NB, bool FULL, bool P7>
 __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const uint2* __restrict__ w_tile,
                                                 int lane, uint32_t k0, int j0, int nb_rt, int from, int to,
                                                 const PixelHoist& h, const Keys& key)
@@ -170,7 +181,7 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
             for (int jj = 0; jj < nb_rt; ++jj) {
                 uint32_t s_hib, hz, lo2;
                 block_setup(h, key, j0 + jj, s_hib, hz, lo2);
-                n += sample_block<false>(wt.x, tap_scalars(s_hib ^ (k0 + kl), key), h, hz, lo2, key, j0 + jj, from, to);
+                n += sample_block<false, P7>(wt.x, tap_scalars(s_hib ^ (k0 + kl), key), h, hz, lo2, key, j0 + jj, from, to);
             }
             acc = mad24(__mul24(xs, (int32_t)n), (int32_t)wt.y, acc);
         }
@@ -219,7 +230,7 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
             for (int e = 0; e < E; ++e)
 #pragma unroll
                 for (int jj = 0; jj < NB; ++jj)
-                    cnt_b[e][jj] = sample_block<FULL>(wt[e].x, ts[e][jj], h, hz[jj], lo2[jj], key, j0 + jj, from, to);
+                    cnt_b[e][jj] = sample_block<FULL, P7>(wt[e].x, ts[e][jj], h, hz[jj], lo2[jj], key, j0 + jj, from, to);
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 uint32_t n = nsamp;
@@ -235,7 +246,7 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
                 uint32_t n = nsamp;
 #pragma unroll
                 for (int jj = 0; jj < NB; ++jj)
-                    n += sample_block<FULL>(wt.x, tap_scalars(s_hib[jj] ^ (k0 + (entry >> 8)), key), h, hz[jj], lo2[jj],
+                    n += sample_block<FULL, P7>(wt.x, tap_scalars(s_hib[jj] ^ (k0 + (entry >> 8)), key), h, hz[jj], lo2[jj],
                                             key, j0 + jj, from, to);
                 acc = mad24(__mul24((int32_t)(int8_t)(entry & 0xFFu), (int32_t)n), (int32_t)wt.y, acc);
             }
@@ -374,23 +385,34 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
                     mulhilo(kMulB, z1, h.hi_b1, lo_b1);                    // round 1: MulB * z1
                     h.y2k = lo_b1 ^ key.k0[2];
 
-                    const int j0 = from >> 2;
-                    const int nb = ((to + 3) >> 2) - j0;
-                    const bool full = ((from | to) & 3) == 0;
+                    // generator blocks serve 4 samples (32-bit uniforms) or 16 (7-bit uniforms)
+                    const bool p7 = p.prob_bits < 23;
+                    const int lg = p7 ? 4 : 2;
+                    const int j0 = from >> lg;
+                    const int nb = ((to + (1 << lg) - 1) >> lg) - j0;
+                    const bool full = ((from | to) & ((1 << lg) - 1)) == 0;
                     const uint32_t kbase = (uint32_t)k0;
-                    if (full) {
+#define PSB_LIST(NB_, FULL_, P7_) \
+    total = process_list<NB_, FULL_, P7_>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key)
+                    if (p7) {
+                        if (full && nb == 1) PSB_LIST(1, true, true);
+                        else if (full && nb == 2) PSB_LIST(2, true, true);
+                        else if (nb == 1) PSB_LIST(1, false, true);
+                        else PSB_LIST(0, false, true);
+                    } else if (full) {
                         switch (nb) {
-                            case 1: total = process_list<1, true>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
-                            case 2: total = process_list<2, true>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
-                            case 4: total = process_list<4, true>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
-                            case 8: total = process_list<8, true>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
-                            default: total = process_list<0, false>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key); break;
+                            case 1: PSB_LIST(1, true, false); break;
+                            case 2: PSB_LIST(2, true, false); break;
+                            case 4: PSB_LIST(4, true, false); break;
+                            case 8: PSB_LIST(8, true, false); break;
+                            default: PSB_LIST(0, false, false); break;
                         }
                     } else if (nb == 1) {
-                        total = process_list<1, false>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key);
+                        PSB_LIST(1, false, false);
                     } else {
-                        total = process_list<0, false>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key);
+                        PSB_LIST(0, false, false);
                     }
+#undef PSB_LIST
                 }
             }
 

@@ -20,7 +20,8 @@ MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE, MAPPING_PRODUCT_LIST = 0
 
 SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
-           "psb_last_device_error", "psb_set_mapping", "psb_profile_enable", "psb_profile_read"]
+           "psb_last_device_error", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
+           "psb_profile_read"]
 
 
 class PsbError(RuntimeError):
@@ -73,6 +74,7 @@ def lib():
         L.psb_conv2d_progressive.argtypes = [vp, vp, C.POINTER(ConvGeom), vp, vp, u64, u32, vp, vp, vp, vp, vp]
         L.psb_last_device_error.argtypes = []
         L.psb_set_mapping.argtypes = [C.c_int]
+        L.psb_query_mapping.argtypes = [vp, C.POINTER(ConvGeom)]
         L.psb_profile_enable.argtypes = [C.c_int]
         L.psb_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         for name in SYMBOLS:
@@ -101,6 +103,14 @@ def _ptr(t, dtype, name):
 
 def set_mapping(mapping):
     return lib().psb_set_mapping(int(mapping))
+
+
+def query_mapping(q, geom):
+    """Mapping (1, 2, 3) a layer call on handle q with geom = (n, h, w, stride_h, stride_w, pad_h, pad_w) would use."""
+    rc = lib().psb_query_mapping(q._h, C.byref(ConvGeom(*geom)))
+    if rc < 0:
+        raise PsbError(rc, "psb_query_mapping")
+    return rc
 
 
 def profile_enable(on=True):
@@ -133,6 +143,7 @@ class Weights:
         self.wshape = (oc, cg * groups, kh, kw, groups)
         self.K = cg * kh * kw
         self.s_max = s_max
+        self.prob_bits = prob_bits
         self._h = C.c_void_p(None)
         shape = WShape(*self.wshape)
         rc = lib().psb_quantize_weights(_ptr(w, torch.float32, "w"), C.byref(shape), prob_bits, exp_bits, x_absmax,

@@ -2,9 +2,9 @@
 import numpy as np
 
 
-def oracle_quantize(orc, L, exp_bits=0):
+def oracle_quantize(orc, L, exp_bits=0, prob_bits=23):
     w = L.w.reshape(L.w.shape[0], -1)
-    return orc.QWeights(w, exp_bits=exp_bits, x_absmax=L.x_absmax, s_max=L.s_max)
+    return orc.QWeights(w, exp_bits=exp_bits, x_absmax=L.x_absmax, s_max=L.s_max, prob_bits=prob_bits)
 
 
 def oracle_layer(orc, L, q=None, budget_to=None, budget_from=None, acc_in=None, points=None, S=None):
@@ -18,10 +18,11 @@ def oracle_layer(orc, L, q=None, budget_to=None, budget_from=None, acc_in=None, 
                       budget_from=budget_from, seed=L.seed, layer_id=L.layer_id, points=points, acc_in=acc_in)
 
 
-def gpu_quantize(psb, L, exp_bits=0, device="cuda"):
+def gpu_quantize(psb, L, exp_bits=0, prob_bits=23, device="cuda"):
     import torch
     w = torch.from_numpy(L.w).to(device)
-    return psb.Weights(w, groups=L.groups, exp_bits=exp_bits, x_absmax=L.x_absmax, s_max=L.s_max)
+    return psb.Weights(w, groups=L.groups, exp_bits=exp_bits, x_absmax=L.x_absmax, s_max=L.s_max,
+                       prob_bits=prob_bits)
 
 
 def gpu_layer(psb, L, q=None, budget_to=None, budget_from=None, acc_in=None, S=None, want_y=False, mult=None,

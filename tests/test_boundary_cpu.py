@@ -60,7 +60,8 @@ def test_null_arguments_are_rejected_before_any_device_work(psb):
     assert L.psb_quantize_weights(C.c_void_p(16), None, 23, 0, 127, 8, None, C.byref(h)) == psb.ERR_NULL
     assert L.psb_quantize_weights(C.c_void_p(16), C.byref(ws), 23, 0, 127, 8, None, None) == psb.ERR_NULL
     # value errors are found before the pointer is ever dereferenced
-    for prob_bits, exp_bits, xmax, smax in ((8, 0, 127, 8), (23, 6, 127, 8), (23, 0, 0, 8), (23, 0, 129, 8),
+    for prob_bits, exp_bits, xmax, smax in ((8, 0, 127, 8), (0, 0, 127, 8), (22, 0, 127, 8), (-3, 0, 127, 8),
+                                            (23, 6, 127, 8), (23, 0, 0, 8), (23, 0, 129, 8),
                                             (23, 0, 127, 0), (23, 0, 127, 256)):
         assert L.psb_quantize_weights(C.c_void_p(16), C.byref(ws), prob_bits, exp_bits, xmax, smax, None,
                                       C.byref(h)) == psb.ERR_VALUE
@@ -73,6 +74,13 @@ def test_null_arguments_are_rejected_before_any_device_work(psb):
     assert L.psb_conv2d(None, None, C.byref(g), 1, 0, 0, None, None, None, None, None) == psb.ERR_NULL
     assert L.psb_conv2d_progressive(None, None, C.byref(g), None, None, 0, 0, None, None, None, None, None) == psb.ERR_NULL
     assert L.psb_last_device_error() == 0
+
+
+def test_query_mapping_null_arguments(psb):
+    L = psb.lib()
+    g = psb.ConvGeom(1, 8, 8, 1, 1, 1, 1)
+    assert L.psb_query_mapping(None, C.byref(g)) == psb.ERR_NULL
+    assert L.psb_query_mapping(C.c_void_p(16), None) == psb.ERR_NULL
 
 
 def test_mapping_switch(psb):

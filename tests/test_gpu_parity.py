@@ -145,6 +145,25 @@ def test_layer_bit_exact(psb, orc, case):
     assert np.array_equal(acc2, ref)
 
 
+def test_query_mapping_names_the_kernel_that_runs(psb):
+    rng = np.random.default_rng(250)
+    dense = _layer(rng, 1, 16, 64, 7, 3, pad=1, S=8)
+    pruned = _layer(rng, 2, 96, 40, 5, 1, S=16, prune=0.9)
+    dw = _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16)
+    geom = lambda L: (L.x.shape[0], L.x.shape[2], L.x.shape[3]) + L.stride + L.pad
+    psb.set_mapping(psb.MAPPING_AUTO)
+    assert psb.query_mapping(helpers.gpu_quantize(psb, dense), geom(dense)) == psb.MAPPING_CHANNEL_LANE
+    assert psb.query_mapping(helpers.gpu_quantize(psb, pruned), geom(pruned)) == psb.MAPPING_PRODUCT_LIST
+    assert psb.query_mapping(helpers.gpu_quantize(psb, dw), geom(dw)) == psb.MAPPING_PRODUCT_LIST
+    psb.set_mapping(psb.MAPPING_PIXEL_LANE)
+    assert psb.query_mapping(helpers.gpu_quantize(psb, dense), geom(dense)) == psb.MAPPING_PIXEL_LANE
+    psb.set_mapping(psb.MAPPING_CHANNEL_LANE)
+    with pytest.raises(psb.PsbError) as ei:
+        psb.query_mapping(helpers.gpu_quantize(psb, dw), geom(dw))
+    assert ei.value.code == psb.ERR_SHAPE
+    psb.set_mapping(psb.MAPPING_AUTO)
+
+
 def test_channel_lane_refuses_grouped_layers(psb):
     rng = np.random.default_rng(201)
     L = _layer(rng, 1, 8, 8, 5, 3, pad=1, groups=2, S=4)

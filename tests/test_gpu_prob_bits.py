@@ -1,0 +1,162 @@
+"""Discretised probabilities (Sect. 4.4) on the GPU vs the CPU oracle: weight rounding with its carry
+into the exponent, and layers sampled with 7-bit uniforms, 16 per generator block.  Bit-exact."""
+import numpy as np
+import pytest
+
+import helpers
+from paper_1904_02205_amd import synth
+from test_gpu_parity import _layer
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def psb():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_1904_02205_amd import psb as m
+    m.lib()
+    yield m
+    m.set_mapping(m.MAPPING_AUTO)
+
+
+def _f32(bits):
+    return np.array(bits, dtype=np.uint32).view(np.float32)
+
+
+def _rounding_cases(kp):
+    """Weights that sit on, just below and just above every kind of rounding boundary for kp bits."""
+    drop = 23 - kp
+    half = 1 << (drop - 1)
+    mants = []
+    for q in (0, 1, 2, (1 << kp) - 2, (1 << kp) - 1):
+        for rem in (0, 1, half - 1, half, half + 1, (1 << drop) - 1):
+            mants.append((q << drop) | rem)
+    mants = np.array(mants, dtype=np.uint32)
+    fields = np.array([120, 125, 126, 127], dtype=np.uint32)
+    bits = (fields[:, None] << 23) | mants[None, :]
+    bits[1::2, ::3] |= 0x80000000          # some negative
+    return _f32(bits)
+
+
+@pytest.mark.parametrize("kp", [1, 2, 3, 4, 5, 6, 7])
+def test_quantize_rounding_matches_oracle(psb, orc, kp):
+    import torch
+    rng = np.random.default_rng(500 + kp)
+    sets = [(_rounding_cases(kp), 127, 4, 0),
+            (synth.he_normal((70, 20, 3, 3), rng), 127, 16, 0),
+            (synth.prune_by_magnitude(synth.he_normal((40, 96), rng), 0.9), 127, 16, 0),
+            ((rng.standard_normal((5, 300)) * 10.0 ** rng.uniform(-8, 1, size=(5, 300))).astype(np.float32), 15, 8, 5)]
+    w = synth.he_normal((6, 32), rng)
+    w[0, :4] = [0.0, 1e-41, -2.0 ** -126, np.nextafter(np.float32(2.0 ** -126), np.float32(0))]
+    sets.append((w, 127, 8, 0))
+    for w, xmax, smax, eb in sets:
+        qo = orc.QWeights(w.reshape(w.shape[0], -1), exp_bits=eb, x_absmax=xmax, s_max=smax, prob_bits=kp)
+        qg = psb.Weights(torch.from_numpy(w).cuda(), exp_bits=eb, x_absmax=xmax, s_max=smax, prob_bits=kp)
+        assert (qg.n_zero, qg.n_flushed, qg.n_live) == (qo.n_zero, qo.n_flushed, qo.n_live)
+        assert (qg.e_top, qg.e_min) == (qo.e_top, qo.e_min)
+        packed = qg.export()
+        assert np.array_equal(packed, helpers.pack_from_oracle(qo))
+        live = packed != 0x7F800000
+        assert np.all((packed[live] & ((1 << (23 - kp)) - 1)) == 0)     # mantissas are on the grid
+
+
+def test_carry_moves_the_window_top(psb, orc):
+    """The largest weight rounds up to the next power of two: e_top follows it."""
+    import torch
+    w = np.full((2, 8), 0.01, np.float32)
+    w[1, 3] = np.nextafter(np.float32(2.0), np.float32(0))     # 1.9999999 -> 2.0, e 0 -> 1
+    qo = orc.QWeights(w, prob_bits=4)
+    qg = psb.Weights(torch.from_numpy(w).cuda(), prob_bits=4)
+    assert qo.e_top == 1 and qg.e_top == 1
+    assert np.array_equal(qg.export(), helpers.pack_from_oracle(qo))
+
+
+def test_prob_bits_error_codes(psb, orc):
+    import torch
+    w = torch.ones((2, 8), device="cuda")
+    for bad in (0, -1, 8, 16, 22, 24, 32):
+        with pytest.raises(psb.PsbError) as ei:
+            psb.Weights(w, prob_bits=bad)
+        assert ei.value.code == psb.ERR_VALUE
+    # the largest finite binary32 rounds past the largest exponent: refused by both sides
+    big = np.ones((1, 4), np.float32)
+    big[0, 1] = np.finfo(np.float32).max
+    with pytest.raises(orc.OracleError) as eo:
+        orc.QWeights(big, prob_bits=7)
+    assert eo.value.code == orc.ERR_VALUE
+    with pytest.raises(psb.PsbError) as ei:
+        psb.Weights(torch.from_numpy(big).cuda(), prob_bits=7)
+    assert ei.value.code == psb.ERR_VALUE
+    psb.Weights(torch.from_numpy(big).cuda(), prob_bits=23, s_max=1, x_absmax=1)      # exact p: fine
+
+
+def _cases():
+    rng = np.random.default_rng(600)
+    c = []
+    all3 = (1, 2, 3)
+    c.append(("linear_s16_k4", _layer(rng, 5, 37, 70, 1, 1, S=16, xkind="u4", std=0.05), 4, all3))
+    c.append(("linear_s5_k7", _layer(rng, 3, 130, 100, 1, 1, S=5, xkind="signed", std=0.05), 7, all3))
+    c.append(("conv_s16_k4", _layer(rng, 2, 20, 70, (9, 11), 3, pad=1, S=16), 4, all3))
+    c.append(("conv_s32_k3", _layer(rng, 1, 16, 64, 7, 3, pad=1, S=32), 3, all3))
+    c.append(("conv_s48_k7", _layer(rng, 1, 8, 32, 6, 3, pad=1, S=48, xkind="signed"), 7, all3))
+    c.append(("conv_s20_k1", _layer(rng, 1, 9, 66, 6, 3, pad=1, S=20), 1, all3))
+    c.append(("conv_s1_k2", _layer(rng, 1, 5, 7, 5, 3, pad=1, S=1), 2, all3))
+    c.append(("conv_s255_k5", _layer(rng, 1, 3, 8, 4, 3, pad=1, S=255, std=0.01), 5, all3))
+    c.append(("conv7x7_s2_k4", _layer(rng, 2, 3, 16, (23, 19), 7, stride=2, pad=3, S=16, xkind="signed"), 4, all3))
+    c.append(("pruned_pointwise_k4", _layer(rng, 2, 96, 40, 5, 1, S=16, prune=0.9), 4, all3))
+    c.append(("depthwise_k4", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), 4, (1, 3)))
+    c.append(("depthwise_s24_k6", _layer(rng, 1, 10, 10, 8, 3, stride=2, pad=1, groups=10, S=24), 6, (1, 3)))
+    return c
+
+
+@pytest.mark.parametrize("case", _cases(), ids=lambda c: c[0])
+def test_layer_bit_exact(psb, orc, case):
+    _, L, kp, mappings = case
+    qo = helpers.oracle_quantize(orc, L, prob_bits=kp)
+    ref, over, _ = helpers.oracle_layer(orc, L, qo)
+    assert over == 0
+    qg = helpers.gpu_quantize(psb, L, prob_bits=kp)
+    for m in mappings + (0,):
+        psb.set_mapping(m)
+        acc, _ = helpers.gpu_layer(psb, L, qg)
+        assert np.array_equal(acc, ref), f"mapping {m}"
+    psb.set_mapping(psb.MAPPING_AUTO)
+    # the 7-bit stream is a different stream from the 32-bit one
+    full, _ = helpers.gpu_layer(psb, L, helpers.gpu_quantize(psb, L))
+    if L.S > 1:
+        assert not np.array_equal(full, ref)
+
+
+@pytest.mark.parametrize("mapping", [1, 2, 3])
+def test_progressive_bit_exact_and_incremental(psb, orc, mapping):
+    rng = np.random.default_rng(700)
+    L = _layer(rng, 3, 12, 70, (9, 8), 3, pad=1, S=64, s_max=64)
+    oh, ow = L.out_hw
+    to = rng.choice([0, 1, 3, 15, 16, 17, 31, 32, 33, 48, 63, 64, 80], size=(3, oh, ow)).astype(np.uint8)
+    qo = helpers.oracle_quantize(orc, L, prob_bits=4)
+    ref, over, _ = helpers.oracle_layer(orc, L, qo, budget_to=to)
+    assert over == 0
+    psb.set_mapping(mapping)
+    qg = helpers.gpu_quantize(psb, L, prob_bits=4)
+    acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to)
+    assert np.array_equal(acc, ref)
+    for m in (16, 5, 21, 32):
+        first = np.minimum(to, m).astype(np.uint8)
+        a1, _ = helpers.gpu_layer(psb, L, qg, budget_to=first)
+        r1, _, _ = helpers.oracle_layer(orc, L, qo, budget_to=first)
+        assert np.array_equal(a1, r1)
+        a2, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, budget_from=first, acc_in=a1)
+        assert np.array_equal(a2, ref)
+    psb.set_mapping(psb.MAPPING_AUTO)
+
+
+def test_rescale_with_discretised_weights(psb, orc):
+    rng = np.random.default_rng(701)
+    L = _layer(rng, 2, 10, 64, 6, 3, pad=1, S=16)
+    qo = helpers.oracle_quantize(orc, L, prob_bits=4)
+    ref, _, _ = helpers.oracle_layer(orc, L, qo)
+    yref = orc.rescale(ref, qo.e_min, S=16, s_max=16)
+    acc, y = helpers.gpu_layer(psb, L, helpers.gpu_quantize(psb, L, prob_bits=4), want_y=True)
+    assert np.array_equal(acc, ref)
+    assert np.allclose(y, yref, rtol=1e-6, atol=0)
