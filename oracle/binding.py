@@ -63,6 +63,13 @@ def lib():
                                   C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32,
                                   C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.psbo_conv2d.restype = C.c_int
+        L.psbo_sample_filter.argtypes = [C.POINTER(Weights), C.c_int32, C.c_int32, C.c_uint64, C.c_uint32,
+                                         C.c_void_p, C.c_int32, C.c_void_p]
+        L.psbo_sample_filter.restype = C.c_int
+        L.psbo_conv2d_shared.argtypes = [C.POINTER(Weights), C.POINTER(WShape), C.c_void_p, C.POINTER(Geom),
+                                         C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32,
+                                         C.c_void_p, C.POINTER(C.c_int64)]
+        L.psbo_conv2d_shared.restype = C.c_int
         L.psbo_rescale.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.psbo_rescale.restype = C.c_int
@@ -206,6 +213,53 @@ def conv2d(q, wshape, x, stride=(1, 1), pad=(0, 0), S=None, s_max=None, budget_t
     if rc != OK:
         raise OracleError(rc)
     return acc, over.value, smac.value
+
+
+def sample_filter(q, S=None, seed=0, layer_id=0, sample_from=0, sample_to=None, u_table=None):
+    """W int64 [oc, K] = sigma 2^shift ((to-from) + count) for samples [from, to) of every weight."""
+    if sample_to is None:
+        sample_to = S
+    W = np.zeros((q.oc, q.K), dtype=np.int64)
+    table_S = 0
+    if u_table is not None:
+        u_table = np.ascontiguousarray(u_table, dtype=np.uint32)
+        table_S = u_table.size // (q.oc * q.K)
+        assert u_table.size == q.oc * q.K * table_S
+    rc = lib().psbo_sample_filter(C.byref(q._q), int(sample_from), int(sample_to), int(seed), int(layer_id),
+                                  _ptr(u_table), table_S, _ptr(W))
+    if rc != OK:
+        raise OracleError(rc)
+    return W
+
+
+def conv2d_shared(q, wshape, x, stride=(1, 1), pad=(0, 0), S=None, s_max=None, budget_to=None, budget_from=None,
+                  seed=0, layer_id=0, acc_in=None):
+    """Shared-filter layer: (acc int32 [n, oc, oh, ow], overflow count)."""
+    oc, cin, kh, kw, groups = wshape
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    n, c, h, w = x.shape
+    assert c == cin
+    ws = WShape(oc, cin, kh, kw, groups)
+    g = Geom(n, h, w, stride[0], stride[1], pad[0], pad[1])
+    oh, ow = out_hw(h, w, kh, kw, stride, pad)
+    if s_max is None:
+        s_max = q.s_max
+    if budget_to is not None:
+        budget_to = np.ascontiguousarray(budget_to, dtype=np.uint8)
+        assert budget_to.shape == (n, oh, ow)
+    if budget_from is not None:
+        budget_from = np.ascontiguousarray(budget_from, dtype=np.uint8)
+        assert budget_from.shape == (n, oh, ow) and acc_in is not None
+        acc = np.ascontiguousarray(acc_in, dtype=np.int32).copy().reshape(n, oc, oh, ow)
+    else:
+        acc = np.zeros((n, oc, oh, ow), dtype=np.int32)
+    over = C.c_int64(0)
+    rc = lib().psbo_conv2d_shared(C.byref(q._q), C.byref(ws), _ptr(x), C.byref(g), 0 if S is None else int(S),
+                                  int(s_max), _ptr(budget_to), _ptr(budget_from), int(seed), int(layer_id),
+                                  _ptr(acc), C.byref(over))
+    if rc != OK:
+        raise OracleError(rc)
+    return acc, over.value
 
 
 def rescale(acc, e_min, S=None, s_max=255, budget_to=None, mult=None, bias=None):

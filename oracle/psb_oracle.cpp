@@ -336,6 +336,135 @@ extern "C" int psbo_conv2d(const psbo_weights* q, const psbo_wshape* ws, const i
 }
 
 /* ---------------------------------------------------------------------------
+ * Shared-filter mode: Eq. (numbersystem:simulation),
+ *     w  ->  s * 2^e * ( B_{n,p} / n + 1 ),
+ * one binomial count per WEIGHT and per pass, after which the layer is an
+ * ordinary convolution with the sampled filter (Sect. 4.1 "Setup": the filter is
+ * sampled directly; suppl. "Efficient simulation of the forward pass", Eq.
+ * (binomial)).  In integers, in units of 2^e_min and before the division by n:
+ *     W[oc][k] = sigma * 2^shift * ( n + B ),   B = #{ i in [from,to) : U_i < p },
+ * n = to - from.  B is the sum of the same kind of Bernoulli draws the
+ * per-product mode uses, taken from the stream of "output element" oc:
+ * U_i = uniform(seed, layer_id, o := oc, k, i).  All output pixels of a channel
+ * therefore see the same filter, which is what the simulation does and what the
+ * per-product mode does not.
+ * ------------------------------------------------------------------------- */
+static int32_t filter_count(const psbo_weights* q, int64_t wi, uint32_t oc, uint32_t k, int32_t from, int32_t to,
+                            uint64_t seed, uint32_t layer_id, const uint32_t* u_row)
+{
+    int32_t B = 0;
+    for (int32_t s = from; s < to; ++s) {
+        double U;
+        if (q->prob_bits == 23) {
+            const uint32_t u = u_row ? u_row[s] : psbo_uniform(seed, layer_id, oc, k, (uint32_t)s);
+            U = (double)u / 4294967296.0;
+        } else {
+            const uint32_t u7 = u_row ? u_row[s] : psbo_uniform7(seed, layer_id, oc, k, (uint32_t)s);
+            U = (double)u7 / 128.0;
+        }
+        if (U < q->p[wi]) B++;
+    }
+    return B;
+}
+
+extern "C" int psbo_sample_filter(const psbo_weights* q, int32_t from, int32_t to, uint64_t seed,
+                                  uint32_t layer_id, const uint32_t* u_table, int32_t table_S, int64_t* W)
+{
+    if (!q || !W || from < 0 || to < from) return PSBO_ERR_ARG;
+    if (u_table && to > table_S) return PSBO_ERR_ARG;
+    for (int32_t oc = 0; oc < q->oc; ++oc)
+        for (int32_t k = 0; k < q->K; ++k) {
+            const int64_t wi = (int64_t)oc * q->K + k;
+            if (q->sign[wi] == 0) { W[wi] = 0; continue; }
+            const uint32_t* u_row = u_table ? u_table + wi * table_S : nullptr;
+            const int32_t B = filter_count(q, wi, (uint32_t)oc, (uint32_t)k, from, to, seed, layer_id, u_row);
+            W[wi] = (int64_t)q->sign[wi] * ((int64_t)1 << q->shift[wi]) * (int64_t)((to - from) + B);
+        }
+    return PSBO_OK;
+}
+
+extern "C" int psbo_conv2d_shared(const psbo_weights* q, const psbo_wshape* ws, const int8_t* x,
+                                  const psbo_geom* g, int32_t S_uniform, int32_t s_max,
+                                  const uint8_t* budget_to, const uint8_t* budget_from,
+                                  uint64_t seed, uint32_t layer_id, int32_t* acc, int64_t* overflow)
+{
+    if (!q || !ws || !x || !g || !acc) return PSBO_ERR_ARG;
+    const int32_t OC = ws->oc, C = ws->cin, KH = ws->kh, KW = ws->kw, G = ws->groups;
+    if (OC <= 0 || C <= 0 || KH <= 0 || KW <= 0 || G <= 0 || C % G || OC % G) return PSBO_ERR_ARG;
+    const int32_t Cg = C / G, OCg = OC / G, K = Cg * KH * KW;
+    if (q->oc != OC || q->K != K) return PSBO_ERR_ARG;
+    const int32_t N = g->n, H = g->h, Wd = g->w;
+    if (N <= 0 || H <= 0 || Wd <= 0 || g->stride_h <= 0 || g->stride_w <= 0 || g->pad_h < 0 || g->pad_w < 0)
+        return PSBO_ERR_ARG;
+    if (H + 2 * g->pad_h < KH || Wd + 2 * g->pad_w < KW) return PSBO_ERR_ARG;
+    const int32_t OH = (H + 2 * g->pad_h - KH) / g->stride_h + 1;
+    const int32_t OW = (Wd + 2 * g->pad_w - KW) / g->stride_w + 1;
+    if (!budget_to && S_uniform <= 0) return PSBO_ERR_ARG;
+    if (budget_from && !budget_to) return PSBO_ERR_ARG;
+    if (s_max <= 0 || s_max > 255) return PSBO_ERR_ARG;
+
+    /* prefix counts: cnt[wi][s] = number of ones among samples 0 .. s-1 of weight wi */
+    const int64_t nw = (int64_t)OC * K;
+    const int32_t smax_used = budget_to ? s_max : (S_uniform < s_max ? S_uniform : s_max);
+    const int64_t row = (int64_t)smax_used + 1;
+    int16_t* cnt = (int16_t*)std::calloc((size_t)(nw * row), sizeof(int16_t));
+    if (!cnt) return PSBO_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t wi = 0; wi < nw; ++wi) {
+        if (q->sign[wi] == 0) continue;
+        const uint32_t oc = (uint32_t)(wi / K), k = (uint32_t)(wi % K);
+        for (int32_t s = 0; s < smax_used; ++s)
+            cnt[wi * row + s + 1] = (int16_t)(cnt[wi * row + s] +
+                                              filter_count(q, wi, oc, k, s, s + 1, seed, layer_id, nullptr));
+    }
+
+    const int64_t total = (int64_t)N * OC * OH * OW;
+    int64_t n_over = 0;
+#pragma omp parallel for reduction(+ : n_over) schedule(dynamic, 64)
+    for (int64_t flat = 0; flat < total; ++flat) {
+        const int32_t ox = (int32_t)(flat % OW);
+        const int32_t oy = (int32_t)((flat / OW) % OH);
+        const int32_t oc = (int32_t)((flat / ((int64_t)OW * OH)) % OC);
+        const int32_t n  = (int32_t)(flat / ((int64_t)OW * OH * OC));
+        const int64_t pix = ((int64_t)n * OH + oy) * OW + ox;
+        int32_t to = budget_to ? budget_to[pix] : S_uniform;
+        if (to > s_max) to = s_max;
+        int32_t from = budget_from ? budget_from[pix] : 0;
+        if (from > to) from = to;
+
+        const int32_t grp = oc / OCg;
+        int64_t exact = 0;
+        uint32_t wrapped = 0;
+        for (int32_t ci = 0; ci < Cg; ++ci)
+            for (int32_t kh = 0; kh < KH; ++kh)
+                for (int32_t kw = 0; kw < KW; ++kw) {
+                    const int32_t k = (ci * KH + kh) * KW + kw;
+                    const int64_t wi = (int64_t)oc * K + k;
+                    if (q->sign[wi] == 0) continue;
+                    const int32_t iy = oy * g->stride_h - g->pad_h + kh;
+                    const int32_t ix = ox * g->stride_w - g->pad_w + kw;
+                    if (iy < 0 || iy >= H || ix < 0 || ix >= Wd) continue;
+                    const int32_t c = grp * Cg + ci;
+                    const int64_t xv = x[(((int64_t)n * C + c) * H + iy) * Wd + ix];
+                    /* the filter value of this pixel's sample range */
+                    const int64_t B = cnt[wi * row + to] - cnt[wi * row + from];
+                    const int64_t Wv = (int64_t)q->sign[wi] * ((int64_t)1 << q->shift[wi]) * ((int64_t)(to - from) + B);
+                    exact += xv * Wv;
+                    wrapped += (uint32_t)(xv * Wv);
+                }
+        if (budget_from) {
+            exact += acc[flat];
+            wrapped += (uint32_t)acc[flat];
+        }
+        if (exact < INT32_MIN || exact > INT32_MAX) n_over++;
+        acc[flat] = (int32_t)wrapped;
+    }
+    std::free(cnt);
+    if (overflow) *overflow = n_over;
+    return PSBO_OK;
+}
+
+/* ---------------------------------------------------------------------------
  * Normalisation by the number of samples (the ">> n" of the shift form in
  * Sect. 3.1, generalised to any sample count by a division in binary32) and
  * the per-channel affine map that stands for folded batch normalisation

@@ -117,6 +117,24 @@ int psbo_conv2d(const psbo_weights* q, const psbo_wshape* ws, const int8_t* x,
                 const int64_t* points, int64_t n_points,
                 int32_t* acc, int64_t* overflow, int64_t* n_smac);
 
+/* Shared-filter mode, Eq. (numbersystem:simulation): one binomial count per weight
+ * and pass.  W[oc][k] = sigma * 2^shift * ((to-from) + B), B = number of samples
+ * i in [from,to) of the stream of "output element" oc (counter (oc, k, i div 4 or
+ * i div 16, layer_id)) that fall below p; 0 for weights that are not live.
+ * u_table: optional replacement of the generator, u(oc,k,i) = u_table[(oc*K+k)*table_S + i].  */
+int psbo_sample_filter(const psbo_weights* q, int32_t from, int32_t to, uint64_t seed,
+                       uint32_t layer_id, const uint32_t* u_table, int32_t table_S, int64_t* W);
+
+/* The layer with a filter sampled once per pass (Sect. 4.1 "Setup"; suppl.
+ * "Efficient simulation of the forward pass"): acc[o] = sum_k x[o,k] * W_[from,to)[oc][k],
+ * where a pixel with sample range [from,to) uses the filter built from exactly
+ * those samples, so that budgets nest the way Sect. 4.5 needs (the first samples
+ * are reused).  Arguments as psbo_conv2d.                                        */
+int psbo_conv2d_shared(const psbo_weights* q, const psbo_wshape* ws, const int8_t* x,
+                       const psbo_geom* g, int32_t S_uniform, int32_t s_max,
+                       const uint8_t* budget_to, const uint8_t* budget_from,
+                       uint64_t seed, uint32_t layer_id, int32_t* acc, int64_t* overflow);
+
 /* Final rescale: y = fl( fl( float(acc) * mult[oc] ) * inv_S ) + bias[oc],
  * every fl one binary32 round-to-nearest-even operation, no fused
  * multiply-add.  inv_S = 1/to' (0 when to' = 0).  mult NULL => 2^e_min;
