@@ -182,6 +182,43 @@ int psb_conv2d_progressive(const psb_weights_t* q, const int8_t* x_dev, const ps
                            uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev,
                            const float* bias_dev, void* hip_stream);
 
+/*
+ * Shared-filter mode [Eq. "numbersystem:simulation": w -> s 2^e (B_{n,p}/n + 1), one binomial count per
+ * WEIGHT and pass; Sect. 4.1 "Setup" and suppl. "Efficient simulation of the forward pass": the filter is
+ * sampled directly, then the layer is an ordinary convolution].  This is the granularity every accuracy
+ * figure of the paper was measured with; it is a different (cheaper, spatially correlated) estimator from
+ * the per-product mode of the entry points above and gives different bits.  In integers:
+ *     W[oc][k] = sigma * 2^shift * ((to - from) + B),  B = #{ i in [from,to) : uniform(oc, k, i) decides 1 },
+ *     acc[o]   = sum_k x[o,k] * W[oc][k]               (exact: the overflow rule of the encoding covers it)
+ * where uniform(oc, k, i) is the stream the per-product mode gives to output element o := oc.
+ * The contraction runs on the int8 matrix cores for groups = 1 and on a direct kernel otherwise.
+ *
+ * psb_sample_filter writes W for samples [sample_from, sample_to) to w_dev (device, int32 [OC][K], 0 for
+ * weights that are not live).  Errors: NULL, VALUE (empty or negative range, sample_to > s_max), DEVICE.
+ *
+ * psb_linear_shared / psb_conv2d_shared / psb_conv2d_progressive_shared take the arguments of their
+ * per-product namesakes and return acc and y in the same units (y = acc * 2^e_min / n_samples [+ bias]).
+ * With a budget map, a pixel with range [from', to') uses the filter built from exactly those samples, so
+ * a refinement call adds what the first call left out [Sect. 4.5].
+ * Differences from the per-product calls: the first shared-filter call on a handle, and any call with a
+ * larger input than before, allocates device memory owned by the handle (the sampled filter, its int8
+ * digit planes, a channels-last copy of the activations); psb_conv2d_progressive_shared synchronises the
+ * stream once (it reads back which budget values occur).  Additional error: TOO_LARGE when
+ * kh*kw*(cin rounded up to 32) >= 2^17 (groups = 1), ALLOC.
+ */
+int psb_sample_filter(const psb_weights_t* q, int32_t sample_from, int32_t sample_to, uint64_t seed,
+                      uint32_t layer_id, int32_t* w_dev, void* hip_stream);
+int psb_linear_shared(const psb_weights_t* q, const int8_t* x_dev, int32_t B, int32_t S, uint64_t seed,
+                      uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev,
+                      const float* bias_dev, void* hip_stream);
+int psb_conv2d_shared(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S,
+                      uint64_t seed, uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev,
+                      const float* bias_dev, void* hip_stream);
+int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom,
+                                  const uint8_t* budget_to_dev, const uint8_t* budget_from_dev, uint64_t seed,
+                                  uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev,
+                                  const float* bias_dev, void* hip_stream);
+
 /* The hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
 int psb_last_device_error(void);
 
@@ -190,6 +227,8 @@ int psb_last_device_error(void);
  * channel per lane (groups = 1 only; made for dense layers), 3 = compacted product list per
  * (channel, 256 pixels) (any layer; made for grouped, depthwise and pruned layers).
  * Results are bit-identical for every mapping; the switch exists for tests and benchmarks.
+ * Shared-filter calls: 1 selects their direct kernel for every layer, any other value leaves the
+ * choice (matrix cores for groups = 1) to the library.
  * Returns the previous value. */
 int psb_set_mapping(int mapping);
 

@@ -13,6 +13,16 @@
 #include "psb_kernels.hip.h"
 #include "psb_kernels_oc.hip.h"
 #include "psb_kernels_list.hip.h"
+#include "psb_kernels_shared.hip.h"
+
+// Device memory of the shared-filter mode; allocated on first use, grown on demand, owned by the handle.
+struct shared_workspace {
+    int32_t* w32_dev = nullptr;      // [OC][K] sampled integer filter
+    int8_t* planes_dev = nullptr;    // digit planes in matrix-core operand order
+    int8_t* xt_dev = nullptr;        // channels-last copy of the activations
+    size_t xt_bytes = 0;
+    uint32_t* present_dev = nullptr; // 256 flags: budget values that occur
+};
 
 struct psb_weights {
     psb_wshape shape;
@@ -26,6 +36,7 @@ struct psb_weights {
     uint32_t* live_idx_dev;  // [OC][K]: live taps of each channel first, any order
     uint32_t* live_cnt_dev;  // [OC]
     uint32_t* sched_dev;     // ticket counter and finish counter of the persistent kernel (both 0 between calls)
+    shared_workspace* ws;    // shared-filter mode
 };
 
 namespace {
@@ -184,6 +195,146 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
     return PSB_OK;
 }
 
+// ---- shared-filter mode -----------------------------------------------------------------------------
+
+int sample_filter_launch(const psb_weights* q, int from, int to, uint64_t seed, uint32_t layer_id, int32_t* w32,
+                         int8_t* planes, int CB, int n_ksteps, hipStream_t stream)
+{
+    const int64_t nw = (int64_t)q->shape.oc * q->K;
+    hipLaunchKernelGGL(psb::k_sample_filter, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, stream, q->packed_dev,
+                       q->shape.oc, q->K, q->shape.kh * q->shape.kw, CB, n_ksteps, q->prob_bits, from, to,
+                       (uint32_t)(seed & 0xFFFFFFFFull), (uint32_t)(seed >> 32), layer_id, w32, planes);
+    PSB_HIP_TRY(hipGetLastError());
+    return PSB_OK;
+}
+
+int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, int32_t S, const uint8_t* budget_to,
+                  const uint8_t* budget_from, uint64_t seed, uint32_t layer_id, int32_t* acc, float* y,
+                  const float* mult, const float* bias, hipStream_t stream)
+{
+    int32_t OH = 0, OW = 0;
+    int rc = check_geom(&q->shape, g, &OH, &OW);
+    if (rc != PSB_OK) return rc;
+    int dev = 0;
+    PSB_HIP_TRY(hipGetDevice(&dev));
+    if (dev != q->device) return PSB_ERR_DEVICE;
+
+    const bool mfma = q->shape.groups == 1 && g_mapping != 1;
+    const int C_pad = (q->shape.cin + 31) / 32 * 32;
+    const int CB = C_pad / 32;
+    const int n_ksteps = q->shape.kh * q->shape.kw * CB;
+    const int n_ocb = (q->shape.oc + 31) / 32;
+    // each digit plane is summed in int32: 128 * 128 * (padded reduction length) must stay below 2^31
+    if (mfma && (int64_t)n_ksteps * 32 >= (1ll << 17)) return PSB_ERR_TOO_LARGE;
+
+    shared_workspace* ws = q->ws;
+    const int64_t nw = (int64_t)q->shape.oc * q->K;
+    if (!ws->w32_dev && hipMalloc(&ws->w32_dev, (size_t)nw * sizeof(int32_t)) != hipSuccess) return PSB_ERR_ALLOC;
+    if (!ws->present_dev && hipMalloc(&ws->present_dev, 256 * sizeof(uint32_t)) != hipSuccess) return PSB_ERR_ALLOC;
+    if (mfma && !ws->planes_dev) {
+        const size_t bytes = (size_t)n_ocb * n_ksteps * psb::kMaxPlanes * psb::kPlaneStride;
+        if (hipMalloc(&ws->planes_dev, bytes) != hipSuccess) return PSB_ERR_ALLOC;
+        // positions of padding channels are never written again and must read as zero
+        PSB_HIP_TRY(hipMemsetAsync(ws->planes_dev, 0, bytes, stream));
+    }
+    const size_t xt_need = (size_t)g->n * g->h * g->w * C_pad;
+    if (mfma && ws->xt_bytes < xt_need) {
+        if (ws->xt_dev) {
+            PSB_HIP_TRY(hipStreamSynchronize(stream));     // an earlier call may still read the old buffer
+            (void)hipFree(ws->xt_dev);
+            ws->xt_dev = nullptr;
+            ws->xt_bytes = 0;
+        }
+        if (hipMalloc(&ws->xt_dev, xt_need) != hipSuccess) return PSB_ERR_ALLOC;
+        ws->xt_bytes = xt_need;
+    }
+
+    psb::SharedParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.x = x; p.xt = ws->xt_dev; p.planes = ws->planes_dev; p.w32 = ws->w32_dev;
+    p.budget_to = budget_to; p.budget_from = budget_from;
+    p.acc = acc; p.y = y; p.mult = mult; p.bias = bias;
+    p.N = g->n; p.C = q->shape.cin; p.H = g->h; p.W = g->w;
+    p.OC = q->shape.oc; p.OH = OH; p.OW = OW; p.KH = q->shape.kh; p.KW = q->shape.kw;
+    p.Cg = q->shape.cin / q->shape.groups; p.OCg = q->shape.oc / q->shape.groups;
+    p.K = q->K; p.C_pad = C_pad; p.n_ksteps = n_ksteps;
+    p.stride_h = g->stride_h; p.stride_w = g->stride_w; p.pad_h = g->pad_h; p.pad_w = g->pad_w;
+    p.S = S; p.s_max = q->s_max;
+    p.default_mult = std::ldexp(1.0f, q->info.e_min);
+    const int max_shift = q->info.e_top - q->info.e_min;
+    const int64_t npix = (int64_t)g->n * OH * OW;
+    if (!mfma && p.OC > 65535) return PSB_ERR_TOO_LARGE;
+
+    if (mfma) {
+        const dim3 grid((unsigned)((g->w + 63) / 64), (unsigned)(g->n * g->h), (unsigned)CB);
+        if ((int64_t)g->n * g->h > 2147483647ll || CB > 65535) return PSB_ERR_TOO_LARGE;
+        hipLaunchKernelGGL(psb::k_to_channels_last, grid, dim3(256), 0, stream, x, p.C, p.H, p.W, C_pad, ws->xt_dev);
+        PSB_HIP_TRY(hipGetLastError());
+    }
+
+    auto contract = [&](int n_samples) -> int {
+        int slot = 0;
+        const bool timed = profile_begin(stream, &slot);
+        if (mfma) {
+            psb::launch_conv_shared_mfma(p, psb::planes_needed(max_shift, n_samples), stream);
+        } else {
+            const dim3 grid((unsigned)((npix + 255) / 256), (unsigned)p.OC);
+            hipLaunchKernelGGL(psb::k_conv_shared_direct, grid, dim3(256), 0, stream, p);
+        }
+        if (timed) profile_end(stream, slot);
+        PSB_HIP_TRY(hipGetLastError());
+        return PSB_OK;
+    };
+
+    if (!budget_to) {
+        rc = sample_filter_launch(q, 0, S, seed, layer_id, ws->w32_dev, mfma ? ws->planes_dev : nullptr, CB, n_ksteps,
+                                  stream);
+        if (rc != PSB_OK) return rc;
+        return contract(S);
+    }
+
+    // per-pixel budgets: the distinct clamped budget values cut the sample axis into segments
+    uint32_t present[256];
+    PSB_HIP_TRY(hipMemsetAsync(ws->present_dev, 0, sizeof(present), stream));
+    {
+        const int blocks = (int)std::min<int64_t>((npix + 255) / 256, 1024);
+        hipLaunchKernelGGL(psb::k_budget_levels, dim3(blocks), dim3(256), 0, stream, budget_to, budget_from, npix,
+                           q->s_max, ws->present_dev);
+        PSB_HIP_TRY(hipGetLastError());
+    }
+    PSB_HIP_TRY(hipMemcpyAsync(present, ws->present_dev, sizeof(present), hipMemcpyDeviceToHost, stream));
+    PSB_HIP_TRY(hipStreamSynchronize(stream));
+    const int64_t total = npix * p.OC;
+    if (!budget_from) {
+        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
+        hipLaunchKernelGGL(psb::k_fill_zero, dim3(blocks), dim3(256), 0, stream, acc, total);
+        PSB_HIP_TRY(hipGetLastError());
+    }
+    p.masked = 1;
+    int prev = -1;
+    for (int v = 0; v < 256; ++v) {
+        if (!present[v]) continue;
+        if (prev >= 0) {
+            p.seg_from = prev; p.seg_to = v;
+            rc = sample_filter_launch(q, prev, v, seed, layer_id, ws->w32_dev, mfma ? ws->planes_dev : nullptr, CB,
+                                      n_ksteps, stream);
+            if (rc != PSB_OK) return rc;
+            rc = contract(v - prev);
+            if (rc != PSB_OK) return rc;
+        }
+        prev = v;
+    }
+    if (y) {
+        psb::LayerParams lp;
+        fill_geometry(q, g, OH, OW, lp);
+        lp.acc = acc; lp.y = y; lp.mult = mult; lp.bias = bias; lp.budget_to = budget_to; lp.S = S;
+        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
+        hipLaunchKernelGGL(psb::k_rescale, dim3(blocks), dim3(256), 0, stream, lp);
+        PSB_HIP_TRY(hipGetLastError());
+    }
+    return PSB_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -259,6 +410,8 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     if (!q) return PSB_ERR_ALLOC;
     std::memset(q, 0, sizeof(*q));
     q->shape = *shape; q->K = (int32_t)K; q->oc_pad = oc_pad;
+    q->ws = new (std::nothrow) shared_workspace;
+    if (!q->ws) { delete q; return PSB_ERR_ALLOC; }
     q->prob_bits = prob_bits; q->exp_bits = exp_bits; q->x_absmax = x_absmax; q->s_max = s_max;
 
     // scratch: [0]=max field, [1]=non-finite flag, then 3 64-bit counters, then the histogram
@@ -366,6 +519,13 @@ void psb_weights_destroy(psb_weights_t* q)
     if (q->sched_dev) (void)hipFree(q->sched_dev);
     if (q->live_idx_dev) (void)hipFree(q->live_idx_dev);
     if (q->live_cnt_dev) (void)hipFree(q->live_cnt_dev);
+    if (q->ws) {
+        if (q->ws->w32_dev) (void)hipFree(q->ws->w32_dev);
+        if (q->ws->planes_dev) (void)hipFree(q->ws->planes_dev);
+        if (q->ws->xt_dev) (void)hipFree(q->ws->xt_dev);
+        if (q->ws->present_dev) (void)hipFree(q->ws->present_dev);
+        delete q->ws;
+    }
     delete q;
 }
 
@@ -399,6 +559,48 @@ int psb_conv2d_progressive(const psb_weights_t* q, const int8_t* x_dev, const ps
     if (!q || !x_dev || !geom || !budget_to_dev || !acc_dev) return PSB_ERR_NULL;
     return launch_layer(q, x_dev, geom, 0, budget_to_dev, budget_from_dev, seed, layer_id, acc_dev, y_dev, mult_dev,
                         bias_dev, (hipStream_t)hip_stream);
+}
+
+int psb_sample_filter(const psb_weights_t* q, int32_t sample_from, int32_t sample_to, uint64_t seed,
+                      uint32_t layer_id, int32_t* w_dev, void* hip_stream)
+{
+    if (!q || !w_dev) return PSB_ERR_NULL;
+    if (sample_from < 0 || sample_to <= sample_from || sample_to > q->s_max) return PSB_ERR_VALUE;
+    return sample_filter_launch(q, sample_from, sample_to, seed, layer_id, w_dev, nullptr, 1, 1,
+                                (hipStream_t)hip_stream);
+}
+
+int psb_linear_shared(const psb_weights_t* q, const int8_t* x_dev, int32_t B, int32_t S, uint64_t seed,
+                      uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev, const float* bias_dev,
+                      void* hip_stream)
+{
+    if (!q || !x_dev || !acc_dev) return PSB_ERR_NULL;
+    if (q->shape.kh != 1 || q->shape.kw != 1 || q->shape.groups != 1) return PSB_ERR_SHAPE;
+    if (B <= 0) return PSB_ERR_SHAPE;
+    if (S <= 0 || S > q->s_max) return PSB_ERR_VALUE;
+    psb_conv_geom g = {B, 1, 1, 1, 1, 0, 0};
+    return launch_shared(q, x_dev, &g, S, nullptr, nullptr, seed, layer_id, acc_dev, y_dev, mult_dev, bias_dev,
+                         (hipStream_t)hip_stream);
+}
+
+int psb_conv2d_shared(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S, uint64_t seed,
+                      uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev, const float* bias_dev,
+                      void* hip_stream)
+{
+    if (!q || !x_dev || !geom || !acc_dev) return PSB_ERR_NULL;
+    if (S <= 0 || S > q->s_max) return PSB_ERR_VALUE;
+    return launch_shared(q, x_dev, geom, S, nullptr, nullptr, seed, layer_id, acc_dev, y_dev, mult_dev, bias_dev,
+                         (hipStream_t)hip_stream);
+}
+
+int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom,
+                                  const uint8_t* budget_to_dev, const uint8_t* budget_from_dev, uint64_t seed,
+                                  uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev,
+                                  const float* bias_dev, void* hip_stream)
+{
+    if (!q || !x_dev || !geom || !budget_to_dev || !acc_dev) return PSB_ERR_NULL;
+    return launch_shared(q, x_dev, geom, 0, budget_to_dev, budget_from_dev, seed, layer_id, acc_dev, y_dev, mult_dev,
+                         bias_dev, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

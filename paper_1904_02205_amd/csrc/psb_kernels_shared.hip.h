@@ -1,0 +1,298 @@
+// Shared-filter mode (Eq. "numbersystem:simulation"; Sect. 4.1 "Setup"; suppl. "Efficient simulation of the
+// forward pass"): one binomial count per WEIGHT and per pass, then an ordinary integer convolution with the
+// sampled filter
+//     W[oc][k] = sigma * 2^shift * ((to - from) + B),   B = #{ i in [from,to) : u(oc, k, i) < threshold }.
+// The random stream of weight (oc, k) is the per-product stream of "output element" oc.
+//
+// With a filter shared by all pixels the layer IS a dense contraction, so it runs on the int8 matrix cores:
+//   * W (up to 31 bits + sign) is split into up to four balanced base-256 digits d_b in [-128,127],
+//     W = sum_b d_b 256^b (mod 2^32); each digit plane is contracted separately with
+//     v_mfma_i32_32x32x32_i8 and the planes are recombined with shifts in the epilogue.  All of it is exact
+//     modulo 2^32, and the true result fits int32 by the overflow rule of the weight encoding.
+//   * the activations are first copied to a channels-last layout [N][H][W][C padded to 32], so that the 16
+//     bytes of reduction index a lane feeds to the matrix core are 16 consecutive bytes in memory; the
+//     reduction index is ordered (kh, kw, channel), which no result depends on;
+//   * the digit planes are written directly in the operand order of the instruction
+//     [block of 32 channels][k-step][plane][lane][16 bytes]: an operand is one coalesced 1 KB read.
+// One wave computes 32 output channels x 64 output pixels; the output is stored with consecutive lanes on
+// consecutive pixels (coalesced in NCHW).
+//
+// Per-pixel budgets: the distinct budget values cut the sample axis into segments; each segment is one
+// filter (built from exactly its samples, so budgets nest) and one masked, accumulating contraction over
+// the pixels whose range contains the segment.
+//
+// Grouped and depthwise layers have no contraction worth a matrix core (a depthwise channel has 9 taps):
+// they use a direct kernel on the int32 filter.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "psb_kernels.hip.h"
+
+namespace psb {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kPlaneStride = 64 * 16;   // bytes of one operand (64 lanes x 16 bytes)
+constexpr int kMaxPlanes = 4;
+
+struct SharedParams {
+    const int8_t* x;           // [N][C][H][W]                      (direct kernel)
+    const int8_t* xt;          // [N][H][W][C_pad], channels last   (matrix-core kernel)
+    const int8_t* planes;      // [OC/32][n_ksteps][4][64][16]
+    const int32_t* w32;        // [OC][K]
+    const uint8_t* budget_to;  // [N][OH][OW] or null
+    const uint8_t* budget_from;
+    int32_t* acc;
+    float* y;
+    const float* mult;
+    const float* bias;
+    int N, C, H, W, OC, OH, OW, KH, KW, Cg, OCg, K, C_pad, n_ksteps;
+    int stride_h, stride_w, pad_h, pad_w;
+    int S, s_max;
+    int masked;                // 0: every pixel, acc overwritten, epilogue fused.  1: only pixels whose sample
+    int seg_from, seg_to;      //    range contains [seg_from, seg_to); acc accumulated
+    float default_mult;
+};
+
+// One thread per weight: count, filter value, digit planes.
+__global__ void __launch_bounds__(256) k_sample_filter(const uint32_t* __restrict__ packed, int OC, int K, int KHW,
+                                                       int CB, int n_ksteps, int prob_bits, int from, int to,
+                                                       uint32_t key0, uint32_t key1, uint32_t layer_id,
+                                                       int32_t* __restrict__ w32, int8_t* __restrict__ planes)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)OC * K) return;
+    const int oc = (int)(i / K);
+    const int k = (int)(i - (int64_t)oc * K);
+    const uint32_t word = packed[i];
+    int32_t wv = 0;
+    if ((word & 0x7F800000u) != kDeadWord) {
+        const uint32_t thr = threshold_of(word & 0x7FFFFFu, prob_bits);
+        const uint32_t cnt = prob_bits < 23 ? count_below7((uint32_t)oc, (uint32_t)k, layer_id, key0, key1, thr, from, to)
+                                            : count_below((uint32_t)oc, (uint32_t)k, layer_id, key0, key1, thr, from, to);
+        const uint32_t mag = ((uint32_t)(to - from) + cnt) << ((word >> 23) & 0xFFu);   // < 2^31 by the overflow rule
+        wv = (word & 0x80000000u) ? -(int32_t)mag : (int32_t)mag;
+    }
+    w32[i] = wv;
+    if (planes) {
+        const int c = k / KHW;
+        const int r = k - c * KHW;
+        const int kstep = r * CB + (c >> 5);
+        const int cl = c & 31;
+        const int lane = (oc & 31) + 32 * (cl >> 4);
+        int8_t* dst = planes + ((((int64_t)(oc >> 5) * n_ksteps + kstep) * kMaxPlanes) * 64 + lane) * 16 + (cl & 15);
+        int64_t v = wv;
+#pragma unroll
+        for (int b = 0; b < kMaxPlanes; ++b) {
+            const int8_t d = (int8_t)(v & 0xFF);     // balanced digit; the last one wraps, which is exact modulo 2^32
+            dst[b * kPlaneStride] = d;
+            v = (v - d) >> 8;
+        }
+    }
+}
+
+// x [N][C][H][W] -> xt [N][H][W][C_pad] (zeros in the padding channels).  One workgroup per
+// (64 columns, row, 32 channels) tile, transposed through LDS.
+__global__ void __launch_bounds__(256) k_to_channels_last(const int8_t* __restrict__ x, int C, int H, int W, int C_pad,
+                                                          int8_t* __restrict__ xt)
+{
+    __shared__ int8_t tile[32][64 + 4];
+    const int ix0 = blockIdx.x * 64;
+    const int64_t row = blockIdx.y;            // n * H + iy
+    const int n = (int)(row / H), iy = (int)(row - (int64_t)n * H);
+    const int c0 = blockIdx.z * 32;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int idx = r * 256 + threadIdx.x;
+        const int c = idx >> 6, dx = idx & 63;
+        int8_t v = 0;
+        if (c0 + c < C && ix0 + dx < W) v = x[(((int64_t)n * C + c0 + c) * H + iy) * W + ix0 + dx];
+        tile[c][dx] = v;
+    }
+    __syncthreads();
+    const int dx = threadIdx.x >> 2, part = threadIdx.x & 3;
+    if (ix0 + dx < W) {
+        uint32_t lo = 0, hi = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            lo |= (uint32_t)(uint8_t)tile[part * 8 + j][dx] << (8 * j);
+            hi |= (uint32_t)(uint8_t)tile[part * 8 + 4 + j][dx] << (8 * j);
+        }
+        uint2* dst = reinterpret_cast<uint2*>(xt + ((row * W + ix0 + dx) * (int64_t)C_pad + c0 + part * 8));
+        *dst = make_uint2(lo, hi);
+    }
+}
+
+// present[v] = 1 for every clamped budget value v that occurs in the maps
+__global__ void __launch_bounds__(256) k_budget_levels(const uint8_t* __restrict__ budget_to,
+                                                       const uint8_t* __restrict__ budget_from, int64_t npix, int s_max,
+                                                       uint32_t* __restrict__ present)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < npix; i += (int64_t)gridDim.x * blockDim.x) {
+        const int to = min((int)budget_to[i], s_max);
+        const int from = budget_from ? min((int)budget_from[i], to) : 0;
+        present[to] = 1u;
+        present[from] = 1u;
+    }
+}
+
+// sample range of a pixel and whether it takes part in this launch
+__device__ __forceinline__ bool shared_pixel_range(const SharedParams& p, int64_t pix, int& to)
+{
+    to = p.budget_to ? (int)p.budget_to[pix] : p.S;
+    to = min(to, p.s_max);
+    if (!p.masked) return true;
+    int from = p.budget_from ? (int)p.budget_from[pix] : 0;
+    from = min(from, to);
+    return from <= p.seg_from && p.seg_to <= to;
+}
+
+template <int P>
+__global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int col = lane & 31, g = lane >> 5;
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int64_t pix0 = ((int64_t)blockIdx.x * 4 + wave) * 64;
+    if (pix0 >= npix) return;                       // wave-uniform
+    const int ocb = blockIdx.y;
+
+    bool live[2];
+    int n_[2], oy_[2], ox_[2], to_[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int64_t pix = pix0 + 32 * h + col;
+        const bool valid = pix < npix;
+        const int64_t pc = valid ? pix : npix - 1;
+        ox_[h] = (int)(pc % p.OW);
+        oy_[h] = (int)((pc / p.OW) % p.OH);
+        n_[h] = (int)(pc / ((int64_t)p.OW * p.OH));
+        live[h] = shared_pixel_range(p, pc, to_[h]) && valid;
+    }
+    if (__ballot(live[0] || live[1]) == 0ull) return;   // no pixel of this tile takes part
+
+    v16i acc[2][P];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int b = 0; b < P; ++b)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
+
+    const int CB = p.C_pad >> 5;
+    const v4i* wp = reinterpret_cast<const v4i*>(p.planes) + ((int64_t)ocb * p.n_ksteps * kMaxPlanes) * 64 + lane;
+    const v4i zero = {0, 0, 0, 0};
+    for (int kh = 0; kh < p.KH; ++kh) {
+        for (int kw = 0; kw < p.KW; ++kw) {
+            bool ok[2];
+            const int8_t* src[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int iy = oy_[h] * p.stride_h - p.pad_h + kh;
+                const int ix = ox_[h] * p.stride_w - p.pad_w + kw;
+                ok[h] = live[h] && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+                const int64_t at = ok[h] ? (((int64_t)n_[h] * p.H + iy) * p.W + ix) : 0;
+                src[h] = p.xt + at * p.C_pad + 16 * g;
+            }
+            if (__ballot(ok[0] || ok[1]) == 0ull) {          // the tap is padding for the whole tile
+                wp += (int64_t)CB * kMaxPlanes * 64;
+                continue;
+            }
+            for (int cb = 0; cb < CB; ++cb) {
+                const v4i b0 = ok[0] ? *reinterpret_cast<const v4i*>(src[0] + cb * 32) : zero;
+                const v4i b1 = ok[1] ? *reinterpret_cast<const v4i*>(src[1] + cb * 32) : zero;
+#pragma unroll
+                for (int b = 0; b < P; ++b) {
+                    const v4i a = wp[b * 64];
+                    acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b0, acc[0][b], 0, 0, 0);
+                    acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b1, acc[1][b], 0, 0, 0);
+                }
+                wp += kMaxPlanes * 64;
+            }
+        }
+    }
+
+    // result row (channel) of register q: 8*(q/4) + 4*(lane/32) + q%4; column (pixel) = lane%32
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        if (!live[h]) continue;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int oc = ocb * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
+            if (oc >= p.OC) continue;
+            uint32_t v = 0;
+#pragma unroll
+            for (int b = 0; b < P; ++b) v += (uint32_t)acc[h][b][q] << (8 * b);
+            const int64_t o = (((int64_t)n_[h] * p.OC + oc) * p.OH + oy_[h]) * p.OW + ox_[h];
+            if (p.masked) {
+                p.acc[o] = (int32_t)((uint32_t)p.acc[o] + v);
+            } else {
+                p.acc[o] = (int32_t)v;
+                if (p.y) p.y[o] = rescale((int32_t)v, p.mult ? p.mult[oc] : p.default_mult, to_[h], p.bias, oc);
+            }
+        }
+    }
+}
+
+// Any layer shape: one output pixel per lane, one output channel per workgroup row.
+__global__ void __launch_bounds__(256) k_conv_shared_direct(const SharedParams p)
+{
+    const int oc = blockIdx.y;
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int64_t pix = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pix >= npix) return;
+    int to;
+    if (!shared_pixel_range(p, pix, to)) return;
+    const int ox = (int)(pix % p.OW);
+    const int oy = (int)((pix / p.OW) % p.OH);
+    const int n = (int)(pix / ((int64_t)p.OW * p.OH));
+    const int grp = oc / p.OCg;
+    const int32_t* wrow = p.w32 + (int64_t)oc * p.K;
+    const int8_t* xn = p.x + ((int64_t)n * p.C + (int64_t)grp * p.Cg) * p.H * p.W;
+    const int iy0 = oy * p.stride_h - p.pad_h, ix0 = ox * p.stride_w - p.pad_w;
+    uint32_t sum = 0;
+    int k = 0;
+    for (int ci = 0; ci < p.Cg; ++ci)
+        for (int kh = 0; kh < p.KH; ++kh)
+            for (int kw = 0; kw < p.KW; ++kw, ++k) {
+                const int iy = iy0 + kh, ix = ix0 + kw;
+                if ((unsigned)iy >= (unsigned)p.H || (unsigned)ix >= (unsigned)p.W) continue;
+                sum += (uint32_t)((int32_t)xn[((int64_t)ci * p.H + iy) * p.W + ix] * wrow[k]);   // modulo 2^32
+            }
+    const int64_t o = (((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox;
+    if (p.masked) {
+        p.acc[o] = (int32_t)((uint32_t)p.acc[o] + sum);
+    } else {
+        p.acc[o] = (int32_t)sum;
+        if (p.y) p.y[o] = rescale((int32_t)sum, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+    }
+}
+
+// Digit planes needed for |W| <= m = 2 * n_samples * 2^max_shift.  P balanced digits represent every integer
+// in [-128 R, 127 R], R = (256^P - 1) / 255, which contains [-2^(8P-2), 2^(8P-2)]: two bits above the
+// length of m are enough (one would not be: 32640 = 255 * 128 has 15 bits and needs three digits).
+// With four planes the last digit may wrap, which is exact modulo 2^32.
+inline int planes_needed(int max_shift, int n_samples)
+{
+    int bits = 2;
+    for (int64_t m = ((int64_t)2 * n_samples) << max_shift; m > 0; m >>= 1) bits++;
+    const int planes = (bits + 7) / 8;
+    return planes > kMaxPlanes ? kMaxPlanes : planes;
+}
+
+inline void launch_conv_shared_mfma(const SharedParams& p, int planes, hipStream_t stream)
+{
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const dim3 grid((unsigned)((npix + 255) / 256), (unsigned)((p.OC + 31) / 32)), block(256);
+    switch (planes) {
+        case 1: hipLaunchKernelGGL(k_conv_shared_mfma<1>, grid, block, 0, stream, p); break;
+        case 2: hipLaunchKernelGGL(k_conv_shared_mfma<2>, grid, block, 0, stream, p); break;
+        case 3: hipLaunchKernelGGL(k_conv_shared_mfma<3>, grid, block, 0, stream, p); break;
+        default: hipLaunchKernelGGL(k_conv_shared_mfma<4>, grid, block, 0, stream, p); break;
+    }
+}
+
+}  // namespace psb

@@ -20,6 +20,7 @@ MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE, MAPPING_PRODUCT_LIST = 0
 
 SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
+           "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
            "psb_last_device_error", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
            "psb_profile_read"]
 
@@ -72,6 +73,10 @@ def lib():
         L.psb_linear.argtypes = [vp, vp, i32, i32, u64, u32, vp, vp, vp, vp, vp]
         L.psb_conv2d.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, u64, u32, vp, vp, vp, vp, vp]
         L.psb_conv2d_progressive.argtypes = [vp, vp, C.POINTER(ConvGeom), vp, vp, u64, u32, vp, vp, vp, vp, vp]
+        L.psb_sample_filter.argtypes = [vp, i32, i32, u64, u32, vp, vp]
+        L.psb_linear_shared.argtypes = L.psb_linear.argtypes
+        L.psb_conv2d_shared.argtypes = L.psb_conv2d.argtypes
+        L.psb_conv2d_progressive_shared.argtypes = L.psb_conv2d_progressive.argtypes
         L.psb_last_device_error.argtypes = []
         L.psb_set_mapping.argtypes = [C.c_int]
         L.psb_query_mapping.argtypes = [vp, C.POINTER(ConvGeom)]
@@ -173,16 +178,25 @@ class Weights:
             pass
 
 
-def linear(q, x, S, seed=0, layer_id=0, acc=None, y=None, mult=None, bias=None):
-    """x int8 [B, K] -> acc int32 [B, OC] (and y float32 if given)."""
+def sample_filter(q, sample_to, sample_from=0, seed=0, layer_id=0, out=None):
+    """The shared-filter mode's integer filter for samples [sample_from, sample_to): int32 [OC, K] on the device."""
+    if out is None:
+        out = torch.empty((q.wshape[0], q.K), dtype=torch.int32, device="cuda")
+    rc = lib().psb_sample_filter(q._h, sample_from, sample_to, seed, layer_id, _ptr(out, torch.int32, "out"), _stream())
+    _check(rc, "psb_sample_filter")
+    return out
+
+
+def linear(q, x, S, seed=0, layer_id=0, acc=None, y=None, mult=None, bias=None, shared=False):
+    """x int8 [B, K] -> acc int32 [B, OC] (and y float32 if given).  shared: one sampled filter per pass."""
     B = x.shape[0]
     oc = q.wshape[0]
     if acc is None:
         acc = torch.empty((B, oc), dtype=torch.int32, device=x.device)
-    rc = lib().psb_linear(q._h, _ptr(x, torch.int8, "x"), B, S, seed, layer_id, _ptr(acc, torch.int32, "acc"),
-                          _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"),
-                          _ptr(bias, torch.float32, "bias"), _stream())
-    _check(rc, "psb_linear")
+    fn = lib().psb_linear_shared if shared else lib().psb_linear
+    rc = fn(q._h, _ptr(x, torch.int8, "x"), B, S, seed, layer_id, _ptr(acc, torch.int32, "acc"),
+            _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
+    _check(rc, "psb_linear_shared" if shared else "psb_linear")
     return acc
 
 
@@ -191,21 +205,22 @@ def _geom(x, stride, pad):
     return ConvGeom(n, h, w, stride[0], stride[1], pad[0], pad[1])
 
 
-def conv2d(q, x, S, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, acc=None, y=None, mult=None, bias=None):
+def conv2d(q, x, S, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, acc=None, y=None, mult=None, bias=None,
+           shared=False):
     """x int8 [N, C, H, W] -> acc int32 [N, OC, OH, OW]."""
     g = _geom(x, stride, pad)
     if acc is None:
         oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
         acc = torch.empty((g.n, q.wshape[0], oh, ow), dtype=torch.int32, device=x.device)
-    rc = lib().psb_conv2d(q._h, _ptr(x, torch.int8, "x"), C.byref(g), S, seed, layer_id,
-                          _ptr(acc, torch.int32, "acc"), _ptr(y, torch.float32, "y"),
-                          _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
-    _check(rc, "psb_conv2d")
+    fn = lib().psb_conv2d_shared if shared else lib().psb_conv2d
+    rc = fn(q._h, _ptr(x, torch.int8, "x"), C.byref(g), S, seed, layer_id, _ptr(acc, torch.int32, "acc"),
+            _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
+    _check(rc, "psb_conv2d_shared" if shared else "psb_conv2d")
     return acc
 
 
 def conv2d_progressive(q, x, budget_to, budget_from=None, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, acc=None,
-                       y=None, mult=None, bias=None):
+                       y=None, mult=None, bias=None, shared=False):
     """budget_to / budget_from uint8 [N, OH, OW]; with budget_from, acc is updated in place."""
     g = _geom(x, stride, pad)
     if acc is None:
@@ -213,10 +228,9 @@ def conv2d_progressive(q, x, budget_to, budget_from=None, stride=(1, 1), pad=(0,
             raise ValueError("a refinement call needs the accumulators of the first pass")
         oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
         acc = torch.empty((g.n, q.wshape[0], oh, ow), dtype=torch.int32, device=x.device)
-    rc = lib().psb_conv2d_progressive(q._h, _ptr(x, torch.int8, "x"), C.byref(g),
-                                      _ptr(budget_to, torch.uint8, "budget_to"),
-                                      _ptr(budget_from, torch.uint8, "budget_from"), seed, layer_id,
-                                      _ptr(acc, torch.int32, "acc"), _ptr(y, torch.float32, "y"),
-                                      _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
-    _check(rc, "psb_conv2d_progressive")
+    fn = lib().psb_conv2d_progressive_shared if shared else lib().psb_conv2d_progressive
+    rc = fn(q._h, _ptr(x, torch.int8, "x"), C.byref(g), _ptr(budget_to, torch.uint8, "budget_to"),
+            _ptr(budget_from, torch.uint8, "budget_from"), seed, layer_id, _ptr(acc, torch.int32, "acc"),
+            _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
+    _check(rc, "psb_conv2d_progressive_shared" if shared else "psb_conv2d_progressive")
     return acc

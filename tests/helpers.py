@@ -7,13 +7,17 @@ def oracle_quantize(orc, L, exp_bits=0, prob_bits=23):
     return orc.QWeights(w, exp_bits=exp_bits, x_absmax=L.x_absmax, s_max=L.s_max, prob_bits=prob_bits)
 
 
-def oracle_layer(orc, L, q=None, budget_to=None, budget_from=None, acc_in=None, points=None, S=None):
-    """acc (int32 [n, oc, oh, ow] or [len(points)]), overflow count, sampled MACs."""
+def oracle_layer(orc, L, q=None, budget_to=None, budget_from=None, acc_in=None, points=None, S=None, shared=False):
+    """acc (int32 [n, oc, oh, ow] or [len(points)]), overflow count, sampled MACs (None in shared-filter mode)."""
     if q is None:
         q = oracle_quantize(orc, L)
     if budget_to is None:
         budget_to = L.budget_to
     S = (L.S if S is None else S) if budget_to is None else None
+    if shared:
+        acc, over = orc.conv2d_shared(q, L.wshape, L.x, L.stride, L.pad, S=S, s_max=L.s_max, budget_to=budget_to,
+                                      budget_from=budget_from, seed=L.seed, layer_id=L.layer_id, acc_in=acc_in)
+        return acc, over, None
     return orc.conv2d(q, L.wshape, L.x, L.stride, L.pad, S=S, s_max=L.s_max, budget_to=budget_to,
                       budget_from=budget_from, seed=L.seed, layer_id=L.layer_id, points=points, acc_in=acc_in)
 
@@ -26,7 +30,7 @@ def gpu_quantize(psb, L, exp_bits=0, prob_bits=23, device="cuda"):
 
 
 def gpu_layer(psb, L, q=None, budget_to=None, budget_from=None, acc_in=None, S=None, want_y=False, mult=None,
-              bias=None, device="cuda"):
+              bias=None, device="cuda", shared=False):
     """Returns acc (numpy int32) and y (numpy float32 or None), through the C-ABI entry point the layer names."""
     import torch
     if q is None:
@@ -47,17 +51,18 @@ def gpu_layer(psb, L, q=None, budget_to=None, budget_from=None, acc_in=None, S=N
         bt = torch.from_numpy(np.ascontiguousarray(budget_to)).to(device)
         bf = None if budget_from is None else torch.from_numpy(np.ascontiguousarray(budget_from)).to(device)
         acc = psb.conv2d_progressive(q, x, bt, bf, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id,
-                                     acc=acc, y=y, mult=m, bias=b)
+                                     acc=acc, y=y, mult=m, bias=b, shared=shared)
     elif L.linear:
         S = L.S if S is None else S
         x2 = x.reshape(n, -1)
         acc2 = torch.empty((n, oc), dtype=torch.int32, device=device)
         y2 = None if y is None else y.reshape(n, oc)
-        psb.linear(q, x2, S, seed=L.seed, layer_id=L.layer_id, acc=acc2, y=y2, mult=m, bias=b)
+        psb.linear(q, x2, S, seed=L.seed, layer_id=L.layer_id, acc=acc2, y=y2, mult=m, bias=b, shared=shared)
         acc = acc2.reshape(n, oc, 1, 1)
     else:
         S = L.S if S is None else S
-        acc = psb.conv2d(q, x, S, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id, y=y, mult=m, bias=b)
+        acc = psb.conv2d(q, x, S, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id, y=y, mult=m, bias=b,
+                         shared=shared)
     torch.cuda.synchronize()
     return acc.cpu().numpy(), (None if y is None else y.cpu().numpy())
 

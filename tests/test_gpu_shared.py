@@ -1,0 +1,178 @@
+"""Shared-filter mode (Eq. numbersystem:simulation) on the GPU vs the CPU oracle: the sampled integer filter
+and the layers built on it (int8 matrix cores for groups = 1, direct kernel otherwise).  Bit-exact."""
+import numpy as np
+import pytest
+
+import helpers
+from paper_1904_02205_amd import synth
+from test_gpu_parity import _layer
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def psb():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_1904_02205_amd import psb as m
+    m.lib()
+    yield m
+    m.set_mapping(m.MAPPING_AUTO)
+
+
+@pytest.mark.parametrize("prob_bits", [23, 4, 7])
+def test_sampled_filter_matches_oracle(psb, orc, prob_bits):
+    rng = np.random.default_rng(800 + prob_bits)
+    L = _layer(rng, 1, 20, 70, 5, 3, pad=1, S=32, s_max=48, prune=0.3)
+    qo = helpers.oracle_quantize(orc, L, prob_bits=prob_bits)
+    qg = helpers.gpu_quantize(psb, L, prob_bits=prob_bits)
+    for a, b in ((0, 16), (0, 1), (0, 48), (3, 4), (5, 37), (16, 32)):
+        ref = orc.sample_filter(qo, seed=L.seed, layer_id=L.layer_id, sample_from=a, sample_to=b)
+        got = psb.sample_filter(qg, b, a, seed=L.seed, layer_id=L.layer_id).cpu().numpy()
+        assert np.array_equal(got.astype(np.int64), ref), (a, b)
+    for a, b in ((-1, 4), (4, 4), (5, 3), (0, 49)):
+        with pytest.raises(psb.PsbError) as ei:
+            psb.sample_filter(qg, b, a)
+        assert ei.value.code == psb.ERR_VALUE
+
+
+def _cases():
+    rng = np.random.default_rng(900)
+    c = []
+    both = (0, 1)             # 0: matrix cores for groups = 1; 1: direct kernel
+    c.append(("linear_small", _layer(rng, 5, 37, 9, 1, 1, S=8, xkind="u4", std=0.05), both))
+    c.append(("linear_ragged", _layer(rng, 67, 130, 100, 1, 1, S=5, xkind="signed", std=0.05), both))
+    c.append(("conv3x3_c20_oc70", _layer(rng, 2, 20, 70, (9, 11), 3, pad=1, S=8), both))
+    c.append(("conv3x3_c64", _layer(rng, 1, 64, 64, 14, 3, pad=1, S=16), both))
+    c.append(("conv3x3_c96_signed", _layer(rng, 1, 96, 33, 6, 3, pad=1, S=32, xkind="signed"), both))
+    c.append(("conv7x7_s2_p3_c3", _layer(rng, 2, 3, 16, (23, 19), 7, stride=2, pad=3, S=8, xkind="signed"), both))
+    c.append(("conv1x1_s2", _layer(rng, 2, 24, 40, 9, 1, stride=2, S=4), both))
+    c.append(("conv_rect_kernel", _layer(rng, 1, 6, 12, (6, 8), (2, 3), stride=(1, 2), pad=(0, 2), S=3), both))
+    c.append(("conv_s1", _layer(rng, 1, 5, 7, 5, 3, pad=1, S=1), both))
+    c.append(("conv_pad3_tiny_image", _layer(rng, 1, 4, 8, 2, 3, pad=3, S=4), both))
+    c.append(("conv_wide_row", _layer(rng, 1, 8, 32, (3, 150), 3, pad=1, S=8), both))
+    c.append(("pruned_pointwise", _layer(rng, 2, 96, 40, 5, 1, S=16, prune=0.9), both))
+    c.append(("s255", _layer(rng, 1, 3, 8, 4, 3, pad=1, S=255, std=0.01), both))
+    c.append(("grouped", _layer(rng, 2, 8, 12, 7, 3, pad=1, groups=4, S=8), (0,)))
+    c.append(("depthwise", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), (0,)))
+    return c
+
+
+@pytest.mark.parametrize("case", _cases(), ids=lambda c: c[0])
+def test_layer_bit_exact(psb, orc, case):
+    _, L, mappings = case
+    ref, over, _ = helpers.oracle_layer(orc, L, shared=True)
+    assert over == 0
+    qg = helpers.gpu_quantize(psb, L)
+    for m in mappings:
+        psb.set_mapping(m)
+        acc, _ = helpers.gpu_layer(psb, L, qg, shared=True)
+        assert np.array_equal(acc, ref), f"mapping {m}"
+        acc, _ = helpers.gpu_layer(psb, L, qg, shared=True)      # workspace reuse: same bits
+        assert np.array_equal(acc, ref), f"mapping {m}, second call"
+    psb.set_mapping(psb.MAPPING_AUTO)
+
+
+@pytest.mark.parametrize("planes_case", [
+    # few taps and a tiny activation range let the window reach deep: filter values up to 2^30
+    ("deep_window", dict(exp_bits=5, x_absmax=1, s_max=2), 2),
+    ("one_exponent", dict(exp_bits=1, x_absmax=127, s_max=1), 1),
+    ("default", dict(exp_bits=0, x_absmax=127, s_max=16), 16),
+], ids=lambda c: c[0])
+def test_every_digit_plane_count(psb, orc, planes_case):
+    """Filters that need 1, 3 and 4 base-256 digit planes."""
+    import torch
+    _, kw, S = planes_case
+    rng = np.random.default_rng(950)
+    w = (rng.standard_normal((40, 4, 1, 1)) * 10.0 ** rng.uniform(-6, 0, size=(40, 4, 1, 1))).astype(np.float32)
+    x = rng.integers(-kw["x_absmax"], kw["x_absmax"] + 1, size=(3, 4, 9, 9)).astype(np.int8)
+    qo = orc.QWeights(w.reshape(40, -1), **kw)
+    qg = psb.Weights(torch.from_numpy(w).cuda(), **kw)
+    ref, over = orc.conv2d_shared(qo, (40, 4, 1, 1, 1), x, S=S, seed=8, layer_id=2)
+    assert over == 0
+    acc = psb.conv2d(qg, torch.from_numpy(x).cuda(), S, seed=8, layer_id=2, shared=True).cpu().numpy()
+    assert np.array_equal(acc, ref)
+    if planes_case[0] == "deep_window":
+        assert np.abs(orc.sample_filter(qo, S, seed=8, layer_id=2)).max() >= 2 ** 24      # really four planes
+
+
+def test_filter_value_between_the_ranges_of_two_and_three_digits(psb, orc):
+    """W = 64 * (255 + 255) = 32640 has 15 bits but lies above 127 * 257, the largest two-digit balanced number."""
+    import torch
+    w = np.full((3, 500), np.nextafter(np.float32(2.0), np.float32(0)), np.float32)
+    x = np.random.default_rng(955).integers(-128, 128, size=(4, 500)).astype(np.int8)
+    qo = orc.QWeights(w, x_absmax=128, s_max=255)
+    assert qo.e_top - qo.e_min == 6
+    W = orc.sample_filter(qo, 255, seed=1)
+    assert W.max() == 32640
+    ref, over = orc.conv2d_shared(qo, (3, 500, 1, 1, 1), x.reshape(4, 500, 1, 1), S=255, seed=1)
+    qg = psb.Weights(torch.from_numpy(w).cuda(), x_absmax=128, s_max=255)
+    acc = psb.linear(qg, torch.from_numpy(x).cuda(), 255, seed=1, shared=True).cpu().numpy()
+    assert over == 0 and np.array_equal(acc, ref.reshape(4, 3))
+
+
+def test_prob_bits_and_seed(psb, orc):
+    rng = np.random.default_rng(960)
+    L = _layer(rng, 2, 32, 64, 8, 3, pad=1, S=16)
+    qo = helpers.oracle_quantize(orc, L, prob_bits=4)
+    qg = helpers.gpu_quantize(psb, L, prob_bits=4)
+    ref, _, _ = helpers.oracle_layer(orc, L, qo, shared=True)
+    acc, _ = helpers.gpu_layer(psb, L, qg, shared=True)
+    assert np.array_equal(acc, ref)
+    L2 = synth.Layer("t", L.w, L.x, pad=L.pad, S=16, s_max=16, seed=L.seed + 1, layer_id=L.layer_id)
+    ref2, _, _ = helpers.oracle_layer(orc, L2, qo, shared=True)
+    acc2, _ = helpers.gpu_layer(psb, L2, qg, shared=True)
+    assert np.array_equal(acc2, ref2) and not np.array_equal(acc2, acc)
+    per_product, _ = helpers.gpu_layer(psb, L, qg)
+    assert not np.array_equal(per_product, acc)                   # a different estimator
+
+
+@pytest.mark.parametrize("mapping", [0, 1])
+def test_progressive_bit_exact_and_incremental(psb, orc, mapping):
+    rng = np.random.default_rng(970)
+    L = _layer(rng, 3, 12, 70, (9, 8), 3, pad=1, S=32, s_max=32)
+    oh, ow = L.out_hw
+    to = rng.choice([0, 1, 2, 3, 4, 7, 8, 16, 31, 32, 40], size=(3, oh, ow)).astype(np.uint8)   # 40 is clamped to 32
+    qo = helpers.oracle_quantize(orc, L)
+    ref, over, _ = helpers.oracle_layer(orc, L, qo, budget_to=to, shared=True)
+    assert over == 0
+    psb.set_mapping(mapping)
+    qg = helpers.gpu_quantize(psb, L)
+    acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, shared=True)
+    assert np.array_equal(acc, ref)
+    for m in (8, 5):
+        first = np.minimum(to, m).astype(np.uint8)
+        a1, _ = helpers.gpu_layer(psb, L, qg, budget_to=first, shared=True)
+        r1, _, _ = helpers.oracle_layer(orc, L, qo, budget_to=first, shared=True)
+        assert np.array_equal(a1, r1)
+        a2, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, budget_from=first, acc_in=a1, shared=True)
+        assert np.array_equal(a2, ref)
+    a3, _ = helpers.gpu_layer(psb, L, qg, budget_to=first, budget_from=to, acc_in=a1, shared=True)   # empty ranges
+    assert np.array_equal(a3, a1)
+    const, _ = helpers.gpu_layer(psb, L, qg, budget_to=np.full((3, oh, ow), 8, np.uint8), shared=True)
+    plain, _ = helpers.gpu_layer(psb, L, qg, S=8, shared=True)
+    assert np.array_equal(const, plain)
+    psb.set_mapping(psb.MAPPING_AUTO)
+
+
+@pytest.mark.parametrize("mapping", [0, 1])
+def test_rescale_matches_oracle(psb, orc, mapping):
+    rng = np.random.default_rng(980)
+    L = _layer(rng, 2, 10, 40, 6, 3, pad=1, S=8, s_max=16)
+    oc = 40
+    mult = (rng.uniform(0.5, 2.0, size=oc) * 2.0 ** -9).astype(np.float32)
+    bias = rng.standard_normal(oc).astype(np.float32)
+    qo = helpers.oracle_quantize(orc, L)
+    qg = helpers.gpu_quantize(psb, L)
+    psb.set_mapping(mapping)
+    ref, _, _ = helpers.oracle_layer(orc, L, qo, shared=True)
+    acc, y = helpers.gpu_layer(psb, L, qg, want_y=True, mult=mult, bias=bias, shared=True)
+    assert np.array_equal(acc, ref)
+    assert np.array_equal(y, orc.rescale(ref, qo.e_min, S=8, s_max=16, mult=mult, bias=bias))
+    oh, ow = L.out_hw
+    to = rng.choice([0, 2, 8, 16], size=(2, oh, ow)).astype(np.uint8)
+    refp, _, _ = helpers.oracle_layer(orc, L, qo, budget_to=to, shared=True)
+    accp, yp = helpers.gpu_layer(psb, L, qg, budget_to=to, want_y=True, shared=True)
+    assert np.array_equal(accp, refp)
+    assert np.array_equal(yp, orc.rescale(refp, qo.e_min, s_max=16, budget_to=to))
+    psb.set_mapping(psb.MAPPING_AUTO)
