@@ -2,7 +2,7 @@
 """Benchmark of the PSB layer hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5] [--prob-bits 23|1..7]
-                    [--no-cpu-baseline]
+                    [--mode product|shared] [--no-cpu-baseline]
 
 A step is one pass of the whole hot path over one batch of synthetic input that is already resident in
 HBM: the layer call(s) of the workload through the C-ABI (zero-fill, sampling kernel, fp32 rescale).  The
@@ -23,6 +23,11 @@ roofline  bound "alu": the sampling kernel is limited by integer VALU issue.  Un
         that need sampling (live weight, tap inside the image, activation != 0).  With --prob-bits 1..7 a
         generator call serves 16 samples and its counting is 4 x (or, subtract, and, bit count) + 1 = 17 units
         instead of 16: 78 units per call.
+--mode shared  the shared-filter mode (one sampled filter per pass, the granularity of the paper's simulation;
+        reported separately from the headline, which is --mode product).  Its contraction runs on the int8 matrix
+        cores: roofline bound "mfma", peak 5.0 POP/s dense int8; achieved = 2 x (output elements) x K x P int8
+        operations per launch / kernel time, P = base-256 digit planes of the sampled filter (K = true taps per
+        output, padding of the channel count to 32 not counted).
 """
 import argparse
 import json
@@ -47,6 +52,28 @@ CALL_UNITS = 15 * WIDE + 31 + 4 * WIDE + 4 * WIDE                          # 77 
 CALL_UNITS_7BIT = 15 * WIDE + 31 + 4 * 4 + 1                               # 78 per generator call (16 samples)
 PRODUCT_UNITS = 2 * WIDE                                                   # v_mul_i32_i24 + v_mad_i32_i24
 KERNEL_NAMES = {1: "k_layer_pixel_lane", 2: "k_layer_oc_lane", 3: "k_layer_product_list"}
+PEAK_INT8_TOPS = 5000.0    # dense int8 MFMA, MI355X
+
+
+def planes_needed(max_shift, n_samples):
+    """Digit planes the library uses for a filter bounded by 2 * n_samples * 2^max_shift (two guard bits)."""
+    return min(4, (2 + ((2 * n_samples) << max_shift).bit_length() + 7) // 8)
+
+
+def shared_ops(L, q):
+    """int8 operations (2 per multiply-add) of the shared-filter contraction(s) of one layer call."""
+    n, oc = L.x.shape[0], L.w.shape[0]
+    oh, ow = L.out_hw
+    K = int(np.prod(L.w.shape[1:]))
+    max_shift = q.e_top - q.e_min
+    if L.budget_to is None:
+        return 2.0 * n * oc * oh * ow * K * planes_needed(max_shift, L.S)
+    b = np.minimum(L.budget_to, L.s_max)
+    levels = sorted(set(np.unique(b).tolist()) | {0})
+    ops = 0.0
+    for lo, hi in zip(levels[:-1], levels[1:]):
+        ops += 2.0 * float((b >= hi).sum()) * oc * K * planes_needed(max_shift, hi - lo)
+    return ops
 
 
 def lane_ops(n_calls, n_products, prob_bits=23):
@@ -105,6 +132,9 @@ def main():
     ap.add_argument("--mapping", type=int, default=0)
     ap.add_argument("--prob-bits", type=int, default=23,
                     help="23 = exact probabilities (the headline metric); 1..7 = discretised, 7-bit uniforms")
+    ap.add_argument("--mode", default="product", choices=["product", "shared"],
+                    help="product = one random bit per (output, tap, sample), the headline; shared = one sampled "
+                         "filter per pass (the paper's simulation granularity)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-y", action="store_true", help="skip the fp32 rescale output")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -126,13 +156,17 @@ def main():
 
     layers, desc = workload_layers(args.workload)
     per_call = 4 if args.prob_bits == 23 else 16
+    shared = args.mode == "shared"
     calls = []
     kernels = []
-    smac = n_calls = n_prod = 0.0
+    smac = n_calls = n_prod = mfma_ops = 0.0
     for L in layers:
         w = torch.from_numpy(L.w).to(dev)
         q = psb.Weights(w, groups=L.groups, x_absmax=L.x_absmax, s_max=L.s_max, prob_bits=args.prob_bits)
         name = KERNEL_NAMES[psb.query_mapping(q, (L.x.shape[0], L.x.shape[2], L.x.shape[3]) + L.stride + L.pad)]
+        if shared:
+            name = "k_conv_shared_mfma" if L.groups == 1 and args.mapping != 1 else "k_conv_shared_direct"
+            mfma_ops += shared_ops(L, q)
         if name not in kernels:
             kernels.append(name)
         x = torch.from_numpy(L.x).to(dev)
@@ -141,7 +175,10 @@ def main():
         acc = torch.empty((n, oc, oh, ow), dtype=torch.int32, device=dev)
         y = None if args.no_y else torch.empty((n, oc, oh, ow), dtype=torch.float32, device=dev)
         bt = None if L.budget_to is None else torch.from_numpy(L.budget_to).to(dev)
-        a, b, c = count_work(L, q.export(), torch, dev, per_call)
+        packed = q.export()
+        if not calls:
+            q0_packed = packed
+        a, b, c = count_work(L, packed, torch, dev, per_call)
         smac += a
         n_calls += b
         n_prod += c
@@ -152,12 +189,14 @@ def main():
         for L, q, x, acc, y, bt in calls:
             if bt is not None:
                 psb.conv2d_progressive(q, x, bt, None, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id,
-                                       acc=acc, y=y)
+                                       acc=acc, y=y, shared=shared)
             elif L.linear:
                 psb.linear(q, x.reshape(x.shape[0], -1), L.S, seed=L.seed, layer_id=L.layer_id,
-                           acc=acc.reshape(acc.shape[0], -1), y=None if y is None else y.reshape(y.shape[0], -1))
+                           acc=acc.reshape(acc.shape[0], -1), y=None if y is None else y.reshape(y.shape[0], -1),
+                           shared=shared)
             else:
-                psb.conv2d(q, x, L.S, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id, acc=acc, y=y)
+                psb.conv2d(q, x, L.S, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id, acc=acc, y=y,
+                           shared=shared)
 
     if args.copy_calibration:
         src = torch.ones(64 << 20, dtype=torch.uint8, device=dev)
@@ -190,7 +229,7 @@ def main():
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": desc, "sampled_macs_per_step": smac,
                    "generator_calls_per_step": n_calls, "samples_per_generator_call": per_call,
-                   "prob_bits": args.prob_bits,
+                   "prob_bits": args.prob_bits, "mode": args.mode,
                    "kernel_launches_per_step": launches_per_step, "mapping": args.mapping,
                    "rescale_output": not args.no_y},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_TIOPS,
@@ -200,6 +239,12 @@ def main():
                      "kernel": "+".join(kernels),
                      "kernel_ms_avg": kern_s * 1e3, "lane_ops_per_launch": ops_per_launch},
     }
+
+    if shared:
+        achieved = mfma_ops / launches_per_step / kern_s / 1e12
+        out["roofline"] = {"bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s (int8)",
+                           "frac": achieved / PEAK_INT8_TOPS, "traffic": None, "kernel": "+".join(kernels),
+                           "kernel_ms_avg": kern_s * 1e3, "int8_ops_per_launch": mfma_ops / launches_per_step}
 
     if not args.no_cpu_baseline:
         from oracle import binding as orc          # the oracle is only timed here, never used for results
@@ -213,8 +258,14 @@ def main():
         n_pts = int(min(total, max(1000, 8e9 / max(per_out, 1))))
         pts = None if n_pts >= total else np.random.default_rng(0).choice(total, n_pts, replace=False).astype(np.int64)
         c0 = time.perf_counter()
-        _, _, cpu_smac = orc.conv2d(qo, L.wshape, L.x, L.stride, L.pad, S=None if L.budget_to is not None else L.S,
-                                    s_max=L.s_max, budget_to=L.budget_to, seed=L.seed, layer_id=L.layer_id, points=pts)
+        if shared:
+            orc.conv2d_shared(qo, L.wshape, L.x, L.stride, L.pad, S=None if L.budget_to is not None else L.S,
+                              s_max=L.s_max, budget_to=L.budget_to, seed=L.seed, layer_id=L.layer_id)
+            cpu_smac, pts = smac if len(layers) == 1 else count_work(L, q0_packed, torch, dev, per_call)[0], None
+        else:
+            _, _, cpu_smac = orc.conv2d(qo, L.wshape, L.x, L.stride, L.pad, S=None if L.budget_to is not None else L.S,
+                                        s_max=L.s_max, budget_to=L.budget_to, seed=L.seed, layer_id=L.layer_id,
+                                        points=pts)
         c1 = time.perf_counter()
         out["cpu_baseline"] = {"value": cpu_smac / (c1 - c0), "unit": "sampled MAC/s",
                                "cores": orc.num_threads(), "kind": "oracle",

@@ -68,7 +68,7 @@ def lib():
         L.psbo_sample_filter.restype = C.c_int
         L.psbo_conv2d_shared.argtypes = [C.POINTER(Weights), C.POINTER(WShape), C.c_void_p, C.POINTER(Geom),
                                          C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32,
-                                         C.c_void_p, C.POINTER(C.c_int64)]
+                                         C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_int64)]
         L.psbo_conv2d_shared.restype = C.c_int
         L.psbo_rescale.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -233,8 +233,8 @@ def sample_filter(q, S=None, seed=0, layer_id=0, sample_from=0, sample_to=None, 
 
 
 def conv2d_shared(q, wshape, x, stride=(1, 1), pad=(0, 0), S=None, s_max=None, budget_to=None, budget_from=None,
-                  seed=0, layer_id=0, acc_in=None):
-    """Shared-filter layer: (acc int32 [n, oc, oh, ow], overflow count)."""
+                  seed=0, layer_id=0, acc_in=None, points=None):
+    """Shared-filter layer: (acc int32 [n, oc, oh, ow] or [len(points)], overflow count)."""
     oc, cin, kh, kw, groups = wshape
     x = np.ascontiguousarray(x, dtype=np.int8)
     n, c, h, w = x.shape
@@ -250,13 +250,19 @@ def conv2d_shared(q, wshape, x, stride=(1, 1), pad=(0, 0), S=None, s_max=None, b
     if budget_from is not None:
         budget_from = np.ascontiguousarray(budget_from, dtype=np.uint8)
         assert budget_from.shape == (n, oh, ow) and acc_in is not None
-        acc = np.ascontiguousarray(acc_in, dtype=np.int32).copy().reshape(n, oc, oh, ow)
+    if points is not None:
+        points = np.ascontiguousarray(points, dtype=np.int64)
+        shape = (points.size,)
     else:
-        acc = np.zeros((n, oc, oh, ow), dtype=np.int32)
+        shape = (n, oc, oh, ow)
+    if budget_from is not None:
+        acc = np.ascontiguousarray(acc_in, dtype=np.int32).copy().reshape(shape)
+    else:
+        acc = np.zeros(shape, dtype=np.int32)
     over = C.c_int64(0)
     rc = lib().psbo_conv2d_shared(C.byref(q._q), C.byref(ws), _ptr(x), C.byref(g), 0 if S is None else int(S),
                                   int(s_max), _ptr(budget_to), _ptr(budget_from), int(seed), int(layer_id),
-                                  _ptr(acc), C.byref(over))
+                                  _ptr(points), 0 if points is None else points.size, _ptr(acc), C.byref(over))
     if rc != OK:
         raise OracleError(rc)
     return acc, over.value

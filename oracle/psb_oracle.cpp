@@ -386,7 +386,8 @@ extern "C" int psbo_sample_filter(const psbo_weights* q, int32_t from, int32_t t
 extern "C" int psbo_conv2d_shared(const psbo_weights* q, const psbo_wshape* ws, const int8_t* x,
                                   const psbo_geom* g, int32_t S_uniform, int32_t s_max,
                                   const uint8_t* budget_to, const uint8_t* budget_from,
-                                  uint64_t seed, uint32_t layer_id, int32_t* acc, int64_t* overflow)
+                                  uint64_t seed, uint32_t layer_id, const int64_t* points, int64_t n_points,
+                                  int32_t* acc, int64_t* overflow)
 {
     if (!q || !ws || !x || !g || !acc) return PSBO_ERR_ARG;
     const int32_t OC = ws->oc, C = ws->cin, KH = ws->kh, KW = ws->kw, G = ws->groups;
@@ -402,6 +403,7 @@ extern "C" int psbo_conv2d_shared(const psbo_weights* q, const psbo_wshape* ws, 
     if (!budget_to && S_uniform <= 0) return PSBO_ERR_ARG;
     if (budget_from && !budget_to) return PSBO_ERR_ARG;
     if (s_max <= 0 || s_max > 255) return PSBO_ERR_ARG;
+    if (points && n_points < 0) return PSBO_ERR_ARG;
 
     /* prefix counts: cnt[wi][s] = number of ones among samples 0 .. s-1 of weight wi */
     const int64_t nw = (int64_t)OC * K;
@@ -419,9 +421,12 @@ extern "C" int psbo_conv2d_shared(const psbo_weights* q, const psbo_wshape* ws, 
     }
 
     const int64_t total = (int64_t)N * OC * OH * OW;
+    const int64_t count = points ? n_points : total;
     int64_t n_over = 0;
 #pragma omp parallel for reduction(+ : n_over) schedule(dynamic, 64)
-    for (int64_t flat = 0; flat < total; ++flat) {
+    for (int64_t idx = 0; idx < count; ++idx) {
+        const int64_t flat = points ? points[idx] : idx;
+        const int64_t dst = points ? idx : flat;
         const int32_t ox = (int32_t)(flat % OW);
         const int32_t oy = (int32_t)((flat / OW) % OH);
         const int32_t oc = (int32_t)((flat / ((int64_t)OW * OH)) % OC);
@@ -453,11 +458,11 @@ extern "C" int psbo_conv2d_shared(const psbo_weights* q, const psbo_wshape* ws, 
                     wrapped += (uint32_t)(xv * Wv);
                 }
         if (budget_from) {
-            exact += acc[flat];
-            wrapped += (uint32_t)acc[flat];
+            exact += acc[dst];
+            wrapped += (uint32_t)acc[dst];
         }
         if (exact < INT32_MIN || exact > INT32_MAX) n_over++;
-        acc[flat] = (int32_t)wrapped;
+        acc[dst] = (int32_t)wrapped;
     }
     std::free(cnt);
     if (overflow) *overflow = n_over;

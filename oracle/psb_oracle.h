@@ -129,11 +129,12 @@ int psbo_sample_filter(const psbo_weights* q, int32_t from, int32_t to, uint64_t
  * "Efficient simulation of the forward pass"): acc[o] = sum_k x[o,k] * W_[from,to)[oc][k],
  * where a pixel with sample range [from,to) uses the filter built from exactly
  * those samples, so that budgets nest the way Sect. 4.5 needs (the first samples
- * are reused).  Arguments as psbo_conv2d.                                        */
+ * are reused).  Arguments as psbo_conv2d, including the optional list of points.   */
 int psbo_conv2d_shared(const psbo_weights* q, const psbo_wshape* ws, const int8_t* x,
                        const psbo_geom* g, int32_t S_uniform, int32_t s_max,
                        const uint8_t* budget_to, const uint8_t* budget_from,
-                       uint64_t seed, uint32_t layer_id, int32_t* acc, int64_t* overflow);
+                       uint64_t seed, uint32_t layer_id, const int64_t* points, int64_t n_points,
+                       int32_t* acc, int64_t* overflow);
 
 /* Final rescale: y = fl( fl( float(acc) * mult[oc] ) * inv_S ) + bias[oc],
  * every fl one binary32 round-to-nearest-even operation, no fused

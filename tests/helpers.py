@@ -16,7 +16,8 @@ def oracle_layer(orc, L, q=None, budget_to=None, budget_from=None, acc_in=None, 
     S = (L.S if S is None else S) if budget_to is None else None
     if shared:
         acc, over = orc.conv2d_shared(q, L.wshape, L.x, L.stride, L.pad, S=S, s_max=L.s_max, budget_to=budget_to,
-                                      budget_from=budget_from, seed=L.seed, layer_id=L.layer_id, acc_in=acc_in)
+                                      budget_from=budget_from, seed=L.seed, layer_id=L.layer_id, acc_in=acc_in,
+                                      points=points)
         return acc, over, None
     return orc.conv2d(q, L.wshape, L.x, L.stride, L.pad, S=S, s_max=L.s_max, budget_to=budget_to,
                       budget_from=budget_from, seed=L.seed, layer_id=L.layer_id, points=points, acc_in=acc_in)

@@ -75,3 +75,40 @@ def test_config4_resnet18_layers_sampled(psb, orc):
         # properties that hold at any size: zero input rows give zero, and the call is repeatable
         acc2, _ = helpers.gpu_layer(psb, L)
         assert np.array_equal(acc, acc2)
+
+
+# ------------------------------------------------------------------ shared-filter mode at the same sizes
+
+def _full_shared(psb, orc, L):
+    print(f"[config, shared filter] {L.name} x{L.x.shape} w{L.w.shape} S={L.S}", flush=True)
+    qo = helpers.oracle_quantize(orc, L)
+    ref, over, _ = helpers.oracle_layer(orc, L, qo, shared=True)
+    acc, y = helpers.gpu_layer(psb, L, want_y=True, shared=True)
+    assert over == 0
+    assert np.array_equal(acc, ref)
+    ref_y = orc.rescale(ref, qo.e_min, S=None if L.budget_to is not None else L.S, s_max=L.s_max,
+                        budget_to=L.budget_to)
+    np.testing.assert_allclose(y, ref_y, rtol=1e-6, atol=0)
+
+
+def test_shared_filter_configs_1_2_3_5(psb, orc):
+    for L in [synth.config1(), synth.config2(), synth.config3()] + synth.config5():
+        _full_shared(psb, orc, L)
+
+
+def test_shared_filter_config4_layers_sampled(psb, orc):
+    rng = np.random.default_rng(4041)
+    for L in synth.config4_layers():
+        print(f"[config4, shared filter] {L.name} x{L.x.shape} w{L.w.shape}", flush=True)
+        qo = helpers.oracle_quantize(orc, L)
+        qg = helpers.gpu_quantize(psb, L)
+        # the whole sampled filter, then 20,000 outputs
+        W = psb.sample_filter(qg, L.S, seed=L.seed, layer_id=L.layer_id).cpu().numpy()
+        assert np.array_equal(W.astype(np.int64), orc.sample_filter(qo, L.S, seed=L.seed, layer_id=L.layer_id))
+        acc, y = helpers.gpu_layer(psb, L, qg, want_y=True, shared=True)
+        pts = rng.choice(acc.size, size=min(20000, acc.size), replace=False).astype(np.int64)
+        ref, over, _ = helpers.oracle_layer(orc, L, qo, points=pts, shared=True)
+        assert over == 0
+        assert np.array_equal(acc.ravel()[pts], ref), L.name
+        ref_y = orc.rescale(ref.reshape(1, 1, -1), qo.e_min, S=L.S).ravel()
+        np.testing.assert_allclose(y.ravel()[pts], ref_y, rtol=1e-6, atol=0)

@@ -161,6 +161,18 @@ def test_progressive_budgets_nest(orc):
     assert np.array_equal(const, plain)
 
 
+def test_points_variant_equals_the_full_one(orc):
+    rng = np.random.default_rng(16)
+    wt = (rng.standard_normal((6, 4, 3, 3)) * 0.1).astype(np.float32)
+    x = rng.integers(-9, 10, size=(2, 4, 6, 5)).astype(np.int8)
+    q = orc.QWeights(wt.reshape(6, -1), x_absmax=9, s_max=8)
+    to = rng.choice([0, 3, 8], size=(2, 3, 5)).astype(np.uint8)
+    full, _ = orc.conv2d_shared(q, (6, 4, 3, 3, 1), x, stride=(2, 1), pad=(1, 1), budget_to=to, seed=3)
+    pts = rng.choice(full.size, 40, replace=False)
+    some, _ = orc.conv2d_shared(q, (6, 4, 3, 3, 1), x, stride=(2, 1), pad=(1, 1), budget_to=to, seed=3, points=pts)
+    assert np.array_equal(some, full.ravel()[pts])
+
+
 def test_layer_output_is_unbiased(orc):
     """Mean over seeds of the rescaled shared-filter output approaches the float convolution (Sect. 3.1)."""
     rng = np.random.default_rng(15)
