@@ -73,6 +73,16 @@ def lib():
         L.psbo_rescale.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.psbo_rescale.restype = C.c_int
+        L.psbo_requantize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_float, C.c_int32,
+                                      C.c_int32, C.c_int64, C.c_void_p]
+        L.psbo_requantize.restype = C.c_int
+        L.psbo_maxpool_i8.argtypes = [C.c_void_p] + [C.c_int32] * 10 + [C.c_void_p]
+        L.psbo_maxpool_i8.restype = C.c_int
+        L.psbo_avgpool_requantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                              C.c_int32, C.c_int32, C.c_void_p]
+        L.psbo_avgpool_requantize.restype = C.c_int
+        L.psbo_budget_resample.argtypes = [C.c_void_p] + [C.c_int32] * 5 + [C.c_void_p]
+        L.psbo_budget_resample.restype = C.c_int
         L.psbo_num_threads.argtypes = []
         L.psbo_num_threads.restype = C.c_int
         _lib = L
@@ -286,3 +296,52 @@ def rescale(acc, e_min, S=None, s_max=255, budget_to=None, mult=None, bias=None)
     if rc != OK:
         raise OracleError(rc)
     return y
+
+
+def requantize(y, inv_step, relu=True, lo=0, hi=127, res_f32=None, res_i8=None, res_step=0.0):
+    """int8 array of y's shape: clamp(rint(g(y [+ r]) * inv_step), lo, hi)."""
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    out = np.zeros(y.shape, dtype=np.int8)
+    if res_f32 is not None:
+        res_f32 = np.ascontiguousarray(res_f32, dtype=np.float32)
+        assert res_f32.shape == y.shape
+    if res_i8 is not None:
+        res_i8 = np.ascontiguousarray(res_i8, dtype=np.int8)
+        assert res_i8.shape == y.shape
+    rc = lib().psbo_requantize(_ptr(y), _ptr(res_f32), _ptr(res_i8), float(np.float32(res_step)), 1 if relu else 0,
+                               float(np.float32(inv_step)), int(lo), int(hi), y.size, _ptr(out))
+    if rc != OK:
+        raise OracleError(rc)
+    return out
+
+
+def maxpool_i8(x, kernel, stride, pad):
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    n, c, h, w = x.shape
+    oh, ow = out_hw(h, w, kernel[0], kernel[1], stride, pad)
+    out = np.zeros((n, c, oh, ow), dtype=np.int8)
+    rc = lib().psbo_maxpool_i8(_ptr(x), n, c, h, w, kernel[0], kernel[1], stride[0], stride[1], pad[0], pad[1],
+                               _ptr(out))
+    if rc != OK:
+        raise OracleError(rc)
+    return out
+
+
+def avgpool_requantize(x, scale, lo=0, hi=127):
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    n, c, h, w = x.shape
+    out = np.zeros((n, c), dtype=np.int8)
+    rc = lib().psbo_avgpool_requantize(_ptr(x), n, c, h, w, float(np.float32(scale)), int(lo), int(hi), _ptr(out))
+    if rc != OK:
+        raise OracleError(rc)
+    return out
+
+
+def budget_resample(b, oh, ow):
+    b = np.ascontiguousarray(b, dtype=np.uint8)
+    n, h, w = b.shape
+    out = np.zeros((n, oh, ow), dtype=np.uint8)
+    rc = lib().psbo_budget_resample(_ptr(b), n, h, w, oh, ow, _ptr(out))
+    if rc != OK:
+        raise OracleError(rc)
+    return out

@@ -498,6 +498,101 @@ extern "C" int psbo_rescale(const int32_t* acc, int32_t n, int32_t oc, int32_t s
     return PSBO_OK;
 }
 
+/* ---------------------------------------------------------------------------
+ * Glue between layers of a network (suppl. "ReLU, Batch-Norm, and Pooling":
+ * ReLU is a gate on the sign, max-pooling needs comparators, the factor of an
+ * average pooling is a fixed multiplication; suppl. "Activations and
+ * Accumulation": activations are stored as fixed-point integers).  Every
+ * floating-point step is one binary32 operation rounded to nearest even, in
+ * the order written, so that both implementations produce the same integers.
+ * ------------------------------------------------------------------------- */
+
+/* x_out = clamp( rint( g( y [+ r] ) * inv_step ), lo, hi ),  g = max(., 0) if relu else identity,
+ * r = res_f32[i] or (float)res_i8[i] * res_step (one rounded multiplication), added in binary32. */
+extern "C" int psbo_requantize(const float* y, const float* res_f32, const int8_t* res_i8, float res_step,
+                               int relu, float inv_step, int32_t lo, int32_t hi, int64_t n, int8_t* x_out)
+{
+    if (!y || !x_out || n < 0 || lo < -128 || hi > 127 || lo > hi) return PSBO_ERR_ARG;
+    if (res_f32 && res_i8) return PSBO_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float t = y[i];
+        if (res_f32) { volatile float u = t + res_f32[i]; t = u; }
+        if (res_i8) {
+            volatile float r = (float)res_i8[i] * res_step;
+            volatile float u = t + r;
+            t = u;
+        }
+        if (relu && !(t > 0.0f)) t = 0.0f;             /* also maps NaN to 0 */
+        volatile float scaled = t * inv_step;
+        float q = std::nearbyintf(scaled);             /* ties to even in the default rounding mode */
+        if (!(q >= (float)lo)) q = (float)lo;          /* NaN goes to lo */
+        if (q > (float)hi) q = (float)hi;
+        x_out[i] = (int8_t)(int32_t)q;
+    }
+    return PSBO_OK;
+}
+
+/* Max-pooling on int8, NCHW; positions in the padding do not take part. */
+extern "C" int psbo_maxpool_i8(const int8_t* x, int32_t n, int32_t c, int32_t h, int32_t w, int32_t kh, int32_t kw,
+                               int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int8_t* out)
+{
+    if (!x || !out || n <= 0 || c <= 0 || h <= 0 || w <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 ||
+        pad_h < 0 || pad_w < 0 || 2 * pad_h > kh || 2 * pad_w > kw || h + 2 * pad_h < kh || w + 2 * pad_w < kw)
+        return PSBO_ERR_ARG;
+    const int32_t oh = (h + 2 * pad_h - kh) / stride_h + 1, ow = (w + 2 * pad_w - kw) / stride_w + 1;
+    for (int64_t img = 0; img < (int64_t)n * c; ++img)
+        for (int32_t oy = 0; oy < oh; ++oy)
+            for (int32_t ox = 0; ox < ow; ++ox) {
+                int32_t best = -129;
+                for (int32_t dy = 0; dy < kh; ++dy)
+                    for (int32_t dx = 0; dx < kw; ++dx) {
+                        const int32_t iy = oy * stride_h - pad_h + dy, ix = ox * stride_w - pad_w + dx;
+                        if (iy < 0 || iy >= h || ix < 0 || ix >= w) continue;
+                        const int32_t v = x[(img * h + iy) * w + ix];
+                        if (v > best) best = v;
+                    }
+                out[(img * oh + oy) * ow + ox] = (int8_t)best;   /* pad <= kernel/2: at least one position is inside */
+            }
+    return PSBO_OK;
+}
+
+/* Global average pooling on int8 with requantisation:
+ * out[n][c] = clamp( rint( ((float)sum * fl(1/(h*w))) * scale ), lo, hi ), sum exact in int32. */
+extern "C" int psbo_avgpool_requantize(const int8_t* x, int32_t n, int32_t c, int32_t h, int32_t w, float scale,
+                                       int32_t lo, int32_t hi, int8_t* out)
+{
+    if (!x || !out || n <= 0 || c <= 0 || h <= 0 || w <= 0 || (int64_t)h * w > (1 << 23) || lo < -128 || hi > 127 ||
+        lo > hi)
+        return PSBO_ERR_ARG;
+    const float inv_count = 1.0f / (float)(h * w);
+    for (int64_t img = 0; img < (int64_t)n * c; ++img) {
+        int32_t sum = 0;
+        for (int64_t i = 0; i < (int64_t)h * w; ++i) sum += x[img * h * w + i];
+        volatile float mean = (float)sum * inv_count;
+        volatile float scaled = mean * scale;
+        float q = std::nearbyintf(scaled);
+        if (!(q >= (float)lo)) q = (float)lo;
+        if (q > (float)hi) q = (float)hi;
+        out[img] = (int8_t)(int32_t)q;
+    }
+    return PSBO_OK;
+}
+
+/* Budget map at another resolution (Sect. 4.5: the two kinds of regions separate the activations
+ * "on all layers"): nearest source pixel, out[n][y][x] = in[n][floor(y*h/oh)][floor(x*w/ow)]. */
+extern "C" int psbo_budget_resample(const uint8_t* in, int32_t n, int32_t h, int32_t w, int32_t oh, int32_t ow,
+                                    uint8_t* out)
+{
+    if (!in || !out || n <= 0 || h <= 0 || w <= 0 || oh <= 0 || ow <= 0) return PSBO_ERR_ARG;
+    for (int32_t b = 0; b < n; ++b)
+        for (int32_t y = 0; y < oh; ++y)
+            for (int32_t x = 0; x < ow; ++x) {
+                const int64_t sy = (int64_t)y * h / oh, sx = (int64_t)x * w / ow;
+                out[((int64_t)b * oh + y) * ow + x] = in[((int64_t)b * h + sy) * w + sx];
+            }
+    return PSBO_OK;
+}
+
 extern "C" int psbo_num_threads(void)
 {
 #ifdef _OPENMP

@@ -145,6 +145,23 @@ int psbo_rescale(const int32_t* acc, int32_t n, int32_t oc, int32_t spatial,
                  int32_t S_uniform, int32_t s_max, const uint8_t* budget_to,
                  int32_t e_min, const float* mult, const float* bias, float* y);
 
+/* Glue between the layers of a network (suppl. "ReLU, Batch-Norm, and Pooling", "Activations and
+ * Accumulation"); every floating-point step is one binary32 round-to-nearest-even operation.
+ *
+ * psbo_requantize: x_out[i] = clamp(rint(g(y[i] [+ r[i]]) * inv_step), lo, hi), g = max(.,0) when relu != 0,
+ * r = res_f32 or (float)res_i8 * res_step (at most one of the two may be given); rint rounds ties to even.
+ * psbo_maxpool_i8: NCHW max-pooling on int8, padding positions excluded (needs 2*pad <= kernel).
+ * psbo_avgpool_requantize: out[n][c] = clamp(rint(((float)sum * fl(1/(h*w))) * scale), lo, hi).
+ * psbo_budget_resample: nearest-pixel resampling of a budget map, source index floor(y*h/oh).          */
+int psbo_requantize(const float* y, const float* res_f32, const int8_t* res_i8, float res_step,
+                    int relu, float inv_step, int32_t lo, int32_t hi, int64_t n, int8_t* x_out);
+int psbo_maxpool_i8(const int8_t* x, int32_t n, int32_t c, int32_t h, int32_t w, int32_t kh, int32_t kw,
+                    int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int8_t* out);
+int psbo_avgpool_requantize(const int8_t* x, int32_t n, int32_t c, int32_t h, int32_t w, float scale,
+                            int32_t lo, int32_t hi, int8_t* out);
+int psbo_budget_resample(const uint8_t* in, int32_t n, int32_t h, int32_t w, int32_t oh, int32_t ow,
+                         uint8_t* out);
+
 /* Number of host threads the layer functions spread output elements over. */
 int psbo_num_threads(void);
 
