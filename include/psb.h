@@ -219,6 +219,36 @@ int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, c
                                   uint32_t layer_id, int32_t* acc_dev, float* y_dev, const float* mult_dev,
                                   const float* bias_dev, void* hip_stream);
 
+/*
+ * Glue between the layers of a network [suppl. "ReLU, Batch-Norm, and Pooling": ReLU is a gate on the
+ * sign bit, max-pooling needs comparators, the factor of an average pooling can be a fixed multiplication;
+ * suppl. "Activations and Accumulation": activations are stored as fixed-point integers].  The affine map of
+ * a folded batch normalisation is the mult/bias of the layer calls.  All pointers are device pointers; the
+ * calls are asynchronous on hip_stream.  Every floating-point step is one binary32 round-to-nearest-even
+ * operation in the order written, so the integers do not depend on compiler or launch shape.
+ *
+ * psb_requantize: layer output to the next layer's activations,
+ *     x[i] = clamp( rint( g( y[i] [+ r[i]] ) * inv_step ), lo, hi ),   rint: ties to even,
+ *     g = max(., 0) if relu != 0 (NaN -> 0), else identity;
+ *     r = res_f32[i], or (float)res_i8[i] * res_step (one rounded multiplication); at most one of the two
+ *     residual operands may be non-NULL (VALUE otherwise); -128 <= lo <= hi <= 127; n > 0 elements.
+ * psb_maxpool2d_i8: NCHW int8 max-pooling; positions in the padding do not take part; needs 2*pad <= kernel
+ *     (SHAPE otherwise).  out is [n][c][OH][OW] with the OH/OW rule of psb_conv_geom.
+ * psb_global_avgpool_requantize: out[n][c] = clamp( rint( ((float)sum * fl(1/(h*w))) * scale ), lo, hi ),
+ *     sum = exact integer sum over the h*w positions (h*w <= 2^23).
+ * psb_budget_resample: a budget map at another resolution [Sect. 4.5: the two kinds of regions separate the
+ *     activations on all layers], out[n][y][x] = in[n][floor(y*h/oh)][floor(x*w/ow)].
+ */
+int psb_requantize(const float* y_dev, const float* res_f32_dev, const int8_t* res_i8_dev, float res_step,
+                   int32_t relu, float inv_step, int32_t lo, int32_t hi, int64_t n, int8_t* x_dev, void* hip_stream);
+int psb_maxpool2d_i8(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, int32_t kh, int32_t kw,
+                     int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int8_t* out_dev,
+                     void* hip_stream);
+int psb_global_avgpool_requantize(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, float scale,
+                                  int32_t lo, int32_t hi, int8_t* out_dev, void* hip_stream);
+int psb_budget_resample(const uint8_t* in_dev, int32_t n, int32_t h, int32_t w, int32_t oh, int32_t ow,
+                        uint8_t* out_dev, void* hip_stream);
+
 /* The hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
 int psb_last_device_error(void);
 

@@ -14,6 +14,7 @@ DEPS = [SRC,
         os.path.join(HERE, "csrc", "psb_kernels_oc.hip.h"),
         os.path.join(HERE, "csrc", "psb_kernels_list.hip.h"),
         os.path.join(HERE, "csrc", "psb_kernels_shared.hip.h"),
+        os.path.join(HERE, "csrc", "psb_kernels_glue.hip.h"),
         os.path.join(HERE, "csrc", "psb_philox.hip.h"),
         os.path.join(os.path.dirname(HERE), "include", "psb.h")]
 

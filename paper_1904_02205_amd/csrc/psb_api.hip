@@ -14,6 +14,7 @@
 #include "psb_kernels_oc.hip.h"
 #include "psb_kernels_list.hip.h"
 #include "psb_kernels_shared.hip.h"
+#include "psb_kernels_glue.hip.h"
 
 // Device memory of the shared-filter mode; allocated on first use, grown on demand, owned by the handle.
 struct shared_workspace {
@@ -601,6 +602,82 @@ int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, c
     if (!q || !x_dev || !geom || !budget_to_dev || !acc_dev) return PSB_ERR_NULL;
     return launch_shared(q, x_dev, geom, 0, budget_to_dev, budget_from_dev, seed, layer_id, acc_dev, y_dev, mult_dev,
                          bias_dev, (hipStream_t)hip_stream);
+}
+
+// ---- glue between layers ------------------------------------------------------------------------------
+
+int psb_requantize(const float* y_dev, const float* res_f32_dev, const int8_t* res_i8_dev, float res_step, int32_t relu,
+                   float inv_step, int32_t lo, int32_t hi, int64_t n, int8_t* x_dev, void* hip_stream)
+{
+    if (!y_dev || !x_dev) return PSB_ERR_NULL;
+    if (n <= 0) return PSB_ERR_SHAPE;
+    if (res_f32_dev && res_i8_dev) return PSB_ERR_VALUE;
+    if (lo < -128 || hi > 127 || lo > hi) return PSB_ERR_VALUE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const uintptr_t bits = (uintptr_t)y_dev | (uintptr_t)res_f32_dev;
+    const bool vec = (bits & 15u) == 0 && (((uintptr_t)res_i8_dev | (uintptr_t)x_dev) & 3u) == 0;
+    const int64_t work = vec ? (n + 3) / 4 : n;
+    const int blocks = (int)std::min<int64_t>((work + 255) / 256, 16384);
+    if (vec)
+        hipLaunchKernelGGL(psb::k_requantize<true>, dim3(blocks), dim3(256), 0, stream, y_dev, res_f32_dev, res_i8_dev,
+                           res_step, (int)relu, inv_step, (float)lo, (float)hi, n, x_dev);
+    else
+        hipLaunchKernelGGL(psb::k_requantize<false>, dim3(blocks), dim3(256), 0, stream, y_dev, res_f32_dev, res_i8_dev,
+                           res_step, (int)relu, inv_step, (float)lo, (float)hi, n, x_dev);
+    PSB_HIP_TRY(hipGetLastError());
+    return PSB_OK;
+}
+
+int psb_maxpool2d_i8(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, int32_t kh, int32_t kw,
+                     int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int8_t* out_dev, void* hip_stream)
+{
+    if (!x_dev || !out_dev) return PSB_ERR_NULL;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 ||
+        pad_w < 0)
+        return PSB_ERR_SHAPE;
+    // every window must contain at least one position of the image
+    if (2 * (int64_t)pad_h > kh || 2 * (int64_t)pad_w > kw || (int64_t)h + 2ll * pad_h < kh ||
+        (int64_t)w + 2ll * pad_w < kw)
+        return PSB_ERR_SHAPE;
+    const int64_t OH = ((int64_t)h + 2ll * pad_h - kh) / stride_h + 1, OW = ((int64_t)w + 2ll * pad_w - kw) / stride_w + 1;
+    const int64_t images = (int64_t)n * c;
+    if (images * h * w >= (1ll << 40) || OH > 2147483647ll || OW > 2147483647ll) return PSB_ERR_TOO_LARGE;
+    const int64_t total = images * OH * OW;
+    const int blocks = (int)std::min<int64_t>((total + 255) / 256, 65536);
+    hipLaunchKernelGGL(psb::k_maxpool_i8, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, x_dev, images, h, w, kh, kw,
+                       stride_h, stride_w, pad_h, pad_w, (int)OH, (int)OW, out_dev);
+    PSB_HIP_TRY(hipGetLastError());
+    return PSB_OK;
+}
+
+int psb_global_avgpool_requantize(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, float scale,
+                                  int32_t lo, int32_t hi, int8_t* out_dev, void* hip_stream)
+{
+    if (!x_dev || !out_dev) return PSB_ERR_NULL;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return PSB_ERR_SHAPE;
+    if ((int64_t)h * w > (1 << 23)) return PSB_ERR_TOO_LARGE;     // the int32 sum and its conversion stay exact
+    if (lo < -128 || hi > 127 || lo > hi) return PSB_ERR_VALUE;
+    const int64_t images = (int64_t)n * c;
+    const int64_t blocks = (images + 3) / 4;
+    if (blocks > 2147483647ll) return PSB_ERR_TOO_LARGE;
+    const float inv_count = 1.0f / (float)(h * w);                 // correctly rounded division on the host
+    hipLaunchKernelGGL(psb::k_avgpool_requantize, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream, x_dev,
+                       images, h * w, inv_count, scale, (float)lo, (float)hi, out_dev);
+    PSB_HIP_TRY(hipGetLastError());
+    return PSB_OK;
+}
+
+int psb_budget_resample(const uint8_t* in_dev, int32_t n, int32_t h, int32_t w, int32_t oh, int32_t ow,
+                        uint8_t* out_dev, void* hip_stream)
+{
+    if (!in_dev || !out_dev) return PSB_ERR_NULL;
+    if (n <= 0 || h <= 0 || w <= 0 || oh <= 0 || ow <= 0) return PSB_ERR_SHAPE;
+    const int64_t total = (int64_t)n * oh * ow;
+    const int blocks = (int)std::min<int64_t>((total + 255) / 256, 65536);
+    hipLaunchKernelGGL(psb::k_budget_resample, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, in_dev, n, h, w, oh,
+                       ow, out_dev);
+    PSB_HIP_TRY(hipGetLastError());
+    return PSB_OK;
 }
 
 }  // extern "C"

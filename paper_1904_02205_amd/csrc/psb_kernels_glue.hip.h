@@ -1,0 +1,124 @@
+// Glue between the layers of a network (suppl. "ReLU, Batch-Norm, and Pooling": ReLU is a gate on the sign,
+// max-pooling needs comparators, the factor of an average pooling is a fixed multiplication; suppl.
+// "Activations and Accumulation": activations are stored as fixed-point integers).  All of these are
+// streaming kernels bound by HBM bandwidth.  Every floating-point step is one binary32 operation rounded
+// to nearest even (__f*_rn intrinsics: no contraction, no reassociation), in a fixed order, so that the
+// integers that come out do not depend on the compiler.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace psb {
+
+// clamp(rint(v), lo, hi) as an integer; NaN goes to lo
+__device__ __forceinline__ int32_t round_clamp(float v, float lo, float hi)
+{
+    float q = rintf(v);               // v_rndne_f32: ties to even
+    if (!(q >= lo)) q = lo;
+    if (q > hi) q = hi;
+    return (int32_t)q;
+}
+
+__device__ __forceinline__ int32_t requantize_one(float y, bool has_res, float r, bool relu, float inv_step, float lo,
+                                                  float hi)
+{
+    float t = y;
+    if (has_res) t = __fadd_rn(t, r);
+    if (relu && !(t > 0.0f)) t = 0.0f;
+    return round_clamp(__fmul_rn(t, inv_step), lo, hi);
+}
+
+// Four elements per thread when every pointer is 16-byte (int8: 4-byte) aligned, else one.
+template <bool VEC>
+__global__ void __launch_bounds__(256) k_requantize(const float* __restrict__ y, const float* __restrict__ res_f32,
+                                                    const int8_t* __restrict__ res_i8, float res_step, int relu,
+                                                    float inv_step, float lo, float hi, int64_t n,
+                                                    int8_t* __restrict__ out)
+{
+    const bool has_res = res_f32 || res_i8;
+    if (VEC) {
+        const int64_t n4 = n >> 2;
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) {
+            const float4 v = reinterpret_cast<const float4*>(y)[i];
+            float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (res_f32) r = reinterpret_cast<const float4*>(res_f32)[i];
+            if (res_i8) {
+                const uint32_t b = reinterpret_cast<const uint32_t*>(res_i8)[i];
+                r.x = __fmul_rn((float)(int8_t)(b & 0xFFu), res_step);
+                r.y = __fmul_rn((float)(int8_t)((b >> 8) & 0xFFu), res_step);
+                r.z = __fmul_rn((float)(int8_t)((b >> 16) & 0xFFu), res_step);
+                r.w = __fmul_rn((float)(int8_t)(b >> 24), res_step);
+            }
+            const uint32_t q0 = (uint32_t)requantize_one(v.x, has_res, r.x, relu, inv_step, lo, hi) & 0xFFu;
+            const uint32_t q1 = (uint32_t)requantize_one(v.y, has_res, r.y, relu, inv_step, lo, hi) & 0xFFu;
+            const uint32_t q2 = (uint32_t)requantize_one(v.z, has_res, r.z, relu, inv_step, lo, hi) & 0xFFu;
+            const uint32_t q3 = (uint32_t)requantize_one(v.w, has_res, r.w, relu, inv_step, lo, hi) & 0xFFu;
+            reinterpret_cast<uint32_t*>(out)[i] = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+        }
+    }
+    // whole array (scalar kernel) or the last n mod 4 elements (vector kernel)
+    const int64_t first = VEC ? (n & ~(int64_t)3) : 0;
+    for (int64_t i = first + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        float r = 0.f;
+        if (res_f32) r = res_f32[i];
+        if (res_i8) r = __fmul_rn((float)res_i8[i], res_step);
+        out[i] = (int8_t)requantize_one(y[i], has_res, r, relu, inv_step, lo, hi);
+    }
+}
+
+// One output element per thread; positions in the padding do not take part.
+__global__ void __launch_bounds__(256) k_maxpool_i8(const int8_t* __restrict__ x, int64_t images, int H, int W, int KH,
+                                                    int KW, int stride_h, int stride_w, int pad_h, int pad_w, int OH,
+                                                    int OW, int8_t* __restrict__ out)
+{
+    const int64_t total = images * OH * OW;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int ox = (int)(i % OW);
+        const int oy = (int)((i / OW) % OH);
+        const int64_t img = i / ((int64_t)OW * OH);
+        const int8_t* src = x + img * H * W;
+        int best = -128;
+        for (int dy = 0; dy < KH; ++dy) {
+            const int iy = oy * stride_h - pad_h + dy;
+            if ((unsigned)iy >= (unsigned)H) continue;
+            for (int dx = 0; dx < KW; ++dx) {
+                const int ix = ox * stride_w - pad_w + dx;
+                if ((unsigned)ix >= (unsigned)W) continue;
+                best = max(best, (int)src[(int64_t)iy * W + ix]);
+            }
+        }
+        out[i] = (int8_t)best;
+    }
+}
+
+// One wave per (n, c) image: exact int32 sum, then two rounded multiplications.
+__global__ void __launch_bounds__(256) k_avgpool_requantize(const int8_t* __restrict__ x, int64_t images, int HW,
+                                                            float inv_count, float scale, float lo, float hi,
+                                                            int8_t* __restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t img = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (img >= images) return;      // wave-uniform
+    const int8_t* src = x + img * HW;
+    int32_t sum = 0;
+    for (int i = lane; i < HW; i += 64) sum += src[i];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    if (lane == 0) out[img] = (int8_t)round_clamp(__fmul_rn(__fmul_rn(__int2float_rn(sum), inv_count), scale), lo, hi);
+}
+
+// out[n][y][x] = in[n][floor(y*H/OH)][floor(x*W/OW)]
+__global__ void __launch_bounds__(256) k_budget_resample(const uint8_t* __restrict__ in, int N, int H, int W, int OH,
+                                                         int OW, uint8_t* __restrict__ out)
+{
+    const int64_t total = (int64_t)N * OH * OW;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int ox = (int)(i % OW);
+        const int oy = (int)((i / OW) % OH);
+        const int64_t n = i / ((int64_t)OW * OH);
+        const int64_t sy = (int64_t)oy * H / OH, sx = (int64_t)ox * W / OW;
+        out[i] = in[(n * H + sy) * W + sx];
+    }
+}
+
+}  // namespace psb

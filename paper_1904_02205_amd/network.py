@@ -1,0 +1,92 @@
+"""A ResNet-18-shaped network run end to end through the C-ABI library: every convolution and the
+classifier are stochastically binarized layers (Sect. 3.1), the affine map of the folded batch
+normalisation (Sect. 3, Eq. 2) is the mult/bias of the layer call, and the glue between layers (ReLU,
+requantisation to 8-bit activations, residual addition, max- and average-pooling; suppl. "ReLU,
+Batch-Norm, and Pooling") runs in the library's glue kernels.  Nothing is computed in Python or PyTorch:
+this file only orders the calls and owns the device buffers.
+
+Sample budgets: either one sample count S for the whole network, or a per-pixel budget map at any
+resolution, which is resampled to the output resolution of every convolution (Sect. 4.5: the regions
+separate the activations "on all layers"); the classifier then uses `s_fc` samples.
+"""
+import numpy as np
+import torch
+
+from . import psb
+from . import resnet_synth as rs
+
+
+class ResNet18:
+    def __init__(self, net: rs.Net, s_max=16, prob_bits=23, seed=3, device="cuda"):
+        self.net, self.seed, self.device, self.s_max = net, seed, device, s_max
+        self.q, self.mult, self.bias = [], [], []
+        self.names = [s.name for s in net.specs]
+        step_in = self._input_steps()
+        for i, sp in enumerate(net.specs):
+            w = torch.from_numpy(net.weights[i]).to(device)
+            q = psb.Weights(w, x_absmax=127, s_max=s_max, prob_bits=prob_bits)
+            # 2^e_min * step is exact (a power of two times a binary32 number); one rounded product with the scale
+            unit = np.float32(np.float32(step_in[i]) * np.float32(2.0) ** q.e_min)
+            self.q.append(q)
+            self.mult.append(torch.from_numpy((net.ch_scale[i] * unit).astype(np.float32)).to(device))
+            self.bias.append(torch.from_numpy(net.ch_bias[i]).to(device))
+        self.x0 = torch.from_numpy(net.x0).to(device)
+
+    def _input_steps(self):
+        """Real value of one integer step of each layer's input activations."""
+        steps = []
+        for i, name in enumerate(self.names):
+            if name == "conv1":
+                steps.append(rs.STEP_INPUT)
+            elif name.endswith("c2"):
+                steps.append(rs.STEP_RELU)
+            elif name.startswith("s1b0"):
+                steps.append(rs.STEP_RELU)          # straight after the max-pool
+            else:
+                steps.append(rs.STEP_BLOCK)         # block inputs and the classifier
+        return steps
+
+    def _conv(self, i, x, S, budget, shared):
+        sp = self.net.specs[i]
+        n, _, h, w = x.shape
+        oh = (h + 2 * sp.pad - sp.k) // sp.stride + 1
+        y = torch.empty((n, sp.cout, oh, oh), dtype=torch.float32, device=self.device)
+        acc = torch.empty((n, sp.cout, oh, oh), dtype=torch.int32, device=self.device)
+        kw = dict(stride=(sp.stride, sp.stride), pad=(sp.pad, sp.pad), seed=self.seed, layer_id=i, acc=acc, y=y,
+                  mult=self.mult[i], bias=self.bias[i], shared=shared)
+        if budget is None:
+            psb.conv2d(self.q[i], x, S, **kw)
+        else:
+            psb.conv2d_progressive(self.q[i], x, psb.budget_resample(budget, oh, oh), None, **kw)
+        return y
+
+    def forward(self, S=8, budget=None, s_fc=None, shared=False, collect=None):
+        """Logits float32 [batch, classes].  collect: optional list that receives every int8 activation tensor."""
+        keep = (lambda t: collect.append(t)) if collect is not None else (lambda t: None)
+        inv_relu, inv_block = float(np.float32(1.0 / rs.STEP_RELU)), float(np.float32(1.0 / rs.STEP_BLOCK))
+        a = psb.requantize(self._conv(0, self.x0, S, budget, shared), inv_relu)
+        keep(a)
+        a = psb.maxpool2d_i8(a, (3, 3), (2, 2), (1, 1))
+        keep(a)
+        step_a = rs.STEP_RELU
+        i = 1
+        while self.names[i] != "fc":
+            has_sc = self.names[i + 2].endswith("sc")
+            a1 = psb.requantize(self._conv(i, a, S, budget, shared), inv_relu)
+            keep(a1)
+            y2 = self._conv(i + 1, a1, S, budget, shared)
+            if has_sc:
+                a = psb.requantize(y2, inv_block, res_f32=self._conv(i + 2, a, S, budget, shared))
+            else:
+                a = psb.requantize(y2, inv_block, res_i8=a, res_step=float(np.float32(step_a)))
+            keep(a)
+            step_a = rs.STEP_BLOCK
+            i += 3 if has_sc else 2
+        pooled = psb.global_avgpool_requantize(a, 1.0)
+        keep(pooled)
+        n = pooled.shape[0]
+        logits = torch.empty((n, self.net.specs[i].cout), dtype=torch.float32, device=self.device)
+        acc = torch.empty((n, self.net.specs[i].cout), dtype=torch.int32, device=self.device)
+        psb.linear(self.q[i], pooled, s_fc if s_fc is not None else S, seed=self.seed, layer_id=i, acc=acc, y=logits,
+                   mult=self.mult[i], bias=self.bias[i], shared=shared)
+        return logits

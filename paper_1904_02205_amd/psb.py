@@ -21,6 +21,7 @@ MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE, MAPPING_PRODUCT_LIST = 0
 SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
            "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
+           "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
            "psb_last_device_error", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
            "psb_profile_read"]
 
@@ -77,6 +78,11 @@ def lib():
         L.psb_linear_shared.argtypes = L.psb_linear.argtypes
         L.psb_conv2d_shared.argtypes = L.psb_conv2d.argtypes
         L.psb_conv2d_progressive_shared.argtypes = L.psb_conv2d_progressive.argtypes
+        f32 = C.c_float
+        L.psb_requantize.argtypes = [vp, vp, vp, f32, i32, f32, i32, i32, C.c_int64, vp, vp]
+        L.psb_maxpool2d_i8.argtypes = [vp] + [i32] * 10 + [vp, vp]
+        L.psb_global_avgpool_requantize.argtypes = [vp, i32, i32, i32, i32, f32, i32, i32, vp, vp]
+        L.psb_budget_resample.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
         L.psb_last_device_error.argtypes = []
         L.psb_set_mapping.argtypes = [C.c_int]
         L.psb_query_mapping.argtypes = [vp, C.POINTER(ConvGeom)]
@@ -234,3 +240,47 @@ def conv2d_progressive(q, x, budget_to, budget_from=None, stride=(1, 1), pad=(0,
             _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
     _check(rc, "psb_conv2d_progressive_shared" if shared else "psb_conv2d_progressive")
     return acc
+
+
+# ---- glue between layers ---------------------------------------------------------------------------------
+
+def requantize(y, inv_step, relu=True, lo=0, hi=127, res_f32=None, res_i8=None, res_step=0.0, out=None):
+    """int8 tensor of y's shape: clamp(rint(g(y [+ r]) * inv_step), lo, hi)."""
+    if out is None:
+        out = torch.empty(y.shape, dtype=torch.int8, device=y.device)
+    rc = lib().psb_requantize(_ptr(y, torch.float32, "y"), _ptr(res_f32, torch.float32, "res_f32"),
+                              _ptr(res_i8, torch.int8, "res_i8"), res_step, 1 if relu else 0, inv_step, lo, hi,
+                              y.numel(), _ptr(out, torch.int8, "out"), _stream())
+    _check(rc, "psb_requantize")
+    return out
+
+
+def maxpool2d_i8(x, kernel, stride, pad, out=None):
+    n, c, h, w = x.shape
+    oh, ow = (h + 2 * pad[0] - kernel[0]) // stride[0] + 1, (w + 2 * pad[1] - kernel[1]) // stride[1] + 1
+    if out is None:
+        out = torch.empty((n, c, max(oh, 0), max(ow, 0)), dtype=torch.int8, device=x.device)
+    rc = lib().psb_maxpool2d_i8(_ptr(x, torch.int8, "x"), n, c, h, w, kernel[0], kernel[1], stride[0], stride[1],
+                                pad[0], pad[1], C.c_void_p(out.data_ptr()), _stream())
+    _check(rc, "psb_maxpool2d_i8")
+    return out
+
+
+def global_avgpool_requantize(x, scale, lo=0, hi=127, out=None):
+    n, c, h, w = x.shape
+    if out is None:
+        out = torch.empty((n, c), dtype=torch.int8, device=x.device)
+    rc = lib().psb_global_avgpool_requantize(_ptr(x, torch.int8, "x"), n, c, h, w, scale, lo, hi,
+                                             _ptr(out, torch.int8, "out"), _stream())
+    _check(rc, "psb_global_avgpool_requantize")
+    return out
+
+
+def budget_resample(b, oh, ow, out=None):
+    n, h, w = b.shape
+    if out is None:
+        out = torch.empty((n, oh, ow), dtype=torch.uint8, device=b.device)
+    rc = lib().psb_budget_resample(_ptr(b, torch.uint8, "budget"), n, h, w, oh, ow, _ptr(out, torch.uint8, "out"),
+                                   _stream())
+    _check(rc, "psb_budget_resample")
+    return out

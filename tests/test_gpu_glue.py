@@ -1,0 +1,124 @@
+"""Glue kernels between layers vs the CPU oracle (bit-exact integers), and the ResNet-18-shaped network
+chained end to end through the C-ABI vs the same chain on the oracle."""
+import numpy as np
+import pytest
+
+import oracle_network
+from paper_1904_02205_amd import resnet_synth as rs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def psb():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_1904_02205_amd import psb as m
+    m.lib()
+    m.set_mapping(m.MAPPING_AUTO)
+    return m
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 1023, 4096, 100003])
+def test_requantize(psb, orc, n):
+    import torch
+    rng = np.random.default_rng(n)
+    y = (rng.standard_normal(n) * 2).astype(np.float32)
+    y[: min(n, 8)] = np.array([0.5, 1.5, 2.5, -0.5, np.nan, np.inf, -np.inf, 1e30], np.float32)[: min(n, 8)]
+    r = (rng.standard_normal(n) * 2).astype(np.float32)
+    ri = rng.integers(-128, 128, size=n).astype(np.int8)
+    inv, step = np.float32(127.0 / 6.0), np.float32(4.0 / 127.0)
+    yd, rd, rid = (torch.from_numpy(a).cuda() for a in (y, r, ri))
+    for kw_o, kw_g in ((dict(), dict()),
+                       (dict(res_f32=r), dict(res_f32=rd)),
+                       (dict(res_i8=ri, res_step=step), dict(res_i8=rid, res_step=float(step))),
+                       (dict(relu=False, lo=-127, hi=127), dict(relu=False, lo=-127, hi=127)),
+                       (dict(relu=False, lo=-128, hi=5, res_f32=r), dict(relu=False, lo=-128, hi=5, res_f32=rd))):
+        ref = orc.requantize(y, inv, **kw_o)
+        got = psb.requantize(yd, float(inv), **kw_g).cpu().numpy()
+        assert np.array_equal(got, ref), kw_o.keys()
+    if n > 8:       # pointers that are not 16-byte aligned take the one-element-per-thread kernel
+        ref = orc.requantize(y[1:], inv, res_f32=r[1:])
+        out = torch.empty(n, dtype=torch.int8, device="cuda")
+        got = psb.requantize(yd[1:], float(inv), res_f32=rd[1:], out=out[1:]).cpu().numpy()
+        assert np.array_equal(got, ref)
+
+
+def test_requantize_errors(psb):
+    import torch
+    y = torch.zeros(8, device="cuda")
+    r8 = torch.zeros(8, dtype=torch.int8, device="cuda")
+    for kw in (dict(lo=-129), dict(hi=128), dict(lo=5, hi=4), dict(res_f32=y, res_i8=r8)):
+        with pytest.raises(psb.PsbError) as ei:
+            psb.requantize(y, 1.0, **kw)
+        assert ei.value.code == psb.ERR_VALUE
+
+
+@pytest.mark.parametrize("geom", [((3, 3), (2, 2), (1, 1), 112, 112), ((2, 2), (2, 2), (0, 0), 8, 8),
+                                  ((3, 2), (1, 2), (1, 0), 5, 7), ((1, 1), (1, 1), (0, 0), 4, 4),
+                                  ((3, 3), (2, 2), (1, 1), 9, 11)])
+def test_maxpool(psb, orc, geom):
+    import torch
+    kernel, stride, pad, h, w = geom
+    x = np.random.default_rng(h * w).integers(-128, 128, size=(3, 5, h, w)).astype(np.int8)
+    got = psb.maxpool2d_i8(torch.from_numpy(x).cuda(), kernel, stride, pad).cpu().numpy()
+    assert np.array_equal(got, orc.maxpool_i8(x, kernel, stride, pad))
+
+
+def test_maxpool_refuses_windows_that_can_lie_in_the_padding(psb):
+    import torch
+    with pytest.raises(psb.PsbError) as ei:
+        psb.maxpool2d_i8(torch.zeros((1, 1, 8, 8), dtype=torch.int8, device="cuda"), (2, 2), (2, 2), (2, 2))
+    assert ei.value.code == psb.ERR_SHAPE
+
+
+@pytest.mark.parametrize("shape", [(4, 16, 7, 7), (1, 3, 1, 1), (2, 70, 9, 13), (3, 1, 64, 64)])
+def test_global_avgpool(psb, orc, shape):
+    import torch
+    rng = np.random.default_rng(shape[1])
+    x = rng.integers(-128, 128, size=shape).astype(np.int8)
+    for scale, lo, hi in ((1.0, 0, 127), (0.731, -128, 127), (3.5, -20, 20)):
+        got = psb.global_avgpool_requantize(torch.from_numpy(x).cuda(), scale, lo, hi).cpu().numpy()
+        assert np.array_equal(got, orc.avgpool_requantize(x, scale, lo, hi))
+
+
+def test_budget_resample(psb, orc):
+    import torch
+    b = np.random.default_rng(7).integers(0, 33, size=(3, 7, 9)).astype(np.uint8)
+    for oh, ow in ((7, 9), (14, 18), (3, 5), (56, 56), (1, 1)):
+        got = psb.budget_resample(torch.from_numpy(b).cuda(), oh, ow).cpu().numpy()
+        assert np.array_equal(got, orc.budget_resample(b, oh, ow))
+
+
+# ------------------------------------------------------------------ the chained network
+
+def _compare(psb, orc, net, prob_bits=23, **kw):
+    from paper_1904_02205_amd import network
+    ref_acts, got_acts = [], []
+    ref = oracle_network.OracleResNet18(orc, net, prob_bits=prob_bits).forward(collect=ref_acts, **kw)
+    model = network.ResNet18(net, prob_bits=prob_bits)
+    kw_g = dict(kw)
+    if kw_g.get("budget") is not None:
+        import torch
+        kw_g["budget"] = torch.from_numpy(kw_g["budget"]).cuda()
+    got = model.forward(collect=got_acts, **kw_g).cpu().numpy()
+    assert len(ref_acts) == len(got_acts)
+    for i, (r, g) in enumerate(zip(ref_acts, got_acts)):        # the first differing activation names the layer
+        assert np.array_equal(g.cpu().numpy(), r), f"activation {i} of {len(ref_acts)} differs"
+    assert np.array_equal(got, ref)                               # fp32 logits, bit for bit
+    return got
+
+
+def test_network_end_to_end(psb, orc):
+    net = rs.resnet18(batch=2, hw=64, width=32, classes=10)
+    a = _compare(psb, orc, net, S=8)
+    b = _compare(psb, orc, net, S=8, shared=True)
+    assert not np.array_equal(a, b)
+    _compare(psb, orc, net, prob_bits=4, S=16)
+
+
+def test_network_with_a_budget_map_on_all_layers(psb, orc):
+    net = rs.resnet18(batch=2, hw=64, width=32, classes=10)
+    budget = np.random.default_rng(5).choice([8, 16], size=(2, 2, 2), p=[0.65, 0.35]).astype(np.uint8)
+    _compare(psb, orc, net, budget=budget, s_fc=16)
+    _compare(psb, orc, net, budget=budget, s_fc=16, shared=True)
