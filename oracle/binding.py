@@ -83,6 +83,9 @@ def lib():
         L.psbo_avgpool_requantize.restype = C.c_int
         L.psbo_budget_resample.argtypes = [C.c_void_p] + [C.c_int32] * 5 + [C.c_void_p]
         L.psbo_budget_resample.restype = C.c_int
+        L.psbo_attention_budget.argtypes = [C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                            C.c_uint8, C.c_uint8, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.psbo_attention_budget.restype = C.c_int
         L.psbo_num_threads.argtypes = []
         L.psbo_num_threads.restype = C.c_int
         _lib = L
@@ -345,3 +348,17 @@ def budget_resample(b, oh, ow):
     if rc != OK:
         raise OracleError(rc)
     return out
+
+
+def attention_budget(act, step, lo, hi):
+    """(entropy float32 [n,h,w], mean float32 [n], budget uint8 [n,h,w]) from int8 activations [n,c,h,w]."""
+    act = np.ascontiguousarray(act, dtype=np.int8)
+    n, c, h, w = act.shape
+    ent = np.zeros((n, h, w), dtype=np.float32)
+    mean = np.zeros(n, dtype=np.float32)
+    bud = np.zeros((n, h, w), dtype=np.uint8)
+    rc = lib().psbo_attention_budget(_ptr(act), float(np.float32(step)), n, c, h, w, int(lo), int(hi), _ptr(ent),
+                                     _ptr(mean), _ptr(bud))
+    if rc != OK:
+        raise OracleError(rc)
+    return ent, mean, bud

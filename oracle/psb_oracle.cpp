@@ -593,6 +593,48 @@ extern "C" int psbo_budget_resample(const uint8_t* in, int32_t n, int32_t h, int
     return PSBO_OK;
 }
 
+/* ---------------------------------------------------------------------------
+ * Attention mask (Sect. 4.5): the pixelwise entropy of the softmax over the
+ * channels of the last convolutional layer,
+ *     h_xy = sum_c - softmax(a_xyc) * log(softmax(a_xyc)),
+ * thresholded at the mean entropy of the image: pixels above the mean are the
+ * regions that get the larger sample count.  a = (double)act * step.
+ * Evaluated in binary64; the entropy handed out, the mean and the comparison
+ * are binary32 (the precision the GPU kernel decides in).
+ * ------------------------------------------------------------------------- */
+extern "C" int psbo_attention_budget(const int8_t* act, float step, int32_t n, int32_t c, int32_t h, int32_t w,
+                                     uint8_t budget_lo, uint8_t budget_hi, float* entropy, float* mean,
+                                     uint8_t* budget)
+{
+    if (!act || !entropy || !budget || n <= 0 || c <= 0 || h <= 0 || w <= 0) return PSBO_ERR_ARG;
+    const int64_t hw = (int64_t)h * w;
+    for (int32_t b = 0; b < n; ++b) {
+        double total = 0.0;
+        for (int64_t px = 0; px < hw; ++px) {
+            double zmax = -1e300;
+            for (int32_t ch = 0; ch < c; ++ch) {
+                const double z = (double)act[((int64_t)b * c + ch) * hw + px] * (double)step;
+                if (z > zmax) zmax = z;
+            }
+            double Z = 0.0;
+            for (int32_t ch = 0; ch < c; ++ch)
+                Z += std::exp((double)act[((int64_t)b * c + ch) * hw + px] * (double)step - zmax);
+            double ent = 0.0;
+            for (int32_t ch = 0; ch < c; ++ch) {
+                const double z = (double)act[((int64_t)b * c + ch) * hw + px] * (double)step - zmax;
+                const double p = std::exp(z) / Z;
+                if (p > 0.0) ent -= p * std::log(p);
+            }
+            entropy[b * hw + px] = (float)ent;
+            total += (double)(float)ent;
+        }
+        const float m = (float)(total / (double)hw);
+        if (mean) mean[b] = m;
+        for (int64_t px = 0; px < hw; ++px) budget[b * hw + px] = entropy[b * hw + px] > m ? budget_hi : budget_lo;
+    }
+    return PSBO_OK;
+}
+
 extern "C" int psbo_num_threads(void)
 {
 #ifdef _OPENMP

@@ -162,6 +162,13 @@ int psbo_avgpool_requantize(const int8_t* x, int32_t n, int32_t c, int32_t h, in
 int psbo_budget_resample(const uint8_t* in, int32_t n, int32_t h, int32_t w, int32_t oh, int32_t ow,
                          uint8_t* out);
 
+/* Attention mask (Sect. 4.5): entropy[n][y][x] = sum_c -softmax(a)_c log softmax(a)_c over the channels of
+ * act (int8 [n][c][h][w], a = act * step), mean[n] (nullable) = mean entropy of image n, and
+ * budget[n][y][x] = budget_hi where the entropy is above the image's mean, else budget_lo.  Evaluated in
+ * binary64; the entropies handed out, the mean and the comparison are binary32.                        */
+int psbo_attention_budget(const int8_t* act, float step, int32_t n, int32_t c, int32_t h, int32_t w,
+                          uint8_t budget_lo, uint8_t budget_hi, float* entropy, float* mean, uint8_t* budget);
+
 /* Number of host threads the layer functions spread output elements over. */
 int psbo_num_threads(void);
 
