@@ -249,6 +249,21 @@ int psb_global_avgpool_requantize(const int8_t* x_dev, int32_t n, int32_t c, int
 int psb_budget_resample(const uint8_t* in_dev, int32_t n, int32_t h, int32_t w, int32_t oh, int32_t ow,
                         uint8_t* out_dev, void* hip_stream);
 
+/*
+ * Attention mask [Sect. 4.5: the pixelwise entropy of the softmax over the channels of the last
+ * convolutional layer, h_xy = sum_c -softmax(a_xyc) log softmax(a_xyc), with a hard threshold at the mean
+ * entropy of the image; the regions above the mean get the larger sample count].
+ *  act_dev      int8 [n][c][h][w], a = act * step (step > 0)
+ *  entropy_dev  float32 [n][h][w], written (evaluated in binary64 with the device library's exp/log, rounded once)
+ *  mean_dev     float32 [n] or NULL: mean entropy of each image (binary64 sum in a fixed order, rounded once)
+ *  budget_dev   uint8 [n][h][w]: budget_hi where entropy > mean (strictly), else budget_lo
+ * The map can be handed to psb_conv2d_progressive at the resolution of any layer via psb_budget_resample.
+ * Errors: NULL, SHAPE, VALUE (step not positive and finite), DEVICE.
+ */
+int psb_attention_budget(const int8_t* act_dev, float step, int32_t n, int32_t c, int32_t h, int32_t w,
+                         uint8_t budget_lo, uint8_t budget_hi, float* entropy_dev, float* mean_dev,
+                         uint8_t* budget_dev, void* hip_stream);
+
 /* The hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
 int psb_last_device_error(void);
 

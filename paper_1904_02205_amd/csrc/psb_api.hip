@@ -680,4 +680,23 @@ int psb_budget_resample(const uint8_t* in_dev, int32_t n, int32_t h, int32_t w, 
     return PSB_OK;
 }
 
+int psb_attention_budget(const int8_t* act_dev, float step, int32_t n, int32_t c, int32_t h, int32_t w,
+                         uint8_t budget_lo, uint8_t budget_hi, float* entropy_dev, float* mean_dev, uint8_t* budget_dev,
+                         void* hip_stream)
+{
+    if (!act_dev || !entropy_dev || !budget_dev) return PSB_ERR_NULL;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return PSB_ERR_SHAPE;
+    if (!(step > 0.0f) || !(step <= 1e30f)) return PSB_ERR_VALUE;
+    const int64_t HW = (int64_t)h * w;
+    const int64_t total = (int64_t)n * HW;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int blocks = (int)std::min<int64_t>((total + 255) / 256, 65536);
+    hipLaunchKernelGGL(psb::k_channel_entropy, dim3(blocks), dim3(256), 0, stream, act_dev, step, n, c, HW, entropy_dev);
+    PSB_HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(psb::k_attention_mask, dim3((unsigned)n), dim3(256), 0, stream, entropy_dev, HW, budget_lo,
+                       budget_hi, mean_dev, budget_dev);
+    PSB_HIP_TRY(hipGetLastError());
+    return PSB_OK;
+}
+
 }  // extern "C"

@@ -121,4 +121,50 @@ __global__ void __launch_bounds__(256) k_budget_resample(const uint8_t* __restri
     }
 }
 
+// Attention mask (Sect. 4.5): entropy of the softmax over the channels of the last convolutional layer,
+//     h = sum_c -p_c log p_c = log Z - (sum_c e_c z_c) / Z,   z_c = a_c*step - max_c, e_c = exp(z_c), Z = sum_c e_c.
+// One pixel per lane; a channel of neighbouring pixels is a run of neighbouring bytes.  Evaluated in binary64
+// and rounded once to binary32: sums of hundreds of binary32 terms would lose the digits the threshold
+// needs, and the work (one exp per activation of ONE layer) is negligible next to the sampling kernels.
+__global__ void __launch_bounds__(256) k_channel_entropy(const int8_t* __restrict__ act, float step, int N, int C,
+                                                         int64_t HW, float* __restrict__ entropy)
+{
+    const int64_t total = (int64_t)N * HW;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t n = i / HW, px = i - n * HW;
+        const int8_t* src = act + n * C * HW + px;
+        int amax = -128;
+        for (int c = 0; c < C; ++c) amax = max(amax, (int)src[(int64_t)c * HW]);
+        double Z = 0.0, T = 0.0;
+        for (int c = 0; c < C; ++c) {
+            const double z = (double)((int)src[(int64_t)c * HW] - amax) * (double)step;     // <= 0
+            const double e = exp(z);
+            Z += e;
+            T += e * z;
+        }
+        entropy[i] = (float)(log(Z) - T / Z);
+    }
+}
+
+// One workgroup per image: mean entropy (binary64 tree sum in a fixed order), then
+// budget = hi where the entropy is strictly above the mean, else lo.
+__global__ void __launch_bounds__(256) k_attention_mask(const float* __restrict__ entropy, int64_t HW, uint8_t lo,
+                                                        uint8_t hi, float* __restrict__ mean_out,
+                                                        uint8_t* __restrict__ budget)
+{
+    __shared__ double part[256];
+    const float* src = entropy + (int64_t)blockIdx.x * HW;
+    double s = 0.0;
+    for (int64_t i = threadIdx.x; i < HW; i += 256) s += (double)src[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
+        __syncthreads();
+    }
+    const float mean = (float)(part[0] / (double)HW);
+    if (threadIdx.x == 0 && mean_out) mean_out[blockIdx.x] = mean;
+    for (int64_t i = threadIdx.x; i < HW; i += 256) budget[(int64_t)blockIdx.x * HW + i] = src[i] > mean ? hi : lo;
+}
+
 }  // namespace psb

@@ -90,3 +90,13 @@ class ResNet18:
         psb.linear(self.q[i], pooled, s_fc if s_fc is not None else S, seed=self.seed, layer_id=i, acc=acc, y=logits,
                    mult=self.mult[i], bias=self.bias[i], shared=shared)
         return logits
+
+    def forward_attention(self, s_lo=8, s_hi=16, shared=False):
+        """The two-stage scheme of Sect. 4.5: a low-precision pass everywhere, the entropy mask of the last
+        convolutional layer, then the network again with s_hi samples inside the mask and s_lo outside, on all
+        layers.  Returns (logits, budget map uint8 [batch, h, w] at the last layer's resolution)."""
+        acts = []
+        self.forward(S=s_lo, shared=shared, collect=acts)
+        last = acts[-2]                                  # output of the last residual block
+        _, _, budget = psb.attention_budget(last, float(np.float32(rs.STEP_BLOCK)), s_lo, s_hi)
+        return self.forward(budget=budget, s_fc=s_hi, shared=shared), budget

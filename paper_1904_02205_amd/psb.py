@@ -22,7 +22,7 @@ SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "ps
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
            "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
            "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
-           "psb_last_device_error", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
+           "psb_attention_budget", "psb_last_device_error", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
            "psb_profile_read"]
 
 
@@ -83,6 +83,7 @@ def lib():
         L.psb_maxpool2d_i8.argtypes = [vp] + [i32] * 10 + [vp, vp]
         L.psb_global_avgpool_requantize.argtypes = [vp, i32, i32, i32, i32, f32, i32, i32, vp, vp]
         L.psb_budget_resample.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
+        L.psb_attention_budget.argtypes = [vp, f32, i32, i32, i32, i32, C.c_uint8, C.c_uint8, vp, vp, vp, vp]
         L.psb_last_device_error.argtypes = []
         L.psb_set_mapping.argtypes = [C.c_int]
         L.psb_query_mapping.argtypes = [vp, C.POINTER(ConvGeom)]
@@ -284,3 +285,16 @@ def budget_resample(b, oh, ow, out=None):
                                    _stream())
     _check(rc, "psb_budget_resample")
     return out
+
+
+def attention_budget(act, step, lo, hi):
+    """(entropy float32 [n,h,w], mean float32 [n], budget uint8 [n,h,w]) from int8 activations [n,c,h,w]."""
+    n, c, h, w = act.shape
+    ent = torch.empty((n, h, w), dtype=torch.float32, device=act.device)
+    mean = torch.empty((n,), dtype=torch.float32, device=act.device)
+    bud = torch.empty((n, h, w), dtype=torch.uint8, device=act.device)
+    rc = lib().psb_attention_budget(_ptr(act, torch.int8, "act"), step, n, c, h, w, lo, hi,
+                                    _ptr(ent, torch.float32, "entropy"), _ptr(mean, torch.float32, "mean"),
+                                    _ptr(bud, torch.uint8, "budget"), _stream())
+    _check(rc, "psb_attention_budget")
+    return ent, mean, bud

@@ -81,3 +81,9 @@ class OracleResNet18:
         assert over == 0
         y = orc.rescale(acc, self.q[i].e_min, S=s, s_max=self.s_max, mult=self.mult[i], bias=self.net.ch_bias[i])
         return y.reshape(n, -1)
+
+    def forward_attention(self, s_lo=8, s_hi=16, shared=False):
+        acts = []
+        self.forward(S=s_lo, shared=shared, collect=acts)
+        ent, mean, budget = self.orc.attention_budget(acts[-2], np.float32(rs.STEP_BLOCK), s_lo, s_hi)
+        return self.forward(budget=budget, s_fc=s_hi, shared=shared), budget, ent, mean
