@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the PSB layer hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5] [--prob-bits 23|1..7]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c4net|c5] [--prob-bits 23|1..7]
                     [--mode product|shared] [--no-cpu-baseline]
 
 A step is one pass of the whole hot path over one batch of synthetic input that is already resident in
@@ -91,6 +91,9 @@ def workload_layers(name):
         return [synth.config3()], "config3: progressive conv3x3 128->128 on 8x128x28x28, blob budgets {2..32}"
     if name == "c4":
         return synth.config4_layers(), "config4: 20 convs + FC of a ResNet-18 shape, batch 32, S=8 (layer inputs synthetic)"
+    if name == "c4net":
+        return None, ("config4 chained: ResNet-18-shaped network end to end, batch 32 at 224x224, S=8, with the glue "
+                      "kernels (requantise, residual, pooling) between the layers; synthetic weights and batch norm")
     if name == "c5":
         return synth.config5(), "config5: MobileNet-v2 block at 14x14, batch 64: pruned 1x1 576->160 + depthwise 3x3, S=16"
     raise SystemExit(f"unknown workload {name}")
@@ -155,6 +158,24 @@ def main():
     torch.cuda.set_device(0)
 
     layers, desc = workload_layers(args.workload)
+    model = None
+    if layers is None:
+        # the chained network: one pass records every layer's real input, which defines the work that is counted
+        from paper_1904_02205_amd import network, resnet_synth, synth
+        net = resnet_synth.resnet18(batch=32, hw=224, width=64, classes=1000, device=dev)
+        model = network.ResNet18(net, s_max=8, prob_bits=args.prob_bits)
+        model.record_inputs = True
+        model.forward(S=8, shared=(args.mode == "shared"))
+        torch.cuda.synchronize()
+        model.record_inputs = False
+        layers = []
+        for i, sp in enumerate(net.specs):
+            x = model.inputs[i].cpu().numpy()
+            if x.ndim == 2:
+                x = x.reshape(x.shape[0], x.shape[1], 1, 1)
+            layers.append(synth.Layer("c4net_" + sp.name, net.weights[i], x, stride=(sp.stride, sp.stride),
+                                      pad=(sp.pad, sp.pad), S=8, s_max=8, seed=3, layer_id=i, linear=(sp.name == "fc")))
+        model.inputs = {}
     per_call = 4 if args.prob_bits == 23 else 16
     shared = args.mode == "shared"
     calls = []
@@ -186,6 +207,9 @@ def main():
     torch.cuda.synchronize()
 
     def step():
+        if model is not None:
+            model.forward(S=8, shared=shared)
+            return
         for L, q, x, acc, y, bt in calls:
             if bt is not None:
                 psb.conv2d_progressive(q, x, bt, None, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id,

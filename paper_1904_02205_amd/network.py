@@ -31,6 +31,8 @@ class ResNet18:
             self.mult.append(torch.from_numpy((net.ch_scale[i] * unit).astype(np.float32)).to(device))
             self.bias.append(torch.from_numpy(net.ch_bias[i]).to(device))
         self.x0 = torch.from_numpy(net.x0).to(device)
+        self.record_inputs = False      # benchmarks: keep the input tensor of every layer of the last pass
+        self.inputs = {}
 
     def _input_steps(self):
         """Real value of one integer step of each layer's input activations."""
@@ -48,6 +50,8 @@ class ResNet18:
 
     def _conv(self, i, x, S, budget, shared):
         sp = self.net.specs[i]
+        if self.record_inputs:
+            self.inputs[i] = x
         n, _, h, w = x.shape
         oh = (h + 2 * sp.pad - sp.k) // sp.stride + 1
         y = torch.empty((n, sp.cout, oh, oh), dtype=torch.float32, device=self.device)
@@ -84,6 +88,8 @@ class ResNet18:
             i += 3 if has_sc else 2
         pooled = psb.global_avgpool_requantize(a, 1.0)
         keep(pooled)
+        if self.record_inputs:
+            self.inputs[i] = pooled
         n = pooled.shape[0]
         logits = torch.empty((n, self.net.specs[i].cout), dtype=torch.float32, device=self.device)
         acc = torch.empty((n, self.net.specs[i].cout), dtype=torch.int32, device=self.device)
