@@ -198,13 +198,23 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
 
 // ---- shared-filter mode -----------------------------------------------------------------------------
 
+psb::FilterJob filter_job(const psb_weights* q, int from, int to, uint64_t seed, uint32_t layer_id, int32_t* w32,
+                          int8_t* planes, int CB, int n_ksteps)
+{
+    psb::FilterJob j;
+    j.packed = q->packed_dev; j.OC = q->shape.oc; j.K = q->K; j.KHW = q->shape.kh * q->shape.kw;
+    j.CB = CB; j.n_ksteps = n_ksteps; j.prob_bits = q->prob_bits; j.from = from; j.to = to;
+    j.key0 = (uint32_t)(seed & 0xFFFFFFFFull); j.key1 = (uint32_t)(seed >> 32); j.layer_id = layer_id;
+    j.w32 = w32; j.planes = planes;
+    return j;
+}
+
 int sample_filter_launch(const psb_weights* q, int from, int to, uint64_t seed, uint32_t layer_id, int32_t* w32,
                          int8_t* planes, int CB, int n_ksteps, hipStream_t stream)
 {
     const int64_t nw = (int64_t)q->shape.oc * q->K;
-    hipLaunchKernelGGL(psb::k_sample_filter, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, stream, q->packed_dev,
-                       q->shape.oc, q->K, q->shape.kh * q->shape.kw, CB, n_ksteps, q->prob_bits, from, to,
-                       (uint32_t)(seed & 0xFFFFFFFFull), (uint32_t)(seed >> 32), layer_id, w32, planes);
+    hipLaunchKernelGGL(psb::k_sample_filter, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, stream,
+                       filter_job(q, from, to, seed, layer_id, w32, planes, CB, n_ksteps));
     PSB_HIP_TRY(hipGetLastError());
     return PSB_OK;
 }
@@ -238,7 +248,8 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         // positions of padding channels are never written again and must read as zero
         PSB_HIP_TRY(hipMemsetAsync(ws->planes_dev, 0, bytes, stream));
     }
-    const size_t xt_need = (size_t)g->n * g->h * g->w * C_pad;
+    // channels-last copy; the last C_pad bytes of the buffer are a page of zeros that padding taps read
+    const size_t xt_need = (size_t)g->n * g->h * g->w * C_pad + C_pad;
     if (mfma && ws->xt_bytes < xt_need) {
         if (ws->xt_dev) {
             PSB_HIP_TRY(hipStreamSynchronize(stream));     // an earlier call may still read the old buffer
@@ -248,6 +259,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         }
         if (hipMalloc(&ws->xt_dev, xt_need) != hipSuccess) return PSB_ERR_ALLOC;
         ws->xt_bytes = xt_need;
+        PSB_HIP_TRY(hipMemsetAsync(ws->xt_dev + (xt_need - C_pad), 0, C_pad, stream));
     }
 
     psb::SharedParams p;
@@ -262,16 +274,32 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     p.stride_h = g->stride_h; p.stride_w = g->stride_w; p.pad_h = g->pad_h; p.pad_w = g->pad_w;
     p.S = S; p.s_max = q->s_max;
     p.default_mult = std::ldexp(1.0f, q->info.e_min);
+    p.zero_page = mfma ? (int64_t)(ws->xt_bytes - C_pad) : 0;
     const int max_shift = q->info.e_top - q->info.e_min;
     const int64_t npix = (int64_t)g->n * OH * OW;
     if (!mfma && p.OC > 65535) return PSB_ERR_TOO_LARGE;
 
+    // preparation: sample the filter of the first (or only) segment and, for the matrix cores, transpose the
+    // activations - one launch for both
+    psb::TransposeJob tj;
+    std::memset(&tj, 0, sizeof(tj));
+    int64_t transpose_blocks = 0;
     if (mfma) {
-        const dim3 grid((unsigned)((g->w + 63) / 64), (unsigned)(g->n * g->h), (unsigned)CB);
-        if ((int64_t)g->n * g->h > 2147483647ll || CB > 65535) return PSB_ERR_TOO_LARGE;
-        hipLaunchKernelGGL(psb::k_to_channels_last, grid, dim3(256), 0, stream, x, p.C, p.H, p.W, C_pad, ws->xt_dev);
-        PSB_HIP_TRY(hipGetLastError());
+        tj.x = x; tj.C = p.C; tj.H = p.H; tj.W = p.W; tj.C_pad = C_pad; tj.xt = ws->xt_dev;
+        tj.tiles_x = (g->w + 63) / 64; tj.rows = (int64_t)g->n * g->h;
+        transpose_blocks = (int64_t)tj.tiles_x * tj.rows * CB;
     }
+    auto prepare = [&](int from, int to) -> int {
+        const int64_t filter_blocks = (nw + 255) / 256;
+        if (filter_blocks + transpose_blocks > 2147483647ll) return PSB_ERR_TOO_LARGE;
+        hipLaunchKernelGGL(psb::k_shared_prologue, dim3((unsigned)(filter_blocks + transpose_blocks)), dim3(256), 0,
+                           stream, filter_job(q, from, to, seed, layer_id, ws->w32_dev, mfma ? ws->planes_dev : nullptr,
+                                              CB, n_ksteps),
+                           tj, (unsigned)filter_blocks);
+        PSB_HIP_TRY(hipGetLastError());
+        transpose_blocks = 0;                       // once per call
+        return PSB_OK;
+    };
 
     auto contract = [&](int n_samples) -> int {
         int slot = 0;
@@ -288,8 +316,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     };
 
     if (!budget_to) {
-        rc = sample_filter_launch(q, 0, S, seed, layer_id, ws->w32_dev, mfma ? ws->planes_dev : nullptr, CB, n_ksteps,
-                                  stream);
+        rc = prepare(0, S);
         if (rc != PSB_OK) return rc;
         return contract(S);
     }
@@ -317,8 +344,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         if (!present[v]) continue;
         if (prev >= 0) {
             p.seg_from = prev; p.seg_to = v;
-            rc = sample_filter_launch(q, prev, v, seed, layer_id, ws->w32_dev, mfma ? ws->planes_dev : nullptr, CB,
-                                      n_ksteps, stream);
+            rc = prepare(prev, v);
             if (rc != PSB_OK) return rc;
             rc = contract(v - prev);
             if (rc != PSB_OK) return rc;

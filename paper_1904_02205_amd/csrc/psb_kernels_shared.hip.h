@@ -39,7 +39,7 @@ constexpr int kMaxPlanes = 4;
 
 struct SharedParams {
     const int8_t* x;           // [N][C][H][W]                      (direct kernel)
-    const int8_t* xt;          // [N][H][W][C_pad], channels last   (matrix-core kernel)
+    const int8_t* xt;          // [N][H][W][C_pad], channels last, channels last (matrix-core kernel)
     const int8_t* planes;      // [OC/32][n_ksteps][4][64][16]
     const int32_t* w32;        // [OC][K]
     const uint8_t* budget_to;  // [N][OH][OW] or null
@@ -51,38 +51,44 @@ struct SharedParams {
     int N, C, H, W, OC, OH, OW, KH, KW, Cg, OCg, K, C_pad, n_ksteps;
     int stride_h, stride_w, pad_h, pad_w;
     int S, s_max;
+    int64_t zero_page;         // offset in xt of C_pad zero bytes
     int masked;                // 0: every pixel, acc overwritten, epilogue fused.  1: only pixels whose sample
     int seg_from, seg_to;      //    range contains [seg_from, seg_to); acc accumulated
     float default_mult;
 };
 
 // One thread per weight: count, filter value, digit planes.
-__global__ void __launch_bounds__(256) k_sample_filter(const uint32_t* __restrict__ packed, int OC, int K, int KHW,
-                                                       int CB, int n_ksteps, int prob_bits, int from, int to,
-                                                       uint32_t key0, uint32_t key1, uint32_t layer_id,
-                                                       int32_t* __restrict__ w32, int8_t* __restrict__ planes)
+struct FilterJob {
+    const uint32_t* packed;   // [OC][K]
+    int OC, K, KHW, CB, n_ksteps, prob_bits, from, to;
+    uint32_t key0, key1, layer_id;
+    int32_t* w32;             // [OC][K]
+    int8_t* planes;           // operand-ordered digit planes, or null
+};
+
+__device__ __forceinline__ void sample_filter_thread(const FilterJob& j, int64_t i)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (int64_t)OC * K) return;
-    const int oc = (int)(i / K);
-    const int k = (int)(i - (int64_t)oc * K);
-    const uint32_t word = packed[i];
+    if (i >= (int64_t)j.OC * j.K) return;
+    const int oc = (int)(i / j.K);
+    const int k = (int)(i - (int64_t)oc * j.K);
+    const uint32_t word = j.packed[i];
     int32_t wv = 0;
     if ((word & 0x7F800000u) != kDeadWord) {
-        const uint32_t thr = threshold_of(word & 0x7FFFFFu, prob_bits);
-        const uint32_t cnt = prob_bits < 23 ? count_below7((uint32_t)oc, (uint32_t)k, layer_id, key0, key1, thr, from, to)
-                                            : count_below((uint32_t)oc, (uint32_t)k, layer_id, key0, key1, thr, from, to);
-        const uint32_t mag = ((uint32_t)(to - from) + cnt) << ((word >> 23) & 0xFFu);   // < 2^31 by the overflow rule
+        const uint32_t thr = threshold_of(word & 0x7FFFFFu, j.prob_bits);
+        const uint32_t cnt = j.prob_bits < 23
+            ? count_below7((uint32_t)oc, (uint32_t)k, j.layer_id, j.key0, j.key1, thr, j.from, j.to)
+            : count_below((uint32_t)oc, (uint32_t)k, j.layer_id, j.key0, j.key1, thr, j.from, j.to);
+        const uint32_t mag = ((uint32_t)(j.to - j.from) + cnt) << ((word >> 23) & 0xFFu);   // < 2^31 by the overflow rule
         wv = (word & 0x80000000u) ? -(int32_t)mag : (int32_t)mag;
     }
-    w32[i] = wv;
-    if (planes) {
-        const int c = k / KHW;
-        const int r = k - c * KHW;
-        const int kstep = r * CB + (c >> 5);
+    j.w32[i] = wv;
+    if (j.planes) {
+        const int c = k / j.KHW;
+        const int r = k - c * j.KHW;
+        const int kstep = r * j.CB + (c >> 5);
         const int cl = c & 31;
         const int lane = (oc & 31) + 32 * (cl >> 4);
-        int8_t* dst = planes + ((((int64_t)(oc >> 5) * n_ksteps + kstep) * kMaxPlanes) * 64 + lane) * 16 + (cl & 15);
+        int8_t* dst = j.planes + ((((int64_t)(oc >> 5) * j.n_ksteps + kstep) * kMaxPlanes) * 64 + lane) * 16 + (cl & 15);
         int64_t v = wv;
 #pragma unroll
         for (int b = 0; b < kMaxPlanes; ++b) {
@@ -94,35 +100,58 @@ __global__ void __launch_bounds__(256) k_sample_filter(const uint32_t* __restric
 }
 
 // x [N][C][H][W] -> xt [N][H][W][C_pad] (zeros in the padding channels).  One workgroup per
-// (64 columns, row, 32 channels) tile, transposed through LDS.
-__global__ void __launch_bounds__(256) k_to_channels_last(const int8_t* __restrict__ x, int C, int H, int W, int C_pad,
-                                                          int8_t* __restrict__ xt)
+// (64 columns, row, 32 channels) tile, transposed through LDS; tiles are numbered columns fastest,
+// then rows (n * H + iy), then channel blocks.
+struct TransposeJob {
+    const int8_t* x;
+    int C, H, W, C_pad;
+    int8_t* xt;
+    int tiles_x;          // ceil(W / 64)
+    int64_t rows;         // N * H
+};
+
+__device__ __forceinline__ void channels_last_tile(const TransposeJob& j, int64_t tile_index, int8_t (*tile)[64 + 4])
 {
-    __shared__ int8_t tile[32][64 + 4];
-    const int ix0 = blockIdx.x * 64;
-    const int64_t row = blockIdx.y;            // n * H + iy
-    const int n = (int)(row / H), iy = (int)(row - (int64_t)n * H);
-    const int c0 = blockIdx.z * 32;
+    const int ix0 = (int)(tile_index % j.tiles_x) * 64;
+    const int64_t row = (tile_index / j.tiles_x) % j.rows;
+    const int c0 = (int)(tile_index / ((int64_t)j.tiles_x * j.rows)) * 32;
+    const int n = (int)(row / j.H), iy = (int)(row - (int64_t)n * j.H);
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         const int idx = r * 256 + threadIdx.x;
         const int c = idx >> 6, dx = idx & 63;
         int8_t v = 0;
-        if (c0 + c < C && ix0 + dx < W) v = x[(((int64_t)n * C + c0 + c) * H + iy) * W + ix0 + dx];
+        if (c0 + c < j.C && ix0 + dx < j.W) v = j.x[(((int64_t)n * j.C + c0 + c) * j.H + iy) * j.W + ix0 + dx];
         tile[c][dx] = v;
     }
     __syncthreads();
     const int dx = threadIdx.x >> 2, part = threadIdx.x & 3;
-    if (ix0 + dx < W) {
+    if (ix0 + dx < j.W) {
         uint32_t lo = 0, hi = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            lo |= (uint32_t)(uint8_t)tile[part * 8 + j][dx] << (8 * j);
-            hi |= (uint32_t)(uint8_t)tile[part * 8 + 4 + j][dx] << (8 * j);
+        for (int q = 0; q < 4; ++q) {
+            lo |= (uint32_t)(uint8_t)tile[part * 8 + q][dx] << (8 * q);
+            hi |= (uint32_t)(uint8_t)tile[part * 8 + 4 + q][dx] << (8 * q);
         }
-        uint2* dst = reinterpret_cast<uint2*>(xt + ((row * W + ix0 + dx) * (int64_t)C_pad + c0 + part * 8));
+        uint2* dst = reinterpret_cast<uint2*>(j.xt + ((row * j.W + ix0 + dx) * (int64_t)j.C_pad + c0 + part * 8));
         *dst = make_uint2(lo, hi);
     }
+}
+
+__global__ void __launch_bounds__(256) k_sample_filter(const FilterJob j)
+{
+    sample_filter_thread(j, (int64_t)blockIdx.x * 256 + threadIdx.x);
+}
+
+// Both preparations of a shared-filter call in one launch: workgroups [0, filter_blocks) sample the filter,
+// the rest transpose the activations.  The two jobs are independent of each other.
+__global__ void __launch_bounds__(256) k_shared_prologue(const FilterJob f, const TransposeJob t, unsigned filter_blocks)
+{
+    __shared__ int8_t tile[32][64 + 4];
+    if (blockIdx.x < filter_blocks)          // uniform over the workgroup
+        sample_filter_thread(f, (int64_t)blockIdx.x * 256 + threadIdx.x);
+    else
+        channels_last_tile(t, (int64_t)(blockIdx.x - filter_blocks), tile);
 }
 
 // present[v] = 1 for every clamped budget value v that occurs in the maps
@@ -149,6 +178,13 @@ __device__ __forceinline__ bool shared_pixel_range(const SharedParams& p, int64_
     return from <= p.seg_from && p.seg_to <= to;
 }
 
+// Operands are read straight from global memory (the weights and the few input rows a tile touches stay
+// in L1/L2) through a software pipeline of kDepth reduction steps: the operands of step s + kDepth are
+// requested right after step s has been consumed, so kDepth x (P + 2) 16-byte loads are in flight per wave.
+// Every load is unconditional - taps that fall into the padding read a page of zeros behind the
+// channels-last copy - so that nothing but the matrix instructions waits on memory.
+constexpr int kDepth = 4;
+
 template <int P>
 __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 {
@@ -161,7 +197,8 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     const int ocb = blockIdx.y;
 
     bool live[2];
-    int n_[2], oy_[2], ox_[2], to_[2];
+    int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
+    int64_t origin[2];                              // offset of xt[n][iy0][ix0][16 g]; only used with an in-image tap added
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int64_t pix = pix0 + 32 * h + col;
@@ -171,6 +208,9 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
         oy_[h] = (int)((pc / p.OW) % p.OH);
         n_[h] = (int)(pc / ((int64_t)p.OW * p.OH));
         live[h] = shared_pixel_range(p, pc, to_[h]) && valid;
+        iy0[h] = oy_[h] * p.stride_h - p.pad_h;
+        ix0[h] = ox_[h] * p.stride_w - p.pad_w;
+        origin[h] = (((int64_t)n_[h] * p.H + iy0[h]) * p.W + ix0[h]) * p.C_pad + 16 * g;
     }
     if (__ballot(live[0] || live[1]) == 0ull) return;   // no pixel of this tile takes part
 
@@ -183,35 +223,52 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
             for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
 
     const int CB = p.C_pad >> 5;
+    const int n_steps = p.KH * p.KW * CB;
+    const int64_t zero_page = p.zero_page + 16 * g;
     const v4i* wp = reinterpret_cast<const v4i*>(p.planes) + ((int64_t)ocb * p.n_ksteps * kMaxPlanes) * 64 + lane;
-    const v4i zero = {0, 0, 0, 0};
-    for (int kh = 0; kh < p.KH; ++kh) {
-        for (int kw = 0; kw < p.KW; ++kw) {
-            bool ok[2];
-            const int8_t* src[2];
+
+    // load cursor: the reduction step whose operands are requested next
+    int l_kh = 0, l_kw = 0, l_cb = 0, l_step = 0;
+    int64_t tap_off[2];
+    auto place_tap = [&]() {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int iy = oy_[h] * p.stride_h - p.pad_h + kh;
-                const int ix = ox_[h] * p.stride_w - p.pad_w + kw;
-                ok[h] = live[h] && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-                const int64_t at = ok[h] ? (((int64_t)n_[h] * p.H + iy) * p.W + ix) : 0;
-                src[h] = p.xt + at * p.C_pad + 16 * g;
+        for (int h = 0; h < 2; ++h) {
+            const int iy = iy0[h] + l_kh, ix = ix0[h] + l_kw;
+            const bool ok = live[h] && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+            tap_off[h] = ok ? origin[h] + ((int64_t)l_kh * p.W + l_kw) * p.C_pad : zero_page;
+        }
+    };
+    place_tap();
+
+    v4i opa[kDepth][P], opb[kDepth][2];
+    auto request = [&](int slot) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) opb[slot][h] = *reinterpret_cast<const v4i*>(p.xt + tap_off[h] + l_cb * 32);
+#pragma unroll
+        for (int b = 0; b < P; ++b) opa[slot][b] = wp[((int64_t)l_step * kMaxPlanes + b) * 64];
+        if (l_step + 1 < n_steps) {                  // past the end the last step is simply requested again
+            ++l_step;
+            if (++l_cb == CB) {
+                l_cb = 0;
+                if (++l_kw == p.KW) { l_kw = 0; ++l_kh; }
+                place_tap();
             }
-            if (__ballot(ok[0] || ok[1]) == 0ull) {          // the tap is padding for the whole tile
-                wp += (int64_t)CB * kMaxPlanes * 64;
-                continue;
-            }
-            for (int cb = 0; cb < CB; ++cb) {
-                const v4i b0 = ok[0] ? *reinterpret_cast<const v4i*>(src[0] + cb * 32) : zero;
-                const v4i b1 = ok[1] ? *reinterpret_cast<const v4i*>(src[1] + cb * 32) : zero;
+        }
+    };
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) request(d);
+
+    for (int s = 0; s < n_steps; s += kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            if (s + d < n_steps) {                   // wave-uniform
 #pragma unroll
                 for (int b = 0; b < P; ++b) {
-                    const v4i a = wp[b * 64];
-                    acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b0, acc[0][b], 0, 0, 0);
-                    acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b1, acc[1][b], 0, 0, 0);
+                    acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(opa[d][b], opb[d][0], acc[0][b], 0, 0, 0);
+                    acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(opa[d][b], opb[d][1], acc[1][b], 0, 0, 0);
                 }
-                wp += kMaxPlanes * 64;
             }
+            request(d);
         }
     }
 
@@ -219,6 +276,8 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         if (!live[h]) continue;
+        const int64_t o0 = (((int64_t)n_[h] * p.OC) * p.OH + oy_[h]) * p.OW + ox_[h];
+        const int64_t plane = (int64_t)p.OH * p.OW;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             const int oc = ocb * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
@@ -226,7 +285,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
             uint32_t v = 0;
 #pragma unroll
             for (int b = 0; b < P; ++b) v += (uint32_t)acc[h][b][q] << (8 * b);
-            const int64_t o = (((int64_t)n_[h] * p.OC + oc) * p.OH + oy_[h]) * p.OW + ox_[h];
+            const int64_t o = o0 + oc * plane;
             if (p.masked) {
                 p.acc[o] = (int32_t)((uint32_t)p.acc[o] + v);
             } else {
