@@ -178,22 +178,31 @@ __device__ __forceinline__ bool shared_pixel_range(const SharedParams& p, int64_
     return from <= p.seg_from && p.seg_to <= to;
 }
 
-// Operands are read straight from global memory (the weights and the few input rows a tile touches stay
-// in L1/L2) through a software pipeline of kDepth reduction steps: the operands of step s + kDepth are
-// requested right after step s has been consumed, so kDepth x (P + 2) 16-byte loads are in flight per wave.
-// Every load is unconditional - taps that fall into the padding read a page of zeros behind the
-// channels-last copy - so that nothing but the matrix instructions waits on memory.
+// Operand movement.  The four waves of a workgroup work on the same block of 32 output channels, so the
+// weight operands are staged through LDS, kStageSteps reduction steps at a time, and shared: the next
+// chunk is already on its way into registers while the current one is consumed.  The activation operands
+// differ per wave and come straight from global memory (the few input rows a tile touches stay in L1/L2)
+// through a software pipeline: the operands of step s + kDepth are requested right after step s has been
+// consumed.  Every load is unconditional - taps that fall into the padding read a page of zeros - so that
+// nothing but the matrix instructions waits on memory.
 constexpr int kDepth = 4;
+constexpr int kStageSteps = 8;      // a multiple of kDepth
 
 template <int P>
 __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 {
+    __shared__ v4i a_lds[kStageSteps * P * 64];
+
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int col = lane & 31, g = lane >> 5;
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
-    const int64_t pix0 = ((int64_t)blockIdx.x * 4 + wave) * 64;
-    if (pix0 >= npix) return;                       // wave-uniform
+    // Workgroups are dealt to the 8 XCDs round-robin by their index; each XCD has its own L2.  Renumber them so
+    // that every XCD works on one contiguous eighth of the pixels and its L2 only has to hold that part of the input.
+    // (The launcher rounds the grid up to a multiple of 8; workgroups past the last tile have no live pixel.)
+    const unsigned per_xcd = gridDim.x >> 3;
+    const unsigned wg = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    const int64_t pix0 = ((int64_t)wg * 4 + wave) * 64;
     const int ocb = blockIdx.y;
 
     bool live[2];
@@ -212,7 +221,8 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
         ix0[h] = ox_[h] * p.stride_w - p.pad_w;
         origin[h] = (((int64_t)n_[h] * p.H + iy0[h]) * p.W + ix0[h]) * p.C_pad + 16 * g;
     }
-    if (__ballot(live[0] || live[1]) == 0ull) return;   // no pixel of this tile takes part
+    // a wave without any pixel that takes part still helps to stage the weights (and keeps the barriers whole)
+    const bool active = __ballot(live[0] || live[1]) != 0ull;
 
     v16i acc[2][P];
 #pragma unroll
@@ -225,9 +235,23 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     const int CB = p.C_pad >> 5;
     const int n_steps = p.KH * p.KW * CB;
     const int64_t zero_page = p.zero_page + 16 * g;
-    const v4i* wp = reinterpret_cast<const v4i*>(p.planes) + ((int64_t)ocb * p.n_ksteps * kMaxPlanes) * 64 + lane;
+    const v4i* wblock = reinterpret_cast<const v4i*>(p.planes) + ((int64_t)ocb * p.n_ksteps * kMaxPlanes) * 64;
 
-    // load cursor: the reduction step whose operands are requested next
+    // weights: operand i of a chunk (i = (step * P + plane) * 64 + lane) is fetched by thread i mod 256
+    constexpr int kStageRegs = kStageSteps * P * 64 / 256;
+    v4i stage[kStageRegs];
+    auto fetch_weights = [&](int s0) {
+#pragma unroll
+        for (int r = 0; r < kStageRegs; ++r) {
+            const int i = r * 256 + (int)threadIdx.x;
+            const int ks = i / (P * 64);
+            const int b = (i >> 6) % P;
+            const int step = min(s0 + ks, n_steps - 1);          // past the end: any valid address
+            stage[r] = wblock[((int64_t)step * kMaxPlanes + b) * 64 + (i & 63)];
+        }
+    };
+
+    // activations: load cursor = the reduction step whose operands are requested next
     int l_kh = 0, l_kw = 0, l_cb = 0, l_step = 0;
     int64_t tap_off[2];
     auto place_tap = [&]() {
@@ -239,13 +263,10 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
         }
     };
     place_tap();
-
-    v4i opa[kDepth][P], opb[kDepth][2];
+    v4i opb[kDepth][2];
     auto request = [&](int slot) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) opb[slot][h] = *reinterpret_cast<const v4i*>(p.xt + tap_off[h] + l_cb * 32);
-#pragma unroll
-        for (int b = 0; b < P; ++b) opa[slot][b] = wp[((int64_t)l_step * kMaxPlanes + b) * 64];
         if (l_step + 1 < n_steps) {                  // past the end the last step is simply requested again
             ++l_step;
             if (++l_cb == CB) {
@@ -255,22 +276,35 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
             }
         }
     };
-#pragma unroll
-    for (int d = 0; d < kDepth; ++d) request(d);
 
-    for (int s = 0; s < n_steps; s += kDepth) {
+    fetch_weights(0);
+    if (active) {
 #pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-            if (s + d < n_steps) {                   // wave-uniform
+        for (int d = 0; d < kDepth; ++d) request(d);
+    }
+    for (int s0 = 0; s0 < n_steps; s0 += kStageSteps) {
+        __syncthreads();                             // the previous chunk has been consumed by every wave
 #pragma unroll
-                for (int b = 0; b < P; ++b) {
-                    acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(opa[d][b], opb[d][0], acc[0][b], 0, 0, 0);
-                    acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(opa[d][b], opb[d][1], acc[1][b], 0, 0, 0);
+        for (int r = 0; r < kStageRegs; ++r) a_lds[r * 256 + threadIdx.x] = stage[r];
+        __syncthreads();
+        if (s0 + kStageSteps < n_steps) fetch_weights(s0 + kStageSteps);     // uniform over the workgroup
+        if (active) {
+#pragma unroll
+            for (int ks = 0; ks < kStageSteps; ++ks) {
+                const int d = ks % kDepth;
+                if (s0 + ks < n_steps) {             // wave-uniform
+#pragma unroll
+                    for (int b = 0; b < P; ++b) {
+                        const v4i a = a_lds[(ks * P + b) * 64 + lane];
+                        acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, opb[d][0], acc[0][b], 0, 0, 0);
+                        acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, opb[d][1], acc[1][b], 0, 0, 0);
+                    }
                 }
+                request(d);
             }
-            request(d);
         }
     }
+    if (!active) return;
 
     // result row (channel) of register q: 8*(q/4) + 4*(lane/32) + q%4; column (pixel) = lane%32
 #pragma unroll
@@ -345,7 +379,8 @@ inline int planes_needed(int max_shift, int n_samples)
 inline void launch_conv_shared_mfma(const SharedParams& p, int planes, hipStream_t stream)
 {
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
-    const dim3 grid((unsigned)((npix + 255) / 256), (unsigned)((p.OC + 31) / 32)), block(256);
+    const int64_t tiles = (npix + 255) / 256;
+    const dim3 grid((unsigned)((tiles + 7) / 8 * 8), (unsigned)((p.OC + 31) / 32)), block(256);   // 8 XCDs
     switch (planes) {
         case 1: hipLaunchKernelGGL(k_conv_shared_mfma<1>, grid, block, 0, stream, p); break;
         case 2: hipLaunchKernelGGL(k_conv_shared_mfma<2>, grid, block, 0, stream, p); break;
