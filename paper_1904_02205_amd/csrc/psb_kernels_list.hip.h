@@ -74,7 +74,8 @@ __device__ __forceinline__ uint32_t count_block_full7(uint32_t o, uint32_t k, ui
 template <int NB, bool P7>
 __global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerParams p,
                                                                     const uint32_t* __restrict__ live_idx,
-                                                                    const uint32_t* __restrict__ live_cnt)
+                                                                    const uint32_t* __restrict__ live_cnt,
+                                                                    int channels_per_wg)
 {
     __shared__ uint32_t list[kListCap];          // pixel | tap slot << 8 | activation byte << 16
     __shared__ int32_t acc_s[kListPixels];
@@ -87,7 +88,6 @@ __global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerP
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int oc = blockIdx.y;
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
     const int64_t pix = (int64_t)blockIdx.x * kListPixels + tid;
     const bool valid = pix < npix;
@@ -99,17 +99,22 @@ __global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerP
     to = min(to, p.s_max);
     int from = p.budget_from ? (int)p.budget_from[pixc] : 0;
     from = min(from, to);
-    const uint32_t o = (uint32_t)((((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox);
-    const int grp = oc / p.OCg;
     const int iy0 = oy * p.stride_h - p.pad_h;
     const int ix0 = ox * p.stride_w - p.pad_w;
+    const bool wants = valid && to > from;
+    range_s[tid] = (uint32_t)from | ((uint32_t)to << 8);
+
+    // A workgroup serves channels_per_wg consecutive channels one after the other, so that the per-pixel set-up
+    // above is paid once even when a channel has only a handful of taps (depthwise layers).
+    const int oc_end = min(p.OC, ((int)blockIdx.y + 1) * channels_per_wg);
+    for (int oc = (int)blockIdx.y * channels_per_wg; oc < oc_end; ++oc) {
+    const uint32_t o = (uint32_t)((((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox);
+    const int grp = oc / p.OCg;
     // index of x[n][grp*Cg][iy0][ix0]; only dereferenced with an in-bounds tap offset added
     const int64_t xbase = (((int64_t)n * p.C + (int64_t)grp * p.Cg) * p.H + iy0) * p.W + ix0;
-    const bool wants = valid && to > from;
 
     acc_s[tid] = 0;
     o_s[tid] = o;
-    range_s[tid] = (uint32_t)from | ((uint32_t)to << 8);
 
     const uint32_t nlive = live_cnt[oc];
     for (uint32_t c0 = 0; c0 < nlive; c0 += kListTaps) {
@@ -130,21 +135,38 @@ __global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerP
         if (tid == 0) count = 0;
         __syncthreads();
 
-        // build the list of products that need sampling
-        for (int i = 0; i < nk; ++i) {
-            const int2 info = tapinfo[i];
-            const int iy = iy0 + (info.y & 0xFFFF);
-            const int ix = ix0 + (info.y >> 16);
-            int32_t xv = 0;
-            if (wants && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W) xv = p.x[xbase + info.x];
-            const unsigned long long mask = __ballot(xv != 0);
-            uint32_t base = 0;
-            if (lane == 0 && mask) base = atomicAdd(&count, (uint32_t)__popcll(mask));
-            base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
-            if (xv != 0) {
-                const uint32_t pos = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-                list[pos] = (uint32_t)tid | ((uint32_t)i << 8) | (((uint32_t)xv & 0xFFu) << 16);
+        // Build the list of products that need sampling.  First every lane requests the activations of all taps
+        // of the chunk (independent loads: one memory latency for the lot), then each wave compacts its own
+        // entries: one range of the list is reserved per wave with a single LDS atomic, and positions inside the
+        // range follow from ballots and prefix counts.  (The order of the list is irrelevant to the result.)
+        int32_t xv[kListTaps];
+#pragma unroll
+        for (int i = 0; i < kListTaps; ++i) {
+            xv[i] = 0;
+            if (i < nk) {            // uniform
+                const int2 info = tapinfo[i];
+                const int iy = iy0 + (info.y & 0xFFFF);
+                const int ix = ix0 + (info.y >> 16);
+                if (wants && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W) xv[i] = p.x[xbase + info.x];
+            }
+        }
+        uint32_t mine = 0;           // entries of this wave (uniform)
+#pragma unroll
+        for (int i = 0; i < kListTaps; ++i)
+            if (i < nk) mine += (uint32_t)__popcll(__ballot(xv[i] != 0));
+        uint32_t run = 0;
+        if (lane == 0 && mine) run = atomicAdd(&count, mine);
+        run = (uint32_t)__builtin_amdgcn_readfirstlane((int)run);
+#pragma unroll
+        for (int i = 0; i < kListTaps; ++i) {
+            if (i < nk) {
+                const unsigned long long mask = __ballot(xv[i] != 0);
+                if (xv[i] != 0) {
+                    const uint32_t pos = run + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                    list[pos] = (uint32_t)tid | ((uint32_t)i << 8) | (((uint32_t)xv[i] & 0xFFu) << 16);
+                }
+                run += (uint32_t)__popcll(mask);
             }
         }
         __syncthreads();
@@ -207,6 +229,7 @@ __global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerP
         p.acc[o] = total;
         if (p.y) p.y[o] = rescale(total, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
     }
+    }   // channels of this workgroup (acc_s and o_s are only touched by their own lane between the barriers)
 }
 
 // Returns 0 or a hipError_t.
@@ -216,8 +239,11 @@ inline int launch_product_list(const LayerParams& p, const uint32_t* live_idx, c
 {
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
     const int64_t gx = (npix + kListPixels - 1) / kListPixels;
-    if (gx > 2147483647ll || p.OC > 65535) return (int)hipErrorInvalidValue;
-    const dim3 grid((unsigned)gx, (unsigned)p.OC), block(kListPixels);
+    // enough channels per workgroup for about 64 taps of work per pixel, at most 8
+    const int channels_per_wg = (int)std::min<int64_t>(8, std::max<int64_t>(1, 64 / std::max(1, p.K)));
+    const int gy = (p.OC + channels_per_wg - 1) / channels_per_wg;
+    if (gx > 2147483647ll || gy > 65535) return (int)hipErrorInvalidValue;
+    const dim3 grid((unsigned)gx, (unsigned)gy), block(kListPixels);
     // compile-time block count only for a uniform S that is a whole number of generator blocks
     const bool p7 = p.prob_bits < 23;
     const int per_block = p7 ? 16 : 4;
@@ -226,7 +252,7 @@ inline int launch_product_list(const LayerParams& p, const uint32_t* live_idx, c
     int slot = 0;
     const bool timed = prof_begin(stream, &slot);
 #define PSB_LAUNCH(NB_, P7_) \
-    hipLaunchKernelGGL((k_layer_product_list<NB_, P7_>), grid, block, 0, stream, p, live_idx, live_cnt)
+    hipLaunchKernelGGL((k_layer_product_list<NB_, P7_>), grid, block, 0, stream, p, live_idx, live_cnt, channels_per_wg)
     if (p7) {
         switch (nb) {
             case 1: PSB_LAUNCH(1, true); break;
