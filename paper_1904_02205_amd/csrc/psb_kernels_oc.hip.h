@@ -99,8 +99,10 @@ __device__ __forceinline__ TapScalars tap_scalars(uint32_t s_x1, const Keys& key
 
 // Number of samples of block j of one product that are below thr.  P7: the block holds sixteen 7-bit
 // uniforms and thr the 7-bit threshold in each byte; otherwise four 32-bit uniforms.
+// VALID = 4: every sample of the block counts; 1..3 (32-bit uniforms only): the first VALID samples count
+// (the last block of a range that starts on a block boundary); 0: the range [from,to) is checked at run time.
 // state after round 1: (.., .., ts.sz ^ lo_a, ts.s_lo); words 0 and 1 were used in the per-pixel set-up.
-template <bool FULL, bool P7>
+template <int VALID, bool P7>
 __device__ __forceinline__ uint32_t sample_block(uint32_t thr, TapScalars ts, const PixelHoist& h, uint32_t hz,
                                                  uint32_t lo2, const Keys& key, int j, int from, int to)
 {
@@ -114,6 +116,7 @@ __device__ __forceinline__ uint32_t sample_block(uint32_t thr, TapScalars ts, co
     c.z = hz ^ ts.s_lo;
     c.w = lo2;
     c = philox_rounds_3_to_9(c, key);
+    constexpr bool FULL = VALID == 4;
     uint32_t n = 0;
     if constexpr (P7) {
         if (FULL) {
@@ -125,11 +128,11 @@ __device__ __forceinline__ uint32_t sample_block(uint32_t thr, TapScalars ts, co
         return (uint32_t)(hi - lo) -
                (not_below7(c.x, thr, valid_bytes7(j, 0, from, to)) + not_below7(c.y, thr, valid_bytes7(j, 1, from, to)) +
                 not_below7(c.z, thr, valid_bytes7(j, 2, from, to)) + not_below7(c.w, thr, valid_bytes7(j, 3, from, to)));
-    } else if (FULL) {
+    } else if constexpr (VALID > 0) {
         n += (c.x < thr) ? 1u : 0u;
-        n += (c.y < thr) ? 1u : 0u;
-        n += (c.z < thr) ? 1u : 0u;
-        n += (c.w < thr) ? 1u : 0u;
+        if (VALID > 1) n += (c.y < thr) ? 1u : 0u;
+        if (VALID > 2) n += (c.z < thr) ? 1u : 0u;
+        if (VALID > 3) n += (c.w < thr) ? 1u : 0u;
     } else {
         const int s0 = 4 * j;
         n += (s0 + 0 >= from && s0 + 0 < to && c.x < thr) ? 1u : 0u;
@@ -164,7 +167,8 @@ __device__ __forceinline__ uint32_t list_entry(uint32_t mylist, int i)
 // (NB = 0: run-time number of blocks).  Returns this lane's partial accumulator.
 // mylist: lane i holds entry i = (tap index inside the tile << 8) | activation byte, and 0
 // beyond cnt (entry 0 addresses tile row 0, so reading one group ahead is always in bounds).
-template <int NB, bool FULL, bool P7>
+// VALID: see sample_block; with NB > 1 it applies to every block (only 4 is used then).
+template <int NB, int VALID, bool P7>
 __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const uint2* __restrict__ w_tile,
                                                 int lane, uint32_t k0, int j0, int nb_rt, int from, int to,
                                                 const PixelHoist& h, const Keys& key)
@@ -181,7 +185,7 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
             for (int jj = 0; jj < nb_rt; ++jj) {
                 uint32_t s_hib, hz, lo2;
                 block_setup(h, key, j0 + jj, s_hib, hz, lo2);
-                n += sample_block<false, P7>(wt.x, tap_scalars(s_hib ^ (k0 + kl), key), h, hz, lo2, key, j0 + jj, from, to);
+                n += sample_block<0, P7>(wt.x, tap_scalars(s_hib ^ (k0 + kl), key), h, hz, lo2, key, j0 + jj, from, to);
             }
             acc = mad24(__mul24(xs, (int32_t)n), (int32_t)wt.y, acc);
         }
@@ -230,7 +234,7 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
             for (int e = 0; e < E; ++e)
 #pragma unroll
                 for (int jj = 0; jj < NB; ++jj)
-                    cnt_b[e][jj] = sample_block<FULL, P7>(wt[e].x, ts[e][jj], h, hz[jj], lo2[jj], key, j0 + jj, from, to);
+                    cnt_b[e][jj] = sample_block<VALID, P7>(wt[e].x, ts[e][jj], h, hz[jj], lo2[jj], key, j0 + jj, from, to);
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 uint32_t n = nsamp;
@@ -246,7 +250,7 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
                 uint32_t n = nsamp;
 #pragma unroll
                 for (int jj = 0; jj < NB; ++jj)
-                    n += sample_block<FULL, P7>(wt.x, tap_scalars(s_hib[jj] ^ (k0 + (entry >> 8)), key), h, hz[jj], lo2[jj],
+                    n += sample_block<VALID, P7>(wt.x, tap_scalars(s_hib[jj] ^ (k0 + (entry >> 8)), key), h, hz[jj], lo2[jj],
                                             key, j0 + jj, from, to);
                 acc = mad24(__mul24((int32_t)(int8_t)(entry & 0xFFu), (int32_t)n), (int32_t)wt.y, acc);
             }
@@ -392,25 +396,32 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
                     const int nb = ((to + (1 << lg) - 1) >> lg) - j0;
                     const bool full = ((from | to) & ((1 << lg) - 1)) == 0;
                     const uint32_t kbase = (uint32_t)k0;
-#define PSB_LIST(NB_, FULL_, P7_) \
-    total = process_list<NB_, FULL_, P7_>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key)
+#define PSB_LIST(NB_, VALID_, P7_) \
+    total = process_list<NB_, VALID_, P7_>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key)
                     if (p7) {
-                        if (full && nb == 1) PSB_LIST(1, true, true);
-                        else if (full && nb == 2) PSB_LIST(2, true, true);
-                        else if (nb == 1) PSB_LIST(1, false, true);
-                        else PSB_LIST(0, false, true);
+                        if (full && nb == 1) PSB_LIST(1, 4, true);
+                        else if (full && nb == 2) PSB_LIST(2, 4, true);
+                        else if (nb == 1) PSB_LIST(1, 0, true);
+                        else PSB_LIST(0, 0, true);
                     } else if (full) {
                         switch (nb) {
-                            case 1: PSB_LIST(1, true, false); break;
-                            case 2: PSB_LIST(2, true, false); break;
-                            case 4: PSB_LIST(4, true, false); break;
-                            case 8: PSB_LIST(8, true, false); break;
-                            default: PSB_LIST(0, false, false); break;
+                            case 1: PSB_LIST(1, 4, false); break;
+                            case 2: PSB_LIST(2, 4, false); break;
+                            case 4: PSB_LIST(4, 4, false); break;
+                            case 8: PSB_LIST(8, 4, false); break;
+                            default: PSB_LIST(0, 0, false); break;
+                        }
+                    } else if (nb == 1 && (from & 3) == 0) {
+                        // one block, its first to - from samples: fewer comparisons, no range checks
+                        switch (to - from) {
+                            case 1: PSB_LIST(1, 1, false); break;
+                            case 2: PSB_LIST(1, 2, false); break;
+                            default: PSB_LIST(1, 3, false); break;
                         }
                     } else if (nb == 1) {
-                        PSB_LIST(1, false, false);
+                        PSB_LIST(1, 0, false);
                     } else {
-                        PSB_LIST(0, false, false);
+                        PSB_LIST(0, 0, false);
                     }
 #undef PSB_LIST
                 }
