@@ -100,7 +100,8 @@ def workload_layers(name):
 
 
 def count_work(L, packed, torch, device, per_call=4):
-    """(sampled MACs, generator calls needed, products needed) of one layer call, from the exported weights.
+    """(sampled MACs, generator calls needed, products needed, sampled MACs with a non-zero activation, dense
+    sampled MACs counting padding and dead weights) of one layer call, from the exported weights.
 
     sampled MACs: sum over outputs of budget x #(live taps inside the image).
     needed: the same restricted to taps whose activation is not 0; calls = ceil(budget/per_call) per such product.
@@ -123,7 +124,9 @@ def count_work(L, packed, torch, device, per_call=4):
     smac = float((taps_all * b).sum().item())
     calls = float((taps_nz * torch.ceil(b / per_call)).sum().item())
     products = float((taps_nz * (b > 0)).sum().item())
-    return smac, calls, products
+    smac_nz = float((taps_nz * b).sum().item())
+    dense = float(b.sum().item()) * oc * cg * kh * kw
+    return smac, calls, products, smac_nz, dense
 
 
 def main():
@@ -180,7 +183,7 @@ def main():
     shared = args.mode == "shared"
     calls = []
     kernels = []
-    smac = n_calls = n_prod = mfma_ops = 0.0
+    smac = n_calls = n_prod = mfma_ops = smac_nz = smac_dense = 0.0
     for L in layers:
         w = torch.from_numpy(L.w).to(dev)
         q = psb.Weights(w, groups=L.groups, x_absmax=L.x_absmax, s_max=L.s_max, prob_bits=args.prob_bits)
@@ -199,10 +202,12 @@ def main():
         packed = q.export()
         if not calls:
             q0_packed = packed
-        a, b, c = count_work(L, packed, torch, dev, per_call)
+        a, b, c, d, e = count_work(L, packed, torch, dev, per_call)
         smac += a
         n_calls += b
         n_prod += c
+        smac_nz += d
+        smac_dense += e
         calls.append((L, q, x, acc, y, bt))
     torch.cuda.synchronize()
 
@@ -252,6 +257,8 @@ def main():
         "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": desc, "sampled_macs_per_step": smac,
+                   "sampled_macs_with_nonzero_activation_per_step": smac_nz,
+                   "sampled_macs_dense_with_padding_per_step": smac_dense,
                    "generator_calls_per_step": n_calls, "samples_per_generator_call": per_call,
                    "prob_bits": args.prob_bits, "mode": args.mode,
                    "kernel_launches_per_step": launches_per_step, "mapping": args.mapping,

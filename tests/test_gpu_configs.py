@@ -1,8 +1,8 @@
 """BASELINE configurations at full size, in the launch configuration bench.py times (needs an MI355X).
 
 Configs 1, 2, 3 and 5 are compared with the oracle on every output element; the ResNet-18-shaped layers of
-config 4 (batch 32) on 20,000 randomly chosen output elements per layer, which the oracle computes one by
-one (possible because the random bits are keyed by output coordinate).
+config 4 on every output element at batch 2, and at batch 32 on 100,000 randomly chosen output elements per
+layer, which the oracle computes one by one (possible because the random bits are keyed by output coordinate).
 """
 import numpy as np
 import pytest
@@ -66,15 +66,20 @@ def test_config4_resnet18_layers_sampled(psb, orc):
         print(f"[config4] {L.name} x{L.x.shape} w{L.w.shape}", flush=True)
         qo = helpers.oracle_quantize(orc, L)
         acc, y = helpers.gpu_layer(psb, L, want_y=True)
-        pts = rng.choice(acc.size, size=min(20000, acc.size), replace=False).astype(np.int64)
+        pts = rng.choice(acc.size, size=min(100000, acc.size), replace=False).astype(np.int64)
         ref, over, _ = helpers.oracle_layer(orc, L, qo, points=pts)
         assert over == 0
         assert np.array_equal(acc.ravel()[pts], ref), L.name
         ref_y = orc.rescale(ref.reshape(1, 1, -1), qo.e_min, S=L.S).ravel()
         np.testing.assert_allclose(y.ravel()[pts], ref_y, rtol=1e-6, atol=0)
-        # properties that hold at any size: zero input rows give zero, and the call is repeatable
+        # the call is repeatable
         acc2, _ = helpers.gpu_layer(psb, L)
         assert np.array_equal(acc, acc2)
+
+
+def test_config4_resnet18_layers_full_at_batch_2(psb, orc):
+    for L in synth.config4_layers(batch=2):
+        _full(psb, orc, L)
 
 
 # ------------------------------------------------------------------ shared-filter mode at the same sizes
