@@ -97,6 +97,19 @@ class ResNet18:
                    mult=self.mult[i], bias=self.bias[i], shared=shared)
         return logits
 
+    def capture(self, S=8, shared=False):
+        """Record one pass with a uniform sample count into a HIP graph.  Returns (graph, logits): graph.replay()
+        reruns the pass (same seed, same bits) into the same logits tensor without any per-launch host work.
+        The pass is run once eagerly first, so that every workspace the library allocates on first use exists
+        before the capture starts; passes with a budget map cannot be captured (they read back which budget
+        values occur)."""
+        self.forward(S=S, shared=shared)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            logits = self.forward(S=S, shared=shared)
+        return graph, logits
+
     def forward_attention(self, s_lo=8, s_hi=16, shared=False):
         """The two-stage scheme of Sect. 4.5: a low-precision pass everywhere, the entropy mask of the last
         convolutional layer, then the network again with s_hi samples inside the mask and s_lo outside, on all

@@ -122,3 +122,22 @@ def test_network_with_a_budget_map_on_all_layers(psb, orc):
     budget = np.random.default_rng(5).choice([8, 16], size=(2, 2, 2), p=[0.65, 0.35]).astype(np.uint8)
     _compare(psb, orc, net, budget=budget, s_fc=16)
     _compare(psb, orc, net, budget=budget, s_fc=16, shared=True)
+
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_network_as_a_hip_graph(psb, orc, shared):
+    """A captured pass replays to the bits of the eager pass, every time, with eager work in between."""
+    import torch
+    from paper_1904_02205_amd import network
+    net = rs.resnet18(batch=2, hw=64, width=32, classes=10)
+    model = network.ResNet18(net)
+    eager = model.forward(S=8, shared=shared).cpu().numpy()
+    graph, logits = model.capture(S=8, shared=shared)
+    for i in range(4):
+        logits.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(logits.cpu().numpy(), eager), f"replay {i}"
+        other = model.forward(S=4, shared=not shared)          # eager work between the replays
+        torch.cuda.synchronize()
+        assert other.shape == logits.shape
