@@ -206,6 +206,7 @@ psb::FilterJob filter_job(const psb_weights* q, int from, int to, uint64_t seed,
     j.CB = CB; j.n_ksteps = n_ksteps; j.prob_bits = q->prob_bits; j.from = from; j.to = to;
     j.key0 = (uint32_t)(seed & 0xFFFFFFFFull); j.key1 = (uint32_t)(seed >> 32); j.layer_id = layer_id;
     j.w32 = w32; j.planes = planes;
+    j.pack_KW = 0; j.pack_C = 0;
     return j;
 }
 
@@ -231,9 +232,12 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     if (dev != q->device) return PSB_ERR_DEVICE;
 
     const bool mfma = q->shape.groups == 1 && g_mapping != 1;
-    const int C_pad = (q->shape.cin + 31) / 32 * 32;
+    // Layers with very few input channels (a network's first layer): pack the kw x C values of one kernel row
+    // into one 32-byte reduction block instead of padding every tap's C channels to 32.
+    const bool rowpack = mfma && q->shape.kw > 1 && q->shape.kw * q->shape.cin <= 32;
+    const int C_pad = rowpack ? 32 : (q->shape.cin + 31) / 32 * 32;
     const int CB = C_pad / 32;
-    const int n_ksteps = q->shape.kh * q->shape.kw * CB;
+    const int n_ksteps = rowpack ? q->shape.kh : q->shape.kh * q->shape.kw * CB;
     const int n_ocb = (q->shape.oc + 31) / 32;
     // each digit plane is summed in int32: 128 * 128 * (padded reduction length) must stay below 2^31
     if (mfma && (int64_t)n_ksteps * 32 >= (1ll << 17)) return PSB_ERR_TOO_LARGE;
@@ -248,8 +252,9 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         // positions of padding channels are never written again and must read as zero
         PSB_HIP_TRY(hipMemsetAsync(ws->planes_dev, 0, bytes, stream));
     }
-    // channels-last copy; the last C_pad bytes of the buffer are a page of zeros that padding taps read
-    const size_t xt_need = (size_t)g->n * g->h * g->w * C_pad + C_pad;
+    // channels-last copy (row-packed: one 32-byte block per input row and output column); the last C_pad bytes of
+    // the buffer are a page of zeros that padding taps read
+    const size_t xt_need = (size_t)g->n * g->h * (rowpack ? OW : g->w) * C_pad + C_pad;
     if (mfma && ws->xt_bytes < xt_need) {
         if (ws->xt_dev) {
             PSB_HIP_TRY(hipStreamSynchronize(stream));     // an earlier call may still read the old buffer
@@ -275,6 +280,18 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     p.S = S; p.s_max = q->s_max;
     p.default_mult = std::ldexp(1.0f, q->info.e_min);
     p.zero_page = mfma ? (int64_t)(ws->xt_bytes - C_pad) : 0;
+    p.tH = g->h; p.tW = g->w; p.tKH = q->shape.kh; p.tKW = q->shape.kw;
+    p.t_stride_h = g->stride_h; p.t_stride_w = g->stride_w; p.t_pad_h = g->pad_h; p.t_pad_w = g->pad_w;
+    if (rowpack) { p.tW = OW; p.tKW = 1; p.t_stride_w = 1; p.t_pad_w = 0; }
+    p.ksplit = 1;
+    if (mfma) {
+        // Few pixel tiles and a long reduction: cut the reduction so that every SIMD has a wave.  Only then: the
+        // partial sums cost a zero-fill, atomics and a separate rescale pass, which measured slower than the
+        // unsplit kernel as soon as the chip is half full.
+        const int64_t waves = ((int64_t)g->n * OH * OW + 63) / 64 * n_ocb;
+        const int64_t want = waves <= 512 ? (1024 + waves - 1) / waves : 1;
+        p.ksplit = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, 8), n_ksteps / 16));
+    }
     const int max_shift = q->info.e_top - q->info.e_min;
     const int64_t npix = (int64_t)g->n * OH * OW;
     if (!mfma && p.OC > 65535) return PSB_ERR_TOO_LARGE;
@@ -288,14 +305,19 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         tj.x = x; tj.C = p.C; tj.H = p.H; tj.W = p.W; tj.C_pad = C_pad; tj.xt = ws->xt_dev;
         tj.tiles_x = (g->w + 63) / 64; tj.rows = (int64_t)g->n * g->h;
         transpose_blocks = (int64_t)tj.tiles_x * tj.rows * CB;
+        if (rowpack) {
+            tj.pack_KW = q->shape.kw; tj.OW = OW; tj.stride_w = g->stride_w; tj.pad_w = g->pad_w;
+            transpose_blocks = (tj.rows * OW + 255) / 256;
+        }
     }
     auto prepare = [&](int from, int to) -> int {
         const int64_t filter_blocks = (nw + 255) / 256;
         if (filter_blocks + transpose_blocks > 2147483647ll) return PSB_ERR_TOO_LARGE;
+        psb::FilterJob fj = filter_job(q, from, to, seed, layer_id, ws->w32_dev, mfma ? ws->planes_dev : nullptr, CB,
+                                       n_ksteps);
+        if (rowpack) { fj.pack_KW = q->shape.kw; fj.pack_C = q->shape.cin; }
         hipLaunchKernelGGL(psb::k_shared_prologue, dim3((unsigned)(filter_blocks + transpose_blocks)), dim3(256), 0,
-                           stream, filter_job(q, from, to, seed, layer_id, ws->w32_dev, mfma ? ws->planes_dev : nullptr,
-                                              CB, n_ksteps),
-                           tj, (unsigned)filter_blocks);
+                           stream, fj, tj, (unsigned)filter_blocks);
         PSB_HIP_TRY(hipGetLastError());
         transpose_blocks = 0;                       // once per call
         return PSB_OK;
@@ -315,10 +337,34 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         return PSB_OK;
     };
 
+    const int64_t total = npix * p.OC;
+    auto rescale_pass = [&]() -> int {
+        psb::LayerParams lp;
+        fill_geometry(q, g, OH, OW, lp);
+        lp.acc = acc; lp.y = y; lp.mult = mult; lp.bias = bias; lp.budget_to = budget_to; lp.S = S;
+        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
+        hipLaunchKernelGGL(psb::k_rescale, dim3(blocks), dim3(256), 0, stream, lp);
+        PSB_HIP_TRY(hipGetLastError());
+        return PSB_OK;
+    };
+    auto zero_acc = [&]() -> int {
+        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
+        hipLaunchKernelGGL(psb::k_fill_zero, dim3(blocks), dim3(256), 0, stream, acc, total);
+        PSB_HIP_TRY(hipGetLastError());
+        return PSB_OK;
+    };
+
     if (!budget_to) {
         rc = prepare(0, S);
         if (rc != PSB_OK) return rc;
-        return contract(S);
+        if (p.ksplit > 1) {                         // partial sums meet in acc: start from zero, rescale afterwards
+            rc = zero_acc();
+            if (rc != PSB_OK) return rc;
+        }
+        rc = contract(S);
+        if (rc != PSB_OK) return rc;
+        if (p.ksplit > 1 && y) return rescale_pass();
+        return PSB_OK;
     }
 
     // per-pixel budgets: the distinct clamped budget values cut the sample axis into segments
@@ -332,11 +378,9 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     }
     PSB_HIP_TRY(hipMemcpyAsync(present, ws->present_dev, sizeof(present), hipMemcpyDeviceToHost, stream));
     PSB_HIP_TRY(hipStreamSynchronize(stream));
-    const int64_t total = npix * p.OC;
     if (!budget_from) {
-        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
-        hipLaunchKernelGGL(psb::k_fill_zero, dim3(blocks), dim3(256), 0, stream, acc, total);
-        PSB_HIP_TRY(hipGetLastError());
+        rc = zero_acc();
+        if (rc != PSB_OK) return rc;
     }
     p.masked = 1;
     int prev = -1;
@@ -351,14 +395,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         }
         prev = v;
     }
-    if (y) {
-        psb::LayerParams lp;
-        fill_geometry(q, g, OH, OW, lp);
-        lp.acc = acc; lp.y = y; lp.mult = mult; lp.bias = bias; lp.budget_to = budget_to; lp.S = S;
-        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
-        hipLaunchKernelGGL(psb::k_rescale, dim3(blocks), dim3(256), 0, stream, lp);
-        PSB_HIP_TRY(hipGetLastError());
-    }
+    if (y) return rescale_pass();
     return PSB_OK;
 }
 

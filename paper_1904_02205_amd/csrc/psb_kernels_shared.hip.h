@@ -52,6 +52,11 @@ struct SharedParams {
     int stride_h, stride_w, pad_h, pad_w;
     int S, s_max;
     int64_t zero_page;         // offset in xt of C_pad zero bytes
+    // Geometry of the convolution as the matrix-core kernel sees it on xt.  Normally the layer's own; for layers
+    // with very few input channels (kw * C <= 32) xt holds, per output column, the kw x C values of one kernel row
+    // ("row packing"), and the kernel sees a kh x 1 convolution with unit column stride on an image OW wide.
+    int tH, tW, tKH, tKW, t_stride_h, t_stride_w, t_pad_h, t_pad_w;
+    int ksplit;                // the reduction is cut into ksplit parts (grid z); > 1: results are added atomically
     int masked;                // 0: every pixel, acc overwritten, epilogue fused.  1: only pixels whose sample
     int seg_from, seg_to;      //    range contains [seg_from, seg_to); acc accumulated
     float default_mult;
@@ -61,6 +66,7 @@ struct SharedParams {
 struct FilterJob {
     const uint32_t* packed;   // [OC][K]
     int OC, K, KHW, CB, n_ksteps, prob_bits, from, to;
+    int pack_KW, pack_C;      // row packing: kernel width and channel count (0: not packed)
     uint32_t key0, key1, layer_id;
     int32_t* w32;             // [OC][K]
     int8_t* planes;           // operand-ordered digit planes, or null
@@ -85,8 +91,12 @@ __device__ __forceinline__ void sample_filter_thread(const FilterJob& j, int64_t
     if (j.planes) {
         const int c = k / j.KHW;
         const int r = k - c * j.KHW;
-        const int kstep = r * j.CB + (c >> 5);
-        const int cl = c & 31;
+        int kstep = r * j.CB + (c >> 5);
+        int cl = c & 31;
+        if (j.pack_KW) {           // one step per kernel row; slot kw * C + c inside it
+            kstep = r / j.pack_KW;
+            cl = (r - kstep * j.pack_KW) * j.pack_C + c;
+        }
         const int lane = (oc & 31) + 32 * (cl >> 4);
         int8_t* dst = j.planes + ((((int64_t)(oc >> 5) * j.n_ksteps + kstep) * kMaxPlanes) * 64 + lane) * 16 + (cl & 15);
         int64_t v = wv;
@@ -108,7 +118,33 @@ struct TransposeJob {
     int8_t* xt;
     int tiles_x;          // ceil(W / 64)
     int64_t rows;         // N * H
+    // row packing (pack_KW > 0): xt[n][iy][ox][kw * C + c] = x[n][c][iy][ox * stride_w - pad_w + kw], zero outside
+    // the row and in the unused slots; one thread per (n, iy, ox)
+    int pack_KW, OW, stride_w, pad_w;
 };
+
+__device__ __forceinline__ void row_pack_block(const TransposeJob& j, int64_t block)
+{
+    const int64_t i = block * 256 + threadIdx.x;          // (n * H + iy) * OW + ox
+    if (i >= j.rows * j.OW) return;
+    const int ox = (int)(i % j.OW);
+    const int64_t row = i / j.OW;
+    const int n = (int)(row / j.H), iy = (int)(row - (int64_t)n * j.H);
+    uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int ix0 = ox * j.stride_w - j.pad_w;
+    for (int kw = 0; kw < j.pack_KW; ++kw) {
+        const int ix = ix0 + kw;
+        if ((unsigned)ix >= (unsigned)j.W) continue;
+        for (int c = 0; c < j.C; ++c) {
+            const int slot = kw * j.C + c;
+            const uint32_t v = (uint8_t)j.x[(((int64_t)n * j.C + c) * j.H + iy) * j.W + ix];
+            w[slot >> 2] |= v << (8 * (slot & 3));
+        }
+    }
+    uint4* dst = reinterpret_cast<uint4*>(j.xt + i * 32);
+    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+}
 
 __device__ __forceinline__ void channels_last_tile(const TransposeJob& j, int64_t tile_index, int8_t (*tile)[64 + 4])
 {
@@ -150,6 +186,8 @@ __global__ void __launch_bounds__(256) k_shared_prologue(const FilterJob f, cons
     __shared__ int8_t tile[32][64 + 4];
     if (blockIdx.x < filter_blocks)          // uniform over the workgroup
         sample_filter_thread(f, (int64_t)blockIdx.x * 256 + threadIdx.x);
+    else if (t.pack_KW)
+        row_pack_block(t, (int64_t)(blockIdx.x - filter_blocks));
     else
         channels_last_tile(t, (int64_t)(blockIdx.x - filter_blocks), tile);
 }
@@ -212,14 +250,15 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     for (int h = 0; h < 2; ++h) {
         const int64_t pix = pix0 + 32 * h + col;
         const bool valid = pix < npix;
-        const int64_t pc = valid ? pix : npix - 1;
-        ox_[h] = (int)(pc % p.OW);
-        oy_[h] = (int)((pc / p.OW) % p.OH);
-        n_[h] = (int)(pc / ((int64_t)p.OW * p.OH));
+        const uint32_t pc = (uint32_t)(valid ? pix : npix - 1);       // the pixel count fits 32 bits (checked by the host)
+        const uint32_t row = pc / (uint32_t)p.OW;
+        ox_[h] = (int)(pc - row * (uint32_t)p.OW);
+        n_[h] = (int)(row / (uint32_t)p.OH);
+        oy_[h] = (int)(row - (uint32_t)n_[h] * (uint32_t)p.OH);
         live[h] = shared_pixel_range(p, pc, to_[h]) && valid;
-        iy0[h] = oy_[h] * p.stride_h - p.pad_h;
-        ix0[h] = ox_[h] * p.stride_w - p.pad_w;
-        origin[h] = (((int64_t)n_[h] * p.H + iy0[h]) * p.W + ix0[h]) * p.C_pad + 16 * g;
+        iy0[h] = oy_[h] * p.t_stride_h - p.t_pad_h;
+        ix0[h] = ox_[h] * p.t_stride_w - p.t_pad_w;
+        origin[h] = (((int64_t)n_[h] * p.tH + iy0[h]) * p.tW + ix0[h]) * p.C_pad + 16 * g;
     }
     // a wave without any pixel that takes part still helps to stage the weights (and keeps the barriers whole)
     const bool active = __ballot(live[0] || live[1]) != 0ull;
@@ -233,7 +272,11 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
             for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
 
     const int CB = p.C_pad >> 5;
-    const int n_steps = p.KH * p.KW * CB;
+    const int n_steps = p.tKH * p.tKW * CB;
+    // this workgroup's part of the reduction
+    const int per_split = (n_steps + p.ksplit - 1) / p.ksplit;
+    const int s_begin = (int)blockIdx.z * per_split;
+    const int s_end = min(n_steps, s_begin + per_split);
     const int64_t zero_page = p.zero_page + 16 * g;
     const v4i* wblock = reinterpret_cast<const v4i*>(p.planes) + ((int64_t)ocb * p.n_ksteps * kMaxPlanes) * 64;
 
@@ -252,14 +295,15 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     };
 
     // activations: load cursor = the reduction step whose operands are requested next
-    int l_kh = 0, l_kw = 0, l_cb = 0, l_step = 0;
+    int l_step = min(s_begin, n_steps - 1);
+    int l_cb = l_step % CB, l_kw = (l_step / CB) % p.tKW, l_kh = (l_step / CB) / p.tKW;
     int64_t tap_off[2];
     auto place_tap = [&]() {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int iy = iy0[h] + l_kh, ix = ix0[h] + l_kw;
-            const bool ok = live[h] && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-            tap_off[h] = ok ? origin[h] + ((int64_t)l_kh * p.W + l_kw) * p.C_pad : zero_page;
+            const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
+            tap_off[h] = ok ? origin[h] + ((int64_t)l_kh * p.tW + l_kw) * p.C_pad : zero_page;
         }
     };
     place_tap();
@@ -271,33 +315,40 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
             ++l_step;
             if (++l_cb == CB) {
                 l_cb = 0;
-                if (++l_kw == p.KW) { l_kw = 0; ++l_kh; }
+                if (++l_kw == p.tKW) { l_kw = 0; ++l_kh; }
                 place_tap();
             }
         }
     };
 
-    fetch_weights(0);
+    fetch_weights(s_begin);
     if (active) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) request(d);
     }
-    for (int s0 = 0; s0 < n_steps; s0 += kStageSteps) {
+    for (int s0 = s_begin; s0 < s_end; s0 += kStageSteps) {
         __syncthreads();                             // the previous chunk has been consumed by every wave
 #pragma unroll
         for (int r = 0; r < kStageRegs; ++r) a_lds[r * 256 + threadIdx.x] = stage[r];
         __syncthreads();
-        if (s0 + kStageSteps < n_steps) fetch_weights(s0 + kStageSteps);     // uniform over the workgroup
+        if (s0 + kStageSteps < s_end) fetch_weights(s0 + kStageSteps);       // uniform over the workgroup
         if (active) {
+            // the weight operands of step ks + 1 are read from LDS while the matrix instructions of step ks run
+            v4i a[2][P];
+#pragma unroll
+            for (int b = 0; b < P; ++b) a[0][b] = a_lds[b * 64 + lane];
 #pragma unroll
             for (int ks = 0; ks < kStageSteps; ++ks) {
                 const int d = ks % kDepth;
-                if (s0 + ks < n_steps) {             // wave-uniform
+                if (ks + 1 < kStageSteps) {
+#pragma unroll
+                    for (int b = 0; b < P; ++b) a[(ks + 1) & 1][b] = a_lds[((ks + 1) * P + b) * 64 + lane];
+                }
+                if (s0 + ks < s_end) {               // wave-uniform
 #pragma unroll
                     for (int b = 0; b < P; ++b) {
-                        const v4i a = a_lds[(ks * P + b) * 64 + lane];
-                        acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, opb[d][0], acc[0][b], 0, 0, 0);
-                        acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, opb[d][1], acc[1][b], 0, 0, 0);
+                        acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][0], acc[0][b], 0, 0, 0);
+                        acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][1], acc[1][b], 0, 0, 0);
                     }
                 }
                 request(d);
@@ -320,8 +371,8 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 #pragma unroll
             for (int b = 0; b < P; ++b) v += (uint32_t)acc[h][b][q] << (8 * b);
             const int64_t o = o0 + oc * plane;
-            if (p.masked) {
-                p.acc[o] = (int32_t)((uint32_t)p.acc[o] + v);
+            if (p.masked || p.ksplit > 1) {
+                atomicAdd(&p.acc[o], (int32_t)v);           // exact in any order: the arithmetic is modulo 2^32
             } else {
                 p.acc[o] = (int32_t)v;
                 if (p.y) p.y[o] = rescale((int32_t)v, p.mult ? p.mult[oc] : p.default_mult, to_[h], p.bias, oc);
@@ -380,7 +431,7 @@ inline void launch_conv_shared_mfma(const SharedParams& p, int planes, hipStream
 {
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
     const int64_t tiles = (npix + 255) / 256;
-    const dim3 grid((unsigned)((tiles + 7) / 8 * 8), (unsigned)((p.OC + 31) / 32)), block(256);   // 8 XCDs
+    const dim3 grid((unsigned)((tiles + 7) / 8 * 8), (unsigned)((p.OC + 31) / 32), (unsigned)p.ksplit), block(256);   // 8 XCDs
     switch (planes) {
         case 1: hipLaunchKernelGGL(k_conv_shared_mfma<1>, grid, block, 0, stream, p); break;
         case 2: hipLaunchKernelGGL(k_conv_shared_mfma<2>, grid, block, 0, stream, p); break;
