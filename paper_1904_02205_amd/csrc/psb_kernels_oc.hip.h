@@ -495,17 +495,6 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
     // benchmark overrides (results do not depend on either)
     if (const char* v = std::getenv("PSB_OC_TAPS")) { const int t = std::atoi(v); if (t >= 1 && t <= kOcMaxTaps) max_taps = t; }
     if (const char* v = std::getenv("PSB_OC_WAVES")) { const int t = std::atoi(v); if (t == 4 || t == 8) waves = t; }
-    // chunks of at most max_taps taps, as equal as possible, none empty
-    int n_chunks = (p.K + max_taps - 1) / max_taps;
-    const int kc = (p.K + n_chunks - 1) / n_chunks;
-    n_chunks = (p.K + kc - 1) / kc;
-    const int n_ocb = p.oc_pad / 64;
-    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
-    const int64_t pixel_groups = (npix + waves - 1) / waves;
-    const int64_t n_tickets = pixel_groups * n_chunks * n_ocb;
-    if (n_tickets >= (1ll << 32) - 65536) return (int)hipErrorInvalidValue;
-    const int64_t total = npix * p.OC;
-
     static int cus = 0;
     if (cus == 0) {
         int dev = 0, n = 0;
@@ -516,6 +505,22 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
     }
     // resident workgroups: 160 KB of LDS hold four tiles; 512 VGPRs per lane hold four (8: three) waves per SIMD
     const int wg_per_cu = (waves == 8) ? 2 : 4;
+    const int n_ocb = p.oc_pad / 64;
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int64_t pixel_groups = (npix + waves - 1) / waves;
+    // chunks of at most max_taps taps, as equal as possible, none empty; a layer too small to give every resident
+    // workgroup a ticket gets shorter chunks (down to 16 taps) instead of leaving part of the chip idle
+    int n_chunks, kc;
+    for (;;) {
+        n_chunks = (p.K + max_taps - 1) / max_taps;
+        kc = (p.K + n_chunks - 1) / n_chunks;
+        n_chunks = (p.K + kc - 1) / kc;
+        if (pixel_groups * n_chunks * n_ocb >= (int64_t)cus * wg_per_cu || max_taps <= 16) break;
+        max_taps /= 2;
+    }
+    const int64_t n_tickets = pixel_groups * n_chunks * n_ocb;
+    if (n_tickets >= (1ll << 32) - 65536) return (int)hipErrorInvalidValue;
+    const int64_t total = npix * p.OC;
     const int64_t grid = std::min<int64_t>(n_tickets, (int64_t)cus * wg_per_cu);
 
     if (n_chunks > 1 && !p.budget_from) {
