@@ -76,6 +76,47 @@ def test_null_arguments_are_rejected_before_any_device_work(psb):
     assert L.psb_last_device_error() == 0
 
 
+def test_later_entry_points_validate_on_the_host(psb):
+    """Shared-filter, glue and attention entry points: every argument error is found before any device work."""
+    L = psb.lib()
+    g = psb.ConvGeom(1, 8, 8, 1, 1, 1, 1)
+    P = C.c_void_p(16)                       # a non-NULL pointer that is never dereferenced
+    assert L.psb_sample_filter(None, 0, 4, 0, 0, P, None) == psb.ERR_NULL
+    assert L.psb_linear_shared(None, P, 1, 1, 0, 0, P, None, None, None, None) == psb.ERR_NULL
+    assert L.psb_conv2d_shared(None, P, C.byref(g), 1, 0, 0, P, None, None, None, None) == psb.ERR_NULL
+    assert L.psb_conv2d_progressive_shared(None, P, C.byref(g), P, None, 0, 0, P, None, None, None, None) == psb.ERR_NULL
+    # requantize
+    rq = L.psb_requantize
+    assert rq(None, None, None, 0.0, 1, 1.0, 0, 127, 8, P, None) == psb.ERR_NULL
+    assert rq(P, None, None, 0.0, 1, 1.0, 0, 127, 8, None, None) == psb.ERR_NULL
+    assert rq(P, None, None, 0.0, 1, 1.0, 0, 127, 0, P, None) == psb.ERR_SHAPE
+    assert rq(P, P, P, 0.0, 1, 1.0, 0, 127, 8, P, None) == psb.ERR_VALUE             # two residual operands
+    for lo, hi in ((-129, 0), (0, 128), (5, 4)):
+        assert rq(P, None, None, 0.0, 1, 1.0, lo, hi, 8, P, None) == psb.ERR_VALUE
+    # pooling
+    mp = L.psb_maxpool2d_i8
+    assert mp(None, 1, 1, 8, 8, 3, 3, 2, 2, 1, 1, P, None) == psb.ERR_NULL
+    assert mp(P, 1, 1, 8, 8, 3, 3, 0, 2, 1, 1, P, None) == psb.ERR_SHAPE              # stride 0
+    assert mp(P, 1, 1, 8, 8, 2, 2, 2, 2, 2, 2, P, None) == psb.ERR_SHAPE              # a window inside the padding
+    assert mp(P, 1, 1, 2, 2, 5, 5, 1, 1, 1, 1, P, None) == psb.ERR_SHAPE              # kernel larger than padded image
+    ap = L.psb_global_avgpool_requantize
+    assert ap(None, 1, 1, 7, 7, 1.0, 0, 127, P, None) == psb.ERR_NULL
+    assert ap(P, 0, 1, 7, 7, 1.0, 0, 127, P, None) == psb.ERR_SHAPE
+    assert ap(P, 1, 1, 4096, 4096, 1.0, 0, 127, P, None) == psb.ERR_TOO_LARGE         # 2^24 positions per image
+    assert ap(P, 1, 1, 7, 7, 1.0, 3, 2, P, None) == psb.ERR_VALUE
+    rs = L.psb_budget_resample
+    assert rs(None, 1, 7, 7, 14, 14, P, None) == psb.ERR_NULL
+    assert rs(P, 1, 7, 7, 0, 14, P, None) == psb.ERR_SHAPE
+    # attention
+    at = L.psb_attention_budget
+    assert at(None, 0.1, 1, 8, 7, 7, 8, 16, P, None, P, None) == psb.ERR_NULL
+    assert at(P, 0.1, 1, 8, 7, 7, 8, 16, None, None, P, None) == psb.ERR_NULL
+    assert at(P, 0.1, 1, 0, 7, 7, 8, 16, P, None, P, None) == psb.ERR_SHAPE
+    for step in (0.0, -1.0, float("nan"), float("inf")):
+        assert at(P, step, 1, 8, 7, 7, 8, 16, P, None, P, None) == psb.ERR_VALUE
+    assert L.psb_last_device_error() == 0
+
+
 def test_query_mapping_null_arguments(psb):
     L = psb.lib()
     g = psb.ConvGeom(1, 8, 8, 1, 1, 1, 1)
