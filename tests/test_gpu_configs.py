@@ -117,3 +117,29 @@ def test_shared_filter_config4_layers_sampled(psb, orc):
         assert np.array_equal(acc.ravel()[pts], ref), L.name
         ref_y = orc.rescale(ref.reshape(1, 1, -1), qo.e_min, S=L.S).ravel()
         np.testing.assert_allclose(y.ravel()[pts], ref_y, rtol=1e-6, atol=0)
+
+
+# ------------------------------------------------------------------ properties that hold at any size
+
+def test_config2_mean_over_seeds_approaches_the_float_convolution(psb, orc):
+    """Unbiasedness (Sect. 3.1) at full size, in both modes: the mean of the rescaled output over 48 seeds lies
+    within five standard errors of the exact convolution with the represented weights, element by element (a
+    handful of the 200,704 elements may exceed it by chance: at most 10 are tolerated, none by more than 7)."""
+    import torch
+    L = synth.config2()
+    qo = helpers.oracle_quantize(orc, L)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(L.x.astype(np.float64)),
+                                     torch.from_numpy(qo.represented().reshape(L.w.shape)), padding=L.pad).numpy()
+    qg = helpers.gpu_quantize(psb, L)
+    x = torch.from_numpy(L.x).cuda()
+    for shared in (False, True):
+        ys = []
+        for seed in range(48):
+            y = torch.empty((1, 64, 56, 56), dtype=torch.float32, device="cuda")
+            psb.conv2d(qg, x, L.S, pad=L.pad, seed=1000 + seed, layer_id=L.layer_id, y=y, shared=shared)
+            ys.append(y.double())
+        ys = torch.stack(ys)
+        mean, sd = ys.mean(dim=0).cpu().numpy(), ys.std(dim=0).cpu().numpy()
+        z = np.abs(mean - ref) / (sd / np.sqrt(48) + 1e-9)
+        assert (z > 5).sum() <= 10 and z.max() < 7, (shared, float(z.max()), int((z > 5).sum()))
+        assert 0.5 < np.median(z) < 0.9          # |N(0,1)| has median 0.67: the spread is the predicted one
