@@ -538,11 +538,10 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     }
     // 3. pack
     {
-        const int64_t total = (int64_t)oc_pad * K;
-        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 4096);
-        hipLaunchKernelGGL(psb::k_pack, dim3(blocks), dim3(256), 0, stream, w_bits, OC, (int)K, oc_pad, (int)prob_bits,
-                           field_min,
-                           q->packed_dev, q->tile_dev, reinterpret_cast<unsigned long long*>(scratch + 2));
+        const dim3 grid((unsigned)((K + 63) / 64), (unsigned)(oc_pad / 64));
+        if (grid.y > 65535) return fail(PSB_ERR_TOO_LARGE, hipSuccess);
+        hipLaunchKernelGGL(psb::k_pack, grid, dim3(256), 0, stream, w_bits, OC, (int)K, oc_pad, (int)prob_bits,
+                           field_min, q->packed_dev, q->tile_dev, reinterpret_cast<unsigned long long*>(scratch + 2));
         QTRY(hipGetLastError());
         hipLaunchKernelGGL(psb::k_live_index, dim3(OC), dim3(256), 0, stream, q->packed_dev, (int)K, q->live_idx_dev,
                            q->live_cnt_dev);

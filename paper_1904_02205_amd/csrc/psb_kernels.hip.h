@@ -56,7 +56,13 @@ __global__ void __launch_bounds__(256) k_exponent_scan(const uint32_t* __restric
         best = max(best, (uint32_t)__shfl_xor((int)best, off, 64));
         bad |= (uint32_t)__shfl_xor((int)bad, off, 64);
     }
-    if ((threadIdx.x & 63) == 0) {
+    // one pair of atomics per workgroup: thousands of waves hitting the same word serialise
+    __shared__ uint32_t s_best[4], s_bad[4];
+    if ((threadIdx.x & 63) == 0) { s_best[threadIdx.x >> 6] = best; s_bad[threadIdx.x >> 6] = bad; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        best = max(max(s_best[0], s_best[1]), max(s_best[2], s_best[3]));
+        bad = s_bad[0] | s_bad[1] | s_bad[2] | s_bad[3];
         if (best) atomicMax(&scan[0], best);
         if (bad) atomicOr(&scan[1], 1u);
     }
@@ -95,15 +101,17 @@ __global__ void __launch_bounds__(256) k_pack(const uint32_t* __restrict__ w_bit
                                               uint32_t* __restrict__ packed, uint2* __restrict__ tile,
                                               unsigned long long* __restrict__ counts)
 {
-    const int64_t total = (int64_t)oc_pad * K;
+    // One workgroup per 64 channels x 64 taps: the weights are read and `packed` is written along k (both
+    // [oc][K]), the words go through LDS, and `tile` is written along oc ([k][oc_pad]): every access coalesced.
+    __shared__ uint32_t words[64][64 + 1];
+    const int k0 = blockIdx.x * 64, oc0 = blockIdx.y * 64;
     unsigned long long n_zero = 0, n_flush = 0, n_live = 0;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-        // i enumerates the transposed array so that its writes are coalesced
-        const int k = (int)(i / oc_pad);
-        const int oc = (int)(i - (int64_t)k * oc_pad);
-        uint2 entry = make_uint2(0u, 0u);
-        if (oc < OC) {
-            uint32_t word = kDeadWord;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int idx = r * 256 + threadIdx.x;
+        const int oc = oc0 + (idx >> 6), k = k0 + (idx & 63);
+        uint32_t word = kDeadWord;
+        if (oc < OC && k < K) {
             const uint32_t bits = round_probability(w_bits[(int64_t)oc * K + k], prob_bits);
             const int f = (int)((bits >> 23) & 0xFFu);
             const uint32_t mant = bits & 0x7FFFFFu;
@@ -111,14 +119,26 @@ __global__ void __launch_bounds__(256) k_pack(const uint32_t* __restrict__ w_bit
             else if (f == 0 || f < field_min) n_flush++;
             else {
                 n_live++;
-                const uint32_t shift = (uint32_t)(f - field_min);
-                word = (bits & 0x80000000u) | (shift << 23) | mant;
-                const uint32_t unit = 1u << shift;              // shift <= 30 by the overflow rule
-                entry = make_uint2(threshold_of(mant, prob_bits), (bits & 0x80000000u) ? (0u - unit) : unit);
+                word = (bits & 0x80000000u) | ((uint32_t)(f - field_min) << 23) | mant;
             }
             packed[(int64_t)oc * K + k] = word;
         }
-        tile[i] = entry;
+        words[idx >> 6][idx & 63] = word;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int idx = r * 256 + threadIdx.x;
+        const int k = k0 + (idx >> 6), oc = oc0 + (idx & 63);       // oc < oc_pad: oc_pad is a multiple of 64
+        if (k < K) {
+            const uint32_t word = words[idx & 63][idx >> 6];
+            uint2 entry = make_uint2(0u, 0u);
+            if ((word & 0x7F800000u) != kDeadWord) {
+                const uint32_t unit = 1u << ((word >> 23) & 0xFFu);          // shift <= 30 by the overflow rule
+                entry = make_uint2(threshold_of(word & 0x7FFFFFu, prob_bits), (word & 0x80000000u) ? (0u - unit) : unit);
+            }
+            tile[(int64_t)k * oc_pad + oc] = entry;
+        }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
