@@ -66,28 +66,42 @@ __global__ void __launch_bounds__(256) k_requantize(const float* __restrict__ y,
     }
 }
 
-// One output element per thread; positions in the padding do not take part.
+// Four neighbouring outputs of one row per thread (one packed 4-byte store when the row allows it); positions in
+// the padding do not take part.  out_aligned: the output pointer is 4-byte aligned.
 __global__ void __launch_bounds__(256) k_maxpool_i8(const int8_t* __restrict__ x, int64_t images, int H, int W, int KH,
                                                     int KW, int stride_h, int stride_w, int pad_h, int pad_w, int OH,
-                                                    int OW, int8_t* __restrict__ out)
+                                                    int OW, int out_aligned, int8_t* __restrict__ out)
 {
-    const int64_t total = images * OH * OW;
+    const int OW4 = (OW + 3) >> 2;
+    const int64_t total = images * OH * OW4;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-        const int ox = (int)(i % OW);
-        const int oy = (int)((i / OW) % OH);
-        const int64_t img = i / ((int64_t)OW * OH);
+        const int ox0 = (int)(i % OW4) * 4;
+        const int oy = (int)((i / OW4) % OH);
+        const int64_t img = i / ((int64_t)OW4 * OH);
         const int8_t* src = x + img * H * W;
-        int best = -128;
+        int best[4] = {-128, -128, -128, -128};
         for (int dy = 0; dy < KH; ++dy) {
             const int iy = oy * stride_h - pad_h + dy;
             if ((unsigned)iy >= (unsigned)H) continue;
-            for (int dx = 0; dx < KW; ++dx) {
-                const int ix = ox * stride_w - pad_w + dx;
-                if ((unsigned)ix >= (unsigned)W) continue;
-                best = max(best, (int)src[(int64_t)iy * W + ix]);
+            const int8_t* row = src + (int64_t)iy * W;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int ix0 = (ox0 + j) * stride_w - pad_w;
+                for (int dx = 0; dx < KW; ++dx) {
+                    const int ix = ix0 + dx;
+                    if ((unsigned)ix < (unsigned)W) best[j] = max(best[j], (int)row[ix]);     // columns past OW read nothing new
+                }
             }
         }
-        out[i] = (int8_t)best;
+        int8_t* dst = out + (img * OH + oy) * (int64_t)OW + ox0;
+        if (out_aligned && (OW & 3) == 0) {
+            *reinterpret_cast<uint32_t*>(dst) = ((uint32_t)best[0] & 0xFFu) | (((uint32_t)best[1] & 0xFFu) << 8) |
+                                                (((uint32_t)best[2] & 0xFFu) << 16) | (((uint32_t)best[3] & 0xFFu) << 24);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (ox0 + j < OW) dst[j] = (int8_t)best[j];
+        }
     }
 }
 
