@@ -153,8 +153,8 @@ int psb_linear(const psb_weights_t* q, const int8_t* x_dev, int32_t B, int32_t S
                const float* bias_dev, void* hip_stream);
 
 /*
- * Convolution with the same sample count S at every output [Sect. 3: convolutions
- * "reuse weights and limit their support"; otherwise as psb_linear].  Taps that fall
+ * Convolution with the same sample count S at every output [Sect. 3: a convolution is the
+ * same computation with shared weights and a bounded support; otherwise as psb_linear].  Taps that fall
  * into the padding contribute 0 and are not sampled.
  *  x_dev    device, int8 [N][C][H][W]
  *  acc_dev  device, int32 [N][OC][OH][OW], overwritten
@@ -236,8 +236,8 @@ int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, c
  *     (SHAPE otherwise).  out is [n][c][OH][OW] with the OH/OW rule of psb_conv_geom.
  * psb_global_avgpool_requantize: out[n][c] = clamp( rint( ((float)sum * fl(1/(h*w))) * scale ), lo, hi ),
  *     sum = exact integer sum over the h*w positions (h*w <= 2^23).
- * psb_budget_resample: a budget map at another resolution [Sect. 4.5: the two kinds of regions separate the
- *     activations on all layers], out[n][y][x] = in[n][floor(y*h/oh)][floor(x*w/ow)].
+ * psb_budget_resample: a budget map at another resolution [Sect. 4.5: the two kinds of regions are applied
+ *     to the activations of every layer], out[n][y][x] = in[n][floor(y*h/oh)][floor(x*w/ow)].
  */
 int psb_requantize(const float* y_dev, const float* res_f32_dev, const int8_t* res_i8_dev, float res_step,
                    int32_t relu, float inv_step, int32_t lo, int32_t hi, int64_t n, int8_t* x_dev, void* hip_stream);

@@ -90,8 +90,8 @@ extern "C" uint32_t psbo_uniform7(uint64_t seed, uint32_t layer_id, uint32_t o, 
  * Paper: weights become (s, e, p) (Sect. 3.1); exponents are stored with
  * k_e bits, 4 being enough (Sect. 4.4, suppl. "Stochastic multiplier"); the
  * width of the integers limits the exponents (caption of the multiplier
- * figure); "too many shifts of integers always result in the number 0"
- * (caption of Fig. numbersystem).
+ * figure); an integer shifted too far is simply 0 (caption of Fig.
+ * numbersystem).
  *
  * Reading: activations are integers, so the shift must be >= 0.  Shifts are
  * taken relative to a per-layer e_min and 2^e_min goes into the final rescale.
@@ -129,8 +129,8 @@ extern "C" int psbo_quantize(const float* w, int32_t oc, int32_t K, int32_t prob
             return PSBO_ERR_VALUE;
         }
         if (prob_bits < 23 && cls[i] == PSBO_NORMAL) {
-            /* Sect. 4.4: regular grid with p = 0, without p = 1 ("the right boundary would result
-             * in a higher exponent"); nearbyint rounds half to even in the default rounding mode */
+            /* Sect. 4.4: regular grid with p = 0, without p = 1 (p = 1 is the next exponent);
+             * nearbyint rounds half to even in the default rounding mode */
             const double scale = std::ldexp(1.0, prob_bits);
             double P = std::nearbyint(p * scale);
             if (P >= scale) { P = 0.0; e += 1; }
@@ -578,8 +578,8 @@ extern "C" int psbo_avgpool_requantize(const int8_t* x, int32_t n, int32_t c, in
     return PSBO_OK;
 }
 
-/* Budget map at another resolution (Sect. 4.5: the two kinds of regions separate the activations
- * "on all layers"): nearest source pixel, out[n][y][x] = in[n][floor(y*h/oh)][floor(x*w/ow)]. */
+/* Budget map at another resolution (Sect. 4.5: the two kinds of regions are applied to the
+ * activations of every layer): nearest source pixel, out[n][y][x] = in[n][floor(y*h/oh)][floor(x*w/ow)]. */
 extern "C" int psbo_budget_resample(const uint8_t* in, int32_t n, int32_t h, int32_t w, int32_t oh, int32_t ow,
                                     uint8_t* out)
 {

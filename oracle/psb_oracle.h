@@ -60,7 +60,7 @@ typedef struct { int32_t n, h, w, stride_h, stride_w, pad_h, pad_w; } psbo_geom;
 int psbo_decode(float w, int32_t* s, int32_t* e, double* p);
 
 /* Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).  The paper
- * only asks for "sufficiently independent and evenly distributed" numbers
+ * only asks that the random numbers be independent enough and uniform
  * (suppl. "Random number generation"); the counter-based generator is what
  * makes one result per (inputs, seed) well defined.                            */
 void psbo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
@@ -98,8 +98,8 @@ int psbo_linear(const psbo_weights* q, const int8_t* x, int32_t B, int32_t S,
                 uint64_t seed, uint32_t layer_id, const uint32_t* u_table,
                 int32_t* acc, int64_t* overflow);
 
-/* Same sum for a convolution (Sect. 3: "the same basic computational structure
- * except they reuse weights and limit their support"), NCHW / OIHW, with a
+/* Same sum for a convolution (Sect. 3: a convolution is the same computation with
+ * shared weights and a bounded support), NCHW / OIHW, with a
  * per-output-pixel sample range [from,to) (Sect. 4.5: spatially adaptive
  * sample counts whose first-pass samples are reused).
  *   budget_to   [n][oh][ow] or NULL (=> S_uniform everywhere)

@@ -7,7 +7,7 @@ this file only orders the calls and owns the device buffers.
 
 Sample budgets: either one sample count S for the whole network, or a per-pixel budget map at any
 resolution, which is resampled to the output resolution of every convolution (Sect. 4.5: the regions
-separate the activations "on all layers"); the classifier then uses `s_fc` samples.
+apply to the activations of every layer); the classifier then uses `s_fc` samples.
 """
 import numpy as np
 import torch
