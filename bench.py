@@ -6,7 +6,7 @@
 
 A step is one pass of the whole hot path over one batch of synthetic input that is already resident in
 HBM: the layer call(s) of the workload through the C-ABI (zero-fill, sampling kernel, fp32 rescale).  The
-default workload is BASELINE config 2 (3x3 conv 64->64 on 1x64x56x56, S=16), the ResNet-shaped layer the
+default workload is benchmark configuration 2 (3x3 conv 64->64 on 1x64x56x56, S=16), the ResNet-shaped layer the
 metric is quoted on.  Prints ONE JSON line.
 
 metric  sampled MACs/s: one sampled MAC = one (output element, live tap inside the image, sample)
@@ -44,7 +44,7 @@ sys.path.insert(0, ROOT)
 # profiles/k_layer_oc_lane_config2.md).  Measured for the default workload and mapping only.
 MEASURED_TRAFFIC_BYTES = {("c2", 0): int((3.9 + 55.4) * (1 << 20))}
 
-# ---- ALU roofline constants (derivation in the design doc, measured by csrc/valu_rates.hip) -----------------
+# ---- ALU roofline constants (issue rates measured by csrc/valu_rates.hip) ------------------------------
 CUS, SIMDS_PER_CU, LANES_PER_SIMD_CLK, CLOCK_HZ = 256, 4, 32, 2.4e9
 PEAK_TIOPS = CUS * SIMDS_PER_CU * LANES_PER_SIMD_CLK * CLOCK_HZ / 1e12     # 78.64 T simple int32 lane-ops/s
 WIDE = 2                   # units of a half-rate instruction (multiply, three operands, lane-mask producer/consumer)

@@ -1,4 +1,4 @@
-"""BASELINE configurations at full size, in the launch configuration bench.py times (needs an MI355X).
+"""The five benchmark configurations at full size, in the launch configuration bench.py times (needs an MI355X).
 
 Configs 1, 2, 3 and 5 are compared with the oracle on every output element; the ResNet-18-shaped layers of
 config 4 on every output element at batch 2, and at batch 32 on 100,000 randomly chosen output elements per
