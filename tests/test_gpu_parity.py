@@ -286,3 +286,26 @@ def test_oracle_philox_against_rocrand_host_generator(orc):
     blocks = {tuple(orc.philox([c, 0, 0, 0], key)) for c in range(16)}
     got = {tuple(int(v) for v in out[i:i + 4]) for i in range(0, 64, 4)}
     assert got == blocks
+
+
+def test_two_handles_on_two_streams(psb, orc):
+    """Calls on different handles may overlap in time: two layers enqueued alternately on two streams (default
+    priority) give the bits of the calls made one after the other."""
+    import torch
+    rng = np.random.default_rng(400)
+    La = _layer(rng, 2, 32, 64, 12, 3, pad=1, S=16, seed=5, layer_id=1)
+    Lb = _layer(rng, 2, 20, 70, (9, 11), 3, pad=1, S=8, seed=6, layer_id=2)
+    refs = [helpers.oracle_layer(orc, L)[0] for L in (La, Lb)]
+    qs = [helpers.gpu_quantize(psb, L) for L in (La, Lb)]
+    xs = [torch.from_numpy(L.x).cuda() for L in (La, Lb)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [[], []]
+    torch.cuda.synchronize()
+    for rep in range(6):
+        for i, L in enumerate((La, Lb)):
+            with torch.cuda.stream(streams[i]):
+                outs[i].append(psb.conv2d(qs[i], xs[i], L.S, pad=L.pad, seed=L.seed, layer_id=L.layer_id))
+    torch.cuda.synchronize()
+    for i in range(2):
+        for acc in outs[i]:
+            assert np.array_equal(acc.cpu().numpy(), refs[i])
