@@ -239,6 +239,27 @@ int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, c
  * psb_budget_resample: a budget map at another resolution [Sect. 4.5: the two kinds of regions are applied
  *     to the activations of every layer], out[n][y][x] = in[n][floor(y*h/oh)][floor(x*w/ow)].
  */
+/* A layer call with psb_requantize fused into its epilogue: the next layer's activations leave the kernel that
+ * produced the accumulators, without a round trip of the fp32 values through memory.
+ *   x_out[o] = clamp( rint( g( y[o] [+ r[o]] ) * inv_step ), lo, hi )  with y as defined for psb_linear and
+ *   g, r, rint exactly as in psb_requantize (residual operands are indexed like the output, [N][OC][OH][OW]).
+ * budget_to_dev NULL: S samples everywhere; non-NULL: the per-pixel budget map of psb_conv2d_progressive
+ * (no refinement form).  shared != 0 selects the shared-filter mode.  A linear layer is geometry {B,1,1,1,1,0,0}.
+ * acc_dev is written as usual; y_dev may be NULL.  Errors: those of the layer call, plus NULL (rq, x_out_dev)
+ * and VALUE (two residual operands, bad clamp range). */
+typedef struct {
+    int32_t relu;                 /* != 0: g = max(., 0)                                */
+    float inv_step;
+    int32_t lo, hi;               /* -128 <= lo <= hi <= 127                            */
+    const float* res_f32_dev;     /* at most one of the two residual operands, or none */
+    const int8_t* res_i8_dev;
+    float res_step;
+} psb_requant;
+int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S,
+                       const uint8_t* budget_to_dev, uint64_t seed, uint32_t layer_id, int32_t* acc_dev,
+                       float* y_dev, const float* mult_dev, const float* bias_dev, const psb_requant* rq,
+                       int8_t* x_out_dev, int32_t shared, void* hip_stream);
+
 int psb_requantize(const float* y_dev, const float* res_f32_dev, const int8_t* res_i8_dev, float res_step,
                    int32_t relu, float inv_step, int32_t lo, int32_t hi, int64_t n, int8_t* x_dev, void* hip_stream);
 int psb_maxpool2d_i8(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, int32_t kh, int32_t kw,

@@ -156,7 +156,8 @@ void fill_geometry(const psb_weights* q, const psb_conv_geom* g, int32_t OH, int
 
 int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, int32_t S,
                  const uint8_t* budget_to, const uint8_t* budget_from, uint64_t seed, uint32_t layer_id,
-                 int32_t* acc, float* y, const float* mult, const float* bias, hipStream_t stream)
+                 int32_t* acc, float* y, const float* mult, const float* bias, hipStream_t stream,
+                 const psb::Requant* rq = nullptr)
 {
     int32_t OH = 0, OW = 0;
     int rc = check_geom(&q->shape, g, &OH, &OW);
@@ -167,6 +168,7 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
     p.packed = q->packed_dev; p.tile = q->tile_dev; p.x = x;
     p.budget_to = budget_to; p.budget_from = budget_from;
     p.acc = acc; p.y = y; p.mult = mult; p.bias = bias;
+    if (rq) p.rq = *rq;
     p.S = S;
     p.key0 = (uint32_t)(seed & 0xFFFFFFFFull); p.key1 = (uint32_t)(seed >> 32); p.layer_id = layer_id;
 
@@ -222,7 +224,7 @@ int sample_filter_launch(const psb_weights* q, int from, int to, uint64_t seed, 
 
 int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, int32_t S, const uint8_t* budget_to,
                   const uint8_t* budget_from, uint64_t seed, uint32_t layer_id, int32_t* acc, float* y,
-                  const float* mult, const float* bias, hipStream_t stream)
+                  const float* mult, const float* bias, hipStream_t stream, const psb::Requant* rq = nullptr)
 {
     int32_t OH = 0, OW = 0;
     int rc = check_geom(&q->shape, g, &OH, &OW);
@@ -272,6 +274,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     p.x = x; p.xt = ws->xt_dev; p.planes = ws->planes_dev; p.w32 = ws->w32_dev;
     p.budget_to = budget_to; p.budget_from = budget_from;
     p.acc = acc; p.y = y; p.mult = mult; p.bias = bias;
+    if (rq) p.rq = *rq;
     p.N = g->n; p.C = q->shape.cin; p.H = g->h; p.W = g->w;
     p.OC = q->shape.oc; p.OH = OH; p.OW = OW; p.KH = q->shape.kh; p.KW = q->shape.kw;
     p.Cg = q->shape.cin / q->shape.groups; p.OCg = q->shape.oc / q->shape.groups;
@@ -342,6 +345,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         psb::LayerParams lp;
         fill_geometry(q, g, OH, OW, lp);
         lp.acc = acc; lp.y = y; lp.mult = mult; lp.bias = bias; lp.budget_to = budget_to; lp.S = S;
+        if (rq) lp.rq = *rq;
         const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
         hipLaunchKernelGGL(psb::k_rescale, dim3(blocks), dim3(256), 0, stream, lp);
         PSB_HIP_TRY(hipGetLastError());
@@ -363,7 +367,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         }
         rc = contract(S);
         if (rc != PSB_OK) return rc;
-        if (p.ksplit > 1 && y) return rescale_pass();
+        if (p.ksplit > 1 && (y || rq)) return rescale_pass();
         return PSB_OK;
     }
 
@@ -395,7 +399,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         }
         prev = v;
     }
-    if (y) return rescale_pass();
+    if (y || rq) return rescale_pass();
     return PSB_OK;
 }
 
@@ -664,6 +668,25 @@ int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, c
     if (!q || !x_dev || !geom || !budget_to_dev || !acc_dev) return PSB_ERR_NULL;
     return launch_shared(q, x_dev, geom, 0, budget_to_dev, budget_from_dev, seed, layer_id, acc_dev, y_dev, mult_dev,
                          bias_dev, (hipStream_t)hip_stream);
+}
+
+int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S,
+                       const uint8_t* budget_to_dev, uint64_t seed, uint32_t layer_id, int32_t* acc_dev, float* y_dev,
+                       const float* mult_dev, const float* bias_dev, const psb_requant* rq, int8_t* x_out_dev,
+                       int32_t shared, void* hip_stream)
+{
+    if (!q || !x_dev || !geom || !acc_dev || !rq || !x_out_dev) return PSB_ERR_NULL;
+    if (!budget_to_dev && (S <= 0 || S > q->s_max)) return PSB_ERR_VALUE;
+    if (rq->res_f32_dev && rq->res_i8_dev) return PSB_ERR_VALUE;
+    if (rq->lo < -128 || rq->hi > 127 || rq->lo > rq->hi) return PSB_ERR_VALUE;
+    psb::Requant r;
+    r.x_out = x_out_dev; r.res_f32 = rq->res_f32_dev; r.res_i8 = rq->res_i8_dev; r.res_step = rq->res_step;
+    r.inv_step = rq->inv_step; r.lo = (float)rq->lo; r.hi = (float)rq->hi; r.relu = rq->relu;
+    if (shared)
+        return launch_shared(q, x_dev, geom, budget_to_dev ? 0 : S, budget_to_dev, nullptr, seed, layer_id, acc_dev, y_dev,
+                             mult_dev, bias_dev, (hipStream_t)hip_stream, &r);
+    return launch_layer(q, x_dev, geom, budget_to_dev ? 0 : S, budget_to_dev, nullptr, seed, layer_id, acc_dev, y_dev,
+                        mult_dev, bias_dev, (hipStream_t)hip_stream, &r);
 }
 
 // ---- glue between layers ------------------------------------------------------------------------------

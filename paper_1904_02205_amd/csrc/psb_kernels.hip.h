@@ -157,6 +157,17 @@ __global__ void __launch_bounds__(256) k_pack(const uint32_t* __restrict__ w_bit
 // Layer kernels
 // ---------------------------------------------------------------------------------
 
+// Optional second output of a layer call: the next layer's 8-bit activations, made from the rescaled value in
+// the same kernel (suppl. "ReLU, Batch-Norm, and Pooling": ReLU as a gate on the sign; "Activations and
+// Accumulation": fixed-point activations):  x = clamp(rint(g(y [+ r]) * inv_step), lo, hi).
+struct Requant {
+    int8_t* x_out;            // null: no fused requantisation
+    const float* res_f32;     // residual operand, or null
+    const int8_t* res_i8;     // residual operand as integers times res_step, or null
+    float res_step, inv_step, lo, hi;
+    int relu;
+};
+
 struct LayerParams {
     // tensors
     const uint32_t* packed;    // [OC][K]
@@ -177,6 +188,7 @@ struct LayerParams {
     uint32_t key0, key1, layer_id;
     float default_mult;        // 2^e_min
     int max_shift;             // largest shift of a live weight
+    Requant rq;
 };
 
 // Number of samples i in [from,to) of product (o,k) whose uniform is below thr.
@@ -242,6 +254,41 @@ __device__ __forceinline__ float rescale(int32_t acc, float mult, int to, const 
     return r;
 }
 
+// clamp(rint(v), lo, hi) as an integer; NaN goes to lo
+__device__ __forceinline__ int32_t round_clamp(float v, float lo, float hi)
+{
+    float q = rintf(v);               // v_rndne_f32: ties to even
+    if (!(q >= lo)) q = lo;
+    if (q > hi) q = hi;
+    return (int32_t)q;
+}
+
+__device__ __forceinline__ int32_t requantize_one(float y, bool has_res, float r, bool relu, float inv_step, float lo,
+                                                  float hi)
+{
+    float t = y;
+    if (has_res) t = __fadd_rn(t, r);
+    if (relu && !(t > 0.0f)) t = 0.0f;
+    return round_clamp(__fmul_rn(t, inv_step), lo, hi);
+}
+
+// Everything a layer kernel writes besides the accumulator: the rescaled value and/or the requantised activation
+// of output element o (channel oc, `to` samples).  P is LayerParams or the shared-filter mode's parameter block.
+template <class P>
+__device__ __forceinline__ void emit(const P& p, int64_t o, int oc, int32_t acc, int to)
+{
+    if (!p.y && !p.rq.x_out) return;
+    const float r = rescale(acc, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+    if (p.y) p.y[o] = r;
+    if (p.rq.x_out) {
+        float res = 0.0f;
+        if (p.rq.res_f32) res = p.rq.res_f32[o];
+        if (p.rq.res_i8) res = __fmul_rn((float)p.rq.res_i8[o], p.rq.res_step);
+        p.rq.x_out[o] = (int8_t)requantize_one(r, p.rq.res_f32 || p.rq.res_i8, res, p.rq.relu != 0, p.rq.inv_step,
+                                               p.rq.lo, p.rq.hi);
+    }
+}
+
 // One output element per lane; blockIdx.y = output channel, so the weight word and the
 // tap position are wave-uniform (scalar loads, scalar branches on dead weights) and the
 // activation reads of neighbouring lanes are neighbouring bytes.
@@ -292,7 +339,7 @@ __global__ void __launch_bounds__(256) k_layer_pixel_lane(const LayerParams p)
     }
     if (p.budget_from) acc += p.acc[o];
     p.acc[o] = acc;
-    if (p.y) p.y[o] = rescale(acc, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+    emit(p, o, oc, acc, to);
 }
 
 }  // namespace psb

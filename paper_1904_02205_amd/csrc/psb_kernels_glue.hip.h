@@ -8,25 +8,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "psb_kernels.hip.h"
+
 namespace psb {
-
-// clamp(rint(v), lo, hi) as an integer; NaN goes to lo
-__device__ __forceinline__ int32_t round_clamp(float v, float lo, float hi)
-{
-    float q = rintf(v);               // v_rndne_f32: ties to even
-    if (!(q >= lo)) q = lo;
-    if (q > hi) q = hi;
-    return (int32_t)q;
-}
-
-__device__ __forceinline__ int32_t requantize_one(float y, bool has_res, float r, bool relu, float inv_step, float lo,
-                                                  float hi)
-{
-    float t = y;
-    if (has_res) t = __fadd_rn(t, r);
-    if (relu && !(t > 0.0f)) t = 0.0f;
-    return round_clamp(__fmul_rn(t, inv_step), lo, hi);
-}
 
 // Four elements per thread when every pointer is 16-byte (int8: 4-byte) aligned, else one.
 template <bool VEC>

@@ -431,7 +431,7 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
                 if (n_chunks == 1) {
                     if (p.budget_from) total += p.acc[o];
                     p.acc[o] = total;
-                    if (p.y) p.y[o] = rescale(total, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+                    emit(p, o, oc, total, to);
                 } else if (total != 0) {
                     atomicAdd(&p.acc[o], total);
                 }
@@ -458,7 +458,7 @@ __global__ void __launch_bounds__(256) k_fill_zero(int32_t* __restrict__ acc, in
         acc[i] = 0;
 }
 
-// y = rescale(acc) for layers whose accumulators were combined with atomics.
+// Rescaled value and/or requantised activation for layers whose accumulators were combined with atomics.
 __global__ void __launch_bounds__(256) k_rescale(const LayerParams p)
 {
     const int64_t total = (int64_t)p.N * p.OC * p.OH * p.OW;
@@ -468,7 +468,7 @@ __global__ void __launch_bounds__(256) k_rescale(const LayerParams p)
         const int64_t pix = (i / (hw * p.OC)) * hw + (i % hw);
         int to = p.budget_to ? (int)p.budget_to[pix] : p.S;
         to = min(to, p.s_max);
-        p.y[i] = rescale(p.acc[i], p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+        emit(p, i, oc, p.acc[i], to);
     }
 }
 
@@ -540,7 +540,7 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
     if (timed) prof_end(stream, slot);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
-    if (n_chunks > 1 && p.y) {
+    if (n_chunks > 1 && (p.y || p.rq.x_out)) {
         const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
         hipLaunchKernelGGL(k_rescale, dim3(blocks), dim3(256), 0, stream, p);
         e = hipGetLastError();

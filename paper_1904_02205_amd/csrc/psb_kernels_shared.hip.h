@@ -60,6 +60,7 @@ struct SharedParams {
     int masked;                // 0: every pixel, acc overwritten, epilogue fused.  1: only pixels whose sample
     int seg_from, seg_to;      //    range contains [seg_from, seg_to); acc accumulated
     float default_mult;
+    Requant rq;
 };
 
 // One thread per weight: count, filter value, digit planes.
@@ -375,7 +376,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
                 atomicAdd(&p.acc[o], (int32_t)v);           // exact in any order: the arithmetic is modulo 2^32
             } else {
                 p.acc[o] = (int32_t)v;
-                if (p.y) p.y[o] = rescale((int32_t)v, p.mult ? p.mult[oc] : p.default_mult, to_[h], p.bias, oc);
+                emit(p, o, oc, (int32_t)v, to_[h]);
             }
         }
     }
@@ -411,7 +412,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_direct(const SharedParams p
         p.acc[o] = (int32_t)((uint32_t)p.acc[o] + sum);
     } else {
         p.acc[o] = (int32_t)sum;
-        if (p.y) p.y[o] = rescale((int32_t)sum, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
+        emit(p, o, oc, (int32_t)sum, to);
     }
 }
 

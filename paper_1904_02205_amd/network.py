@@ -48,6 +48,20 @@ class ResNet18:
                 steps.append(rs.STEP_BLOCK)         # block inputs and the classifier
         return steps
 
+    def _conv_requant(self, i, x, S, budget, shared, inv_step, res_f32=None, res_i8=None, res_step=0.0):
+        """Convolution i with ReLU, residual and requantisation fused into its epilogue: int8 activations."""
+        sp = self.net.specs[i]
+        if self.record_inputs:
+            self.inputs[i] = x
+        bt = None
+        if budget is not None:
+            oh = (x.shape[2] + 2 * sp.pad - sp.k) // sp.stride + 1
+            bt = psb.budget_resample(budget, oh, oh)
+        return psb.conv2d_requant(self.q[i], x, inv_step, S=None if bt is not None else S, budget_to=bt,
+                                  stride=(sp.stride, sp.stride), pad=(sp.pad, sp.pad), seed=self.seed, layer_id=i,
+                                  res_f32=res_f32, res_i8=res_i8, res_step=res_step, mult=self.mult[i],
+                                  bias=self.bias[i], shared=shared)
+
     def _conv(self, i, x, S, budget, shared):
         sp = self.net.specs[i]
         if self.record_inputs:
@@ -64,11 +78,16 @@ class ResNet18:
             psb.conv2d_progressive(self.q[i], x, psb.budget_resample(budget, oh, oh), None, **kw)
         return y
 
-    def forward(self, S=8, budget=None, s_fc=None, shared=False, collect=None):
-        """Logits float32 [batch, classes].  collect: optional list that receives every int8 activation tensor."""
+    def forward(self, S=8, budget=None, s_fc=None, shared=False, collect=None, fused=True):
+        """Logits float32 [batch, classes].  collect: optional list that receives every int8 activation tensor.
+        fused: requantisation in the epilogue of the layer kernels (default) or as separate glue kernels; the
+        activations are the same integers either way."""
         keep = (lambda t: collect.append(t)) if collect is not None else (lambda t: None)
         inv_relu, inv_block = float(np.float32(1.0 / rs.STEP_RELU)), float(np.float32(1.0 / rs.STEP_BLOCK))
-        a = psb.requantize(self._conv(0, self.x0, S, budget, shared), inv_relu)
+        if fused:
+            a = self._conv_requant(0, self.x0, S, budget, shared, inv_relu)
+        else:
+            a = psb.requantize(self._conv(0, self.x0, S, budget, shared), inv_relu)
         keep(a)
         a = psb.maxpool2d_i8(a, (3, 3), (2, 2), (1, 1))
         keep(a)
@@ -76,13 +95,23 @@ class ResNet18:
         i = 1
         while self.names[i] != "fc":
             has_sc = self.names[i + 2].endswith("sc")
-            a1 = psb.requantize(self._conv(i, a, S, budget, shared), inv_relu)
-            keep(a1)
-            y2 = self._conv(i + 1, a1, S, budget, shared)
-            if has_sc:
-                a = psb.requantize(y2, inv_block, res_f32=self._conv(i + 2, a, S, budget, shared))
+            if fused:
+                a1 = self._conv_requant(i, a, S, budget, shared, inv_relu)
+                keep(a1)
+                if has_sc:
+                    a = self._conv_requant(i + 1, a1, S, budget, shared, inv_block,
+                                           res_f32=self._conv(i + 2, a, S, budget, shared))
+                else:
+                    a = self._conv_requant(i + 1, a1, S, budget, shared, inv_block, res_i8=a,
+                                           res_step=float(np.float32(step_a)))
             else:
-                a = psb.requantize(y2, inv_block, res_i8=a, res_step=float(np.float32(step_a)))
+                a1 = psb.requantize(self._conv(i, a, S, budget, shared), inv_relu)
+                keep(a1)
+                y2 = self._conv(i + 1, a1, S, budget, shared)
+                if has_sc:
+                    a = psb.requantize(y2, inv_block, res_f32=self._conv(i + 2, a, S, budget, shared))
+                else:
+                    a = psb.requantize(y2, inv_block, res_i8=a, res_step=float(np.float32(step_a)))
             keep(a)
             step_a = rs.STEP_BLOCK
             i += 3 if has_sc else 2

@@ -21,7 +21,7 @@ MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE, MAPPING_PRODUCT_LIST = 0
 SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
            "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
-           "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
+           "psb_conv2d_requant", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
            "psb_attention_budget", "psb_last_device_error", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
            "psb_profile_read"]
 
@@ -42,6 +42,11 @@ class WShape(C.Structure):
 class ConvGeom(C.Structure):
     _fields_ = [("n", C.c_int32), ("h", C.c_int32), ("w", C.c_int32), ("stride_h", C.c_int32),
                 ("stride_w", C.c_int32), ("pad_h", C.c_int32), ("pad_w", C.c_int32)]
+
+
+class Requant(C.Structure):
+    _fields_ = [("relu", C.c_int32), ("inv_step", C.c_float), ("lo", C.c_int32), ("hi", C.c_int32),
+                ("res_f32_dev", C.c_void_p), ("res_i8_dev", C.c_void_p), ("res_step", C.c_float)]
 
 
 class WInfo(C.Structure):
@@ -79,6 +84,8 @@ def lib():
         L.psb_conv2d_shared.argtypes = L.psb_conv2d.argtypes
         L.psb_conv2d_progressive_shared.argtypes = L.psb_conv2d_progressive.argtypes
         f32 = C.c_float
+        L.psb_conv2d_requant.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, vp, u64, u32, vp, vp, vp, vp,
+                                         C.POINTER(Requant), vp, i32, vp]
         L.psb_requantize.argtypes = [vp, vp, vp, f32, i32, f32, i32, i32, C.c_int64, vp, vp]
         L.psb_maxpool2d_i8.argtypes = [vp] + [i32] * 10 + [vp, vp]
         L.psb_global_avgpool_requantize.argtypes = [vp, i32, i32, i32, i32, f32, i32, i32, vp, vp]
@@ -241,6 +248,29 @@ def conv2d_progressive(q, x, budget_to, budget_from=None, stride=(1, 1), pad=(0,
             _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
     _check(rc, "psb_conv2d_progressive_shared" if shared else "psb_conv2d_progressive")
     return acc
+
+
+def conv2d_requant(q, x, inv_step, S=None, budget_to=None, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, relu=True,
+                   lo=0, hi=127, res_f32=None, res_i8=None, res_step=0.0, mult=None, bias=None, acc=None, y=None,
+                   x_out=None, shared=False):
+    """Layer call with the requantisation fused in: returns the int8 activations [N, OC, OH, OW] (acc is written too)."""
+    g = _geom(x, stride, pad)
+    oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
+    shape = (g.n, q.wshape[0], oh, ow)
+    if acc is None:
+        acc = torch.empty(shape, dtype=torch.int32, device=x.device)
+    if x_out is None:
+        x_out = torch.empty(shape, dtype=torch.int8, device=x.device)
+    rq = Requant(1 if relu else 0, inv_step, lo, hi,
+                 None if res_f32 is None else _ptr(res_f32, torch.float32, "res_f32").value,
+                 None if res_i8 is None else _ptr(res_i8, torch.int8, "res_i8").value, res_step)
+    rc = lib().psb_conv2d_requant(q._h, _ptr(x, torch.int8, "x"), C.byref(g), 0 if S is None else S,
+                                  _ptr(budget_to, torch.uint8, "budget_to"), seed, layer_id,
+                                  _ptr(acc, torch.int32, "acc"), _ptr(y, torch.float32, "y"),
+                                  _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), C.byref(rq),
+                                  _ptr(x_out, torch.int8, "x_out"), 1 if shared else 0, _stream())
+    _check(rc, "psb_conv2d_requant")
+    return x_out
 
 
 # ---- glue between layers ---------------------------------------------------------------------------------

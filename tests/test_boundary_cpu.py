@@ -85,6 +85,7 @@ def test_later_entry_points_validate_on_the_host(psb):
     assert L.psb_linear_shared(None, P, 1, 1, 0, 0, P, None, None, None, None) == psb.ERR_NULL
     assert L.psb_conv2d_shared(None, P, C.byref(g), 1, 0, 0, P, None, None, None, None) == psb.ERR_NULL
     assert L.psb_conv2d_progressive_shared(None, P, C.byref(g), P, None, 0, 0, P, None, None, None, None) == psb.ERR_NULL
+    assert L.psb_conv2d_requant(None, P, C.byref(g), 4, None, 0, 0, P, None, None, None, None, P, 0, None) == psb.ERR_NULL
     # requantize
     rq = L.psb_requantize
     assert rq(None, None, None, 0.0, 1, 1.0, 0, 127, 8, P, None) == psb.ERR_NULL

@@ -90,12 +90,65 @@ def test_budget_resample(psb, orc):
         assert np.array_equal(got, orc.budget_resample(b, oh, ow))
 
 
+@pytest.mark.parametrize("shared", [False, True])
+def test_fused_requantisation_equals_layer_then_requantize(psb, orc, shared):
+    """psb_conv2d_requant on every kernel vs the oracle's layer -> rescale -> requantize chain."""
+    import torch
+    import helpers
+    from test_gpu_parity import _layer
+    rng = np.random.default_rng(77)
+    cases = [(_layer(rng, 2, 20, 70, (9, 11), 3, pad=1, S=8), (1, 2, 3, 0)),            # several tap chunks
+             (_layer(rng, 2, 24, 40, 9, 1, stride=2, S=4), (1, 2, 3, 0)),               # one chunk: fused in the sampling kernel
+             (_layer(rng, 1, 256, 64, 6, 3, pad=1, S=8), (0,)),                         # shared: split reduction
+             (_layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), (1, 3, 0))]         # depthwise
+    inv = float(np.float32(127.0 / 6.0))
+    for L, mappings in cases:
+        oc = L.w.shape[0]
+        mult = (rng.uniform(0.5, 2.0, size=oc) * 2.0 ** -6).astype(np.float32)
+        bias = rng.standard_normal(oc).astype(np.float32)
+        qo, qg = helpers.oracle_quantize(orc, L), helpers.gpu_quantize(psb, L)
+        x = torch.from_numpy(L.x).cuda()
+        oh, ow = L.out_hw
+        shape = (L.x.shape[0], oc, oh, ow)
+        res = (rng.standard_normal(shape) * 2).astype(np.float32)
+        res8 = rng.integers(0, 128, size=shape).astype(np.int8)
+        budget = rng.choice([0, 2, L.S], size=(shape[0], oh, ow)).astype(np.uint8)
+        for bt in (None, budget):
+            acc, _, _ = helpers.oracle_layer(orc, L, qo, budget_to=bt, shared=shared)
+            y = orc.rescale(acc, qo.e_min, S=None if bt is not None else L.S, s_max=L.s_max, budget_to=bt, mult=mult,
+                            bias=bias)
+            for kw_o, kw_g in ((dict(), dict()),
+                               (dict(res_f32=res), dict(res_f32=torch.from_numpy(res).cuda())),
+                               (dict(res_i8=res8, res_step=np.float32(0.05)),
+                                dict(res_i8=torch.from_numpy(res8).cuda(), res_step=float(np.float32(0.05)))),
+                               (dict(relu=False, lo=-128, hi=127), dict(relu=False, lo=-128, hi=127))):
+                ref = orc.requantize(y, inv, **kw_o)
+                for m in mappings:
+                    psb.set_mapping(m)
+                    accg = torch.empty(shape, dtype=torch.int32, device="cuda")
+                    got = psb.conv2d_requant(qg, x, inv, S=None if bt is not None else L.S,
+                                             budget_to=None if bt is None else torch.from_numpy(bt).cuda(),
+                                             stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id,
+                                             mult=torch.from_numpy(mult).cuda(), bias=torch.from_numpy(bias).cuda(),
+                                             acc=accg, shared=shared, **kw_g)
+                    assert np.array_equal(accg.cpu().numpy(), acc), (L.w.shape, m)
+                    assert np.array_equal(got.cpu().numpy(), ref), (L.w.shape, m, list(kw_o))
+    psb.set_mapping(psb.MAPPING_AUTO)
+    q = psb.Weights(torch.ones((4, 4, 1, 1), device="cuda"))
+    xx = torch.zeros((1, 4, 2, 2), dtype=torch.int8, device="cuda")
+    for kw in (dict(lo=-129), dict(hi=128), dict(lo=3, hi=2), dict(S=0), dict(S=17)):
+        with pytest.raises(psb.PsbError) as ei:
+            psb.conv2d_requant(q, xx, 1.0, **{**dict(S=4), **kw})
+        assert ei.value.code == psb.ERR_VALUE
+
+
 # ------------------------------------------------------------------ the chained network
 
 def _compare(psb, orc, net, prob_bits=23, **kw):
     from paper_1904_02205_amd import network
     ref_acts, got_acts = [], []
-    ref = oracle_network.OracleResNet18(orc, net, prob_bits=prob_bits).forward(collect=ref_acts, **kw)
+    kw_ref = {k: v for k, v in kw.items() if k != "fused"}
+    ref = oracle_network.OracleResNet18(orc, net, prob_bits=prob_bits).forward(collect=ref_acts, **kw_ref)
     model = network.ResNet18(net, prob_bits=prob_bits)
     kw_g = dict(kw)
     if kw_g.get("budget") is not None:
@@ -112,6 +165,8 @@ def _compare(psb, orc, net, prob_bits=23, **kw):
 def test_network_end_to_end(psb, orc):
     net = rs.resnet18(batch=2, hw=64, width=32, classes=10)
     a = _compare(psb, orc, net, S=8)
+    _compare(psb, orc, net, S=8, fused=False)
+    _compare(psb, orc, net, S=8, shared=True, fused=False)
     b = _compare(psb, orc, net, S=8, shared=True)
     assert not np.array_equal(a, b)
     _compare(psb, orc, net, prob_bits=4, S=16)
