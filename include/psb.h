@@ -245,8 +245,11 @@ int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, c
  *   g, r, rint exactly as in psb_requantize (residual operands are indexed like the output, [N][OC][OH][OW]).
  * budget_to_dev NULL: S samples everywhere; non-NULL: the per-pixel budget map of psb_conv2d_progressive
  * (no refinement form).  shared != 0 selects the shared-filter mode.  A linear layer is geometry {B,1,1,1,1,0,0}.
- * acc_dev is written as usual; y_dev may be NULL.  Errors: those of the layer call, plus NULL (rq, x_out_dev)
- * and VALUE (two residual operands, bad clamp range). */
+ * y_dev may be NULL, and so may acc_dev: then no accumulators are handed out (a network pass does not read
+ * them), which saves their write; where a kernel combines partial sums in the accumulators the library uses
+ * scratch memory owned by the handle instead (allocated on first use, grown on demand).
+ * Errors: those of the layer call, plus NULL (rq, x_out_dev), VALUE (two residual operands, bad clamp range)
+ * and ALLOC. */
 typedef struct {
     int32_t relu;                 /* != 0: g = max(., 0)                                */
     float inv_step;

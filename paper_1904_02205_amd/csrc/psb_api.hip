@@ -23,7 +23,25 @@ struct shared_workspace {
     int8_t* xt_dev = nullptr;        // channels-last copy of the activations
     size_t xt_bytes = 0;
     uint32_t* present_dev = nullptr; // 256 flags: budget values that occur
+    int32_t* acc_dev = nullptr;      // accumulators of calls that do not hand any out but combine partial sums
+    size_t acc_bytes = 0;
 };
+
+// Accumulator scratch of a handle for psb_conv2d_requant calls without acc_dev (grown on demand).
+int32_t* scratch_acc(shared_workspace* ws, size_t bytes, hipStream_t stream)
+{
+    if (ws->acc_bytes < bytes) {
+        if (ws->acc_dev) {
+            if (hipStreamSynchronize(stream) != hipSuccess) return nullptr;   // an earlier call may still use it
+            (void)hipFree(ws->acc_dev);
+            ws->acc_dev = nullptr;
+            ws->acc_bytes = 0;
+        }
+        if (hipMalloc(&ws->acc_dev, bytes) != hipSuccess) return nullptr;
+        ws->acc_bytes = bytes;
+    }
+    return ws->acc_dev;
+}
 
 struct psb_weights {
     psb_wshape shape;
@@ -178,6 +196,10 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
 
     const int mapping = pick_mapping(q, p);
     if (mapping < 0) return mapping;
+    if (!p.acc && mapping == 2) {       // the channel-lane kernel may combine partial sums in the accumulators
+        p.acc = scratch_acc(q->ws, (size_t)p.N * p.OC * OH * OW * sizeof(int32_t), stream);
+        if (!p.acc) return PSB_ERR_ALLOC;
+    }
 
     if (mapping == 2) {
         rc = psb::launch_oc_lane(p, q->sched_dev, stream, profile_begin, profile_end);
@@ -341,6 +363,11 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     };
 
     const int64_t total = npix * p.OC;
+    if (!acc && (p.ksplit > 1 || budget_to)) {      // partial sums meet in the accumulators
+        acc = scratch_acc(ws, (size_t)total * sizeof(int32_t), stream);
+        if (!acc) return PSB_ERR_ALLOC;
+        p.acc = acc;
+    }
     auto rescale_pass = [&]() -> int {
         psb::LayerParams lp;
         fill_geometry(q, g, OH, OW, lp);
@@ -591,6 +618,7 @@ void psb_weights_destroy(psb_weights_t* q)
         if (q->ws->planes_dev) (void)hipFree(q->ws->planes_dev);
         if (q->ws->xt_dev) (void)hipFree(q->ws->xt_dev);
         if (q->ws->present_dev) (void)hipFree(q->ws->present_dev);
+        if (q->ws->acc_dev) (void)hipFree(q->ws->acc_dev);
         delete q->ws;
     }
     delete q;
@@ -675,7 +703,7 @@ int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_co
                        const float* mult_dev, const float* bias_dev, const psb_requant* rq, int8_t* x_out_dev,
                        int32_t shared, void* hip_stream)
 {
-    if (!q || !x_dev || !geom || !acc_dev || !rq || !x_out_dev) return PSB_ERR_NULL;
+    if (!q || !x_dev || !geom || !rq || !x_out_dev) return PSB_ERR_NULL;
     if (!budget_to_dev && (S <= 0 || S > q->s_max)) return PSB_ERR_VALUE;
     if (rq->res_f32_dev && rq->res_i8_dev) return PSB_ERR_VALUE;
     if (rq->lo < -128 || rq->hi > 127 || rq->lo > rq->hi) return PSB_ERR_VALUE;

@@ -338,7 +338,7 @@ __global__ void __launch_bounds__(256) k_layer_pixel_lane(const LayerParams p)
         }
     }
     if (p.budget_from) acc += p.acc[o];
-    p.acc[o] = acc;
+    if (p.acc) p.acc[o] = acc;          // null: the caller only wants the requantised activations
     emit(p, o, oc, acc, to);
 }
 

@@ -226,7 +226,7 @@ __global__ void __launch_bounds__(kListPixels) k_layer_product_list(const LayerP
     if (valid) {
         int32_t total = acc_s[tid];
         if (p.budget_from) total += p.acc[o];
-        p.acc[o] = total;
+        if (p.acc) p.acc[o] = total;
         emit(p, o, oc, total, to);
     }
     }   // channels of this workgroup (acc_s and o_s are only touched by their own lane between the barriers)

@@ -430,7 +430,7 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
             if (oc < p.OC) {
                 if (n_chunks == 1) {
                     if (p.budget_from) total += p.acc[o];
-                    p.acc[o] = total;
+                    if (p.acc) p.acc[o] = total;
                     emit(p, o, oc, total, to);
                 } else if (total != 0) {
                     atomicAdd(&p.acc[o], total);

@@ -375,7 +375,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
             if (p.masked || p.ksplit > 1) {
                 atomicAdd(&p.acc[o], (int32_t)v);           // exact in any order: the arithmetic is modulo 2^32
             } else {
-                p.acc[o] = (int32_t)v;
+                if (p.acc) p.acc[o] = (int32_t)v;
                 emit(p, o, oc, (int32_t)v, to_[h]);
             }
         }
@@ -411,7 +411,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_direct(const SharedParams p
     if (p.masked) {
         p.acc[o] = (int32_t)((uint32_t)p.acc[o] + sum);
     } else {
-        p.acc[o] = (int32_t)sum;
+        if (p.acc) p.acc[o] = (int32_t)sum;
         emit(p, o, oc, (int32_t)sum, to);
     }
 }

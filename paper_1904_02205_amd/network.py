@@ -60,7 +60,7 @@ class ResNet18:
         return psb.conv2d_requant(self.q[i], x, inv_step, S=None if bt is not None else S, budget_to=bt,
                                   stride=(sp.stride, sp.stride), pad=(sp.pad, sp.pad), seed=self.seed, layer_id=i,
                                   res_f32=res_f32, res_i8=res_i8, res_step=res_step, mult=self.mult[i],
-                                  bias=self.bias[i], shared=shared)
+                                  bias=self.bias[i], shared=shared, want_acc=False)
 
     def _conv(self, i, x, S, budget, shared):
         sp = self.net.specs[i]

@@ -252,12 +252,13 @@ def conv2d_progressive(q, x, budget_to, budget_from=None, stride=(1, 1), pad=(0,
 
 def conv2d_requant(q, x, inv_step, S=None, budget_to=None, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, relu=True,
                    lo=0, hi=127, res_f32=None, res_i8=None, res_step=0.0, mult=None, bias=None, acc=None, y=None,
-                   x_out=None, shared=False):
-    """Layer call with the requantisation fused in: returns the int8 activations [N, OC, OH, OW] (acc is written too)."""
+                   x_out=None, shared=False, want_acc=True):
+    """Layer call with the requantisation fused in: returns the int8 activations [N, OC, OH, OW].  want_acc=False
+    (and acc None): no accumulators are handed out."""
     g = _geom(x, stride, pad)
     oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
     shape = (g.n, q.wshape[0], oh, ow)
-    if acc is None:
+    if acc is None and want_acc:
         acc = torch.empty(shape, dtype=torch.int32, device=x.device)
     if x_out is None:
         x_out = torch.empty(shape, dtype=torch.int8, device=x.device)

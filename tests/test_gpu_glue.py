@@ -133,6 +133,13 @@ def test_fused_requantisation_equals_layer_then_requantize(psb, orc, shared):
                                              acc=accg, shared=shared, **kw_g)
                     assert np.array_equal(accg.cpu().numpy(), acc), (L.w.shape, m)
                     assert np.array_equal(got.cpu().numpy(), ref), (L.w.shape, m, list(kw_o))
+                    # without an accumulator output: same activations
+                    got2 = psb.conv2d_requant(qg, x, inv, S=None if bt is not None else L.S,
+                                              budget_to=None if bt is None else torch.from_numpy(bt).cuda(),
+                                              stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id,
+                                              mult=torch.from_numpy(mult).cuda(), bias=torch.from_numpy(bias).cuda(),
+                                              shared=shared, want_acc=False, **kw_g)
+                    assert np.array_equal(got2.cpu().numpy(), ref), (L.w.shape, m, "no acc")
     psb.set_mapping(psb.MAPPING_AUTO)
     q = psb.Weights(torch.ones((4, 4, 1, 1), device="cuda"))
     xx = torch.zeros((1, 4, 2, 2), dtype=torch.int8, device="cuda")
