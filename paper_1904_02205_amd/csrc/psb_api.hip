@@ -230,7 +230,7 @@ psb::FilterJob filter_job(const psb_weights* q, int from, int to, uint64_t seed,
     j.CB = CB; j.n_ksteps = n_ksteps; j.prob_bits = q->prob_bits; j.from = from; j.to = to;
     j.key0 = (uint32_t)(seed & 0xFFFFFFFFull); j.key1 = (uint32_t)(seed >> 32); j.layer_id = layer_id;
     j.w32 = w32; j.planes = planes;
-    j.pack_KW = 0; j.pack_C = 0;
+    j.pack_KW = 0; j.pack_C = 0; j.n_planes = psb::kMaxPlanes;
     return j;
 }
 
@@ -268,13 +268,12 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
 
     shared_workspace* ws = q->ws;
     const int64_t nw = (int64_t)q->shape.oc * q->K;
-    if (!ws->w32_dev && hipMalloc(&ws->w32_dev, (size_t)nw * sizeof(int32_t)) != hipSuccess) return PSB_ERR_ALLOC;
+    if (!mfma && !ws->w32_dev && hipMalloc(&ws->w32_dev, (size_t)nw * sizeof(int32_t)) != hipSuccess)
+        return PSB_ERR_ALLOC;
     if (!ws->present_dev && hipMalloc(&ws->present_dev, 256 * sizeof(uint32_t)) != hipSuccess) return PSB_ERR_ALLOC;
     if (mfma && !ws->planes_dev) {
         const size_t bytes = (size_t)n_ocb * n_ksteps * psb::kMaxPlanes * psb::kPlaneStride;
-        if (hipMalloc(&ws->planes_dev, bytes) != hipSuccess) return PSB_ERR_ALLOC;
-        // positions of padding channels are never written again and must read as zero
-        PSB_HIP_TRY(hipMemsetAsync(ws->planes_dev, 0, bytes, stream));
+        if (hipMalloc(&ws->planes_dev, bytes) != hipSuccess) return PSB_ERR_ALLOC;   // written whole by every call
     }
     // channels-last copy (row-packed: one 32-byte block per input row and output column); the last C_pad bytes of
     // the buffer are a page of zeros that padding taps read
@@ -308,6 +307,8 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     p.tH = g->h; p.tW = g->w; p.tKH = q->shape.kh; p.tKW = q->shape.kw;
     p.t_stride_h = g->stride_h; p.t_stride_w = g->stride_w; p.t_pad_h = g->pad_h; p.t_pad_w = g->pad_w;
     if (rowpack) { p.tW = OW; p.tKW = 1; p.t_stride_w = 1; p.t_pad_w = 0; }
+    p.quad_store = rq && rq->x_out && ((int64_t)OH * OW) % 4 == 0 && ((uintptr_t)rq->x_out & 3u) == 0 &&
+                   ((uintptr_t)rq->res_i8 & 3u) == 0;
     p.ksplit = 1;
     if (mfma) {
         // Few pixel tiles and a long reduction: cut the reduction so that every SIMD has a wave.  Only then: the
@@ -336,10 +337,12 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         }
     }
     auto prepare = [&](int from, int to) -> int {
-        const int64_t filter_blocks = (nw + 255) / 256;
+        // matrix cores: one thread per slot of the operand-ordered planes; otherwise one per weight
+        const int64_t filter_blocks = mfma ? (int64_t)n_ocb * n_ksteps * 4 : (nw + 255) / 256;
         if (filter_blocks + transpose_blocks > 2147483647ll) return PSB_ERR_TOO_LARGE;
-        psb::FilterJob fj = filter_job(q, from, to, seed, layer_id, ws->w32_dev, mfma ? ws->planes_dev : nullptr, CB,
-                                       n_ksteps);
+        psb::FilterJob fj = filter_job(q, from, to, seed, layer_id, mfma ? nullptr : ws->w32_dev,
+                                       mfma ? ws->planes_dev : nullptr, CB, n_ksteps);
+        fj.n_planes = psb::planes_needed(max_shift, to - from);
         if (rowpack) { fj.pack_KW = q->shape.kw; fj.pack_C = q->shape.cin; }
         hipLaunchKernelGGL(psb::k_shared_prologue, dim3((unsigned)(filter_blocks + transpose_blocks)), dim3(256), 0,
                            stream, fj, tj, (unsigned)filter_blocks);

@@ -61,53 +61,91 @@ struct SharedParams {
     int seg_from, seg_to;      //    range contains [seg_from, seg_to); acc accumulated
     float default_mult;
     Requant rq;
+    int quad_store;            // fused requantisation writes four pixels of one channel as one word (the launcher
+                               // sets it when OH * OW and the byte tensors' addresses are multiples of 4)
 };
 
-// One thread per weight: count, filter value, digit planes.
+// Filter sampling: count and filter value of one weight; digit planes for the matrix cores.
 struct FilterJob {
     const uint32_t* packed;   // [OC][K]
     int OC, K, KHW, CB, n_ksteps, prob_bits, from, to;
     int pack_KW, pack_C;      // row packing: kernel width and channel count (0: not packed)
+    int n_planes;             // digit planes the contraction of this sample range reads
     uint32_t key0, key1, layer_id;
-    int32_t* w32;             // [OC][K]
+    int32_t* w32;             // [OC][K], or null when only the planes are wanted
     int8_t* planes;           // operand-ordered digit planes, or null
 };
 
+// W[oc][k] for the job's sample range
+__device__ __forceinline__ int32_t sample_weight(const FilterJob& j, int oc, int k)
+{
+    const uint32_t word = j.packed[(int64_t)oc * j.K + k];
+    if ((word & 0x7F800000u) == kDeadWord) return 0;
+    const uint32_t thr = threshold_of(word & 0x7FFFFFu, j.prob_bits);
+    const uint32_t cnt = j.prob_bits < 23
+        ? count_below7((uint32_t)oc, (uint32_t)k, j.layer_id, j.key0, j.key1, thr, j.from, j.to)
+        : count_below((uint32_t)oc, (uint32_t)k, j.layer_id, j.key0, j.key1, thr, j.from, j.to);
+    const uint32_t mag = ((uint32_t)(j.to - j.from) + cnt) << ((word >> 23) & 0xFFu);   // < 2^31 by the overflow rule
+    return (word & 0x80000000u) ? -(int32_t)mag : (int32_t)mag;
+}
+
+// One thread per weight: the int32 filter.
 __device__ __forceinline__ void sample_filter_thread(const FilterJob& j, int64_t i)
 {
     if (i >= (int64_t)j.OC * j.K) return;
     const int oc = (int)(i / j.K);
-    const int k = (int)(i - (int64_t)oc * j.K);
-    const uint32_t word = j.packed[i];
-    int32_t wv = 0;
-    if ((word & 0x7F800000u) != kDeadWord) {
-        const uint32_t thr = threshold_of(word & 0x7FFFFFu, j.prob_bits);
-        const uint32_t cnt = j.prob_bits < 23
-            ? count_below7((uint32_t)oc, (uint32_t)k, j.layer_id, j.key0, j.key1, thr, j.from, j.to)
-            : count_below((uint32_t)oc, (uint32_t)k, j.layer_id, j.key0, j.key1, thr, j.from, j.to);
-        const uint32_t mag = ((uint32_t)(j.to - j.from) + cnt) << ((word >> 23) & 0xFFu);   // < 2^31 by the overflow rule
-        wv = (word & 0x80000000u) ? -(int32_t)mag : (int32_t)mag;
+    j.w32[i] = sample_weight(j, oc, (int)(i - (int64_t)oc * j.K));
+}
+
+// 4 x 4 byte transpose across the four lanes of a quad: afterwards byte i of lane j is what byte j of
+// lane i was.  Every lane of the quad must be active.
+__device__ __forceinline__ uint32_t quad_transpose_bytes(uint32_t d)
+{
+    const uint32_t d0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)d, 0x00, 0xF, 0xF, true);   // quad_perm [0,0,0,0]
+    const uint32_t d1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)d, 0x55, 0xF, 0xF, true);   // [1,1,1,1]
+    const uint32_t d2 = (uint32_t)__builtin_amdgcn_mov_dpp((int)d, 0xAA, 0xF, 0xF, true);   // [2,2,2,2]
+    const uint32_t d3 = (uint32_t)__builtin_amdgcn_mov_dpp((int)d, 0xFF, 0xF, 0xF, true);   // [3,3,3,3]
+    const int s = 8 * (int)(threadIdx.x & 3u);
+    return ((d0 >> s) & 0xFFu) | (((d1 >> s) & 0xFFu) << 8) | (((d2 >> s) & 0xFFu) << 16) | ((d3 >> s) << 24);
+}
+
+// Digit planes in operand order: one thread per (channel, slot) of every 32-channel x 32-slot operand block,
+// padding included (those get zeros, so the buffer needs no clearing).  Thread t: bits 0-3 and 9 = slot,
+// bits 4-8 = channel inside its block of 32, the rest = (channel block, reduction step).  The four lanes
+// of a quad hold four consecutive slots; after the byte transpose lane b of the quad stores plane b's four
+// digits as one 32-bit word.
+__device__ __forceinline__ void sample_planes_thread(const FilterJob& j, int64_t t)
+{
+    const int cl = (int)(t & 15) + 16 * (int)((t >> 9) & 1);
+    const int ocl = (int)(t >> 4) & 31;
+    const int64_t blk = t >> 10;                       // channel block * n_ksteps + reduction step
+    const int kstep = (int)(blk % j.n_ksteps);
+    const int oc = (int)(blk / j.n_ksteps) * 32 + ocl;
+    int c, r;
+    bool valid = oc < j.OC;
+    if (j.pack_KW) {                                   // one step per kernel row; slot kw * C + c inside it
+        const int kw = cl / j.pack_C;
+        c = cl - kw * j.pack_C;
+        r = kstep * j.pack_KW + kw;
+        valid = valid && kw < j.pack_KW;
+    } else {
+        r = kstep / j.CB;
+        c = (kstep - r * j.CB) * 32 + cl;
+        valid = valid && c < j.K / j.KHW;
     }
-    j.w32[i] = wv;
-    if (j.planes) {
-        const int c = k / j.KHW;
-        const int r = k - c * j.KHW;
-        int kstep = r * j.CB + (c >> 5);
-        int cl = c & 31;
-        if (j.pack_KW) {           // one step per kernel row; slot kw * C + c inside it
-            kstep = r / j.pack_KW;
-            cl = (r - kstep * j.pack_KW) * j.pack_C + c;
-        }
-        const int lane = (oc & 31) + 32 * (cl >> 4);
-        int8_t* dst = j.planes + ((((int64_t)(oc >> 5) * j.n_ksteps + kstep) * kMaxPlanes) * 64 + lane) * 16 + (cl & 15);
-        int64_t v = wv;
+    int64_t v = 0;
+    if (valid) v = sample_weight(j, oc, c * j.KHW + r);
+    uint32_t digits = 0;
 #pragma unroll
-        for (int b = 0; b < kMaxPlanes; ++b) {
-            const int8_t d = (int8_t)(v & 0xFF);     // balanced digit; the last one wraps, which is exact modulo 2^32
-            dst[b * kPlaneStride] = d;
-            v = (v - d) >> 8;
-        }
+    for (int b = 0; b < kMaxPlanes; ++b) {
+        const int8_t d = (int8_t)(v & 0xFF);           // balanced digit; the last one wraps, which is exact modulo 2^32
+        digits |= (uint32_t)(uint8_t)d << (8 * b);
+        v = (v - d) >> 8;
     }
+    const uint32_t word = quad_transpose_bytes(digits);
+    const int plane = (int)(t & 3);
+    if (plane < j.n_planes)
+        *reinterpret_cast<uint32_t*>(j.planes + ((blk * kMaxPlanes + plane) * 64 + ocl + 32 * (cl >> 4)) * 16 + (cl & 12)) = word;
 }
 
 // x [N][C][H][W] -> xt [N][H][W][C_pad] (zeros in the padding channels).  One workgroup per
@@ -185,9 +223,10 @@ __global__ void __launch_bounds__(256) k_sample_filter(const FilterJob j)
 __global__ void __launch_bounds__(256) k_shared_prologue(const FilterJob f, const TransposeJob t, unsigned filter_blocks)
 {
     __shared__ int8_t tile[32][64 + 4];
-    if (blockIdx.x < filter_blocks)          // uniform over the workgroup
-        sample_filter_thread(f, (int64_t)blockIdx.x * 256 + threadIdx.x);
-    else if (t.pack_KW)
+    if (blockIdx.x < filter_blocks) {        // uniform over the workgroup
+        if (f.planes) sample_planes_thread(f, (int64_t)blockIdx.x * 256 + threadIdx.x);
+        else sample_filter_thread(f, (int64_t)blockIdx.x * 256 + threadIdx.x);
+    } else if (t.pack_KW)
         row_pack_block(t, (int64_t)(blockIdx.x - filter_blocks));
     else
         channels_last_tile(t, (int64_t)(blockIdx.x - filter_blocks), tile);
@@ -359,11 +398,56 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     if (!active) return;
 
     // result row (channel) of register q: 8*(q/4) + 4*(lane/32) + q%4; column (pixel) = lane%32
+    const int64_t plane = (int64_t)p.OH * p.OW;
+    const bool partial = p.masked || p.ksplit > 1;
+    if (!partial && p.rq.x_out && p.quad_store) {
+        // A lane holds four consecutive channels of one pixel per group of registers; the byte tensors want
+        // consecutive pixels of one channel.  The four lanes of a quad (four consecutive pixels of one image,
+        // as OH * OW is a multiple of 4) swap bytes, and each lane moves one 32-bit word per group.
+        const int j = lane & 3;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (!live[h]) continue;                    // uniform over a quad
+            const int64_t img = (int64_t)n_[h] * p.OC * plane;
+            const int pin = oy_[h] * p.OW + ox_[h];
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const int oc0 = ocb * 32 + 8 * qq + 4 * g;
+                const int64_t oj = img + (int64_t)(oc0 + j) * plane + (pin & ~3);    // this lane's word
+                uint32_t resw = 0;
+                if (p.rq.res_i8) {
+                    if (oc0 + j < p.OC) resw = *reinterpret_cast<const uint32_t*>(p.rq.res_i8 + oj);
+                    resw = quad_transpose_bytes(resw);  // byte i: channel oc0 + i at this lane's pixel
+                }
+                uint32_t outw = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int oc = oc0 + i;
+                    if (oc >= p.OC) continue;
+                    uint32_t v = 0;
+#pragma unroll
+                    for (int b = 0; b < P; ++b) v += (uint32_t)acc[h][b][4 * qq + i] << (8 * b);
+                    const int64_t o = img + (int64_t)oc * plane + pin;
+                    if (p.acc) p.acc[o] = (int32_t)v;
+                    const float r = rescale((int32_t)v, p.mult ? p.mult[oc] : p.default_mult, to_[h], p.bias, oc);
+                    if (p.y) p.y[o] = r;
+                    float res = 0.0f;
+                    if (p.rq.res_f32) res = p.rq.res_f32[o];
+                    if (p.rq.res_i8) res = __fmul_rn((float)(int8_t)(resw >> (8 * i)), p.rq.res_step);
+                    const int32_t xq = requantize_one(r, p.rq.res_f32 || p.rq.res_i8, res, p.rq.relu != 0,
+                                                      p.rq.inv_step, p.rq.lo, p.rq.hi);
+                    outw |= ((uint32_t)xq & 0xFFu) << (8 * i);
+                }
+                outw = quad_transpose_bytes(outw);      // byte i: channel oc0 + j at pixel (pin & ~3) + i
+                if (oc0 + j < p.OC) *reinterpret_cast<uint32_t*>(p.rq.x_out + oj) = outw;
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         if (!live[h]) continue;
         const int64_t o0 = (((int64_t)n_[h] * p.OC) * p.OH + oy_[h]) * p.OW + ox_[h];
-        const int64_t plane = (int64_t)p.OH * p.OW;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             const int oc = ocb * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
@@ -372,7 +456,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 #pragma unroll
             for (int b = 0; b < P; ++b) v += (uint32_t)acc[h][b][q] << (8 * b);
             const int64_t o = o0 + oc * plane;
-            if (p.masked || p.ksplit > 1) {
+            if (partial) {
                 atomicAdd(&p.acc[o], (int32_t)v);           // exact in any order: the arithmetic is modulo 2^32
             } else {
                 if (p.acc) p.acc[o] = (int32_t)v;
