@@ -27,6 +27,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "psb_kernels.hip.h"
 
 namespace psb {
@@ -39,7 +41,7 @@ constexpr int kMaxPlanes = 4;
 
 struct SharedParams {
     const int8_t* x;           // [N][C][H][W]                      (direct kernel)
-    const int8_t* xt;          // [N][H][W][C_pad], channels last, channels last (matrix-core kernel)
+    const int8_t* xt;          // [N][H][C_pad/32][W][32]: blocks of 32 channels, pixels of a row contiguous (matrix-core kernel)
     const int8_t* planes;      // [OC/32][n_ksteps][4][64][16]
     const int32_t* w32;        // [OC][K]
     const uint8_t* budget_to;  // [N][OH][OW] or null
@@ -51,7 +53,7 @@ struct SharedParams {
     int N, C, H, W, OC, OH, OW, KH, KW, Cg, OCg, K, C_pad, n_ksteps;
     int stride_h, stride_w, pad_h, pad_w;
     int S, s_max;
-    int64_t zero_page;         // offset in xt of C_pad zero bytes
+    int64_t zero_page;         // offset in xt of one row (tW * C_pad bytes) of zeros
     // Geometry of the convolution as the matrix-core kernel sees it on xt.  Normally the layer's own; for layers
     // with very few input channels (kw * C <= 32) xt holds, per output column, the kw x C values of one kernel row
     // ("row packing"), and the kernel sees a kh x 1 convolution with unit column stride on an image OW wide.
@@ -148,7 +150,7 @@ __device__ __forceinline__ void sample_planes_thread(const FilterJob& j, int64_t
         *reinterpret_cast<uint32_t*>(j.planes + ((blk * kMaxPlanes + plane) * 64 + ocl + 32 * (cl >> 4)) * 16 + (cl & 12)) = word;
 }
 
-// x [N][C][H][W] -> xt [N][H][W][C_pad] (zeros in the padding channels).  One workgroup per
+// x [N][C][H][W] -> xt [N][H][C_pad/32][W][32] (zeros in the padding channels).  One workgroup per
 // (64 columns, row, 32 channels) tile, transposed through LDS; tiles are numbered columns fastest,
 // then rows (n * H + iy), then channel blocks.
 struct TransposeJob {
@@ -208,7 +210,7 @@ __device__ __forceinline__ void channels_last_tile(const TransposeJob& j, int64_
             lo |= (uint32_t)(uint8_t)tile[part * 8 + q][dx] << (8 * q);
             hi |= (uint32_t)(uint8_t)tile[part * 8 + 4 + q][dx] << (8 * q);
         }
-        uint2* dst = reinterpret_cast<uint2*>(j.xt + ((row * j.W + ix0 + dx) * (int64_t)j.C_pad + c0 + part * 8));
+        uint2* dst = reinterpret_cast<uint2*>(j.xt + (((row * (j.C_pad >> 5) + (c0 >> 5)) * j.W + ix0 + dx) * 32 + part * 8));
         *dst = make_uint2(lo, hi);
     }
 }
@@ -266,10 +268,16 @@ __device__ __forceinline__ bool shared_pixel_range(const SharedParams& p, int64_
 constexpr int kDepth = 4;
 constexpr int kStageSteps = 8;      // a multiple of kDepth
 
-template <int P>
+// What a workgroup does with its sums: add them to the accumulators atomically (masked or split reductions; the
+// rescaling is a separate pass then), store accumulators (and rescaled values), or store requantised activations
+// (and, if asked for, the other two).  A template parameter, so that the unrolled epilogue is straight-line code.
+enum { kOutPartial = 0, kOutAcc = 1, kOutRequant = 2 };
+
+template <int P, int OUT>
 __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 {
     __shared__ v4i a_lds[kStageSteps * P * 64];
+    __shared__ float s_mult[32], s_bias[32];       // rescale factors of this block of channels (read after the loop)
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -283,41 +291,12 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     const int64_t pix0 = ((int64_t)wg * 4 + wave) * 64;
     const int ocb = blockIdx.y;
 
-    bool live[2];
-    int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
-    int64_t origin[2];                              // offset of xt[n][iy0][ix0][16 g]; only used with an in-image tap added
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int64_t pix = pix0 + 32 * h + col;
-        const bool valid = pix < npix;
-        const uint32_t pc = (uint32_t)(valid ? pix : npix - 1);       // the pixel count fits 32 bits (checked by the host)
-        const uint32_t row = pc / (uint32_t)p.OW;
-        ox_[h] = (int)(pc - row * (uint32_t)p.OW);
-        n_[h] = (int)(row / (uint32_t)p.OH);
-        oy_[h] = (int)(row - (uint32_t)n_[h] * (uint32_t)p.OH);
-        live[h] = shared_pixel_range(p, pc, to_[h]) && valid;
-        iy0[h] = oy_[h] * p.t_stride_h - p.t_pad_h;
-        ix0[h] = ox_[h] * p.t_stride_w - p.t_pad_w;
-        origin[h] = (((int64_t)n_[h] * p.tH + iy0[h]) * p.tW + ix0[h]) * p.C_pad + 16 * g;
-    }
-    // a wave without any pixel that takes part still helps to stage the weights (and keeps the barriers whole)
-    const bool active = __ballot(live[0] || live[1]) != 0ull;
-
-    v16i acc[2][P];
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int b = 0; b < P; ++b)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
-
     const int CB = p.C_pad >> 5;
     const int n_steps = p.tKH * p.tKW * CB;
     // this workgroup's part of the reduction
     const int per_split = (n_steps + p.ksplit - 1) / p.ksplit;
     const int s_begin = (int)blockIdx.z * per_split;
     const int s_end = min(n_steps, s_begin + per_split);
-    const int64_t zero_page = p.zero_page + 16 * g;
     const v4i* wblock = reinterpret_cast<const v4i*>(p.planes) + ((int64_t)ocb * p.n_ksteps * kMaxPlanes) * 64;
 
     // weights: operand i of a chunk (i = (step * P + plane) * 64 + lane) is fetched by thread i mod 256
@@ -334,6 +313,38 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
         }
     };
 
+    fetch_weights(s_begin);          // first of all: nothing below depends on it until the first barrier
+
+    bool live[2];
+    int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
+    int64_t origin[2];                              // offset of xt[n][iy0][ix0][16 g]; only used with an in-image tap added
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int64_t pix = pix0 + 32 * h + col;
+        const bool valid = pix < npix;
+        const uint32_t pc = (uint32_t)(valid ? pix : npix - 1);       // the pixel count fits 32 bits (checked by the host)
+        const uint32_t row = pc / (uint32_t)p.OW;
+        ox_[h] = (int)(pc - row * (uint32_t)p.OW);
+        n_[h] = (int)(row / (uint32_t)p.OH);
+        oy_[h] = (int)(row - (uint32_t)n_[h] * (uint32_t)p.OH);
+        live[h] = shared_pixel_range(p, pc, to_[h]) && valid;
+        iy0[h] = oy_[h] * p.t_stride_h - p.t_pad_h;
+        ix0[h] = ox_[h] * p.t_stride_w - p.t_pad_w;
+        origin[h] = ((((int64_t)n_[h] * p.tH + iy0[h]) * (p.C_pad >> 5)) * p.tW + ix0[h]) * 32 + 16 * g;
+    }
+    // a wave without any pixel that takes part still helps to stage the weights (and keeps the barriers whole)
+    const bool active = __ballot(live[0] || live[1]) != 0ull;
+
+    v16i acc[2][P];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int b = 0; b < P; ++b)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
+
+    const int64_t zero_page = p.zero_page + 16 * g;
+    const int cb_stride = p.tW * 32;                 // bytes between the channel blocks of one pixel
     // activations: load cursor = the reduction step whose operands are requested next
     int l_step = min(s_begin, n_steps - 1);
     int l_cb = l_step % CB, l_kw = (l_step / CB) % p.tKW, l_kh = (l_step / CB) / p.tKW;
@@ -343,14 +354,14 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
         for (int h = 0; h < 2; ++h) {
             const int iy = iy0[h] + l_kh, ix = ix0[h] + l_kw;
             const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
-            tap_off[h] = ok ? origin[h] + ((int64_t)l_kh * p.tW + l_kw) * p.C_pad : zero_page;
+            tap_off[h] = ok ? origin[h] + ((int64_t)l_kh * CB * p.tW + l_kw) * 32 : zero_page;
         }
     };
     place_tap();
     v4i opb[kDepth][2];
     auto request = [&](int slot) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) opb[slot][h] = *reinterpret_cast<const v4i*>(p.xt + tap_off[h] + l_cb * 32);
+        for (int h = 0; h < 2; ++h) opb[slot][h] = *reinterpret_cast<const v4i*>(p.xt + tap_off[h] + (int64_t)l_cb * cb_stride);
         if (l_step + 1 < n_steps) {                  // past the end the last step is simply requested again
             ++l_step;
             if (++l_cb == CB) {
@@ -361,10 +372,14 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
         }
     };
 
-    fetch_weights(s_begin);
     if (active) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) request(d);
+    }
+    if (OUT != kOutPartial && threadIdx.x < 32) {    // visible to every wave after the loop's first barrier
+        const int oc = ocb * 32 + (int)threadIdx.x;
+        s_mult[threadIdx.x] = (p.mult && oc < p.OC) ? p.mult[oc] : p.default_mult;
+        s_bias[threadIdx.x] = (p.bias && oc < p.OC) ? p.bias[oc] : 0.0f;
     }
     for (int s0 = s_begin; s0 < s_end; s0 += kStageSteps) {
         __syncthreads();                             // the previous chunk has been consumed by every wave
@@ -391,7 +406,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
                         acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][1], acc[1][b], 0, 0, 0);
                     }
                 }
-                request(d);
+                if (s0 + ks + kDepth < s_end) request(d);   // wave-uniform; nothing is in flight when the loop ends
             }
         }
     }
@@ -399,71 +414,126 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 
     // result row (channel) of register q: 8*(q/4) + 4*(lane/32) + q%4; column (pixel) = lane%32
     const int64_t plane = (int64_t)p.OH * p.OW;
-    const bool partial = p.masked || p.ksplit > 1;
-    if (!partial && p.rq.x_out && p.quad_store) {
-        // A lane holds four consecutive channels of one pixel per group of registers; the byte tensors want
-        // consecutive pixels of one channel.  The four lanes of a quad (four consecutive pixels of one image,
-        // as OH * OW is a multiple of 4) swap bytes, and each lane moves one 32-bit word per group.
-        const int j = lane & 3;
+    auto sum_of = [&](int h, int q) {                  // the digit planes recombined
+        uint32_t u = 0;
+#pragma unroll
+        for (int b = 0; b < P; ++b) u += (uint32_t)acc[h][b][q] << (8 * b);
+        return u;
+    };
+    // Per half tile, `full` (the block has 32 real channels) is a compile-time constant in the code below.
+    auto finish = [&](auto full_c) {
+        constexpr bool FULL = decltype(full_c)::value;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            if (!live[h]) continue;                    // uniform over a quad
-            const int64_t img = (int64_t)n_[h] * p.OC * plane;
-            const int pin = oy_[h] * p.OW + ox_[h];
+            if (!live[h]) continue;                    // uniform over a quad of lanes where that matters
+            const int oc_first = ocb * 32 + 4 * g;     // channel of register 0; register q: + 8 (q / 4) + q % 4
+            const int64_t o_first = ((int64_t)n_[h] * p.OC + oc_first) * plane + oy_[h] * p.OW + ox_[h];
+            if constexpr (OUT == kOutPartial) {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int dq = 8 * (q >> 2) + (q & 3);
+                    if (FULL || oc_first + dq < p.OC)   // exact in any order: the arithmetic is modulo 2^32
+                        atomicAdd(&p.acc[o_first + dq * plane], (int32_t)sum_of(h, q));
+                }
+                continue;
+            }
+            const float inv_s = (to_[h] > 0) ? __fdiv_rn(1.0f, (float)to_[h]) : 0.0f;
+            const bool has_bias = p.bias != nullptr;
+            auto rescaled = [&](int q, uint32_t u) {    // the arithmetic of rescale()
+                const int ocl = 8 * (q >> 2) + 4 * g + (q & 3);
+                float r = __fmul_rn(__fmul_rn(__int2float_rn((int32_t)u), s_mult[ocl]), inv_s);
+                if (has_bias) r = __fadd_rn(r, s_bias[ocl]);
+                return r;
+            };
+            if constexpr (OUT == kOutAcc) {
+                const bool with_y = p.y != nullptr;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int dq = 8 * (q >> 2) + (q & 3);
+                    if (!FULL && oc_first + dq >= p.OC) continue;
+                    const uint32_t u = sum_of(h, q);
+                    p.acc[o_first + dq * plane] = (int32_t)u;
+                    if (with_y) p.y[o_first + dq * plane] = rescaled(q, u);
+                }
+                continue;
+            }
+            // Requantised activations.  Every global operand (the residual) is loaded before the first store: a
+            // store may alias a later load as far as the compiler can tell, and interleaving them would put the
+            // latency of each load in series.
+            const bool quad = p.quad_store != 0;
+            const int j = lane & 3;
+            // with quad: lane j of a quad moves the word of channel (first of the group of four) + j, pixels
+            // (pin & ~3) .. + 3, and the four lanes - consecutive pixels of one image - swap bytes
+            const int64_t w_first = o_first + j * plane - ((oy_[h] * p.OW + ox_[h]) & 3);
+            float res[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) res[q] = 0.0f;
+            const bool has_res = p.rq.res_f32 || p.rq.res_i8;
+            if (p.rq.res_f32) {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int dq = 8 * (q >> 2) + (q & 3);
+                    if (FULL || oc_first + dq < p.OC) res[q] = p.rq.res_f32[o_first + dq * plane];
+                }
+            } else if (p.rq.res_i8 && quad) {
+                uint32_t resw[4];
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    resw[qq] = 0;
+                    if (FULL || oc_first + 8 * qq + j < p.OC)
+                        resw[qq] = *reinterpret_cast<const uint32_t*>(p.rq.res_i8 + w_first + 8 * qq * plane);
+                }
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const uint32_t w = quad_transpose_bytes(resw[qq]);    // byte i: channel + i at this lane's pixel
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) res[4 * qq + i] = __fmul_rn((float)(int8_t)(w >> (8 * i)), p.rq.res_step);
+                }
+            } else if (p.rq.res_i8) {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int dq = 8 * (q >> 2) + (q & 3);
+                    if (FULL || oc_first + dq < p.OC)
+                        res[q] = __fmul_rn((float)p.rq.res_i8[o_first + dq * plane], p.rq.res_step);
+                }
+            }
+            const bool relu = p.rq.relu != 0;
+            if (p.acc || p.y) {                        // rarely: the other outputs as well, in a pass of their own
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int dq = 8 * (q >> 2) + (q & 3);
+                    if (!FULL && oc_first + dq >= p.OC) continue;
+                    const uint32_t u = sum_of(h, q);
+                    if (p.acc) p.acc[o_first + dq * plane] = (int32_t)u;
+                    if (p.y) p.y[o_first + dq * plane] = rescaled(q, u);
+                }
+            }
 #pragma unroll
             for (int qq = 0; qq < 4; ++qq) {
-                const int oc0 = ocb * 32 + 8 * qq + 4 * g;
-                const int64_t oj = img + (int64_t)(oc0 + j) * plane + (pin & ~3);    // this lane's word
-                uint32_t resw = 0;
-                if (p.rq.res_i8) {
-                    if (oc0 + j < p.OC) resw = *reinterpret_cast<const uint32_t*>(p.rq.res_i8 + oj);
-                    resw = quad_transpose_bytes(resw);  // byte i: channel oc0 + i at this lane's pixel
-                }
-                uint32_t outw = 0;
+                uint32_t word = 0;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int oc = oc0 + i;
-                    if (oc >= p.OC) continue;
-                    uint32_t v = 0;
-#pragma unroll
-                    for (int b = 0; b < P; ++b) v += (uint32_t)acc[h][b][4 * qq + i] << (8 * b);
-                    const int64_t o = img + (int64_t)oc * plane + pin;
-                    if (p.acc) p.acc[o] = (int32_t)v;
-                    const float r = rescale((int32_t)v, p.mult ? p.mult[oc] : p.default_mult, to_[h], p.bias, oc);
-                    if (p.y) p.y[o] = r;
-                    float res = 0.0f;
-                    if (p.rq.res_f32) res = p.rq.res_f32[o];
-                    if (p.rq.res_i8) res = __fmul_rn((float)(int8_t)(resw >> (8 * i)), p.rq.res_step);
-                    const int32_t xq = requantize_one(r, p.rq.res_f32 || p.rq.res_i8, res, p.rq.relu != 0,
-                                                      p.rq.inv_step, p.rq.lo, p.rq.hi);
-                    outw |= ((uint32_t)xq & 0xFFu) << (8 * i);
+                    const int q = 4 * qq + i;
+                    const uint32_t u = sum_of(h, q);
+                    const float r = rescaled(q, u);
+                    const uint32_t xq = (uint32_t)requantize_one(r, has_res, res[q], relu, p.rq.inv_step, p.rq.lo, p.rq.hi) & 0xFFu;
+                    word |= xq << (8 * i);
                 }
-                outw = quad_transpose_bytes(outw);      // byte i: channel oc0 + j at pixel (pin & ~3) + i
-                if (oc0 + j < p.OC) *reinterpret_cast<uint32_t*>(p.rq.x_out + oj) = outw;
+                if (quad) {
+                    word = quad_transpose_bytes(word); // byte i: this lane's channel at pixel (pin & ~3) + i
+                    if (FULL || oc_first + 8 * qq + j < p.OC)
+                        *reinterpret_cast<uint32_t*>(p.rq.x_out + w_first + 8 * qq * plane) = word;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (FULL || oc_first + 8 * qq + i < p.OC)
+                            p.rq.x_out[o_first + (8 * qq + i) * plane] = (int8_t)(word >> (8 * i));
+                }
             }
         }
-        return;
-    }
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        if (!live[h]) continue;
-        const int64_t o0 = (((int64_t)n_[h] * p.OC) * p.OH + oy_[h]) * p.OW + ox_[h];
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int oc = ocb * 32 + 8 * (q >> 2) + 4 * g + (q & 3);
-            if (oc >= p.OC) continue;
-            uint32_t v = 0;
-#pragma unroll
-            for (int b = 0; b < P; ++b) v += (uint32_t)acc[h][b][q] << (8 * b);
-            const int64_t o = o0 + oc * plane;
-            if (partial) {
-                atomicAdd(&p.acc[o], (int32_t)v);           // exact in any order: the arithmetic is modulo 2^32
-            } else {
-                if (p.acc) p.acc[o] = (int32_t)v;
-                emit(p, o, oc, (int32_t)v, to_[h]);
-            }
-        }
-    }
+    };
+    if (ocb * 32 + 32 <= p.OC) finish(std::true_type{});
+    else finish(std::false_type{});
 }
 
 // Any layer shape: one output pixel per lane, one output channel per workgroup row.
@@ -512,17 +582,26 @@ inline int planes_needed(int max_shift, int n_samples)
     return planes > kMaxPlanes ? kMaxPlanes : planes;
 }
 
+template <int OUT>
+inline void launch_conv_shared_mfma_out(const SharedParams& p, int planes, dim3 grid, hipStream_t stream)
+{
+    const dim3 block(256);
+    switch (planes) {
+        case 1: hipLaunchKernelGGL((k_conv_shared_mfma<1, OUT>), grid, block, 0, stream, p); break;
+        case 2: hipLaunchKernelGGL((k_conv_shared_mfma<2, OUT>), grid, block, 0, stream, p); break;
+        case 3: hipLaunchKernelGGL((k_conv_shared_mfma<3, OUT>), grid, block, 0, stream, p); break;
+        default: hipLaunchKernelGGL((k_conv_shared_mfma<4, OUT>), grid, block, 0, stream, p); break;
+    }
+}
+
 inline void launch_conv_shared_mfma(const SharedParams& p, int planes, hipStream_t stream)
 {
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
     const int64_t tiles = (npix + 255) / 256;
-    const dim3 grid((unsigned)((tiles + 7) / 8 * 8), (unsigned)((p.OC + 31) / 32), (unsigned)p.ksplit), block(256);   // 8 XCDs
-    switch (planes) {
-        case 1: hipLaunchKernelGGL(k_conv_shared_mfma<1>, grid, block, 0, stream, p); break;
-        case 2: hipLaunchKernelGGL(k_conv_shared_mfma<2>, grid, block, 0, stream, p); break;
-        case 3: hipLaunchKernelGGL(k_conv_shared_mfma<3>, grid, block, 0, stream, p); break;
-        default: hipLaunchKernelGGL(k_conv_shared_mfma<4>, grid, block, 0, stream, p); break;
-    }
+    const dim3 grid((unsigned)((tiles + 7) / 8 * 8), (unsigned)((p.OC + 31) / 32), (unsigned)p.ksplit);   // 8 XCDs
+    if (p.masked || p.ksplit > 1) launch_conv_shared_mfma_out<kOutPartial>(p, planes, grid, stream);
+    else if (p.rq.x_out) launch_conv_shared_mfma_out<kOutRequant>(p, planes, grid, stream);
+    else launch_conv_shared_mfma_out<kOutAcc>(p, planes, grid, stream);
 }
 
 }  // namespace psb
