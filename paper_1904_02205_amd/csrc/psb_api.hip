@@ -273,13 +273,15 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         return PSB_ERR_ALLOC;
     if (!ws->present_dev && hipMalloc(&ws->present_dev, 256 * sizeof(uint32_t)) != hipSuccess) return PSB_ERR_ALLOC;
     if (mfma && !ws->planes_dev) {
-        const size_t bytes = (size_t)n_ocb * n_ksteps * psb::kMaxPlanes * psb::kPlaneStride;
+        // one chunk of padding: the kernel stages whole chunks of reduction steps
+        const size_t bytes = (size_t)(n_ocb * n_ksteps + psb::kStageSteps) * psb::kMaxPlanes * psb::kPlaneStride;
         if (hipMalloc(&ws->planes_dev, bytes) != hipSuccess) return PSB_ERR_ALLOC;   // written whole by every call
     }
     // blocked channels-last copy (row-packed: one 32-byte block per input row and output column); the buffer ends
     // in one row of zeros that padding taps read
     const size_t xt_row = (size_t)(rowpack ? OW : g->w) * C_pad;
     const size_t xt_need = (size_t)g->n * g->h * xt_row + xt_row;
+    if (mfma && xt_need >= (1ull << 32)) return PSB_ERR_TOO_LARGE;      // the kernel addresses it with 32-bit offsets
     if (mfma && (ws->xt_bytes < xt_need - xt_row + ws->xt_zero_bytes || ws->xt_zero_bytes < xt_row)) {
         if (ws->xt_dev) {
             PSB_HIP_TRY(hipStreamSynchronize(stream));     // an earlier call may still read the old buffer

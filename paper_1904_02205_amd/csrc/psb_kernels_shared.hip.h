@@ -297,27 +297,32 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     const int per_split = (n_steps + p.ksplit - 1) / p.ksplit;
     const int s_begin = (int)blockIdx.z * per_split;
     const int s_end = min(n_steps, s_begin + per_split);
-    const v4i* wblock = reinterpret_cast<const v4i*>(p.planes) + ((int64_t)ocb * p.n_ksteps * kMaxPlanes) * 64;
+    const int8_t* wblock = p.planes + (int64_t)ocb * p.n_ksteps * (kMaxPlanes * kPlaneStride);
 
-    // weights: operand i of a chunk (i = (step * P + plane) * 64 + lane) is fetched by thread i mod 256
+    // weights: operand i of a chunk (i = (step * P + plane) * 64 + lane) is fetched by thread i mod 256; its byte
+    // offset inside the chunk is fixed.  A chunk may reach past the last step: the buffer is padded by one chunk
+    // (those operands are staged but never multiplied).
     constexpr int kStageRegs = kStageSteps * P * 64 / 256;
     v4i stage[kStageRegs];
-    auto fetch_weights = [&](int s0) {
+    uint32_t woff[kStageRegs];
 #pragma unroll
-        for (int r = 0; r < kStageRegs; ++r) {
-            const int i = r * 256 + (int)threadIdx.x;
-            const int ks = i / (P * 64);
-            const int b = (i >> 6) % P;
-            const int step = min(s0 + ks, n_steps - 1);          // past the end: any valid address
-            stage[r] = wblock[((int64_t)step * kMaxPlanes + b) * 64 + (i & 63)];
-        }
+    for (int r = 0; r < kStageRegs; ++r) {
+        const int i = r * 256 + (int)threadIdx.x;
+        woff[r] = (uint32_t)((((i / (P * 64)) * kMaxPlanes + (i >> 6) % P) * 64 + (i & 63)) * 16);
+    }
+    auto fetch_weights = [&](int s0) {
+        const int8_t* chunk = wblock + (int64_t)s0 * (kMaxPlanes * kPlaneStride);      // uniform
+#pragma unroll
+        for (int r = 0; r < kStageRegs; ++r) stage[r] = *reinterpret_cast<const v4i*>(chunk + woff[r]);
     };
 
     fetch_weights(s_begin);          // first of all: nothing below depends on it until the first barrier
 
     bool live[2];
     int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
-    int64_t origin[2];                              // offset of xt[n][iy0][ix0][16 g]; only used with an in-image tap added
+    // Offsets into xt are 32 bits wide (the host keeps the buffer below 4 GB), so that an operand address is the
+    // uniform base pointer plus one vector register.
+    uint32_t origin[2];        // offset of xt[n][iy0][0][ix0][16 g] modulo 2^32; only used with an in-image tap added
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int64_t pix = pix0 + 32 * h + col;
@@ -330,7 +335,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
         live[h] = shared_pixel_range(p, pc, to_[h]) && valid;
         iy0[h] = oy_[h] * p.t_stride_h - p.t_pad_h;
         ix0[h] = ox_[h] * p.t_stride_w - p.t_pad_w;
-        origin[h] = ((((int64_t)n_[h] * p.tH + iy0[h]) * (p.C_pad >> 5)) * p.tW + ix0[h]) * 32 + 16 * g;
+        origin[h] = ((uint32_t)(n_[h] * p.tH + iy0[h]) * (uint32_t)(CB * p.tW) + (uint32_t)ix0[h]) * 32u + 16u * (uint32_t)g;
     }
     // a wave without any pixel that takes part still helps to stage the weights (and keeps the barriers whole)
     const bool active = __ballot(live[0] || live[1]) != 0ull;
@@ -343,30 +348,36 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
 
-    const int64_t zero_page = p.zero_page + 16 * g;
-    const int cb_stride = p.tW * 32;                 // bytes between the channel blocks of one pixel
-    // activations: load cursor = the reduction step whose operands are requested next
+    const uint32_t zero_off = (uint32_t)p.zero_page + 16u * (uint32_t)g;
+    const uint32_t cb_stride = (uint32_t)p.tW * 32u;            // bytes between the channel blocks of one pixel
+    const uint32_t row_stride = (uint32_t)CB * cb_stride;       // ... between the rows of one image
+    // activations: load cursor = the reduction step whose operands are requested next (all of it uniform)
     int l_step = min(s_begin, n_steps - 1);
     int l_cb = l_step % CB, l_kw = (l_step / CB) % p.tKW, l_kh = (l_step / CB) / p.tKW;
-    int64_t tap_off[2];
+    uint32_t l_tap = (uint32_t)l_kh * row_stride + (uint32_t)l_kw * 32u;   // offset of tap (l_kh, l_kw) from the origin
+    uint32_t l_cboff = (uint32_t)l_cb * cb_stride;
+    uint32_t tap_off[2];
     auto place_tap = [&]() {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int iy = iy0[h] + l_kh, ix = ix0[h] + l_kw;
             const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
-            tap_off[h] = ok ? origin[h] + ((int64_t)l_kh * CB * p.tW + l_kw) * 32 : zero_page;
+            tap_off[h] = ok ? origin[h] + l_tap : zero_off;
         }
     };
     place_tap();
     v4i opb[kDepth][2];
     auto request = [&](int slot) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) opb[slot][h] = *reinterpret_cast<const v4i*>(p.xt + tap_off[h] + (int64_t)l_cb * cb_stride);
+        for (int h = 0; h < 2; ++h) opb[slot][h] = *reinterpret_cast<const v4i*>(p.xt + (tap_off[h] + l_cboff));
         if (l_step + 1 < n_steps) {                  // past the end the last step is simply requested again
             ++l_step;
+            l_cboff += cb_stride;
             if (++l_cb == CB) {
                 l_cb = 0;
-                if (++l_kw == p.tKW) { l_kw = 0; ++l_kh; }
+                l_cboff = 0;
+                l_tap += 32u;
+                if (++l_kw == p.tKW) { l_kw = 0; ++l_kh; l_tap += row_stride - (uint32_t)p.tKW * 32u; }
                 place_tap();
             }
         }
@@ -406,7 +417,8 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
                         acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][1], acc[1][b], 0, 0, 0);
                     }
                 }
-                if (s0 + ks + kDepth < s_end) request(d);   // wave-uniform; nothing is in flight when the loop ends
+                request(d);     // unconditional (past the end: the last step again), so that the number of
+                                // loads in flight is the same on every path and no wait is longer than needed
             }
         }
     }
