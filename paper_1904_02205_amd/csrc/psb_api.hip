@@ -20,9 +20,8 @@
 struct shared_workspace {
     int32_t* w32_dev = nullptr;      // [OC][K] sampled integer filter
     int8_t* planes_dev = nullptr;    // digit planes in matrix-core operand order
-    int8_t* xt_dev = nullptr;        // blocked channels-last copy of the activations, then a run of zeros
+    int8_t* xt_dev = nullptr;        // blocked channels-last copy of the activations
     size_t xt_bytes = 0;
-    size_t xt_zero_bytes = 0;        // length of that run (the last bytes of the buffer)
     uint32_t* present_dev = nullptr; // 256 flags: budget values that occur
     int32_t* acc_dev = nullptr;      // accumulators of calls that do not hand any out but combine partial sums
     size_t acc_bytes = 0;
@@ -277,23 +276,18 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         const size_t bytes = (size_t)(n_ocb * n_ksteps + psb::kStageSteps) * psb::kMaxPlanes * psb::kPlaneStride;
         if (hipMalloc(&ws->planes_dev, bytes) != hipSuccess) return PSB_ERR_ALLOC;   // written whole by every call
     }
-    // blocked channels-last copy (row-packed: one 32-byte block per input row and output column); the buffer ends
-    // in one row of zeros that padding taps read
-    const size_t xt_row = (size_t)(rowpack ? OW : g->w) * C_pad;
-    const size_t xt_need = (size_t)g->n * g->h * xt_row + xt_row;
-    if (mfma && xt_need >= (1ull << 32)) return PSB_ERR_TOO_LARGE;      // the kernel addresses it with 32-bit offsets
-    if (mfma && (ws->xt_bytes < xt_need - xt_row + ws->xt_zero_bytes || ws->xt_zero_bytes < xt_row)) {
+    // blocked channels-last copy (row-packed: one 32-byte block per input row and output column)
+    const size_t xt_need = (size_t)g->n * g->h * (rowpack ? OW : g->w) * C_pad;
+    if (mfma && xt_need >= (1ull << 31)) return PSB_ERR_TOO_LARGE;      // the kernel addresses it with 32-bit offsets
+    if (mfma && ws->xt_bytes < xt_need) {
         if (ws->xt_dev) {
             PSB_HIP_TRY(hipStreamSynchronize(stream));     // an earlier call may still read the old buffer
             (void)hipFree(ws->xt_dev);
             ws->xt_dev = nullptr;
             ws->xt_bytes = 0;
-            ws->xt_zero_bytes = 0;
         }
         if (hipMalloc(&ws->xt_dev, xt_need) != hipSuccess) return PSB_ERR_ALLOC;
         ws->xt_bytes = xt_need;
-        ws->xt_zero_bytes = xt_row;
-        PSB_HIP_TRY(hipMemsetAsync(ws->xt_dev + (xt_need - xt_row), 0, xt_row, stream));
     }
 
     psb::SharedParams p;
@@ -309,7 +303,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     p.stride_h = g->stride_h; p.stride_w = g->stride_w; p.pad_h = g->pad_h; p.pad_w = g->pad_w;
     p.S = S; p.s_max = q->s_max;
     p.default_mult = std::ldexp(1.0f, q->info.e_min);
-    p.zero_page = mfma ? (int64_t)(ws->xt_bytes - ws->xt_zero_bytes) : 0;
+    p.xt_bytes = (uint32_t)xt_need;
     p.tH = g->h; p.tW = g->w; p.tKH = q->shape.kh; p.tKW = q->shape.kw;
     p.t_stride_h = g->stride_h; p.t_stride_w = g->stride_w; p.t_pad_h = g->pad_h; p.t_pad_w = g->pad_w;
     if (rowpack) { p.tW = OW; p.tKW = 1; p.t_stride_w = 1; p.t_pad_w = 0; }

@@ -53,7 +53,7 @@ struct SharedParams {
     int N, C, H, W, OC, OH, OW, KH, KW, Cg, OCg, K, C_pad, n_ksteps;
     int stride_h, stride_w, pad_h, pad_w;
     int S, s_max;
-    int64_t zero_page;         // offset in xt of one row (tW * C_pad bytes) of zeros
+    uint32_t xt_bytes;         // size of xt (below 2^31): operand loads are range-checked against it
     // Geometry of the convolution as the matrix-core kernel sees it on xt.  Normally the layer's own; for layers
     // with very few input channels (kw * C <= 32) xt holds, per output column, the kw x C values of one kernel row
     // ("row packing"), and the kernel sees a kh x 1 convolution with unit column stride on an image OW wide.
@@ -263,8 +263,25 @@ __device__ __forceinline__ bool shared_pixel_range(const SharedParams& p, int64_
 // chunk is already on its way into registers while the current one is consumed.  The activation operands
 // differ per wave and come straight from global memory (the few input rows a tile touches stay in L1/L2)
 // through a software pipeline: the operands of step s + kDepth are requested right after step s has been
-// consumed.  Every load is unconditional - taps that fall into the padding read a page of zeros - so that
-// nothing but the matrix instructions waits on memory.
+// consumed.  Every load is unconditional, so that nothing but the matrix instructions waits on memory.
+// Activation operands are fetched with range-checked buffer loads: a tap in the padding gets an offset beyond the
+// buffer and the hardware returns zeros for it, so every load is unconditional and no zero-filled memory is needed.
+constexpr uint32_t kOutOfRange = 0x80000000u;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_buffer(const int8_t* base, uint32_t bytes)
+{
+    // raw buffer (stride 0): the record count is in bytes; 0x00020000 = 32-bit data format, as gfx9 wants it
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(base), 0, (int)bytes, 0x00020000);
+}
+
+// 16 bytes at base + lane_offset + uniform_offset, zeros when lane_offset is outside the buffer
+__device__ __forceinline__ v4i load_operand(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_offset, uint32_t uniform_offset)
+{
+    typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+    const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_offset, (int)uniform_offset, 0);
+    return v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+}
+
 constexpr int kDepth = 4;
 constexpr int kStageSteps = 8;      // a multiple of kDepth
 
@@ -348,9 +365,9 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
 
-    const uint32_t zero_off = (uint32_t)p.zero_page + 16u * (uint32_t)g;
     const uint32_t cb_stride = (uint32_t)p.tW * 32u;            // bytes between the channel blocks of one pixel
     const uint32_t row_stride = (uint32_t)CB * cb_stride;       // ... between the rows of one image
+    const __amdgpu_buffer_rsrc_t xt_rsrc = operand_buffer(p.xt, p.xt_bytes);
     // activations: load cursor = the reduction step whose operands are requested next (all of it uniform)
     int l_step = min(s_begin, n_steps - 1);
     int l_cb = l_step % CB, l_kw = (l_step / CB) % p.tKW, l_kh = (l_step / CB) / p.tKW;
@@ -362,14 +379,14 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
         for (int h = 0; h < 2; ++h) {
             const int iy = iy0[h] + l_kh, ix = ix0[h] + l_kw;
             const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
-            tap_off[h] = ok ? origin[h] + l_tap : zero_off;
+            tap_off[h] = ok ? origin[h] + l_tap : kOutOfRange;
         }
     };
     place_tap();
     v4i opb[kDepth][2];
     auto request = [&](int slot) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) opb[slot][h] = *reinterpret_cast<const v4i*>(p.xt + (tap_off[h] + l_cboff));
+        for (int h = 0; h < 2; ++h) opb[slot][h] = load_operand(xt_rsrc, tap_off[h], l_cboff);
         if (l_step + 1 < n_steps) {                  // past the end the last step is simply requested again
             ++l_step;
             l_cboff += cb_stride;
