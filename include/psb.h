@@ -263,6 +263,37 @@ int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_co
                        float* y_dev, const float* mult_dev, const float* bias_dev, const psb_requant* rq,
                        int8_t* x_out_dev, int32_t shared, void* hip_stream);
 
+/*
+ * The chained shared-filter pass [Sect. 4.1 and suppl. "Efficient simulation of the forward pass": one sampled
+ * filter per layer and pass].  Two additions for callers that run layer after layer on one GPU:
+ *
+ * Blocked channels-last activations.  The matrix-core kernel reads its int8 activations as
+ *     xb[ (((n * H + y) * CB + c / 32) * W + x) * 32 + c % 32 ],   CB = ceil(C / 32)
+ * (blocks of 32 channels, the pixels of a row contiguous; padding channels are ignored on input and
+ * unspecified on output).  psb_conv2d_shared_requant_blocked is psb_conv2d_requant with shared = 1, a uniform S,
+ * no accumulator output, and `layout` saying which of its int8 tensors use that layout: PSB_BLOCKED_IN (x_dev:
+ * read in place, no copy is made), PSB_BLOCKED_OUT (x_out_dev), PSB_BLOCKED_RES (rq->res_i8_dev); the others, and
+ * the fp32 tensors, are [N][C][H][W].  y_dev and x_out_dev are both optional but not both NULL; with x_out_dev NULL
+ * rq is not read (a shortcut branch: only the rescaled values).  Results are those of psb_conv2d_requant, element
+ * for element.
+ * Blocked tensors must be 16-byte (input) / 4-byte (output, residual) aligned (VALUE otherwise).  PSB_BLOCKED_IN
+ * needs a layer that runs on the matrix cores (groups = 1) with more than 32 / kw input channels (SHAPE otherwise:
+ * such layers - a network's first - take [N][C][H][W]).
+ *
+ * psb_shared_prepare_filters samples the digit planes of n handles in one launch, for S samples and the given
+ * (seed, layer_id) of each.  The next shared-filter call on such a handle with the same S, seed and layer_id and
+ * no budget map uses them instead of sampling again (once: the call after that samples as usual); any other
+ * shared-filter call on the handle discards them.  Handles whose layers do not run on the matrix cores are skipped.  Same results as
+ * without the call.  Errors: NULL, SHAPE (n <= 0), VALUE (S), DEVICE, TOO_LARGE, ALLOC.
+ */
+enum { PSB_BLOCKED_IN = 1, PSB_BLOCKED_OUT = 2, PSB_BLOCKED_RES = 4 };
+int psb_conv2d_shared_requant_blocked(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S,
+                                      uint64_t seed, uint32_t layer_id, float* y_dev, const float* mult_dev,
+                                      const float* bias_dev, const psb_requant* rq, int8_t* x_out_dev, int32_t layout,
+                                      void* hip_stream);
+int psb_shared_prepare_filters(const psb_weights_t* const* handles, int32_t n, int32_t S, const uint64_t* seeds,
+                               const uint32_t* layer_ids, void* hip_stream);
+
 int psb_requantize(const float* y_dev, const float* res_f32_dev, const int8_t* res_i8_dev, float res_step,
                    int32_t relu, float inv_step, int32_t lo, int32_t hi, int64_t n, int8_t* x_dev, void* hip_stream);
 int psb_maxpool2d_i8(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, int32_t kh, int32_t kw,

@@ -25,6 +25,11 @@ struct shared_workspace {
     uint32_t* present_dev = nullptr; // 256 flags: budget values that occur
     int32_t* acc_dev = nullptr;      // accumulators of calls that do not hand any out but combine partial sums
     size_t acc_bytes = 0;
+    // digit planes sampled ahead of the call by psb_shared_prepare_filters; the next matching call consumes them
+    bool ready = false;
+    uint64_t ready_seed = 0;
+    uint32_t ready_layer = 0;
+    int32_t ready_S = 0;
 };
 
 // Accumulator scratch of a handle for psb_conv2d_requant calls without acc_dev (grown on demand).
@@ -244,9 +249,45 @@ int sample_filter_launch(const psb_weights* q, int from, int to, uint64_t seed, 
     return PSB_OK;
 }
 
+// How a handle's shared-filter calls run: on the matrix cores or with the direct kernel, and the shape of the
+// digit planes.  Depends on the weight shape (and the mapping switch) only.
+struct shared_plan {
+    bool mfma, rowpack;
+    int C_pad, CB, n_ksteps, n_ocb;
+};
+
+shared_plan plan_shared(const psb_weights* q)
+{
+    shared_plan s;
+    s.mfma = q->shape.groups == 1 && g_mapping != 1;
+    // Layers with very few input channels (a network's first layer): pack the kw x C values of one kernel row
+    // into one 32-byte reduction block instead of padding every tap's C channels to 32.
+    s.rowpack = s.mfma && q->shape.kw > 1 && q->shape.kw * q->shape.cin <= 32;
+    s.C_pad = s.rowpack ? 32 : (q->shape.cin + 31) / 32 * 32;
+    s.CB = s.C_pad / 32;
+    s.n_ksteps = s.rowpack ? q->shape.kh : q->shape.kh * q->shape.kw * s.CB;
+    s.n_ocb = (q->shape.oc + 31) / 32;
+    return s;
+}
+
+// The digit-plane buffer of a handle (allocated on first use).
+int ensure_planes(const psb_weights* q, const shared_plan& sp)
+{
+    // each digit plane is summed in int32: 128 * 128 * (padded reduction length) must stay below 2^31
+    if ((int64_t)sp.n_ksteps * 32 >= (1ll << 17)) return PSB_ERR_TOO_LARGE;
+    if (!q->ws->planes_dev) {
+        // one chunk of padding: the kernel stages whole chunks of reduction steps
+        const size_t bytes = (size_t)(sp.n_ocb * sp.n_ksteps + psb::kStageSteps) * psb::kMaxPlanes * psb::kPlaneStride;
+        if (hipMalloc(&q->ws->planes_dev, bytes) != hipSuccess) return PSB_ERR_ALLOC;   // written whole by every sampling
+    }
+    return PSB_OK;
+}
+
+// layout: PSB_BLOCKED_IN | PSB_BLOCKED_OUT | PSB_BLOCKED_RES
 int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, int32_t S, const uint8_t* budget_to,
                   const uint8_t* budget_from, uint64_t seed, uint32_t layer_id, int32_t* acc, float* y,
-                  const float* mult, const float* bias, hipStream_t stream, const psb::Requant* rq = nullptr)
+                  const float* mult, const float* bias, hipStream_t stream, const psb::Requant* rq = nullptr,
+                  int layout = 0)
 {
     int32_t OH = 0, OW = 0;
     int rc = check_geom(&q->shape, g, &OH, &OW);
@@ -255,31 +296,27 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     PSB_HIP_TRY(hipGetDevice(&dev));
     if (dev != q->device) return PSB_ERR_DEVICE;
 
-    const bool mfma = q->shape.groups == 1 && g_mapping != 1;
-    // Layers with very few input channels (a network's first layer): pack the kw x C values of one kernel row
-    // into one 32-byte reduction block instead of padding every tap's C channels to 32.
-    const bool rowpack = mfma && q->shape.kw > 1 && q->shape.kw * q->shape.cin <= 32;
-    const int C_pad = rowpack ? 32 : (q->shape.cin + 31) / 32 * 32;
-    const int CB = C_pad / 32;
-    const int n_ksteps = rowpack ? q->shape.kh : q->shape.kh * q->shape.kw * CB;
-    const int n_ocb = (q->shape.oc + 31) / 32;
-    // each digit plane is summed in int32: 128 * 128 * (padded reduction length) must stay below 2^31
-    if (mfma && (int64_t)n_ksteps * 32 >= (1ll << 17)) return PSB_ERR_TOO_LARGE;
+    const shared_plan sp = plan_shared(q);
+    const bool mfma = sp.mfma, rowpack = sp.rowpack;
+    const int C_pad = sp.C_pad, CB = sp.CB, n_ksteps = sp.n_ksteps, n_ocb = sp.n_ocb;
+    const bool in_blocked = (layout & PSB_BLOCKED_IN) != 0;
+    // a blocked input is read in place by the matrix-core kernel; the other kernels have no use for it
+    if (in_blocked && (!mfma || rowpack)) return PSB_ERR_SHAPE;
+    if (in_blocked && ((uintptr_t)x & 15u) != 0) return PSB_ERR_VALUE;
 
     shared_workspace* ws = q->ws;
     const int64_t nw = (int64_t)q->shape.oc * q->K;
     if (!mfma && !ws->w32_dev && hipMalloc(&ws->w32_dev, (size_t)nw * sizeof(int32_t)) != hipSuccess)
         return PSB_ERR_ALLOC;
     if (!ws->present_dev && hipMalloc(&ws->present_dev, 256 * sizeof(uint32_t)) != hipSuccess) return PSB_ERR_ALLOC;
-    if (mfma && !ws->planes_dev) {
-        // one chunk of padding: the kernel stages whole chunks of reduction steps
-        const size_t bytes = (size_t)(n_ocb * n_ksteps + psb::kStageSteps) * psb::kMaxPlanes * psb::kPlaneStride;
-        if (hipMalloc(&ws->planes_dev, bytes) != hipSuccess) return PSB_ERR_ALLOC;   // written whole by every call
+    if (mfma) {
+        rc = ensure_planes(q, sp);
+        if (rc != PSB_OK) return rc;
     }
     // blocked channels-last copy (row-packed: one 32-byte block per input row and output column)
     const size_t xt_need = (size_t)g->n * g->h * (rowpack ? OW : g->w) * C_pad;
     if (mfma && xt_need >= (1ull << 31)) return PSB_ERR_TOO_LARGE;      // the kernel addresses it with 32-bit offsets
-    if (mfma && ws->xt_bytes < xt_need) {
+    if (mfma && !in_blocked && ws->xt_bytes < xt_need) {
         if (ws->xt_dev) {
             PSB_HIP_TRY(hipStreamSynchronize(stream));     // an earlier call may still read the old buffer
             (void)hipFree(ws->xt_dev);
@@ -292,7 +329,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
 
     psb::SharedParams p;
     std::memset(&p, 0, sizeof(p));
-    p.x = x; p.xt = ws->xt_dev; p.planes = ws->planes_dev; p.w32 = ws->w32_dev;
+    p.x = x; p.xt = in_blocked ? x : ws->xt_dev; p.planes = ws->planes_dev; p.w32 = ws->w32_dev;
     p.budget_to = budget_to; p.budget_from = budget_from;
     p.acc = acc; p.y = y; p.mult = mult; p.bias = bias;
     if (rq) p.rq = *rq;
@@ -307,8 +344,12 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     p.tH = g->h; p.tW = g->w; p.tKH = q->shape.kh; p.tKW = q->shape.kw;
     p.t_stride_h = g->stride_h; p.t_stride_w = g->stride_w; p.t_pad_h = g->pad_h; p.t_pad_w = g->pad_w;
     if (rowpack) { p.tW = OW; p.tKW = 1; p.t_stride_w = 1; p.t_pad_w = 0; }
-    p.quad_store = rq && rq->x_out && ((int64_t)OH * OW) % 4 == 0 && ((uintptr_t)rq->x_out & 3u) == 0 &&
-                   ((uintptr_t)rq->res_i8 & 3u) == 0;
+    const bool words = ((int64_t)OH * OW) % 4 == 0;
+    p.quad_store = rq && rq->x_out && !rq->out_blocked && words && ((uintptr_t)rq->x_out & 3u) == 0;
+    p.quad_res = rq && rq->res_i8 && !rq->res_blocked && words && ((uintptr_t)rq->res_i8 & 3u) == 0;
+    if (rq && ((rq->out_blocked && ((uintptr_t)rq->x_out & 3u) != 0) ||
+               (rq->res_blocked && ((uintptr_t)rq->res_i8 & 3u) != 0)))
+        return PSB_ERR_VALUE;
     p.ksplit = 1;
     if (mfma) {
         // Few pixel tiles and a long reduction: cut the reduction so that every SIMD has a wave.  Only then: the
@@ -327,7 +368,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     psb::TransposeJob tj;
     std::memset(&tj, 0, sizeof(tj));
     int64_t transpose_blocks = 0;
-    if (mfma) {
+    if (mfma && !in_blocked) {
         tj.x = x; tj.C = p.C; tj.H = p.H; tj.W = p.W; tj.C_pad = C_pad; tj.xt = ws->xt_dev;
         tj.tiles_x = (g->w + 63) / 64; tj.rows = (int64_t)g->n * g->h;
         transpose_blocks = (int64_t)tj.tiles_x * tj.rows * CB;
@@ -338,8 +379,13 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     }
     auto prepare = [&](int from, int to) -> int {
         // matrix cores: one thread per slot of the operand-ordered planes; otherwise one per weight
-        const int64_t filter_blocks = mfma ? (int64_t)n_ocb * n_ksteps * 4 : (nw + 255) / 256;
+        // planes sampled ahead of this call (psb_shared_prepare_filters) are used once
+        const bool have = mfma && ws->ready && ws->ready_seed == seed && ws->ready_layer == layer_id && from == 0 &&
+                          to == ws->ready_S;
+        ws->ready = false;
+        const int64_t filter_blocks = have ? 0 : mfma ? (int64_t)n_ocb * n_ksteps * 4 : (nw + 255) / 256;
         if (filter_blocks + transpose_blocks > 2147483647ll) return PSB_ERR_TOO_LARGE;
+        if (filter_blocks + transpose_blocks == 0) return PSB_OK;
         psb::FilterJob fj = filter_job(q, from, to, seed, layer_id, mfma ? nullptr : ws->w32_dev,
                                        mfma ? ws->planes_dev : nullptr, CB, n_ksteps);
         fj.n_planes = psb::planes_needed(max_shift, to - from);
@@ -711,6 +757,7 @@ int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_co
     if (rq->res_f32_dev && rq->res_i8_dev) return PSB_ERR_VALUE;
     if (rq->lo < -128 || rq->hi > 127 || rq->lo > rq->hi) return PSB_ERR_VALUE;
     psb::Requant r;
+    std::memset(&r, 0, sizeof(r));
     r.x_out = x_out_dev; r.res_f32 = rq->res_f32_dev; r.res_i8 = rq->res_i8_dev; r.res_step = rq->res_step;
     r.inv_step = rq->inv_step; r.lo = (float)rq->lo; r.hi = (float)rq->hi; r.relu = rq->relu;
     if (shared)
@@ -718,6 +765,78 @@ int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_co
                              mult_dev, bias_dev, (hipStream_t)hip_stream, &r);
     return launch_layer(q, x_dev, geom, budget_to_dev ? 0 : S, budget_to_dev, nullptr, seed, layer_id, acc_dev, y_dev,
                         mult_dev, bias_dev, (hipStream_t)hip_stream, &r);
+}
+
+int psb_conv2d_shared_requant_blocked(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S,
+                                      uint64_t seed, uint32_t layer_id, float* y_dev, const float* mult_dev,
+                                      const float* bias_dev, const psb_requant* rq, int8_t* x_out_dev, int32_t layout,
+                                      void* hip_stream)
+{
+    if (!q || !x_dev || !geom || (!y_dev && !x_out_dev) || (x_out_dev && !rq)) return PSB_ERR_NULL;
+    if (S <= 0 || S > q->s_max) return PSB_ERR_VALUE;
+    if (layout & ~(PSB_BLOCKED_IN | PSB_BLOCKED_OUT | PSB_BLOCKED_RES)) return PSB_ERR_VALUE;
+    if (!x_out_dev)         // the rescaled values only
+        return launch_shared(q, x_dev, geom, S, nullptr, nullptr, seed, layer_id, nullptr, y_dev, mult_dev, bias_dev,
+                             (hipStream_t)hip_stream, nullptr, layout & PSB_BLOCKED_IN);
+    if (rq->res_f32_dev && rq->res_i8_dev) return PSB_ERR_VALUE;
+    if (rq->lo < -128 || rq->hi > 127 || rq->lo > rq->hi) return PSB_ERR_VALUE;
+    psb::Requant r;
+    std::memset(&r, 0, sizeof(r));
+    r.x_out = x_out_dev; r.res_f32 = rq->res_f32_dev; r.res_i8 = rq->res_i8_dev; r.res_step = rq->res_step;
+    r.inv_step = rq->inv_step; r.lo = (float)rq->lo; r.hi = (float)rq->hi; r.relu = rq->relu;
+    r.out_blocked = (layout & PSB_BLOCKED_OUT) != 0;
+    r.res_blocked = (layout & PSB_BLOCKED_RES) != 0 && rq->res_i8_dev;
+    return launch_shared(q, x_dev, geom, S, nullptr, nullptr, seed, layer_id, nullptr, y_dev, mult_dev, bias_dev,
+                         (hipStream_t)hip_stream, &r, layout);
+}
+
+int psb_shared_prepare_filters(const psb_weights_t* const* handles, int32_t n, int32_t S, const uint64_t* seeds,
+                               const uint32_t* layer_ids, void* hip_stream)
+{
+    if (!handles || !seeds || !layer_ids) return PSB_ERR_NULL;
+    if (n <= 0) return PSB_ERR_SHAPE;
+    for (int i = 0; i < n; ++i) {
+        if (!handles[i]) return PSB_ERR_NULL;
+        if (S <= 0 || S > handles[i]->s_max) return PSB_ERR_VALUE;
+    }
+    int dev = 0;
+    PSB_HIP_TRY(hipGetDevice(&dev));
+    hipStream_t stream = (hipStream_t)hip_stream;
+    psb::FilterBatch batch;
+    std::memset(&batch, 0, sizeof(batch));
+    int64_t blocks = 0;
+    auto flush = [&]() -> int {
+        if (batch.n == 0) return PSB_OK;
+        batch.first_block[batch.n] = (unsigned)blocks;
+        hipLaunchKernelGGL(psb::k_sample_planes_batch, dim3((unsigned)blocks), dim3(256), 0, stream, batch);
+        PSB_HIP_TRY(hipGetLastError());
+        batch.n = 0;
+        blocks = 0;
+        return PSB_OK;
+    };
+    for (int i = 0; i < n; ++i) {
+        const psb_weights* q = handles[i];
+        if (q->device != dev) return PSB_ERR_DEVICE;
+        const shared_plan sp = plan_shared(q);
+        if (!sp.mfma) continue;                 // the direct kernel samples its filter in the call itself
+        int rc = ensure_planes(q, sp);
+        if (rc != PSB_OK) return rc;
+        const int64_t need = (int64_t)sp.n_ocb * sp.n_ksteps * 4;
+        if (batch.n == psb::kMaxBatchJobs || blocks + need > 2147483647ll) {
+            rc = flush();
+            if (rc != PSB_OK) return rc;
+        }
+        if (need > 2147483647ll) return PSB_ERR_TOO_LARGE;
+        psb::FilterJob fj = filter_job(q, 0, S, seeds[i], layer_ids[i], nullptr, q->ws->planes_dev, sp.CB, sp.n_ksteps);
+        fj.n_planes = psb::planes_needed(q->info.e_top - q->info.e_min, S);
+        if (sp.rowpack) { fj.pack_KW = q->shape.kw; fj.pack_C = q->shape.cin; }
+        batch.jobs[batch.n] = fj;
+        batch.first_block[batch.n] = (unsigned)blocks;
+        batch.n++;
+        blocks += need;
+        q->ws->ready = true; q->ws->ready_seed = seeds[i]; q->ws->ready_layer = layer_ids[i]; q->ws->ready_S = S;
+    }
+    return flush();
 }
 
 // ---- glue between layers ------------------------------------------------------------------------------

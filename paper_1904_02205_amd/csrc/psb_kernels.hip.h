@@ -166,6 +166,9 @@ struct Requant {
     const int8_t* res_i8;     // residual operand as integers times res_step, or null
     float res_step, inv_step, lo, hi;
     int relu;
+    // Layout of x_out / of res_i8: 0 = [N][OC][OH][OW]; 1 = blocked channels-last [N][OH][ceil(OC/32)][OW][32]
+    // (the layout the shared-filter kernel reads its activations in).  res_f32 is always [N][OC][OH][OW].
+    int out_blocked, res_blocked;
 };
 
 struct LayerParams {
@@ -274,6 +277,17 @@ __device__ __forceinline__ int32_t requantize_one(float y, bool has_res, float r
 
 // Everything a layer kernel writes besides the accumulator: the rescaled value and/or the requantised activation
 // of output element o (channel oc, `to` samples).  P is LayerParams or the shared-filter mode's parameter block.
+// Index of output element o = ((n * OC + oc) * OH + oy) * OW + ox in the blocked channels-last layout.
+template <class P>
+__device__ __forceinline__ int64_t blocked_index(const P& p, int64_t o, int oc)
+{
+    const int64_t hw = (int64_t)p.OH * p.OW;
+    const int64_t n = o / (hw * p.OC);
+    const int pix = (int)(o % hw);
+    const int oy = pix / p.OW, ox = pix - oy * p.OW;
+    return ((((n * p.OH + oy) * ((p.OC + 31) >> 5) + (oc >> 5)) * p.OW + ox) << 5) + (oc & 31);
+}
+
 template <class P>
 __device__ __forceinline__ void emit(const P& p, int64_t o, int oc, int32_t acc, int to)
 {
@@ -281,11 +295,12 @@ __device__ __forceinline__ void emit(const P& p, int64_t o, int oc, int32_t acc,
     const float r = rescale(acc, p.mult ? p.mult[oc] : p.default_mult, to, p.bias, oc);
     if (p.y) p.y[o] = r;
     if (p.rq.x_out) {
+        const int64_t ob = (p.rq.out_blocked || p.rq.res_blocked) ? blocked_index(p, o, oc) : o;
         float res = 0.0f;
         if (p.rq.res_f32) res = p.rq.res_f32[o];
-        if (p.rq.res_i8) res = __fmul_rn((float)p.rq.res_i8[o], p.rq.res_step);
-        p.rq.x_out[o] = (int8_t)requantize_one(r, p.rq.res_f32 || p.rq.res_i8, res, p.rq.relu != 0, p.rq.inv_step,
-                                               p.rq.lo, p.rq.hi);
+        if (p.rq.res_i8) res = __fmul_rn((float)p.rq.res_i8[p.rq.res_blocked ? ob : o], p.rq.res_step);
+        p.rq.x_out[p.rq.out_blocked ? ob : o] = (int8_t)requantize_one(r, p.rq.res_f32 || p.rq.res_i8, res, p.rq.relu != 0,
+                                                                       p.rq.inv_step, p.rq.lo, p.rq.hi);
     }
 }
 

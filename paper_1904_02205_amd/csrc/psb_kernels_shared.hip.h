@@ -63,8 +63,10 @@ struct SharedParams {
     int seg_from, seg_to;      //    range contains [seg_from, seg_to); acc accumulated
     float default_mult;
     Requant rq;
-    int quad_store;            // fused requantisation writes four pixels of one channel as one word (the launcher
-                               // sets it when OH * OW and the byte tensors' addresses are multiples of 4)
+    // [N][OC][OH][OW] byte tensors of the fused requantisation move as 32-bit words (four pixels of one channel,
+    // after a byte transpose over four lanes) when OH * OW and the tensor's address are multiples of 4:
+    int quad_store;            // ... x_out
+    int quad_res;              // ... res_i8
 };
 
 // Filter sampling: count and filter value of one weight; digit planes for the matrix cores.
@@ -213,6 +215,22 @@ __device__ __forceinline__ void channels_last_tile(const TransposeJob& j, int64_
         uint2* dst = reinterpret_cast<uint2*>(j.xt + (((row * (j.C_pad >> 5) + (c0 >> 5)) * j.W + ix0 + dx) * 32 + part * 8));
         *dst = make_uint2(lo, hi);
     }
+}
+
+// The digit planes of several layers in one launch (a network pass samples all its filters at once): job i owns
+// the blocks [first_block[i], first_block[i + 1]).
+constexpr int kMaxBatchJobs = 32;
+struct FilterBatch {
+    FilterJob jobs[kMaxBatchJobs];
+    unsigned first_block[kMaxBatchJobs + 1];
+    int n;
+};
+
+__global__ void __launch_bounds__(256) k_sample_planes_batch(const FilterBatch b)
+{
+    int i = 0;
+    while (i + 1 < b.n && blockIdx.x >= b.first_block[i + 1]) ++i;     // uniform over the workgroup
+    sample_planes_thread(b.jobs[i], (int64_t)(blockIdx.x - b.first_block[i]) * 256 + threadIdx.x);
 }
 
 __global__ void __launch_bounds__(256) k_sample_filter(const FilterJob j)
@@ -481,7 +499,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
                     const int dq = 8 * (q >> 2) + (q & 3);
                     if (!FULL && oc_first + dq >= p.OC) continue;
                     const uint32_t u = sum_of(h, q);
-                    p.acc[o_first + dq * plane] = (int32_t)u;
+                    if (p.acc) p.acc[o_first + dq * plane] = (int32_t)u;
                     if (with_y) p.y[o_first + dq * plane] = rescaled(q, u);
                 }
                 continue;
@@ -489,11 +507,12 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
             // Requantised activations.  Every global operand (the residual) is loaded before the first store: a
             // store may alias a later load as far as the compiler can tell, and interleaving them would put the
             // latency of each load in series.
-            const bool quad = p.quad_store != 0;
             const int j = lane & 3;
-            // with quad: lane j of a quad moves the word of channel (first of the group of four) + j, pixels
-            // (pin & ~3) .. + 3, and the four lanes - consecutive pixels of one image - swap bytes
+            // [N][OC][OH][OW] as words: lane j of a quad moves the word of channel (first of the group of four) + j,
+            // pixels (pin & ~3) .. + 3, and the four lanes - consecutive pixels of one image - swap bytes
             const int64_t w_first = o_first + j * plane - ((oy_[h] * p.OW + ox_[h]) & 3);
+            // blocked layout: the four channels of a register group are four consecutive bytes of the pixel's block
+            const int64_t b_first = (((((int64_t)n_[h] * p.OH + oy_[h]) * gridDim.y + ocb) * p.OW + ox_[h]) << 5) + 4 * g;
             float res[16];
 #pragma unroll
             for (int q = 0; q < 16; ++q) res[q] = 0.0f;
@@ -504,17 +523,20 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
                     const int dq = 8 * (q >> 2) + (q & 3);
                     if (FULL || oc_first + dq < p.OC) res[q] = p.rq.res_f32[o_first + dq * plane];
                 }
-            } else if (p.rq.res_i8 && quad) {
+            } else if (p.rq.res_i8 && (p.rq.res_blocked || p.quad_res)) {
                 uint32_t resw[4];
 #pragma unroll
                 for (int qq = 0; qq < 4; ++qq) {
                     resw[qq] = 0;
-                    if (FULL || oc_first + 8 * qq + j < p.OC)
+                    if (p.rq.res_blocked)
+                        resw[qq] = *reinterpret_cast<const uint32_t*>(p.rq.res_i8 + b_first + 8 * qq);
+                    else if (FULL || oc_first + 8 * qq + j < p.OC)
                         resw[qq] = *reinterpret_cast<const uint32_t*>(p.rq.res_i8 + w_first + 8 * qq * plane);
                 }
 #pragma unroll
                 for (int qq = 0; qq < 4; ++qq) {
-                    const uint32_t w = quad_transpose_bytes(resw[qq]);    // byte i: channel + i at this lane's pixel
+                    // byte i: channel (first of the group) + i at this lane's pixel
+                    const uint32_t w = p.rq.res_blocked ? resw[qq] : quad_transpose_bytes(resw[qq]);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) res[4 * qq + i] = __fmul_rn((float)(int8_t)(w >> (8 * i)), p.rq.res_step);
                 }
@@ -545,10 +567,13 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
                     const int q = 4 * qq + i;
                     const uint32_t u = sum_of(h, q);
                     const float r = rescaled(q, u);
-                    const uint32_t xq = (uint32_t)requantize_one(r, has_res, res[q], relu, p.rq.inv_step, p.rq.lo, p.rq.hi) & 0xFFu;
+                    uint32_t xq = (uint32_t)requantize_one(r, has_res, res[q], relu, p.rq.inv_step, p.rq.lo, p.rq.hi) & 0xFFu;
+                    if (!FULL && oc_first + 8 * qq + i >= p.OC) xq = 0;   // padding channels of the blocked layout
                     word |= xq << (8 * i);
                 }
-                if (quad) {
+                if (p.rq.out_blocked) {
+                    *reinterpret_cast<uint32_t*>(p.rq.x_out + b_first + 8 * qq) = word;
+                } else if (p.quad_store) {
                     word = quad_transpose_bytes(word); // byte i: this lane's channel at pixel (pin & ~3) + i
                     if (FULL || oc_first + 8 * qq + j < p.OC)
                         *reinterpret_cast<uint32_t*>(p.rq.x_out + w_first + 8 * qq * plane) = word;

@@ -78,10 +78,76 @@ class ResNet18:
             psb.conv2d_progressive(self.q[i], x, psb.budget_resample(budget, oh, oh), None, **kw)
         return y
 
-    def forward(self, S=8, budget=None, s_fc=None, shared=False, collect=None, fused=True):
+    def _chain_call(self, i, x, x_shape, S, inv_step, layout, **kw):
+        sp = self.net.specs[i]
+        return psb.conv2d_shared_requant_blocked(self.q[i], x, x_shape, inv_step, S, stride=(sp.stride, sp.stride),
+                                                 pad=(sp.pad, sp.pad), seed=self.seed, layer_id=i, mult=self.mult[i],
+                                                 bias=self.bias[i], layout=layout, **kw)
+
+    def _forward_chain(self, S, collect):
+        """Shared-filter pass with a uniform sample count, as one chain on the GPU: every filter of the pass is
+        sampled in one launch up front, and between the convolutions the activations stay in the blocked
+        channels-last layout that the matrix-core kernel reads in place (no layout copies).  Same integers as the
+        layer-by-layer pass."""
+        def keep(t, shape=None):
+            if collect is None:
+                return
+            if shape is not None:        # diagnostic copy back to [N, C, H, W]
+                n, c, h, w = shape
+                t = t.permute(0, 2, 4, 1, 3).reshape(n, -1, h, w)[:, :c].contiguous()
+            collect.append(t)
+        inv_relu, inv_block = float(np.float32(1.0 / rs.STEP_RELU)), float(np.float32(1.0 / rs.STEP_BLOCK))
+        n_layers = len(self.q)
+        psb.shared_prepare_filters(self.q, S, [self.seed] * n_layers, list(range(n_layers)))
+        a = self._conv_requant(0, self.x0, S, None, True, inv_relu)
+        keep(a)
+        a = psb.maxpool2d_i8(a, (3, 3), (2, 2), (1, 1))
+        keep(a)
+        shape, blocked = tuple(a.shape), False      # logical [N, C, H, W] of `a` and its layout
+        step_a = rs.STEP_RELU
+        i = 1
+        B_IN, B_OUT, B_RES = psb.BLOCKED_IN, psb.BLOCKED_OUT, psb.BLOCKED_RES
+        while self.names[i] != "fc":
+            has_sc = self.names[i + 2].endswith("sc")
+            last = self.names[i + (3 if has_sc else 2)] == "fc"
+            sp = self.net.specs[i]
+            oh = (shape[2] + 2 * sp.pad - sp.k) // sp.stride + 1
+            shape1 = (shape[0], sp.cout, oh, oh)
+            lin = B_IN if blocked else 0
+            a1 = self._chain_call(i, a, shape, S, inv_relu, lin | B_OUT)
+            keep(a1, shape1)
+            lout = 0 if last else B_OUT              # the average pooling reads [N, C, H, W]
+            if has_sc:
+                ysc = self._chain_call(i + 2, a, shape, S, 0.0, lin, want_x=False)
+                a = self._chain_call(i + 1, a1, shape1, S, inv_block, B_IN | lout, res_f32=ysc)
+            else:
+                a = self._chain_call(i + 1, a1, shape1, S, inv_block, B_IN | lout | (B_RES if blocked else 0), res_i8=a,
+                                     res_step=float(np.float32(step_a)))
+            shape, blocked = shape1, not last
+            keep(a, shape if blocked else None)
+            step_a = rs.STEP_BLOCK
+            i += 3 if has_sc else 2
+        pooled = psb.global_avgpool_requantize(a, 1.0)
+        keep(pooled)
+        n = pooled.shape[0]
+        logits = torch.empty((n, self.net.specs[i].cout), dtype=torch.float32, device=self.device)
+        acc = torch.empty((n, self.net.specs[i].cout), dtype=torch.int32, device=self.device)
+        psb.linear(self.q[i], pooled, S, seed=self.seed, layer_id=i, acc=acc, y=logits, mult=self.mult[i],
+                   bias=self.bias[i], shared=True)
+        return logits
+
+    def forward(self, S=8, budget=None, s_fc=None, shared=False, collect=None, fused=True, chain=None):
         """Logits float32 [batch, classes].  collect: optional list that receives every int8 activation tensor.
         fused: requantisation in the epilogue of the layer kernels (default) or as separate glue kernels; the
-        activations are the same integers either way."""
+        activations are the same integers either way.  chain: run a shared-filter pass with a uniform sample count
+        as one chain (see _forward_chain); by default whenever that applies."""
+        can_chain = shared and fused and budget is None and (s_fc is None or s_fc == S) and not self.record_inputs
+        if chain is None:
+            chain = can_chain
+        if chain:
+            if not can_chain:
+                raise ValueError("chain=True needs shared=True, fused=True, no budget map and s_fc == S")
+            return self._forward_chain(S, collect)
         keep = (lambda t: collect.append(t)) if collect is not None else (lambda t: None)
         inv_relu, inv_block = float(np.float32(1.0 / rs.STEP_RELU)), float(np.float32(1.0 / rs.STEP_BLOCK))
         if fused:

@@ -21,7 +21,7 @@ MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE, MAPPING_PRODUCT_LIST = 0
 SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
            "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
-           "psb_conv2d_requant", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
+           "psb_conv2d_requant", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
            "psb_attention_budget", "psb_last_device_error", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
            "psb_profile_read"]
 
@@ -84,6 +84,9 @@ def lib():
         L.psb_conv2d_shared.argtypes = L.psb_conv2d.argtypes
         L.psb_conv2d_progressive_shared.argtypes = L.psb_conv2d_progressive.argtypes
         f32 = C.c_float
+        L.psb_conv2d_shared_requant_blocked.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, u64, u32, vp, vp, vp,
+                                                        C.POINTER(Requant), vp, i32, vp]
+        L.psb_shared_prepare_filters.argtypes = [vp, i32, i32, vp, vp, vp]
         L.psb_conv2d_requant.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, vp, u64, u32, vp, vp, vp, vp,
                                          C.POINTER(Requant), vp, i32, vp]
         L.psb_requantize.argtypes = [vp, vp, vp, f32, i32, f32, i32, i32, C.c_int64, vp, vp]
@@ -272,6 +275,50 @@ def conv2d_requant(q, x, inv_step, S=None, budget_to=None, stride=(1, 1), pad=(0
                                   _ptr(x_out, torch.int8, "x_out"), 1 if shared else 0, _stream())
     _check(rc, "psb_conv2d_requant")
     return x_out
+
+
+BLOCKED_IN, BLOCKED_OUT, BLOCKED_RES = 1, 2, 4
+
+
+def blocked_shape(n, c, h, w):
+    """Shape of the blocked channels-last form of an [n, c, h, w] int8 tensor: [n, h, ceil(c/32), w, 32]."""
+    return (n, h, (c + 31) // 32, w, 32)
+
+
+def conv2d_shared_requant_blocked(q, x, x_shape, inv_step, S, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, relu=True,
+                                  lo=0, hi=127, res_f32=None, res_i8=None, res_step=0.0, mult=None, bias=None,
+                                  x_out=None, y=None, layout=0, want_x=True):
+    """Shared-filter layer with fused requantisation whose int8 tensors may be in the blocked channels-last layout
+    (layout: BLOCKED_IN | BLOCKED_OUT | BLOCKED_RES).  x_shape = (N, C, H, W) of the input whatever its layout.
+    Returns x_out: [N, OC, OH, OW], or its blocked form with BLOCKED_OUT.  want_x=False: only the rescaled fp32
+    values are computed, into y [N, OC, OH, OW] (allocated if None), which is returned."""
+    n, c, h, w = x_shape
+    g = ConvGeom(n, h, w, stride[0], stride[1], pad[0], pad[1])
+    oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
+    oc = q.wshape[0]
+    if want_x and x_out is None:
+        shape = blocked_shape(n, oc, oh, ow) if layout & BLOCKED_OUT else (n, oc, oh, ow)
+        x_out = torch.empty(shape, dtype=torch.int8, device=x.device)
+    if not want_x and y is None:
+        y = torch.empty((n, oc, oh, ow), dtype=torch.float32, device=x.device)
+    rq = Requant(1 if relu else 0, inv_step, lo, hi,
+                 None if res_f32 is None else _ptr(res_f32, torch.float32, "res_f32").value,
+                 None if res_i8 is None else _ptr(res_i8, torch.int8, "res_i8").value, res_step)
+    rc = lib().psb_conv2d_shared_requant_blocked(q._h, _ptr(x, torch.int8, "x"), C.byref(g), S, seed, layer_id,
+                                                 _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"),
+                                                 _ptr(bias, torch.float32, "bias"), C.byref(rq),
+                                                 _ptr(x_out if want_x else None, torch.int8, "x_out"), layout, _stream())
+    _check(rc, "psb_conv2d_shared_requant_blocked")
+    return x_out if want_x else y
+
+
+def shared_prepare_filters(handles, S, seeds, layer_ids):
+    """Sample the digit planes of several layers in one launch; the next matching shared-filter call of each uses them."""
+    n = len(handles)
+    hs = (C.c_void_p * n)(*[q._h for q in handles])
+    sd = (C.c_uint64 * n)(*[int(v) for v in seeds])
+    li = (C.c_uint32 * n)(*[int(v) for v in layer_ids])
+    _check(lib().psb_shared_prepare_filters(hs, n, S, sd, li, _stream()), "psb_shared_prepare_filters")
 
 
 # ---- glue between layers ---------------------------------------------------------------------------------

@@ -154,7 +154,7 @@ def test_fused_requantisation_equals_layer_then_requantize(psb, orc, shared):
 def _compare(psb, orc, net, prob_bits=23, **kw):
     from paper_1904_02205_amd import network
     ref_acts, got_acts = [], []
-    kw_ref = {k: v for k, v in kw.items() if k != "fused"}
+    kw_ref = {k: v for k, v in kw.items() if k not in ("fused", "chain")}
     ref = oracle_network.OracleResNet18(orc, net, prob_bits=prob_bits).forward(collect=ref_acts, **kw_ref)
     model = network.ResNet18(net, prob_bits=prob_bits)
     kw_g = dict(kw)
@@ -174,8 +174,9 @@ def test_network_end_to_end(psb, orc):
     a = _compare(psb, orc, net, S=8)
     _compare(psb, orc, net, S=8, fused=False)
     _compare(psb, orc, net, S=8, shared=True, fused=False)
-    b = _compare(psb, orc, net, S=8, shared=True)
+    b = _compare(psb, orc, net, S=8, shared=True)                  # as one chain: blocked activations, filters up front
     assert not np.array_equal(a, b)
+    _compare(psb, orc, net, S=8, shared=True, chain=False)         # layer by layer
     _compare(psb, orc, net, prob_bits=4, S=16)
 
 
