@@ -236,6 +236,8 @@ psb::FilterJob filter_job(const psb_weights* q, int from, int to, uint64_t seed,
     j.key0 = (uint32_t)(seed & 0xFFFFFFFFull); j.key1 = (uint32_t)(seed >> 32); j.layer_id = layer_id;
     j.w32 = w32; j.planes = planes;
     j.pack_KW = 0; j.pack_C = 0; j.n_planes = psb::kMaxPlanes;
+    j.C = q->K / j.KHW;
+    j.inv_ksteps = psb::inverse_of((uint32_t)n_ksteps); j.inv_CB = psb::inverse_of((uint32_t)CB); j.inv_pack_C = 0xFFFFFFFFu;
     return j;
 }
 
@@ -383,13 +385,13 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         const bool have = mfma && ws->ready && ws->ready_seed == seed && ws->ready_layer == layer_id && from == 0 &&
                           to == ws->ready_S;
         ws->ready = false;
-        const int64_t filter_blocks = have ? 0 : mfma ? (int64_t)n_ocb * n_ksteps * 4 : (nw + 255) / 256;
+        const int64_t filter_blocks = have ? 0 : mfma ? ((int64_t)n_ocb * n_ksteps + psb::kPlaneGroup - 1) / psb::kPlaneGroup * 4 : (nw + 255) / 256;
         if (filter_blocks + transpose_blocks > 2147483647ll) return PSB_ERR_TOO_LARGE;
         if (filter_blocks + transpose_blocks == 0) return PSB_OK;
         psb::FilterJob fj = filter_job(q, from, to, seed, layer_id, mfma ? nullptr : ws->w32_dev,
                                        mfma ? ws->planes_dev : nullptr, CB, n_ksteps);
         fj.n_planes = psb::planes_needed(max_shift, to - from);
-        if (rowpack) { fj.pack_KW = q->shape.kw; fj.pack_C = q->shape.cin; }
+        if (rowpack) { fj.pack_KW = q->shape.kw; fj.pack_C = q->shape.cin; fj.inv_pack_C = psb::inverse_of((uint32_t)q->shape.cin); }
         hipLaunchKernelGGL(psb::k_shared_prologue, dim3((unsigned)(filter_blocks + transpose_blocks)), dim3(256), 0,
                            stream, fj, tj, (unsigned)filter_blocks);
         PSB_HIP_TRY(hipGetLastError());
@@ -803,17 +805,22 @@ int psb_shared_prepare_filters(const psb_weights_t* const* handles, int32_t n, i
     PSB_HIP_TRY(hipGetDevice(&dev));
     hipStream_t stream = (hipStream_t)hip_stream;
     psb::FilterBatch batch;
-    std::memset(&batch, 0, sizeof(batch));
+    int n_jobs = 0;
     int64_t blocks = 0;
+    auto reset = [&]() {
+        std::memset(&batch, 0, sizeof(batch));
+        for (int k = 0; k <= psb::kMaxBatchJobs; ++k) batch.first_block[k] = 0xFFFFFFFFu;
+        n_jobs = 0;
+        blocks = 0;
+    };
     auto flush = [&]() -> int {
-        if (batch.n == 0) return PSB_OK;
-        batch.first_block[batch.n] = (unsigned)blocks;
+        if (n_jobs == 0) return PSB_OK;
         hipLaunchKernelGGL(psb::k_sample_planes_batch, dim3((unsigned)blocks), dim3(256), 0, stream, batch);
         PSB_HIP_TRY(hipGetLastError());
-        batch.n = 0;
-        blocks = 0;
+        reset();
         return PSB_OK;
     };
+    reset();
     for (int i = 0; i < n; ++i) {
         const psb_weights* q = handles[i];
         if (q->device != dev) return PSB_ERR_DEVICE;
@@ -821,18 +828,18 @@ int psb_shared_prepare_filters(const psb_weights_t* const* handles, int32_t n, i
         if (!sp.mfma) continue;                 // the direct kernel samples its filter in the call itself
         int rc = ensure_planes(q, sp);
         if (rc != PSB_OK) return rc;
-        const int64_t need = (int64_t)sp.n_ocb * sp.n_ksteps * 4;
-        if (batch.n == psb::kMaxBatchJobs || blocks + need > 2147483647ll) {
+        const int64_t need = ((int64_t)sp.n_ocb * sp.n_ksteps + psb::kPlaneGroup - 1) / psb::kPlaneGroup * 4;
+        if (n_jobs == psb::kMaxBatchJobs || blocks + need > 2147483647ll) {
             rc = flush();
             if (rc != PSB_OK) return rc;
         }
         if (need > 2147483647ll) return PSB_ERR_TOO_LARGE;
         psb::FilterJob fj = filter_job(q, 0, S, seeds[i], layer_ids[i], nullptr, q->ws->planes_dev, sp.CB, sp.n_ksteps);
         fj.n_planes = psb::planes_needed(q->info.e_top - q->info.e_min, S);
-        if (sp.rowpack) { fj.pack_KW = q->shape.kw; fj.pack_C = q->shape.cin; }
-        batch.jobs[batch.n] = fj;
-        batch.first_block[batch.n] = (unsigned)blocks;
-        batch.n++;
+        if (sp.rowpack) { fj.pack_KW = q->shape.kw; fj.pack_C = q->shape.cin; fj.inv_pack_C = psb::inverse_of((uint32_t)q->shape.cin); }
+        batch.jobs[n_jobs] = fj;
+        batch.first_block[n_jobs] = (unsigned)blocks;
+        n_jobs++;
         blocks += need;
         q->ws->ready = true; q->ws->ready_seed = seeds[i]; q->ws->ready_layer = layer_ids[i]; q->ws->ready_S = S;
     }

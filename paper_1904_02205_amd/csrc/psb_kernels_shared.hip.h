@@ -75,15 +75,16 @@ struct FilterJob {
     int OC, K, KHW, CB, n_ksteps, prob_bits, from, to;
     int pack_KW, pack_C;      // row packing: kernel width and channel count (0: not packed)
     int n_planes;             // digit planes the contraction of this sample range reads
+    int C;                    // input channels (K / KHW)
+    uint32_t inv_ksteps, inv_CB, inv_pack_C;   // floor(2^32 / d) of the three divisors of the index arithmetic
     uint32_t key0, key1, layer_id;
     int32_t* w32;             // [OC][K], or null when only the planes are wanted
     int8_t* planes;           // operand-ordered digit planes, or null
 };
 
-// W[oc][k] for the job's sample range
-__device__ __forceinline__ int32_t sample_weight(const FilterJob& j, int oc, int k)
+// W[oc][k] for the job's sample range, from the weight's encoded word
+__device__ __forceinline__ int32_t sample_word(const FilterJob& j, uint32_t word, int oc, int k)
 {
-    const uint32_t word = j.packed[(int64_t)oc * j.K + k];
     if ((word & 0x7F800000u) == kDeadWord) return 0;
     const uint32_t thr = threshold_of(word & 0x7FFFFFu, j.prob_bits);
     const uint32_t cnt = j.prob_bits < 23
@@ -98,7 +99,7 @@ __device__ __forceinline__ void sample_filter_thread(const FilterJob& j, int64_t
 {
     if (i >= (int64_t)j.OC * j.K) return;
     const int oc = (int)(i / j.K);
-    j.w32[i] = sample_weight(j, oc, (int)(i - (int64_t)oc * j.K));
+    j.w32[i] = sample_word(j, j.packed[i], oc, (int)(i - (int64_t)oc * j.K));
 }
 
 // 4 x 4 byte transpose across the four lanes of a quad: afterwards byte i of lane j is what byte j of
@@ -113,43 +114,78 @@ __device__ __forceinline__ uint32_t quad_transpose_bytes(uint32_t d)
     return ((d0 >> s) & 0xFFu) | (((d1 >> s) & 0xFFu) << 8) | (((d2 >> s) & 0xFFu) << 16) | ((d3 >> s) << 24);
 }
 
-// Digit planes in operand order: one thread per (channel, slot) of every 32-channel x 32-slot operand block,
-// padding included (those get zeros, so the buffer needs no clearing).  Thread t: bits 0-3 and 9 = slot,
-// bits 4-8 = channel inside its block of 32, the rest = (channel block, reduction step).  The four lanes
-// of a quad hold four consecutive slots; after the byte transpose lane b of the quad stores plane b's four
-// digits as one 32-bit word.
-__device__ __forceinline__ void sample_planes_thread(const FilterJob& j, int64_t t)
+// x / d and x % d for any 32-bit x, given inv = floor(2^32 / d) (0xFFFFFFFF for d = 1): the product's high word
+// is the quotient or one less.
+__host__ __device__ inline uint32_t inverse_of(uint32_t d) { return d <= 1u ? 0xFFFFFFFFu : (uint32_t)(0x100000000ull / d); }
+__device__ __forceinline__ uint32_t div_mod(uint32_t x, uint32_t d, uint32_t inv, uint32_t& rem)
 {
-    const int cl = (int)(t & 15) + 16 * (int)((t >> 9) & 1);
+    uint32_t q = __umulhi(x, inv);
+    uint32_t r = x - q * d;
+    if (r >= d) { ++q; r -= d; }
+    rem = r;
+    return q;
+}
+
+// Digit planes in operand order: one thread per (channel, slot) of a 32-channel x 32-slot operand block, padding
+// included (those get zeros, so the buffer needs no clearing), and kPlaneGroup operand blocks per thread, so that
+// the weight words of all of them are in flight before the first is sampled.  Workgroup `block` of the job works
+// on operand blocks (block >> 2) * kPlaneGroup + g, each = (channel block, reduction step) - uniform values, whose
+// divisions run on the scalar unit - and its thread t' = (block & 3) * 256 + thread index on slot (bits 0-3 and
+// 9 of t') of channel (bits 4-8).  The four lanes of a quad hold four consecutive slots; after the byte transpose
+// lane b of the quad stores plane b's four digits as one 32-bit word.
+constexpr int kPlaneGroup = 4;
+
+__device__ __forceinline__ void sample_planes_block(const FilterJob& j, uint32_t block)
+{
+    const uint32_t t = (block & 3u) * 256u + threadIdx.x;
+    const int cl = (int)(t & 15u) + 16 * (int)((t >> 9) & 1u);
     const int ocl = (int)(t >> 4) & 31;
-    const int64_t blk = t >> 10;                       // channel block * n_ksteps + reduction step
-    const int kstep = (int)(blk % j.n_ksteps);
-    const int oc = (int)(blk / j.n_ksteps) * 32 + ocl;
-    int c, r;
-    bool valid = oc < j.OC;
-    if (j.pack_KW) {                                   // one step per kernel row; slot kw * C + c inside it
-        const int kw = cl / j.pack_C;
-        c = cl - kw * j.pack_C;
-        r = kstep * j.pack_KW + kw;
-        valid = valid && kw < j.pack_KW;
-    } else {
-        r = kstep / j.CB;
-        c = (kstep - r * j.CB) * 32 + cl;
-        valid = valid && c < j.K / j.KHW;
-    }
-    int64_t v = 0;
-    if (valid) v = sample_weight(j, oc, c * j.KHW + r);
-    uint32_t digits = 0;
+    const uint32_t n_blk = (uint32_t)((j.OC + 31) >> 5) * (uint32_t)j.n_ksteps;
+    const uint32_t blk0 = (block >> 2) * kPlaneGroup;
+    uint32_t word[kPlaneGroup];
+    int oc_[kPlaneGroup], k_[kPlaneGroup];
+    bool valid[kPlaneGroup];
 #pragma unroll
-    for (int b = 0; b < kMaxPlanes; ++b) {
-        const int8_t d = (int8_t)(v & 0xFF);           // balanced digit; the last one wraps, which is exact modulo 2^32
-        digits |= (uint32_t)(uint8_t)d << (8 * b);
-        v = (v - d) >> 8;
+    for (int g = 0; g < kPlaneGroup; ++g) {
+        const uint32_t blk = min(blk0 + g, n_blk - 1);     // past the end: the last block again (not stored)
+        uint32_t kstep;
+        const uint32_t ocb = div_mod(blk, (uint32_t)j.n_ksteps, j.inv_ksteps, kstep);
+        const int oc = (int)ocb * 32 + ocl;
+        int c, r;
+        bool ok = oc < j.OC;
+        if (j.pack_KW) {                               // one step per kernel row; slot kw * C + c inside it
+            uint32_t cu;
+            const int kw = (int)div_mod((uint32_t)cl, (uint32_t)j.pack_C, j.inv_pack_C, cu);
+            c = (int)cu;
+            r = (int)kstep * j.pack_KW + kw;
+            ok = ok && kw < j.pack_KW;
+        } else {
+            uint32_t cb;
+            r = (int)div_mod(kstep, (uint32_t)j.CB, j.inv_CB, cb);
+            c = (int)cb * 32 + cl;
+            ok = ok && c < j.C;
+        }
+        oc_[g] = oc;
+        k_[g] = c * j.KHW + r;
+        valid[g] = ok;
+        word[g] = ok ? j.packed[(int64_t)oc * j.K + k_[g]] : kDeadWord;
     }
-    const uint32_t word = quad_transpose_bytes(digits);
     const int plane = (int)(t & 3);
-    if (plane < j.n_planes)
-        *reinterpret_cast<uint32_t*>(j.planes + ((blk * kMaxPlanes + plane) * 64 + ocl + 32 * (cl >> 4)) * 16 + (cl & 12)) = word;
+#pragma unroll
+    for (int g = 0; g < kPlaneGroup; ++g) {
+        int64_t v = valid[g] ? sample_word(j, word[g], oc_[g], k_[g]) : 0;
+        uint32_t digits = 0;
+#pragma unroll
+        for (int b = 0; b < kMaxPlanes; ++b) {
+            const int8_t d = (int8_t)(v & 0xFF);       // balanced digit; the last one wraps, which is exact modulo 2^32
+            digits |= (uint32_t)(uint8_t)d << (8 * b);
+            v = (v - d) >> 8;
+        }
+        const uint32_t out = quad_transpose_bytes(digits);
+        if (plane < j.n_planes && blk0 + g < n_blk)
+            *reinterpret_cast<uint32_t*>(j.planes + (((int64_t)(blk0 + g) * kMaxPlanes + plane) * 64 + ocl + 32 * (cl >> 4)) * 16 +
+                                         (cl & 12)) = out;
+    }
 }
 
 // x [N][C][H][W] -> xt [N][H][C_pad/32][W][32] (zeros in the padding channels).  One workgroup per
@@ -218,19 +254,21 @@ __device__ __forceinline__ void channels_last_tile(const TransposeJob& j, int64_
 }
 
 // The digit planes of several layers in one launch (a network pass samples all its filters at once): job i owns
-// the blocks [first_block[i], first_block[i + 1]).
+// the workgroups [first_block[i], first_block[i + 1]); entries past the last job hold 0xFFFFFFFF.
 constexpr int kMaxBatchJobs = 32;
 struct FilterBatch {
     FilterJob jobs[kMaxBatchJobs];
     unsigned first_block[kMaxBatchJobs + 1];
-    int n;
 };
 
 __global__ void __launch_bounds__(256) k_sample_planes_batch(const FilterBatch b)
 {
+    // the job of this workgroup = number of later jobs' first workgroups it has reached; without a loop over
+    // dependent loads (the table arrives in a few wide scalar loads, the rest is scalar compares)
     int i = 0;
-    while (i + 1 < b.n && blockIdx.x >= b.first_block[i + 1]) ++i;     // uniform over the workgroup
-    sample_planes_thread(b.jobs[i], (int64_t)(blockIdx.x - b.first_block[i]) * 256 + threadIdx.x);
+#pragma unroll
+    for (int k = 1; k < kMaxBatchJobs; ++k) i += (blockIdx.x >= b.first_block[k]) ? 1 : 0;
+    sample_planes_block(b.jobs[i], blockIdx.x - b.first_block[i]);
 }
 
 __global__ void __launch_bounds__(256) k_sample_filter(const FilterJob j)
@@ -244,7 +282,7 @@ __global__ void __launch_bounds__(256) k_shared_prologue(const FilterJob f, cons
 {
     __shared__ int8_t tile[32][64 + 4];
     if (blockIdx.x < filter_blocks) {        // uniform over the workgroup
-        if (f.planes) sample_planes_thread(f, (int64_t)blockIdx.x * 256 + threadIdx.x);
+        if (f.planes) sample_planes_block(f, blockIdx.x);
         else sample_filter_thread(f, (int64_t)blockIdx.x * 256 + threadIdx.x);
     } else if (t.pack_KW)
         row_pack_block(t, (int64_t)(blockIdx.x - filter_blocks));
