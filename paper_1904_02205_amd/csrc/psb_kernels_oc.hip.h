@@ -441,12 +441,13 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
         __syncthreads();
     }
 
+    // No device-scope fence here: on this chip it writes back the XCD's L2, once per workgroup.  None is needed - a
+    // workgroup counts itself out only after its last draw has returned (so the draw has been performed), the words
+    // are only ever touched by device-scope atomics, and the results become visible at the end of the kernel.
     if (threadIdx.x == 0) {
-        __threadfence();
         if (atomicAdd(&sched[1], 1u) == gridDim.x - 1) {   // every workgroup has drawn its last ticket
-            sched[0] = 0;
-            sched[1] = 0;
-            __threadfence();
+            __hip_atomic_store(&sched[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&sched[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
