@@ -283,7 +283,9 @@ int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_co
  * psb_shared_prepare_filters samples the digit planes of n handles in one launch, for S samples and the given
  * (seed, layer_id) of each.  The next shared-filter call on such a handle with the same S, seed and layer_id and
  * no budget map uses them instead of sampling again (once: the call after that samples as usual); any other
- * shared-filter call on the handle discards them.  Handles whose layers do not run on the matrix cores are skipped.  Same results as
+ * shared-filter call on the handle discards them.  Handles whose layers do not run on the matrix cores are skipped.  The call
+ * counts as a layer call on every handle it is given (it writes their workspaces) and must not overlap with other
+ * calls on them.  Same results as
  * without the call.  Errors: NULL, SHAPE (n <= 0), VALUE (S), DEVICE, TOO_LARGE, ALLOC.
  */
 enum { PSB_BLOCKED_IN = 1, PSB_BLOCKED_OUT = 2, PSB_BLOCKED_RES = 4 };
