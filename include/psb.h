@@ -231,7 +231,8 @@ int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, c
  *     x[i] = clamp( rint( g( y[i] [+ r[i]] ) * inv_step ), lo, hi ),   rint: ties to even,
  *     g = max(., 0) if relu != 0 (NaN -> 0), else identity;
  *     r = res_f32[i], or (float)res_i8[i] * res_step (one rounded multiplication); at most one of the two
- *     residual operands may be non-NULL (VALUE otherwise); -128 <= lo <= hi <= 127; n > 0 elements.
+ *     residual operands may be non-NULL (VALUE otherwise); -128 <= lo <= hi <= 127 and inv_step >= 0 (VALUE
+ *     otherwise); n > 0 elements.
  * psb_maxpool2d_i8: NCHW int8 max-pooling; positions in the padding do not take part; needs 2*pad <= kernel
  *     (SHAPE otherwise).  out is [n][c][OH][OW] with the OH/OW rule of psb_conv_geom.
  * psb_global_avgpool_requantize: out[n][c] = clamp( rint( ((float)sum * fl(1/(h*w))) * scale ), lo, hi ),
@@ -249,7 +250,7 @@ int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, c
  * them), which saves their write; where a kernel combines partial sums in the accumulators the library uses
  * scratch memory owned by the handle instead (allocated on first use, grown on demand).
  * Errors: those of the layer call, plus NULL (rq, x_out_dev), VALUE (two residual operands, bad clamp range)
- * and ALLOC. */
+ * (also a negative or NaN inv_step) and ALLOC. */
 typedef struct {
     int32_t relu;                 /* != 0: g = max(., 0)                                */
     float inv_step;

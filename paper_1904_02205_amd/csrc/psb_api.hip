@@ -757,7 +757,7 @@ int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_co
     if (!q || !x_dev || !geom || !rq || !x_out_dev) return PSB_ERR_NULL;
     if (!budget_to_dev && (S <= 0 || S > q->s_max)) return PSB_ERR_VALUE;
     if (rq->res_f32_dev && rq->res_i8_dev) return PSB_ERR_VALUE;
-    if (rq->lo < -128 || rq->hi > 127 || rq->lo > rq->hi) return PSB_ERR_VALUE;
+    if (rq->lo < -128 || rq->hi > 127 || rq->lo > rq->hi || !(rq->inv_step >= 0.0f)) return PSB_ERR_VALUE;
     psb::Requant r;
     std::memset(&r, 0, sizeof(r));
     r.x_out = x_out_dev; r.res_f32 = rq->res_f32_dev; r.res_i8 = rq->res_i8_dev; r.res_step = rq->res_step;
@@ -781,7 +781,7 @@ int psb_conv2d_shared_requant_blocked(const psb_weights_t* q, const int8_t* x_de
         return launch_shared(q, x_dev, geom, S, nullptr, nullptr, seed, layer_id, nullptr, y_dev, mult_dev, bias_dev,
                              (hipStream_t)hip_stream, nullptr, layout & PSB_BLOCKED_IN);
     if (rq->res_f32_dev && rq->res_i8_dev) return PSB_ERR_VALUE;
-    if (rq->lo < -128 || rq->hi > 127 || rq->lo > rq->hi) return PSB_ERR_VALUE;
+    if (rq->lo < -128 || rq->hi > 127 || rq->lo > rq->hi || !(rq->inv_step >= 0.0f)) return PSB_ERR_VALUE;
     psb::Requant r;
     std::memset(&r, 0, sizeof(r));
     r.x_out = x_out_dev; r.res_f32 = rq->res_f32_dev; r.res_i8 = rq->res_i8_dev; r.res_step = rq->res_step;
@@ -854,7 +854,7 @@ int psb_requantize(const float* y_dev, const float* res_f32_dev, const int8_t* r
     if (!y_dev || !x_dev) return PSB_ERR_NULL;
     if (n <= 0) return PSB_ERR_SHAPE;
     if (res_f32_dev && res_i8_dev) return PSB_ERR_VALUE;
-    if (lo < -128 || hi > 127 || lo > hi) return PSB_ERR_VALUE;
+    if (lo < -128 || hi > 127 || lo > hi || !(inv_step >= 0.0f)) return PSB_ERR_VALUE;
     hipStream_t stream = (hipStream_t)hip_stream;
     const uintptr_t bits = (uintptr_t)y_dev | (uintptr_t)res_f32_dev;
     const bool vec = (bits & 15u) == 0 && (((uintptr_t)res_i8_dev | (uintptr_t)x_dev) & 3u) == 0;

@@ -554,7 +554,6 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
             float res[16];
 #pragma unroll
             for (int q = 0; q < 16; ++q) res[q] = 0.0f;
-            const bool has_res = p.rq.res_f32 || p.rq.res_i8;
             if (p.rq.res_f32) {
 #pragma unroll
                 for (int q = 0; q < 16; ++q) {
@@ -597,18 +596,29 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
                     if (p.y) p.y[o_first + dq * plane] = rescaled(q, u);
                 }
             }
+            // The integers of requantize_one() with fewer instructions (32 outputs per lane make this loop a third
+            // of a short layer's time): the bias and the residual are added unconditionally (they are 0.0 when
+            // absent; that can only turn a -0.0 into +0.0, which rounds to the same integer), the ReLU gate and
+            // the clamp are max/min (a NaN ends at lo either way, as inv_step is not negative - checked by the
+            // host), and the conversion adds 1.5 * 2^23, which leaves the two's-complement byte in the low bits.
+            const float floor_t = relu ? 0.0f : -__builtin_huge_valf();
 #pragma unroll
             for (int qq = 0; qq < 4; ++qq) {
-                uint32_t word = 0;
+                uint32_t w[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int q = 4 * qq + i;
-                    const uint32_t u = sum_of(h, q);
-                    const float r = rescaled(q, u);
-                    uint32_t xq = (uint32_t)requantize_one(r, has_res, res[q], relu, p.rq.inv_step, p.rq.lo, p.rq.hi) & 0xFFu;
-                    if (!FULL && oc_first + 8 * qq + i >= p.OC) xq = 0;   // padding channels of the blocked layout
-                    word |= xq << (8 * i);
+                    const int ocl = 8 * qq + 4 * g + i;
+                    float t = __fmul_rn(__fmul_rn(__int2float_rn((int32_t)sum_of(h, q)), s_mult[ocl]), inv_s);
+                    t = __fadd_rn(__fadd_rn(t, s_bias[ocl]), res[q]);
+                    t = __builtin_fmaxf(t, floor_t);
+                    float v = rintf(__fmul_rn(t, p.rq.inv_step));
+                    v = __builtin_fminf(__builtin_fmaxf(v, p.rq.lo), p.rq.hi);
+                    w[i] = __float_as_uint(__fadd_rn(v, 12582912.0f));
+                    if (!FULL && oc_first + 8 * qq + i >= p.OC) w[i] = 0;   // padding channels of the blocked layout
                 }
+                // byte 0 of w[0..3] -> bytes 0..3
+                uint32_t word = __builtin_amdgcn_perm(w[1], w[0], 0x0c0c0400u) | __builtin_amdgcn_perm(w[3], w[2], 0x04000c0cu);
                 if (p.rq.out_blocked) {
                     *reinterpret_cast<uint32_t*>(p.rq.x_out + b_first + 8 * qq) = word;
                 } else if (p.quad_store) {

@@ -58,6 +58,7 @@ def test_blocked_tensors_on_every_side(psb, orc, case):
     acc, _, _ = helpers.oracle_layer(orc, L, qo, shared=True)
     y = orc.rescale(acc, qo.e_min, S=L.S, s_max=L.s_max, mult=mult, bias=bias)
     res = (rng.standard_normal(shape) * 2).astype(np.float32)
+    res.reshape(-1)[:6] = np.array([np.nan, np.inf, -np.inf, -0.0, 1e30, -1e30], np.float32)   # special values
     res8 = rng.integers(-128, 128, size=shape).astype(np.int8)
     inv = float(np.float32(127.0 / 6.0))
     x_plain = torch.from_numpy(L.x).cuda()
@@ -72,7 +73,9 @@ def test_blocked_tensors_on_every_side(psb, orc, case):
     variants = [(dict(), dict(), False),
                 (dict(res_f32=res), dict(res_f32=torch.from_numpy(res).cuda()), False),
                 (dict(res_i8=res8, res_step=np.float32(0.05)), dict(res_step=float(np.float32(0.05))), True),
-                (dict(relu=False, lo=-128, hi=127), dict(relu=False, lo=-128, hi=127), False)]
+                (dict(relu=False, lo=-128, hi=127), dict(relu=False, lo=-128, hi=127), False),
+                (dict(res_f32=res, relu=False, lo=-100, hi=50),
+                 dict(res_f32=torch.from_numpy(res).cuda(), relu=False, lo=-100, hi=50), False)]
     for kw_o, kw_g, with_res8 in variants:
         ref = orc.requantize(y, inv, **kw_o)
         for layout in range(8):

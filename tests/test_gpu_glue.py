@@ -148,6 +148,10 @@ def test_fused_requantisation_equals_layer_then_requantize(psb, orc, shared):
         with pytest.raises(psb.PsbError) as ei:
             psb.conv2d_requant(q, xx, 1.0, **{**dict(S=4), **kw})
         assert ei.value.code == psb.ERR_VALUE
+    for bad in (-1.0, float("nan")):
+        with pytest.raises(psb.PsbError) as ei:
+            psb.conv2d_requant(q, xx, bad, S=4)
+        assert ei.value.code == psb.ERR_VALUE
 
 
 # ------------------------------------------------------------------ the chained network
