@@ -403,7 +403,15 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         int slot = 0;
         const bool timed = profile_begin(stream, &slot);
         if (mfma) {
-            psb::launch_conv_shared_mfma(p, psb::planes_needed(max_shift, n_samples), stream);
+            static const int resident_wgs = [] {
+                if (const char* v = std::getenv("PSB_SHARED_RESIDENT")) { if (std::atoi(v) == 0) return 0; }   // benchmark switch
+                int dev = 0, n = 0;
+                if (hipGetDevice(&dev) != hipSuccess ||
+                    hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+                    n = 256;
+                return 2 * n;
+            }();
+            psb::launch_conv_shared_mfma(p, psb::planes_needed(max_shift, n_samples), resident_wgs, stream);
         } else {
             const dim3 grid((unsigned)((npix + 255) / 256), (unsigned)p.OC);
             hipLaunchKernelGGL(psb::k_conv_shared_direct, grid, dim3(256), 0, stream, p);

@@ -27,6 +27,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "psb_kernels.hip.h"
@@ -341,61 +342,14 @@ __device__ __forceinline__ v4i load_operand(__amdgpu_buffer_rsrc_t rsrc, uint32_
 constexpr int kDepth = 4;
 constexpr int kStageSteps = 8;      // a multiple of kDepth
 
-// What a workgroup does with its sums: add them to the accumulators atomically (masked or split reductions; the
-// rescaling is a separate pass then), store accumulators (and rescaled values), or store requantised activations
-// (and, if asked for, the other two).  A template parameter, so that the unrolled epilogue is straight-line code.
-enum { kOutPartial = 0, kOutAcc = 1, kOutRequant = 2 };
-
-template <int P, int OUT>
-__global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
+// The two pixels of a lane (one per half tile of 32 pixels): image, output position, sample count, whether it takes
+// part, the input position of tap (0, 0) and origin = offset in xt of xt[n][iy0][0][ix0][16 g] modulo 2^32 (only used
+// with an in-image tap added).  Offsets into xt are 32 bits wide (the host keeps the buffer below 2 GB), so that an
+// operand address is the uniform buffer plus one vector register.
+__device__ __forceinline__ void decode_half_tiles(const SharedParams& p, int64_t pix0, int col, int g, int CB, int64_t npix,
+                                                  bool (&live)[2], int (&n_)[2], int (&oy_)[2], int (&ox_)[2],
+                                                  int (&to_)[2], int (&iy0)[2], int (&ix0)[2], uint32_t (&origin)[2])
 {
-    __shared__ v4i a_lds[kStageSteps * P * 64];
-    __shared__ float s_mult[32], s_bias[32];       // rescale factors of this block of channels (read after the loop)
-
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int col = lane & 31, g = lane >> 5;
-    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
-    // Workgroups are dealt to the 8 XCDs round-robin by their index; each XCD has its own L2.  Renumber them so
-    // that every XCD works on one contiguous eighth of the pixels and its L2 only has to hold that part of the input.
-    // (The launcher rounds the grid up to a multiple of 8; workgroups past the last tile have no live pixel.)
-    const unsigned per_xcd = gridDim.x >> 3;
-    const unsigned wg = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-    const int64_t pix0 = ((int64_t)wg * 4 + wave) * 64;
-    const int ocb = blockIdx.y;
-
-    const int CB = p.C_pad >> 5;
-    const int n_steps = p.tKH * p.tKW * CB;
-    // this workgroup's part of the reduction
-    const int per_split = (n_steps + p.ksplit - 1) / p.ksplit;
-    const int s_begin = (int)blockIdx.z * per_split;
-    const int s_end = min(n_steps, s_begin + per_split);
-    const int8_t* wblock = p.planes + (int64_t)ocb * p.n_ksteps * (kMaxPlanes * kPlaneStride);
-
-    // weights: operand i of a chunk (i = (step * P + plane) * 64 + lane) is fetched by thread i mod 256; its byte
-    // offset inside the chunk is fixed.  A chunk may reach past the last step: the buffer is padded by one chunk
-    // (those operands are staged but never multiplied).
-    constexpr int kStageRegs = kStageSteps * P * 64 / 256;
-    v4i stage[kStageRegs];
-    uint32_t woff[kStageRegs];
-#pragma unroll
-    for (int r = 0; r < kStageRegs; ++r) {
-        const int i = r * 256 + (int)threadIdx.x;
-        woff[r] = (uint32_t)((((i / (P * 64)) * kMaxPlanes + (i >> 6) % P) * 64 + (i & 63)) * 16);
-    }
-    auto fetch_weights = [&](int s0) {
-        const int8_t* chunk = wblock + (int64_t)s0 * (kMaxPlanes * kPlaneStride);      // uniform
-#pragma unroll
-        for (int r = 0; r < kStageRegs; ++r) stage[r] = *reinterpret_cast<const v4i*>(chunk + woff[r]);
-    };
-
-    fetch_weights(s_begin);          // first of all: nothing below depends on it until the first barrier
-
-    bool live[2];
-    int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
-    // Offsets into xt are 32 bits wide (the host keeps the buffer below 4 GB), so that an operand address is the
-    // uniform base pointer plus one vector register.
-    uint32_t origin[2];        // offset of xt[n][iy0][0][ix0][16 g] modulo 2^32; only used with an in-image tap added
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int64_t pix = pix0 + 32 * h + col;
@@ -410,93 +364,20 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
         ix0[h] = ox_[h] * p.t_stride_w - p.t_pad_w;
         origin[h] = ((uint32_t)(n_[h] * p.tH + iy0[h]) * (uint32_t)(CB * p.tW) + (uint32_t)ix0[h]) * 32u + 16u * (uint32_t)g;
     }
-    // a wave without any pixel that takes part still helps to stage the weights (and keeps the barriers whole)
-    const bool active = __ballot(live[0] || live[1]) != 0ull;
+}
 
-    v16i acc[2][P];
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int b = 0; b < P; ++b)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
+// Values of the OUT template parameter (explained at the layer kernel).
+enum { kOutPartial = 0, kOutAcc = 1, kOutRequant = 2 };
 
-    const uint32_t cb_stride = (uint32_t)p.tW * 32u;            // bytes between the channel blocks of one pixel
-    const uint32_t row_stride = (uint32_t)CB * cb_stride;       // ... between the rows of one image
-    const __amdgpu_buffer_rsrc_t xt_rsrc = operand_buffer(p.xt, p.xt_bytes);
-    // activations: load cursor = the reduction step whose operands are requested next (all of it uniform)
-    int l_step = min(s_begin, n_steps - 1);
-    int l_cb = l_step % CB, l_kw = (l_step / CB) % p.tKW, l_kh = (l_step / CB) / p.tKW;
-    uint32_t l_tap = (uint32_t)l_kh * row_stride + (uint32_t)l_kw * 32u;   // offset of tap (l_kh, l_kw) from the origin
-    uint32_t l_cboff = (uint32_t)l_cb * cb_stride;
-    uint32_t tap_off[2];
-    auto place_tap = [&]() {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int iy = iy0[h] + l_kh, ix = ix0[h] + l_kw;
-            const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
-            tap_off[h] = ok ? origin[h] + l_tap : kOutOfRange;
-        }
-    };
-    place_tap();
-    v4i opb[kDepth][2];
-    auto request = [&](int slot) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) opb[slot][h] = load_operand(xt_rsrc, tap_off[h], l_cboff);
-        if (l_step + 1 < n_steps) {                  // past the end the last step is simply requested again
-            ++l_step;
-            l_cboff += cb_stride;
-            if (++l_cb == CB) {
-                l_cb = 0;
-                l_cboff = 0;
-                l_tap += 32u;
-                if (++l_kw == p.tKW) { l_kw = 0; ++l_kh; l_tap += row_stride - (uint32_t)p.tKW * 32u; }
-                place_tap();
-            }
-        }
-    };
-
-    if (active) {
-#pragma unroll
-        for (int d = 0; d < kDepth; ++d) request(d);
-    }
-    if (OUT != kOutPartial && threadIdx.x < 32) {    // visible to every wave after the loop's first barrier
-        const int oc = ocb * 32 + (int)threadIdx.x;
-        s_mult[threadIdx.x] = (p.mult && oc < p.OC) ? p.mult[oc] : p.default_mult;
-        s_bias[threadIdx.x] = (p.bias && oc < p.OC) ? p.bias[oc] : 0.0f;
-    }
-    for (int s0 = s_begin; s0 < s_end; s0 += kStageSteps) {
-        __syncthreads();                             // the previous chunk has been consumed by every wave
-#pragma unroll
-        for (int r = 0; r < kStageRegs; ++r) a_lds[r * 256 + threadIdx.x] = stage[r];
-        __syncthreads();
-        if (s0 + kStageSteps < s_end) fetch_weights(s0 + kStageSteps);       // uniform over the workgroup
-        if (active) {
-            // the weight operands of step ks + 1 are read from LDS while the matrix instructions of step ks run
-            v4i a[2][P];
-#pragma unroll
-            for (int b = 0; b < P; ++b) a[0][b] = a_lds[b * 64 + lane];
-#pragma unroll
-            for (int ks = 0; ks < kStageSteps; ++ks) {
-                const int d = ks % kDepth;
-                if (ks + 1 < kStageSteps) {
-#pragma unroll
-                    for (int b = 0; b < P; ++b) a[(ks + 1) & 1][b] = a_lds[((ks + 1) * P + b) * 64 + lane];
-                }
-                if (s0 + ks < s_end) {               // wave-uniform
-#pragma unroll
-                    for (int b = 0; b < P; ++b) {
-                        acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][0], acc[0][b], 0, 0, 0);
-                        acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][1], acc[1][b], 0, 0, 0);
-                    }
-                }
-                request(d);     // unconditional (past the end: the last step again), so that the number of
-                                // loads in flight is the same on every path and no wait is longer than needed
-            }
-        }
-    }
-    if (!active) return;
-
+// The end of a wave's tile: what is done with the sums of its 32 channels x 64 pixels (see the OUT values below).
+// acc[h][b]: digit plane b of half tile h; live / n_ / oy_ / ox_ / to_: this lane's pixel in each half tile.
+template <int P, int OUT>
+__device__ __forceinline__ void tile_epilogue(const SharedParams& p, v16i (&acc)[2][P], const bool (&live)[2],
+                                              const int (&n_)[2], const int (&oy_)[2], const int (&ox_)[2],
+                                              const int (&to_)[2], int ocb, int lane, const float* s_mult,
+                                              const float* s_bias)
+{
+    const int g = lane >> 5;
     // result row (channel) of register q: 8*(q/4) + 4*(lane/32) + q%4; column (pixel) = lane%32
     const int64_t plane = (int64_t)p.OH * p.OW;
     auto sum_of = [&](int h, int q) {                  // the digit planes recombined
@@ -638,6 +519,256 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     else finish(std::false_type{});
 }
 
+// What a workgroup does with its sums: add them to the accumulators atomically (masked or split reductions; the
+// rescaling is a separate pass then), store accumulators (and rescaled values), or store requantised activations
+// (and, if asked for, the other two).  A template parameter, so that the unrolled epilogue is straight-line code.
+
+template <int P, int OUT>
+__global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
+{
+    __shared__ v4i a_lds[kStageSteps * P * 64];
+    __shared__ float s_mult[32], s_bias[32];       // rescale factors of this block of channels (read after the loop)
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int col = lane & 31, g = lane >> 5;
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    // Workgroups are dealt to the 8 XCDs round-robin by their index; each XCD has its own L2.  Renumber them so
+    // that every XCD works on one contiguous eighth of the pixels and its L2 only has to hold that part of the input.
+    // (The launcher rounds the grid up to a multiple of 8; workgroups past the last tile have no live pixel.)
+    const unsigned per_xcd = gridDim.x >> 3;
+    const unsigned wg = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    const int64_t pix0 = ((int64_t)wg * 4 + wave) * 64;
+    const int ocb = blockIdx.y;
+
+    const int CB = p.C_pad >> 5;
+    const int n_steps = p.tKH * p.tKW * CB;
+    // this workgroup's part of the reduction
+    const int per_split = (n_steps + p.ksplit - 1) / p.ksplit;
+    const int s_begin = (int)blockIdx.z * per_split;
+    const int s_end = min(n_steps, s_begin + per_split);
+    const int8_t* wblock = p.planes + (int64_t)ocb * p.n_ksteps * (kMaxPlanes * kPlaneStride);
+
+    // weights: operand i of a chunk (i = (step * P + plane) * 64 + lane) is fetched by thread i mod 256; its byte
+    // offset inside the chunk is fixed.  A chunk may reach past the last step: the buffer is padded by one chunk
+    // (those operands are staged but never multiplied).
+    constexpr int kStageRegs = kStageSteps * P * 64 / 256;
+    v4i stage[kStageRegs];
+    uint32_t woff[kStageRegs];
+#pragma unroll
+    for (int r = 0; r < kStageRegs; ++r) {
+        const int i = r * 256 + (int)threadIdx.x;
+        woff[r] = (uint32_t)((((i / (P * 64)) * kMaxPlanes + (i >> 6) % P) * 64 + (i & 63)) * 16);
+    }
+    auto fetch_weights = [&](int s0) {
+        const int8_t* chunk = wblock + (int64_t)s0 * (kMaxPlanes * kPlaneStride);      // uniform
+#pragma unroll
+        for (int r = 0; r < kStageRegs; ++r) stage[r] = *reinterpret_cast<const v4i*>(chunk + woff[r]);
+    };
+
+    fetch_weights(s_begin);          // first of all: nothing below depends on it until the first barrier
+
+    bool live[2];
+    int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
+    uint32_t origin[2];
+    decode_half_tiles(p, pix0, col, g, CB, npix, live, n_, oy_, ox_, to_, iy0, ix0, origin);
+    // a wave without any pixel that takes part still helps to stage the weights (and keeps the barriers whole)
+    const bool active = __ballot(live[0] || live[1]) != 0ull;
+
+    v16i acc[2][P];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int b = 0; b < P; ++b)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
+
+    const uint32_t cb_stride = (uint32_t)p.tW * 32u;            // bytes between the channel blocks of one pixel
+    const uint32_t row_stride = (uint32_t)CB * cb_stride;       // ... between the rows of one image
+    const __amdgpu_buffer_rsrc_t xt_rsrc = operand_buffer(p.xt, p.xt_bytes);
+    // activations: load cursor = the reduction step whose operands are requested next (all of it uniform)
+    int l_step = min(s_begin, n_steps - 1);
+    int l_cb = l_step % CB, l_kw = (l_step / CB) % p.tKW, l_kh = (l_step / CB) / p.tKW;
+    uint32_t l_tap = (uint32_t)l_kh * row_stride + (uint32_t)l_kw * 32u;   // offset of tap (l_kh, l_kw) from the origin
+    uint32_t l_cboff = (uint32_t)l_cb * cb_stride;
+    uint32_t tap_off[2];
+    auto place_tap = [&]() {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int iy = iy0[h] + l_kh, ix = ix0[h] + l_kw;
+            const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
+            tap_off[h] = ok ? origin[h] + l_tap : kOutOfRange;
+        }
+    };
+    place_tap();
+    v4i opb[kDepth][2];
+    auto request = [&](int slot) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) opb[slot][h] = load_operand(xt_rsrc, tap_off[h], l_cboff);
+        if (l_step + 1 < n_steps) {                  // past the end the last step is simply requested again
+            ++l_step;
+            l_cboff += cb_stride;
+            if (++l_cb == CB) {
+                l_cb = 0;
+                l_cboff = 0;
+                l_tap += 32u;
+                if (++l_kw == p.tKW) { l_kw = 0; ++l_kh; l_tap += row_stride - (uint32_t)p.tKW * 32u; }
+                place_tap();
+            }
+        }
+    };
+
+    if (active) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) request(d);
+    }
+    if (OUT != kOutPartial && threadIdx.x < 32) {    // visible to every wave after the loop's first barrier
+        const int oc = ocb * 32 + (int)threadIdx.x;
+        s_mult[threadIdx.x] = (p.mult && oc < p.OC) ? p.mult[oc] : p.default_mult;
+        s_bias[threadIdx.x] = (p.bias && oc < p.OC) ? p.bias[oc] : 0.0f;
+    }
+    for (int s0 = s_begin; s0 < s_end; s0 += kStageSteps) {
+        __syncthreads();                             // the previous chunk has been consumed by every wave
+#pragma unroll
+        for (int r = 0; r < kStageRegs; ++r) a_lds[r * 256 + threadIdx.x] = stage[r];
+        __syncthreads();
+        if (s0 + kStageSteps < s_end) fetch_weights(s0 + kStageSteps);       // uniform over the workgroup
+        if (active) {
+            // the weight operands of step ks + 1 are read from LDS while the matrix instructions of step ks run
+            v4i a[2][P];
+#pragma unroll
+            for (int b = 0; b < P; ++b) a[0][b] = a_lds[b * 64 + lane];
+#pragma unroll
+            for (int ks = 0; ks < kStageSteps; ++ks) {
+                const int d = ks % kDepth;
+                if (ks + 1 < kStageSteps) {
+#pragma unroll
+                    for (int b = 0; b < P; ++b) a[(ks + 1) & 1][b] = a_lds[((ks + 1) * P + b) * 64 + lane];
+                }
+                if (s0 + ks < s_end) {               // wave-uniform
+#pragma unroll
+                    for (int b = 0; b < P; ++b) {
+                        acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][0], acc[0][b], 0, 0, 0);
+                        acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][1], acc[1][b], 0, 0, 0);
+                    }
+                }
+                request(d);     // unconditional (past the end: the last step again), so that the number of
+                                // loads in flight is the same on every path and no wait is longer than needed
+            }
+        }
+    }
+    if (!active) return;
+
+    tile_epilogue<P, OUT>(p, acc, live, n_, oy_, ox_, to_, ocb, lane, s_mult, s_bias);
+}
+
+// Short reductions (all weight operands of a channel block fit LDS: the first layer of a network, 3x3 layers on 64
+// channels, 1x1 shortcuts, classifiers): a persistent variant.  A workgroup stages the whole block once and then walks
+// over pixel tiles, `columns` apart; inside the walk there is no barrier and no staging, the kernel arguments and
+// the rescale factors are read once, and the four waves run independently of each other.  Unsplit, unmasked calls
+// only.  Dynamic LDS: n_steps * P * 1024 bytes.  gridDim.x is a multiple of 8, columns = the grid the plain kernel
+// would get.
+template <int P, int OUT>
+__global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const SharedParams p, unsigned columns)
+{
+    extern __shared__ v4i a_all[];                 // [n_steps][P][64]
+    __shared__ float s_mult[32], s_bias[32];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int col = lane & 31, g = lane >> 5;
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int ocb = blockIdx.y;
+    const int CB = p.C_pad >> 5;
+    const int n_steps = p.tKH * p.tKW * CB;
+    const int8_t* wblock = p.planes + (int64_t)ocb * p.n_ksteps * (kMaxPlanes * kPlaneStride);
+    for (int i = threadIdx.x; i < n_steps * P * 64; i += 256) {
+        const int step = i / (P * 64), b = (i >> 6) % P;
+        a_all[i] = *reinterpret_cast<const v4i*>(wblock + ((int64_t)(step * kMaxPlanes + b) * 64 + (i & 63)) * 16);
+    }
+    if (threadIdx.x < 32) {
+        const int oc = ocb * 32 + (int)threadIdx.x;
+        s_mult[threadIdx.x] = (p.mult && oc < p.OC) ? p.mult[oc] : p.default_mult;
+        s_bias[threadIdx.x] = (p.bias && oc < p.OC) ? p.bias[oc] : 0.0f;
+    }
+    __syncthreads();
+
+    const uint32_t cb_stride = (uint32_t)p.tW * 32u;
+    const uint32_t row_stride = (uint32_t)CB * cb_stride;
+    const __amdgpu_buffer_rsrc_t xt_rsrc = operand_buffer(p.xt, p.xt_bytes);
+    const unsigned per_xcd = columns >> 3;         // each XCD keeps one contiguous eighth of the pixels
+    for (unsigned v = blockIdx.x; v < columns; v += gridDim.x) {
+        const unsigned wg = (v & 7u) * per_xcd + (v >> 3);
+        const int64_t pix0 = ((int64_t)wg * 4 + wave) * 64;
+        bool live[2];
+        int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
+        uint32_t origin[2];
+        decode_half_tiles(p, pix0, col, g, CB, npix, live, n_, oy_, ox_, to_, iy0, ix0, origin);
+        if (__ballot(live[0] || live[1]) == 0ull) continue;      // wave-uniform; no barrier below
+
+        v16i acc[2][P];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int b = 0; b < P; ++b)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
+
+        // load cursor, as in the plain kernel
+        int l_step = 0, l_cb = 0, l_kw = 0, l_kh = 0;
+        uint32_t l_tap = 0, l_cboff = 0;
+        uint32_t tap_off[2];
+        auto place_tap = [&]() {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int iy = iy0[h] + l_kh, ix = ix0[h] + l_kw;
+                const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
+                tap_off[h] = ok ? origin[h] + l_tap : kOutOfRange;
+            }
+        };
+        place_tap();
+        v4i opb[kDepth][2];
+        auto request = [&](int slot) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) opb[slot][h] = load_operand(xt_rsrc, tap_off[h], l_cboff);
+            if (l_step + 1 < n_steps) {              // past the end the last step is simply requested again
+                ++l_step;
+                l_cboff += cb_stride;
+                if (++l_cb == CB) {
+                    l_cb = 0;
+                    l_cboff = 0;
+                    l_tap += 32u;
+                    if (++l_kw == p.tKW) { l_kw = 0; ++l_kh; l_tap += row_stride - (uint32_t)p.tKW * 32u; }
+                    place_tap();
+                }
+            }
+        };
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) request(d);
+
+        v4i a[2][P];
+#pragma unroll
+        for (int b = 0; b < P; ++b) a[0][b] = a_all[b * 64 + lane];
+        for (int s0 = 0; s0 < n_steps; s0 += kDepth) {
+#pragma unroll
+            for (int ks = 0; ks < kDepth; ++ks) {
+                const int nxt = min(s0 + ks + 1, n_steps - 1);       // the operands of the next step, one step ahead
+#pragma unroll
+                for (int b = 0; b < P; ++b) a[(ks + 1) & 1][b] = a_all[(nxt * P + b) * 64 + lane];
+                if (s0 + ks < n_steps) {             // wave-uniform
+#pragma unroll
+                    for (int b = 0; b < P; ++b) {
+                        acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[ks][0], acc[0][b], 0, 0, 0);
+                        acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[ks][1], acc[1][b], 0, 0, 0);
+                    }
+                }
+                request(ks);
+            }
+        }
+        tile_epilogue<P, OUT>(p, acc, live, n_, oy_, ox_, to_, ocb, lane, s_mult, s_bias);
+    }
+}
+
 // Any layer shape: one output pixel per lane, one output channel per workgroup row.
 __global__ void __launch_bounds__(256) k_conv_shared_direct(const SharedParams p)
 {
@@ -696,11 +827,38 @@ inline void launch_conv_shared_mfma_out(const SharedParams& p, int planes, dim3 
     }
 }
 
-inline void launch_conv_shared_mfma(const SharedParams& p, int planes, hipStream_t stream)
+template <int OUT>
+inline void launch_conv_shared_mfma_resident(const SharedParams& p, int planes, dim3 grid, unsigned columns, size_t lds,
+                                             hipStream_t stream)
+{
+    const dim3 block(256);
+    switch (planes) {
+        case 1: hipLaunchKernelGGL((k_conv_shared_mfma_resident<1, OUT>), grid, block, lds, stream, p, columns); break;
+        case 2: hipLaunchKernelGGL((k_conv_shared_mfma_resident<2, OUT>), grid, block, lds, stream, p, columns); break;
+        case 3: hipLaunchKernelGGL((k_conv_shared_mfma_resident<3, OUT>), grid, block, lds, stream, p, columns); break;
+        default: hipLaunchKernelGGL((k_conv_shared_mfma_resident<4, OUT>), grid, block, lds, stream, p, columns); break;
+    }
+}
+
+// resident_wgs: workgroups the chip holds at once with this kernel (two per CU), or 0 to rule the persistent variant out.
+inline void launch_conv_shared_mfma(const SharedParams& p, int planes, int resident_wgs, hipStream_t stream)
 {
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
     const int64_t tiles = (npix + 255) / 256;
-    const dim3 grid((unsigned)((tiles + 7) / 8 * 8), (unsigned)((p.OC + 31) / 32), (unsigned)p.ksplit);   // 8 XCDs
+    const unsigned columns = (unsigned)((tiles + 7) / 8 * 8);                        // 8 XCDs
+    const unsigned n_ocb = (unsigned)((p.OC + 31) / 32);
+    const int n_steps = p.tKH * p.tKW * (p.C_pad >> 5);
+    const size_t lds = (size_t)n_steps * planes * kPlaneStride;
+    // worth it when a workgroup gets more than one tile: staging the whole block before the first matrix instruction
+    // costs more than the chunked start of the plain kernel
+    const unsigned fit = std::max(8u, (unsigned)std::max(resident_wgs, 0) / n_ocb / 8u * 8u);
+    if (resident_wgs > 0 && !p.masked && p.ksplit == 1 && lds <= 65536 && columns > fit) {
+        const dim3 grid(fit, n_ocb);
+        if (p.rq.x_out) launch_conv_shared_mfma_resident<kOutRequant>(p, planes, grid, columns, lds, stream);
+        else launch_conv_shared_mfma_resident<kOutAcc>(p, planes, grid, columns, lds, stream);
+        return;
+    }
+    const dim3 grid(columns, n_ocb, (unsigned)p.ksplit);
     if (p.masked || p.ksplit > 1) launch_conv_shared_mfma_out<kOutPartial>(p, planes, grid, stream);
     else if (p.rq.x_out) launch_conv_shared_mfma_out<kOutRequant>(p, planes, grid, stream);
     else launch_conv_shared_mfma_out<kOutAcc>(p, planes, grid, stream);

@@ -40,6 +40,7 @@ CASES = [
     dict(n=2, c=64, oc=64, hw=8, k=3, stride=2, pad=1, S=4),        # whole blocks, OH*OW a multiple of 4
     dict(n=1, c=256, oc=64, hw=6, k=3, pad=1, S=8),                 # split reduction: separate rescale pass
     dict(n=3, c=33, oc=32, hw=(5, 8), k=1, S=16),                   # 1x1, one channel in the second block
+    dict(n=1, c=32, oc=40, hw=(260, 264), k=3, pad=1, S=4),         # many pixel tiles: the persistent kernel variant
 ]
 
 

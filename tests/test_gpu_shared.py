@@ -57,6 +57,9 @@ def _cases():
     c.append(("deep_linear", _layer(rng, 3, 2048, 40, 1, 1, S=4, xkind="u4", std=0.02), both))     # split 4 ways
     c.append(("row_packed_5x5_c6", _layer(rng, 2, 6, 20, (13, 17), 5, stride=2, pad=2, S=8, xkind="signed"), both))
     c.append(("row_packed_1x3_c10", _layer(rng, 1, 10, 8, (4, 9), (1, 3), pad=(0, 1), S=4), both))
+    # more pixel tiles than workgroups fit the chip, short reduction: the persistent variant of the matrix-core kernel
+    c.append(("many_tiles_short_reduction", _layer(rng, 1, 16, 40, (370, 372), 3, pad=1, S=4), (0,)))
+    c.append(("many_tiles_row_packed", _layer(rng, 1, 3, 33, (530, 540), 5, stride=2, pad=2, S=4, xkind="signed"), (0,)))
     c.append(("grouped", _layer(rng, 2, 8, 12, 7, 3, pad=1, groups=4, S=8), (0,)))
     c.append(("depthwise", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), (0,)))
     return c
