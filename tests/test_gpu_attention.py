@@ -66,13 +66,15 @@ def test_attention_closed_forms(psb, orc):
         assert ei.value.code == psb.ERR_VALUE
 
 
-def test_two_pass_network(psb, orc):
+@pytest.mark.parametrize("shared", [False, True])
+def test_two_pass_network(psb, orc, shared):
     """psb8/16: low-precision pass, mask, mixed-precision pass.  Up to the mask both sides agree bit for bit;
-    where no pixel lies in the tie band the masks agree and so do the final logits."""
+    where no pixel lies in the tie band the masks agree and so do the final logits.  (shared: the first pass runs
+    as one chain on the GPU, the second - with its budget map - layer by layer.)"""
     from paper_1904_02205_amd import network
     net = rs.resnet18(batch=2, hw=96, width=32, classes=10)
-    ref_logits, ref_budget, ent, mean = oracle_network.OracleResNet18(orc, net).forward_attention(8, 16)
-    logits, budget = network.ResNet18(net).forward_attention(8, 16)
+    ref_logits, ref_budget, ent, mean = oracle_network.OracleResNet18(orc, net).forward_attention(8, 16, shared=shared)
+    logits, budget = network.ResNet18(net).forward_attention(8, 16, shared=shared)
     clear = np.abs(ent - mean[:, None, None]) > TIE_BAND
     assert np.array_equal(budget.cpu().numpy()[clear], ref_budget[clear])
     assert set(np.unique(ref_budget)) == {8, 16}

@@ -183,6 +183,7 @@ def test_network_end_to_end(psb, orc):
     assert not np.array_equal(a, b)
     _compare(psb, orc, net, S=8, shared=True, chain=False)         # layer by layer
     _compare(psb, orc, net, prob_bits=4, S=16)
+    _compare(psb, orc, net, prob_bits=4, S=16, shared=True)
 
 
 def test_network_with_a_budget_map_on_all_layers(psb, orc):
