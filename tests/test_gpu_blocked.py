@@ -158,3 +158,53 @@ def test_blocked_call_errors(psb):
     rc = lib.psb_conv2d_shared_requant_blocked(q._h, ctypes.c_void_p(xb.data_ptr()), ctypes.byref(g), 8, 0, 0, None,
                                                None, None, None, None, 0, None)
     assert rc == psb.ERR_NULL
+
+
+def _random_blocked_case(i):
+    rng = np.random.default_rng(9100 + i)
+    kh, kw = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+    c = int(rng.integers(max(1, 32 // kw + 1), 100))          # more than 32 / kw channels: the layer can take blocked input
+    oc = int(rng.integers(1, 100))
+    sh, sw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+    ph, pw = int(rng.integers(0, kh)), int(rng.integers(0, kw))
+    h = max(int(rng.integers(1, 14)), kh - 2 * ph)
+    w = max(int(rng.integers(1, 14)), kw - 2 * pw)
+    n = int(rng.integers(1, 4))
+    S = int(rng.integers(1, 17))
+    return dict(n=n, c=c, oc=oc, hw=(h, w), k=(kh, kw), stride=(sh, sw), pad=(ph, pw), S=S, s_max=16,
+                xkind=str(rng.choice(["relu", "signed"])), seed=int(rng.integers(0, 2 ** 40)),
+                layer_id=int(rng.integers(0, 2 ** 31)))
+
+
+@pytest.mark.parametrize("i", range(24))
+def test_random_blocked_layer(psb, orc, i):
+    """Seeded random shapes, every combination of blocked and plain tensors, int8 residual."""
+    import torch
+    case = _random_blocked_case(i)
+    print(f"[blocked {i}] {case}", flush=True)
+    rng = np.random.default_rng(9500 + i)
+    L = _layer(rng, **case)
+    oc = L.w.shape[0]
+    oh, ow = L.out_hw
+    shape = (L.x.shape[0], oc, oh, ow)
+    mult = (rng.uniform(0.5, 2.0, size=oc) * 2.0 ** -6).astype(np.float32)
+    bias = rng.standard_normal(oc).astype(np.float32)
+    qo, qg = helpers.oracle_quantize(orc, L), helpers.gpu_quantize(psb, L)
+    acc, _, _ = helpers.oracle_layer(orc, L, qo, shared=True)
+    y = orc.rescale(acc, qo.e_min, S=L.S, s_max=L.s_max, mult=mult, bias=bias)
+    res8 = rng.integers(-128, 128, size=shape).astype(np.int8)
+    inv, step = float(np.float32(127.0 / 6.0)), np.float32(0.05)
+    relu = bool(i % 2)
+    lo, hi = (0, 127) if relu else (-128, 127)
+    ref = orc.requantize(y, inv, res_i8=res8, res_step=step, relu=relu, lo=lo, hi=hi)
+    x_plain = torch.from_numpy(L.x).cuda()
+    x_blocked = torch.from_numpy(to_blocked(L.x, -3)).cuda()
+    for layout in range(8):
+        r8 = to_blocked(res8, 9) if layout & psb.BLOCKED_RES else res8
+        got = psb.conv2d_shared_requant_blocked(
+            qg, x_blocked if layout & psb.BLOCKED_IN else x_plain, L.x.shape, inv, L.S, stride=L.stride, pad=L.pad,
+            seed=L.seed, layer_id=L.layer_id, mult=torch.from_numpy(mult).cuda(), bias=torch.from_numpy(bias).cuda(),
+            res_i8=torch.from_numpy(r8).cuda(), res_step=float(step), relu=relu, lo=lo, hi=hi, layout=layout).cpu().numpy()
+        if layout & psb.BLOCKED_OUT:
+            got = from_blocked(got, oc)
+        assert np.array_equal(got, ref), (case, layout)
