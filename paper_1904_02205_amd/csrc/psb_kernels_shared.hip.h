@@ -342,6 +342,57 @@ __device__ __forceinline__ v4i load_operand(__amdgpu_buffer_rsrc_t rsrc, uint32_
 constexpr int kDepth = 4;
 constexpr int kStageSteps = 8;      // a multiple of kDepth
 
+// Load cursor of a wave: the reduction step whose activation operands are requested next.  Steps are ordered
+// (kh, kw, block of 32 channels); step, position and the two offsets are uniform over the wave, tap_off (per lane
+// and half tile: where this tap of the lane's pixel lies in xt, or out of range for a tap in the padding) is not.
+struct TapCursor {
+    int step, cb, kw, kh;
+    uint32_t tap;          // offset of tap (kh, kw) from a pixel's origin
+    uint32_t cboff;        // offset of channel block cb from the tap
+    uint32_t tap_off[2];
+
+    __device__ __forceinline__ void place(const SharedParams& p, const bool (&live)[2], const int (&iy0)[2],
+                                          const int (&ix0)[2], const uint32_t (&origin)[2])
+    {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int iy = iy0[h] + kh, ix = ix0[h] + kw;
+            const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
+            tap_off[h] = ok ? origin[h] + tap : kOutOfRange;
+        }
+    }
+    // start at reduction step s (CB channel blocks per tap; cb_stride / row_stride: bytes between the channel blocks
+    // of a pixel / the rows of an image)
+    __device__ __forceinline__ void start(const SharedParams& p, int s, int CB, uint32_t cb_stride, uint32_t row_stride,
+                                          const bool (&live)[2], const int (&iy0)[2], const int (&ix0)[2],
+                                          const uint32_t (&origin)[2])
+    {
+        step = s;
+        cb = s % CB;
+        kw = (s / CB) % p.tKW;
+        kh = (s / CB) / p.tKW;
+        tap = (uint32_t)kh * row_stride + (uint32_t)kw * 32u;
+        cboff = (uint32_t)cb * cb_stride;
+        place(p, live, iy0, ix0, origin);
+    }
+    // one step on; past the last step it stays where it is (that step is then simply requested again)
+    __device__ __forceinline__ void advance(const SharedParams& p, int n_steps, int CB, uint32_t cb_stride,
+                                            uint32_t row_stride, const bool (&live)[2], const int (&iy0)[2],
+                                            const int (&ix0)[2], const uint32_t (&origin)[2])
+    {
+        if (step + 1 >= n_steps) return;
+        ++step;
+        cboff += cb_stride;
+        if (++cb == CB) {
+            cb = 0;
+            cboff = 0;
+            tap += 32u;
+            if (++kw == p.tKW) { kw = 0; ++kh; tap += row_stride - (uint32_t)p.tKW * 32u; }
+            place(p, live, iy0, ix0, origin);
+        }
+    }
+};
+
 // The two pixels of a lane (one per half tile of 32 pixels): image, output position, sample count, whether it takes
 // part, the input position of tap (0, 0) and origin = offset in xt of xt[n][iy0][0][ix0][16 g] modulo 2^32 (only used
 // with an in-image tap added).  Offsets into xt are 32 bits wide (the host keeps the buffer below 2 GB), so that an
@@ -586,36 +637,13 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     const uint32_t cb_stride = (uint32_t)p.tW * 32u;            // bytes between the channel blocks of one pixel
     const uint32_t row_stride = (uint32_t)CB * cb_stride;       // ... between the rows of one image
     const __amdgpu_buffer_rsrc_t xt_rsrc = operand_buffer(p.xt, p.xt_bytes);
-    // activations: load cursor = the reduction step whose operands are requested next (all of it uniform)
-    int l_step = min(s_begin, n_steps - 1);
-    int l_cb = l_step % CB, l_kw = (l_step / CB) % p.tKW, l_kh = (l_step / CB) / p.tKW;
-    uint32_t l_tap = (uint32_t)l_kh * row_stride + (uint32_t)l_kw * 32u;   // offset of tap (l_kh, l_kw) from the origin
-    uint32_t l_cboff = (uint32_t)l_cb * cb_stride;
-    uint32_t tap_off[2];
-    auto place_tap = [&]() {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int iy = iy0[h] + l_kh, ix = ix0[h] + l_kw;
-            const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
-            tap_off[h] = ok ? origin[h] + l_tap : kOutOfRange;
-        }
-    };
-    place_tap();
+    TapCursor cur;
+    cur.start(p, min(s_begin, n_steps - 1), CB, cb_stride, row_stride, live, iy0, ix0, origin);
     v4i opb[kDepth][2];
     auto request = [&](int slot) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) opb[slot][h] = load_operand(xt_rsrc, tap_off[h], l_cboff);
-        if (l_step + 1 < n_steps) {                  // past the end the last step is simply requested again
-            ++l_step;
-            l_cboff += cb_stride;
-            if (++l_cb == CB) {
-                l_cb = 0;
-                l_cboff = 0;
-                l_tap += 32u;
-                if (++l_kw == p.tKW) { l_kw = 0; ++l_kh; l_tap += row_stride - (uint32_t)p.tKW * 32u; }
-                place_tap();
-            }
-        }
+        for (int h = 0; h < 2; ++h) opb[slot][h] = load_operand(xt_rsrc, cur.tap_off[h], cur.cboff);
+        cur.advance(p, n_steps, CB, cb_stride, row_stride, live, iy0, ix0, origin);
     };
 
     if (active) {
@@ -714,34 +742,13 @@ __global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const Shar
 #pragma unroll
                 for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
 
-        // load cursor, as in the plain kernel
-        int l_step = 0, l_cb = 0, l_kw = 0, l_kh = 0;
-        uint32_t l_tap = 0, l_cboff = 0;
-        uint32_t tap_off[2];
-        auto place_tap = [&]() {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int iy = iy0[h] + l_kh, ix = ix0[h] + l_kw;
-                const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
-                tap_off[h] = ok ? origin[h] + l_tap : kOutOfRange;
-            }
-        };
-        place_tap();
+        TapCursor cur;
+        cur.start(p, 0, CB, cb_stride, row_stride, live, iy0, ix0, origin);
         v4i opb[kDepth][2];
         auto request = [&](int slot) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) opb[slot][h] = load_operand(xt_rsrc, tap_off[h], l_cboff);
-            if (l_step + 1 < n_steps) {              // past the end the last step is simply requested again
-                ++l_step;
-                l_cboff += cb_stride;
-                if (++l_cb == CB) {
-                    l_cb = 0;
-                    l_cboff = 0;
-                    l_tap += 32u;
-                    if (++l_kw == p.tKW) { l_kw = 0; ++l_kh; l_tap += row_stride - (uint32_t)p.tKW * 32u; }
-                    place_tap();
-                }
-            }
+            for (int h = 0; h < 2; ++h) opb[slot][h] = load_operand(xt_rsrc, cur.tap_off[h], cur.cboff);
+            cur.advance(p, n_steps, CB, cb_stride, row_stride, live, iy0, ix0, origin);
         };
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) request(d);
