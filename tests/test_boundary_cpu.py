@@ -86,8 +86,19 @@ def test_later_entry_points_validate_on_the_host(psb):
     assert L.psb_conv2d_shared(None, P, C.byref(g), 1, 0, 0, P, None, None, None, None) == psb.ERR_NULL
     assert L.psb_conv2d_progressive_shared(None, P, C.byref(g), P, None, 0, 0, P, None, None, None, None) == psb.ERR_NULL
     assert L.psb_conv2d_requant(None, P, C.byref(g), 4, None, 0, 0, P, None, None, None, None, P, 0, None) == psb.ERR_NULL
+    # the chained shared-filter pass
+    bl = L.psb_conv2d_shared_requant_blocked
+    assert bl(None, P, C.byref(g), 4, 0, 0, None, None, None, None, P, 0, None) == psb.ERR_NULL
+    pf = L.psb_shared_prepare_filters
+    assert pf(None, 1, 4, P, P, None) == psb.ERR_NULL
+    assert pf(P, 1, 4, None, P, None) == psb.ERR_NULL
+    assert pf(P, 0, 4, P, P, None) == psb.ERR_SHAPE
+    handles = (C.c_void_p * 1)(None)
+    assert pf(handles, 1, 4, P, P, None) == psb.ERR_NULL                             # a NULL handle in the list
     # requantize
     rq = L.psb_requantize
+    for inv in (-1.0, float("nan")):
+        assert rq(P, None, None, 0.0, 1, inv, 0, 127, 8, P, None) == psb.ERR_VALUE   # the step cannot be negative
     assert rq(None, None, None, 0.0, 1, 1.0, 0, 127, 8, P, None) == psb.ERR_NULL
     assert rq(P, None, None, 0.0, 1, 1.0, 0, 127, 8, None, None) == psb.ERR_NULL
     assert rq(P, None, None, 0.0, 1, 1.0, 0, 127, 0, P, None) == psb.ERR_SHAPE
