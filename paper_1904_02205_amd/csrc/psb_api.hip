@@ -353,11 +353,13 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
                (rq->res_blocked && ((uintptr_t)rq->res_i8 & 3u) != 0)))
         return PSB_ERR_VALUE;
     p.ksplit = 1;
+    int half_tiles = 2;
     if (mfma) {
         // Few pixel tiles and a long reduction: cut the reduction so that every SIMD has a wave.  Only then: the
         // partial sums cost a zero-fill, atomics and a separate rescale pass, which measured slower than the
         // unsplit kernel as soon as the chip is half full.
-        const int64_t waves = ((int64_t)g->n * OH * OW + 63) / 64 * n_ocb;
+        half_tiles = psb::shared_half_tiles((int64_t)g->n * OH * OW, n_ocb);
+        const int64_t waves = ((int64_t)g->n * OH * OW + 32 * half_tiles - 1) / (32 * half_tiles) * n_ocb;
         const int64_t want = waves <= 512 ? (1024 + waves - 1) / waves : 1;
         p.ksplit = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, 8), n_ksteps / 16));
     }
@@ -411,7 +413,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
                     n = 256;
                 return 2 * n;
             }();
-            psb::launch_conv_shared_mfma(p, psb::planes_needed(max_shift, n_samples), resident_wgs, stream);
+            psb::launch_conv_shared_mfma(p, psb::planes_needed(max_shift, n_samples), resident_wgs, half_tiles, stream);
         } else {
             const dim3 grid((unsigned)((npix + 255) / 256), (unsigned)p.OC);
             hipLaunchKernelGGL(psb::k_conv_shared_direct, grid, dim3(256), 0, stream, p);

@@ -345,6 +345,8 @@ constexpr int kStageSteps = 8;      // a multiple of kDepth
 // Load cursor of a wave: the reduction step whose activation operands are requested next.  Steps are ordered
 // (kh, kw, block of 32 channels); step, position and the two offsets are uniform over the wave, tap_off (per lane
 // and half tile: where this tap of the lane's pixel lies in xt, or out of range for a tap in the padding) is not.
+// HT: half tiles (of 32 pixels) per wave, 1 or 2.
+template <int HT>
 struct TapCursor {
     int step, cb, kw, kh;
     uint32_t tap;          // offset of tap (kh, kw) from a pixel's origin
@@ -355,7 +357,7 @@ struct TapCursor {
                                           const int (&ix0)[2], const uint32_t (&origin)[2])
     {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < HT; ++h) {
             const int iy = iy0[h] + kh, ix = ix0[h] + kw;
             const bool ok = live[h] && (unsigned)iy < (unsigned)p.tH && (unsigned)ix < (unsigned)p.tW;
             tap_off[h] = ok ? origin[h] + tap : kOutOfRange;
@@ -397,12 +399,19 @@ struct TapCursor {
 // part, the input position of tap (0, 0) and origin = offset in xt of xt[n][iy0][0][ix0][16 g] modulo 2^32 (only used
 // with an in-image tap added).  Offsets into xt are 32 bits wide (the host keeps the buffer below 2 GB), so that an
 // operand address is the uniform buffer plus one vector register.
+template <int HT>
 __device__ __forceinline__ void decode_half_tiles(const SharedParams& p, int64_t pix0, int col, int g, int CB, int64_t npix,
                                                   bool (&live)[2], int (&n_)[2], int (&oy_)[2], int (&ox_)[2],
                                                   int (&to_)[2], int (&iy0)[2], int (&ix0)[2], uint32_t (&origin)[2])
 {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = HT; h < 2; ++h) {                     // half tiles this wave does not have
+        live[h] = false;
+        n_[h] = oy_[h] = ox_[h] = to_[h] = iy0[h] = ix0[h] = 0;
+        origin[h] = 0;
+    }
+#pragma unroll
+    for (int h = 0; h < HT; ++h) {
         const int64_t pix = pix0 + 32 * h + col;
         const bool valid = pix < npix;
         const uint32_t pc = (uint32_t)(valid ? pix : npix - 1);       // the pixel count fits 32 bits (checked by the host)
@@ -422,8 +431,8 @@ enum { kOutPartial = 0, kOutAcc = 1, kOutRequant = 2 };
 
 // The end of a wave's tile: what is done with the sums of its 32 channels x 64 pixels (see the OUT values below).
 // acc[h][b]: digit plane b of half tile h; live / n_ / oy_ / ox_ / to_: this lane's pixel in each half tile.
-template <int P, int OUT>
-__device__ __forceinline__ void tile_epilogue(const SharedParams& p, v16i (&acc)[2][P], const bool (&live)[2],
+template <int P, int OUT, int HT>
+__device__ __forceinline__ void tile_epilogue(const SharedParams& p, v16i (&acc)[HT][P], const bool (&live)[2],
                                               const int (&n_)[2], const int (&oy_)[2], const int (&ox_)[2],
                                               const int (&to_)[2], int ocb, int lane, const float* s_mult,
                                               const float* s_bias)
@@ -441,7 +450,7 @@ __device__ __forceinline__ void tile_epilogue(const SharedParams& p, v16i (&acc)
     auto finish = [&](auto full_c) {
         constexpr bool FULL = decltype(full_c)::value;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < HT; ++h) {
             if (!live[h]) continue;                    // uniform over a quad of lanes where that matters
             const int oc_first = ocb * 32 + 4 * g;     // channel of register 0; register q: + 8 (q / 4) + q % 4
             const int64_t o_first = ((int64_t)n_[h] * p.OC + oc_first) * plane + oy_[h] * p.OW + ox_[h];
@@ -574,7 +583,7 @@ __device__ __forceinline__ void tile_epilogue(const SharedParams& p, v16i (&acc)
 // rescaling is a separate pass then), store accumulators (and rescaled values), or store requantised activations
 // (and, if asked for, the other two).  A template parameter, so that the unrolled epilogue is straight-line code.
 
-template <int P, int OUT>
+template <int P, int OUT, int HT>
 __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 {
     __shared__ v4i a_lds[kStageSteps * P * 64];
@@ -589,7 +598,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     // (The launcher rounds the grid up to a multiple of 8; workgroups past the last tile have no live pixel.)
     const unsigned per_xcd = gridDim.x >> 3;
     const unsigned wg = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-    const int64_t pix0 = ((int64_t)wg * 4 + wave) * 64;
+    const int64_t pix0 = ((int64_t)wg * 4 + wave) * (32 * HT);
     const int ocb = blockIdx.y;
 
     const int CB = p.C_pad >> 5;
@@ -622,13 +631,13 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     bool live[2];
     int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
     uint32_t origin[2];
-    decode_half_tiles(p, pix0, col, g, CB, npix, live, n_, oy_, ox_, to_, iy0, ix0, origin);
+    decode_half_tiles<HT>(p, pix0, col, g, CB, npix, live, n_, oy_, ox_, to_, iy0, ix0, origin);
     // a wave without any pixel that takes part still helps to stage the weights (and keeps the barriers whole)
     const bool active = __ballot(live[0] || live[1]) != 0ull;
 
-    v16i acc[2][P];
+    v16i acc[HT][P];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < HT; ++h)
 #pragma unroll
         for (int b = 0; b < P; ++b)
 #pragma unroll
@@ -637,12 +646,12 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     const uint32_t cb_stride = (uint32_t)p.tW * 32u;            // bytes between the channel blocks of one pixel
     const uint32_t row_stride = (uint32_t)CB * cb_stride;       // ... between the rows of one image
     const __amdgpu_buffer_rsrc_t xt_rsrc = operand_buffer(p.xt, p.xt_bytes);
-    TapCursor cur;
+    TapCursor<HT> cur;
     cur.start(p, min(s_begin, n_steps - 1), CB, cb_stride, row_stride, live, iy0, ix0, origin);
-    v4i opb[kDepth][2];
+    v4i opb[kDepth][HT];
     auto request = [&](int slot) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) opb[slot][h] = load_operand(xt_rsrc, cur.tap_off[h], cur.cboff);
+        for (int h = 0; h < HT; ++h) opb[slot][h] = load_operand(xt_rsrc, cur.tap_off[h], cur.cboff);
         cur.advance(p, n_steps, CB, cb_stride, row_stride, live, iy0, ix0, origin);
     };
 
@@ -675,10 +684,10 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
                 }
                 if (s0 + ks < s_end) {               // wave-uniform
 #pragma unroll
-                    for (int b = 0; b < P; ++b) {
-                        acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][0], acc[0][b], 0, 0, 0);
-                        acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][1], acc[1][b], 0, 0, 0);
-                    }
+                    for (int b = 0; b < P; ++b)
+#pragma unroll
+                        for (int h = 0; h < HT; ++h)
+                            acc[h][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][h], acc[h][b], 0, 0, 0);
                 }
                 request(d);     // unconditional (past the end: the last step again), so that the number of
                                 // loads in flight is the same on every path and no wait is longer than needed
@@ -687,7 +696,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     }
     if (!active) return;
 
-    tile_epilogue<P, OUT>(p, acc, live, n_, oy_, ox_, to_, ocb, lane, s_mult, s_bias);
+    tile_epilogue<P, OUT, HT>(p, acc, live, n_, oy_, ox_, to_, ocb, lane, s_mult, s_bias);
 }
 
 // Short reductions (all weight operands of a channel block fit LDS: the first layer of a network, 3x3 layers on 64
@@ -731,7 +740,7 @@ __global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const Shar
         bool live[2];
         int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
         uint32_t origin[2];
-        decode_half_tiles(p, pix0, col, g, CB, npix, live, n_, oy_, ox_, to_, iy0, ix0, origin);
+        decode_half_tiles<2>(p, pix0, col, g, CB, npix, live, n_, oy_, ox_, to_, iy0, ix0, origin);
         if (__ballot(live[0] || live[1]) == 0ull) continue;      // wave-uniform; no barrier below
 
         v16i acc[2][P];
@@ -742,7 +751,7 @@ __global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const Shar
 #pragma unroll
                 for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
 
-        TapCursor cur;
+        TapCursor<2> cur;
         cur.start(p, 0, CB, cb_stride, row_stride, live, iy0, ix0, origin);
         v4i opb[kDepth][2];
         auto request = [&](int slot) {
@@ -772,7 +781,7 @@ __global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const Shar
                 request(ks);
             }
         }
-        tile_epilogue<P, OUT>(p, acc, live, n_, oy_, ox_, to_, ocb, lane, s_mult, s_bias);
+        tile_epilogue<P, OUT, 2>(p, acc, live, n_, oy_, ox_, to_, ocb, lane, s_mult, s_bias);
     }
 }
 
@@ -822,15 +831,15 @@ inline int planes_needed(int max_shift, int n_samples)
     return planes > kMaxPlanes ? kMaxPlanes : planes;
 }
 
-template <int OUT>
+template <int OUT, int HT>
 inline void launch_conv_shared_mfma_out(const SharedParams& p, int planes, dim3 grid, hipStream_t stream)
 {
     const dim3 block(256);
     switch (planes) {
-        case 1: hipLaunchKernelGGL((k_conv_shared_mfma<1, OUT>), grid, block, 0, stream, p); break;
-        case 2: hipLaunchKernelGGL((k_conv_shared_mfma<2, OUT>), grid, block, 0, stream, p); break;
-        case 3: hipLaunchKernelGGL((k_conv_shared_mfma<3, OUT>), grid, block, 0, stream, p); break;
-        default: hipLaunchKernelGGL((k_conv_shared_mfma<4, OUT>), grid, block, 0, stream, p); break;
+        case 1: hipLaunchKernelGGL((k_conv_shared_mfma<1, OUT, HT>), grid, block, 0, stream, p); break;
+        case 2: hipLaunchKernelGGL((k_conv_shared_mfma<2, OUT, HT>), grid, block, 0, stream, p); break;
+        case 3: hipLaunchKernelGGL((k_conv_shared_mfma<3, OUT, HT>), grid, block, 0, stream, p); break;
+        default: hipLaunchKernelGGL((k_conv_shared_mfma<4, OUT, HT>), grid, block, 0, stream, p); break;
     }
 }
 
@@ -847,11 +856,17 @@ inline void launch_conv_shared_mfma_resident(const SharedParams& p, int planes, 
     }
 }
 
+// Half tiles (32 pixels) per wave: two, unless the layer is so small that one-half-tile waves still fit the chip at
+// once (then twice the waves share the work, and a long reduction need not be split).
+inline int shared_half_tiles(int64_t npix, int n_ocb) { return (npix + 63) / 64 * n_ocb <= 1024 ? 1 : 2; }
+
 // resident_wgs: workgroups the chip holds at once with this kernel (two per CU), or 0 to rule the persistent variant out.
-inline void launch_conv_shared_mfma(const SharedParams& p, int planes, int resident_wgs, hipStream_t stream)
+// half_tiles: shared_half_tiles() of the layer (p.ksplit was chosen for it).
+inline void launch_conv_shared_mfma(const SharedParams& p, int planes, int resident_wgs, int half_tiles, hipStream_t stream)
 {
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
-    const int64_t tiles = (npix + 255) / 256;
+    const int64_t wg_pixels = 128 * half_tiles;
+    const int64_t tiles = (npix + wg_pixels - 1) / wg_pixels;
     const unsigned columns = (unsigned)((tiles + 7) / 8 * 8);                        // 8 XCDs
     const unsigned n_ocb = (unsigned)((p.OC + 31) / 32);
     const int n_steps = p.tKH * p.tKW * (p.C_pad >> 5);
@@ -859,16 +874,22 @@ inline void launch_conv_shared_mfma(const SharedParams& p, int planes, int resid
     // worth it when a workgroup gets more than one tile: staging the whole block before the first matrix instruction
     // costs more than the chunked start of the plain kernel
     const unsigned fit = std::max(8u, (unsigned)std::max(resident_wgs, 0) / n_ocb / 8u * 8u);
-    if (resident_wgs > 0 && !p.masked && p.ksplit == 1 && lds <= 65536 && columns > fit) {
+    if (half_tiles == 2 && resident_wgs > 0 && !p.masked && p.ksplit == 1 && lds <= 65536 && columns > fit) {
         const dim3 grid(fit, n_ocb);
         if (p.rq.x_out) launch_conv_shared_mfma_resident<kOutRequant>(p, planes, grid, columns, lds, stream);
         else launch_conv_shared_mfma_resident<kOutAcc>(p, planes, grid, columns, lds, stream);
         return;
     }
     const dim3 grid(columns, n_ocb, (unsigned)p.ksplit);
-    if (p.masked || p.ksplit > 1) launch_conv_shared_mfma_out<kOutPartial>(p, planes, grid, stream);
-    else if (p.rq.x_out) launch_conv_shared_mfma_out<kOutRequant>(p, planes, grid, stream);
-    else launch_conv_shared_mfma_out<kOutAcc>(p, planes, grid, stream);
+    if (half_tiles == 1) {
+        if (p.masked || p.ksplit > 1) launch_conv_shared_mfma_out<kOutPartial, 1>(p, planes, grid, stream);
+        else if (p.rq.x_out) launch_conv_shared_mfma_out<kOutRequant, 1>(p, planes, grid, stream);
+        else launch_conv_shared_mfma_out<kOutAcc, 1>(p, planes, grid, stream);
+    } else {
+        if (p.masked || p.ksplit > 1) launch_conv_shared_mfma_out<kOutPartial, 2>(p, planes, grid, stream);
+        else if (p.rq.x_out) launch_conv_shared_mfma_out<kOutRequant, 2>(p, planes, grid, stream);
+        else launch_conv_shared_mfma_out<kOutAcc, 2>(p, planes, grid, stream);
+    }
 }
 
 }  // namespace psb
