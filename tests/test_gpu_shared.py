@@ -60,6 +60,8 @@ def _cases():
     # more pixel tiles than workgroups fit the chip, short reduction: the persistent variant of the matrix-core kernel
     c.append(("many_tiles_short_reduction", _layer(rng, 1, 16, 40, (370, 372), 3, pad=1, S=4), (0,)))
     c.append(("many_tiles_row_packed", _layer(rng, 1, 3, 33, (530, 540), 5, stride=2, pad=2, S=4, xkind="signed"), (0,)))
+    # two half tiles per wave without the persistent variant: many channel blocks, few pixel tiles per block
+    c.append(("two_half_tiles_many_blocks", _layer(rng, 1, 32, 250, (100, 120), 3, pad=1, S=4), (0,)))
     c.append(("grouped", _layer(rng, 2, 8, 12, 7, 3, pad=1, groups=4, S=8), (0,)))
     c.append(("depthwise", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), (0,)))
     return c
@@ -160,6 +162,19 @@ def test_progressive_bit_exact_and_incremental(psb, orc, mapping):
     plain, _ = helpers.gpu_layer(psb, L, qg, S=8, shared=True)
     assert np.array_equal(const, plain)
     psb.set_mapping(psb.MAPPING_AUTO)
+
+
+def test_progressive_on_a_large_image(psb, orc):
+    """Budget segments (masked, accumulating launches) with two half tiles per wave."""
+    rng = np.random.default_rng(981)
+    L = _layer(rng, 2, 16, 40, (200, 190), 3, pad=1, S=8, s_max=8)
+    oh, ow = L.out_hw
+    to = rng.choice([0, 2, 4, 8], size=(2, oh, ow)).astype(np.uint8)
+    qo, qg = helpers.oracle_quantize(orc, L), helpers.gpu_quantize(psb, L)
+    ref, over, _ = helpers.oracle_layer(orc, L, qo, budget_to=to, shared=True)
+    assert over == 0
+    acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, shared=True)
+    assert np.array_equal(acc, ref)
 
 
 @pytest.mark.parametrize("mapping", [0, 1])
