@@ -894,6 +894,14 @@ int psb_maxpool2d_i8(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32
     const int64_t OH = ((int64_t)h + 2ll * pad_h - kh) / stride_h + 1, OW = ((int64_t)w + 2ll * pad_w - kw) / stride_w + 1;
     const int64_t images = (int64_t)n * c;
     if (images * h * w >= (1ll << 40) || OH > 2147483647ll || OW > 2147483647ll) return PSB_ERR_TOO_LARGE;
+    if (kh == 3 && kw == 3 && stride_h == 2 && stride_w == 2 && pad_h == 1 && pad_w == 1 && w % 4 == 0 && OW % 4 == 0 &&
+        (((uintptr_t)x_dev | (uintptr_t)out_dev) & 3u) == 0) {
+        const int64_t work = images * OH * (OW / 4);
+        hipLaunchKernelGGL(psb::k_maxpool_3x3s2p1_i8, dim3((unsigned)std::min<int64_t>((work + 255) / 256, 65536)), dim3(256),
+                           0, (hipStream_t)hip_stream, x_dev, images, h, w, (int)OH, (int)OW, out_dev);
+        PSB_HIP_TRY(hipGetLastError());
+        return PSB_OK;
+    }
     const int64_t total = images * OH * ((OW + 3) / 4);
     const int blocks = (int)std::min<int64_t>((total + 255) / 256, 65536);
     hipLaunchKernelGGL(psb::k_maxpool_i8, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, x_dev, images, h, w, kh, kw,

@@ -89,6 +89,41 @@ __global__ void __launch_bounds__(256) k_maxpool_i8(const int8_t* __restrict__ x
     }
 }
 
+// The pooling of a ResNet stem - 3x3 windows, stride 2, padding 1 - with W and OW multiples of 4 and 4-byte aligned
+// tensors: four neighbouring outputs per thread from three 32-bit loads per input row (columns 8 ox4 - 4 .. 8 ox4 + 7;
+// output j takes columns 8 ox4 + 2 j - 1 .. + 1) instead of twelve byte loads, one 32-bit store.
+__global__ void __launch_bounds__(256) k_maxpool_3x3s2p1_i8(const int8_t* __restrict__ x, int64_t images, int H, int W,
+                                                            int OH, int OW, int8_t* __restrict__ out)
+{
+    const int OW4 = OW >> 2;
+    const int64_t total = images * OH * OW4;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int ox4 = (int)(i % OW4);
+        const int oy = (int)((i / OW4) % OH);
+        const int64_t img = i / ((int64_t)OW4 * OH);
+        const int8_t* src = x + img * H * W;
+        int best[4] = {-128, -128, -128, -128};
+#pragma unroll
+        for (int dy = 0; dy < 3; ++dy) {
+            const int iy = 2 * oy - 1 + dy;
+            if ((unsigned)iy >= (unsigned)H) continue;
+            const uint32_t* row = reinterpret_cast<const uint32_t*>(src + (int64_t)iy * W) + 2 * ox4;
+            // a column outside the image does not take part: -128 cannot raise a maximum
+            const uint32_t left = ox4 > 0 ? row[-1] : 0x80808080u;
+            const uint32_t d0 = row[0];
+            const uint32_t d1 = 8 * ox4 + 4 < W ? row[1] : 0x80808080u;
+            auto byte = [](uint32_t w, int b) { return (int)(int8_t)(w >> (8 * b)); };
+            best[0] = max(best[0], max(byte(left, 3), max(byte(d0, 0), byte(d0, 1))));
+            best[1] = max(best[1], max(byte(d0, 1), max(byte(d0, 2), byte(d0, 3))));
+            best[2] = max(best[2], max(byte(d0, 3), max(byte(d1, 0), byte(d1, 1))));
+            best[3] = max(best[3], max(byte(d1, 1), max(byte(d1, 2), byte(d1, 3))));
+        }
+        *reinterpret_cast<uint32_t*>(out + (img * OH + oy) * (int64_t)OW + 4 * ox4) =
+            ((uint32_t)best[0] & 0xFFu) | (((uint32_t)best[1] & 0xFFu) << 8) | (((uint32_t)best[2] & 0xFFu) << 16) |
+            (((uint32_t)best[3] & 0xFFu) << 24);
+    }
+}
+
 // One wave per (n, c) image: exact int32 sum, then two rounded multiplications.
 __global__ void __launch_bounds__(256) k_avgpool_requantize(const int8_t* __restrict__ x, int64_t images, int HW,
                                                             float inv_count, float scale, float lo, float hi,

@@ -57,7 +57,8 @@ def test_requantize_errors(psb):
 @pytest.mark.parametrize("geom", [((3, 3), (2, 2), (1, 1), 112, 112), ((2, 2), (2, 2), (0, 0), 8, 8),
                                   ((3, 2), (1, 2), (1, 0), 5, 7), ((1, 1), (1, 1), (0, 0), 4, 4),
                                   ((3, 3), (2, 2), (1, 1), 9, 11), ((3, 3), (2, 2), (1, 1), 4, 20000),   # rows too long for LDS
-                                  ((3, 3), (1, 1), (1, 1), 300, 12), ((2, 2), (2, 2), (1, 1), 64, 64)])
+                                  ((3, 3), (1, 1), (1, 1), 300, 12), ((2, 2), (2, 2), (1, 1), 64, 64),
+                                  ((3, 3), (2, 2), (1, 1), 9, 16), ((3, 3), (2, 2), (1, 1), 1, 8)])   # the stem-pooling kernel
 def test_maxpool(psb, orc, geom):
     import torch
     kernel, stride, pad, h, w = geom
