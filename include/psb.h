@@ -284,10 +284,12 @@ int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_co
  * psb_shared_prepare_filters samples the digit planes of n handles in one launch, for S samples and the given
  * (seed, layer_id) of each.  The next shared-filter call on such a handle with the same S, seed and layer_id and
  * no budget map uses them instead of sampling again (once: the call after that samples as usual); any other
- * shared-filter call on the handle discards them.  Handles whose layers do not run on the matrix cores are skipped.  The call
- * counts as a layer call on every handle it is given (it writes their workspaces) and must not overlap with other
- * calls on them.  Same results as
+ * shared-filter call on the handle discards them.  Handles whose layers do not run on the matrix cores are
+ * skipped.  The call counts as a layer call on every handle it is given (it writes their workspaces) and must not
+ * overlap with other calls on them.  handles, seeds and layer_ids are host arrays of n entries.  Same results as
  * without the call.  Errors: NULL, SHAPE (n <= 0), VALUE (S), DEVICE, TOO_LARGE, ALLOC.
+ * Errors of psb_conv2d_shared_requant_blocked: those of psb_conv2d_requant, plus VALUE (unknown layout bits,
+ * alignment) and SHAPE (PSB_BLOCKED_IN on a layer that cannot take it).
  */
 enum { PSB_BLOCKED_IN = 1, PSB_BLOCKED_OUT = 2, PSB_BLOCKED_RES = 4 };
 int psb_conv2d_shared_requant_blocked(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S,
