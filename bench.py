@@ -284,7 +284,10 @@ def main():
                    "generator_calls_per_step": n_calls, "samples_per_generator_call": per_call,
                    "prob_bits": args.prob_bits, "mode": args.mode, "hip_graph": bool(args.graph),
                    "kernel_launches_per_step": launches_per_step, "mapping": args.mapping,
-                   "rescale_output": not args.no_y},
+                   "rescale_output": not args.no_y,
+                   # the network in shared-filter mode runs as one chain: all filters sampled in one launch per pass,
+                   # blocked channels-last activations between the convolutions
+                   "chained_pass": args.workload == "c4net" and args.mode == "shared"},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_TIOPS,
                      "unit": "TIOP/s (simple int32 lane-ops)", "frac": achieved / PEAK_TIOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mapping))
