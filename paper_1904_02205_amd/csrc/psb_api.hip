@@ -301,10 +301,13 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     const shared_plan sp = plan_shared(q);
     const bool mfma = sp.mfma, rowpack = sp.rowpack;
     const int C_pad = sp.C_pad, CB = sp.CB, n_ksteps = sp.n_ksteps, n_ocb = sp.n_ocb;
-    const bool in_blocked = (layout & PSB_BLOCKED_IN) != 0;
+    bool in_blocked = (layout & PSB_BLOCKED_IN) != 0;
     // a blocked input is read in place by the matrix-core kernel; the other kernels have no use for it
     if (in_blocked && (!mfma || rowpack)) return PSB_ERR_SHAPE;
     if (in_blocked && ((uintptr_t)x & 15u) != 0) return PSB_ERR_VALUE;
+    // a 1 x 1 image with whole channel blocks (a linear layer) has the same bytes in both layouts: no copy needed
+    if (mfma && !rowpack && g->h == 1 && g->w == 1 && q->shape.cin % 32 == 0 && ((uintptr_t)x & 15u) == 0)
+        in_blocked = true;
 
     shared_workspace* ws = q->ws;
     const int64_t nw = (int64_t)q->shape.oc * q->K;
