@@ -9,13 +9,15 @@
 //     W = sum_b d_b 256^b (mod 2^32); each digit plane is contracted separately with
 //     v_mfma_i32_32x32x32_i8 and the planes are recombined with shifts in the epilogue.  All of it is exact
 //     modulo 2^32, and the true result fits int32 by the overflow rule of the weight encoding.
-//   * the activations are first copied to a channels-last layout [N][H][W][C padded to 32], so that the 16
-//     bytes of reduction index a lane feeds to the matrix core are 16 consecutive bytes in memory; the
-//     reduction index is ordered (kh, kw, channel), which no result depends on;
+//   * the activations are read in a blocked channels-last layout [N][H][C/32][W][32] (a copy made by the
+//     prologue launch, or the caller's tensor if it already has that layout): the 16 bytes of reduction index a
+//     lane feeds to the matrix core are 16 consecutive bytes, and the 32 pixels of a half tile are 1 KB of
+//     consecutive memory; the reduction index is ordered (kh, kw, channel), which no result depends on;
 //   * the digit planes are written directly in the operand order of the instruction
 //     [block of 32 channels][k-step][plane][lane][16 bytes]: an operand is one coalesced 1 KB read.
-// One wave computes 32 output channels x 64 output pixels; the output is stored with consecutive lanes on
-// consecutive pixels (coalesced in NCHW).
+// One wave computes 32 output channels x 64 (or 32) output pixels.  Three kernels share the pieces below: the
+// plain one (weights staged through LDS chunk by chunk), a persistent one for short reductions (all weights of a
+// channel block resident in LDS) and the direct one for grouped layers.
 //
 // Per-pixel budgets: the distinct budget values cut the sample axis into segments; each segment is one
 // filter (built from exactly its samples, so budgets nest) and one masked, accumulating contraction over
