@@ -203,8 +203,10 @@ int psb_conv2d_progressive(const psb_weights_t* q, const int8_t* x_dev, const ps
  * Differences from the per-product calls: the first shared-filter call on a handle, and any call with a
  * larger input than before, allocates device memory owned by the handle (the sampled filter, its int8
  * digit planes, a channels-last copy of the activations); psb_conv2d_progressive_shared synchronises the
- * stream once (it reads back which budget values occur).  Additional error: TOO_LARGE when
- * kh*kw*(cin rounded up to 32) >= 2^17 (groups = 1), ALLOC.
+ * stream once (it reads back which budget values occur).  Additional errors: TOO_LARGE when
+ * kh*kw*(cin rounded up to 32) >= 2^17 (groups = 1) or when the channels-last activation tensor
+ * (n*h*w*(cin rounded up to 32) bytes) reaches 2 GiB, which the matrix-core kernel's 32-bit offsets
+ * cannot address; ALLOC.
  */
 int psb_sample_filter(const psb_weights_t* q, int32_t sample_from, int32_t sample_to, uint64_t seed,
                       uint32_t layer_id, int32_t* w_dev, void* hip_stream);
