@@ -126,6 +126,9 @@ def _cases():
     c.append(("grouped", _layer(rng, 2, 8, 12, 7, 3, pad=1, groups=4, S=8), (1, 3)))
     c.append(("depthwise", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), (1, 3)))
     c.append(("depthwise_s2", _layer(rng, 1, 10, 10, 8, 3, stride=2, pad=1, groups=10, S=4, xkind="signed"), (1, 3)))
+    # no padding: every tap of every pixel is inside the image (the product-list kernel drops its bounds checks)
+    c.append(("conv3x3_unpadded_s2", _layer(rng, 2, 7, 9, (12, 10), 3, stride=2, S=8), both))
+    c.append(("depthwise_unpadded", _layer(rng, 1, 12, 12, (21, 17), (3, 2), groups=12, S=16, xkind="signed"), (1, 3)))
     return c
 
 

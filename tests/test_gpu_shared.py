@@ -177,6 +177,21 @@ def test_progressive_on_a_large_image(psb, orc):
     assert np.array_equal(acc, ref)
 
 
+def test_activation_tensor_beyond_the_offset_range_is_refused(psb):
+    """The matrix-core kernel addresses the channels-last activations with 32-bit offsets: a tensor that
+    reaches 2 GiB in that layout is an error, not a launch."""
+    import torch
+    w = torch.full((1, 1, 3, 3), 0.25, device="cuda")
+    q = psb.Weights(w, x_absmax=127, s_max=8)
+    x = torch.zeros((1, 1, 8192, 8192), dtype=torch.int8, device="cuda")    # 8192 * 8192 * 32 bytes once blocked
+    acc = torch.empty((1, 1, 8192, 8192), dtype=torch.int32, device="cuda")
+    with pytest.raises(psb.PsbError) as ei:
+        psb.conv2d(q, x, 8, pad=(1, 1), acc=acc, shared=True)
+    assert ei.value.code == psb.ERR_TOO_LARGE
+    ok = psb.conv2d(q, x[:, :, :64, :64].contiguous(), 8, pad=(1, 1), shared=True)
+    assert int(ok.abs().max()) == 0
+
+
 @pytest.mark.parametrize("mapping", [0, 1])
 def test_rescale_matches_oracle(psb, orc, mapping):
     rng = np.random.default_rng(980)
