@@ -60,7 +60,7 @@ typedef enum {
     PSB_ERR_SHAPE = -2,           /* non-positive or inconsistent dimension                      */
     PSB_ERR_VALUE = -3,           /* NaN/Inf weight, S <= 0, S > s_max, unsupported bit width    */
     PSB_ERR_OVERFLOW_UNSAFE = -4, /* no exponent window keeps the worst case inside int32        */
-    PSB_ERR_TOO_LARGE = -5,       /* N*OC*OH*OW or K does not fit the 32-bit counter words       */
+    PSB_ERR_TOO_LARGE = -5,       /* N*OC*OH*OW or K does not fit the 32-bit counter words; kh or kw >= 2^15 */
     PSB_ERR_DEVICE = -6,          /* a HIP call failed; see psb_last_device_error()              */
     PSB_ERR_ALLOC = -7            /* host or device allocation failed                            */
 } psb_status;

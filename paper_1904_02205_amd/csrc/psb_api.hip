@@ -107,6 +107,7 @@ int check_wshape(const psb_wshape* s, int64_t* K_out)
     if (s->cin % s->groups || s->oc % s->groups) return PSB_ERR_SHAPE;
     const int64_t K = (int64_t)(s->cin / s->groups) * s->kh * s->kw;
     if (K >= (1ll << 24)) return PSB_ERR_TOO_LARGE;   // taps are packed into 24 bits by the kernels
+    if (s->kh >= (1 << 15) || s->kw >= (1 << 15)) return PSB_ERR_TOO_LARGE;   // and a tap's (kh, kw) into two 16-bit halves
     if ((int64_t)s->oc * K >= (1ll << 31)) return PSB_ERR_TOO_LARGE;
     if (K_out) *K_out = K;
     return PSB_OK;

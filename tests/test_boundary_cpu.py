@@ -42,7 +42,8 @@ def test_out_dims_and_shape_errors(psb):
            ((64, 64, 9, 9, 1), (1, 4, 4, 1, 1, 1, 1), psb.ERR_SHAPE),       # kernel larger than padded input
            ((64, 64, 3, 3, 1), (0, 8, 8, 1, 1, 1, 1), psb.ERR_SHAPE),
            ((1024, 64, 1, 1, 1), (4096, 64, 64, 1, 1, 0, 0), psb.ERR_TOO_LARGE),   # 2^34 outputs
-           ((64, 1 << 22, 3, 3, 1), (1, 8, 8, 1, 1, 1, 1), psb.ERR_TOO_LARGE)]     # K >= 2^24
+           ((64, 1 << 22, 3, 3, 1), (1, 8, 8, 1, 1, 1, 1), psb.ERR_TOO_LARGE),     # K >= 2^24
+           ((4, 1, 1 << 15, 1, 1), (1, 1 << 16, 1, 1, 1, 0, 0), psb.ERR_TOO_LARGE)]  # a kernel side of 2^15
     for ws, g, code in bad:
         with pytest.raises(psb.PsbError) as ei:
             psb.conv2d_out_dims(ws, g)
