@@ -154,7 +154,8 @@ class QWeights:
         self.shape = w.shape
 
     def __del__(self):
-        if getattr(self, "_q", None) is not None:
+        # at interpreter shutdown the module globals may already be gone: then the process frees the memory
+        if getattr(self, "_q", None) is not None and lib is not None and C is not None:
             self.sign = self.shift = self.p = None
             lib().psbo_weights_free(C.byref(self._q))
             self._q = None
