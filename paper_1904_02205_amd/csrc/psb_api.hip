@@ -378,8 +378,8 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     int64_t transpose_blocks = 0;
     if (mfma && !in_blocked) {
         tj.x = x; tj.C = p.C; tj.H = p.H; tj.W = p.W; tj.C_pad = C_pad; tj.xt = ws->xt_dev;
-        tj.tiles_x = (g->w + 63) / 64; tj.rows = (int64_t)g->n * g->h;
-        transpose_blocks = (int64_t)tj.tiles_x * tj.rows * CB;
+        tj.N = g->n; tj.tiles_p = (int)(((int64_t)g->h * g->w + 63) / 64); tj.rows = (int64_t)g->n * g->h;
+        transpose_blocks = (int64_t)tj.tiles_p * g->n * CB;
         if (rowpack) {
             tj.pack_KW = q->shape.kw; tj.OW = OW; tj.stride_w = g->stride_w; tj.pad_w = g->pad_w;
             transpose_blocks = (tj.rows * OW + 255) / 256;
@@ -419,8 +419,17 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
             }();
             psb::launch_conv_shared_mfma(p, psb::planes_needed(max_shift, n_samples), resident_wgs, half_tiles, stream);
         } else {
-            const dim3 grid((unsigned)((npix + 255) / 256), (unsigned)p.OC);
-            hipLaunchKernelGGL(psb::k_conv_shared_direct, grid, dim3(256), 0, stream, p);
+            const int64_t columns = (npix + 255) / 256;
+            if (p.Cg == 1 && p.KH == 3 && p.KW == 3) {
+                // several channels per workgroup row while that leaves eight waves for every SIMD of the chip
+                int channels = 8;
+                while (channels > 2 && columns * ((p.OC + channels - 1) / channels) < 2048) channels /= 2;
+                const dim3 grid((unsigned)columns, (unsigned)((p.OC + channels - 1) / channels));
+                hipLaunchKernelGGL((psb::k_conv_shared_depthwise<3, 3>), grid, dim3(256), 0, stream, p, channels);
+            } else {
+                const dim3 grid((unsigned)columns, (unsigned)p.OC);
+                hipLaunchKernelGGL(psb::k_conv_shared_direct, grid, dim3(256), 0, stream, p);
+            }
         }
         if (timed) profile_end(stream, slot);
         PSB_HIP_TRY(hipGetLastError());

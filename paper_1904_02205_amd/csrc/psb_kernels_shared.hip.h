@@ -191,14 +191,14 @@ __device__ __forceinline__ void sample_planes_block(const FilterJob& j, uint32_t
     }
 }
 
-// x [N][C][H][W] -> xt [N][H][C_pad/32][W][32] (zeros in the padding channels).  One workgroup per
-// (64 columns, row, 32 channels) tile, transposed through LDS; tiles are numbered columns fastest,
-// then rows (n * H + iy), then channel blocks.
+// x [N][C][H][W] -> xt [N][H][C_pad/32][W][32] (zeros in the padding channels).  One workgroup per tile of
+// 32 channels x 64 consecutive positions of an image plane, transposed through LDS.
 struct TransposeJob {
     const int8_t* x;
     int C, H, W, C_pad;
     int8_t* xt;
-    int tiles_x;          // ceil(W / 64)
+    int N;
+    int tiles_p;          // ceil(H * W / 64)
     int64_t rows;         // N * H
     // row packing (pack_KW > 0): xt[n][iy][ox][kw * C + c] = x[n][c][iy][ox * stride_w - pad_w + kw], zero outside
     // the row and in the unused slots; one thread per (n, iy, ox)
@@ -230,28 +230,34 @@ __device__ __forceinline__ void row_pack_block(const TransposeJob& j, int64_t bl
 
 __device__ __forceinline__ void channels_last_tile(const TransposeJob& j, int64_t tile_index, int8_t (*tile)[64 + 4])
 {
-    const int ix0 = (int)(tile_index % j.tiles_x) * 64;
-    const int64_t row = (tile_index / j.tiles_x) % j.rows;
-    const int c0 = (int)(tile_index / ((int64_t)j.tiles_x * j.rows)) * 32;
-    const int n = (int)(row / j.H), iy = (int)(row - (int64_t)n * j.H);
+    // tile = 32 channels x 64 consecutive positions of one image plane (positions run over rows, so that narrow
+    // images still fill the tile); tiles of a plane first, then images, then channel blocks
+    const uint32_t plane = (uint32_t)(j.H * j.W);
+    const uint32_t p0 = (uint32_t)(tile_index % j.tiles_p) * 64u;
+    const int n = (int)((tile_index / j.tiles_p) % j.N);
+    const int c0 = (int)(tile_index / ((int64_t)j.tiles_p * j.N)) * 32;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         const int idx = r * 256 + threadIdx.x;
-        const int c = idx >> 6, dx = idx & 63;
+        const int c = idx >> 6;
+        const uint32_t pos = p0 + (uint32_t)(idx & 63);
         int8_t v = 0;
-        if (c0 + c < j.C && ix0 + dx < j.W) v = j.x[(((int64_t)n * j.C + c0 + c) * j.H + iy) * j.W + ix0 + dx];
-        tile[c][dx] = v;
+        if (c0 + c < j.C && pos < plane) v = j.x[((int64_t)n * j.C + c0 + c) * plane + pos];
+        tile[c][idx & 63] = v;
     }
     __syncthreads();
     const int dx = threadIdx.x >> 2, part = threadIdx.x & 3;
-    if (ix0 + dx < j.W) {
+    const uint32_t pos = p0 + (uint32_t)dx;
+    if (pos < plane) {
         uint32_t lo = 0, hi = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             lo |= (uint32_t)(uint8_t)tile[part * 8 + q][dx] << (8 * q);
             hi |= (uint32_t)(uint8_t)tile[part * 8 + 4 + q][dx] << (8 * q);
         }
-        uint2* dst = reinterpret_cast<uint2*>(j.xt + (((row * (j.C_pad >> 5) + (c0 >> 5)) * j.W + ix0 + dx) * 32 + part * 8));
+        const uint32_t iy = pos / (uint32_t)j.W, ix = pos - iy * (uint32_t)j.W;
+        const int64_t row = (int64_t)n * j.H + iy;
+        uint2* dst = reinterpret_cast<uint2*>(j.xt + (((row * (j.C_pad >> 5) + (c0 >> 5)) * j.W + ix) * 32 + part * 8));
         *dst = make_uint2(lo, hi);
     }
 }
@@ -790,7 +796,9 @@ __global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const Shar
     }
 }
 
-// Any layer shape: one output pixel per lane, one output channel per workgroup row.
+// Any layer shape: one output pixel per lane, one output channel per workgroup row.  (Grouping the taps' loads
+// here, with (channel, kh, kw) stepped at run time, measured slower than this plain loop: the stepping is more
+// scalar work per tap than the loop counters; 3 x 3 depthwise layers have the unrolled kernel below instead.)
 __global__ void __launch_bounds__(256) k_conv_shared_direct(const SharedParams p)
 {
     const int oc = blockIdx.y;
@@ -799,28 +807,99 @@ __global__ void __launch_bounds__(256) k_conv_shared_direct(const SharedParams p
     if (pix >= npix) return;
     int to;
     if (!shared_pixel_range(p, pix, to)) return;
-    const int ox = (int)(pix % p.OW);
-    const int oy = (int)((pix / p.OW) % p.OH);
-    const int n = (int)(pix / ((int64_t)p.OW * p.OH));
+    const uint32_t pix32 = (uint32_t)pix;                  // the number of outputs fits 32 bits, so pixels do too
+    const uint32_t row32 = pix32 / (uint32_t)p.OW;
+    const int ox = (int)(pix32 - row32 * (uint32_t)p.OW);
+    const int n = (int)(row32 / (uint32_t)p.OH);
+    const int oy = (int)(row32 - (uint32_t)n * (uint32_t)p.OH);
     const int grp = oc / p.OCg;
     const int32_t* wrow = p.w32 + (int64_t)oc * p.K;
-    const int8_t* xn = p.x + ((int64_t)n * p.C + (int64_t)grp * p.Cg) * p.H * p.W;
+    // the activation tensor has fewer than 2^31 elements: 32-bit indices
+    const uint32_t xn = (uint32_t)(n * p.C + grp * p.Cg) * (uint32_t)(p.H * p.W);
     const int iy0 = oy * p.stride_h - p.pad_h, ix0 = ox * p.stride_w - p.pad_w;
     uint32_t sum = 0;
     int k = 0;
     for (int ci = 0; ci < p.Cg; ++ci)
-        for (int kh = 0; kh < p.KH; ++kh)
+        for (int kh = 0; kh < p.KH; ++kh) {
+            const int iy = iy0 + kh;
+            const uint32_t row = xn + (uint32_t)(ci * p.H + iy) * (uint32_t)p.W;
             for (int kw = 0; kw < p.KW; ++kw, ++k) {
-                const int iy = iy0 + kh, ix = ix0 + kw;
+                const int ix = ix0 + kw;
                 if ((unsigned)iy >= (unsigned)p.H || (unsigned)ix >= (unsigned)p.W) continue;
-                sum += (uint32_t)((int32_t)xn[((int64_t)ci * p.H + iy) * p.W + ix] * wrow[k]);   // modulo 2^32
+                sum += (uint32_t)((int32_t)p.x[row + (uint32_t)ix] * wrow[k]);   // modulo 2^32
             }
+        }
     const int64_t o = (((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox;
     if (p.masked) {
         p.acc[o] = (int32_t)((uint32_t)p.acc[o] + sum);
     } else {
         if (p.acc) p.acc[o] = (int32_t)sum;
         emit(p, o, oc, (int32_t)sum, to);
+    }
+}
+
+// Depthwise layers (one input channel per group) with a kernel size known at compile time: the taps' offsets and
+// their inside-the-image tests do not depend on the channel, so a lane computes them once and then walks over
+// `channels` output channels, two at a time, with every load of a pair requested before the first is used
+// (range-checked buffer loads: a tap in the padding has an offset beyond the tensor and reads as zero).
+template <int KH, int KW>
+__global__ void __launch_bounds__(256) k_conv_shared_depthwise(const SharedParams p, int channels)
+{
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int64_t pix = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pix >= npix) return;
+    int to;
+    if (!shared_pixel_range(p, pix, to)) return;
+    const uint32_t pix32 = (uint32_t)pix;                  // the number of outputs fits 32 bits, so pixels do too
+    const uint32_t row32 = pix32 / (uint32_t)p.OW;
+    const int ox = (int)(pix32 - row32 * (uint32_t)p.OW);
+    const int n = (int)(row32 / (uint32_t)p.OH);
+    const int oy = (int)(row32 - (uint32_t)n * (uint32_t)p.OH);
+    const __amdgpu_buffer_rsrc_t x_rsrc = operand_buffer(p.x, (uint32_t)((int64_t)p.N * p.C * p.H * p.W));
+    const int iy0 = oy * p.stride_h - p.pad_h, ix0 = ox * p.stride_w - p.pad_w;
+    constexpr int T = KH * KW;
+    uint32_t rel[T];           // offset of the tap inside an image plane; beyond the tensor when outside the image
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < KW; ++kw) {
+            const int iy = iy0 + kh, ix = ix0 + kw;
+            const bool ok = ((unsigned)iy < (unsigned)p.H) & ((unsigned)ix < (unsigned)p.W);
+            rel[kh * KW + kw] = ok ? (uint32_t)(iy * p.W + ix) : kOutOfRange;
+        }
+    const uint32_t plane = (uint32_t)(p.H * p.W);
+    const int oc_end = min(p.OC, ((int)blockIdx.y + 1) * channels);
+    for (int oc0 = (int)blockIdx.y * channels; oc0 < oc_end; oc0 += 2) {
+        const int oc1 = min(oc0 + 1, oc_end - 1);          // a single last channel is computed twice, stored once
+        int32_t xa[T], xb[T];
+        const uint32_t base_a = (uint32_t)(n * p.C + oc0 / p.OCg) * plane;     // plane starts are below 2^31, so
+        const uint32_t base_b = (uint32_t)(n * p.C + oc1 / p.OCg) * plane;     // base + kOutOfRange stays beyond
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            xa[u] = (int32_t)(int8_t)__builtin_amdgcn_raw_buffer_load_b8(x_rsrc, (int)(base_a + rel[u]), 0, 0);
+            xb[u] = (int32_t)(int8_t)__builtin_amdgcn_raw_buffer_load_b8(x_rsrc, (int)(base_b + rel[u]), 0, 0);
+        }
+        const int32_t* wa = p.w32 + (int64_t)oc0 * T;
+        const int32_t* wb = p.w32 + (int64_t)oc1 * T;
+        uint32_t sum_a = 0, sum_b = 0;
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            sum_a += (uint32_t)(xa[u] * wa[u]);            // modulo 2^32
+            sum_b += (uint32_t)(xb[u] * wb[u]);
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int oc = h ? oc1 : oc0;
+            const uint32_t sum = h ? sum_b : sum_a;
+            if (h && oc1 == oc0) break;
+            const int64_t o = (((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox;
+            if (p.masked) {
+                p.acc[o] = (int32_t)((uint32_t)p.acc[o] + sum);
+            } else {
+                if (p.acc) p.acc[o] = (int32_t)sum;
+                emit(p, o, oc, (int32_t)sum, to);
+            }
+        }
     }
 }
 

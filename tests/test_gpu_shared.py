@@ -64,6 +64,11 @@ def _cases():
     c.append(("two_half_tiles_many_blocks", _layer(rng, 1, 32, 250, (100, 120), 3, pad=1, S=4), (0,)))
     c.append(("grouped", _layer(rng, 2, 8, 12, 7, 3, pad=1, groups=4, S=8), (0,)))
     c.append(("depthwise", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), (0,)))
+    # 3 x 3 depthwise layers have a kernel of their own: odd channel count, stride 2, two outputs per input channel
+    c.append(("depthwise_s2_odd_channels", _layer(rng, 3, 13, 13, (11, 9), 3, stride=2, pad=1, groups=13, S=8), (0,)))
+    c.append(("depthwise_multiplier_2_unpadded", _layer(rng, 1, 10, 20, 8, 3, groups=10, S=4, xkind="signed"), (0,)))
+    c.append(("depthwise_many_pixels", _layer(rng, 2, 5, 5, (40, 70), 3, pad=1, groups=5, S=8), (0,)))
+    c.append(("depthwise_5x5", _layer(rng, 1, 6, 6, 9, 5, pad=2, groups=6, S=8), (0,)))
     return c
 
 
@@ -175,6 +180,23 @@ def test_progressive_on_a_large_image(psb, orc):
     assert over == 0
     acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, shared=True)
     assert np.array_equal(acc, ref)
+
+
+def test_progressive_depthwise(psb, orc):
+    """Budget segments through the 3 x 3 depthwise kernel: masked, accumulating launches; refinement in two calls."""
+    rng = np.random.default_rng(982)
+    L = _layer(rng, 2, 9, 9, (17, 12), 3, pad=1, groups=9, S=16, s_max=16)
+    oh, ow = L.out_hw
+    to = rng.choice([0, 2, 4, 8, 16], size=(2, oh, ow)).astype(np.uint8)
+    qo, qg = helpers.oracle_quantize(orc, L), helpers.gpu_quantize(psb, L)
+    ref, over, _ = helpers.oracle_layer(orc, L, qo, budget_to=to, shared=True)
+    assert over == 0
+    acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, shared=True)
+    assert np.array_equal(acc, ref)
+    first = np.minimum(to, 4).astype(np.uint8)
+    a1, _ = helpers.gpu_layer(psb, L, qg, budget_to=first, shared=True)
+    a2, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, budget_from=first, acc_in=a1, shared=True)
+    assert np.array_equal(a2, ref)
 
 
 def test_activation_tensor_beyond_the_offset_range_is_refused(psb):
