@@ -378,7 +378,9 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     int64_t transpose_blocks = 0;
     if (mfma && !in_blocked) {
         tj.x = x; tj.C = p.C; tj.H = p.H; tj.W = p.W; tj.C_pad = C_pad; tj.xt = ws->xt_dev;
-        tj.N = g->n; tj.tiles_p = (int)(((int64_t)g->h * g->w + 63) / 64); tj.rows = (int64_t)g->n * g->h;
+        tj.wide = ((int64_t)g->h * g->w) % 4 == 0 && ((uintptr_t)x & 3u) == 0;
+        const int per_tile = tj.wide ? psb::kWideTilePositions : 64;
+        tj.N = g->n; tj.tiles_p = (int)(((int64_t)g->h * g->w + per_tile - 1) / per_tile); tj.rows = (int64_t)g->n * g->h;
         transpose_blocks = (int64_t)tj.tiles_p * g->n * CB;
         if (rowpack) {
             tj.pack_KW = q->shape.kw; tj.OW = OW; tj.stride_w = g->stride_w; tj.pad_w = g->pad_w;

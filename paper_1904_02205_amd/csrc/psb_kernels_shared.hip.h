@@ -198,7 +198,8 @@ struct TransposeJob {
     int C, H, W, C_pad;
     int8_t* xt;
     int N;
-    int tiles_p;          // ceil(H * W / 64)
+    int tiles_p;          // tiles per image plane: ceil(H * W / 64), or / 256 with `wide`
+    int wide;             // H * W and the address of x are multiples of 4: the copy moves 32-bit words
     int64_t rows;         // N * H
     // row packing (pack_KW > 0): xt[n][iy][ox][kw * C + c] = x[n][c][iy][ox * stride_w - pad_w + kw], zero outside
     // the row and in the unused slots; one thread per (n, iy, ox)
@@ -262,6 +263,61 @@ __device__ __forceinline__ void channels_last_tile(const TransposeJob& j, int64_
     }
 }
 
+// The same copy for image planes whose size and address are multiples of 4 bytes (TransposeJob::wide): a tile is
+// 32 channels x 256 consecutive plane positions.  A thread loads four positions of four channels as four 32-bit
+// words (a wave reads 256 consecutive bytes of each channel), transposes the 4 x 4 bytes in registers and writes
+// four words of four channels each into a position-major LDS tile; after the barrier it owns one position and
+// moves its 32 channel bytes with two 16-byte reads and two 16-byte stores.
+constexpr int kWideTilePositions = 256;
+constexpr int kWideTileRow = 48;            // bytes per position in LDS: 32 used, padded to spread the banks
+__device__ __forceinline__ void channels_last_tile_wide(const TransposeJob& j, int64_t tile_index, int8_t* tile)
+{
+    const uint32_t plane = (uint32_t)(j.H * j.W);
+    const uint32_t p0 = (uint32_t)(tile_index % j.tiles_p) * (uint32_t)kWideTilePositions;
+    const int n = (int)((tile_index / j.tiles_p) % j.N);
+    const int c0 = (int)(tile_index / ((int64_t)j.tiles_p * j.N)) * 32;
+    uint32_t w[2][4];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int unit = r * 256 + (int)threadIdx.x;       // (channel quad, position quad)
+        const int cq = unit >> 6;
+        const uint32_t pos = p0 + 4u * (uint32_t)(unit & 63);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = c0 + cq * 4 + i;
+            w[r][i] = 0;
+            if (c < j.C && pos < plane)
+                w[r][i] = *reinterpret_cast<const uint32_t*>(j.x + ((int64_t)n * j.C + c) * plane + pos);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int unit = r * 256 + (int)threadIdx.x;
+        const int cq = unit >> 6, pq = unit & 63;
+        // byte b of w[r][i] = channel i, position b  ->  byte i of out[b]
+        const uint32_t t0 = __builtin_amdgcn_perm(w[r][1], w[r][0], 0x05010400u);
+        const uint32_t t1 = __builtin_amdgcn_perm(w[r][3], w[r][2], 0x05010400u);
+        const uint32_t t2 = __builtin_amdgcn_perm(w[r][1], w[r][0], 0x07030602u);
+        const uint32_t t3 = __builtin_amdgcn_perm(w[r][3], w[r][2], 0x07030602u);
+        const uint32_t out[4] = {__builtin_amdgcn_perm(t1, t0, 0x05040100u), __builtin_amdgcn_perm(t1, t0, 0x07060302u),
+                                 __builtin_amdgcn_perm(t3, t2, 0x05040100u), __builtin_amdgcn_perm(t3, t2, 0x07060302u)};
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            *reinterpret_cast<uint32_t*>(tile + (pq * 4 + b) * kWideTileRow + cq * 4) = out[b];
+    }
+    __syncthreads();
+    const uint32_t pos = p0 + threadIdx.x;
+    if (pos < plane) {
+        const uint4 lo = *reinterpret_cast<const uint4*>(tile + (int)threadIdx.x * kWideTileRow);
+        const uint4 hi = *reinterpret_cast<const uint4*>(tile + (int)threadIdx.x * kWideTileRow + 16);
+        const uint32_t iy = pos / (uint32_t)j.W, ix = pos - iy * (uint32_t)j.W;
+        const int64_t row = (int64_t)n * j.H + iy;
+        uint4* dst = reinterpret_cast<uint4*>(j.xt + ((row * (j.C_pad >> 5) + (c0 >> 5)) * j.W + ix) * 32);
+        dst[0] = lo;
+        dst[1] = hi;
+    }
+}
+
 // The digit planes of several layers in one launch (a network pass samples all its filters at once): job i owns
 // the workgroups [first_block[i], first_block[i + 1]); entries past the last job hold 0xFFFFFFFF.
 constexpr int kMaxBatchJobs = 32;
@@ -289,14 +345,16 @@ __global__ void __launch_bounds__(256) k_sample_filter(const FilterJob j)
 // the rest transpose the activations.  The two jobs are independent of each other.
 __global__ void __launch_bounds__(256) k_shared_prologue(const FilterJob f, const TransposeJob t, unsigned filter_blocks)
 {
-    __shared__ int8_t tile[32][64 + 4];
+    __shared__ __align__(16) int8_t tile[kWideTilePositions * kWideTileRow];
     if (blockIdx.x < filter_blocks) {        // uniform over the workgroup
         if (f.planes) sample_planes_block(f, blockIdx.x);
         else sample_filter_thread(f, (int64_t)blockIdx.x * 256 + threadIdx.x);
     } else if (t.pack_KW)
         row_pack_block(t, (int64_t)(blockIdx.x - filter_blocks));
+    else if (t.wide)
+        channels_last_tile_wide(t, (int64_t)(blockIdx.x - filter_blocks), tile);
     else
-        channels_last_tile(t, (int64_t)(blockIdx.x - filter_blocks), tile);
+        channels_last_tile(t, (int64_t)(blockIdx.x - filter_blocks), reinterpret_cast<int8_t(*)[64 + 4]>(tile));
 }
 
 // present[v] = 1 for every clamped budget value v that occurs in the maps

@@ -182,6 +182,25 @@ def test_progressive_on_a_large_image(psb, orc):
     assert np.array_equal(acc, ref)
 
 
+def test_activation_pointer_alignment(psb, orc):
+    """The layout copy moves 32-bit words when the image plane and the pointer allow it: same integers at any
+    byte offset of the input tensor, for planes that are and are not multiples of four bytes."""
+    import torch
+    rng = np.random.default_rng(983)
+    for hw in ((20, 18), (9, 7)):
+        L = _layer(rng, 2, 40, 48, hw, 3, pad=1, S=8)
+        qo, qg = helpers.oracle_quantize(orc, L), helpers.gpu_quantize(psb, L)
+        ref, over, _ = helpers.oracle_layer(orc, L, qo, shared=True)
+        assert over == 0
+        flat = torch.from_numpy(L.x).reshape(-1)
+        for offset in (0, 1, 2, 4):
+            buf = torch.zeros(flat.numel() + 8, dtype=torch.int8, device="cuda")
+            buf[offset:offset + flat.numel()] = flat.cuda()
+            x = buf[offset:offset + flat.numel()].view(L.x.shape)
+            acc = psb.conv2d(qg, x, L.S, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id, shared=True)
+            assert np.array_equal(acc.cpu().numpy(), ref), (hw, offset)
+
+
 def test_progressive_depthwise(psb, orc):
     """Budget segments through the 3 x 3 depthwise kernel: masked, accumulating launches; refinement in two calls."""
     rng = np.random.default_rng(982)
