@@ -232,6 +232,34 @@ def test_progressive_constant_map_equals_plain_call(psb):
     assert np.array_equal(plain, prog)
 
 
+def test_several_pixels_per_wave_and_ticket(psb, orc):
+    """Large layers hand a wave several pixels per ticket; here the count is forced (benchmark override of the
+    channel-lane launcher) on layers small enough for the oracle, with pixel counts that leave a ragged last group:
+    the kernel variants for a fixed number of generator blocks, 7-bit uniforms, and per-pixel budgets."""
+    import os
+    rng = np.random.default_rng(260)
+    cases = [(_layer(rng, 3, 20, 70, (9, 11), 3, pad=1, S=8), 23, False),           # 297 pixels, 3 chunks, 2 channel blocks
+             (_layer(rng, 1, 24, 64, (7, 9), 1, S=16), 23, False),                    # single chunk: fused epilogue
+             (_layer(rng, 2, 12, 64, (10, 7), 3, pad=1, S=16, s_max=16), 4, False),   # 7-bit uniforms, one block
+             (_layer(rng, 2, 16, 64, (9, 9), 3, pad=1, S=32, s_max=32), 23, True)]    # per-pixel ranges
+    psb.set_mapping(2)
+    try:
+        for L, prob_bits, prog in cases:
+            oh, ow = L.out_hw
+            to = rng.choice([0, 2, 5, 8, 16, 32], size=(L.x.shape[0], oh, ow)).astype(np.uint8) if prog else None
+            qo = helpers.oracle_quantize(orc, L, prob_bits=prob_bits)
+            qg = helpers.gpu_quantize(psb, L, prob_bits=prob_bits)
+            ref, over, _ = helpers.oracle_layer(orc, L, qo, budget_to=to)
+            assert over == 0
+            for ppw in (1, 2, 3, 5, 64):
+                os.environ["PSB_OC_PPW"] = str(ppw)
+                acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to)
+                assert np.array_equal(acc, ref), (L.name, prob_bits, ppw)
+    finally:
+        os.environ.pop("PSB_OC_PPW", None)
+        psb.set_mapping(psb.MAPPING_AUTO)
+
+
 # ------------------------------------------------------------------ fp32 rescale
 
 @pytest.mark.parametrize("mapping", [1, 2, 3])
