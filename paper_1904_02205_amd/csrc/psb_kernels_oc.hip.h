@@ -341,38 +341,76 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
         __syncthreads();
 
         const int oc = ocb * 64 + lane;
+        // This lane's tap of the chunk (a chunk has at most 64 taps: one per lane) is the same for every pixel of
+        // the ticket.  The activation of the NEXT pixel is requested before the current one is sampled, so that the
+        // load's latency falls into the sampling loop.
+        static_assert(kOcMaxTaps <= 64, "one tap per lane");
+        const bool has_tap = lane < kn;
+        const int2 info = has_tap ? tap_tab[lane] : make_int2(0, 0);
+        struct Pixel { bool valid; int ox, oy, n; };
+        auto locate = [&](int pp) {
+            const int64_t pix = ((int64_t)pgroup * ppw + pp) * WAVES + wave;       // wave-uniform
+            Pixel q;
+            q.valid = pix < npix;
+            const uint32_t pc = q.valid ? (uint32_t)pix : 0u;      // the number of outputs fits 32 bits
+            const uint32_t row = pc / (uint32_t)p.OW;
+            q.ox = (int)(pc - row * (uint32_t)p.OW);
+            q.n = (int)(row / (uint32_t)p.OH);
+            q.oy = (int)(row - (uint32_t)q.n * (uint32_t)p.OH);
+            return q;
+        };
+        auto request = [&](const Pixel& q) {
+            int32_t xv = 0;
+            const int iy0 = q.oy * p.stride_h - p.pad_h, ix0 = q.ox * p.stride_w - p.pad_w;
+            const int iy = iy0 + (info.y & 0xFFFF), ix = ix0 + (info.y >> 16);
+            if (q.valid && has_tap && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W)
+                xv = p.x[((int64_t)q.n * p.C * p.H + iy0) * p.W + ix0 + info.x];
+            return xv;
+        };
+        // the pixel's sample range travels with its activation (a load between two pixels would make the wave wait
+        // for the next pixel's activation as well); kernels for a fixed block count have no budget maps
+        auto budget = [&](const Pixel& q, int pp, int& to_raw, int& from_raw) {
+            if constexpr (FIXED_NB == 0) {
+                const int64_t pix = ((int64_t)pgroup * ppw + pp) * WAVES + wave;
+                to_raw = (q.valid && p.budget_to) ? (int)p.budget_to[pix] : p.S;
+                from_raw = (q.valid && p.budget_from) ? (int)p.budget_from[pix] : 0;
+            }
+        };
+        Pixel next = locate(0);
+        int32_t xv_next = request(next);
+        int to_next = 0, from_next = 0;
+        budget(next, 0, to_next, from_next);
         for (int pp = 0; pp < ppw; ++pp) {
-        const int64_t pix = ((int64_t)pgroup * ppw + pp) * WAVES + wave;
-        if (pix < npix) {   // wave-uniform
-            const int ox = (int)(pix % p.OW);
-            const int oy = (int)((pix / p.OW) % p.OH);
-            const int n = (int)(pix / ((int64_t)p.OW * p.OH));
+        const Pixel me = next;
+        const int32_t xv = xv_next;
+        const int to_raw = to_next, from_raw = from_next;
+        if (pp + 1 < ppw) {
+            next = locate(pp + 1);
+            xv_next = request(next);
+            budget(next, pp + 1, to_next, from_next);
+        }
+        if (me.valid) {   // wave-uniform
+            const int ox = me.ox, oy = me.oy, n = me.n;
 
-            int to = p.budget_to ? (int)p.budget_to[pix] : p.S;
-            to = min(to, p.s_max);
-            int from = p.budget_from ? (int)p.budget_from[pix] : 0;
-            from = min(from, to);
-            to = (int)uniform_u32((uint32_t)to);
-            from = (int)uniform_u32((uint32_t)from);
+            int to, from;
+            if constexpr (FIXED_NB > 0) {
+                to = min(p.S, p.s_max);
+                from = 0;
+            } else {
+                to = min(to_raw, p.s_max);
+                from = min(from_raw, to);
+                to = (int)uniform_u32((uint32_t)to);
+                from = (int)uniform_u32((uint32_t)from);
+            }
 
             const uint32_t o = (uint32_t)((((int64_t)n * p.OC + oc) * p.OH + oy) * p.OW + ox);
             int32_t total = 0;
 
             if (to > from) {
-                // gather this pixel's taps of the chunk and keep the non-zero ones
-                const int iy0 = oy * p.stride_h - p.pad_h;
-                const int ix0 = ox * p.stride_w - p.pad_w;
-                const int8_t* xb = p.x + (int64_t)n * p.C * p.H * p.W + (int64_t)iy0 * p.W + ix0;
+                // keep the non-zero ones of this pixel's taps of the chunk
                 int cnt = 0;
-                for (int t0 = 0; t0 < kn; t0 += 64) {
-                    const int t = t0 + lane;
-                    int32_t xv = 0;
-                    if (t < kn) {
-                        const int2 info = tap_tab[t];
-                        const int iy = iy0 + (info.y & 0xFFFF);
-                        const int ix = ix0 + (info.y >> 16);
-                        if ((unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W) xv = xb[info.x];
-                    }
+                {
+                    const int t = lane;
                     const unsigned long long mask = __ballot(xv != 0);
                     const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
                                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
@@ -543,7 +581,7 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
     {
         const int64_t per_wg = pixel_groups * n_chunks * n_ocb / ((int64_t)cus * wg_per_cu);
         if (per_wg >= 128) ppw = 4;
-        else if (per_wg >= 64) ppw = 2;
+        else if (per_wg >= 32) ppw = 2;
         if (const char* v = std::getenv("PSB_OC_PPW")) { const int t = std::atoi(v); if (t >= 1 && t <= 64) ppw = t; }
     }
     pixel_groups = (npix + (int64_t)waves * ppw - 1) / ((int64_t)waves * ppw);
