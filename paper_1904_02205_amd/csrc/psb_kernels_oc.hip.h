@@ -574,14 +574,21 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
         if (pixel_groups * n_chunks * n_ocb >= (int64_t)cus * wg_per_cu || max_taps <= 16) break;
         max_taps /= 2;
     }
-    // Pixels per wave and ticket: large layers take four (fewer draws, barriers and restagings per product:
-    // 0.66 -> 0.69 of the roofline over the 21 ResNet-18-shaped layers; 8 and 16 measured the same as 4), as long
-    // as every resident workgroup still draws some thirty tickets, so that the end of the launch stays balanced.
+    // Pixels per wave and ticket.  A ticket costs a draw, a restaging on small layers, three barriers and one
+    // exposed activation load whatever it holds, so a ticket should hold some 10 us of sampling per wave (estimated
+    // at half of the chunk's taps per pixel and 86 ns per generator call), which products of one or two calls only
+    // reach with several pixels; large layers take four in any case (config 4: 0.66 -> 0.69 of the roofline;
+    // 8 and 16 measured like 4).  Never so many that a resident workgroup would draw fewer than 1.5 tickets on
+    // average (config 2 with its 7 tickets per workgroup and 11 us per ticket keeps one pixel: two measured -4 %;
+    // with 7-bit uniforms, a quarter of the calls, it takes four: +16 %).
     int ppw = 1;
     {
-        const int64_t per_wg = pixel_groups * n_chunks * n_ocb / ((int64_t)cus * wg_per_cu);
-        if (per_wg >= 128) ppw = 4;
-        else if (per_wg >= 32) ppw = 2;
+        const double per_wg = (double)(pixel_groups * n_chunks * n_ocb) / ((double)cus * wg_per_cu);
+        const int calls = p.budget_to ? 1 : (p.S + per_block - 1) / per_block;
+        const double ticket_us = 0.5 * kc * calls * 0.086;
+        const int want = (int)std::min(8.0, std::max(1.0, std::floor(11.0 / ticket_us + 0.5)));
+        ppw = std::max(want, per_wg >= 128 ? 4 : per_wg >= 32 ? 2 : 1);
+        while (ppw > 1 && per_wg / ppw < 1.5) --ppw;
         if (const char* v = std::getenv("PSB_OC_PPW")) { const int t = std::atoi(v); if (t >= 1 && t <= 64) ppw = t; }
     }
     pixel_groups = (npix + (int64_t)waves * ppw - 1) / ((int64_t)waves * ppw);
