@@ -259,9 +259,9 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
     }
 }
 
-// Persistent kernel.  A ticket is one (channel block, tap chunk, group of WAVES pixels);
-// tickets are numbered so that consecutive tickets are consecutive pixel groups of the same
-// (channel block, chunk).  Workgroups draw tickets from a device counter until none is left:
+// Persistent kernel.  A ticket is one (channel block, tap chunk, group of WAVES * ppw pixels:
+// ppw per wave); tickets are numbered so that consecutive tickets are consecutive pixel groups
+// of the same (channel block, chunk).  Workgroups draw tickets from a device counter until none is left:
 // the grid is only as large as the chip can hold at once, there is no launch gap between
 // work items, and the tail at the end of the kernel is at most one ticket long.
 //   sched[0] = next ticket, sched[1] = number of workgroups that have finished.  Both are 0
