@@ -266,8 +266,9 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
 // work items, and the tail at the end of the kernel is at most one ticket long.
 //   sched[0] = next ticket, sched[1] = number of workgroups that have finished.  Both are 0
 //   before the launch; the last workgroup to finish sets them back to 0.
+// FIXED_P7: the layer uses 7-bit uniforms (prob_bits < 23); each kernel is compiled for one of the two.
 // FIXED_NB > 0: every pixel draws generator blocks 0 .. FIXED_NB-1 completely (a call with one S everywhere that is
-// a whole number of blocks; FIXED_P7: 7-bit uniforms).  Only that path of the sampling loop is compiled then, which
+// a whole number of blocks).  Only that path of the sampling loop is compiled then, which
 // takes 76 vector registers instead of 110 and measured 3 % faster than the kernel that can do everything.
 // ppw: pixels per wave and ticket.
 template <int WAVES, int FIXED_NB = 0, bool FIXED_P7 = false>
@@ -433,8 +434,8 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
                     h.y2k = lo_b1 ^ key.k0[2];
 
                     // generator blocks serve 4 samples (32-bit uniforms) or 16 (7-bit uniforms)
-                    const bool p7 = p.prob_bits < 23;
-                    const int lg = p7 ? 4 : 2;
+                    constexpr bool p7 = FIXED_P7;
+                    constexpr int lg = p7 ? 4 : 2;
                     const int j0 = from >> lg;
                     const int nb = ((to + (1 << lg) - 1) >> lg) - j0;
                     const bool full = ((from | to) & ((1 << lg) - 1)) == 0;
@@ -443,13 +444,13 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
     total = process_list<NB_, VALID_, P7_>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key)
                     if constexpr (FIXED_NB > 0) {
                         PSB_LIST(FIXED_NB, 4, FIXED_P7);
-                    } else
-                    if (p7) {
+                    } else if constexpr (p7) {
                         if (full && nb == 1) PSB_LIST(1, 4, true);
                         else if (full && nb == 2) PSB_LIST(2, 4, true);
                         else if (nb == 1) PSB_LIST(1, 0, true);
                         else PSB_LIST(0, 0, true);
-                    } else if (full) {
+                    } else {
+                    if (full) {
                         switch (nb) {
                             case 1: PSB_LIST(1, 4, false); break;
                             case 2: PSB_LIST(2, 4, false); break;
@@ -468,6 +469,7 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
                         PSB_LIST(1, 0, false);
                     } else {
                         PSB_LIST(0, 0, false);
+                    }
                     }
 #undef PSB_LIST
                 }
@@ -608,12 +610,14 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
 #define PSB_OC_LAUNCH(WAVES_, NB_, P7_)                                                                           \
     hipLaunchKernelGGL((k_layer_oc_lane<WAVES_, NB_, P7_>), dim3((unsigned)grid), dim3(WAVES_ * 64), 0, stream, p,   \
                        n_chunks, kc, (uint32_t)pixel_groups, (uint32_t)n_tickets, sched, ppw)
-    if (waves == 8) PSB_OC_LAUNCH(8, 0, false);
-    else if (p7) {
+    if (waves == 8) {
+        if (p7) PSB_OC_LAUNCH(8, 0, true);
+        else PSB_OC_LAUNCH(8, 0, false);
+    } else if (p7) {
         switch (fixed_nb) {
             case 1: PSB_OC_LAUNCH(4, 1, true); break;
             case 2: PSB_OC_LAUNCH(4, 2, true); break;
-            default: PSB_OC_LAUNCH(4, 0, false); break;
+            default: PSB_OC_LAUNCH(4, 0, true); break;
         }
     } else {
         switch (fixed_nb) {
