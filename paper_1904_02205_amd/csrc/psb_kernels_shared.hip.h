@@ -210,20 +210,30 @@ __device__ __forceinline__ void row_pack_block(const TransposeJob& j, int64_t bl
 {
     const int64_t i = block * 256 + threadIdx.x;          // (n * H + iy) * OW + ox
     if (i >= j.rows * j.OW) return;
-    const int ox = (int)(i % j.OW);
-    const int64_t row = i / j.OW;
-    const int n = (int)(row / j.H), iy = (int)(row - (int64_t)n * j.H);
-    uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const uint32_t i32 = (uint32_t)i;                     // rows * OW is below 2^31 (xt has 32 bytes per element)
+    const uint32_t row = i32 / (uint32_t)j.OW;
+    const int ox = (int)(i32 - row * (uint32_t)j.OW);
+    const int n = (int)(row / (uint32_t)j.H), iy = (int)(row - (uint32_t)n * (uint32_t)j.H);
     const int ix0 = ox * j.stride_w - j.pad_w;
-    for (int kw = 0; kw < j.pack_KW; ++kw) {
+    // All 32 slots in straight-line code: slot s = kw * C + c; a slot outside the row (or beyond kw * C) reads
+    // element 0 of the tensor instead and is masked, so the loads do not wait for each other.
+    const uint32_t plane = (uint32_t)(j.H * j.W);
+    const uint32_t base = ((uint32_t)n * (uint32_t)j.C * (uint32_t)j.H + (uint32_t)iy) * (uint32_t)j.W;   // x[n][0][iy][0]
+    const int n_slots = j.pack_KW * j.C;
+    uint32_t v[32];
+    int kw = 0, c = 0;                                    // uniform, stepped on the scalar unit
+#pragma unroll
+    for (int s = 0; s < 32; ++s) {
         const int ix = ix0 + kw;
-        if ((unsigned)ix >= (unsigned)j.W) continue;
-        for (int c = 0; c < j.C; ++c) {
-            const int slot = kw * j.C + c;
-            const uint32_t v = (uint8_t)j.x[(((int64_t)n * j.C + c) * j.H + iy) * j.W + ix];
-            w[slot >> 2] |= v << (8 * (slot & 3));
-        }
+        const bool ok = (s < n_slots) & ((unsigned)ix < (unsigned)j.W);
+        const uint32_t at = ok ? base + (uint32_t)c * plane + (uint32_t)ix : 0u;
+        const uint32_t b = (uint8_t)j.x[at];
+        v[s] = ok ? b : 0u;
+        if (++c == j.C) { c = 0; ++kw; }
     }
+    uint32_t w[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) w[q] = v[4 * q] | (v[4 * q + 1] << 8) | (v[4 * q + 2] << 16) | (v[4 * q + 3] << 24);
     uint4* dst = reinterpret_cast<uint4*>(j.xt + i * 32);
     dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
     dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
