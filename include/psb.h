@@ -301,6 +301,18 @@ int psb_conv2d_shared_requant_blocked(const psb_weights_t* q, const int8_t* x_de
 int psb_shared_prepare_filters(const psb_weights_t* const* handles, int32_t n, int32_t S, const uint64_t* seeds,
                                const uint32_t* layer_ids, void* hip_stream);
 
+/* Budget values of a pass, told in advance [Sect. 4.5: the two-stage scheme has two].  A shared-filter call with a
+ * budget map cuts the sample axis at every value that occurs in the map; by default it finds those values itself,
+ * which costs a read-back and a stream synchronisation per call.  After psb_shared_budget_levels(levels, n) the
+ * calling thread's shared-filter calls with budget maps take the n values of the host array `levels` instead
+ * (clamped to the handle's s_max; 0 is added when there is no budget_from map), issue no synchronisation, and can
+ * be captured into a HIP graph.  EVERY value that occurs in a call's maps (budget_to and budget_from, after
+ * clamping) must be among them: a pixel whose budget is missing silently receives the samples of the next lower
+ * listed value only.  Listed values that do not occur cost one filter sampling and one empty launch each.
+ * n = 0 (levels may be NULL) restores the default.  Host only.  Errors: NULL (n > 0 without levels), SHAPE (n < 0
+ * or n > 256). */
+int psb_shared_budget_levels(const uint8_t* levels_host, int32_t n);
+
 int psb_requantize(const float* y_dev, const float* res_f32_dev, const int8_t* res_i8_dev, float res_step,
                    int32_t relu, float inv_step, int32_t lo, int32_t hi, int64_t n, int8_t* x_dev, void* hip_stream);
 int psb_maxpool2d_i8(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, int32_t kh, int32_t kw,

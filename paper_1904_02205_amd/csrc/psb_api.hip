@@ -66,6 +66,9 @@ struct psb_weights {
 namespace {
 
 thread_local int tl_last_device_error = 0;
+// budget values announced by psb_shared_budget_levels (n = 0: none, the calls read them back from their maps)
+thread_local int tl_levels_n = 0;
+thread_local uint8_t tl_levels[256];
 int g_mapping = 0;
 
 // optional timing of the sampling kernels (psb_profile_enable / psb_profile_read)
@@ -476,15 +479,19 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
 
     // per-pixel budgets: the distinct clamped budget values cut the sample axis into segments
     uint32_t present[256];
-    PSB_HIP_TRY(hipMemsetAsync(ws->present_dev, 0, sizeof(present), stream));
-    {
+    if (tl_levels_n > 0) {                          // announced by the caller: nothing to read back
+        std::memset(present, 0, sizeof(present));
+        for (int i = 0; i < tl_levels_n; ++i) present[std::min<int>(tl_levels[i], q->s_max)] = 1u;
+        if (!budget_from) present[0] = 1u;
+    } else {
+        PSB_HIP_TRY(hipMemsetAsync(ws->present_dev, 0, sizeof(present), stream));
         const int blocks = (int)std::min<int64_t>((npix + 255) / 256, 1024);
         hipLaunchKernelGGL(psb::k_budget_levels, dim3(blocks), dim3(256), 0, stream, budget_to, budget_from, npix,
                            q->s_max, ws->present_dev);
         PSB_HIP_TRY(hipGetLastError());
+        PSB_HIP_TRY(hipMemcpyAsync(present, ws->present_dev, sizeof(present), hipMemcpyDeviceToHost, stream));
+        PSB_HIP_TRY(hipStreamSynchronize(stream));
     }
-    PSB_HIP_TRY(hipMemcpyAsync(present, ws->present_dev, sizeof(present), hipMemcpyDeviceToHost, stream));
-    PSB_HIP_TRY(hipStreamSynchronize(stream));
     if (!budget_from) {
         rc = zero_acc();
         if (rc != PSB_OK) return rc;
@@ -815,6 +822,15 @@ int psb_conv2d_shared_requant_blocked(const psb_weights_t* q, const int8_t* x_de
     r.res_blocked = (layout & PSB_BLOCKED_RES) != 0 && rq->res_i8_dev;
     return launch_shared(q, x_dev, geom, S, nullptr, nullptr, seed, layer_id, nullptr, y_dev, mult_dev, bias_dev,
                          (hipStream_t)hip_stream, &r, layout);
+}
+
+int psb_shared_budget_levels(const uint8_t* levels_host, int32_t n)
+{
+    if (n < 0 || n > 256) return PSB_ERR_SHAPE;
+    if (n > 0 && !levels_host) return PSB_ERR_NULL;
+    for (int i = 0; i < n; ++i) tl_levels[i] = levels_host[i];
+    tl_levels_n = n;
+    return PSB_OK;
 }
 
 int psb_shared_prepare_filters(const psb_weights_t* const* handles, int32_t n, int32_t S, const uint64_t* seeds,

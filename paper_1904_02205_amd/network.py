@@ -136,11 +136,19 @@ class ResNet18:
                    bias=self.bias[i], shared=True)
         return logits
 
-    def forward(self, S=8, budget=None, s_fc=None, shared=False, collect=None, fused=True, chain=None):
+    def forward(self, S=8, budget=None, s_fc=None, shared=False, collect=None, fused=True, chain=None, levels=None):
         """Logits float32 [batch, classes].  collect: optional list that receives every int8 activation tensor.
         fused: requantisation in the epilogue of the layer kernels (default) or as separate glue kernels; the
         activations are the same integers either way.  chain: run a shared-filter pass with a uniform sample count
-        as one chain (see _forward_chain); by default whenever that applies."""
+        as one chain (see _forward_chain); by default whenever that applies.  levels: the values the budget map
+        holds, if the caller knows them (nearest-pixel resampling only ever drops values): a shared-filter pass
+        then announces them to the library once instead of every layer reading them back from its map."""
+        if budget is not None and shared and levels is not None:
+            psb.shared_budget_levels(levels)
+            try:
+                return self.forward(S, budget, s_fc, shared, collect, fused, chain, None)
+            finally:
+                psb.shared_budget_levels(None)
         can_chain = shared and fused and budget is None and (s_fc is None or s_fc == S) and not self.record_inputs
         if chain is None:
             chain = can_chain
@@ -213,4 +221,4 @@ class ResNet18:
         self.forward(S=s_lo, shared=shared, collect=acts)
         last = acts[-2]                                  # output of the last residual block
         _, _, budget = psb.attention_budget(last, float(np.float32(rs.STEP_BLOCK)), s_lo, s_hi)
-        return self.forward(budget=budget, s_fc=s_hi, shared=shared), budget
+        return self.forward(budget=budget, s_fc=s_hi, shared=shared, levels=(s_lo, s_hi)), budget

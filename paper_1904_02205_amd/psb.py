@@ -21,7 +21,7 @@ MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE, MAPPING_PRODUCT_LIST = 0
 SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
            "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
-           "psb_conv2d_requant", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
+           "psb_conv2d_requant", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_shared_budget_levels", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
            "psb_attention_budget", "psb_last_device_error", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
            "psb_profile_read"]
 
@@ -87,6 +87,7 @@ def lib():
         L.psb_conv2d_shared_requant_blocked.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, u64, u32, vp, vp, vp,
                                                         C.POINTER(Requant), vp, i32, vp]
         L.psb_shared_prepare_filters.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.psb_shared_budget_levels.argtypes = [vp, i32]
         L.psb_conv2d_requant.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, vp, u64, u32, vp, vp, vp, vp,
                                          C.POINTER(Requant), vp, i32, vp]
         L.psb_requantize.argtypes = [vp, vp, vp, f32, i32, f32, i32, i32, C.c_int64, vp, vp]
@@ -319,6 +320,15 @@ def shared_prepare_filters(handles, S, seeds, layer_ids):
     sd = (C.c_uint64 * n)(*[int(v) for v in seeds])
     li = (C.c_uint32 * n)(*[int(v) for v in layer_ids])
     _check(lib().psb_shared_prepare_filters(hs, n, S, sd, li, _stream()), "psb_shared_prepare_filters")
+
+
+def shared_budget_levels(levels=None):
+    """Announce the budget values of the coming shared-filter calls with budget maps (an iterable of ints; every
+    value that occurs in the maps must be listed), so that they need not read them back; None or () restores the
+    default."""
+    vals = sorted({int(v) for v in levels}) if levels is not None else []
+    arr = (C.c_uint8 * max(1, len(vals)))(*vals)
+    _check(lib().psb_shared_budget_levels(arr if vals else None, len(vals)), "psb_shared_budget_levels")
 
 
 # ---- glue between layers ---------------------------------------------------------------------------------

@@ -96,6 +96,13 @@ def test_later_entry_points_validate_on_the_host(psb):
     assert pf(P, 0, 4, P, P, None) == psb.ERR_SHAPE
     handles = (C.c_void_p * 1)(None)
     assert pf(handles, 1, 4, P, P, None) == psb.ERR_NULL                             # a NULL handle in the list
+    # announced budget values (host-only state of the calling thread)
+    lv = L.psb_shared_budget_levels
+    assert lv(None, 1) == psb.ERR_NULL
+    assert lv(None, -1) == psb.ERR_SHAPE and lv(None, 257) == psb.ERR_SHAPE
+    two = (C.c_uint8 * 2)(8, 16)
+    assert lv(two, 2) == psb.OK
+    assert lv(None, 0) == psb.OK                                                      # back to the default
     # requantize
     rq = L.psb_requantize
     for inv in (-1.0, float("nan")):

@@ -201,6 +201,50 @@ def test_activation_pointer_alignment(psb, orc):
             assert np.array_equal(acc.cpu().numpy(), ref), (hw, offset)
 
 
+def test_announced_budget_levels(psb, orc):
+    """Budget values announced by the caller instead of read back from the map: same integers (exact set, a
+    superset, values above s_max), for the matrix-core and the direct kernel, with and without a budget_from map;
+    without the read-back the call can be captured into a HIP graph."""
+    import torch
+    rng = np.random.default_rng(984)
+    for groups in (1, 4):
+        L = _layer(rng, 2, 16, 40, (12, 9), 3, pad=1, groups=groups, S=16, s_max=16)
+        oh, ow = L.out_hw
+        to = rng.choice([4, 8, 16], size=(2, oh, ow)).astype(np.uint8)
+        qo, qg = helpers.oracle_quantize(orc, L), helpers.gpu_quantize(psb, L)
+        ref, over, _ = helpers.oracle_layer(orc, L, qo, budget_to=to, shared=True)
+        assert over == 0
+        try:
+            for levels in ((4, 8, 16), (16, 4, 8, 2, 12), (4, 8, 200)):          # 200 clamps to s_max = 16
+                psb.shared_budget_levels(levels)
+                acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, shared=True)
+                assert np.array_equal(acc, ref), (groups, levels)
+            first = np.minimum(to, 8).astype(np.uint8)
+            a1, _ = helpers.gpu_layer(psb, L, qg, budget_to=first, shared=True)
+            a2, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, budget_from=first, acc_in=a1, shared=True)
+            assert np.array_equal(a2, ref)
+            # captured: replays give the same integers
+            x = torch.from_numpy(L.x).cuda()
+            bt = torch.from_numpy(to).cuda()
+            acc_t = torch.zeros((2, 40, oh, ow), dtype=torch.int32, device="cuda")
+            psb.conv2d_progressive(qg, x, bt, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id, acc=acc_t,
+                                   shared=True)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                psb.conv2d_progressive(qg, x, bt, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id,
+                                       acc=acc_t, shared=True)
+            for _ in range(3):
+                acc_t.fill_(-1)
+                graph.replay()
+                torch.cuda.synchronize()
+                assert np.array_equal(acc_t.cpu().numpy(), ref)
+        finally:
+            psb.shared_budget_levels(None)
+    acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, shared=True)       # default path again
+    assert np.array_equal(acc, ref)
+
+
 def test_progressive_depthwise(psb, orc):
     """Budget segments through the 3 x 3 depthwise kernel: masked, accumulating launches; refinement in two calls."""
     rng = np.random.default_rng(982)
