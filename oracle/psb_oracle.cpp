@@ -599,8 +599,10 @@ extern "C" int psbo_budget_resample(const uint8_t* in, int32_t n, int32_t h, int
  *     h_xy = sum_c - softmax(a_xyc) * log(softmax(a_xyc)),
  * thresholded at the mean entropy of the image: pixels above the mean are the
  * regions that get the larger sample count.  a = (double)act * step.
- * Evaluated in binary64; the entropy handed out, the mean and the comparison
- * are binary32 (the precision the GPU kernel decides in).
+ * Sect. 4.5 fixes no precision.  Reading: the entropy map and its mean are
+ * binary32 tensors, like every tensor of the paper's experiments (Sect. 4.1
+ * "Setup": float32), so the threshold compares binary32 values; each of them is
+ * one rounding of a binary64 evaluation.
  * ------------------------------------------------------------------------- */
 extern "C" int psbo_attention_budget(const int8_t* act, float step, int32_t n, int32_t c, int32_t h, int32_t w,
                                      uint8_t budget_lo, uint8_t budget_hi, float* entropy, float* mean,

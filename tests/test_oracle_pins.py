@@ -555,3 +555,88 @@ def test_discretised_mean_converges_to_quantised_weights(orc):
     a, _ = orc.linear(q, x, S, seed=3, layer_id=2)
     b, _, _ = orc.conv2d(q, (OC, K, 1, 1, 1), x.reshape(B, K, 1, 1), S=S, seed=3, layer_id=2)
     assert np.array_equal(a, b.reshape(B, OC))
+
+
+# ------------------------------------------------------------------ counter keying of the convolution
+
+def _conv_by_hand(orc, q, wshape, x, stride, pad, seed, layer, outputs, ranges, key_o=None, key_k=None, p7=False):
+    """Accumulators of selected outputs (n, oc, oy, ox), rebuilt in Python from the pinned uniforms: one
+    independent bit per (output element, tap, sample) (Sect. 3.1, shift form after Eq. "numbersystem:simulation";
+    Sect. 2: one random bit per shift), B = [u / 2^32 < p] (7-bit uniforms: u7 / 128), term sigma x 2^(shift + B).
+    key_o / key_k replace the keying functions (used to show that a transposed index would be noticed)."""
+    OC, C, KH, KW, G = wshape
+    N, _, H, W = x.shape
+    Cg, OCg = C // G, OC // G
+    OH, OW = (H + 2 * pad[0] - KH) // stride[0] + 1, (W + 2 * pad[1] - KW) // stride[1] + 1
+    if key_o is None:
+        key_o = lambda n, oc, oy, ox: ((n * OC + oc) * OH + oy) * OW + ox            # flat NCHW output index
+    if key_k is None:
+        key_k = lambda ci, kh, kw: (ci * KH + kh) * KW + kw                          # flat tap index in the group
+    draw, denom = (orc.uniform7, 128.0) if p7 else (orc.uniform, 4294967296.0)
+    res = []
+    for (n, oc, oy, ox), (lo, hi) in zip(outputs, ranges):
+        total = 0
+        for ci in range(Cg):
+            for kh in range(KH):
+                for kw in range(KW):
+                    wi = (ci * KH + kh) * KW + kw                # position in the weight tensor [oc][ci][kh][kw]
+                    if q.sign[oc, wi] == 0:
+                        continue
+                    iy, ix = oy * stride[0] - pad[0] + kh, ox * stride[1] - pad[1] + kw
+                    if not (0 <= iy < H and 0 <= ix < W):
+                        continue
+                    xv = int(x[n, (oc // OCg) * Cg + ci, iy, ix])
+                    for s in range(lo, hi):
+                        B = 1 if draw(seed, layer, key_o(n, oc, oy, ox), key_k(ci, kh, kw), s) / denom < q.p[oc, wi] else 0
+                        total += int(q.sign[oc, wi]) * xv * (1 << (int(q.shift[oc, wi]) + B))
+        res.append(total)
+    return np.array(res, dtype=np.int64)
+
+
+@pytest.mark.parametrize("prob_bits", [23, 4])
+def test_conv_counter_keying(orc, prob_bits):
+    """The uniform of (output, tap, sample) is keyed o = ((n OC + oc) OH + oy) OW + ox, k = (ci KH + kh) KW + kw:
+    a non-square, strided, padded, grouped layer with general weights, every size different from every other, so
+    that no transposition of indices leaves the result unchanged."""
+    rng = np.random.default_rng(81)
+    OC, C, KH, KW, G = 6, 8, 3, 2, 2
+    N, H, W = 2, 7, 9
+    stride, pad = (2, 1), (1, 1)
+    wshape = (OC, C, KH, KW, G)
+    w = (rng.standard_normal((OC, C // G, KH, KW)) * 0.2).astype(np.float32)
+    w[rng.random(w.shape) < 0.1] = 0.0
+    x = rng.integers(-100, 101, size=(N, C, H, W)).astype(np.int8)
+    x[rng.random(x.shape) < 0.2] = 0
+    S, seed, layer = 5, 0x1234567890ABCDEF, 7
+    q = orc.QWeights(w, x_absmax=128, s_max=16, prob_bits=prob_bits)
+    OH, OW = (H + 2 * pad[0] - KH) // stride[0] + 1, (W + 2 * pad[1] - KW) // stride[1] + 1
+    assert len({N, OC, OH, OW}) == 4 and KH != KW and OH != OW
+    full, over, _ = orc.conv2d(q, wshape, x, stride, pad, S=S, seed=seed, layer_id=layer)
+    assert over == 0 and full.shape == (N, OC, OH, OW)
+    outs = [tuple(int(v) for v in rng.integers(0, (N, OC, OH, OW))) for _ in range(40)]
+    outs += [(N - 1, OC - 1, OH - 1, OW - 1), (0, 0, 0, 0), (1, 2, 0, OW - 1), (0, OC - 1, OH - 1, 0)]
+    want = np.array([full[o] for o in outs], dtype=np.int64)
+    p7 = prob_bits != 23
+    hand = _conv_by_hand(orc, q, wshape, x, stride, pad, seed, layer, outs, [(0, S)] * len(outs), p7=p7)
+    assert np.array_equal(hand, want)
+    # the comparison notices each of these mistakes (so the oracle makes none of them)
+    wrong = {
+        "kh/kw transposed": dict(key_k=lambda ci, kh, kw: (ci * KW + kw) * KH + kh),
+        "channel innermost": dict(key_k=lambda ci, kh, kw: (kh * KW + kw) * (C // G) + ci),
+        "oy/ox transposed": dict(key_o=lambda n, oc, oy, ox: ((n * OC + oc) * OW + ox) * OH + oy),
+        "channels-last output index": dict(key_o=lambda n, oc, oy, ox: ((n * OH + oy) * OW + ox) * OC + oc),
+        "channel counted over all groups": dict(key_k=lambda ci, kh, kw: ((ci + C // G) * KH + kh) * KW + kw),
+    }
+    for name, kw_ in wrong.items():
+        assert not np.array_equal(_conv_by_hand(orc, q, wshape, x, stride, pad, seed, layer, outs,
+                                                [(0, S)] * len(outs), p7=p7, **kw_), want), name
+    # per-pixel ranges use the same keying and the sample index itself: refinement from a first pass
+    to = rng.choice([0, 3, 5, 9, 16], size=(N, OH, OW)).astype(np.uint8)
+    frm = np.minimum(to, rng.choice([0, 2, 5], size=(N, OH, OW))).astype(np.uint8)
+    first, _, _ = orc.conv2d(q, wshape, x, stride, pad, budget_to=frm, seed=seed, layer_id=layer)
+    both, _, _ = orc.conv2d(q, wshape, x, stride, pad, budget_to=to, budget_from=frm, seed=seed, layer_id=layer,
+                            acc_in=first)
+    ranges = [(int(frm[n, oy, ox]), int(to[n, oy, ox])) for n, oc, oy, ox in outs]
+    added = _conv_by_hand(orc, q, wshape, x, stride, pad, seed, layer, outs, ranges, p7=p7)
+    assert np.array_equal(np.array([both[o] for o in outs], dtype=np.int64),
+                          np.array([first[o] for o in outs], dtype=np.int64) + added)
