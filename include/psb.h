@@ -125,10 +125,11 @@ int psb_weights_export(const psb_weights_t* q, uint32_t* packed_host);
 
 /* Release a handle (NULL is allowed).  The caller must make sure no layer call
  * using it is still running.
- * A handle also owns two device words with which the layer kernel hands out work to its
- * workgroups; they are zero between calls.  Layer calls that use the SAME handle must
- * therefore not overlap in time (same stream, or ordered by events); calls on different
- * handles may run concurrently. */
+ * A handle also owns a device word with which the layer kernel hands out work to its
+ * workgroups (every call resets it on its stream before the kernel starts) and the
+ * workspaces named below.  Layer calls that use the SAME handle must therefore not
+ * overlap in time (same stream, or ordered by events); calls on different handles may
+ * run concurrently. */
 void psb_weights_destroy(psb_weights_t* q);
 
 /* Output height/width of a convolution, on the host, with the validation every

@@ -205,13 +205,14 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
 
     const int mapping = pick_mapping(q, p);
     if (mapping < 0) return mapping;
+    uint32_t* sched = q->sched_dev;
     if (!p.acc && mapping == 2) {       // the channel-lane kernel may combine partial sums in the accumulators
         p.acc = scratch_acc(q->ws, (size_t)p.N * p.OC * OH * OW * sizeof(int32_t), stream);
         if (!p.acc) return PSB_ERR_ALLOC;
     }
 
     if (mapping == 2) {
-        rc = psb::launch_oc_lane(p, q->sched_dev, stream, profile_begin, profile_end);
+        rc = psb::launch_oc_lane(p, sched, stream, profile_begin, profile_end);
         if (rc != 0) { tl_last_device_error = rc; return PSB_ERR_DEVICE; }
     } else if (mapping == 3) {
         rc = psb::launch_product_list(p, q->live_idx_dev, q->live_cnt_dev, stream, profile_begin, profile_end);

@@ -106,13 +106,6 @@ __global__ void __launch_bounds__(kListPixels, 7) k_layer_product_list(const Lay
         key.k0[r] = p.key0 + (uint32_t)r * kWeyl0;
         key.k1[r] = p.key1 + (uint32_t)r * kWeyl1;
     }
-#pragma unroll
-    for (int r = 0; r < 7; ++r) {
-        key.vk0[r] = key.k0[r + 3];
-        key.vk1[r] = key.k1[r + 3];
-    }
-    key.vmul_a = kMulA;
-    key.vmul_b = kMulB;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;

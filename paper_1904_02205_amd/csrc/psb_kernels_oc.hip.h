@@ -30,7 +30,7 @@
 
 namespace psb {
 
-constexpr int kOcWaves = 4;     // default waves per workgroup (the kernel is also built for 8)
+constexpr int kOcWaves = 4;     // waves per workgroup
 constexpr int kOcMaxTaps = 64;  // taps per LDS tile: 64 * 64 channels * 8 B = 32 KB
 
 __device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
@@ -44,43 +44,26 @@ struct PixelHoist {
     uint32_t y2k;     // low half of the same product, xor round-2 key 0
 };
 
-// Round keys and multipliers.  vk0/vk1/vmul_* are the operands of rounds 3..9; with PSB_PIN_KEYS=1 they are
-// pinned to vector registers.  (An instruction stream in which EVERY two-operand VALU instruction has a
-// scalar-register source issues at half rate on gfx950 - 4.2 vs 2.4 cycles per wave64 - but in this loop
-// only 14 of 58 instructions per call do, and pinning them measured no gain while costing 16 VGPRs, so
-// the default leaves them in scalar registers.)
+// Round keys and multipliers.  Everything here is wave-uniform and stays in scalar registers.  (An instruction
+// stream in which EVERY two-operand VALU instruction has a scalar-register source issues at half rate on gfx950 -
+// 4.2 vs 2.4 cycles per wave64 - but in this loop only 14 of 58 instructions per call have one, and copies of the
+// keys in vector registers measured no gain while costing 16 registers.)
 struct Keys {
     uint32_t k0[10], k1[10];
-    uint32_t vk0[7], vk1[7];   // rounds 3..9, in VGPRs
-    uint32_t vmul_a, vmul_b;   // kMulA, kMulB in VGPRs
 };
 
-#ifndef PSB_PIN_KEYS
-#define PSB_PIN_KEYS 0
-#endif
-__device__ __forceinline__ uint32_t pin_to_vgpr(uint32_t s)
-{
-#if PSB_PIN_KEYS
-    uint32_t v;
-    asm volatile("v_mov_b32 %0, %1" : "=v"(v) : "s"(s));
-    return v;
-#else
-    return s;
-#endif
-}
-
-// Rounds 3..9 with every operand in a vector register.
+// Rounds 3..9.
 __device__ __forceinline__ u32x4 philox_rounds_3_to_9(u32x4 c, const Keys& key)
 {
 #pragma unroll
     for (int r = 0; r < 7; ++r) {
         uint32_t hi_a, lo_a, hi_b, lo_b;
-        mulhilo(key.vmul_a, c.x, hi_a, lo_a);
-        mulhilo(key.vmul_b, c.z, hi_b, lo_b);
+        mulhilo(kMulA, c.x, hi_a, lo_a);
+        mulhilo(kMulB, c.z, hi_b, lo_b);
         u32x4 t;
-        t.x = hi_b ^ c.y ^ key.vk0[r];
+        t.x = hi_b ^ c.y ^ key.k0[r + 3];
         t.y = lo_b;
-        t.z = hi_a ^ c.w ^ key.vk1[r];
+        t.z = hi_a ^ c.w ^ key.k1[r + 3];
         t.w = lo_a;
         c = t;
     }
@@ -109,7 +92,7 @@ __device__ __forceinline__ uint32_t sample_block(uint32_t thr, TapScalars ts, co
     const uint32_t z2 = ts.sz ^ h.lo_a;
     // round 2: only MulB * z2 is new
     uint32_t hi_b2, lo_b2;
-    mulhilo(key.vmul_b, z2, hi_b2, lo_b2);
+    mulhilo(kMulB, z2, hi_b2, lo_b2);
     u32x4 c;
     c.x = hi_b2 ^ h.y2k;
     c.y = lo_b2;
@@ -264,8 +247,8 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
 // of the same (channel block, chunk).  Workgroups draw tickets from a device counter until none is left:
 // the grid is only as large as the chip can hold at once, there is no launch gap between
 // work items, and the tail at the end of the kernel is at most one ticket long.
-//   sched[0] = next ticket, sched[1] = number of workgroups that have finished.  Both are 0
-//   before the launch; the last workgroup to finish sets them back to 0.
+//   sched[0] = number of tickets drawn from the counter; the launcher sets it to 0 on the stream before
+//   every launch (in the kernel that zero-fills the accumulators, where there is one).
 // FIXED_P7: the layer uses 7-bit uniforms (prob_bits < 23); each kernel is compiled for one of the two.
 // FIXED_NB > 0: every pixel draws generator blocks 0 .. FIXED_NB-1 completely (a call with one S everywhere that is
 // a whole number of blocks).  Only that path of the sampling loop is compiled then, which
@@ -290,13 +273,6 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
         key.k0[r] = p.key0 + (uint32_t)r * kWeyl0;
         key.k1[r] = p.key1 + (uint32_t)r * kWeyl1;
     }
-#pragma unroll
-    for (int r = 0; r < 7; ++r) {
-        key.vk0[r] = pin_to_vgpr(key.k0[r + 3]);
-        key.vk1[r] = pin_to_vgpr(key.k1[r + 3]);
-    }
-    key.vmul_a = pin_to_vgpr(kMulA);
-    key.vmul_b = pin_to_vgpr(kMulB);
 
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
     uint32_t* list = lists[wave];
@@ -490,20 +466,13 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
         __syncthreads();
     }
 
-    // No device-scope fence here: on this chip it writes back the XCD's L2, once per workgroup.  None is needed - a
-    // workgroup counts itself out only after its last draw has returned (so the draw has been performed), the words
-    // are only ever touched by device-scope atomics, and the results become visible at the end of the kernel.
-    if (threadIdx.x == 0) {
-        if (atomicAdd(&sched[1], 1u) == gridDim.x - 1) {   // every workgroup has drawn its last ticket
-            __hip_atomic_store(&sched[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&sched[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
 }
 
-// acc[i] = 0  (a plain store kernel: safe inside a captured graph, unlike a memset node)
-__global__ void __launch_bounds__(256) k_fill_zero(int32_t* __restrict__ acc, int64_t n)
+// acc[i] = 0 and, if given, the ticket counter of the persistent kernel = 0  (a plain store kernel: safe inside a
+// captured graph, unlike a memset node)
+__global__ void __launch_bounds__(256) k_fill_zero(int32_t* __restrict__ acc, int64_t n, uint32_t* __restrict__ sched = nullptr)
 {
+    if (sched && blockIdx.x == 0 && threadIdx.x == 0) sched[0] = 0u;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
         acc[i] = 0;
 }
@@ -540,11 +509,16 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
                           ProfileEnd prof_end)
 {
     if (!oc_lane_supported(p)) return (int)hipErrorInvalidValue;
-    int max_taps = kOcMaxTaps;
-    int waves = kOcWaves;
-    // benchmark overrides (results do not depend on either)
-    if (const char* v = std::getenv("PSB_OC_TAPS")) { const int t = std::atoi(v); if (t >= 1 && t <= kOcMaxTaps) max_taps = t; }
-    if (const char* v = std::getenv("PSB_OC_WAVES")) { const int t = std::atoi(v); if (t == 4 || t == 8) waves = t; }
+    // benchmark overrides, read once per process (results do not depend on them)
+    struct Tuning { int max_taps = kOcMaxTaps, ppw = 0; };
+    static const Tuning tuning = [] {
+        Tuning t;
+        if (const char* v = std::getenv("PSB_OC_TAPS")) { const int n = std::atoi(v); if (n >= 1 && n <= kOcMaxTaps) t.max_taps = n; }
+        if (const char* v = std::getenv("PSB_OC_PPW")) { const int n = std::atoi(v); if (n >= 1 && n <= 64) t.ppw = n; }
+        return t;
+    }();
+    int max_taps = tuning.max_taps;
+    constexpr int waves = kOcWaves;
     static int cus = 0;
     if (cus == 0) {
         int dev = 0, n = 0;
@@ -553,13 +527,13 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
             n = 256;
         cus = n;
     }
-    // resident workgroups: 160 KB of LDS hold four tiles; 512 VGPRs per lane hold four (8: three) waves per SIMD
-    const int wg_per_cu = (waves == 8) ? 2 : 4;
+    // resident workgroups: 160 KB of LDS hold four tiles; 512 VGPRs per lane hold four waves per SIMD
+    const int wg_per_cu = 4;
     // one S everywhere, a whole number of generator blocks for which a specialised kernel is built (0: none)
     const bool p7 = p.prob_bits < 23;
     const int per_block = p7 ? 16 : 4;
     int fixed_nb = 0;
-    if (waves == 4 && !p.budget_to && !p.budget_from && p.S % per_block == 0) {
+    if (!p.budget_to && !p.budget_from && p.S % per_block == 0) {
         const int nb = p.S / per_block;
         if (p7 ? (nb == 1 || nb == 2) : (nb == 1 || nb == 2 || nb == 4 || nb == 8)) fixed_nb = nb;
     }
@@ -591,7 +565,7 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
         const int want = (int)std::min(8.0, std::max(1.0, std::floor(11.0 / ticket_us + 0.5)));
         ppw = std::max(want, per_wg >= 128 ? 4 : per_wg >= 32 ? 2 : 1);
         while (ppw > 1 && per_wg / ppw < 1.5) --ppw;
-        if (const char* v = std::getenv("PSB_OC_PPW")) { const int t = std::atoi(v); if (t >= 1 && t <= 64) ppw = t; }
+        if (tuning.ppw > 0) ppw = tuning.ppw;
     }
     pixel_groups = (npix + (int64_t)waves * ppw - 1) / ((int64_t)waves * ppw);
     const int64_t n_tickets = pixel_groups * n_chunks * n_ocb;
@@ -599,9 +573,11 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
     const int64_t total = npix * p.OC;
     const int64_t grid = std::min<int64_t>(n_tickets, (int64_t)cus * wg_per_cu);
 
-    if (n_chunks > 1 && !p.budget_from) {
-        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
-        hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, stream, p.acc, total);
+    // the ticket counter starts at 0; partial sums of a split reduction meet in accumulators that start at 0
+    {
+        const bool fill = n_chunks > 1 && !p.budget_from;
+        const int blocks = fill ? (int)std::min<int64_t>((total + 255) / 256, 8192) : 1;
+        hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(fill ? 256 : 64), 0, stream, p.acc, fill ? total : 0, sched);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return (int)e;
     }
@@ -610,10 +586,7 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
 #define PSB_OC_LAUNCH(WAVES_, NB_, P7_)                                                                           \
     hipLaunchKernelGGL((k_layer_oc_lane<WAVES_, NB_, P7_>), dim3((unsigned)grid), dim3(WAVES_ * 64), 0, stream, p,   \
                        n_chunks, kc, (uint32_t)pixel_groups, (uint32_t)n_tickets, sched, ppw)
-    if (waves == 8) {
-        if (p7) PSB_OC_LAUNCH(8, 0, true);
-        else PSB_OC_LAUNCH(8, 0, false);
-    } else if (p7) {
+    if (p7) {
         switch (fixed_nb) {
             case 1: PSB_OC_LAUNCH(4, 1, true); break;
             case 2: PSB_OC_LAUNCH(4, 2, true); break;

@@ -124,6 +124,29 @@ def _ptr(t, dtype, name):
     return C.c_void_p(t.data_ptr())
 
 
+def _expect(t, shape, name):
+    """The library cannot see tensor shapes behind the raw pointers it is given: a wrong one is refused here."""
+    if t is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+
+
+def _expect_layer_io(q, out_shape, acc=None, y=None, mult=None, bias=None, budget_to=None, budget_from=None,
+                     x_out=None, x_out_shape=None, res_f32=None, res_i8=None, res_i8_shape=None):
+    """Shapes of everything a layer call reads or writes besides x, for output shape (N, OC, OH, OW) or (B, OC)."""
+    oc = q.wshape[0]
+    _expect(acc, out_shape, "acc")
+    _expect(y, out_shape, "y")
+    _expect(mult, (oc,), "mult")
+    _expect(bias, (oc,), "bias")
+    if len(out_shape) == 4:
+        pix = (out_shape[0], out_shape[2], out_shape[3])
+        _expect(budget_to, pix, "budget_to")
+        _expect(budget_from, pix, "budget_from")
+    _expect(x_out, x_out_shape or out_shape, "x_out")
+    _expect(res_f32, out_shape, "res_f32")
+    _expect(res_i8, res_i8_shape or out_shape, "res_i8")
+
+
 def set_mapping(mapping):
     return lib().psb_set_mapping(int(mapping))
 
@@ -200,6 +223,7 @@ def sample_filter(q, sample_to, sample_from=0, seed=0, layer_id=0, out=None):
     """The shared-filter mode's integer filter for samples [sample_from, sample_to): int32 [OC, K] on the device."""
     if out is None:
         out = torch.empty((q.wshape[0], q.K), dtype=torch.int32, device="cuda")
+    _expect(out, (q.wshape[0], q.K), "out")
     rc = lib().psb_sample_filter(q._h, sample_from, sample_to, seed, layer_id, _ptr(out, torch.int32, "out"), _stream())
     _check(rc, "psb_sample_filter")
     return out
@@ -207,10 +231,13 @@ def sample_filter(q, sample_to, sample_from=0, seed=0, layer_id=0, out=None):
 
 def linear(q, x, S, seed=0, layer_id=0, acc=None, y=None, mult=None, bias=None, shared=False):
     """x int8 [B, K] -> acc int32 [B, OC] (and y float32 if given).  shared: one sampled filter per pass."""
+    if x.dim() != 2 or x.shape[1] != q.K or q.wshape[2:] != (1, 1, 1):
+        raise ValueError(f"x: shape {tuple(x.shape)}, expected (B, {q.K}) and a handle of a linear layer")
     B = x.shape[0]
     oc = q.wshape[0]
     if acc is None:
         acc = torch.empty((B, oc), dtype=torch.int32, device=x.device)
+    _expect_layer_io(q, (B, oc), acc=acc, y=y, mult=mult, bias=bias)
     fn = lib().psb_linear_shared if shared else lib().psb_linear
     rc = fn(q._h, _ptr(x, torch.int8, "x"), B, S, seed, layer_id, _ptr(acc, torch.int32, "acc"),
             _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
@@ -218,18 +245,23 @@ def linear(q, x, S, seed=0, layer_id=0, acc=None, y=None, mult=None, bias=None, 
     return acc
 
 
-def _geom(x, stride, pad):
+def _geom(q, x, stride, pad):
+    """Geometry of a convolution call and its output shape; the input must have the handle's channel count."""
+    if x.dim() != 4 or x.shape[1] != q.wshape[1]:
+        raise ValueError(f"x: shape {tuple(x.shape)}, expected (N, {q.wshape[1]}, H, W)")
     n, _, h, w = x.shape
-    return ConvGeom(n, h, w, stride[0], stride[1], pad[0], pad[1])
+    g = ConvGeom(n, h, w, stride[0], stride[1], pad[0], pad[1])
+    oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
+    return g, (n, q.wshape[0], oh, ow)
 
 
 def conv2d(q, x, S, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, acc=None, y=None, mult=None, bias=None,
            shared=False):
     """x int8 [N, C, H, W] -> acc int32 [N, OC, OH, OW]."""
-    g = _geom(x, stride, pad)
+    g, shape = _geom(q, x, stride, pad)
     if acc is None:
-        oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
-        acc = torch.empty((g.n, q.wshape[0], oh, ow), dtype=torch.int32, device=x.device)
+        acc = torch.empty(shape, dtype=torch.int32, device=x.device)
+    _expect_layer_io(q, shape, acc=acc, y=y, mult=mult, bias=bias)
     fn = lib().psb_conv2d_shared if shared else lib().psb_conv2d
     rc = fn(q._h, _ptr(x, torch.int8, "x"), C.byref(g), S, seed, layer_id, _ptr(acc, torch.int32, "acc"),
             _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), _stream())
@@ -240,12 +272,12 @@ def conv2d(q, x, S, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, acc=None, y=N
 def conv2d_progressive(q, x, budget_to, budget_from=None, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0, acc=None,
                        y=None, mult=None, bias=None, shared=False):
     """budget_to / budget_from uint8 [N, OH, OW]; with budget_from, acc is updated in place."""
-    g = _geom(x, stride, pad)
+    g, shape = _geom(q, x, stride, pad)
     if acc is None:
         if budget_from is not None:
             raise ValueError("a refinement call needs the accumulators of the first pass")
-        oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
-        acc = torch.empty((g.n, q.wshape[0], oh, ow), dtype=torch.int32, device=x.device)
+        acc = torch.empty(shape, dtype=torch.int32, device=x.device)
+    _expect_layer_io(q, shape, acc=acc, y=y, mult=mult, bias=bias, budget_to=budget_to, budget_from=budget_from)
     fn = lib().psb_conv2d_progressive_shared if shared else lib().psb_conv2d_progressive
     rc = fn(q._h, _ptr(x, torch.int8, "x"), C.byref(g), _ptr(budget_to, torch.uint8, "budget_to"),
             _ptr(budget_from, torch.uint8, "budget_from"), seed, layer_id, _ptr(acc, torch.int32, "acc"),
@@ -259,13 +291,13 @@ def conv2d_requant(q, x, inv_step, S=None, budget_to=None, stride=(1, 1), pad=(0
                    x_out=None, shared=False, want_acc=True):
     """Layer call with the requantisation fused in: returns the int8 activations [N, OC, OH, OW].  want_acc=False
     (and acc None): no accumulators are handed out."""
-    g = _geom(x, stride, pad)
-    oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
-    shape = (g.n, q.wshape[0], oh, ow)
+    g, shape = _geom(q, x, stride, pad)
     if acc is None and want_acc:
         acc = torch.empty(shape, dtype=torch.int32, device=x.device)
     if x_out is None:
         x_out = torch.empty(shape, dtype=torch.int8, device=x.device)
+    _expect_layer_io(q, shape, acc=acc, y=y, mult=mult, bias=bias, budget_to=budget_to, x_out=x_out, res_f32=res_f32,
+                     res_i8=res_i8)
     rq = Requant(1 if relu else 0, inv_step, lo, hi,
                  None if res_f32 is None else _ptr(res_f32, torch.float32, "res_f32").value,
                  None if res_i8 is None else _ptr(res_i8, torch.int8, "res_i8").value, res_step)
@@ -302,6 +334,12 @@ def conv2d_shared_requant_blocked(q, x, x_shape, inv_step, S, stride=(1, 1), pad
         x_out = torch.empty(shape, dtype=torch.int8, device=x.device)
     if not want_x and y is None:
         y = torch.empty((n, oc, oh, ow), dtype=torch.float32, device=x.device)
+    if c != q.wshape[1]:
+        raise ValueError(f"x_shape: {c} channels, the handle has {q.wshape[1]}")
+    _expect(x, blocked_shape(n, c, h, w) if layout & BLOCKED_IN else (n, c, h, w), "x")
+    _expect_layer_io(q, (n, oc, oh, ow), y=y, mult=mult, bias=bias, x_out=x_out if want_x else None,
+                     x_out_shape=blocked_shape(n, oc, oh, ow) if layout & BLOCKED_OUT else None, res_f32=res_f32,
+                     res_i8=res_i8, res_i8_shape=blocked_shape(n, oc, oh, ow) if layout & BLOCKED_RES else None)
     rq = Requant(1 if relu else 0, inv_step, lo, hi,
                  None if res_f32 is None else _ptr(res_f32, torch.float32, "res_f32").value,
                  None if res_i8 is None else _ptr(res_i8, torch.int8, "res_i8").value, res_step)
@@ -337,6 +375,9 @@ def requantize(y, inv_step, relu=True, lo=0, hi=127, res_f32=None, res_i8=None, 
     """int8 tensor of y's shape: clamp(rint(g(y [+ r]) * inv_step), lo, hi)."""
     if out is None:
         out = torch.empty(y.shape, dtype=torch.int8, device=y.device)
+    _expect(out, y.shape, "out")
+    _expect(res_f32, y.shape, "res_f32")
+    _expect(res_i8, y.shape, "res_i8")
     rc = lib().psb_requantize(_ptr(y, torch.float32, "y"), _ptr(res_f32, torch.float32, "res_f32"),
                               _ptr(res_i8, torch.int8, "res_i8"), res_step, 1 if relu else 0, inv_step, lo, hi,
                               y.numel(), _ptr(out, torch.int8, "out"), _stream())
@@ -349,8 +390,9 @@ def maxpool2d_i8(x, kernel, stride, pad, out=None):
     oh, ow = (h + 2 * pad[0] - kernel[0]) // stride[0] + 1, (w + 2 * pad[1] - kernel[1]) // stride[1] + 1
     if out is None:
         out = torch.empty((n, c, max(oh, 0), max(ow, 0)), dtype=torch.int8, device=x.device)
+    _expect(out, (n, c, max(oh, 0), max(ow, 0)), "out")
     rc = lib().psb_maxpool2d_i8(_ptr(x, torch.int8, "x"), n, c, h, w, kernel[0], kernel[1], stride[0], stride[1],
-                                pad[0], pad[1], C.c_void_p(out.data_ptr()), _stream())
+                                pad[0], pad[1], _ptr(out, torch.int8, "out"), _stream())
     _check(rc, "psb_maxpool2d_i8")
     return out
 
@@ -359,6 +401,7 @@ def global_avgpool_requantize(x, scale, lo=0, hi=127, out=None):
     n, c, h, w = x.shape
     if out is None:
         out = torch.empty((n, c), dtype=torch.int8, device=x.device)
+    _expect(out, (n, c), "out")
     rc = lib().psb_global_avgpool_requantize(_ptr(x, torch.int8, "x"), n, c, h, w, scale, lo, hi,
                                              _ptr(out, torch.int8, "out"), _stream())
     _check(rc, "psb_global_avgpool_requantize")
@@ -369,6 +412,7 @@ def budget_resample(b, oh, ow, out=None):
     n, h, w = b.shape
     if out is None:
         out = torch.empty((n, oh, ow), dtype=torch.uint8, device=b.device)
+    _expect(out, (n, oh, ow), "out")
     rc = lib().psb_budget_resample(_ptr(b, torch.uint8, "budget"), n, h, w, oh, ow, _ptr(out, torch.uint8, "out"),
                                    _stream())
     _check(rc, "psb_budget_resample")

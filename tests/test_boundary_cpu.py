@@ -154,3 +154,82 @@ def test_binding_refuses_cpu_tensors(psb):
     import torch
     with pytest.raises(TypeError):
         psb.Weights(torch.zeros(4, 4, 3, 3))
+
+
+def _fake_handle(psb, wshape):
+    """A handle object without a library handle behind it: the binding must refuse wrong shapes before it would
+    dereference anything."""
+    q = object.__new__(psb.Weights)
+    q.wshape = wshape
+    q.K = wshape[1] // wshape[4] * wshape[2] * wshape[3]
+    q.s_max, q.prob_bits, q._h = 16, 23, C.c_void_p(None)
+    return q
+
+
+def test_binding_refuses_wrong_tensor_shapes(psb):
+    """The C-ABI takes raw pointers and cannot check sizes: every tensor's shape is compared with what the handle
+    and the geometry imply, and a mismatch is a ValueError before any pointer is handed over."""
+    import torch
+    q = _fake_handle(psb, (6, 4, 3, 3, 1))
+    x = torch.zeros((2, 4, 8, 8), dtype=torch.int8)
+    ok_acc = torch.zeros((2, 6, 8, 8), dtype=torch.int32)
+    with pytest.raises(ValueError, match="x: shape"):
+        psb.conv2d(q, torch.zeros((2, 5, 8, 8), dtype=torch.int8), 8, pad=(1, 1), acc=ok_acc)     # wrong channel count
+    with pytest.raises(ValueError, match="x: shape"):
+        psb.conv2d(q, torch.zeros((2, 4, 8), dtype=torch.int8), 8, pad=(1, 1), acc=ok_acc)
+    with pytest.raises(ValueError, match="acc"):
+        psb.conv2d(q, x, 8, pad=(1, 1), acc=torch.zeros((2, 6, 8, 7), dtype=torch.int32))
+    with pytest.raises(ValueError, match="y"):
+        psb.conv2d(q, x, 8, pad=(1, 1), acc=ok_acc, y=torch.zeros((2, 6, 6, 6)))
+    with pytest.raises(ValueError, match="mult"):
+        psb.conv2d(q, x, 8, pad=(1, 1), acc=ok_acc, mult=torch.zeros(5))
+    with pytest.raises(ValueError, match="bias"):
+        psb.conv2d(q, x, 8, pad=(1, 1), acc=ok_acc, bias=torch.zeros(7))
+    bt = torch.zeros((2, 8, 8), dtype=torch.uint8)
+    with pytest.raises(ValueError, match="budget_to"):
+        psb.conv2d_progressive(q, x, torch.zeros((2, 8, 9), dtype=torch.uint8), pad=(1, 1), acc=ok_acc)
+    with pytest.raises(ValueError, match="budget_from"):
+        psb.conv2d_progressive(q, x, bt, torch.zeros((1, 8, 8), dtype=torch.uint8), pad=(1, 1), acc=ok_acc)
+    xo = torch.zeros((2, 6, 8, 8), dtype=torch.int8)
+    with pytest.raises(ValueError, match="x_out"):
+        psb.conv2d_requant(q, x, 1.0, S=8, pad=(1, 1), acc=ok_acc, x_out=torch.zeros((2, 6, 8), dtype=torch.int8))
+    with pytest.raises(ValueError, match="res_i8"):
+        psb.conv2d_requant(q, x, 1.0, S=8, pad=(1, 1), acc=ok_acc, x_out=xo, res_i8=torch.zeros((2, 4, 8, 8), dtype=torch.int8))
+    with pytest.raises(ValueError, match="res_f32"):
+        psb.conv2d_requant(q, x, 1.0, S=8, pad=(1, 1), acc=ok_acc, x_out=xo, res_f32=torch.zeros((2, 6, 8, 9)))
+    # blocked layouts
+    xb = torch.zeros(psb.blocked_shape(2, 4, 8, 8), dtype=torch.int8)
+    with pytest.raises(ValueError, match="x: shape"):
+        psb.conv2d_shared_requant_blocked(q, x, (2, 4, 8, 8), 1.0, 8, pad=(1, 1), layout=psb.BLOCKED_IN)
+    with pytest.raises(ValueError, match="x_shape"):
+        psb.conv2d_shared_requant_blocked(q, xb, (2, 5, 8, 8), 1.0, 8, pad=(1, 1), layout=psb.BLOCKED_IN)
+    with pytest.raises(ValueError, match="x_out"):
+        psb.conv2d_shared_requant_blocked(q, xb, (2, 4, 8, 8), 1.0, 8, pad=(1, 1), layout=psb.BLOCKED_IN | psb.BLOCKED_OUT,
+                                          x_out=xo)
+    with pytest.raises(ValueError, match="res_i8"):
+        psb.conv2d_shared_requant_blocked(q, xb, (2, 4, 8, 8), 1.0, 8, pad=(1, 1), layout=psb.BLOCKED_IN | psb.BLOCKED_RES,
+                                          x_out=xo, res_i8=xo)
+    # linear layers
+    ql = _fake_handle(psb, (6, 20, 1, 1, 1))
+    with pytest.raises(ValueError, match="x: shape"):
+        psb.linear(ql, torch.zeros((3, 21), dtype=torch.int8), 8)
+    with pytest.raises(ValueError, match="x: shape"):
+        psb.linear(q, torch.zeros((3, 36), dtype=torch.int8), 8)                # a convolution's handle
+    with pytest.raises(ValueError, match="acc"):
+        psb.linear(ql, torch.zeros((3, 20), dtype=torch.int8), 8, acc=torch.zeros((3, 5), dtype=torch.int32))
+    # glue
+    y = torch.zeros((2, 3, 4, 4))
+    with pytest.raises(ValueError, match="out"):
+        psb.requantize(y, 1.0, out=torch.zeros((2, 3, 4, 5), dtype=torch.int8))
+    with pytest.raises(ValueError, match="res_i8"):
+        psb.requantize(y, 1.0, res_i8=torch.zeros((2, 3, 4), dtype=torch.int8), out=torch.zeros((2, 3, 4, 4), dtype=torch.int8))
+    xi = torch.zeros((2, 3, 8, 8), dtype=torch.int8)
+    with pytest.raises(ValueError, match="out"):
+        psb.maxpool2d_i8(xi, (3, 3), (2, 2), (1, 1), out=torch.zeros((2, 3, 4, 5), dtype=torch.int8))
+    with pytest.raises(ValueError, match="out"):
+        psb.global_avgpool_requantize(xi, 1.0, out=torch.zeros((2, 4), dtype=torch.int8))
+    with pytest.raises(ValueError, match="out"):
+        psb.budget_resample(torch.zeros((2, 4, 4), dtype=torch.uint8), 8, 8, out=torch.zeros((2, 8, 7), dtype=torch.uint8))
+    with pytest.raises(ValueError, match="out"):
+        psb.sample_filter(q, 8, out=torch.zeros((6, 35), dtype=torch.int32))
+

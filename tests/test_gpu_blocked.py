@@ -144,11 +144,13 @@ def test_blocked_call_errors(psb):
         assert ei.value.code == code
     q = helpers.gpu_quantize(psb, plain)
     xb = torch.from_numpy(to_blocked(plain.x, 0)).cuda()
+    xn = torch.from_numpy(plain.x).cuda()
     shifted = torch.zeros(xb.numel() + 16, dtype=torch.int8, device="cuda")[1:1 + xb.numel()].view(xb.shape)
     for kw, code in ((dict(layout=8), psb.ERR_VALUE), (dict(layout=psb.BLOCKED_IN, S=9), psb.ERR_VALUE),
                      (dict(layout=psb.BLOCKED_IN, x=shifted), psb.ERR_VALUE)):
-        args = dict(x=xb, S=8, layout=0)
+        args = dict(S=8, layout=0)
         args.update(kw)
+        args.setdefault("x", xb if args["layout"] & psb.BLOCKED_IN else xn)      # the binding checks the shape
         with pytest.raises(psb.PsbError) as ei:
             psb.conv2d_shared_requant_blocked(q, args["x"], plain.x.shape, 1.0, args["S"], stride=plain.stride,
                                               pad=plain.pad, layout=args["layout"])

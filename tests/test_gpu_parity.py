@@ -98,9 +98,14 @@ def test_quantize_error_codes(psb, orc):
         with pytest.raises(psb.PsbError) as ei:
             psb.linear(q, x, S)
         assert ei.value.code == psb.ERR_VALUE
-    with pytest.raises(psb.PsbError) as ei:         # a conv handle is not a linear layer
-        psb.linear(psb.Weights(torch.ones((4, 2, 3, 3), device="cuda")), x, 1)
-    assert ei.value.code == psb.ERR_SHAPE
+    qc = psb.Weights(torch.ones((4, 2, 3, 3), device="cuda"))      # a conv handle is not a linear layer
+    with pytest.raises(ValueError):
+        psb.linear(qc, x, 1)
+    import ctypes
+    acc = torch.zeros((2, 4), dtype=torch.int32, device="cuda")
+    rc = psb.lib().psb_linear(qc._h, ctypes.c_void_p(x.data_ptr()), 2, 1, 0, 0, ctypes.c_void_p(acc.data_ptr()), None,
+                              None, None, None)
+    assert rc == psb.ERR_SHAPE
 
 
 # ------------------------------------------------------------------ layers, both mappings
