@@ -268,6 +268,29 @@ int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_co
                        int8_t* x_out_dev, int32_t shared, void* hip_stream);
 
 /*
+ * psb_conv2d_requant for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  It is psb_conv2d_requant with acc_dev = NULL and shared = 0 (per-product
+ * mode, requantised activations and/or rescaled values out, no accumulators handed out), element for element, but
+ * the scratch memory of its kernels - the ticket counter of the persistent layer kernel and the accumulators in
+ * which the partial sums of a split tap reduction meet - is a fixed array inside the library's device code instead
+ * of memory owned by the handle.  The call issues no hipMalloc, no hipFree and no synchronisation.
+ *  - Limit: n * oc * OH * OW <= PSB_STATIC_MAX_OUTPUTS (the array holds that many int32 accumulators, 32 MiB, plus
+ *    256 bytes; each GPU the library runs on holds it until the process ends).  Larger calls return TOO_LARGE and
+ *    launch nothing.
+ *  - All calls on one GPU share that GPU's array, and it keeps the last call's contents; the call clears what it
+ *    needs (in a kernel, not a memset, so it can be captured).  Two such calls that overlap in time on one GPU -
+ *    different streams without ordering - race on it; same-stream calls are ordered and safe.
+ *  - The array's device address is looked up once per GPU, by psb_quantize_weights (any handle of that GPU), which
+ *    therefore has to have run outside the capture - it allocates and synchronises anyway.
+ * Errors: those of psb_conv2d_requant without ALLOC, plus TOO_LARGE as above.
+ */
+#define PSB_STATIC_MAX_OUTPUTS (8 * 1024 * 1024)
+int psb_conv2d_requant_static(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S,
+                              const uint8_t* budget_to_dev, uint64_t seed, uint32_t layer_id, float* y_dev,
+                              const float* mult_dev, const float* bias_dev, const psb_requant* rq, int8_t* x_out_dev,
+                              void* hip_stream);
+
+/*
  * The chained shared-filter pass [Sect. 4.1 and suppl. "Efficient simulation of the forward pass": one sampled
  * filter per layer and pass].  Two additions for callers that run layer after layer on one GPU:
  *

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -47,6 +48,15 @@ int32_t* scratch_acc(shared_workspace* ws, size_t bytes, hipStream_t stream)
     }
     return ws->acc_dev;
 }
+
+// Scratch memory of psb_conv2d_requant_static: the ticket counter of the persistent layer kernel (first word of a
+// 256-byte head) and the accumulators in which the partial sums of a split tap reduction meet.  A file-scope device
+// array, so that the entry point never allocates; every GPU the library runs on holds its own copy at its own
+// address until the process ends.  Host code never uses the array's name as an address: the per-device pointer
+// comes from hipGetSymbolAddress (static_scratch() below).
+constexpr size_t kStaticHeadWords = 64;
+constexpr size_t kStaticAccWords = (size_t)PSB_STATIC_MAX_OUTPUTS;
+static __device__ __align__(256) uint32_t scratch[kStaticHeadWords + kStaticAccWords];
 
 struct psb_weights {
     psb_wshape shape;
@@ -92,6 +102,29 @@ bool profile_begin(hipStream_t stream, int* slot)
 void profile_end(hipStream_t stream, int slot)
 {
     if (hipEventRecord(g_profile_events[2 * slot + 1], stream) == hipSuccess) g_profile_used = slot + 1;
+}
+
+// Device address of `scratch` on device dev, which must be the current device.  Resolved once per device (by
+// psb_quantize_weights, the set-up call of every handle, or else by the first call that needs it) and kept.
+constexpr int kMaxDevices = 64;
+uint32_t* g_static_scratch[kMaxDevices] = {};
+std::mutex g_static_scratch_mutex;
+
+int static_scratch(int dev, uint32_t** out)
+{
+    if (dev < 0 || dev >= kMaxDevices) return PSB_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            tl_last_device_error = (int)e;
+            return PSB_ERR_DEVICE;
+        }
+        g_static_scratch[dev] = static_cast<uint32_t*>(ptr);
+    }
+    if (out) *out = g_static_scratch[dev];
+    return PSB_OK;
 }
 
 #define PSB_HIP_TRY(expr)                                 \
@@ -184,11 +217,12 @@ void fill_geometry(const psb_weights* q, const psb_conv_geom* g, int32_t OH, int
 int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, int32_t S,
                  const uint8_t* budget_to, const uint8_t* budget_from, uint64_t seed, uint32_t layer_id,
                  int32_t* acc, float* y, const float* mult, const float* bias, hipStream_t stream,
-                 const psb::Requant* rq = nullptr)
+                 const psb::Requant* rq = nullptr, bool use_static_scratch = false)
 {
     int32_t OH = 0, OW = 0;
     int rc = check_geom(&q->shape, g, &OH, &OW);
     if (rc != PSB_OK) return rc;
+    if (use_static_scratch && (int64_t)g->n * q->shape.oc * OH * OW > (int64_t)kStaticAccWords) return PSB_ERR_TOO_LARGE;
 
     psb::LayerParams p;
     fill_geometry(q, g, OH, OW, p);
@@ -206,7 +240,13 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
     const int mapping = pick_mapping(q, p);
     if (mapping < 0) return mapping;
     uint32_t* sched = q->sched_dev;
-    if (!p.acc && mapping == 2) {       // the channel-lane kernel may combine partial sums in the accumulators
+    if (use_static_scratch) {           // ticket counter and accumulators in the static array: nothing is allocated
+        uint32_t* base = nullptr;
+        rc = static_scratch(dev, &base);
+        if (rc != PSB_OK) return rc;
+        sched = base;
+        if (!p.acc && mapping == 2) p.acc = reinterpret_cast<int32_t*>(base + kStaticHeadWords);
+    } else if (!p.acc && mapping == 2) {       // the channel-lane kernel may combine partial sums in the accumulators
         p.acc = scratch_acc(q->ws, (size_t)p.N * p.OC * OH * OW * sizeof(int32_t), stream);
         if (!p.acc) return PSB_ERR_ALLOC;
     }
@@ -609,6 +649,12 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     } while (0)
 
     QTRY(hipGetDevice(&q->device));
+    // set-up of the static scratch array of this device (psb_conv2d_requant_static): its address is looked up here,
+    // outside any stream capture, so that the entry point itself finds it ready
+    {
+        const int rc_scratch = static_scratch(q->device, nullptr);
+        if (rc_scratch != PSB_OK) return fail(rc_scratch, hipSuccess);
+    }
     if (hipMalloc(&scratch, scratch_words * sizeof(uint32_t)) != hipSuccess) return fail(PSB_ERR_ALLOC, hipSuccess);
     if (hipMalloc(&q->packed_dev, (size_t)nw * sizeof(uint32_t)) != hipSuccess) return fail(PSB_ERR_ALLOC, hipSuccess);
     if (hipMalloc(&q->tile_dev, (size_t)oc_pad * K * sizeof(uint2)) != hipSuccess)
@@ -800,6 +846,23 @@ int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_co
                              mult_dev, bias_dev, (hipStream_t)hip_stream, &r);
     return launch_layer(q, x_dev, geom, budget_to_dev ? 0 : S, budget_to_dev, nullptr, seed, layer_id, acc_dev, y_dev,
                         mult_dev, bias_dev, (hipStream_t)hip_stream, &r);
+}
+
+int psb_conv2d_requant_static(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S,
+                              const uint8_t* budget_to_dev, uint64_t seed, uint32_t layer_id, float* y_dev,
+                              const float* mult_dev, const float* bias_dev, const psb_requant* rq, int8_t* x_out_dev,
+                              void* hip_stream)
+{
+    if (!q || !x_dev || !geom || !rq || !x_out_dev) return PSB_ERR_NULL;
+    if (!budget_to_dev && (S <= 0 || S > q->s_max)) return PSB_ERR_VALUE;
+    if (rq->res_f32_dev && rq->res_i8_dev) return PSB_ERR_VALUE;
+    if (rq->lo < -128 || rq->hi > 127 || rq->lo > rq->hi || !(rq->inv_step >= 0.0f)) return PSB_ERR_VALUE;
+    psb::Requant r;
+    std::memset(&r, 0, sizeof(r));
+    r.x_out = x_out_dev; r.res_f32 = rq->res_f32_dev; r.res_i8 = rq->res_i8_dev; r.res_step = rq->res_step;
+    r.inv_step = rq->inv_step; r.lo = (float)rq->lo; r.hi = (float)rq->hi; r.relu = rq->relu;
+    return launch_layer(q, x_dev, geom, budget_to_dev ? 0 : S, budget_to_dev, nullptr, seed, layer_id, nullptr, y_dev,
+                        mult_dev, bias_dev, (hipStream_t)hip_stream, &r, /*use_static_scratch=*/true);
 }
 
 int psb_conv2d_shared_requant_blocked(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom, int32_t S,

@@ -21,7 +21,7 @@ MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE, MAPPING_PRODUCT_LIST = 0
 SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
            "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
-           "psb_conv2d_requant", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_shared_budget_levels", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
+           "psb_conv2d_requant", "psb_conv2d_requant_static", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_shared_budget_levels", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
            "psb_attention_budget", "psb_last_device_error", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
            "psb_profile_read"]
 
@@ -90,6 +90,8 @@ def lib():
         L.psb_shared_budget_levels.argtypes = [vp, i32]
         L.psb_conv2d_requant.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, vp, u64, u32, vp, vp, vp, vp,
                                          C.POINTER(Requant), vp, i32, vp]
+        L.psb_conv2d_requant_static.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, vp, u64, u32, vp, vp, vp,
+                                                C.POINTER(Requant), vp, vp]
         L.psb_requantize.argtypes = [vp, vp, vp, f32, i32, f32, i32, i32, C.c_int64, vp, vp]
         L.psb_maxpool2d_i8.argtypes = [vp] + [i32] * 10 + [vp, vp]
         L.psb_global_avgpool_requantize.argtypes = [vp, i32, i32, i32, i32, f32, i32, i32, vp, vp]
@@ -307,6 +309,28 @@ def conv2d_requant(q, x, inv_step, S=None, budget_to=None, stride=(1, 1), pad=(0
                                   _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), C.byref(rq),
                                   _ptr(x_out, torch.int8, "x_out"), 1 if shared else 0, _stream())
     _check(rc, "psb_conv2d_requant")
+    return x_out
+
+
+STATIC_MAX_OUTPUTS = 8 * 1024 * 1024
+
+
+def conv2d_requant_static(q, x, inv_step, x_out, S=None, budget_to=None, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0,
+                          relu=True, lo=0, hi=127, res_f32=None, res_i8=None, res_step=0.0, mult=None, bias=None, y=None):
+    """psb_conv2d_requant_static: conv2d_requant without accumulators out (per-product mode) that allocates nothing;
+    the caller passes every tensor, x_out [N, OC, OH, OW] included.  At most STATIC_MAX_OUTPUTS output elements."""
+    g, shape = _geom(q, x, stride, pad)
+    _expect_layer_io(q, shape, y=y, mult=mult, bias=bias, budget_to=budget_to, x_out=x_out, res_f32=res_f32,
+                     res_i8=res_i8)
+    rq = Requant(1 if relu else 0, inv_step, lo, hi,
+                 None if res_f32 is None else _ptr(res_f32, torch.float32, "res_f32").value,
+                 None if res_i8 is None else _ptr(res_i8, torch.int8, "res_i8").value, res_step)
+    rc = lib().psb_conv2d_requant_static(q._h, _ptr(x, torch.int8, "x"), C.byref(g), 0 if S is None else S,
+                                         _ptr(budget_to, torch.uint8, "budget_to"), seed, layer_id,
+                                         _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"),
+                                         _ptr(bias, torch.float32, "bias"), C.byref(rq),
+                                         _ptr(x_out, torch.int8, "x_out"), _stream())
+    _check(rc, "psb_conv2d_requant_static")
     return x_out
 
 

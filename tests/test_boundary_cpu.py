@@ -197,6 +197,8 @@ def test_binding_refuses_wrong_tensor_shapes(psb):
         psb.conv2d_requant(q, x, 1.0, S=8, pad=(1, 1), acc=ok_acc, x_out=xo, res_i8=torch.zeros((2, 4, 8, 8), dtype=torch.int8))
     with pytest.raises(ValueError, match="res_f32"):
         psb.conv2d_requant(q, x, 1.0, S=8, pad=(1, 1), acc=ok_acc, x_out=xo, res_f32=torch.zeros((2, 6, 8, 9)))
+    with pytest.raises(ValueError, match="x_out"):
+        psb.conv2d_requant_static(q, x, 1.0, torch.zeros((2, 6, 7, 8), dtype=torch.int8), S=8, pad=(1, 1))
     # blocked layouts
     xb = torch.zeros(psb.blocked_shape(2, 4, 8, 8), dtype=torch.int8)
     with pytest.raises(ValueError, match="x: shape"):
@@ -233,3 +235,14 @@ def test_binding_refuses_wrong_tensor_shapes(psb):
     with pytest.raises(ValueError, match="out"):
         psb.sample_filter(q, 8, out=torch.zeros((6, 35), dtype=torch.int32))
 
+
+def test_static_entry_point_rejects_on_the_host(psb):
+    L = psb.lib()
+    g = psb.ConvGeom(1, 8, 8, 1, 1, 1, 1)
+    rq = psb.Requant(1, 1.0, 0, 127, None, None, 0.0)
+    dummy = C.c_void_p(16)
+    assert L.psb_conv2d_requant_static(None, dummy, C.byref(g), 8, None, 0, 0, None, None, None, C.byref(rq), dummy,
+                                       None) == psb.ERR_NULL
+    assert psb.STATIC_MAX_OUTPUTS == 8 * 1024 * 1024
+    text = open(os.path.join(ROOT, "include", "psb.h")).read()
+    assert "#define PSB_STATIC_MAX_OUTPUTS (8 * 1024 * 1024)" in text
