@@ -24,12 +24,31 @@
  *  - Layouts: activations NCHW int8, weights OIHW float32 (O = output channel,
  *    I = input channels per group), accumulators and outputs NCHW.
  *  - hip_stream is a hipStream_t passed as void* (NULL = the null stream).
- *    Layer calls are asynchronous on that stream and never synchronise.
- *    psb_quantize_weights synchronises the stream twice (it reads back the
- *    largest exponent and a per-channel exponent histogram).
+ *    Every call is asynchronous on that stream.  Which calls also synchronise it
+ *    or allocate device memory:
+ *      psb_quantize_weights     allocates the handle's memory and synchronises three
+ *                               times (largest exponent, per-channel exponent
+ *                               histogram, class counts);
+ *      psb_weights_export       synchronous copy;
+ *      per-product layer calls  (psb_linear, psb_conv2d, psb_conv2d_progressive)
+ *                               never allocate and never synchronise;
+ *      psb_conv2d_requant       without acc_dev: the first such call on a handle, and any
+ *                               with more outputs than before, allocates scratch
+ *                               accumulators (a growing call first synchronises the
+ *                               stream and frees the old ones);
+ *      shared-filter calls      allocate workspaces owned by the handle on first use and
+ *                               when an input is larger than any before (then also one
+ *                               synchronisation); with a budget map and no announced
+ *                               levels they synchronise once to read the budget values;
+ *      psb_conv2d_requant_static  never allocates, never synchronises;
+ *      glue calls               never allocate, never synchronise.
  *  - Every function returns PSB_OK (0) or a negative psb_status; nothing
  *    throws, aborts or prints.  Arguments are validated on the host before any
- *    device work is started; on error nothing has been launched.
+ *    device work is started: after a NULL, SHAPE, VALUE, OVERFLOW_UNSAFE or
+ *    TOO_LARGE error nothing has been launched.  A call is up to three launches
+ *    (clearing, sampling, rescaling; shared-filter calls with budget maps more), so a
+ *    DEVICE or ALLOC error may leave the first of them on the stream; the outputs are
+ *    then unspecified.
  *  - The random bit of (output element o, tap k, sample i) is
  *        B = [ u < p * 2^32 ],
  *    u = word (i mod 4) of Philox4x32-10 with key (seed mod 2^32, seed div 2^32)
@@ -364,6 +383,12 @@ int psb_attention_budget(const int8_t* act_dev, float step, int32_t n, int32_t c
 
 /* The hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
 int psb_last_device_error(void);
+
+/* Identifies the sources the library was built from: the hexadecimal SHA-256 of the concatenated source files
+ * (this header and the files under csrc/, in the order the build script lists them), as given to the compiler by
+ * the build script; "unknown" for a build made any other way.  The Python binding refuses to load a library whose
+ * identifier differs from the hash of the sources beside it.  The pointer is valid for the life of the process. */
+const char* psb_build_id(void);
 
 /* Select the kernel mapping for subsequent layer calls of this process:
  * 0 = automatic, 1 = one output pixel per lane (any layer; the simplest kernel), 2 = one output

@@ -24,8 +24,18 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-ffp-contract=off", "-Wall", "-Wno-unused-function"]
 
 
+def source_id() -> str:
+    """SHA-256 over the sources the library is built from, in the order of DEPS."""
+    import hashlib
+    h = hashlib.sha256()
+    for d in DEPS:
+        with open(d, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def build(verbose: bool = False, extra=()) -> str:
-    cmd = ["hipcc", *FLAGS, *extra, SRC, "-o", LIB]
+    cmd = ["hipcc", *FLAGS, f'-DPSB_BUILD_ID="{source_id()}"', *extra, SRC, "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True, cwd=HERE)
@@ -39,8 +49,6 @@ def ensure_built() -> str:
     return LIB
 
 
-def stale() -> bool:
-    return (not os.path.exists(LIB)) or any(os.path.getmtime(d) > os.path.getmtime(LIB) for d in DEPS)
 
 
 if __name__ == "__main__":

@@ -560,6 +560,11 @@ extern "C" {
 
 int psb_last_device_error(void) { return tl_last_device_error; }
 
+#ifndef PSB_BUILD_ID
+#define PSB_BUILD_ID "unknown"
+#endif
+const char* psb_build_id(void) { return PSB_BUILD_ID; }
+
 int psb_set_mapping(int mapping)
 {
     const int prev = g_mapping;

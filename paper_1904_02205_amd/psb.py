@@ -22,7 +22,7 @@ SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "ps
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
            "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
            "psb_conv2d_requant", "psb_conv2d_requant_static", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_shared_budget_levels", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
-           "psb_attention_budget", "psb_last_device_error", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
+           "psb_attention_budget", "psb_last_device_error", "psb_build_id", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
            "psb_profile_read"]
 
 
@@ -62,7 +62,8 @@ def library_path():
 
 
 def lib():
-    """Load libpsb_hip.so (built in-tree; built here only if it does not exist)."""
+    """Load libpsb_hip.so (built in-tree; built here only if it does not exist; refused if it was built from
+    other sources than the ones in the tree)."""
     global _lib
     if _lib is None:
         path = _build.ensure_built()
@@ -103,8 +104,14 @@ def lib():
         L.psb_profile_enable.argtypes = [C.c_int]
         L.psb_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         for name in SYMBOLS:
-            if name != "psb_weights_destroy":
+            if name not in ("psb_weights_destroy", "psb_build_id"):
                 getattr(L, name).restype = C.c_int
+        L.psb_build_id.argtypes = []
+        L.psb_build_id.restype = C.c_char_p
+        built_from, sources = L.psb_build_id().decode(), _build.source_id()
+        if built_from != sources:        # a kernel was edited and the library not rebuilt: never run the old code
+            raise PsbError(ERR_DEVICE, f"{path} was built from other sources ({built_from[:12]}) than the ones beside "
+                                       f"it ({sources[:12]}): run python -m paper_1904_02205_amd.build")
         _lib = L
     return _lib
 

@@ -640,3 +640,15 @@ def test_conv_counter_keying(orc, prob_bits):
     added = _conv_by_hand(orc, q, wshape, x, stride, pad, seed, layer, outs, ranges, p7=p7)
     assert np.array_equal(np.array([both[o] for o in outs], dtype=np.int64),
                           np.array([first[o] for o in outs], dtype=np.int64) + added)
+
+
+# ------------------------------------------------------------------ memory and arithmetic hygiene of the oracle
+
+def test_oracle_under_address_and_undefined_behaviour_sanitizers():
+    """Every oracle entry point on small, exactly sized buffers in a build with -fsanitize=address,undefined
+    (oracle/sanitize_check.cpp): an access outside a buffer, a signed overflow or an invalid shift aborts the run."""
+    import shutil
+    if shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    from oracle import build_oracle
+    assert build_oracle.sanitize() == 0
