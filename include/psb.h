@@ -344,16 +344,46 @@ int psb_conv2d_shared_requant_blocked(const psb_weights_t* q, const int8_t* x_de
 int psb_shared_prepare_filters(const psb_weights_t* const* handles, int32_t n, int32_t S, const uint64_t* seeds,
                                const uint32_t* layer_ids, void* hip_stream);
 
-/* Budget values of a pass, told in advance [Sect. 4.5: the two-stage scheme has two].  A shared-filter call with a
- * budget map cuts the sample axis at every value that occurs in the map; by default it finds those values itself,
- * which costs a read-back and a stream synchronisation per call.  After psb_shared_budget_levels(levels, n) the
- * calling thread's shared-filter calls with budget maps take the n values of the host array `levels` instead
- * (clamped to the handle's s_max; 0 is added when there is no budget_from map), issue no synchronisation, and can
- * be captured into a HIP graph.  EVERY value that occurs in a call's maps (budget_to and budget_from, after
- * clamping) must be among them: a pixel whose budget is missing silently receives the samples of the next lower
- * listed value only.  Listed values that do not occur cost one filter sampling and one empty launch each.
- * n = 0 (levels may be NULL) restores the default.  Host only.  Errors: NULL (n > 0 without levels), SHAPE (n < 0
- * or n > 256). */
+/*
+ * The second pass of the two-stage scheme as a chain [Sect. 4.5: more samples only inside the mask, on all layers,
+ * the first samples reused].  psb_conv2d_shared_budget_requant_blocked is psb_conv2d_shared_requant_blocked with a
+ * per-pixel budget map instead of one S, and the budget values of the pass given with the call:
+ *  budget_to_dev  device, uint8 [N][OH][OW]
+ *  levels_host    host array of n_levels budget values (any order, duplicates and zeros ignored, each clamped to
+ *                 s_max); at most four distinct values (VALUE otherwise).
+ * A pixel's budget is rounded DOWN to the largest listed value it reaches (0 if it reaches none: such a pixel gets
+ * no sample, y = bias); the result is, element for element, what psb_conv2d_requant (shared = 1) gives for the map
+ * rounded that way.  The levels l_1 < l_2 < ... cut the sample axis into the nested segments [0, l_1), [l_1, l_2),
+ * ..., each with its own sampled filter; on the matrix cores all segments run in ONE launch - a tile accumulates
+ * the contractions of the segments its pixels reach in the same registers, then the fused epilogue - with no
+ * read-back, no synchronisation, no zero-fill and no separate rescale launch, so the call can be captured into a
+ * HIP graph.  Layers that do not run that way (groups > 1, a reduction that is split over the grid) take the
+ * segments one launch at a time on a rounded copy of the map, with the same results.
+ * psb_shared_prepare_filters_levels samples the filters of all segments of n handles in one launch (two when there
+ * are more than 32 filters); the next psb_conv2d_shared_budget_requant_blocked call on such a handle with the same
+ * levels, seed and layer_id uses them, once.
+ * Errors: those of psb_conv2d_shared_requant_blocked, plus NULL (budget_to_dev, levels_host), SHAPE (n_levels
+ * outside 1..256), VALUE (more than four distinct levels; prepare: no level above 0).
+ */
+int psb_conv2d_shared_budget_requant_blocked(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom,
+                                             const uint8_t* budget_to_dev, const uint8_t* levels_host, int32_t n_levels,
+                                             uint64_t seed, uint32_t layer_id, float* y_dev, const float* mult_dev,
+                                             const float* bias_dev, const psb_requant* rq, int8_t* x_out_dev,
+                                             int32_t layout, void* hip_stream);
+int psb_shared_prepare_filters_levels(const psb_weights_t* const* handles, int32_t n, const uint8_t* levels_host,
+                                      int32_t n_levels, const uint64_t* seeds, const uint32_t* layer_ids, void* hip_stream);
+
+/* Budget values of the NEXT call, told in advance [Sect. 4.5: the two-stage scheme has two].  A shared-filter call
+ * with a budget map (psb_conv2d_progressive_shared, psb_conv2d_requant with shared = 1) cuts the sample axis at
+ * every value that occurs in the map; by default it finds those values itself, which costs a read-back and a stream
+ * synchronisation.  After psb_shared_budget_levels(levels, n) the calling thread's next such call - that one call
+ * only - takes the n values of the host array `levels` instead (clamped to the handle's s_max; 0 is added when there
+ * is no budget_from map) and issues no synchronisation.  EVERY value that occurs in that call's maps (budget_to and
+ * budget_from, after clamping) must be among them: a pixel whose budget is missing receives the samples of the next
+ * lower listed value only while its result is still divided by its own budget.  (psb_conv2d_shared_budget_requant_blocked
+ * takes the levels as an argument and rounds budgets down to them instead.)  Listed values that do not occur cost
+ * one filter sampling and one empty launch each.  n = 0 (levels may be NULL) withdraws an announcement.  Host only.
+ * Errors: NULL (n > 0 without levels), SHAPE (n < 0 or n > 256). */
 int psb_shared_budget_levels(const uint8_t* levels_host, int32_t n);
 
 int psb_requantize(const float* y_dev, const float* res_f32_dev, const int8_t* res_i8_dev, float res_step,

@@ -20,7 +20,10 @@
 // Device memory of the shared-filter mode; allocated on first use, grown on demand, owned by the handle.
 struct shared_workspace {
     int32_t* w32_dev = nullptr;      // [OC][K] sampled integer filter
-    int8_t* planes_dev = nullptr;    // digit planes in matrix-core operand order
+    int8_t* planes_dev = nullptr;    // digit planes in matrix-core operand order, one buffer per segment of the sample axis
+    int planes_segments = 0;         // segments the allocation holds
+    uint8_t* qmap_dev = nullptr;     // a budget map rounded down to announced levels (calls that cannot take them in one launch)
+    size_t qmap_bytes = 0;
     int8_t* xt_dev = nullptr;        // blocked channels-last copy of the activations
     size_t xt_bytes = 0;
     uint32_t* present_dev = nullptr; // 256 flags: budget values that occur
@@ -30,7 +33,8 @@ struct shared_workspace {
     bool ready = false;
     uint64_t ready_seed = 0;
     uint32_t ready_layer = 0;
-    int32_t ready_S = 0;
+    int ready_n_seg = 0;             // segments [0, l_1), [l_1, l_2), ... of the sample axis; a uniform S is one segment
+    int ready_level[4] = {0, 0, 0, 0};
 };
 
 // Accumulator scratch of a handle for psb_conv2d_requant calls without acc_dev (grown on demand).
@@ -76,7 +80,8 @@ struct psb_weights {
 namespace {
 
 thread_local int tl_last_device_error = 0;
-// budget values announced by psb_shared_budget_levels (n = 0: none, the calls read them back from their maps)
+// budget values announced by psb_shared_budget_levels for the thread's next shared-filter call with a budget map
+// (n = 0: none, the call reads them back from its maps)
 thread_local int tl_levels_n = 0;
 thread_local uint8_t tl_levels[256];
 int g_mapping = 0;
@@ -317,16 +322,66 @@ shared_plan plan_shared(const psb_weights* q)
     return s;
 }
 
-// The digit-plane buffer of a handle (allocated on first use).
-int ensure_planes(const psb_weights* q, const shared_plan& sp)
+// Bytes of the digit planes of one segment (one chunk of padding: the kernel stages whole chunks of reduction steps).
+size_t planes_segment_bytes(const shared_plan& sp)
+{
+    return (size_t)(sp.n_ocb * sp.n_ksteps + psb::kStageSteps) * psb::kMaxPlanes * psb::kPlaneStride;
+}
+
+// The digit-plane buffer of a handle for n_seg segments (allocated on first use, grown when a call has more
+// segments than any before; growing synchronises the stream first: an earlier call may still read the old buffer).
+int ensure_planes(const psb_weights* q, const shared_plan& sp, int n_seg, hipStream_t stream)
 {
     // each digit plane is summed in int32: 128 * 128 * (padded reduction length) must stay below 2^31
-    if ((int64_t)sp.n_ksteps * 32 >= (1ll << 17)) return PSB_ERR_TOO_LARGE;
-    if (!q->ws->planes_dev) {
-        // one chunk of padding: the kernel stages whole chunks of reduction steps
-        const size_t bytes = (size_t)(sp.n_ocb * sp.n_ksteps + psb::kStageSteps) * psb::kMaxPlanes * psb::kPlaneStride;
-        if (hipMalloc(&q->ws->planes_dev, bytes) != hipSuccess) return PSB_ERR_ALLOC;   // written whole by every sampling
+    if ((int64_t)sp.n_ksteps * 32 * n_seg >= (1ll << 17)) return PSB_ERR_TOO_LARGE;
+    shared_workspace* ws = q->ws;
+    if (ws->planes_segments < n_seg) {
+        if (ws->planes_dev) {
+            PSB_HIP_TRY(hipStreamSynchronize(stream));
+            (void)hipFree(ws->planes_dev);
+            ws->planes_dev = nullptr;
+            ws->planes_segments = 0;
+            ws->ready = false;
+        }
+        if (hipMalloc(&ws->planes_dev, planes_segment_bytes(sp) * n_seg) != hipSuccess) return PSB_ERR_ALLOC;   // written whole by every sampling
+        ws->planes_segments = n_seg;
     }
+    return PSB_OK;
+}
+
+// Sorted distinct non-zero levels, clamped to s_max; at most 4 are taken in one launch (more: returns -1).
+int normalise_levels(const uint8_t* levels, int n, int s_max, int (&out)[4])
+{
+    bool seen[256] = {};
+    for (int i = 0; i < n; ++i) seen[std::min<int>(levels[i], s_max)] = true;
+    int m = 0;
+    for (int v = 1; v < 256; ++v)
+        if (seen[v]) {
+            if (m == 4) return -1;
+            out[m++] = v;
+        }
+    return m;
+}
+
+// One launch that samples the digit planes of segments [0, l_1), [l_1, l_2), ... of a handle.
+int sample_segments(const psb_weights* q, const shared_plan& sp, const int (&level)[4], int n_seg, uint64_t seed,
+                    uint32_t layer_id, int n_planes, hipStream_t stream)
+{
+    psb::FilterBatch batch;
+    std::memset(&batch, 0, sizeof(batch));
+    for (int k = 0; k <= psb::kMaxBatchJobs; ++k) batch.first_block[k] = 0xFFFFFFFFu;
+    const int64_t need = ((int64_t)sp.n_ocb * sp.n_ksteps + psb::kPlaneGroup - 1) / psb::kPlaneGroup * 4;
+    if (need * n_seg > 2147483647ll) return PSB_ERR_TOO_LARGE;
+    for (int i = 0; i < n_seg; ++i) {
+        psb::FilterJob fj = filter_job(q, i == 0 ? 0 : level[i - 1], level[i], seed, layer_id, nullptr,
+                                       q->ws->planes_dev + planes_segment_bytes(sp) * i, sp.CB, sp.n_ksteps);
+        fj.n_planes = n_planes;
+        if (sp.rowpack) { fj.pack_KW = q->shape.kw; fj.pack_C = q->shape.cin; fj.inv_pack_C = psb::inverse_of((uint32_t)q->shape.cin); }
+        batch.jobs[i] = fj;
+        batch.first_block[i] = (unsigned)(need * i);
+    }
+    hipLaunchKernelGGL(psb::k_sample_planes_batch, dim3((unsigned)(need * n_seg)), dim3(256), 0, stream, batch);
+    PSB_HIP_TRY(hipGetLastError());
     return PSB_OK;
 }
 
@@ -334,7 +389,7 @@ int ensure_planes(const psb_weights* q, const shared_plan& sp)
 int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, int32_t S, const uint8_t* budget_to,
                   const uint8_t* budget_from, uint64_t seed, uint32_t layer_id, int32_t* acc, float* y,
                   const float* mult, const float* bias, hipStream_t stream, const psb::Requant* rq = nullptr,
-                  int layout = 0)
+                  int layout = 0, const uint8_t* levels = nullptr, int n_levels = 0)
 {
     int32_t OH = 0, OW = 0;
     int rc = check_geom(&q->shape, g, &OH, &OW);
@@ -342,6 +397,18 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     int dev = 0;
     PSB_HIP_TRY(hipGetDevice(&dev));
     if (dev != q->device) return PSB_ERR_DEVICE;
+    // Levels given with the call: budgets are rounded DOWN to them.  Levels announced by psb_shared_budget_levels
+    // are for this call only and must cover the maps (nothing is rounded).
+    const bool round_down = budget_to && levels && n_levels > 0;
+    uint8_t announced[256];
+    int n_announced = 0;
+    if (budget_to && !round_down && tl_levels_n > 0) {
+        n_announced = tl_levels_n;
+        std::memcpy(announced, tl_levels, (size_t)n_announced);
+    }
+    if (budget_to) tl_levels_n = 0;                 // announced levels are used once
+    int seg_level[4] = {0, 0, 0, 0};
+    int n_seg = round_down ? normalise_levels(levels, n_levels, q->s_max, seg_level) : 0;
 
     const shared_plan sp = plan_shared(q);
     const bool mfma = sp.mfma, rowpack = sp.rowpack;
@@ -359,9 +426,59 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     if (!mfma && !ws->w32_dev && hipMalloc(&ws->w32_dev, (size_t)nw * sizeof(int32_t)) != hipSuccess)
         return PSB_ERR_ALLOC;
     if (!ws->present_dev && hipMalloc(&ws->present_dev, 256 * sizeof(uint32_t)) != hipSuccess) return PSB_ERR_ALLOC;
+    // ksplit and the tile shape decide whether the segments can share one launch: computed before the planes are sized
+    int ksplit = 1, half_tiles = 2;
     if (mfma) {
-        rc = ensure_planes(q, sp);
+        // Few pixel tiles and a long reduction: cut the reduction so that every SIMD has a wave.  Only then: the
+        // partial sums cost a zero-fill, atomics and a separate rescale pass, which measured slower than the
+        // unsplit kernel as soon as the chip is half full.
+        half_tiles = psb::shared_half_tiles((int64_t)g->n * OH * OW, n_ocb);
+        const int64_t waves = ((int64_t)g->n * OH * OW + 32 * half_tiles - 1) / (32 * half_tiles) * n_ocb;
+        const int64_t want = waves <= 512 ? (1024 + waves - 1) / waves : 1;
+        ksplit = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, 8), n_ksteps / 16));
+    }
+    // all segments in one launch, accumulated in registers, epilogue fused
+    const bool fused_segments = round_down && mfma && n_seg > 0 && !budget_from && ksplit == 1 &&
+                                (int64_t)n_ksteps * 32 * n_seg < (1ll << 17);
+    if (mfma) {
+        rc = ensure_planes(q, sp, fused_segments ? n_seg : 1, stream);
         if (rc != PSB_OK) return rc;
+    }
+    if (round_down && !fused_segments) {
+        // This call takes the segments one launch at a time (direct kernel, split reduction, more than four
+        // levels): round the map down to the levels first, then it is a map that holds only announced values.
+        const size_t need = (size_t)g->n * OH * OW;
+        if (ws->qmap_bytes < need) {
+            if (ws->qmap_dev) {
+                PSB_HIP_TRY(hipStreamSynchronize(stream));
+                (void)hipFree(ws->qmap_dev);
+                ws->qmap_dev = nullptr;
+                ws->qmap_bytes = 0;
+            }
+            if (hipMalloc(&ws->qmap_dev, need) != hipSuccess) return PSB_ERR_ALLOC;
+            ws->qmap_bytes = need;
+        }
+        uint8_t all[256];
+        int n_all = 0;
+        {
+            bool seen[256] = {};
+            for (int i = 0; i < n_levels; ++i) seen[std::min<int>(levels[i], q->s_max)] = true;
+            for (int v = 1; v < 256; ++v) if (seen[v]) all[n_all++] = (uint8_t)v;
+        }
+        if (n_all <= 4) {
+            psb::BudgetLevels bl;
+            bl.n = n_all;
+            for (int i = 0; i < 4; ++i) bl.level[i] = i < n_all ? all[i] : 0;
+            const int blocks = (int)std::min<int64_t>(((int64_t)need + 255) / 256, 1024);
+            hipLaunchKernelGGL(psb::k_budget_round_down, dim3(blocks), dim3(256), 0, stream, budget_to, (int64_t)need,
+                               q->s_max, bl, ws->qmap_dev);
+            PSB_HIP_TRY(hipGetLastError());
+        } else {
+            return PSB_ERR_VALUE;           // more than four levels
+        }
+        budget_to = ws->qmap_dev;
+        n_announced = n_all;
+        std::memcpy(announced, all, (size_t)n_all);
     }
     // blocked channels-last copy (row-packed: one 32-byte block per input row and output column)
     const size_t xt_need = (size_t)g->n * g->h * (rowpack ? OW : g->w) * C_pad;
@@ -400,17 +517,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     if (rq && ((rq->out_blocked && ((uintptr_t)rq->x_out & 3u) != 0) ||
                (rq->res_blocked && ((uintptr_t)rq->res_i8 & 3u) != 0)))
         return PSB_ERR_VALUE;
-    p.ksplit = 1;
-    int half_tiles = 2;
-    if (mfma) {
-        // Few pixel tiles and a long reduction: cut the reduction so that every SIMD has a wave.  Only then: the
-        // partial sums cost a zero-fill, atomics and a separate rescale pass, which measured slower than the
-        // unsplit kernel as soon as the chip is half full.
-        half_tiles = psb::shared_half_tiles((int64_t)g->n * OH * OW, n_ocb);
-        const int64_t waves = ((int64_t)g->n * OH * OW + 32 * half_tiles - 1) / (32 * half_tiles) * n_ocb;
-        const int64_t want = waves <= 512 ? (1024 + waves - 1) / waves : 1;
-        p.ksplit = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, 8), n_ksteps / 16));
-    }
+    p.ksplit = ksplit;
     const int max_shift = q->info.e_top - q->info.e_min;
     const int64_t npix = (int64_t)g->n * OH * OW;
     if (!mfma && p.OC > 65535) return PSB_ERR_TOO_LARGE;
@@ -435,7 +542,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         // matrix cores: one thread per slot of the operand-ordered planes; otherwise one per weight
         // planes sampled ahead of this call (psb_shared_prepare_filters) are used once
         const bool have = mfma && ws->ready && ws->ready_seed == seed && ws->ready_layer == layer_id && from == 0 &&
-                          to == ws->ready_S;
+                          ws->ready_n_seg == 1 && to == ws->ready_level[0];
         ws->ready = false;
         const int64_t filter_blocks = have ? 0 : mfma ? ((int64_t)n_ocb * n_ksteps + psb::kPlaneGroup - 1) / psb::kPlaneGroup * 4 : (nw + 255) / 256;
         if (filter_blocks + transpose_blocks > 2147483647ll) return PSB_ERR_TOO_LARGE;
@@ -483,7 +590,7 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     };
 
     const int64_t total = npix * p.OC;
-    if (!acc && (p.ksplit > 1 || budget_to)) {      // partial sums meet in the accumulators
+    if (!acc && !fused_segments && (p.ksplit > 1 || budget_to)) {      // partial sums meet in the accumulators
         acc = scratch_acc(ws, (size_t)total * sizeof(int32_t), stream);
         if (!acc) return PSB_ERR_ALLOC;
         p.acc = acc;
@@ -505,6 +612,36 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         return PSB_OK;
     };
 
+    if (fused_segments) {
+        int longest = 0;
+        for (int i = 0; i < n_seg; ++i) longest = std::max(longest, seg_level[i] - (i ? seg_level[i - 1] : 0));
+        const int n_planes = psb::planes_needed(max_shift, longest);
+        bool have = ws->ready && ws->ready_seed == seed && ws->ready_layer == layer_id && ws->ready_n_seg == n_seg;
+        for (int i = 0; have && i < n_seg; ++i) have = ws->ready_level[i] == seg_level[i];
+        ws->ready = false;
+        if (!have) {
+            rc = sample_segments(q, sp, seg_level, n_seg, seed, layer_id, n_planes, stream);
+            if (rc != PSB_OK) return rc;
+        }
+        if (transpose_blocks > 0) {                 // the layout copy alone
+            if (transpose_blocks > 2147483647ll) return PSB_ERR_TOO_LARGE;
+            psb::FilterJob none;
+            std::memset(&none, 0, sizeof(none));
+            hipLaunchKernelGGL(psb::k_shared_prologue, dim3((unsigned)transpose_blocks), dim3(256), 0, stream, none, tj, 0u);
+            PSB_HIP_TRY(hipGetLastError());
+        }
+        p.n_seg = n_seg;
+        for (int i = 0; i < 4; ++i) p.seg_level[i] = seg_level[i];
+        p.seg_stride = (uint64_t)planes_segment_bytes(sp);
+        p.masked = 0;
+        int slot = 0;
+        const bool timed = profile_begin(stream, &slot);
+        psb::launch_conv_shared_mfma(p, n_planes, 0, half_tiles, stream);
+        if (timed) profile_end(stream, slot);
+        PSB_HIP_TRY(hipGetLastError());
+        return PSB_OK;
+    }
+
     if (!budget_to) {
         rc = prepare(0, S);
         if (rc != PSB_OK) return rc;
@@ -520,9 +657,9 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
 
     // per-pixel budgets: the distinct clamped budget values cut the sample axis into segments
     uint32_t present[256];
-    if (tl_levels_n > 0) {                          // announced by the caller: nothing to read back
+    if (n_announced > 0) {                          // announced by the caller: nothing to read back
         std::memset(present, 0, sizeof(present));
-        for (int i = 0; i < tl_levels_n; ++i) present[std::min<int>(tl_levels[i], q->s_max)] = 1u;
+        for (int i = 0; i < n_announced; ++i) present[std::min<int>(announced[i], q->s_max)] = 1u;
         if (!budget_from) present[0] = 1u;
     } else {
         PSB_HIP_TRY(hipMemsetAsync(ws->present_dev, 0, sizeof(present), stream));
@@ -753,6 +890,7 @@ void psb_weights_destroy(psb_weights_t* q)
         if (q->ws->planes_dev) (void)hipFree(q->ws->planes_dev);
         if (q->ws->xt_dev) (void)hipFree(q->ws->xt_dev);
         if (q->ws->present_dev) (void)hipFree(q->ws->present_dev);
+        if (q->ws->qmap_dev) (void)hipFree(q->ws->qmap_dev);
         if (q->ws->acc_dev) (void)hipFree(q->ws->acc_dev);
         delete q->ws;
     }
@@ -902,18 +1040,12 @@ int psb_shared_budget_levels(const uint8_t* levels_host, int32_t n)
     return PSB_OK;
 }
 
-int psb_shared_prepare_filters(const psb_weights_t* const* handles, int32_t n, int32_t S, const uint64_t* seeds,
-                               const uint32_t* layer_ids, void* hip_stream)
+// Digit planes of n handles sampled ahead of their calls, for the segments [0, l_1), [l_1, l_2), ... of the sample axis.
+static int prepare_filters(const psb_weights_t* const* handles, int32_t n, const uint8_t* levels, int32_t n_levels,
+                           const uint64_t* seeds, const uint32_t* layer_ids, hipStream_t stream)
 {
-    if (!handles || !seeds || !layer_ids) return PSB_ERR_NULL;
-    if (n <= 0) return PSB_ERR_SHAPE;
-    for (int i = 0; i < n; ++i) {
-        if (!handles[i]) return PSB_ERR_NULL;
-        if (S <= 0 || S > handles[i]->s_max) return PSB_ERR_VALUE;
-    }
     int dev = 0;
     PSB_HIP_TRY(hipGetDevice(&dev));
-    hipStream_t stream = (hipStream_t)hip_stream;
     psb::FilterBatch batch;
     int n_jobs = 0;
     int64_t blocks = 0;
@@ -936,24 +1068,88 @@ int psb_shared_prepare_filters(const psb_weights_t* const* handles, int32_t n, i
         if (q->device != dev) return PSB_ERR_DEVICE;
         const shared_plan sp = plan_shared(q);
         if (!sp.mfma) continue;                 // the direct kernel samples its filter in the call itself
-        int rc = ensure_planes(q, sp);
+        int level[4] = {0, 0, 0, 0};
+        const int n_seg = normalise_levels(levels, n_levels, q->s_max, level);
+        if (n_seg <= 0) return PSB_ERR_VALUE;   // no level above 0, or more than four
+        if ((int64_t)sp.n_ksteps * 32 * n_seg >= (1ll << 17)) continue;    // the call takes its segments one at a time
+        int rc = ensure_planes(q, sp, n_seg, stream);
         if (rc != PSB_OK) return rc;
+        int longest = 0;
+        for (int k = 0; k < n_seg; ++k) longest = std::max(longest, level[k] - (k ? level[k - 1] : 0));
+        const int n_planes = psb::planes_needed(q->info.e_top - q->info.e_min, longest);
         const int64_t need = ((int64_t)sp.n_ocb * sp.n_ksteps + psb::kPlaneGroup - 1) / psb::kPlaneGroup * 4;
-        if (n_jobs == psb::kMaxBatchJobs || blocks + need > 2147483647ll) {
-            rc = flush();
-            if (rc != PSB_OK) return rc;
-        }
         if (need > 2147483647ll) return PSB_ERR_TOO_LARGE;
-        psb::FilterJob fj = filter_job(q, 0, S, seeds[i], layer_ids[i], nullptr, q->ws->planes_dev, sp.CB, sp.n_ksteps);
-        fj.n_planes = psb::planes_needed(q->info.e_top - q->info.e_min, S);
-        if (sp.rowpack) { fj.pack_KW = q->shape.kw; fj.pack_C = q->shape.cin; fj.inv_pack_C = psb::inverse_of((uint32_t)q->shape.cin); }
-        batch.jobs[n_jobs] = fj;
-        batch.first_block[n_jobs] = (unsigned)blocks;
-        n_jobs++;
-        blocks += need;
-        q->ws->ready = true; q->ws->ready_seed = seeds[i]; q->ws->ready_layer = layer_ids[i]; q->ws->ready_S = S;
+        for (int k = 0; k < n_seg; ++k) {
+            if (n_jobs == psb::kMaxBatchJobs || blocks + need > 2147483647ll) {
+                rc = flush();
+                if (rc != PSB_OK) return rc;
+            }
+            psb::FilterJob fj = filter_job(q, k ? level[k - 1] : 0, level[k], seeds[i], layer_ids[i], nullptr,
+                                           q->ws->planes_dev + planes_segment_bytes(sp) * k, sp.CB, sp.n_ksteps);
+            fj.n_planes = n_planes;
+            if (sp.rowpack) { fj.pack_KW = q->shape.kw; fj.pack_C = q->shape.cin; fj.inv_pack_C = psb::inverse_of((uint32_t)q->shape.cin); }
+            batch.jobs[n_jobs] = fj;
+            batch.first_block[n_jobs] = (unsigned)blocks;
+            n_jobs++;
+            blocks += need;
+        }
+        q->ws->ready = true; q->ws->ready_seed = seeds[i]; q->ws->ready_layer = layer_ids[i];
+        q->ws->ready_n_seg = n_seg;
+        for (int k = 0; k < 4; ++k) q->ws->ready_level[k] = level[k];
     }
     return flush();
+}
+
+int psb_shared_prepare_filters(const psb_weights_t* const* handles, int32_t n, int32_t S, const uint64_t* seeds,
+                               const uint32_t* layer_ids, void* hip_stream)
+{
+    if (!handles || !seeds || !layer_ids) return PSB_ERR_NULL;
+    if (n <= 0) return PSB_ERR_SHAPE;
+    for (int i = 0; i < n; ++i) {
+        if (!handles[i]) return PSB_ERR_NULL;
+        if (S <= 0 || S > handles[i]->s_max) return PSB_ERR_VALUE;
+    }
+    const uint8_t level = (uint8_t)S;
+    return prepare_filters(handles, n, &level, 1, seeds, layer_ids, (hipStream_t)hip_stream);
+}
+
+int psb_shared_prepare_filters_levels(const psb_weights_t* const* handles, int32_t n, const uint8_t* levels_host,
+                                      int32_t n_levels, const uint64_t* seeds, const uint32_t* layer_ids, void* hip_stream)
+{
+    if (!handles || !seeds || !layer_ids || !levels_host) return PSB_ERR_NULL;
+    if (n <= 0 || n_levels <= 0 || n_levels > 256) return PSB_ERR_SHAPE;
+    for (int i = 0; i < n; ++i)
+        if (!handles[i]) return PSB_ERR_NULL;
+    return prepare_filters(handles, n, levels_host, n_levels, seeds, layer_ids, (hipStream_t)hip_stream);
+}
+
+int psb_conv2d_shared_budget_requant_blocked(const psb_weights_t* q, const int8_t* x_dev, const psb_conv_geom* geom,
+                                             const uint8_t* budget_to_dev, const uint8_t* levels_host, int32_t n_levels,
+                                             uint64_t seed, uint32_t layer_id, float* y_dev, const float* mult_dev,
+                                             const float* bias_dev, const psb_requant* rq, int8_t* x_out_dev,
+                                             int32_t layout, void* hip_stream)
+{
+    if (!q || !x_dev || !geom || !budget_to_dev || !levels_host || (!y_dev && !x_out_dev) || (x_out_dev && !rq))
+        return PSB_ERR_NULL;
+    if (n_levels <= 0 || n_levels > 256) return PSB_ERR_SHAPE;
+    if (layout & ~(PSB_BLOCKED_IN | PSB_BLOCKED_OUT | PSB_BLOCKED_RES)) return PSB_ERR_VALUE;
+    {
+        int level[4];
+        if (normalise_levels(levels_host, n_levels, q->s_max, level) < 0) return PSB_ERR_VALUE;     // more than four
+    }
+    if (!x_out_dev)         // the rescaled values only
+        return launch_shared(q, x_dev, geom, 0, budget_to_dev, nullptr, seed, layer_id, nullptr, y_dev, mult_dev, bias_dev,
+                             (hipStream_t)hip_stream, nullptr, layout & PSB_BLOCKED_IN, levels_host, n_levels);
+    if (rq->res_f32_dev && rq->res_i8_dev) return PSB_ERR_VALUE;
+    if (rq->lo < -128 || rq->hi > 127 || rq->lo > rq->hi || !(rq->inv_step >= 0.0f)) return PSB_ERR_VALUE;
+    psb::Requant r;
+    std::memset(&r, 0, sizeof(r));
+    r.x_out = x_out_dev; r.res_f32 = rq->res_f32_dev; r.res_i8 = rq->res_i8_dev; r.res_step = rq->res_step;
+    r.inv_step = rq->inv_step; r.lo = (float)rq->lo; r.hi = (float)rq->hi; r.relu = rq->relu;
+    r.out_blocked = (layout & PSB_BLOCKED_OUT) != 0;
+    r.res_blocked = (layout & PSB_BLOCKED_RES) != 0 && rq->res_i8_dev;
+    return launch_shared(q, x_dev, geom, 0, budget_to_dev, nullptr, seed, layer_id, nullptr, y_dev, mult_dev, bias_dev,
+                         (hipStream_t)hip_stream, &r, layout, levels_host, n_levels);
 }
 
 // ---- glue between layers ------------------------------------------------------------------------------

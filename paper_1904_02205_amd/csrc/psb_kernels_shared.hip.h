@@ -64,6 +64,14 @@ struct SharedParams {
     int ksplit;                // the reduction is cut into ksplit parts (grid z); > 1: results are added atomically
     int masked;                // 0: every pixel, acc overwritten, epilogue fused.  1: only pixels whose sample
     int seg_from, seg_to;      //    range contains [seg_from, seg_to); acc accumulated
+    // Budget map with announced levels, in one launch (n_seg > 0; masked = 0, budget_to given, no budget_from):
+    // levels l_1 < ... < l_n cut the sample axis into nested segments [l_(i-1), l_i), l_0 = 0, each with its own
+    // sampled filter (digit planes seg_stride bytes apart).  A pixel's budget is rounded DOWN to a level (0 if it is
+    // below all of them); the pixel takes part in segment i when that level is >= l_i.  The segments' contractions
+    // accumulate in the same registers (a pixel that does not take part feeds zeros), and the epilogue is fused.
+    int n_seg;
+    int seg_level[4];
+    uint64_t seg_stride;
     float default_mult;
     Requant rq;
     // [N][OC][OH][OW] byte tensors of the fused requantisation move as 32-bit words (four pixels of one channel,
@@ -380,11 +388,33 @@ __global__ void __launch_bounds__(256) k_budget_levels(const uint8_t* __restrict
     }
 }
 
+// out[i] = the largest of the n ascending levels that min(in[i], s_max) reaches, 0 if it reaches none
+struct BudgetLevels { int n; int level[4]; };
+__global__ void __launch_bounds__(256) k_budget_round_down(const uint8_t* __restrict__ in, int64_t npix, int s_max,
+                                                           const BudgetLevels lv, uint8_t* __restrict__ out)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < npix; i += (int64_t)gridDim.x * blockDim.x) {
+        const int to = min((int)in[i], s_max);
+        int eff = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (k < lv.n && lv.level[k] <= to) eff = lv.level[k];
+        out[i] = (uint8_t)eff;
+    }
+}
+
 // sample range of a pixel and whether it takes part in this launch
 __device__ __forceinline__ bool shared_pixel_range(const SharedParams& p, int64_t pix, int& to)
 {
     to = p.budget_to ? (int)p.budget_to[pix] : p.S;
     to = min(to, p.s_max);
+    if (p.n_seg > 0) {                 // the largest announced level that the budget reaches
+        int eff = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i < p.n_seg && p.seg_level[i] <= to) eff = p.seg_level[i];
+        to = eff;
+    }
     if (!p.masked) return true;
     int from = p.budget_from ? (int)p.budget_from[pix] : 0;
     from = min(from, to);
@@ -664,6 +694,7 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
 {
     __shared__ v4i a_lds[kStageSteps * P * 64];
     __shared__ float s_mult[32], s_bias[32];       // rescale factors of this block of channels (read after the loop)
+    __shared__ int s_takes_part[4];                // per wave: one of its pixels takes part in the segment voted on
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -683,7 +714,8 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     const int per_split = (n_steps + p.ksplit - 1) / p.ksplit;
     const int s_begin = (int)blockIdx.z * per_split;
     const int s_end = min(n_steps, s_begin + per_split);
-    const int8_t* wblock = p.planes + (int64_t)ocb * p.n_ksteps * (kMaxPlanes * kPlaneStride);
+    const int8_t* const wblock0 = p.planes + (int64_t)ocb * p.n_ksteps * (kMaxPlanes * kPlaneStride);
+    const int8_t* wblock = wblock0;                // the channel block in the planes of the current segment
 
     // weights: operand i of a chunk (i = (step * P + plane) * 64 + lane) is fetched by thread i mod 256; its byte
     // offset inside the chunk is fixed.  A chunk may reach past the last step: the buffer is padded by one chunk
@@ -722,54 +754,78 @@ __global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
     const uint32_t cb_stride = (uint32_t)p.tW * 32u;            // bytes between the channel blocks of one pixel
     const uint32_t row_stride = (uint32_t)CB * cb_stride;       // ... between the rows of one image
     const __amdgpu_buffer_rsrc_t xt_rsrc = operand_buffer(p.xt, p.xt_bytes);
-    TapCursor<HT> cur;
-    cur.start(p, min(s_begin, n_steps - 1), CB, cb_stride, row_stride, live, iy0, ix0, origin);
-    // one-half-tile waves run alone or nearly alone on their SIMD (that is when they are chosen) and have registers
-    // to spare: a deeper pipeline hides more of the load latency there (stage 4 of ResNet-18: 28 -> 24.5 us)
-    constexpr int kDepthT = HT == 1 ? kStageSteps : kDepth;
-    v4i opb[kDepthT][HT];
-    auto request = [&](int slot) {
-#pragma unroll
-        for (int h = 0; h < HT; ++h) opb[slot][h] = load_operand(xt_rsrc, cur.tap_off[h], cur.cboff);
-        cur.advance(p, n_steps, CB, cb_stride, row_stride, live, iy0, ix0, origin);
-    };
-
-    if (active) {
-#pragma unroll
-        for (int d = 0; d < kDepthT; ++d) request(d);
-    }
     if (OUT != kOutPartial && threadIdx.x < 32) {    // visible to every wave after the loop's first barrier
         const int oc = ocb * 32 + (int)threadIdx.x;
         s_mult[threadIdx.x] = (p.mult && oc < p.OC) ? p.mult[oc] : p.default_mult;
         s_bias[threadIdx.x] = (p.bias && oc < p.OC) ? p.bias[oc] : 0.0f;
     }
-    for (int s0 = s_begin; s0 < s_end; s0 += kStageSteps) {
-        __syncthreads();                             // the previous chunk has been consumed by every wave
+
+    // One pass over the reduction per segment of the sample axis (one pass when there are no segments).  The passes
+    // accumulate into the same registers: a pixel that does not take part in a segment feeds zeros, because its
+    // operand offsets are out of range.
+    const int n_seg = p.n_seg > 0 ? p.n_seg : 1;
+    for (int seg = 0; seg < n_seg; ++seg) {
+        bool lv[2] = {live[0], live[1]};             // pixels that take part in this pass
+        if (p.n_seg > 0) {
 #pragma unroll
-        for (int r = 0; r < kStageRegs; ++r) a_lds[r * 256 + threadIdx.x] = stage[r];
-        __syncthreads();
-        if (s0 + kStageSteps < s_end) fetch_weights(s0 + kStageSteps);       // uniform over the workgroup
-        if (active) {
-            // the weight operands of step ks + 1 are read from LDS while the matrix instructions of step ks run
-            v4i a[2][P];
+            for (int h = 0; h < 2; ++h) lv[h] = live[h] && to_[h] >= p.seg_level[seg];
+            if (seg > 0) {
+                // Levels nest: when no pixel of the workgroup reaches this one, none reaches a later one.  The
+                // decision has to be the workgroup's (the passes have barriers).  The votes of two segments cannot
+                // mix: a pass, with its barriers, lies between them.
+                const int mine = (__ballot(lv[0] || lv[1]) != 0ull) ? 1 : 0;       // taken by the whole wave
+                if (lane == 0) s_takes_part[wave] = mine;
+                __syncthreads();
+                if ((s_takes_part[0] | s_takes_part[1] | s_takes_part[2] | s_takes_part[3]) == 0) break;
+                wblock = wblock0 + (int64_t)seg * p.seg_stride;
+                fetch_weights(s_begin);
+            }
+        }
+        const bool active_seg = __ballot(lv[0] || lv[1]) != 0ull;
+        TapCursor<HT> cur;
+        cur.start(p, min(s_begin, n_steps - 1), CB, cb_stride, row_stride, lv, iy0, ix0, origin);
+        // one-half-tile waves run alone or nearly alone on their SIMD (that is when they are chosen) and have registers
+        // to spare: a deeper pipeline hides more of the load latency there (stage 4 of ResNet-18: 28 -> 24.5 us)
+        constexpr int kDepthT = HT == 1 ? kStageSteps : kDepth;
+        v4i opb[kDepthT][HT];
+        auto request = [&](int slot) {
 #pragma unroll
-            for (int b = 0; b < P; ++b) a[0][b] = a_lds[b * 64 + lane];
+            for (int h = 0; h < HT; ++h) opb[slot][h] = load_operand(xt_rsrc, cur.tap_off[h], cur.cboff);
+            cur.advance(p, n_steps, CB, cb_stride, row_stride, lv, iy0, ix0, origin);
+        };
+
+        if (active_seg) {
 #pragma unroll
-            for (int ks = 0; ks < kStageSteps; ++ks) {
-                const int d = ks % kDepthT;
-                if (ks + 1 < kStageSteps) {
+            for (int d = 0; d < kDepthT; ++d) request(d);
+        }
+        for (int s0 = s_begin; s0 < s_end; s0 += kStageSteps) {
+            __syncthreads();                             // the previous chunk has been consumed by every wave
 #pragma unroll
-                    for (int b = 0; b < P; ++b) a[(ks + 1) & 1][b] = a_lds[((ks + 1) * P + b) * 64 + lane];
+            for (int r = 0; r < kStageRegs; ++r) a_lds[r * 256 + threadIdx.x] = stage[r];
+            __syncthreads();
+            if (s0 + kStageSteps < s_end) fetch_weights(s0 + kStageSteps);       // uniform over the workgroup
+            if (active_seg) {
+                // the weight operands of step ks + 1 are read from LDS while the matrix instructions of step ks run
+                v4i a[2][P];
+#pragma unroll
+                for (int b = 0; b < P; ++b) a[0][b] = a_lds[b * 64 + lane];
+#pragma unroll
+                for (int ks = 0; ks < kStageSteps; ++ks) {
+                    const int d = ks % kDepthT;
+                    if (ks + 1 < kStageSteps) {
+#pragma unroll
+                        for (int b = 0; b < P; ++b) a[(ks + 1) & 1][b] = a_lds[((ks + 1) * P + b) * 64 + lane];
+                    }
+                    if (s0 + ks < s_end) {               // wave-uniform
+#pragma unroll
+                        for (int b = 0; b < P; ++b)
+#pragma unroll
+                            for (int h = 0; h < HT; ++h)
+                                acc[h][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][h], acc[h][b], 0, 0, 0);
+                    }
+                    request(d);     // unconditional (past the end: the last step again), so that the number of
+                                    // loads in flight is the same on every path and no wait is longer than needed
                 }
-                if (s0 + ks < s_end) {               // wave-uniform
-#pragma unroll
-                    for (int b = 0; b < P; ++b)
-#pragma unroll
-                        for (int h = 0; h < HT; ++h)
-                            acc[h][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[d][h], acc[h][b], 0, 0, 0);
-                }
-                request(d);     // unconditional (past the end: the last step again), so that the number of
-                                // loads in flight is the same on every path and no wait is longer than needed
             }
         }
     }
@@ -1026,7 +1082,7 @@ inline void launch_conv_shared_mfma(const SharedParams& p, int planes, int resid
     // worth it when a workgroup gets more than one tile: staging the whole block before the first matrix instruction
     // costs more than the chunked start of the plain kernel
     const unsigned fit = std::max(8u, (unsigned)std::max(resident_wgs, 0) / n_ocb / 8u * 8u);
-    if (half_tiles == 2 && resident_wgs > 0 && !p.masked && p.ksplit == 1 && lds <= 65536 && columns > fit) {
+    if (half_tiles == 2 && resident_wgs > 0 && !p.masked && p.n_seg == 0 && p.ksplit == 1 && lds <= 65536 && columns > fit) {
         const dim3 grid(fit, n_ocb);
         if (p.rq.x_out) launch_conv_shared_mfma_resident<kOutRequant>(p, planes, grid, columns, lds, stream);
         else launch_conv_shared_mfma_resident<kOutAcc>(p, planes, grid, columns, lds, stream);

@@ -33,6 +33,7 @@ class ResNet18:
         self.x0 = torch.from_numpy(net.x0).to(device)
         self.record_inputs = False      # benchmarks: keep the input tensor of every layer of the last pass
         self.inputs = {}
+        self._levels = None             # budget values of the pass that is running, if the caller gave them
 
     def _input_steps(self):
         """Real value of one integer step of each layer's input activations."""
@@ -57,6 +58,8 @@ class ResNet18:
         if budget is not None:
             oh = (x.shape[2] + 2 * sp.pad - sp.k) // sp.stride + 1
             bt = psb.budget_resample(budget, oh, oh)
+            if shared and self._levels is not None:
+                psb.shared_budget_levels(self._levels)      # for this call: it need not read the values back
         return psb.conv2d_requant(self.q[i], x, inv_step, S=None if bt is not None else S, budget_to=bt,
                                   stride=(sp.stride, sp.stride), pad=(sp.pad, sp.pad), seed=self.seed, layer_id=i,
                                   res_f32=res_f32, res_i8=res_i8, res_step=res_step, mult=self.mult[i],
@@ -75,20 +78,30 @@ class ResNet18:
         if budget is None:
             psb.conv2d(self.q[i], x, S, **kw)
         else:
-            psb.conv2d_progressive(self.q[i], x, psb.budget_resample(budget, oh, oh), None, **kw)
+            bt = psb.budget_resample(budget, oh, oh)
+            if shared and self._levels is not None:
+                psb.shared_budget_levels(self._levels)
+            psb.conv2d_progressive(self.q[i], x, bt, None, **kw)
         return y
 
-    def _chain_call(self, i, x, x_shape, S, inv_step, layout, **kw):
+    def _chain_call(self, i, x, x_shape, S, inv_step, layout, budget=None, maps=None, **kw):
+        """Convolution i of a chained pass: uniform S, or (budget given) the budget map resampled to the layer's
+        output resolution with its values rounded down to self._levels - all sample segments in one launch."""
         sp = self.net.specs[i]
-        return psb.conv2d_shared_requant_blocked(self.q[i], x, x_shape, inv_step, S, stride=(sp.stride, sp.stride),
-                                                 pad=(sp.pad, sp.pad), seed=self.seed, layer_id=i, mult=self.mult[i],
-                                                 bias=self.bias[i], layout=layout, **kw)
+        common = dict(stride=(sp.stride, sp.stride), pad=(sp.pad, sp.pad), seed=self.seed, layer_id=i,
+                      mult=self.mult[i], bias=self.bias[i], layout=layout, **kw)
+        if budget is None:
+            return psb.conv2d_shared_requant_blocked(self.q[i], x, x_shape, inv_step, S, **common)
+        oh = (x_shape[2] + 2 * sp.pad - sp.k) // sp.stride + 1
+        if oh not in maps:                       # one resampled map per resolution and pass
+            maps[oh] = psb.budget_resample(budget, oh, oh)
+        return psb.conv2d_shared_budget_requant_blocked(self.q[i], x, x_shape, inv_step, maps[oh], self._levels, **common)
 
-    def _forward_chain(self, S, collect):
-        """Shared-filter pass with a uniform sample count, as one chain on the GPU: every filter of the pass is
-        sampled in one launch up front, and between the convolutions the activations stay in the blocked
-        channels-last layout that the matrix-core kernel reads in place (no layout copies).  Same integers as the
-        layer-by-layer pass."""
+    def _forward_chain(self, S, collect, budget=None, s_fc=None):
+        """Shared-filter pass as one chain on the GPU: every filter of the pass is sampled in one launch up front
+        (with a budget map: the filters of every segment between its levels), and between the convolutions the
+        activations stay in the blocked channels-last layout that the matrix-core kernel reads in place (no layout
+        copies).  Same integers as the layer-by-layer pass."""
         def keep(t, shape=None):
             if collect is None:
                 return
@@ -98,8 +111,15 @@ class ResNet18:
             collect.append(t)
         inv_relu, inv_block = float(np.float32(1.0 / rs.STEP_RELU)), float(np.float32(1.0 / rs.STEP_BLOCK))
         n_layers = len(self.q)
-        psb.shared_prepare_filters(self.q, S, [self.seed] * n_layers, list(range(n_layers)))
-        a = self._conv_requant(0, self.x0, S, None, True, inv_relu)
+        maps = {}
+        bkw = dict(budget=budget, maps=maps)
+        if budget is None:
+            psb.shared_prepare_filters(self.q, S, [self.seed] * n_layers, list(range(n_layers)))
+            a = self._conv_requant(0, self.x0, S, None, True, inv_relu)
+        else:
+            psb.shared_prepare_filters_levels(self.q[:-1], self._levels, [self.seed] * (n_layers - 1),
+                                              list(range(n_layers - 1)))
+            a = self._chain_call(0, self.x0, tuple(self.x0.shape), S, inv_relu, 0, **bkw)
         keep(a)
         a = psb.maxpool2d_i8(a, (3, 3), (2, 2), (1, 1))
         keep(a)
@@ -114,15 +134,15 @@ class ResNet18:
             oh = (shape[2] + 2 * sp.pad - sp.k) // sp.stride + 1
             shape1 = (shape[0], sp.cout, oh, oh)
             lin = B_IN if blocked else 0
-            a1 = self._chain_call(i, a, shape, S, inv_relu, lin | B_OUT)
+            a1 = self._chain_call(i, a, shape, S, inv_relu, lin | B_OUT, **bkw)
             keep(a1, shape1)
             lout = 0 if last else B_OUT              # the average pooling reads [N, C, H, W]
             if has_sc:
-                ysc = self._chain_call(i + 2, a, shape, S, 0.0, lin, want_x=False)
-                a = self._chain_call(i + 1, a1, shape1, S, inv_block, B_IN | lout, res_f32=ysc)
+                ysc = self._chain_call(i + 2, a, shape, S, 0.0, lin, want_x=False, **bkw)
+                a = self._chain_call(i + 1, a1, shape1, S, inv_block, B_IN | lout, res_f32=ysc, **bkw)
             else:
                 a = self._chain_call(i + 1, a1, shape1, S, inv_block, B_IN | lout | (B_RES if blocked else 0), res_i8=a,
-                                     res_step=float(np.float32(step_a)))
+                                     res_step=float(np.float32(step_a)), **bkw)
             shape, blocked = shape1, not last
             keep(a, shape if blocked else None)
             step_a = rs.STEP_BLOCK
@@ -132,8 +152,8 @@ class ResNet18:
         n = pooled.shape[0]
         logits = torch.empty((n, self.net.specs[i].cout), dtype=torch.float32, device=self.device)
         acc = torch.empty((n, self.net.specs[i].cout), dtype=torch.int32, device=self.device)
-        psb.linear(self.q[i], pooled, S, seed=self.seed, layer_id=i, acc=acc, y=logits, mult=self.mult[i],
-                   bias=self.bias[i], shared=True)
+        psb.linear(self.q[i], pooled, s_fc if s_fc is not None else S, seed=self.seed, layer_id=i, acc=acc, y=logits,
+                   mult=self.mult[i], bias=self.bias[i], shared=True)
         return logits
 
     def forward(self, S=8, budget=None, s_fc=None, shared=False, collect=None, fused=True, chain=None, levels=None):
@@ -142,20 +162,21 @@ class ResNet18:
         activations are the same integers either way.  chain: run a shared-filter pass with a uniform sample count
         as one chain (see _forward_chain); by default whenever that applies.  levels: the values the budget map
         holds, if the caller knows them (nearest-pixel resampling only ever drops values): a shared-filter pass
-        then announces them to the library once instead of every layer reading them back from its map."""
-        if budget is not None and shared and levels is not None:
-            psb.shared_budget_levels(levels)
-            try:
-                return self.forward(S, budget, s_fc, shared, collect, fused, chain, None)
-            finally:
-                psb.shared_budget_levels(None)
-        can_chain = shared and fused and budget is None and (s_fc is None or s_fc == S) and not self.record_inputs
+        then runs as a chain too (every layer takes the levels with its call, all sample segments in one launch), or,
+        layer by layer, announces them before every call instead of reading them back from the map."""
+        self._levels = None
+        if budget is not None and levels is not None:
+            self._levels = tuple(sorted({int(v) for v in levels}))
+        uniform = budget is None and (s_fc is None or s_fc == S)
+        masked = budget is not None and self._levels is not None and len([v for v in self._levels if v > 0]) <= 4
+        can_chain = shared and fused and (uniform or masked) and not self.record_inputs
         if chain is None:
             chain = can_chain
         if chain:
             if not can_chain:
-                raise ValueError("chain=True needs shared=True, fused=True, no budget map and s_fc == S")
-            return self._forward_chain(S, collect)
+                raise ValueError("chain=True needs shared=True, fused=True, and either no budget map and s_fc == S or "
+                                 "a budget map with at most four levels given")
+            return self._forward_chain(S, collect, budget, s_fc)
         keep = (lambda t: collect.append(t)) if collect is not None else (lambda t: None)
         inv_relu, inv_block = float(np.float32(1.0 / rs.STEP_RELU)), float(np.float32(1.0 / rs.STEP_BLOCK))
         if fused:
@@ -200,17 +221,19 @@ class ResNet18:
                    mult=self.mult[i], bias=self.bias[i], shared=shared)
         return logits
 
-    def capture(self, S=8, shared=False):
+    def capture(self, S=8, shared=False, budget=None, s_fc=None, levels=None):
         """Record one pass with a uniform sample count into a HIP graph.  Returns (graph, logits): graph.replay()
         reruns the pass (same seed, same bits) into the same logits tensor without any per-launch host work.
         The pass is run once eagerly first, so that every workspace the library allocates on first use exists
-        before the capture starts; passes with a budget map cannot be captured (they read back which budget
-        values occur)."""
-        self.forward(S=S, shared=shared)
+        before the capture starts.  A shared-filter pass with a budget map can be captured when its levels are
+        given (the map tensor is read at every replay); other passes with a budget map cannot (they read back
+        which budget values occur)."""
+        kw = dict(S=S, shared=shared, budget=budget, s_fc=s_fc, levels=levels)
+        self.forward(**kw)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            logits = self.forward(S=S, shared=shared)
+            logits = self.forward(**kw)
         return graph, logits
 
     def forward_attention(self, s_lo=8, s_hi=16, shared=False):

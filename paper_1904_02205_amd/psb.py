@@ -21,7 +21,7 @@ MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE, MAPPING_PRODUCT_LIST = 0
 SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
            "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
-           "psb_conv2d_requant", "psb_conv2d_requant_static", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_shared_budget_levels", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
+           "psb_conv2d_requant", "psb_conv2d_requant_static", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_shared_prepare_filters_levels", "psb_conv2d_shared_budget_requant_blocked", "psb_shared_budget_levels", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
            "psb_attention_budget", "psb_last_device_error", "psb_build_id", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
            "psb_profile_read"]
 
@@ -89,6 +89,9 @@ def lib():
                                                         C.POINTER(Requant), vp, i32, vp]
         L.psb_shared_prepare_filters.argtypes = [vp, i32, i32, vp, vp, vp]
         L.psb_shared_budget_levels.argtypes = [vp, i32]
+        L.psb_shared_prepare_filters_levels.argtypes = [vp, i32, vp, i32, vp, vp, vp]
+        L.psb_conv2d_shared_budget_requant_blocked.argtypes = [vp, vp, C.POINTER(ConvGeom), vp, vp, i32, u64, u32, vp, vp,
+                                                               vp, C.POINTER(Requant), vp, i32, vp]
         L.psb_conv2d_requant.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, vp, u64, u32, vp, vp, vp, vp,
                                          C.POINTER(Requant), vp, i32, vp]
         L.psb_conv2d_requant_static.argtypes = [vp, vp, C.POINTER(ConvGeom), i32, vp, u64, u32, vp, vp, vp,
@@ -382,6 +385,59 @@ def conv2d_shared_requant_blocked(q, x, x_shape, inv_step, S, stride=(1, 1), pad
     return x_out if want_x else y
 
 
+def _levels_array(levels):
+    vals = sorted({int(v) for v in levels})
+    if not vals or min(vals) < 0 or max(vals) > 255:
+        raise ValueError("levels: one or more budget values in 0..255")
+    return (C.c_uint8 * len(vals))(*vals), len(vals)
+
+
+def conv2d_shared_budget_requant_blocked(q, x, x_shape, inv_step, budget_to, levels, stride=(1, 1), pad=(0, 0), seed=0,
+                                         layer_id=0, relu=True, lo=0, hi=127, res_f32=None, res_i8=None, res_step=0.0,
+                                         mult=None, bias=None, x_out=None, y=None, layout=0, want_x=True):
+    """conv2d_shared_requant_blocked with a per-pixel budget map [N, OH, OW] whose values are rounded down to
+    `levels` (at most four distinct values): all sample segments in one launch, epilogue fused."""
+    n, c, h, w = x_shape
+    g = ConvGeom(n, h, w, stride[0], stride[1], pad[0], pad[1])
+    oh, ow = conv2d_out_dims(q.wshape, (g.n, g.h, g.w, g.stride_h, g.stride_w, g.pad_h, g.pad_w))
+    oc = q.wshape[0]
+    if want_x and x_out is None:
+        shape = blocked_shape(n, oc, oh, ow) if layout & BLOCKED_OUT else (n, oc, oh, ow)
+        x_out = torch.empty(shape, dtype=torch.int8, device=x.device)
+    if not want_x and y is None:
+        y = torch.empty((n, oc, oh, ow), dtype=torch.float32, device=x.device)
+    if c != q.wshape[1]:
+        raise ValueError(f"x_shape: {c} channels, the handle has {q.wshape[1]}")
+    _expect(x, blocked_shape(n, c, h, w) if layout & BLOCKED_IN else (n, c, h, w), "x")
+    _expect_layer_io(q, (n, oc, oh, ow), y=y, mult=mult, bias=bias, budget_to=budget_to,
+                     x_out=x_out if want_x else None,
+                     x_out_shape=blocked_shape(n, oc, oh, ow) if layout & BLOCKED_OUT else None, res_f32=res_f32,
+                     res_i8=res_i8, res_i8_shape=blocked_shape(n, oc, oh, ow) if layout & BLOCKED_RES else None)
+    if budget_to is None:
+        raise ValueError("budget_to: a budget map is required")
+    lv, n_lv = _levels_array(levels)
+    rq = Requant(1 if relu else 0, inv_step, lo, hi,
+                 None if res_f32 is None else _ptr(res_f32, torch.float32, "res_f32").value,
+                 None if res_i8 is None else _ptr(res_i8, torch.int8, "res_i8").value, res_step)
+    rc = lib().psb_conv2d_shared_budget_requant_blocked(
+        q._h, _ptr(x, torch.int8, "x"), C.byref(g), _ptr(budget_to, torch.uint8, "budget_to"), lv, n_lv, seed, layer_id,
+        _ptr(y, torch.float32, "y"), _ptr(mult, torch.float32, "mult"), _ptr(bias, torch.float32, "bias"), C.byref(rq),
+        _ptr(x_out if want_x else None, torch.int8, "x_out"), layout, _stream())
+    _check(rc, "psb_conv2d_shared_budget_requant_blocked")
+    return x_out if want_x else y
+
+
+def shared_prepare_filters_levels(handles, levels, seeds, layer_ids):
+    """Sample the filters of every segment of the sample axis cut at `levels`, for several layers in one launch; the
+    next conv2d_shared_budget_requant_blocked call of each with the same levels uses them."""
+    n = len(handles)
+    hs = (C.c_void_p * n)(*[q._h for q in handles])
+    sd = (C.c_uint64 * n)(*[int(v) for v in seeds])
+    li = (C.c_uint32 * n)(*[int(v) for v in layer_ids])
+    lv, n_lv = _levels_array(levels)
+    _check(lib().psb_shared_prepare_filters_levels(hs, n, lv, n_lv, sd, li, _stream()), "psb_shared_prepare_filters_levels")
+
+
 def shared_prepare_filters(handles, S, seeds, layer_ids):
     """Sample the digit planes of several layers in one launch; the next matching shared-filter call of each uses them."""
     n = len(handles)
@@ -392,9 +448,9 @@ def shared_prepare_filters(handles, S, seeds, layer_ids):
 
 
 def shared_budget_levels(levels=None):
-    """Announce the budget values of the coming shared-filter calls with budget maps (an iterable of ints; every
-    value that occurs in the maps must be listed), so that they need not read them back; None or () restores the
-    default."""
+    """Announce the budget values of the NEXT shared-filter call with a budget map (an iterable of ints; every value
+    that occurs in its maps must be listed), so that it need not read them back; None or () withdraws an
+    announcement."""
     vals = sorted({int(v) for v in levels}) if levels is not None else []
     arr = (C.c_uint8 * max(1, len(vals)))(*vals)
     _check(lib().psb_shared_budget_levels(arr if vals else None, len(vals)), "psb_shared_budget_levels")

@@ -70,7 +70,7 @@ def test_attention_closed_forms(psb, orc):
 def test_two_pass_network(psb, orc, shared):
     """psb8/16: low-precision pass, mask, mixed-precision pass.  Up to the mask both sides agree bit for bit;
     where no pixel lies in the tie band the masks agree and so do the final logits.  (shared: the first pass runs
-    as one chain on the GPU, the second - with its budget map - layer by layer.)"""
+    as one chain on the GPU, and so does the second, with the two budget values given to every layer call.)"""
     from paper_1904_02205_amd import network
     net = rs.resnet18(batch=2, hw=96, width=32, classes=10)
     ref_logits, ref_budget, ent, mean = oracle_network.OracleResNet18(orc, net).forward_attention(8, 16, shared=shared)
@@ -80,3 +80,34 @@ def test_two_pass_network(psb, orc, shared):
     assert set(np.unique(ref_budget)) == {8, 16}
     if clear.all():
         assert np.array_equal(logits.cpu().numpy(), ref_logits)
+
+
+def test_masked_chain_as_a_hip_graph(psb, orc):
+    """The second pass of psb8/16 in shared-filter mode is a chain like the first (levels given with every call, all
+    segments in one launch): it can be captured, and replays give the eager pass's bits; a replay reads the map
+    tensor as it is then."""
+    import torch
+    from paper_1904_02205_amd import network
+    net = rs.resnet18(batch=2, hw=96, width=32, classes=10)
+    model = network.ResNet18(net)
+    rng = np.random.default_rng(3)
+    b1 = rng.choice([8, 16], size=(2, 3, 3), p=[0.6, 0.4]).astype(np.uint8)
+    b2 = rng.choice([8, 16], size=(2, 3, 3), p=[0.3, 0.7]).astype(np.uint8)
+    budget = torch.from_numpy(b1).cuda()
+    ref1 = oracle_network.OracleResNet18(orc, net).forward(budget=b1, s_fc=16, shared=True)
+    ref2 = oracle_network.OracleResNet18(orc, net).forward(budget=b2, s_fc=16, shared=True)
+    eager = model.forward(budget=budget, s_fc=16, shared=True, levels=(8, 16)).cpu().numpy()
+    assert np.array_equal(eager, ref1)
+    layerwise = model.forward(budget=budget, s_fc=16, shared=True, levels=(8, 16), chain=False).cpu().numpy()
+    assert np.array_equal(layerwise, ref1)
+    graph, logits = model.capture(shared=True, budget=budget, s_fc=16, levels=(8, 16))
+    for i in range(3):
+        logits.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(logits.cpu().numpy(), ref1), f"replay {i}"
+        model.forward(S=8, shared=True)                       # eager work between the replays
+    budget.copy_(torch.from_numpy(b2).cuda())
+    graph.replay()
+    torch.cuda.synchronize()
+    assert np.array_equal(logits.cpu().numpy(), ref2)

@@ -202,9 +202,9 @@ def test_activation_pointer_alignment(psb, orc):
 
 
 def test_announced_budget_levels(psb, orc):
-    """Budget values announced by the caller instead of read back from the map: same integers (exact set, a
-    superset, values above s_max), for the matrix-core and the direct kernel, with and without a budget_from map;
-    without the read-back the call can be captured into a HIP graph."""
+    """Budget values announced by the caller (for its next call) instead of read back from the map: same integers
+    (exact set, a superset, values above s_max), for the matrix-core and the direct kernel, with and without a
+    budget_from map; without the read-back the call can be captured into a HIP graph."""
     import torch
     rng = np.random.default_rng(984)
     for groups in (1, 4):
@@ -220,7 +220,9 @@ def test_announced_budget_levels(psb, orc):
                 acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, shared=True)
                 assert np.array_equal(acc, ref), (groups, levels)
             first = np.minimum(to, 8).astype(np.uint8)
+            psb.shared_budget_levels((4, 8))
             a1, _ = helpers.gpu_layer(psb, L, qg, budget_to=first, shared=True)
+            psb.shared_budget_levels((4, 8, 16))
             a2, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, budget_from=first, acc_in=a1, shared=True)
             assert np.array_equal(a2, ref)
             # captured: replays give the same integers
@@ -232,6 +234,7 @@ def test_announced_budget_levels(psb, orc):
             torch.cuda.synchronize()
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph):
+                psb.shared_budget_levels((4, 8, 16))          # an announcement is for the next call only
                 psb.conv2d_progressive(qg, x, bt, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id,
                                        acc=acc_t, shared=True)
             for _ in range(3):
