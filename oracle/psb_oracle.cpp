@@ -107,7 +107,7 @@ extern "C" int psbo_quantize(const float* w, int32_t oc, int32_t K, int32_t prob
                              int32_t x_absmax, int32_t s_max, psbo_weights* out)
 {
     if (!w || !out || oc <= 0 || K <= 0) return PSBO_ERR_ARG;
-    if (prob_bits != 23 && (prob_bits < 1 || prob_bits > 7)) return PSBO_ERR_VALUE;
+    if (prob_bits < 1 || prob_bits > 23) return PSBO_ERR_VALUE;
     if (exp_bits <= 0) exp_bits = 4;
     if (exp_bits > 5 || x_absmax <= 0 || x_absmax > 128 || s_max <= 0 || s_max > 255) return PSBO_ERR_VALUE;
 
@@ -214,7 +214,7 @@ static int64_t product_samples(int32_t x, int sigma, int32_t shift, double p, in
     int64_t sum = 0;
     for (int32_t s = from; s < to; ++s) {
         double U;                                   /* uniform on [0,1) */
-        if (prob_bits == 23) {
+        if (prob_bits >= 8) {      /* p exact, or on a grid of 8..22 bits: a k_p-bit comparator on the top k_p bits of u */
             const uint32_t u = u_row ? u_row[s] : psbo_uniform(seed, layer_id, o, k, (uint32_t)s);
             U = (double)u / 4294967296.0;
         } else {
@@ -355,7 +355,7 @@ static int32_t filter_count(const psbo_weights* q, int64_t wi, uint32_t oc, uint
     int32_t B = 0;
     for (int32_t s = from; s < to; ++s) {
         double U;
-        if (q->prob_bits == 23) {
+        if (q->prob_bits >= 8) {
             const uint32_t u = u_row ? u_row[s] : psbo_uniform(seed, layer_id, oc, k, (uint32_t)s);
             U = (double)u / 4294967296.0;
         } else {

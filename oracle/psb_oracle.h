@@ -45,8 +45,8 @@ typedef struct {
     int8_t*  sign;          /* -1, +1; 0 = not live (zero or flushed)            */
     int32_t* shift;         /* e - e_min >= 0 for live weights                   */
     double*  p;             /* probability of the larger shift, in [0,1)         */
-    int32_t  prob_bits;     /* 23: p is the full mantissa; 1..7: p is a multiple
-                               of 2^-prob_bits and samples use 7-bit uniforms     */
+    int32_t  prob_bits;     /* 23: p is the full mantissa; 1..22: p is a multiple
+                               of 2^-prob_bits; 1..7: samples use 7-bit uniforms  */
     psbo_winfo info;
 } psbo_weights;
 
@@ -78,9 +78,13 @@ uint32_t psbo_uniform(uint64_t seed, uint32_t layer_id, uint32_t o, uint32_t k, 
 uint32_t psbo_uniform7(uint64_t seed, uint32_t layer_id, uint32_t o, uint32_t k, uint32_t s);
 
 /* Encode a layer.  exp_bits<=0 selects 4 (Sect. 4.4: 4-bit exponents).
- * prob_bits = 23 keeps p exactly; prob_bits = 1..7 discretises it to a regular
+ * prob_bits = 23 keeps p exactly; prob_bits = 1..22 discretises it to a regular
  * grid that includes 0 and excludes 1 (Sect. 4.4): P = round-half-even(p * 2^prob_bits),
- * and P = 2^prob_bits moves the weight to the next exponent with p = 0.  The
+ * and P = 2^prob_bits moves the weight to the next exponent with p = 0.  A sample
+ * compares P with k_p random bits (suppl. "Stochastic multiplier": a k_p-bit
+ * comparator): for prob_bits = 1..7 the 7-bit uniform below (sixteen samples per
+ * generator block), for prob_bits = 8..22 the top prob_bits bits of the 32-bit
+ * uniform of the sample (four per block) - B = [u < P * 2^(32 - prob_bits)].  The
  * window and the overflow rule are described at the definition.  Allocates the
  * arrays of *out with malloc; release with psbo_weights_free.                   */
 int  psbo_quantize(const float* w, int32_t oc, int32_t K, int32_t prob_bits, int32_t exp_bits,

@@ -481,7 +481,7 @@ def test_probability_grid_includes_zero_excludes_one(orc):
     assert list(q.p[0][:3]) == [0.0, 0.5, 0.5] and q.p[0][3] == 0.0 and q.shift[0][3] + q.e_min == 1
     rng = np.random.default_rng(71)
     w = (rng.standard_normal((6, 200)) * 0.1).astype(np.float32)
-    for kp in (1, 2, 3, 4, 6, 7):
+    for kp in (1, 2, 3, 4, 6, 7, 8, 12, 22):
         q = orc.QWeights(w, x_absmax=1, s_max=1, prob_bits=kp)
         live = q.sign != 0
         grid = q.p[live] * 2 ** kp
@@ -491,7 +491,7 @@ def test_probability_grid_includes_zero_excludes_one(orc):
         assert np.all(np.abs(rep - w)[live] <= 2.0 ** e[live] * 2.0 ** -(kp + 1) + 1e-18)
     full = orc.QWeights(w, x_absmax=1, s_max=1, prob_bits=23)
     assert np.all(full.represented()[full.sign != 0] == w[full.sign != 0])
-    for bad in (0, 8, 16, 22, 24):
+    for bad in (0, -1, 24, 32):
         with pytest.raises(orc.OracleError) as ei:
             orc.QWeights(w, prob_bits=bad)
         assert ei.value.code == orc.ERR_VALUE
@@ -652,3 +652,37 @@ def test_oracle_under_address_and_undefined_behaviour_sanitizers():
         pytest.skip("no host compiler")
     from oracle import build_oracle
     assert build_oracle.sanitize() == 0
+
+
+def test_wider_probability_grids_compare_the_top_bits_of_the_32_bit_uniform(orc):
+    """prob_bits = 8..22 (Sect. 4.4; suppl. "Stochastic multiplier": a k_p-bit comparator): the rounded p is compared
+    with the top k_p bits of the sample's 32-bit uniform, B = [u < P 2^(32 - k_p)]: only those bits decide, the
+    threshold is strict, all 2^8 top bytes give the exact mean, and the stream is the 32-bit one (four samples per
+    generator block), not the 7-bit one."""
+    w = np.array([[1.25, -0.87890625]], dtype=np.float32)      # p = 64/256 ; 0.87890625 = (1/2)(1 + 194.5/256): tie -> 194
+    x = np.array([[5, -9]], dtype=np.int8)
+    q = orc.QWeights(w, x_absmax=16, s_max=1, prob_bits=8)
+    assert list(q.p[0] * 256) == [64.0, 194.0]
+    unit = 2.0 ** -q.e_min
+    total = 0
+    for a in range(256):
+        row = []
+        for b in range(256):
+            lo_bits = (a * 7919 + b * 104729) & 0xFFFFFF          # the low 24 bits must not matter
+            acc, _ = orc.linear(q, x, 1, u_table=np.array([(a << 24) | lo_bits, (b << 24) | (lo_bits ^ 0xABCDEF)], dtype=np.uint32))
+            row.append(int(acc[0, 0]))
+        total += sum(row)
+        if a in (63, 64):                                         # strict: P = 64 means top byte 0..63
+            first = 5 * unit * (2 if a < 64 else 1)
+            assert row[255] == first + (-9) * (-0.5) * unit       # b = 255: never below
+    assert total == 256 * 256 * (5 * 1.25 * unit + (-9) * -(0.5 * (1 + 194 / 256)) * unit)
+    # the generator stream is the 32-bit one
+    one = orc.QWeights(np.array([[1.5]], np.float32), x_absmax=1, s_max=16, prob_bits=8, exp_bits=1)
+    xs = np.array([[1]], np.int8)
+    for seed in range(5):
+        acc, _ = orc.linear(one, xs, 16, seed=seed, layer_id=2)
+        ones = sum(1 for s_ in range(16) if orc.uniform(seed, 2, 0, 0, s_) < (1 << 31))
+        assert int(acc[0, 0]) == (16 + ones) << int(one.shift[0, 0])
+    # exact p (23 bits) is the same rule with P = the mantissa
+    full = orc.QWeights(np.array([[1.5]], np.float32), x_absmax=1, s_max=16, prob_bits=23, exp_bits=1)
+    assert np.array_equal(orc.linear(full, xs, 16, seed=3, layer_id=2)[0], orc.linear(one, xs, 16, seed=3, layer_id=2)[0])
