@@ -91,7 +91,7 @@ def shared_ops(L, q):
 
 def lane_ops(n_calls, n_products, prob_bits=23):
     """Simple-int32-lane-operation units of n_calls generator calls and n_products products (per lane)."""
-    return n_calls * (CALL_UNITS if prob_bits == 23 else CALL_UNITS_7BIT) + n_products * PRODUCT_UNITS
+    return n_calls * (CALL_UNITS if prob_bits >= 8 else CALL_UNITS_7BIT) + n_products * PRODUCT_UNITS
 
 
 WORKLOADS = {
@@ -193,7 +193,7 @@ def prepare(workload, args, torch, psb, dev):
                                       pad=(sp.pad, sp.pad), S=8, s_max=8, seed=3, layer_id=i, linear=(sp.name == "fc")))
         P.model.inputs = {}
     P.layers = layers
-    P.per_call = 4 if args.prob_bits == 23 else 16
+    P.per_call = 4 if args.prob_bits >= 8 else 16
     P.calls, P.kernels, P.layer_smac = [], [], []
     P.smac = P.n_calls = P.n_prod = P.mfma_ops = P.mfma_plane_ops = P.smac_nz = P.smac_dense = 0.0
     for L in layers:
@@ -346,7 +346,8 @@ def main():
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--mapping", type=int, default=0)
     ap.add_argument("--prob-bits", type=int, default=23,
-                    help="23 = exact probabilities (the headline metric); 1..7 = discretised, 7-bit uniforms")
+                    help="23 = exact probabilities (the headline metric); 8..22 = discretised, 32-bit uniforms; 1..7 = discretised, "
+                         "7-bit uniforms")
     ap.add_argument("--mode", default="product", choices=["product", "shared"],
                     help="product = one random bit per (output, tap, sample), the headline; shared = one sampled "
                          "filter per pass (the paper's simulation granularity)")

@@ -57,7 +57,10 @@
  *    k = (ci*KH + kh)*KW + kw with ci counted inside the group.  The result is
  *    therefore a pure function of (inputs, seed, layer_id): independent of
  *    tiling, launch geometry and call order.
- *  - With discretised probabilities (prob_bits = 1..7, Sect. 4.4) p is a multiple of
+ *  - With probabilities discretised to prob_bits = 8..22 bits the same rule holds for the
+ *    rounded p: it compares the top prob_bits bits of u [suppl. "Stochastic multiplier": a
+ *    k_p-bit comparator].
+ *  - With discretised probabilities of prob_bits = 1..7 bits (Sect. 4.4) p is a multiple of
  *    2^-prob_bits and a 7-bit uniform decides the bit:
  *        B = [ u7 < p * 128 ],
  *    u7 = the low 7 bits of byte (i mod 16) of the Philox block with counter
@@ -107,7 +110,7 @@ typedef struct {
  * binary32 number these are its three bit fields].
  *
  * Discretised probabilities [Sect. 4.4: probabilities on a regular grid that contains
- * p = 0 but not p = 1, because p = 1 is the next exponent]: with prob_bits = 1..7, p is
+ * p = 0 but not p = 1, because p = 1 is the next exponent]: with prob_bits = 1..22, p is
  * rounded to the nearest multiple of 2^-prob_bits, ties to the even multiple; a p that
  * rounds to 1 becomes p = 0 with e + 1.  The rounding comes first: e_top, the window and
  * the overflow rule below see the rounded weights.  A weight that rounds past the largest
@@ -123,7 +126,8 @@ typedef struct {
  * samples.  Weights below e_min, subnormals and zeros are not live.
  *
  *  w_dev      device, float32 [oc][cin/groups][kh][kw], read only during the call
- *  prob_bits  23 (p exact: the full binary32 mantissa, 32-bit uniforms) or 1..7
+ *  prob_bits  23 (p exact: the full binary32 mantissa), 8..22 (rounded p, still one 32-bit uniform per
+ *             sample) or 1..7 (rounded p, sixteen 7-bit uniforms per generator block)
  *  exp_bits   1..5; <= 0 selects 4
  *  x_absmax   1..128, largest |activation| the caller will pass
  *  s_max      1..255, largest sample count / budget the caller will use

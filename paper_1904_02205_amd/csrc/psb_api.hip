@@ -757,7 +757,7 @@ int psb_quantize_weights(const float* w_dev, const psb_wshape* shape, int32_t pr
     int64_t K = 0;
     int rc = check_wshape(shape, &K);
     if (rc != PSB_OK) return rc;
-    if (prob_bits != 23 && (prob_bits < 1 || prob_bits > 7)) return PSB_ERR_VALUE;
+    if (prob_bits < 1 || prob_bits > 23) return PSB_ERR_VALUE;
     if (exp_bits <= 0) exp_bits = 4;
     if (exp_bits > 5 || x_absmax <= 0 || x_absmax > 128 || s_max <= 0 || s_max > 255) return PSB_ERR_VALUE;
 

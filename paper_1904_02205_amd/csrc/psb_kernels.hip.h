@@ -89,11 +89,13 @@ __global__ void __launch_bounds__(256) k_exponent_hist(const uint32_t* __restric
 // packed[oc][k] (row-major, the export format) and tile[k][oc_pad] (transposed, padded
 // with dead entries to a multiple of 64 channels, for the channel-lane kernel):
 // tile entry = { threshold,  unit = +-2^shift (0 when not live) }; the threshold is mantissa << 9 for
-// 32-bit uniforms and the 7-bit numerator of p in each of the four bytes for 7-bit uniforms.
+// 32-bit uniforms (prob_bits 8..23: the mantissa is exact or rounded to prob_bits bits, and the comparison with
+// the 32-bit uniform is a comparison of its top prob_bits bits) and the 7-bit numerator of p in each of the four
+// bytes for 7-bit uniforms (prob_bits 1..7).
 // counts[0..2] = zero, flushed, live.
 __device__ __forceinline__ uint32_t threshold_of(uint32_t mant, int prob_bits)
 {
-    return prob_bits < 23 ? (mant >> 16) * 0x01010101u : mant << 9;
+    return prob_bits <= 7 ? (mant >> 16) * 0x01010101u : mant << 9;
 }
 
 __global__ void __launch_bounds__(256) k_pack(const uint32_t* __restrict__ w_bits, int OC, int K, int oc_pad,
@@ -187,7 +189,7 @@ struct LayerParams {
     int stride_h, stride_w, pad_h, pad_w;
     // sampling
     int S, s_max;
-    int prob_bits;             // 23: 32-bit uniforms, 4 per generator block; 1..7: 7-bit uniforms, 16 per block
+    int prob_bits;             // 8..23: 32-bit uniforms, 4 per generator block; 1..7: 7-bit uniforms, 16 per block
     uint32_t key0, key1, layer_id;
     float default_mult;        // 2^e_min
     int max_shift;             // largest shift of a live weight
@@ -342,7 +344,7 @@ __global__ void __launch_bounds__(256) k_layer_pixel_lane(const LayerParams p)
                     const int32_t xv = xn[((int64_t)ci * p.H + iy) * p.W + ix];
                     if (xv == 0) continue;
                     const uint32_t thr = threshold_of(word & 0x7FFFFFu, p.prob_bits);
-                    const uint32_t cnt = p.prob_bits < 23
+                    const uint32_t cnt = p.prob_bits <= 7
                         ? count_below7(o, (uint32_t)k, p.layer_id, p.key0, p.key1, thr, from, to)
                         : count_below(o, (uint32_t)k, p.layer_id, p.key0, p.key1, thr, from, to);
                     const int32_t shifted = (int32_t)((uint32_t)xv << ((word >> 23) & 0xFFu));

@@ -321,7 +321,7 @@ inline int launch_product_list(const LayerParams& p, const uint32_t* live_idx, c
     if (gx > 2147483647ll || gy > 65535) return (int)hipErrorInvalidValue;
     const dim3 grid((unsigned)gx, (unsigned)gy), block(kListPixels);
     // compile-time block count only for a uniform S that is a whole number of generator blocks
-    const bool p7 = p.prob_bits < 23;
+    const bool p7 = p.prob_bits <= 7;
     const int per_block = p7 ? 16 : 4;
     int nb = 0;
     if (!p.budget_to && p.S % per_block == 0) nb = p.S / per_block;

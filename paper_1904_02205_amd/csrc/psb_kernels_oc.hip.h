@@ -530,7 +530,7 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
     // resident workgroups: 160 KB of LDS hold four tiles; 512 VGPRs per lane hold four waves per SIMD
     const int wg_per_cu = 4;
     // one S everywhere, a whole number of generator blocks for which a specialised kernel is built (0: none)
-    const bool p7 = p.prob_bits < 23;
+    const bool p7 = p.prob_bits <= 7;
     const int per_block = p7 ? 16 : 4;
     int fixed_nb = 0;
     if (!p.budget_to && !p.budget_from && p.S % per_block == 0) {

@@ -98,7 +98,7 @@ __device__ __forceinline__ int32_t sample_word(const FilterJob& j, uint32_t word
 {
     if ((word & 0x7F800000u) == kDeadWord) return 0;
     const uint32_t thr = threshold_of(word & 0x7FFFFFu, j.prob_bits);
-    const uint32_t cnt = j.prob_bits < 23
+    const uint32_t cnt = j.prob_bits <= 7
         ? count_below7((uint32_t)oc, (uint32_t)k, j.layer_id, j.key0, j.key1, thr, j.from, j.to)
         : count_below((uint32_t)oc, (uint32_t)k, j.layer_id, j.key0, j.key1, thr, j.from, j.to);
     const uint32_t mag = ((uint32_t)(j.to - j.from) + cnt) << ((word >> 23) & 0xFFu);   // < 2^31 by the overflow rule
@@ -689,8 +689,11 @@ __device__ __forceinline__ void tile_epilogue(const SharedParams& p, v16i (&acc)
 // rescaling is a separate pass then), store accumulators (and rescaled values), or store requantised activations
 // (and, if asked for, the other two).  A template parameter, so that the unrolled epilogue is straight-line code.
 
+// Two waves per SIMD must stay resident (512 registers per lane and SIMD, accumulators included): left alone the
+// compiler takes 162 + 96 for the requantising two-half-tile variant, and a layer with more than 256 workgroups
+// then needs a second round.  (Four planes and two half tiles, 128 accumulators, do not fit twice without spills.)
 template <int P, int OUT, int HT>
-__global__ void __launch_bounds__(256) k_conv_shared_mfma(const SharedParams p)
+__global__ void __launch_bounds__(256, (P == 4 && HT == 2) ? 1 : 2) k_conv_shared_mfma(const SharedParams p)
 {
     __shared__ v4i a_lds[kStageSteps * P * 64];
     __shared__ float s_mult[32], s_bias[32];       // rescale factors of this block of channels (read after the loop)

@@ -61,7 +61,7 @@ def test_null_arguments_are_rejected_before_any_device_work(psb):
     assert L.psb_quantize_weights(C.c_void_p(16), None, 23, 0, 127, 8, None, C.byref(h)) == psb.ERR_NULL
     assert L.psb_quantize_weights(C.c_void_p(16), C.byref(ws), 23, 0, 127, 8, None, None) == psb.ERR_NULL
     # value errors are found before the pointer is ever dereferenced
-    for prob_bits, exp_bits, xmax, smax in ((8, 0, 127, 8), (0, 0, 127, 8), (22, 0, 127, 8), (-3, 0, 127, 8),
+    for prob_bits, exp_bits, xmax, smax in ((24, 0, 127, 8), (0, 0, 127, 8), (32, 0, 127, 8), (-3, 0, 127, 8),
                                             (23, 6, 127, 8), (23, 0, 0, 8), (23, 0, 129, 8),
                                             (23, 0, 127, 0), (23, 0, 127, 256)):
         assert L.psb_quantize_weights(C.c_void_p(16), C.byref(ws), prob_bits, exp_bits, xmax, smax, None,

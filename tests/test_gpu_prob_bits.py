@@ -39,7 +39,7 @@ def _rounding_cases(kp):
     return _f32(bits)
 
 
-@pytest.mark.parametrize("kp", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("kp", [1, 2, 3, 4, 5, 6, 7, 8, 10, 16, 22])
 def test_quantize_rounding_matches_oracle(psb, orc, kp):
     import torch
     rng = np.random.default_rng(500 + kp)
@@ -75,7 +75,7 @@ def test_carry_moves_the_window_top(psb, orc):
 def test_prob_bits_error_codes(psb, orc):
     import torch
     w = torch.ones((2, 8), device="cuda")
-    for bad in (0, -1, 8, 16, 22, 24, 32):
+    for bad in (0, -1, 24, 32):
         with pytest.raises(psb.PsbError) as ei:
             psb.Weights(w, prob_bits=bad)
         assert ei.value.code == psb.ERR_VALUE
@@ -107,6 +107,12 @@ def _cases():
     c.append(("pruned_pointwise_k4", _layer(rng, 2, 96, 40, 5, 1, S=16, prune=0.9), 4, all3))
     c.append(("depthwise_k4", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), 4, (1, 3)))
     c.append(("depthwise_s24_k6", _layer(rng, 1, 10, 10, 8, 3, stride=2, pad=1, groups=10, S=24), 6, (1, 3)))
+    # 8 bits and more: the rounded p against the top bits of the 32-bit uniform (four samples per generator block)
+    c.append(("conv_s16_k8", _layer(rng, 2, 20, 70, (9, 11), 3, pad=1, S=16), 8, all3))
+    c.append(("linear_s5_k8", _layer(rng, 3, 130, 100, 1, 1, S=5, xkind="signed", std=0.05), 8, all3))
+    c.append(("conv_s12_k12", _layer(rng, 1, 9, 10, 6, 3, pad=1, S=12), 12, all3))
+    c.append(("depthwise_k8", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), 8, (1, 3)))
+    c.append(("pruned_pointwise_k22", _layer(rng, 2, 96, 40, 5, 1, S=16, prune=0.9), 22, all3))
     return c
 
 
@@ -122,10 +128,14 @@ def test_layer_bit_exact(psb, orc, case):
         acc, _ = helpers.gpu_layer(psb, L, qg)
         assert np.array_equal(acc, ref), f"mapping {m}"
     psb.set_mapping(psb.MAPPING_AUTO)
-    # the 7-bit stream is a different stream from the 32-bit one
+    # the 7-bit stream is a different stream from the 32-bit one (and wider grids still round the weights)
     full, _ = helpers.gpu_layer(psb, L, helpers.gpu_quantize(psb, L))
-    if L.S > 1:
+    if L.S > 1 and kp <= 8:
         assert not np.array_equal(full, ref)
+    # shared-filter mode samples its filter with the same rule
+    ref_s, over_s, _ = helpers.oracle_layer(orc, L, qo, shared=True)
+    acc_s, _ = helpers.gpu_layer(psb, L, qg, shared=True)
+    assert over_s == 0 and np.array_equal(acc_s, ref_s)
 
 
 @pytest.mark.parametrize("mapping", [1, 2, 3])
