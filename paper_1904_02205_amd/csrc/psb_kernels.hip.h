@@ -250,6 +250,17 @@ __device__ __forceinline__ uint32_t count_below7(uint32_t o, uint32_t k, uint32_
     return (uint32_t)(to - from) - not_below;
 }
 
+// Workgroups are dealt to the 8 XCDs of the chip round-robin by their linear index, and every XCD has its own L2.
+// For a grid whose x size is a multiple of 8, this maps workgroup index b (XCD b mod 8, the (b div 8)-th workgroup
+// of that XCD) to one of n work items so that every XCD gets a contiguous range, the ranges differing in length
+// by at most one; 0xFFFFFFFF for the surplus workgroups of an XCD with a shorter range.
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned n)
+{
+    const unsigned xcd = b & 7u, local = b >> 3;
+    const unsigned begin = (unsigned)(((uint64_t)xcd * n) >> 3), end = (unsigned)(((uint64_t)(xcd + 1u) * n) >> 3);
+    return begin + local < end ? begin + local : 0xFFFFFFFFu;
+}
+
 // Final rescale: four separately rounded binary32 operations.
 __device__ __forceinline__ float rescale(int32_t acc, float mult, int to, const float* bias, int oc)
 {

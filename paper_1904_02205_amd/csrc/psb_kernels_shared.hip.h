@@ -704,10 +704,11 @@ __global__ void __launch_bounds__(256, (P == 4 && HT == 2) ? 1 : 2) k_conv_share
     const int col = lane & 31, g = lane >> 5;
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
     // Workgroups are dealt to the 8 XCDs round-robin by their index; each XCD has its own L2.  Renumber them so
-    // that every XCD works on one contiguous eighth of the pixels and its L2 only has to hold that part of the input.
-    // (The launcher rounds the grid up to a multiple of 8; workgroups past the last tile have no live pixel.)
-    const unsigned per_xcd = gridDim.x >> 3;
-    const unsigned wg = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    // that every XCD works on one contiguous eighth of the pixel tiles (lengths differing by at most one tile) and
+    // its L2 only has to hold that part of the input.  (The launcher rounds the grid up to a multiple of 8.)
+    const unsigned n_tiles = (unsigned)((npix + 128 * HT - 1) / (128 * HT));
+    const unsigned wg = xcd_contiguous(blockIdx.x, n_tiles);
+    if (wg == 0xFFFFFFFFu) return;                 // uniform over the workgroup, before any barrier
     const int64_t pix0 = ((int64_t)wg * 4 + wave) * (32 * HT);
     const int ocb = blockIdx.y;
 
@@ -871,9 +872,10 @@ __global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const Shar
     const uint32_t cb_stride = (uint32_t)p.tW * 32u;
     const uint32_t row_stride = (uint32_t)CB * cb_stride;
     const __amdgpu_buffer_rsrc_t xt_rsrc = operand_buffer(p.xt, p.xt_bytes);
-    const unsigned per_xcd = columns >> 3;         // each XCD keeps one contiguous eighth of the pixels
+    const unsigned n_tiles = (unsigned)((npix + 255) / 256);
     for (unsigned v = blockIdx.x; v < columns; v += gridDim.x) {
-        const unsigned wg = (v & 7u) * per_xcd + (v >> 3);
+        const unsigned wg = xcd_contiguous(v, n_tiles);     // each XCD keeps one contiguous eighth of the pixel tiles
+        if (wg == 0xFFFFFFFFu) continue;
         const int64_t pix0 = ((int64_t)wg * 4 + wave) * 64;
         bool live[2];
         int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
