@@ -732,10 +732,15 @@ __global__ void __launch_bounds__(256, (P == 4 && HT == 2) ? 1 : 2) k_conv_share
         const int i = r * 256 + (int)threadIdx.x;
         woff[r] = (uint32_t)((((i / (P * 64)) * kMaxPlanes + (i >> 6) % P) * 64 + (i & 63)) * 16);
     }
+    // Buffer loads: the address of an operand is the (uniform) block of this channel block and segment, a scalar
+    // offset for the chunk and the thread's fixed offset - no per-load address arithmetic in vector registers, which
+    // the compiler would otherwise do in registers it also uses for operands, making every first LDS read of a chunk
+    // wait for the weight loads that were just issued.
+    __amdgpu_buffer_rsrc_t w_rsrc = operand_buffer(wblock, (uint32_t)(p.n_ksteps + kStageSteps) * (kMaxPlanes * kPlaneStride));
     auto fetch_weights = [&](int s0) {
-        const int8_t* chunk = wblock + (int64_t)s0 * (kMaxPlanes * kPlaneStride);      // uniform
+        const uint32_t chunk = (uint32_t)s0 * (uint32_t)(kMaxPlanes * kPlaneStride);   // uniform
 #pragma unroll
-        for (int r = 0; r < kStageRegs; ++r) stage[r] = *reinterpret_cast<const v4i*>(chunk + woff[r]);
+        for (int r = 0; r < kStageRegs; ++r) stage[r] = load_operand(w_rsrc, woff[r], chunk);
     };
 
     fetch_weights(s_begin);          // first of all: nothing below depends on it until the first barrier
@@ -782,6 +787,7 @@ __global__ void __launch_bounds__(256, (P == 4 && HT == 2) ? 1 : 2) k_conv_share
                 __syncthreads();
                 if ((s_takes_part[0] | s_takes_part[1] | s_takes_part[2] | s_takes_part[3]) == 0) break;
                 wblock = wblock0 + (int64_t)seg * p.seg_stride;
+                w_rsrc = operand_buffer(wblock, (uint32_t)(p.n_ksteps + kStageSteps) * (kMaxPlanes * kPlaneStride));
                 fetch_weights(s_begin);
             }
         }
@@ -807,7 +813,10 @@ __global__ void __launch_bounds__(256, (P == 4 && HT == 2) ? 1 : 2) k_conv_share
 #pragma unroll
             for (int r = 0; r < kStageRegs; ++r) a_lds[r * 256 + threadIdx.x] = stage[r];
             __syncthreads();
-            if (s0 + kStageSteps < s_end) fetch_weights(s0 + kStageSteps);       // uniform over the workgroup
+            // unconditional, like the activation requests (past the last chunk it reads the padding chunk of the
+            // buffer, or the next block's first chunk): a branch around it makes the compiler's wait counts assume
+            // the path without loads, and the first LDS reads of every chunk then wait for loads just issued
+            fetch_weights(s0 + kStageSteps);
             if (active_seg) {
                 // the weight operands of step ks + 1 are read from LDS while the matrix instructions of step ks run
                 v4i a[2][P];
