@@ -436,6 +436,10 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
         const int64_t waves = ((int64_t)g->n * OH * OW + 32 * half_tiles - 1) / (32 * half_tiles) * n_ocb;
         const int64_t want = waves <= 512 ? (1024 + waves - 1) / waves : 1;
         ksplit = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, 8), n_ksteps / 16));
+        // the 3 x 3 kernel with both operands in LDS deals the channel blocks to teams inside a workgroup instead
+        if (!rowpack && psb::window_slots(q->shape.kh, q->shape.kw, g->stride_h, g->stride_w, g->pad_h, g->pad_w, g->h, g->w,
+                                          half_tiles) > 0)
+            ksplit = 1;
     }
     // all segments in one launch, accumulated in registers, epilogue fused
     const bool fused_segments = round_down && mfma && n_seg > 0 && !budget_from && ksplit == 1 &&

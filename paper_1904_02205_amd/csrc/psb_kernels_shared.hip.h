@@ -30,6 +30,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 
 #include "psb_kernels.hip.h"
@@ -934,6 +935,205 @@ __global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const Shar
     }
 }
 
+// 3 x 3 layers with unit stride and one pixel of padding on the blocked layout: BOTH operands come from LDS.
+// The plain kernel fetches each activation operand straight from global memory, once per tap: two 16-byte loads per
+// lane and reduction step, which the path from L2 through L1 into the registers of eight waves cannot deliver as fast
+// as the matrix cores consume them.  Here the reduction runs channel block by channel block; for the current block of
+// 32 input channels a team of four waves keeps, next to the nine taps' weight operands, the WINDOW of the input
+// that its pixel tile touches: all positions from the first pixel's tap (0, 0) to the last pixel's tap (2, 2), in a
+// "virtual" row-major order in which every image row is preceded by one zero position (its left padding, and the
+// right padding of the row before) and every image by one zero row.  In that order tap (kh, kw) of output pixel
+// (n, oy, ox) is at  ((n (H + 1) + oy + kh) (W + 1) + ox + kw)  - the pixel's own position plus a uniform offset - so
+// an activation operand is one 16-byte LDS read at  (lane's slot + kh (W + 1) + kw)  and the nine taps of a pixel
+// re-use what was fetched once.  The two 16-channel halves of a position live in two half planes, so that the lanes
+// of a half tile read consecutive 16-byte words.
+//
+// TEAMS > 1: few pixel tiles and a long reduction - the channel blocks are dealt to TEAMS teams of four waves that
+// work on the SAME pixels with their own LDS regions; their sums meet in LDS at the end and team 0 runs the
+// epilogue.  This gives every SIMD two waves to interleave where the tile count alone would give it one.
+//
+// Unsplit, unsegmented calls (p.ksplit = 1, p.n_seg = 0); pixels that do not take part are computed and not stored.
+// WS: window slots / 256.  Dynamic LDS: TEAMS * (kAregs + 2 WS) * 4096 bytes.
+template <int P, int OUT, int HT, int TEAMS, int WS>
+__global__ void __launch_bounds__(256 * TEAMS, 2) k_conv3x3_window(const SharedParams p)
+{
+    extern __shared__ v4i win_lds[];
+    __shared__ float s_mult[32], s_bias[32];
+    constexpr int kTaps = 9;
+    constexpr int kAregs = (kTaps * P * 64 + 255) / 256;        // 16-byte weight words per thread and channel block
+    constexpr int kTeamWords = (kAregs + 2 * WS) * 256;         // v4i per team
+
+    const int team = (int)threadIdx.x >> 8, tid = (int)threadIdx.x & 255;
+    const int lane = threadIdx.x & 63, wave = ((int)threadIdx.x >> 6) & 3;
+    const int col = lane & 31, g = lane >> 5;
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    constexpr int kTile = 128 * HT;                             // pixels of a workgroup
+    const unsigned n_tiles = (unsigned)((npix + kTile - 1) / kTile);
+    const unsigned wg = xcd_contiguous(blockIdx.x, n_tiles);
+    if (wg == 0xFFFFFFFFu) return;                 // uniform over the workgroup, before any barrier
+    const int64_t pix_first = (int64_t)wg * kTile;
+    const int64_t pix0 = pix_first + wave * (32 * HT);
+    const int ocb = blockIdx.y;
+    const int CB = p.C_pad >> 5;
+    const int cb_per_team = CB / TEAMS;            // the host checks that it divides
+    const int cb_begin = team * cb_per_team;
+    v4i* const a_lds = win_lds + team * kTeamWords;             // [tap][plane][lane]
+    v4i* const b_lds = a_lds + kAregs * 256;                    // [half][slot]
+
+    // weights: word i = (tap * P + plane) * 64 + lane of a channel block's chunk is fetched by thread i mod 256
+    const int8_t* const wblock = p.planes + (int64_t)ocb * p.n_ksteps * (kMaxPlanes * kPlaneStride);
+    const __amdgpu_buffer_rsrc_t w_rsrc = operand_buffer(wblock, (uint32_t)(p.n_ksteps + kStageSteps) * (kMaxPlanes * kPlaneStride));
+    v4i stage_a[kAregs];
+    uint32_t woff[kAregs];
+#pragma unroll
+    for (int r = 0; r < kAregs; ++r) {
+        const int i = r * 256 + tid;
+        const int t = i / (P * 64), b = (i >> 6) % P;
+        // reduction step of (tap t, channel block cb) = t * CB + cb; words past the ninth tap read as zeros
+        woff[r] = t < kTaps ? (uint32_t)((((t * CB) * kMaxPlanes + b) * 64 + (i & 63)) * 16) : kOutOfRange;
+    }
+    auto fetch_weights = [&](int cb) {
+        const uint32_t chunk = (uint32_t)cb * (uint32_t)(kMaxPlanes * kPlaneStride);      // uniform
+#pragma unroll
+        for (int r = 0; r < kAregs; ++r) stage_a[r] = load_operand(w_rsrc, woff[r], chunk);
+    };
+    fetch_weights(cb_begin);         // first of all: nothing below depends on it until the first barrier
+
+    // the window: slot s holds virtual position q_first + s
+    const int W1 = p.tW + 1, H1 = p.tH + 1;
+    auto virtual_position = [&](uint32_t pix) {
+        const uint32_t row = pix / (uint32_t)p.OW, ox = pix - row * (uint32_t)p.OW;
+        const uint32_t n = row / (uint32_t)p.OH, oy = row - n * (uint32_t)p.OH;
+        return (n * (uint32_t)H1 + oy) * (uint32_t)W1 + ox;
+    };
+    const uint32_t pix_last = (uint32_t)(min(pix_first + kTile, npix) - 1);
+    const uint32_t q_first = virtual_position((uint32_t)pix_first);
+    const uint32_t n_slots = virtual_position(pix_last) - q_first + 2u * (uint32_t)W1 + 3u;   // at most 256 WS (host)
+    const uint32_t cb_stride = (uint32_t)p.tW * 32u;            // bytes between the channel blocks of one pixel
+    const __amdgpu_buffer_rsrc_t xt_rsrc = operand_buffer(p.xt, p.xt_bytes);
+    v4i stage_b[WS][2];
+    uint32_t goff[WS];               // slot e * 256 + tid: offset of its position in channel block 0, or out of range
+#pragma unroll
+    for (int e = 0; e < WS; ++e) {
+        const uint32_t s = (uint32_t)(e * 256 + tid);
+        const uint32_t q = q_first + s;
+        const uint32_t vr = q / (uint32_t)W1, vc = q - vr * (uint32_t)W1;
+        const uint32_t n = vr / (uint32_t)H1, rr = vr - n * (uint32_t)H1;
+        const bool ok = s < n_slots && vc >= 1u && rr >= 1u && n < (uint32_t)p.N;
+        goff[e] = ok ? (((n * (uint32_t)p.tH + (rr - 1u)) * (uint32_t)CB) * (uint32_t)p.tW + (vc - 1u)) * 32u : kOutOfRange;
+    }
+    auto fetch_window = [&](int cb) {
+        const uint32_t block = (uint32_t)cb * cb_stride;                                    // uniform
+#pragma unroll
+        for (int e = 0; e < WS; ++e) {
+            stage_b[e][0] = load_operand(xt_rsrc, goff[e], block);
+            stage_b[e][1] = load_operand(xt_rsrc, goff[e] + 16u, block);     // out of range stays out of range
+        }
+    };
+    fetch_window(cb_begin);
+
+    bool live[2];
+    int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
+    uint32_t origin[2];
+    decode_half_tiles<HT>(p, pix0, col, g, CB, npix, live, n_, oy_, ox_, to_, iy0, ix0, origin);
+    const bool active = __ballot(live[0] || live[1]) != 0ull;
+    // this lane's operand of tap (kh, kw) and half tile h: b_lds[row_slot[h][kh] + kw]
+    int row_slot[HT][3];
+#pragma unroll
+    for (int h = 0; h < HT; ++h) {
+        const int slot = (int)(((uint32_t)(n_[h] * H1 + oy_[h])) * (uint32_t)W1 + (uint32_t)ox_[h] - q_first);
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) row_slot[h][kh] = g * (WS * 256) + slot + kh * W1;
+    }
+
+    v16i acc[HT][P];
+#pragma unroll
+    for (int h = 0; h < HT; ++h)
+#pragma unroll
+        for (int b = 0; b < P; ++b)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
+
+    if (OUT != kOutPartial && threadIdx.x < 32) {    // visible to every wave after the loop's first barrier
+        const int oc = ocb * 32 + (int)threadIdx.x;
+        s_mult[threadIdx.x] = (p.mult && oc < p.OC) ? p.mult[oc] : p.default_mult;
+        s_bias[threadIdx.x] = (p.bias && oc < p.OC) ? p.bias[oc] : 0.0f;
+    }
+
+    for (int c = 0; c < cb_per_team; ++c) {
+        __syncthreads();                             // the previous channel block has been consumed by every wave
+#pragma unroll
+        for (int r = 0; r < kAregs; ++r) a_lds[r * 256 + tid] = stage_a[r];
+#pragma unroll
+        for (int e = 0; e < WS; ++e) {
+            b_lds[e * 256 + tid] = stage_b[e][0];
+            b_lds[WS * 256 + e * 256 + tid] = stage_b[e][1];
+        }
+        __syncthreads();
+        // the next block's operands travel while this one is multiplied (after the last block: the same again, so
+        // that the loads in flight are the same on every path)
+        const int nxt = cb_begin + min(c + 1, cb_per_team - 1);
+        fetch_weights(nxt);
+        fetch_window(nxt);
+
+        v4i a[2][P], b[2][HT];
+#pragma unroll
+        for (int pl = 0; pl < P; ++pl) a[0][pl] = a_lds[pl * 64 + lane];
+#pragma unroll
+        for (int h = 0; h < HT; ++h) b[0][h] = b_lds[row_slot[h][0]];
+#pragma unroll
+        for (int t = 0; t < kTaps; ++t) {
+            if (t + 1 < kTaps) {
+                const int kh = (t + 1) / 3, kw = (t + 1) % 3;
+#pragma unroll
+                for (int pl = 0; pl < P; ++pl) a[(t + 1) & 1][pl] = a_lds[((t + 1) * P + pl) * 64 + lane];
+#pragma unroll
+                for (int h = 0; h < HT; ++h) b[(t + 1) & 1][h] = b_lds[row_slot[h][kh] + kw];
+            }
+#pragma unroll
+            for (int pl = 0; pl < P; ++pl)
+#pragma unroll
+                for (int h = 0; h < HT; ++h)
+                    acc[h][pl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t & 1][pl], b[t & 1][h], acc[h][pl], 0, 0, 0);
+        }
+    }
+
+    if constexpr (TEAMS > 1) {
+        // the teams' sums meet in LDS: team k > 0 leaves its registers at [k - 1][wave][register quad][lane]
+        constexpr int kQuads = HT * P * 4;
+        __syncthreads();                             // every operand has been read
+        if (team > 0) {
+            v4i* const dst = win_lds + (((team - 1) * 4 + wave) * kQuads) * 64 + lane;
+#pragma unroll
+            for (int h = 0; h < HT; ++h)
+#pragma unroll
+                for (int pl = 0; pl < P; ++pl)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4)
+                        dst[((h * P + pl) * 4 + q4) * 64] = v4i{acc[h][pl][4 * q4], acc[h][pl][4 * q4 + 1], acc[h][pl][4 * q4 + 2], acc[h][pl][4 * q4 + 3]};
+        }
+        __syncthreads();
+        if (team > 0) return;
+#pragma unroll
+        for (int k = 1; k < TEAMS; ++k) {
+            const v4i* const src = win_lds + (((k - 1) * 4 + wave) * kQuads) * 64 + lane;
+#pragma unroll
+            for (int h = 0; h < HT; ++h)
+#pragma unroll
+                for (int pl = 0; pl < P; ++pl)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const v4i v = src[((h * P + pl) * 4 + q4) * 64];
+                        acc[h][pl][4 * q4] += v.x; acc[h][pl][4 * q4 + 1] += v.y;
+                        acc[h][pl][4 * q4 + 2] += v.z; acc[h][pl][4 * q4 + 3] += v.w;
+                    }
+        }
+    }
+    if (!active) return;
+
+    tile_epilogue<P, OUT, HT>(p, acc, live, n_, oy_, ox_, to_, ocb, lane, s_mult, s_bias);
+}
+
 // Any layer shape: one output pixel per lane, one output channel per workgroup row.  (Grouping the taps' loads
 // here, with (channel, kh, kw) stepped at run time, measured slower than this plain loop: the stepping is more
 // scalar work per tap than the loop counters; 3 x 3 depthwise layers have the unrolled kernel below instead.)
@@ -1078,6 +1278,68 @@ inline void launch_conv_shared_mfma_resident(const SharedParams& p, int planes, 
     }
 }
 
+// Whether k_conv3x3_window can take the call, and in which shape.  slots = the longest window of a pixel tile:
+// T - 1 positions between its first and last pixel, one more per image row and W + 1 more per image that the tile
+// crosses, and the taps' reach of 2 (W + 1) + 2 beyond the last pixel.
+struct WindowPlan { bool ok; int teams, ws; };
+// slots of the longest window of a layer with this geometry, or 0 when the kernel does not take the geometry
+// (the reduction of such a layer is never split over workgroups: the teams do that inside one)
+inline int window_slots(int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w, int H, int W, int half_tiles)
+{
+    static const bool enabled = [] { const char* v = std::getenv("PSB_SHARED_WINDOW"); return !(v && std::atoi(v) == 0); }();   // benchmark switch
+    if (!enabled || kh != 3 || kw != 3 || stride_h != 1 || stride_w != 1 || pad_h != 1 || pad_w != 1) return 0;
+    const int64_t T = 128 * half_tiles;
+    const int64_t rows = (T + W - 2) / W, images = (T + (int64_t)H * W - 2) / ((int64_t)H * W);
+    const int64_t slots = T - 1 + rows + images * (W + 1) + 2 * (W + 1) + 3;
+    return slots <= 512 ? (int)slots : 0;
+}
+inline WindowPlan window_plan(const SharedParams& p, int planes, int half_tiles, int n_cus)
+{
+    WindowPlan w{false, 1, 1};
+    if (p.OH != p.tH || p.OW != p.tW || p.n_seg != 0 || p.ksplit != 1 || planes < 3) return w;
+    const int64_t T = 128 * half_tiles;
+    const int slots = window_slots(p.tKH, p.tKW, p.t_stride_h, p.t_stride_w, p.t_pad_h, p.t_pad_w, p.tH, p.tW, half_tiles);
+    if (slots == 0) return w;
+    w.ws = slots <= 256 ? 1 : 2;
+    if (half_tiles == 2 && w.ws != 2) return w;      // (cannot happen: 256 pixels need more than 256 slots)
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int64_t wgs = (npix + T - 1) / T * ((p.OC + 31) / 32);
+    const int CB = p.C_pad >> 5;
+    // two teams when the layer has at most one workgroup per CU: then every SIMD still gets two waves
+    w.teams = (half_tiles == 1 && CB % 2 == 0 && CB >= 4 && wgs <= n_cus) ? 2 : 1;
+    w.ok = true;
+    return w;
+}
+
+template <int P, int OUT, int HT, int TEAMS, int WS>
+inline bool launch_window_one(const SharedParams& p, dim3 grid, hipStream_t stream)
+{
+    constexpr int kAregs = (9 * P * 64 + 255) / 256;
+    constexpr size_t lds = (size_t)TEAMS * (kAregs + 2 * WS) * 4096;
+    static_assert(TEAMS == 1 || (size_t)(TEAMS - 1) * 4 * HT * P * 4 * 64 * 16 <= lds, "the teams' sums must fit the operand area");
+    auto kernel = k_conv3x3_window<P, OUT, HT, TEAMS, WS>;
+    // more than 64 KB of dynamic LDS has to be asked for once
+    static const bool usable = lds <= 65536 || hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
+    if (!usable) return false;
+    hipLaunchKernelGGL(kernel, grid, dim3(256 * TEAMS), lds, stream, p);
+    return true;
+}
+
+template <int P, int OUT>
+inline bool launch_window_shape(const SharedParams& p, int half_tiles, const WindowPlan& w, dim3 grid, hipStream_t stream)
+{
+    if (half_tiles == 2) return launch_window_one<P, OUT, 2, 1, 2>(p, grid, stream);
+    if (w.teams == 2) return w.ws == 1 ? launch_window_one<P, OUT, 1, 2, 1>(p, grid, stream) : launch_window_one<P, OUT, 1, 2, 2>(p, grid, stream);
+    return w.ws == 1 ? launch_window_one<P, OUT, 1, 1, 1>(p, grid, stream) : launch_window_one<P, OUT, 1, 1, 2>(p, grid, stream);
+}
+
+template <int OUT>
+inline bool launch_window_out(const SharedParams& p, int planes, int half_tiles, const WindowPlan& w, dim3 grid, hipStream_t stream)
+{
+    return planes == 3 ? launch_window_shape<3, OUT>(p, half_tiles, w, grid, stream) : launch_window_shape<4, OUT>(p, half_tiles, w, grid, stream);
+}
+
 // Half tiles (32 pixels) per wave: two, unless the layer is so small that one-half-tile waves still fit the chip at
 // once (then twice the waves share the work, and a long reduction need not be split).
 inline int shared_half_tiles(int64_t npix, int n_ocb) { return (npix + 63) / 64 * n_ocb <= 1024 ? 1 : 2; }
@@ -1093,6 +1355,14 @@ inline void launch_conv_shared_mfma(const SharedParams& p, int planes, int resid
     const unsigned n_ocb = (unsigned)((p.OC + 31) / 32);
     const int n_steps = p.tKH * p.tKW * (p.C_pad >> 5);
     const size_t lds = (size_t)n_steps * planes * kPlaneStride;
+    const WindowPlan win = window_plan(p, planes, half_tiles, std::max(resident_wgs, 512) / 2);
+    if (win.ok) {
+        const dim3 grid(columns, n_ocb);
+        const bool done = p.masked ? launch_window_out<kOutPartial>(p, planes, half_tiles, win, grid, stream)
+                        : p.rq.x_out ? launch_window_out<kOutRequant>(p, planes, half_tiles, win, grid, stream)
+                                     : launch_window_out<kOutAcc>(p, planes, half_tiles, win, grid, stream);
+        if (done) return;
+    }
     // worth it when a workgroup gets more than one tile: staging the whole block before the first matrix instruction
     // costs more than the chunked start of the plain kernel
     const unsigned fit = std::max(8u, (unsigned)std::max(resident_wgs, 0) / n_ocb / 8u * 8u);

@@ -41,6 +41,8 @@ CASES = [
     dict(n=1, c=256, oc=64, hw=6, k=3, pad=1, S=8),                 # split reduction: separate rescale pass
     dict(n=3, c=33, oc=32, hw=(5, 8), k=1, S=16),                   # 1x1, one channel in the second block
     dict(n=1, c=32, oc=40, hw=(260, 264), k=3, pad=1, S=4),         # many pixel tiles: the persistent kernel variant
+    dict(n=2, c=128, oc=64, hw=14, k=3, pad=1, S=8),                # 3x3 with both operands in LDS, two teams
+    dict(n=2, c=32, oc=480, hw=50, k=3, pad=1, S=4),                # ... two half tiles per wave
 ]
 
 

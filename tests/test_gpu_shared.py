@@ -62,6 +62,17 @@ def _cases():
     c.append(("many_tiles_row_packed", _layer(rng, 1, 3, 33, (530, 540), 5, stride=2, pad=2, S=4, xkind="signed"), (0,)))
     # two half tiles per wave without the persistent variant: many channel blocks, few pixel tiles per block
     c.append(("two_half_tiles_many_blocks", _layer(rng, 1, 32, 250, (100, 120), 3, pad=1, S=4), (0,)))
+    # 3 x 3, stride 1, padding 1 with both operands in LDS, in each of its shapes: two teams that split the channel
+    # blocks (narrow and wide window), one team (ragged sizes, channel padding), one channel block on a wide image,
+    # two half tiles per wave with a tile that crosses an image boundary, and tiles that span many tiny images
+    c.append(("window_two_teams", _layer(rng, 2, 128, 64, 14, 3, pad=1, S=8), (0,)))
+    c.append(("window_two_teams_wide", _layer(rng, 1, 128, 32, 40, 3, pad=1, S=4), (0,)))
+    c.append(("window_ragged", _layer(rng, 3, 64, 40, (13, 11), 3, pad=1, S=8), (0,)))
+    c.append(("window_one_block_wide", _layer(rng, 1, 20, 33, (37, 45), 3, pad=1, S=4), (0,)))
+    c.append(("window_two_half_tiles", _layer(rng, 2, 32, 480, 50, 3, pad=1, S=4), (0,)))
+    c.append(("window_many_small_images", _layer(rng, 40, 128, 32, 4, 3, pad=1, S=8, xkind="signed"), (0,)))
+    c.append(("window_one_pixel_images", _layer(rng, 70, 64, 32, 1, 3, pad=1, S=8, xkind="signed"), (0,)))
+    c.append(("window_one_column_images", _layer(rng, 9, 64, 32, (17, 1), 3, pad=1, S=8, xkind="signed"), (0,)))
     c.append(("grouped", _layer(rng, 2, 8, 12, 7, 3, pad=1, groups=4, S=8), (0,)))
     c.append(("depthwise", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), (0,)))
     # 3 x 3 depthwise layers have a kernel of their own: odd channel count, stride 2, two outputs per input channel
@@ -108,6 +119,23 @@ def test_every_digit_plane_count(psb, orc, planes_case):
     assert np.array_equal(acc, ref)
     if planes_case[0] == "deep_window":
         assert np.abs(orc.sample_filter(qo, S, seed=8, layer_id=2)).max() >= 2 ** 24      # really four planes
+
+
+def test_four_digit_planes_on_a_3x3_layer(psb, orc):
+    """The both-operands-in-LDS kernel with four planes, with one team and with two."""
+    import torch
+    rng = np.random.default_rng(951)
+    kw = dict(exp_bits=5, x_absmax=1, s_max=2)
+    for c, hw in ((64, 9), (128, 12)):
+        w = (rng.standard_normal((40, c, 3, 3)) * 10.0 ** rng.uniform(-6, 0, size=(40, c, 3, 3))).astype(np.float32)
+        x = rng.integers(-1, 2, size=(3, c, hw, hw)).astype(np.int8)
+        qo = orc.QWeights(w.reshape(40, -1), **kw)
+        qg = psb.Weights(torch.from_numpy(w).cuda(), **kw)
+        ref, over = orc.conv2d_shared(qo, (40, c, 3, 3, 1), x, (1, 1), (1, 1), S=2, seed=8, layer_id=2)
+        assert over == 0
+        assert np.abs(orc.sample_filter(qo, 2, seed=8, layer_id=2)).max() >= 2 ** 24      # really four planes
+        acc = psb.conv2d(qg, torch.from_numpy(x).cuda(), 2, pad=(1, 1), seed=8, layer_id=2, shared=True).cpu().numpy()
+        assert np.array_equal(acc, ref), c
 
 
 def test_filter_value_between_the_ranges_of_two_and_three_digits(psb, orc):
@@ -167,6 +195,19 @@ def test_progressive_bit_exact_and_incremental(psb, orc, mapping):
     plain, _ = helpers.gpu_layer(psb, L, qg, S=8, shared=True)
     assert np.array_equal(const, plain)
     psb.set_mapping(psb.MAPPING_AUTO)
+
+
+def test_progressive_with_many_channel_blocks(psb, orc):
+    """Budget segments as masked, accumulating launches of the 3 x 3 kernel with two teams."""
+    rng = np.random.default_rng(982)
+    L = _layer(rng, 2, 128, 40, 12, 3, pad=1, S=8, s_max=8)
+    oh, ow = L.out_hw
+    to = rng.choice([0, 2, 4, 8], size=(2, oh, ow)).astype(np.uint8)
+    qo, qg = helpers.oracle_quantize(orc, L), helpers.gpu_quantize(psb, L)
+    ref, over, _ = helpers.oracle_layer(orc, L, qo, budget_to=to, shared=True)
+    assert over == 0
+    acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, shared=True)
+    assert np.array_equal(acc, ref)
 
 
 def test_progressive_on_a_large_image(psb, orc):
