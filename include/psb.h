@@ -261,6 +261,10 @@ int psb_conv2d_progressive_shared(const psb_weights_t* q, const int8_t* x_dev, c
  *     otherwise); n > 0 elements.
  * psb_maxpool2d_i8: NCHW int8 max-pooling; positions in the padding do not take part; needs 2*pad <= kernel
  *     (SHAPE otherwise).  out is [n][c][OH][OW] with the OH/OW rule of psb_conv_geom.
+ * psb_maxpool2d_i8_blocked: the same pooling on the blocked channels-last layout, x = [n][h][ceil(c/32)][w][32] and
+ *     out = [n][OH][ceil(c/32)][OW][32] (both 16-byte aligned, VALUE otherwise); the padding channels of a block are
+ *     pooled like the others (whatever they hold), so a chain of layers stays in this layout from the first
+ *     convolution on.
  * psb_global_avgpool_requantize: out[n][c] = clamp( rint( ((float)sum * fl(1/(h*w))) * scale ), lo, hi ),
  *     sum = exact integer sum over the h*w positions (h*w <= 2^23).
  * psb_budget_resample: a budget map at another resolution [Sect. 4.5: the two kinds of regions are applied
@@ -395,6 +399,9 @@ int psb_requantize(const float* y_dev, const float* res_f32_dev, const int8_t* r
 int psb_maxpool2d_i8(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, int32_t kh, int32_t kw,
                      int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int8_t* out_dev,
                      void* hip_stream);
+int psb_maxpool2d_i8_blocked(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, int32_t kh, int32_t kw,
+                             int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int8_t* out_dev,
+                             void* hip_stream);
 int psb_global_avgpool_requantize(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, float scale,
                                   int32_t lo, int32_t hi, int8_t* out_dev, void* hip_stream);
 int psb_budget_resample(const uint8_t* in_dev, int32_t n, int32_t h, int32_t w, int32_t oh, int32_t ow,

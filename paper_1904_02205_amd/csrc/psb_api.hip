@@ -1210,6 +1210,30 @@ int psb_maxpool2d_i8(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32
     return PSB_OK;
 }
 
+int psb_maxpool2d_i8_blocked(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, int32_t kh, int32_t kw,
+                             int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int8_t* out_dev,
+                             void* hip_stream)
+{
+    if (!x_dev || !out_dev) return PSB_ERR_NULL;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 ||
+        pad_w < 0)
+        return PSB_ERR_SHAPE;
+    if (2 * (int64_t)pad_h > kh || 2 * (int64_t)pad_w > kw || (int64_t)h + 2ll * pad_h < kh ||
+        (int64_t)w + 2ll * pad_w < kw)
+        return PSB_ERR_SHAPE;
+    if ((((uintptr_t)x_dev | (uintptr_t)out_dev) & 15u) != 0) return PSB_ERR_VALUE;
+    const int64_t OH = ((int64_t)h + 2ll * pad_h - kh) / stride_h + 1, OW = ((int64_t)w + 2ll * pad_w - kw) / stride_w + 1;
+    const int64_t cb = ((int64_t)c + 31) / 32;
+    if ((int64_t)n * cb * 32 * h * w >= (1ll << 40) || OH > 2147483647ll || OW > 2147483647ll || cb > 2147483647ll)
+        return PSB_ERR_TOO_LARGE;
+    const int64_t total = (int64_t)n * OH * cb * OW * 2;
+    const int blocks = (int)std::min<int64_t>((total + 255) / 256, 65536);
+    hipLaunchKernelGGL(psb::k_maxpool_blocked_i8, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, x_dev, n, (int)cb, h, w,
+                       kh, kw, stride_h, stride_w, pad_h, pad_w, (int)OH, (int)OW, out_dev);
+    PSB_HIP_TRY(hipGetLastError());
+    return PSB_OK;
+}
+
 int psb_global_avgpool_requantize(const int8_t* x_dev, int32_t n, int32_t c, int32_t h, int32_t w, float scale,
                                   int32_t lo, int32_t hi, int8_t* out_dev, void* hip_stream)
 {

@@ -124,6 +124,56 @@ __global__ void __launch_bounds__(256) k_maxpool_3x3s2p1_i8(const int8_t* __rest
     }
 }
 
+// Max-pooling on the blocked channels-last layout [N][H][C/32][W][32] (in and out): one thread per output pixel and
+// half block of 16 channels, a 16-byte load per window position, sixteen byte-wise maxima at once.  Bytes are
+// compared as unsigned numbers after their sign bits are flipped, two at a time as the 16-bit halves of a
+// register (v_pk_max_u16): even bytes in one register, odd bytes in another.  Zero is the flipped -128: positions
+// in the padding do not take part.
+__global__ void __launch_bounds__(256) k_maxpool_blocked_i8(const int8_t* __restrict__ x, int N, int CB, int H, int W, int KH,
+                                                            int KW, int stride_h, int stride_w, int pad_h, int pad_w, int OH,
+                                                            int OW, int8_t* __restrict__ out)
+{
+    typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+    const int64_t total = (int64_t)N * OH * CB * OW * 2;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int half = (int)(i & 1);
+        int64_t r = i >> 1;
+        const int ox = (int)(r % OW); r /= OW;
+        const int cb = (int)(r % CB); r /= CB;
+        const int oy = (int)(r % OH);
+        const int64_t n = r / OH;
+        u16x2 even[4], odd[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) even[d] = odd[d] = u16x2{0, 0};
+        for (int dy = 0; dy < KH; ++dy) {
+            const int iy = oy * stride_h - pad_h + dy;
+            if ((unsigned)iy >= (unsigned)H) continue;
+            const int8_t* row = x + (((n * H + iy) * CB + cb) * (int64_t)W) * 32 + 16 * half;
+            for (int dx = 0; dx < KW; ++dx) {
+                const int ix = ox * stride_w - pad_w + dx;
+                if ((unsigned)ix >= (unsigned)W) continue;
+                const uint4 v = *reinterpret_cast<const uint4*>(row + (int64_t)ix * 32);
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const uint32_t f = w[d] ^ 0x80808080u;
+                    const uint32_t e = __builtin_amdgcn_perm(0u, f, 0x0c020c00u);     // bytes 0 and 2, zero-extended
+                    const uint32_t o = __builtin_amdgcn_perm(0u, f, 0x0c030c01u);     // bytes 1 and 3
+                    even[d] = __builtin_elementwise_max(even[d], __builtin_bit_cast(u16x2, e));
+                    odd[d] = __builtin_elementwise_max(odd[d], __builtin_bit_cast(u16x2, o));
+                }
+            }
+        }
+        uint32_t res[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d)      // byte 0, byte 1, byte 2, byte 3 = even.lo, odd.lo, even.hi, odd.hi
+            res[d] = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, odd[d]), __builtin_bit_cast(uint32_t, even[d]), 0x06020400u) ^
+                     0x80808080u;
+        *reinterpret_cast<uint4*>(out + ((((n * OH + oy) * CB + cb) * (int64_t)OW + ox) * 32 + 16 * half)) =
+            make_uint4(res[0], res[1], res[2], res[3]);
+    }
+}
+
 // One wave per (n, c) image: exact int32 sum, then two rounded multiplications.
 __global__ void __launch_bounds__(256) k_avgpool_requantize(const int8_t* __restrict__ x, int64_t images, int HW,
                                                             float inv_count, float scale, float lo, float hi,

@@ -115,15 +115,20 @@ class ResNet18:
         bkw = dict(budget=budget, maps=maps)
         if budget is None:
             psb.shared_prepare_filters(self.q, S, [self.seed] * n_layers, list(range(n_layers)))
-            a = self._conv_requant(0, self.x0, S, None, True, inv_relu)
         else:
             psb.shared_prepare_filters_levels(self.q[:-1], self._levels, [self.seed] * (n_layers - 1),
                                               list(range(n_layers - 1)))
-            a = self._chain_call(0, self.x0, tuple(self.x0.shape), S, inv_relu, 0, **bkw)
-        keep(a)
-        a = psb.maxpool2d_i8(a, (3, 3), (2, 2), (1, 1))
-        keep(a)
-        shape, blocked = tuple(a.shape), False      # logical [N, C, H, W] of `a` and its layout
+        # the first convolution reads the network input as it is and writes the blocked layout; the pooling and
+        # every convolution after it read and write that layout
+        sp = self.net.specs[0]
+        oh = (self.x0.shape[2] + 2 * sp.pad - sp.k) // sp.stride + 1
+        shape = (self.x0.shape[0], sp.cout, oh, oh)
+        a = self._chain_call(0, self.x0, tuple(self.x0.shape), S, inv_relu, psb.BLOCKED_OUT, **bkw)
+        keep(a, shape)
+        a = psb.maxpool2d_i8_blocked(a, shape, (3, 3), (2, 2), (1, 1))
+        shape = (shape[0], shape[1], (oh + 2 - 3) // 2 + 1, (oh + 2 - 3) // 2 + 1)
+        keep(a, shape)
+        blocked = True                              # logical [N, C, H, W] of `a` is `shape`
         step_a = rs.STEP_RELU
         i = 1
         B_IN, B_OUT, B_RES = psb.BLOCKED_IN, psb.BLOCKED_OUT, psb.BLOCKED_RES

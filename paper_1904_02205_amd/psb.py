@@ -21,7 +21,7 @@ MAPPING_AUTO, MAPPING_PIXEL_LANE, MAPPING_CHANNEL_LANE, MAPPING_PRODUCT_LIST = 0
 SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "psb_weights_destroy",
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
            "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
-           "psb_conv2d_requant", "psb_conv2d_requant_static", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_shared_prepare_filters_levels", "psb_conv2d_shared_budget_requant_blocked", "psb_shared_budget_levels", "psb_requantize", "psb_maxpool2d_i8", "psb_global_avgpool_requantize", "psb_budget_resample",
+           "psb_conv2d_requant", "psb_conv2d_requant_static", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_shared_prepare_filters_levels", "psb_conv2d_shared_budget_requant_blocked", "psb_shared_budget_levels", "psb_requantize", "psb_maxpool2d_i8", "psb_maxpool2d_i8_blocked", "psb_global_avgpool_requantize", "psb_budget_resample",
            "psb_attention_budget", "psb_last_device_error", "psb_build_id", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
            "psb_profile_read"]
 
@@ -98,6 +98,7 @@ def lib():
                                                 C.POINTER(Requant), vp, vp]
         L.psb_requantize.argtypes = [vp, vp, vp, f32, i32, f32, i32, i32, C.c_int64, vp, vp]
         L.psb_maxpool2d_i8.argtypes = [vp] + [i32] * 10 + [vp, vp]
+        L.psb_maxpool2d_i8_blocked.argtypes = [vp] + [i32] * 10 + [vp, vp]
         L.psb_global_avgpool_requantize.argtypes = [vp, i32, i32, i32, i32, f32, i32, i32, vp, vp]
         L.psb_budget_resample.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
         L.psb_attention_budget.argtypes = [vp, f32, i32, i32, i32, i32, C.c_uint8, C.c_uint8, vp, vp, vp, vp]
@@ -481,6 +482,21 @@ def maxpool2d_i8(x, kernel, stride, pad, out=None):
     rc = lib().psb_maxpool2d_i8(_ptr(x, torch.int8, "x"), n, c, h, w, kernel[0], kernel[1], stride[0], stride[1],
                                 pad[0], pad[1], _ptr(out, torch.int8, "out"), _stream())
     _check(rc, "psb_maxpool2d_i8")
+    return out
+
+
+def maxpool2d_i8_blocked(x, x_shape, kernel, stride, pad, out=None):
+    """maxpool2d_i8 on the blocked channels-last layout: x is blocked_shape(*x_shape), x_shape = (N, C, H, W); returns
+    the blocked form of [N, C, OH, OW]."""
+    n, c, h, w = x_shape
+    oh, ow = (h + 2 * pad[0] - kernel[0]) // stride[0] + 1, (w + 2 * pad[1] - kernel[1]) // stride[1] + 1
+    _expect(x, blocked_shape(n, c, h, w), "x")
+    if out is None:
+        out = torch.empty(blocked_shape(n, c, max(oh, 0), max(ow, 0)), dtype=torch.int8, device=x.device)
+    _expect(out, blocked_shape(n, c, max(oh, 0), max(ow, 0)), "out")
+    rc = lib().psb_maxpool2d_i8_blocked(_ptr(x, torch.int8, "x"), n, c, h, w, kernel[0], kernel[1], stride[0], stride[1],
+                                        pad[0], pad[1], _ptr(out, torch.int8, "out"), _stream())
+    _check(rc, "psb_maxpool2d_i8_blocked")
     return out
 
 

@@ -119,6 +119,10 @@ def test_later_entry_points_validate_on_the_host(psb):
     assert mp(P, 1, 1, 8, 8, 3, 3, 0, 2, 1, 1, P, None) == psb.ERR_SHAPE              # stride 0
     assert mp(P, 1, 1, 8, 8, 2, 2, 2, 2, 2, 2, P, None) == psb.ERR_SHAPE              # a window inside the padding
     assert mp(P, 1, 1, 2, 2, 5, 5, 1, 1, 1, 1, P, None) == psb.ERR_SHAPE              # kernel larger than padded image
+    mb = L.psb_maxpool2d_i8_blocked
+    assert mb(None, 1, 1, 8, 8, 3, 3, 2, 2, 1, 1, P, None) == psb.ERR_NULL
+    assert mb(P, 1, 1, 8, 8, 3, 3, 2, 0, 1, 1, P, None) == psb.ERR_SHAPE
+    assert mb(P, 1, 1, 8, 8, 2, 2, 2, 2, 2, 2, P, None) == psb.ERR_SHAPE
     ap = L.psb_global_avgpool_requantize
     assert ap(None, 1, 1, 7, 7, 1.0, 0, 127, P, None) == psb.ERR_NULL
     assert ap(P, 0, 1, 7, 7, 1.0, 0, 127, P, None) == psb.ERR_SHAPE
@@ -230,6 +234,11 @@ def test_binding_refuses_wrong_tensor_shapes(psb):
         psb.maxpool2d_i8(xi, (3, 3), (2, 2), (1, 1), out=torch.zeros((2, 3, 4, 5), dtype=torch.int8))
     with pytest.raises(ValueError, match="out"):
         psb.global_avgpool_requantize(xi, 1.0, out=torch.zeros((2, 4), dtype=torch.int8))
+    with pytest.raises(ValueError, match="x"):
+        psb.maxpool2d_i8_blocked(xi, (2, 3, 8, 8), (3, 3), (2, 2), (1, 1))           # not the blocked form
+    with pytest.raises(ValueError, match="out"):
+        psb.maxpool2d_i8_blocked(torch.zeros((2, 8, 1, 8, 32), dtype=torch.int8), (2, 3, 8, 8), (3, 3), (2, 2), (1, 1),
+                                 out=torch.zeros((2, 4, 1, 5, 32), dtype=torch.int8))
     with pytest.raises(ValueError, match="out"):
         psb.budget_resample(torch.zeros((2, 4, 4), dtype=torch.uint8), 8, 8, out=torch.zeros((2, 8, 7), dtype=torch.uint8))
     with pytest.raises(ValueError, match="out"):

@@ -67,6 +67,25 @@ def test_maxpool(psb, orc, geom):
     assert np.array_equal(got, orc.maxpool_i8(x, kernel, stride, pad))
 
 
+@pytest.mark.parametrize("geom", [((3, 3), (2, 2), (1, 1), 3, 64, 112, 112), ((2, 2), (2, 2), (0, 0), 2, 40, 8, 8),
+                                  ((3, 2), (1, 2), (1, 0), 3, 5, 5, 7), ((1, 1), (1, 1), (0, 0), 1, 33, 4, 4),
+                                  ((3, 3), (2, 2), (1, 1), 2, 96, 9, 11), ((2, 2), (2, 2), (1, 1), 1, 32, 64, 64)])
+def test_maxpool_on_the_blocked_layout(psb, orc, geom):
+    """Same maxima as the oracle's [N][C][H][W] pooling; the layout conversions here are plain numpy."""
+    import torch
+    from test_gpu_blocked import to_blocked, from_blocked
+    kernel, stride, pad, n, c, h, w = geom
+    x = np.random.default_rng(h * w + c).integers(-128, 128, size=(n, c, h, w)).astype(np.int8)
+    got = psb.maxpool2d_i8_blocked(torch.from_numpy(to_blocked(x, -77)).cuda(), x.shape, kernel, stride, pad).cpu().numpy()
+    ref = orc.maxpool_i8(x, kernel, stride, pad)
+    assert got.shape == psb.blocked_shape(*ref.shape)
+    assert np.array_equal(from_blocked(got, c), ref)
+    with pytest.raises(psb.PsbError) as ei:        # the blocked tensors move as 16-byte words
+        flat = torch.zeros(int(np.prod(psb.blocked_shape(*x.shape))) + 16, dtype=torch.int8, device="cuda")
+        psb.maxpool2d_i8_blocked(flat[4:-12].view(psb.blocked_shape(*x.shape)), x.shape, kernel, stride, pad)
+    assert ei.value.code == psb.ERR_VALUE
+
+
 def test_maxpool_refuses_windows_that_can_lie_in_the_padding(psb):
     import torch
     with pytest.raises(psb.PsbError) as ei:
