@@ -515,6 +515,8 @@ int launch_shared(const psb_weights* q, const int8_t* x, const psb_conv_geom* g,
     p.tH = g->h; p.tW = g->w; p.tKH = q->shape.kh; p.tKW = q->shape.kw;
     p.t_stride_h = g->stride_h; p.t_stride_w = g->stride_w; p.t_pad_h = g->pad_h; p.t_pad_w = g->pad_w;
     if (rowpack) { p.tW = OW; p.tKW = 1; p.t_stride_w = 1; p.t_pad_w = 0; }
+    p.inv_OW = psb::inverse_of((uint32_t)OW); p.inv_OH = psb::inverse_of((uint32_t)OH);
+    p.inv_W1 = psb::inverse_of((uint32_t)p.tW + 1u); p.inv_H1 = psb::inverse_of((uint32_t)p.tH + 1u);
     const bool words = ((int64_t)OH * OW) % 4 == 0;
     p.quad_store = rq && rq->x_out && !rq->out_blocked && words && ((uintptr_t)rq->x_out & 3u) == 0;
     p.quad_res = rq && rq->res_i8 && !rq->res_blocked && words && ((uintptr_t)rq->res_i8 & 3u) == 0;

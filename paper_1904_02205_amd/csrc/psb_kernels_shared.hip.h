@@ -74,6 +74,9 @@ struct SharedParams {
     int seg_level[4];
     uint64_t seg_stride;
     float default_mult;
+    // floor(2^32 / d) for d = OW, OH, tW + 1, tH + 1 (inverse_of): the matrix-core kernels decompose pixel indices with
+    // a multiplication instead of a division (some 30 instructions each, per half tile and per pixel tile)
+    uint32_t inv_OW, inv_OH, inv_W1, inv_H1;
     Requant rq;
     // [N][OC][OH][OW] byte tensors of the fused requantisation move as 32-bit words (four pixels of one channel,
     // after a byte transpose over four lanes) when OH * OW and the tensor's address are multiples of 4:
@@ -477,9 +480,12 @@ struct TapCursor {
                                           const uint32_t (&origin)[2])
     {
         step = s;
-        cb = s % CB;
-        kw = (s / CB) % p.tKW;
-        kh = (s / CB) / p.tKW;
+        cb = kw = kh = 0;
+        if (s != 0) {                                  // uniform; most calls start at the first step
+            cb = s % CB;
+            kw = (s / CB) % p.tKW;
+            kh = (s / CB) / p.tKW;
+        }
         tap = (uint32_t)kh * row_stride + (uint32_t)kw * 32u;
         cboff = (uint32_t)cb * cb_stride;
         place(p, live, iy0, ix0, origin);
@@ -522,10 +528,11 @@ __device__ __forceinline__ void decode_half_tiles(const SharedParams& p, int64_t
         const int64_t pix = pix0 + 32 * h + col;
         const bool valid = pix < npix;
         const uint32_t pc = (uint32_t)(valid ? pix : npix - 1);       // the pixel count fits 32 bits (checked by the host)
-        const uint32_t row = pc / (uint32_t)p.OW;
-        ox_[h] = (int)(pc - row * (uint32_t)p.OW);
-        n_[h] = (int)(row / (uint32_t)p.OH);
-        oy_[h] = (int)(row - (uint32_t)n_[h] * (uint32_t)p.OH);
+        uint32_t ox, oy;
+        const uint32_t row = div_mod(pc, (uint32_t)p.OW, p.inv_OW, ox);
+        n_[h] = (int)div_mod(row, (uint32_t)p.OH, p.inv_OH, oy);
+        ox_[h] = (int)ox;
+        oy_[h] = (int)oy;
         live[h] = shared_pixel_range(p, pc, to_[h]) && valid;
         iy0[h] = oy_[h] * p.t_stride_h - p.t_pad_h;
         ix0[h] = ox_[h] * p.t_stride_w - p.t_pad_w;
@@ -1002,8 +1009,9 @@ __global__ void __launch_bounds__(256 * TEAMS, 2) k_conv3x3_window(const SharedP
     // the window: slot s holds virtual position q_first + s
     const int W1 = p.tW + 1, H1 = p.tH + 1;
     auto virtual_position = [&](uint32_t pix) {
-        const uint32_t row = pix / (uint32_t)p.OW, ox = pix - row * (uint32_t)p.OW;
-        const uint32_t n = row / (uint32_t)p.OH, oy = row - n * (uint32_t)p.OH;
+        uint32_t ox, oy;
+        const uint32_t row = div_mod(pix, (uint32_t)p.OW, p.inv_OW, ox);
+        const uint32_t n = div_mod(row, (uint32_t)p.OH, p.inv_OH, oy);
         return (n * (uint32_t)H1 + oy) * (uint32_t)W1 + ox;
     };
     const uint32_t pix_last = (uint32_t)(min(pix_first + kTile, npix) - 1);
@@ -1017,8 +1025,9 @@ __global__ void __launch_bounds__(256 * TEAMS, 2) k_conv3x3_window(const SharedP
     for (int e = 0; e < WS; ++e) {
         const uint32_t s = (uint32_t)(e * 256 + tid);
         const uint32_t q = q_first + s;
-        const uint32_t vr = q / (uint32_t)W1, vc = q - vr * (uint32_t)W1;
-        const uint32_t n = vr / (uint32_t)H1, rr = vr - n * (uint32_t)H1;
+        uint32_t vc, rr;
+        const uint32_t vr = div_mod(q, (uint32_t)W1, p.inv_W1, vc);
+        const uint32_t n = div_mod(vr, (uint32_t)H1, p.inv_H1, rr);
         const bool ok = s < n_slots && vc >= 1u && rr >= 1u && n < (uint32_t)p.N;
         goff[e] = ok ? (((n * (uint32_t)p.tH + (rr - 1u)) * (uint32_t)CB) * (uint32_t)p.tW + (vc - 1u)) * 32u : kOutOfRange;
     }
