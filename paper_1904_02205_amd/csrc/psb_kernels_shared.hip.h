@@ -97,12 +97,58 @@ struct FilterJob {
     int8_t* planes;           // operand-ordered digit planes, or null
 };
 
-// W[oc][k] for the job's sample range, from the weight's encoded word
-__device__ __forceinline__ int32_t sample_word(const FilterJob& j, uint32_t word, int oc, int k)
+// The ten pairs of round keys of a generator key: uniform over a job, so they are computed once per wave and kept
+// in scalar registers instead of being stepped inside every generator call.
+struct RoundKeys { uint32_t k0[10], k1[10]; };
+__device__ __forceinline__ RoundKeys round_keys(uint32_t key0, uint32_t key1)
+{
+    RoundKeys rk;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        rk.k0[r] = key0 + (uint32_t)r * kWeyl0;
+        rk.k1[r] = key1 + (uint32_t)r * kWeyl1;
+    }
+    return rk;
+}
+
+// count_below() for the whole generator blocks 0 .. NB - 1 of one weight (samples 0 .. 4 NB - 1): no per-sample
+// range tests, and what the blocks share is computed once - in round 0 the product with the output index, in round 1
+// the product with state word 2 (neither depends on the block number, whose own product is a constant).
+template <int NB>
+__device__ __forceinline__ uint32_t count_below_blocks(uint32_t o, uint32_t k, uint32_t layer, const RoundKeys& rk, uint32_t thr)
+{
+    uint32_t hi_a, lo_a, hi_b1, lo_b1;
+    mulhilo(kMulA, o, hi_a, lo_a);
+    const uint32_t z1 = hi_a ^ layer ^ rk.k1[0];               // state word 2 after round 0
+    mulhilo(kMulB, z1, hi_b1, lo_b1);
+    uint32_t n = 0;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        uint32_t hi_bj, lo_bj, hi_a1, lo_a1;
+        mulhilo(kMulB, (uint32_t)j, hi_bj, lo_bj);             // constants
+        const uint32_t x1 = hi_bj ^ k ^ rk.k0[0];              // state after round 0: (x1, lo_bj, z1, lo_a)
+        mulhilo(kMulA, x1, hi_a1, lo_a1);
+        u32x4 c{hi_b1 ^ lo_bj ^ rk.k0[1], lo_b1, hi_a1 ^ lo_a ^ rk.k1[1], lo_a1};      // after round 1
+#pragma unroll
+        for (int r = 2; r < 10; ++r) c = philox_round(c, rk.k0[r], rk.k1[r]);
+        n += (c.x < thr ? 1u : 0u) + (c.y < thr ? 1u : 0u) + (c.z < thr ? 1u : 0u) + (c.w < thr ? 1u : 0u);
+    }
+    return n;
+}
+
+// W[oc][k] for the job's sample range, from the weight's encoded word.  whole_blocks: 1..4 when the range is samples
+// 0 .. 4 whole_blocks - 1 of 32-bit uniforms (the usual call), else 0; rk: round_keys() of the job's key.
+__device__ __forceinline__ int32_t sample_word(const FilterJob& j, uint32_t word, int oc, int k, int whole_blocks = 0,
+                                               const RoundKeys* rk = nullptr)
 {
     if ((word & 0x7F800000u) == kDeadWord) return 0;
     const uint32_t thr = threshold_of(word & 0x7FFFFFu, j.prob_bits);
-    const uint32_t cnt = j.prob_bits <= 7
+    uint32_t cnt;
+    if (whole_blocks == 1) cnt = count_below_blocks<1>((uint32_t)oc, (uint32_t)k, j.layer_id, *rk, thr);
+    else if (whole_blocks == 2) cnt = count_below_blocks<2>((uint32_t)oc, (uint32_t)k, j.layer_id, *rk, thr);
+    else if (whole_blocks == 3) cnt = count_below_blocks<3>((uint32_t)oc, (uint32_t)k, j.layer_id, *rk, thr);
+    else if (whole_blocks == 4) cnt = count_below_blocks<4>((uint32_t)oc, (uint32_t)k, j.layer_id, *rk, thr);
+    else cnt = j.prob_bits <= 7
         ? count_below7((uint32_t)oc, (uint32_t)k, j.layer_id, j.key0, j.key1, thr, j.from, j.to)
         : count_below((uint32_t)oc, (uint32_t)k, j.layer_id, j.key0, j.key1, thr, j.from, j.to);
     const uint32_t mag = ((uint32_t)(j.to - j.from) + cnt) << ((word >> 23) & 0xFFu);   // < 2^31 by the overflow rule
@@ -186,16 +232,15 @@ __device__ __forceinline__ void sample_planes_block(const FilterJob& j, uint32_t
         word[g] = ok ? j.packed[(int64_t)oc * j.K + k_[g]] : kDeadWord;
     }
     const int plane = (int)(t & 3);
+    const RoundKeys rk = round_keys(j.key0, j.key1);
+    const int whole_blocks = (j.prob_bits > 7 && j.from == 0 && (j.to & 3) == 0 && j.to <= 16) ? j.to >> 2 : 0;   // uniform
 #pragma unroll
     for (int g = 0; g < kPlaneGroup; ++g) {
-        int64_t v = valid[g] ? sample_word(j, word[g], oc_[g], k_[g]) : 0;
-        uint32_t digits = 0;
-#pragma unroll
-        for (int b = 0; b < kMaxPlanes; ++b) {
-            const int8_t d = (int8_t)(v & 0xFF);       // balanced digit; the last one wraps, which is exact modulo 2^32
-            digits |= (uint32_t)(uint8_t)d << (8 * b);
-            v = (v - d) >> 8;
-        }
+        // Balanced base-256 digits d_b in [-128, 127] with v = sum d_b 256^b modulo 2^32, all four at once: adding 128
+        // to every digit gives the ordinary digits (0..255) of v + 0x80808080, and subtracting 128 from a byte
+        // flips its top bit.
+        const uint32_t v = valid[g] ? (uint32_t)sample_word(j, word[g], oc_[g], k_[g], whole_blocks, &rk) : 0u;
+        const uint32_t digits = (v + 0x80808080u) ^ 0x80808080u;
         const uint32_t out = quad_transpose_bytes(digits);
         if (plane < j.n_planes && blk0 + g < n_blk)
             *reinterpret_cast<uint32_t*>(j.planes + (((int64_t)(blk0 + g) * kMaxPlanes + plane) * 64 + ocl + 32 * (cl >> 4)) * 16 +
