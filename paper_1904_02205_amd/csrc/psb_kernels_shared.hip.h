@@ -171,8 +171,11 @@ __device__ __forceinline__ uint32_t quad_transpose_bytes(uint32_t d)
     const uint32_t d1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)d, 0x55, 0xF, 0xF, true);   // [1,1,1,1]
     const uint32_t d2 = (uint32_t)__builtin_amdgcn_mov_dpp((int)d, 0xAA, 0xF, 0xF, true);   // [2,2,2,2]
     const uint32_t d3 = (uint32_t)__builtin_amdgcn_mov_dpp((int)d, 0xFF, 0xF, 0xF, true);   // [3,3,3,3]
-    const int s = 8 * (int)(threadIdx.x & 3u);
-    return ((d0 >> s) & 0xFFu) | (((d1 >> s) & 0xFFu) << 8) | (((d2 >> s) & 0xFFu) << 16) | ((d3 >> s) << 24);
+    // byte j of d0, d1 into bytes 0, 1 and byte j of d2, d3 into bytes 2, 3 (selector byte 0x0c yields zero)
+    const uint32_t j = threadIdx.x & 3u;
+    const uint32_t lo = __builtin_amdgcn_perm(d1, d0, 0x0c0c0000u | ((4u + j) << 8) | j);
+    const uint32_t hi = __builtin_amdgcn_perm(d3, d2, 0x00000c0cu | ((4u + j) << 24) | (j << 16));
+    return lo | hi;
 }
 
 // x / d and x % d for any 32-bit x, given inv = floor(2^32 / d) (0xFFFFFFFF for d = 1): the product's high word
