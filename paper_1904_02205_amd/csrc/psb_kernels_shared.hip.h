@@ -77,6 +77,9 @@ struct SharedParams {
     // floor(2^32 / d) for d = OW, OH, tW + 1, tH + 1 (inverse_of): the matrix-core kernels decompose pixel indices with
     // a multiplication instead of a division (some 30 instructions each, per half tile and per pixel tile)
     uint32_t inv_OW, inv_OH, inv_W1, inv_H1;
+    // k_conv3x3_window: 1 = each XCD works on an eighth of the CHANNEL blocks (all pixel tiles) instead of an eighth of
+    // the pixel tiles (all channel blocks) - for layers whose weights outweigh their activations (set by the launcher)
+    int xcd_by_channels;
     Requant rq;
     // [N][OC][OH][OW] byte tensors of the fused requantisation move as 32-bit words (four pixels of one channel,
     // after a byte transpose over four lanes) when OH * OW and the tensor's address are multiples of 4:
@@ -1024,11 +1027,21 @@ __global__ void __launch_bounds__(256 * TEAMS, 2) k_conv3x3_window(const SharedP
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
     constexpr int kTile = 128 * HT;                             // pixels of a workgroup
     const unsigned n_tiles = (unsigned)((npix + kTile - 1) / kTile);
-    const unsigned wg = xcd_contiguous(blockIdx.x, n_tiles);
-    if (wg == 0xFFFFFFFFu) return;                 // uniform over the workgroup, before any barrier
+    unsigned wg;
+    int ocb;
+    if (p.xcd_by_channels) {
+        // the grid is n_tiles x (a multiple of 8 channel blocks); workgroup L of the launch runs on XCD L mod 8, which
+        // owns gridDim.y / 8 consecutive channel blocks: its L2 holds their weights and the (small) input
+        const unsigned linear = blockIdx.y * gridDim.x + blockIdx.x, local = linear >> 3, per_xcd = gridDim.y >> 3;
+        ocb = (int)((linear & 7u) * per_xcd + local % per_xcd);
+        wg = local / per_xcd;
+    } else {
+        wg = xcd_contiguous(blockIdx.x, n_tiles);
+        if (wg == 0xFFFFFFFFu) return;             // uniform over the workgroup, before any barrier
+        ocb = blockIdx.y;
+    }
     const int64_t pix_first = (int64_t)wg * kTile;
     const int64_t pix0 = pix_first + wave * (32 * HT);
-    const int ocb = blockIdx.y;
     const int CB = p.C_pad >> 5;
     const int cb_per_team = CB / TEAMS;            // the host checks that it divides
     const int cb_begin = team * cb_per_team;
@@ -1414,10 +1427,13 @@ inline void launch_conv_shared_mfma(const SharedParams& p, int planes, int resid
     const size_t lds = (size_t)n_steps * planes * kPlaneStride;
     const WindowPlan win = window_plan(p, planes, half_tiles, std::max(resident_wgs, 512) / 2);
     if (win.ok) {
-        const dim3 grid(columns, n_ocb);
-        const bool done = p.masked ? launch_window_out<kOutPartial>(p, planes, half_tiles, win, grid, stream)
-                        : p.rq.x_out ? launch_window_out<kOutRequant>(p, planes, half_tiles, win, grid, stream)
-                                     : launch_window_out<kOutAcc>(p, planes, half_tiles, win, grid, stream);
+        SharedParams pw = p;
+        // weights (digit planes) against activations, in bytes: worth it from about twice as many on (measured)
+        pw.xcd_by_channels = n_ocb % 8 == 0 && (int64_t)n_ocb * 32 * n_steps * 32 * planes > 2 * (int64_t)p.N * p.tH * p.tW * p.C_pad;
+        const dim3 grid(pw.xcd_by_channels ? (unsigned)tiles : columns, n_ocb);
+        const bool done = p.masked ? launch_window_out<kOutPartial>(pw, planes, half_tiles, win, grid, stream)
+                        : p.rq.x_out ? launch_window_out<kOutRequant>(pw, planes, half_tiles, win, grid, stream)
+                                     : launch_window_out<kOutAcc>(pw, planes, half_tiles, win, grid, stream);
         if (done) return;
     }
     // worth it when a workgroup gets more than one tile: staging the whole block before the first matrix instruction

@@ -71,6 +71,9 @@ def _cases():
     c.append(("window_one_block_wide", _layer(rng, 1, 20, 33, (37, 45), 3, pad=1, S=4), (0,)))
     c.append(("window_two_half_tiles", _layer(rng, 2, 32, 480, 50, 3, pad=1, S=4), (0,)))
     c.append(("window_many_small_images", _layer(rng, 40, 128, 32, 4, 3, pad=1, S=8, xkind="signed"), (0,)))
+    # ... and a weight-heavy layer (every XCD takes an eighth of the channel blocks instead of the pixel tiles)
+    c.append(("window_many_channel_blocks", _layer(rng, 3, 128, 250, 6, 3, pad=1, S=8, xkind="signed"), (0,)))
+    c.append(("window_sixteen_channel_blocks", _layer(rng, 2, 64, 512, 9, 3, pad=1, S=4), (0,)))
     c.append(("window_one_pixel_images", _layer(rng, 70, 64, 32, 1, 3, pad=1, S=8, xkind="signed"), (0,)))
     c.append(("window_one_column_images", _layer(rng, 9, 64, 32, (17, 1), 3, pad=1, S=8, xkind="signed"), (0,)))
     c.append(("grouped", _layer(rng, 2, 8, 12, 7, 3, pad=1, groups=4, S=8), (0,)))
