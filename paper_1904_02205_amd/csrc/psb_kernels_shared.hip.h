@@ -1010,13 +1010,14 @@ __global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const Shar
 // work on the SAME pixels with their own LDS regions; their sums meet in LDS at the end and team 0 runs the
 // epilogue.  This gives every SIMD two waves to interleave where the tile count alone would give it one.
 //
-// Unsplit, unsegmented calls (p.ksplit = 1, p.n_seg = 0); pixels that do not take part are computed and not stored.
+// Unsplit calls (p.ksplit = 1); pixels that do not take part in the call feed zeros and are not stored.
 // WS: window slots / 256.  Dynamic LDS: TEAMS * (kAregs + 2 WS) * 4096 bytes.
 template <int P, int OUT, int HT, int TEAMS, int WS>
 __global__ void __launch_bounds__(256 * TEAMS, 2) k_conv3x3_window(const SharedParams p)
 {
     extern __shared__ v4i win_lds[];
     __shared__ float s_mult[32], s_bias[32];
+    __shared__ int s_segments;                     // segments of the sample axis that some pixel of the workgroup reaches
     constexpr int kTaps = 9;
     constexpr int kAregs = (kTaps * P * 64 + 255) / 256;        // 16-byte weight words per thread and channel block
     constexpr int kTeamWords = (kAregs + 2 * WS) * 256;         // v4i per team
@@ -1050,7 +1051,10 @@ __global__ void __launch_bounds__(256 * TEAMS, 2) k_conv3x3_window(const SharedP
 
     // weights: word i = (tap * P + plane) * 64 + lane of a channel block's chunk is fetched by thread i mod 256
     const int8_t* const wblock = p.planes + (int64_t)ocb * p.n_ksteps * (kMaxPlanes * kPlaneStride);
-    const __amdgpu_buffer_rsrc_t w_rsrc = operand_buffer(wblock, (uint32_t)(p.n_ksteps + kStageSteps) * (kMaxPlanes * kPlaneStride));
+    auto segment_planes = [&](int seg) {           // the channel block in the digit planes of a segment's filter
+        return operand_buffer(wblock + (int64_t)seg * (int64_t)p.seg_stride, (uint32_t)(p.n_ksteps + kStageSteps) * (kMaxPlanes * kPlaneStride));
+    };
+    __amdgpu_buffer_rsrc_t w_rsrc = segment_planes(0);
     v4i stage_a[kAregs];
     uint32_t woff[kAregs];
 #pragma unroll
@@ -1130,7 +1134,24 @@ __global__ void __launch_bounds__(256 * TEAMS, 2) k_conv3x3_window(const SharedP
         s_bias[threadIdx.x] = (p.bias && oc < p.OC) ? p.bias[oc] : 0.0f;
     }
 
-    for (int c = 0; c < cb_per_team; ++c) {
+    // Budget map with announced levels (p.n_seg > 0): one pass over the channel blocks per segment of the sample axis,
+    // each with its own filter, into the same sums; a pixel that does not reach a segment feeds zeros.  Levels nest,
+    // so the workgroup runs the first n_seg segments, n_seg = the most that any of its pixels reaches.
+    int n_seg = 1;
+    if (p.n_seg > 0) {
+        int reached = 0;                             // wave-uniform
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i < p.n_seg && __ballot((live[0] && to_[0] >= p.seg_level[i]) || (live[1] && to_[1] >= p.seg_level[i])) != 0ull)
+                reached = i + 1;
+        if (threadIdx.x == 0) s_segments = 0;
+        __syncthreads();
+        if (lane == 0 && reached > 0) atomicMax(&s_segments, reached);
+        __syncthreads();
+        n_seg = max(s_segments, 1);                  // (a pass over nothing but zeros when no pixel takes part at all)
+    }
+    int seg = 0, c = 0;
+    for (int it = 0; it < n_seg * cb_per_team; ++it) {
         __syncthreads();                             // the previous channel block has been consumed by every wave
 #pragma unroll
         for (int r = 0; r < kAregs; ++r) a_lds[r * 256 + tid] = stage_a[r];
@@ -1142,15 +1163,28 @@ __global__ void __launch_bounds__(256 * TEAMS, 2) k_conv3x3_window(const SharedP
         __syncthreads();
         // the next block's operands travel while this one is multiplied (after the last block: the same again, so
         // that the loads in flight are the same on every path)
-        const int nxt = cb_begin + min(c + 1, cb_per_team - 1);
-        fetch_weights(nxt);
-        fetch_window(nxt);
+        bool lv[2] = {live[0], live[1]};             // pixels that take part in this segment
+        if (p.n_seg > 0) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) lv[h] = live[h] && to_[h] >= p.seg_level[seg];
+        }
+        int c_next = c + 1, seg_next = seg;
+        if (c_next == cb_per_team && seg + 1 < n_seg) { c_next = 0; seg_next = seg + 1; w_rsrc = segment_planes(seg_next); }
+        c_next = min(c_next, cb_per_team - 1);
+        fetch_weights(cb_begin + c_next);
+        fetch_window(cb_begin + c_next);
+        c = c_next;
+        seg = seg_next;
 
         v4i a[2][P], b[2][HT];
+        auto activation = [&](int h, int at) {       // zeros for a pixel outside the segment
+            const v4i v = b_lds[at];
+            return lv[h] ? v : v4i{0, 0, 0, 0};
+        };
 #pragma unroll
         for (int pl = 0; pl < P; ++pl) a[0][pl] = a_lds[pl * 64 + lane];
 #pragma unroll
-        for (int h = 0; h < HT; ++h) b[0][h] = b_lds[row_slot[h][0]];
+        for (int h = 0; h < HT; ++h) b[0][h] = activation(h, row_slot[h][0]);
 #pragma unroll
         for (int t = 0; t < kTaps; ++t) {
             if (t + 1 < kTaps) {
@@ -1158,7 +1192,7 @@ __global__ void __launch_bounds__(256 * TEAMS, 2) k_conv3x3_window(const SharedP
 #pragma unroll
                 for (int pl = 0; pl < P; ++pl) a[(t + 1) & 1][pl] = a_lds[((t + 1) * P + pl) * 64 + lane];
 #pragma unroll
-                for (int h = 0; h < HT; ++h) b[(t + 1) & 1][h] = b_lds[row_slot[h][kh] + kw];
+                for (int h = 0; h < HT; ++h) b[(t + 1) & 1][h] = activation(h, row_slot[h][kh] + kw);
             }
 #pragma unroll
             for (int pl = 0; pl < P; ++pl)
@@ -1366,7 +1400,7 @@ inline int window_slots(int kh, int kw, int stride_h, int stride_w, int pad_h, i
 inline WindowPlan window_plan(const SharedParams& p, int planes, int half_tiles, int n_cus)
 {
     WindowPlan w{false, 1, 1};
-    if (p.OH != p.tH || p.OW != p.tW || p.n_seg != 0 || p.ksplit != 1 || planes < 3) return w;
+    if (p.OH != p.tH || p.OW != p.tW || p.ksplit != 1 || planes < 3) return w;
     const int64_t T = 128 * half_tiles;
     const int slots = window_slots(p.tKH, p.tKW, p.t_stride_h, p.t_stride_w, p.t_pad_h, p.t_pad_w, p.tH, p.tW, half_tiles);
     if (slots == 0) return w;

@@ -40,6 +40,9 @@ CASES = [
     (dict(n=2, c=24, oc=24, hw=9, k=3, pad=1, groups=24, S=16), (8, 16), (3, 8, 16)),                # depthwise: direct kernel
     (dict(n=2, c=40, oc=70, hw=(9, 11), k=3, pad=1, S=16), (12,), (0, 11, 12, 13)),                  # one level
     (dict(n=2, c=40, oc=70, hw=(9, 11), k=3, pad=1, S=8), (8, 16, 200), (5, 8, 16, 100)),            # levels beyond s_max = 8
+    (dict(n=2, c=128, oc=64, hw=14, k=3, pad=1, S=16), (8, 16), (0, 8, 16)),                         # 3x3 from LDS, two teams
+    (dict(n=2, c=32, oc=480, hw=50, k=3, pad=1, S=8), (2, 4, 8), (0, 2, 4, 8)),                      # ... two half tiles
+    (dict(n=2, c=64, oc=256, hw=9, k=3, pad=1, S=16), (4, 16), (4, 16)),                             # ... XCDs by channels
 ]
 
 
