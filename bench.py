@@ -201,7 +201,11 @@ def prepare(workload, args, torch, psb, dev):
         q = psb.Weights(w, groups=L.groups, x_absmax=L.x_absmax, s_max=L.s_max, prob_bits=args.prob_bits)
         name = KERNEL_NAMES[psb.query_mapping(q, (L.x.shape[0], L.x.shape[2], L.x.shape[3]) + L.stride + L.pad)]
         if shared:
-            name = "k_conv_shared_mfma" if L.groups == 1 and args.mapping != 1 else "k_conv_shared_direct"
+            # matrix-core contraction: 3 x 3 / stride 1 / padding 1 layers normally run in k_conv3x3_window (both operands
+            # from LDS), the others in k_conv_shared_mfma; the library's timer covers whichever it launched
+            window = L.w.shape[2:] == (3, 3) and L.stride == (1, 1) and L.pad == (1, 1)
+            name = ("k_conv3x3_window" if window else "k_conv_shared_mfma") if L.groups == 1 and args.mapping != 1 \
+                else "k_conv_shared_direct"
             a, b = shared_ops(L, q)
             P.mfma_ops += a
             P.mfma_plane_ops += b
