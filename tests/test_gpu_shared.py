@@ -53,6 +53,7 @@ def _cases():
     c.append(("conv_wide_row", _layer(rng, 1, 8, 32, (3, 150), 3, pad=1, S=8), both))
     c.append(("pruned_pointwise", _layer(rng, 2, 96, 40, 5, 1, S=16, prune=0.9), both))
     c.append(("s255", _layer(rng, 1, 3, 8, 4, 3, pad=1, S=255, std=0.01), both))
+    c.append(("s12_three_generator_blocks", _layer(rng, 2, 40, 48, 10, 3, pad=1, S=12), both))
     c.append(("deep_reduction_few_pixels", _layer(rng, 1, 256, 64, 6, 3, pad=1, S=8), both))      # reduction split 4 ways
     c.append(("deep_linear", _layer(rng, 3, 2048, 40, 1, 1, S=4, xkind="u4", std=0.02), both))     # split 4 ways
     c.append(("row_packed_5x5_c6", _layer(rng, 2, 6, 20, (13, 17), 5, stride=2, pad=2, S=8, xkind="signed"), both))
