@@ -911,9 +911,9 @@ __global__ void __launch_bounds__(256, (P == 4 && HT == 2) ? 1 : 2) k_conv_share
 // over pixel tiles, `columns` apart; inside the walk there is no barrier and no staging, the kernel arguments and
 // the rescale factors are read once, and the four waves run independently of each other.  Unsplit, unmasked calls
 // only.  Dynamic LDS: n_steps * P * 1024 bytes.  gridDim.x is a multiple of 8, columns = the grid the plain kernel
-// would get.
-template <int P, int OUT>
-__global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const SharedParams p, unsigned columns)
+// would get.  HT: half tiles of 32 pixels per wave (a tile of the walk is 128 HT pixels).
+template <int P, int OUT, int HT>
+__global__ void __launch_bounds__(256, HT == 1 ? 4 : 2) k_conv_shared_mfma_resident(const SharedParams p, unsigned columns)
 {
     extern __shared__ v4i a_all[];                 // [n_steps][P][64]
     __shared__ float s_mult[32], s_bias[32];
@@ -940,31 +940,31 @@ __global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const Shar
     const uint32_t cb_stride = (uint32_t)p.tW * 32u;
     const uint32_t row_stride = (uint32_t)CB * cb_stride;
     const __amdgpu_buffer_rsrc_t xt_rsrc = operand_buffer(p.xt, p.xt_bytes);
-    const unsigned n_tiles = (unsigned)((npix + 255) / 256);
+    const unsigned n_tiles = (unsigned)((npix + 128 * HT - 1) / (128 * HT));
     for (unsigned v = blockIdx.x; v < columns; v += gridDim.x) {
         const unsigned wg = xcd_contiguous(v, n_tiles);     // each XCD keeps one contiguous eighth of the pixel tiles
         if (wg == 0xFFFFFFFFu) continue;
-        const int64_t pix0 = ((int64_t)wg * 4 + wave) * 64;
+        const int64_t pix0 = ((int64_t)wg * 4 + wave) * (32 * HT);
         bool live[2];
         int n_[2], oy_[2], ox_[2], to_[2], iy0[2], ix0[2];
         uint32_t origin[2];
-        decode_half_tiles<2>(p, pix0, col, g, CB, npix, live, n_, oy_, ox_, to_, iy0, ix0, origin);
+        decode_half_tiles<HT>(p, pix0, col, g, CB, npix, live, n_, oy_, ox_, to_, iy0, ix0, origin);
         if (__ballot(live[0] || live[1]) == 0ull) continue;      // wave-uniform; no barrier below
 
-        v16i acc[2][P];
+        v16i acc[HT][P];
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < HT; ++h)
 #pragma unroll
             for (int b = 0; b < P; ++b)
 #pragma unroll
                 for (int q = 0; q < 16; ++q) acc[h][b][q] = 0;
 
-        TapCursor<2> cur;
+        TapCursor<HT> cur;
         cur.start(p, 0, CB, cb_stride, row_stride, live, iy0, ix0, origin);
-        v4i opb[kDepth][2];
+        v4i opb[kDepth][HT];
         auto request = [&](int slot) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) opb[slot][h] = load_operand(xt_rsrc, cur.tap_off[h], cur.cboff);
+            for (int h = 0; h < HT; ++h) opb[slot][h] = load_operand(xt_rsrc, cur.tap_off[h], cur.cboff);
             cur.advance(p, n_steps, CB, cb_stride, row_stride, live, iy0, ix0, origin);
         };
 #pragma unroll
@@ -981,15 +981,15 @@ __global__ void __launch_bounds__(256, 2) k_conv_shared_mfma_resident(const Shar
                 for (int b = 0; b < P; ++b) a[(ks + 1) & 1][b] = a_all[(nxt * P + b) * 64 + lane];
                 if (s0 + ks < n_steps) {             // wave-uniform
 #pragma unroll
-                    for (int b = 0; b < P; ++b) {
-                        acc[0][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[ks][0], acc[0][b], 0, 0, 0);
-                        acc[1][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[ks][1], acc[1][b], 0, 0, 0);
-                    }
+                    for (int b = 0; b < P; ++b)
+#pragma unroll
+                        for (int h = 0; h < HT; ++h)
+                            acc[h][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks & 1][b], opb[ks][h], acc[h][b], 0, 0, 0);
                 }
                 request(ks);
             }
         }
-        tile_epilogue<P, OUT, 2>(p, acc, live, n_, oy_, ox_, to_, ocb, lane, s_mult, s_bias);
+        tile_epilogue<P, OUT, HT>(p, acc, live, n_, oy_, ox_, to_, ocb, lane, s_mult, s_bias);
     }
 }
 
@@ -1369,16 +1369,16 @@ inline void launch_conv_shared_mfma_out(const SharedParams& p, int planes, dim3 
     }
 }
 
-template <int OUT>
+template <int OUT, int HT>
 inline void launch_conv_shared_mfma_resident(const SharedParams& p, int planes, dim3 grid, unsigned columns, size_t lds,
                                              hipStream_t stream)
 {
     const dim3 block(256);
     switch (planes) {
-        case 1: hipLaunchKernelGGL((k_conv_shared_mfma_resident<1, OUT>), grid, block, lds, stream, p, columns); break;
-        case 2: hipLaunchKernelGGL((k_conv_shared_mfma_resident<2, OUT>), grid, block, lds, stream, p, columns); break;
-        case 3: hipLaunchKernelGGL((k_conv_shared_mfma_resident<3, OUT>), grid, block, lds, stream, p, columns); break;
-        default: hipLaunchKernelGGL((k_conv_shared_mfma_resident<4, OUT>), grid, block, lds, stream, p, columns); break;
+        case 1: hipLaunchKernelGGL((k_conv_shared_mfma_resident<1, OUT, HT>), grid, block, lds, stream, p, columns); break;
+        case 2: hipLaunchKernelGGL((k_conv_shared_mfma_resident<2, OUT, HT>), grid, block, lds, stream, p, columns); break;
+        case 3: hipLaunchKernelGGL((k_conv_shared_mfma_resident<3, OUT, HT>), grid, block, lds, stream, p, columns); break;
+        default: hipLaunchKernelGGL((k_conv_shared_mfma_resident<4, OUT, HT>), grid, block, lds, stream, p, columns); break;
     }
 }
 
@@ -1474,9 +1474,21 @@ inline void launch_conv_shared_mfma(const SharedParams& p, int planes, int resid
     // costs more than the chunked start of the plain kernel
     const unsigned fit = std::max(8u, (unsigned)std::max(resident_wgs, 0) / n_ocb / 8u * 8u);
     if (half_tiles == 2 && resident_wgs > 0 && !p.masked && p.n_seg == 0 && p.ksplit == 1 && lds <= 65536 && columns > fit) {
+        // A short reduction leaves the walk bound by the vector instructions of tile set-up and epilogue (the first
+        // convolution of a ResNet: ~1000 per tile and wave against 42 matrix instructions), which two waves per SIMD
+        // issue at half the rate four do: one half tile per wave then (half the accumulators, four waves per SIMD),
+        // when four workgroups' weight blocks fit the LDS of a CU (first convolution of config 4: 45 -> 37 us).
+        if (lds <= 36864) {
+            const unsigned columns1 = (unsigned)(((npix + 127) / 128 + 7) / 8 * 8);
+            const unsigned fit1 = std::max(8u, 2u * (unsigned)resident_wgs / n_ocb / 8u * 8u);
+            const dim3 grid(std::min(fit1, columns1), n_ocb);
+            if (p.rq.x_out) launch_conv_shared_mfma_resident<kOutRequant, 1>(p, planes, grid, columns1, lds, stream);
+            else launch_conv_shared_mfma_resident<kOutAcc, 1>(p, planes, grid, columns1, lds, stream);
+            return;
+        }
         const dim3 grid(fit, n_ocb);
-        if (p.rq.x_out) launch_conv_shared_mfma_resident<kOutRequant>(p, planes, grid, columns, lds, stream);
-        else launch_conv_shared_mfma_resident<kOutAcc>(p, planes, grid, columns, lds, stream);
+        if (p.rq.x_out) launch_conv_shared_mfma_resident<kOutRequant, 2>(p, planes, grid, columns, lds, stream);
+        else launch_conv_shared_mfma_resident<kOutAcc, 2>(p, planes, grid, columns, lds, stream);
         return;
     }
     const dim3 grid(columns, n_ocb, (unsigned)p.ksplit);
