@@ -446,6 +446,14 @@ int psb_set_mapping(int mapping);
  * TOO_LARGE; SHAPE also when mapping 2 is forced on a grouped layer).  Host only: no device work. */
 int psb_query_mapping(const psb_weights_t* q, const psb_conv_geom* geom);
 
+/* Shared-filter mode, host only (no device work; for tests): the number of 16-byte slots per half plane that the
+ * 3 x 3 kernel with both operands in LDS reserves for the input window of one pixel tile (128 * half_tiles consecutive
+ * output pixels, half_tiles = 1 or 2) of a layer with this geometry - an upper bound on
+ *     vpos(last pixel) - vpos(first pixel) + 2 (w + 1) + 3,   vpos(n, oy, ox) = (n (h + 1) + oy) (w + 1) + ox,
+ * over all tiles and batch sizes - or 0 when that kernel does not take the geometry (not 3 x 3 / stride 1 / padding 1,
+ * or more than 512 slots) and the call runs in the plain matrix-core kernel.  SHAPE for non-positive sizes. */
+int psb_shared_window_slots(int32_t kh, int32_t kw, const psb_conv_geom* geom, int32_t half_tiles);
+
 /* Timing of the sampling kernels, for benchmarks.  While enabled, every layer call
  * brackets its sampling kernel (not the zero-fill or the separate rescale kernel) with a
  * pair of HIP events on the caller's stream; at most 4096 pairs are kept between reads.

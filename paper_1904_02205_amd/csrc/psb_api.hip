@@ -715,6 +715,15 @@ int psb_set_mapping(int mapping)
     return prev;
 }
 
+int psb_shared_window_slots(int32_t kh, int32_t kw, const psb_conv_geom* geom, int32_t half_tiles)
+{
+    if (!geom) return PSB_ERR_NULL;
+    if (kh <= 0 || kw <= 0 || geom->h <= 0 || geom->w <= 0 || geom->stride_h <= 0 || geom->stride_w <= 0 || geom->pad_h < 0 ||
+        geom->pad_w < 0 || half_tiles < 1 || half_tiles > 2)
+        return PSB_ERR_SHAPE;
+    return psb::window_slots(kh, kw, geom->stride_h, geom->stride_w, geom->pad_h, geom->pad_w, geom->h, geom->w, half_tiles);
+}
+
 int psb_query_mapping(const psb_weights_t* q, const psb_conv_geom* geom)
 {
     if (!q || !geom) return PSB_ERR_NULL;

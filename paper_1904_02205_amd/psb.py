@@ -22,7 +22,7 @@ SYMBOLS = ["psb_quantize_weights", "psb_weights_info", "psb_weights_export", "ps
            "psb_conv2d_out_dims", "psb_linear", "psb_conv2d", "psb_conv2d_progressive",
            "psb_sample_filter", "psb_linear_shared", "psb_conv2d_shared", "psb_conv2d_progressive_shared",
            "psb_conv2d_requant", "psb_conv2d_requant_static", "psb_conv2d_shared_requant_blocked", "psb_shared_prepare_filters", "psb_shared_prepare_filters_levels", "psb_conv2d_shared_budget_requant_blocked", "psb_shared_budget_levels", "psb_requantize", "psb_maxpool2d_i8", "psb_maxpool2d_i8_blocked", "psb_global_avgpool_requantize", "psb_budget_resample",
-           "psb_attention_budget", "psb_last_device_error", "psb_build_id", "psb_set_mapping", "psb_query_mapping", "psb_profile_enable",
+           "psb_attention_budget", "psb_last_device_error", "psb_build_id", "psb_set_mapping", "psb_query_mapping", "psb_shared_window_slots", "psb_profile_enable",
            "psb_profile_read"]
 
 
@@ -105,6 +105,7 @@ def lib():
         L.psb_last_device_error.argtypes = []
         L.psb_set_mapping.argtypes = [C.c_int]
         L.psb_query_mapping.argtypes = [vp, C.POINTER(ConvGeom)]
+        L.psb_shared_window_slots.argtypes = [i32, i32, C.POINTER(ConvGeom), i32]
         L.psb_profile_enable.argtypes = [C.c_int]
         L.psb_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         for name in SYMBOLS:
@@ -169,6 +170,15 @@ def query_mapping(q, geom):
     rc = lib().psb_query_mapping(q._h, C.byref(ConvGeom(*geom)))
     if rc < 0:
         raise PsbError(rc, "psb_query_mapping")
+    return rc
+
+
+def shared_window_slots(kernel, geom, half_tiles):
+    """LDS window slots of the 3 x 3 shared-filter kernel for kernel = (kh, kw) and geom = (n, h, w, stride_h, stride_w,
+    pad_h, pad_w) with pixel tiles of 128 * half_tiles outputs; 0 when that kernel does not take the layer.  Host only."""
+    rc = lib().psb_shared_window_slots(int(kernel[0]), int(kernel[1]), C.byref(ConvGeom(*geom)), int(half_tiles))
+    if rc < 0:
+        raise PsbError(rc, "psb_shared_window_slots")
     return rc
 
 

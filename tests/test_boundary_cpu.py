@@ -255,3 +255,40 @@ def test_static_entry_point_rejects_on_the_host(psb):
     assert psb.STATIC_MAX_OUTPUTS == 8 * 1024 * 1024
     text = open(os.path.join(ROOT, "include", "psb.h")).read()
     assert "#define PSB_STATIC_MAX_OUTPUTS (8 * 1024 * 1024)" in text
+
+
+def test_window_of_the_3x3_shared_filter_kernel_covers_every_tile(psb):
+    """Host logic: the slot count that the launcher reserves per pixel tile is an upper bound of what any tile of
+    any batch needs - brute force over every tile start of small geometries - and geometries the kernel does not
+    take answer 0."""
+    def vpos(pix, h, w):
+        n, r = divmod(pix, h * w)
+        oy, ox = divmod(r, w)
+        return (n * (h + 1) + oy) * (w + 1) + ox
+    for h, w in ((1, 1), (1, 9), (9, 1), (2, 3), (4, 4), (7, 7), (14, 14), (5, 28), (28, 28), (13, 56), (56, 56), (3, 100)):
+        for ht in (1, 2):
+            T = 128 * ht
+            slots = psb.shared_window_slots((3, 3), (1, h, w, 1, 1, 1, 1), ht)
+            need = 0
+            period = h * w                               # tile starts repeat with the image
+            for start in range(0, period * T, T):        # every residue of a tile start modulo the image size
+                need = max(need, vpos(start + T - 1, h, w) - vpos(start, h, w) + 2 * (w + 1) + 3)
+                if start // T > 4 * period:
+                    break
+            if slots:
+                assert need <= slots <= 512, (h, w, ht, need, slots)
+            else:
+                assert need > 0                          # refused: more than 512 slots by the launcher's bound
+                rows, images = (T + w - 2) // w, (T + h * w - 2) // (h * w)
+                assert T - 1 + rows + images * (w + 1) + 2 * (w + 1) + 3 > 512
+    g = (2, 14, 14, 1, 1, 1, 1)
+    assert psb.shared_window_slots((3, 3), g, 1) > 0
+    for kernel, geom in (((1, 1), g), ((3, 1), g), ((5, 5), g), ((3, 3), (2, 14, 14, 2, 1, 1, 1)), ((3, 3), (2, 14, 14, 1, 1, 0, 1)),
+                         ((3, 3), (2, 14, 14, 1, 1, 1, 2)), ((3, 3), (1, 8, 300, 1, 1, 1, 1))):
+        assert psb.shared_window_slots(kernel, geom, 1) == 0, (kernel, geom)
+    L = psb.lib()
+    assert L.psb_shared_window_slots(3, 3, None, 1) == psb.ERR_NULL
+    gg = psb.ConvGeom(*g)
+    import ctypes
+    assert L.psb_shared_window_slots(3, 3, ctypes.byref(gg), 3) == psb.ERR_SHAPE
+    assert L.psb_shared_window_slots(0, 3, ctypes.byref(gg), 1) == psb.ERR_SHAPE
