@@ -58,7 +58,8 @@ CUS, SIMDS_PER_CU, LANES_PER_SIMD_CLK, CLOCK_HZ = 256, 4, 32, 2.4e9
 PEAK_TIOPS = CUS * SIMDS_PER_CU * LANES_PER_SIMD_CLK * CLOCK_HZ / 1e12     # 78.64 T simple int32 lane-ops/s
 WIDE = 2                   # units of a half-rate instruction (multiply, three operands, lane-mask producer/consumer)
 CALL_UNITS = 15 * WIDE + 31 + 4 * WIDE + 4 * WIDE                          # 77 per generator call (4 samples)
-CALL_UNITS_7BIT = 15 * WIDE + 31 + 4 * 4 + 1                               # 78 per generator call (16 samples)
+CALL_UNITS_7BIT = 15 * WIDE + 31 + 1                                       # 62 per generator call (16 samples) ...
+WORD_UNITS_7BIT = 4                                                        # ... + 4 per word of four samples it needs
 PRODUCT_UNITS = 2 * WIDE                                                   # v_mul_i32_i24 + v_mad_i32_i24
 KERNEL_NAMES = {1: "k_layer_pixel_lane", 2: "k_layer_oc_lane", 3: "k_layer_product_list"}
 PEAK_INT8_TOPS = 5000.0    # dense int8 MFMA, MI355X
@@ -89,9 +90,15 @@ def shared_ops(L, q):
     return ops, planes
 
 
-def lane_ops(n_calls, n_products, prob_bits=23):
-    """Simple-int32-lane-operation units of n_calls generator calls and n_products products (per lane)."""
-    return n_calls * (CALL_UNITS if prob_bits >= 8 else CALL_UNITS_7BIT) + n_products * PRODUCT_UNITS
+def lane_ops(n_calls, n_products, prob_bits=23, n_words=None):
+    """Simple-int32-lane-operation units of n_calls generator calls and n_products products (per lane).
+    n_words (7-bit uniforms): the words of four samples those calls have to compare (a budget of 8 needs two of a
+    call's four); None = four per call."""
+    if prob_bits >= 8:
+        return n_calls * CALL_UNITS + n_products * PRODUCT_UNITS
+    if n_words is None:
+        n_words = 4 * n_calls
+    return n_calls * CALL_UNITS_7BIT + n_words * WORD_UNITS_7BIT + n_products * PRODUCT_UNITS
 
 
 WORKLOADS = {
@@ -116,7 +123,8 @@ def workload_layers(name):
 
 def count_work(L, packed, per_call=4):
     """(sampled MACs, generator calls needed, products needed, sampled MACs with a non-zero activation, dense
-    sampled MACs counting padding and dead weights) of one layer call, from the exported weights.  Host arithmetic.
+    sampled MACs counting padding and dead weights, words of four samples needed) of one layer call, from the
+    exported weights.  Host arithmetic.
 
     sampled MACs: sum over outputs of budget x #(live taps inside the image).
     needed: the same restricted to taps whose activation is not 0; calls = ceil(budget/per_call) per such product.
@@ -152,7 +160,8 @@ def count_work(L, packed, per_call=4):
     products = float((taps_nz * (b > 0)).sum())
     smac_nz = float((taps_nz * b).sum())
     dense = float(b.sum()) * oc * cg * kh * kw
-    return smac, calls, products, smac_nz, dense
+    words = float((taps_nz * np.ceil(b / 4)).sum())
+    return smac, calls, products, smac_nz, dense, words
 
 
 def traffic_of(workload, mode, prob_bits):
@@ -195,7 +204,7 @@ def prepare(workload, args, torch, psb, dev):
     P.layers = layers
     P.per_call = 4 if args.prob_bits >= 8 else 16
     P.calls, P.kernels, P.layer_smac = [], [], []
-    P.smac = P.n_calls = P.n_prod = P.mfma_ops = P.mfma_plane_ops = P.smac_nz = P.smac_dense = 0.0
+    P.smac = P.n_calls = P.n_prod = P.n_words = P.mfma_ops = P.mfma_plane_ops = P.smac_nz = P.smac_dense = 0.0
     for L in layers:
         w = torch.from_numpy(L.w).to(dev)
         q = psb.Weights(w, groups=L.groups, x_absmax=L.x_absmax, s_max=L.s_max, prob_bits=args.prob_bits)
@@ -217,7 +226,8 @@ def prepare(workload, args, torch, psb, dev):
         acc = torch.empty((n, oc, oh, ow), dtype=torch.int32, device=dev)
         y = None if args.no_y else torch.empty((n, oc, oh, ow), dtype=torch.float32, device=dev)
         bt = None if L.budget_to is None else torch.from_numpy(L.budget_to).to(dev)
-        a, b, c, d, e = count_work(L, q.export(), P.per_call)
+        a, b, c, d, e, f = count_work(L, q.export(), P.per_call)
+        P.n_words += f
         P.smac += a
         P.n_calls += b
         P.n_prod += c
@@ -296,7 +306,7 @@ def measure(P, steps, warmup, torch, psb):
                     "int8_ops_per_launch": P.mfma_ops / launches_per_step,
                     "frac_with_digit_planes": with_planes / PEAK_INT8_TOPS}
     else:
-        ops_per_launch = lane_ops(P.n_calls, P.n_prod, P.prob_bits) / launches_per_step
+        ops_per_launch = lane_ops(P.n_calls, P.n_prod, P.prob_bits, P.n_words) / launches_per_step
         achieved = ops_per_launch / kern_s / 1e12
         roofline = {"bound": "alu", "achieved": achieved, "peak": PEAK_TIOPS,
                     "unit": "TIOP/s (simple int32 lane-ops)", "frac": achieved / PEAK_TIOPS,

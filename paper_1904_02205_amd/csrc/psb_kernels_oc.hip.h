@@ -82,8 +82,9 @@ __device__ __forceinline__ TapScalars tap_scalars(uint32_t s_x1, const Keys& key
 
 // Number of samples of block j of one product that are below thr.  P7: the block holds sixteen 7-bit
 // uniforms and thr the 7-bit threshold in each byte; otherwise four 32-bit uniforms.
-// VALID = 4: every sample of the block counts; 1..3 (32-bit uniforms only): the first VALID samples count
-// (the last block of a range that starts on a block boundary); 0: the range [from,to) is checked at run time.
+// VALID = 4: every sample of the block counts; 1..3: the first VALID samples count with 32-bit uniforms, the first
+// 4 VALID (whole words) with 7-bit uniforms (the last block of a range that starts on a block boundary);
+// 0: the range [from,to) is checked at run time.
 // state after round 1: (.., .., ts.sz ^ lo_a, ts.s_lo); words 0 and 1 were used in the per-pixel set-up.
 template <int VALID, bool P7>
 __device__ __forceinline__ uint32_t sample_block(uint32_t thr, TapScalars ts, const PixelHoist& h, uint32_t hz,
@@ -102,10 +103,13 @@ __device__ __forceinline__ uint32_t sample_block(uint32_t thr, TapScalars ts, co
     constexpr bool FULL = VALID == 4;
     uint32_t n = 0;
     if constexpr (P7) {
-        if (FULL) {
+        if constexpr (VALID > 0) {       // the first 4 VALID samples of the block: its first VALID words, whole
             const uint32_t all = 0x80808080u;
-            return 16u - (not_below7(c.x, thr, all) + not_below7(c.y, thr, all) + not_below7(c.z, thr, all) +
-                          not_below7(c.w, thr, all));
+            uint32_t not_below = not_below7(c.x, thr, all);
+            if (VALID > 1) not_below += not_below7(c.y, thr, all);
+            if (VALID > 2) not_below += not_below7(c.z, thr, all);
+            if (VALID > 3) not_below += not_below7(c.w, thr, all);
+            return (uint32_t)(4 * VALID) - not_below;
         }
         const int lo = max(from, 16 * j), hi = min(to, 16 * j + 16);
         return (uint32_t)(hi - lo) -
@@ -253,8 +257,10 @@ __device__ __forceinline__ int32_t process_list(uint32_t mylist, int cnt, const 
 // FIXED_NB > 0: every pixel draws generator blocks 0 .. FIXED_NB-1 completely (a call with one S everywhere that is
 // a whole number of blocks).  Only that path of the sampling loop is compiled then, which
 // takes 76 vector registers instead of 110 and measured 3 % faster than the kernel that can do everything.
+// FIXED_VALID < 4 (with FIXED_NB = 1, 7-bit uniforms): every pixel draws the first 4 FIXED_VALID samples of block 0
+// (S = 4, 8 or 12: a 16-sample block is more than such a call needs).
 // ppw: pixels per wave and ticket.
-template <int WAVES, int FIXED_NB = 0, bool FIXED_P7 = false>
+template <int WAVES, int FIXED_NB = 0, bool FIXED_P7 = false, int FIXED_VALID = 4>
 __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams p, int n_chunks, int kc,
                                                               uint32_t pixel_groups, uint32_t n_tickets,
                                                               uint32_t* __restrict__ sched, int ppw)
@@ -419,11 +425,18 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
 #define PSB_LIST(NB_, VALID_, P7_) \
     total = process_list<NB_, VALID_, P7_>(mylist, cnt, w_tile, lane, kbase, j0, nb, from, to, h, key)
                     if constexpr (FIXED_NB > 0) {
-                        PSB_LIST(FIXED_NB, 4, FIXED_P7);
+                        PSB_LIST(FIXED_NB, FIXED_VALID, FIXED_P7);
                     } else if constexpr (p7) {
                         if (full && nb == 1) PSB_LIST(1, 4, true);
                         else if (full && nb == 2) PSB_LIST(2, 4, true);
-                        else if (nb == 1) PSB_LIST(1, 0, true);
+                        else if (nb == 1 && (from & 15) == 0 && ((to - from) & 3) == 0) {
+                            // one block, its first whole words
+                            switch ((to - from) >> 2) {
+                                case 1: PSB_LIST(1, 1, true); break;
+                                case 2: PSB_LIST(1, 2, true); break;
+                                default: PSB_LIST(1, 3, true); break;
+                            }
+                        } else if (nb == 1) PSB_LIST(1, 0, true);
                         else PSB_LIST(0, 0, true);
                     } else {
                     if (full) {
@@ -532,10 +545,13 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
     // one S everywhere, a whole number of generator blocks for which a specialised kernel is built (0: none)
     const bool p7 = p.prob_bits <= 7;
     const int per_block = p7 ? 16 : 4;
-    int fixed_nb = 0;
+    int fixed_nb = 0, fixed_valid = 4;
     if (!p.budget_to && !p.budget_from && p.S % per_block == 0) {
         const int nb = p.S / per_block;
         if (p7 ? (nb == 1 || nb == 2) : (nb == 1 || nb == 2 || nb == 4 || nb == 8)) fixed_nb = nb;
+    } else if (!p.budget_to && !p.budget_from && p7 && p.S < 16 && p.S % 4 == 0) {
+        fixed_nb = 1;                       // part of one block of sixteen 7-bit uniforms: S / 4 whole words
+        fixed_valid = p.S / 4;
     }
     const int n_ocb = p.oc_pad / 64;
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
@@ -586,7 +602,17 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
 #define PSB_OC_LAUNCH(WAVES_, NB_, P7_)                                                                           \
     hipLaunchKernelGGL((k_layer_oc_lane<WAVES_, NB_, P7_>), dim3((unsigned)grid), dim3(WAVES_ * 64), 0, stream, p,   \
                        n_chunks, kc, (uint32_t)pixel_groups, (uint32_t)n_tickets, sched, ppw)
-    if (p7) {
+    if (p7 && fixed_nb == 1 && fixed_valid < 4) {
+        auto launch_valid = [&](auto valid_c) {
+            hipLaunchKernelGGL((k_layer_oc_lane<4, 1, true, decltype(valid_c)::value>), dim3((unsigned)grid), dim3(4 * 64), 0, stream,
+                               p, n_chunks, kc, (uint32_t)pixel_groups, (uint32_t)n_tickets, sched, ppw);
+        };
+        switch (fixed_valid) {
+            case 1: launch_valid(std::integral_constant<int, 1>{}); break;
+            case 2: launch_valid(std::integral_constant<int, 2>{}); break;
+            default: launch_valid(std::integral_constant<int, 3>{}); break;
+        }
+    } else if (p7) {
         switch (fixed_nb) {
             case 1: PSB_OC_LAUNCH(4, 1, true); break;
             case 2: PSB_OC_LAUNCH(4, 2, true); break;

@@ -103,6 +103,11 @@ def _cases():
     c.append(("conv_s20_k1", _layer(rng, 1, 9, 66, 6, 3, pad=1, S=20), 1, all3))
     c.append(("conv_s1_k2", _layer(rng, 1, 5, 7, 5, 3, pad=1, S=1), 2, all3))
     c.append(("conv_s255_k5", _layer(rng, 1, 3, 8, 4, 3, pad=1, S=255, std=0.01), 5, all3))
+    # 7-bit uniforms, a budget that is one, two or three whole words of a generator block
+    c.append(("conv_s8_k4", _layer(rng, 2, 20, 70, (9, 11), 3, pad=1, S=8, s_max=8), 4, all3))
+    c.append(("conv_s4_k6", _layer(rng, 1, 24, 64, (7, 6), 3, pad=1, S=4, xkind="signed"), 6, all3))
+    c.append(("conv_s12_k7", _layer(rng, 1, 17, 130, 6, 3, pad=1, S=12), 7, all3))
+    c.append(("linear_s8_k3", _layer(rng, 9, 200, 96, 1, 1, S=8, xkind="u4", std=0.05), 3, all3))
     c.append(("conv7x7_s2_k4", _layer(rng, 2, 3, 16, (23, 19), 7, stride=2, pad=3, S=16, xkind="signed"), 4, all3))
     c.append(("pruned_pointwise_k4", _layer(rng, 2, 96, 40, 5, 1, S=16, prune=0.9), 4, all3))
     c.append(("depthwise_k4", _layer(rng, 2, 70, 70, 9, 3, pad=1, groups=70, S=16), 4, (1, 3)))
@@ -158,6 +163,30 @@ def test_progressive_bit_exact_and_incremental(psb, orc, mapping):
         assert np.array_equal(a1, r1)
         a2, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, budget_from=first, acc_in=a1)
         assert np.array_equal(a2, ref)
+    psb.set_mapping(psb.MAPPING_AUTO)
+
+
+@pytest.mark.parametrize("mapping", [1, 2, 3])
+def test_budgets_of_whole_words(psb, orc, mapping):
+    """Budget maps whose values are multiples of four samples (7-bit uniforms: whole words of one generator block),
+    next to ranges that start inside a block."""
+    rng = np.random.default_rng(701)
+    L = _layer(rng, 2, 20, 70, (8, 9), 3, pad=1, S=16, s_max=16)
+    oh, ow = L.out_hw
+    to = rng.choice([0, 4, 8, 12, 16], size=(2, oh, ow)).astype(np.uint8)
+    qo = helpers.oracle_quantize(orc, L, prob_bits=5)
+    ref, over, _ = helpers.oracle_layer(orc, L, qo, budget_to=to)
+    assert over == 0
+    psb.set_mapping(mapping)
+    qg = helpers.gpu_quantize(psb, L, prob_bits=5)
+    acc, _ = helpers.gpu_layer(psb, L, qg, budget_to=to)
+    assert np.array_equal(acc, ref)
+    first = np.minimum(to, 4).astype(np.uint8)
+    a1, _ = helpers.gpu_layer(psb, L, qg, budget_to=first)
+    r1, _, _ = helpers.oracle_layer(orc, L, qo, budget_to=first)
+    assert np.array_equal(a1, r1)
+    a2, _ = helpers.gpu_layer(psb, L, qg, budget_to=to, budget_from=first, acc_in=a1)
+    assert np.array_equal(a2, ref)
     psb.set_mapping(psb.MAPPING_AUTO)
 
 
