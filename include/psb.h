@@ -30,12 +30,16 @@
  *                               times (largest exponent, per-channel exponent
  *                               histogram, class counts);
  *      psb_weights_export       synchronous copy;
- *      per-product layer calls  (psb_linear, psb_conv2d, psb_conv2d_progressive)
- *                               never allocate and never synchronise;
- *      psb_conv2d_requant       without acc_dev: the first such call on a handle, and any
- *                               with more outputs than before, allocates scratch
- *                               accumulators (a growing call first synchronises the
- *                               stream and frees the old ones);
+ *      per-product layer calls  (psb_linear, psb_conv2d, psb_conv2d_progressive,
+ *                               psb_conv2d_requant with shared = 0) never synchronise and
+ *                               never allocate, except when the channel-lane kernel cuts
+ *                               the tap reduction in chunks (more than 64 taps per output,
+ *                               or a layer too small to fill the chip otherwise): its
+ *                               partial sums meet in scratch accumulators owned by the
+ *                               handle, N*OH*OW x (OC rounded up to 64) int32, which the
+ *                               first such call on a handle, and any with more outputs
+ *                               than before, allocates (a growing call first synchronises
+ *                               the stream and frees the old ones);
  *      shared-filter calls      allocate workspaces owned by the handle on first use and
  *                               when an input is larger than any before (then also one
  *                               synchronisation); with a budget map and no announced
@@ -301,9 +305,9 @@ int psb_conv2d_requant(const psb_weights_t* q, const int8_t* x_dev, const psb_co
  * the scratch memory of its kernels - the ticket counter of the persistent layer kernel and the accumulators in
  * which the partial sums of a split tap reduction meet - is a fixed array inside the library's device code instead
  * of memory owned by the handle.  The call issues no hipMalloc, no hipFree and no synchronisation.
- *  - Limit: n * oc * OH * OW <= PSB_STATIC_MAX_OUTPUTS (the array holds that many int32 accumulators, 32 MiB, plus
- *    256 bytes; each GPU the library runs on holds it until the process ends).  Larger calls return TOO_LARGE and
- *    launch nothing.
+ *  - Limit: n * OH * OW * (oc rounded up to a multiple of 64) <= PSB_STATIC_MAX_OUTPUTS (the array holds that many
+ *    int32 accumulators, 32 MiB, plus 256 bytes; each GPU the library runs on holds it until the process ends).
+ *    Larger calls return TOO_LARGE and launch nothing.
  *  - All calls on one GPU share that GPU's array, and it keeps the last call's contents; the call clears what it
  *    needs (in a kernel, not a memset, so it can be captured).  Two such calls that overlap in time on one GPU -
  *    different streams without ordering - race on it; same-stream calls are ordered and safe.

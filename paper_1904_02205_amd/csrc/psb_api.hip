@@ -227,7 +227,8 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
     int32_t OH = 0, OW = 0;
     int rc = check_geom(&q->shape, g, &OH, &OW);
     if (rc != PSB_OK) return rc;
-    if (use_static_scratch && (int64_t)g->n * q->shape.oc * OH * OW > (int64_t)kStaticAccWords) return PSB_ERR_TOO_LARGE;
+    // the static array holds the partial sums with the channel count rounded up to whole blocks of 64
+    if (use_static_scratch && (int64_t)g->n * q->oc_pad * OH * OW > (int64_t)kStaticAccWords) return PSB_ERR_TOO_LARGE;
 
     psb::LayerParams p;
     fill_geometry(q, g, OH, OW, p);
@@ -245,15 +246,17 @@ int launch_layer(const psb_weights* q, const int8_t* x, const psb_conv_geom* g, 
     const int mapping = pick_mapping(q, p);
     if (mapping < 0) return mapping;
     uint32_t* sched = q->sched_dev;
+    // the channel-lane kernel combines the partial sums of a split tap reduction in scratch accumulators
+    const bool split = mapping == 2 && psb::oc_lane_chunks(p).n_chunks > 1;
     if (use_static_scratch) {           // ticket counter and accumulators in the static array: nothing is allocated
         uint32_t* base = nullptr;
         rc = static_scratch(dev, &base);
         if (rc != PSB_OK) return rc;
         sched = base;
-        if (!p.acc && mapping == 2) p.acc = reinterpret_cast<int32_t*>(base + kStaticHeadWords);
-    } else if (!p.acc && mapping == 2) {       // the channel-lane kernel may combine partial sums in the accumulators
-        p.acc = scratch_acc(q->ws, (size_t)p.N * p.OC * OH * OW * sizeof(int32_t), stream);
-        if (!p.acc) return PSB_ERR_ALLOC;
+        if (split) p.acc_cl = reinterpret_cast<int32_t*>(base + kStaticHeadWords);
+    } else if (split) {
+        p.acc_cl = scratch_acc(q->ws, (size_t)p.N * OH * OW * (size_t)p.oc_pad * sizeof(int32_t), stream);
+        if (!p.acc_cl) return PSB_ERR_ALLOC;
     }
 
     if (mapping == 2) {

@@ -181,6 +181,7 @@ struct LayerParams {
     const uint8_t* budget_to;  // [N][OH][OW] or null
     const uint8_t* budget_from;  // [N][OH][OW] or null (non-null: acc is read-modify-write)
     int32_t* acc;              // [N][OC][OH][OW]
+    int32_t* acc_cl;           // channel-lane kernel with a split tap reduction: partial sums [N*OH*OW][oc_pad]
     float* y;                  // same shape or null
     const float* mult;         // [OC] or null
     const float* bias;         // [OC] or null

@@ -100,7 +100,6 @@ __device__ __forceinline__ uint32_t sample_block(uint32_t thr, TapScalars ts, co
     c.z = hz ^ ts.s_lo;
     c.w = lo2;
     c = philox_rounds_3_to_9(c, key);
-    constexpr bool FULL = VALID == 4;
     uint32_t n = 0;
     if constexpr (P7) {
         if constexpr (VALID > 0) {       // the first 4 VALID samples of the block: its first VALID words, whole
@@ -330,12 +329,13 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
         static_assert(kOcMaxTaps <= 64, "one tap per lane");
         const bool has_tap = lane < kn;
         const int2 info = has_tap ? tap_tab[lane] : make_int2(0, 0);
-        struct Pixel { bool valid; int ox, oy, n; };
+        struct Pixel { bool valid; int ox, oy, n; uint32_t pix; };
         auto locate = [&](int pp) {
             const int64_t pix = ((int64_t)pgroup * ppw + pp) * WAVES + wave;       // wave-uniform
             Pixel q;
             q.valid = pix < npix;
             const uint32_t pc = q.valid ? (uint32_t)pix : 0u;      // the number of outputs fits 32 bits
+            q.pix = pc;
             const uint32_t row = pc / (uint32_t)p.OW;
             q.ox = (int)(pc - row * (uint32_t)p.OW);
             q.n = (int)(row / (uint32_t)p.OH);
@@ -470,7 +470,10 @@ __global__ void __launch_bounds__(WAVES * 64) k_layer_oc_lane(const LayerParams 
                     if (p.acc) p.acc[o] = total;
                     emit(p, o, oc, total, to);
                 } else if (total != 0) {
-                    atomicAdd(&p.acc[o], total);
+                    // the 64 channels of the wave are 64 consecutive words: the adds of a wave are one or two
+                    // requests of whole lines (in [N][OC][OH][OW] order they would be 64 lines, one plane apart,
+                    // which the memory side takes 16 times more slowly)
+                    atomicAdd(&p.acc_cl[(int64_t)me.pix * p.oc_pad + oc], total);
                 }
             }
         }
@@ -500,7 +503,51 @@ __global__ void __launch_bounds__(256) k_rescale(const LayerParams p)
         const int64_t pix = (i / (hw * p.OC)) * hw + (i % hw);
         int to = p.budget_to ? (int)p.budget_to[pix] : p.S;
         to = min(to, p.s_max);
-        emit(p, i, oc, p.acc[i], to);
+        int32_t v;
+        if (p.acc_cl) {     // partial sums of the channel-lane kernel, channels last (small layers: see below)
+            v = p.acc_cl[pix * p.oc_pad + oc];
+            if (p.budget_from) v += p.acc[i];
+            if (p.acc) p.acc[i] = v;
+        } else {
+            v = p.acc[i];
+        }
+        emit(p, i, oc, v, to);
+    }
+}
+
+// The same for the channel-lane kernel's split reduction, whose partial sums met in acc_cl [N*OH*OW][oc_pad]:
+// acc (if given; with budget_from it holds the earlier samples' sums and the new ones are added), rescaled value
+// and/or requantised activation, all [N][OC][OH][OW].  A workgroup moves a tile of 64 pixels x 64 channels through
+// LDS, so that it reads whole rows of channels and writes runs of 64 pixels.  (Layers whose partial sums fit the L2
+// several times over take k_rescale instead: one output per thread, more workgroups.)
+__global__ void __launch_bounds__(256) k_rescale_channels_last(const LayerParams p)
+{
+    __shared__ int32_t tile[64][65];
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int64_t pix0 = (int64_t)blockIdx.x * 64;
+    const int oc0 = blockIdx.y * 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll 4
+    for (int r = 0; r < 16; ++r) {
+        const int px = r * 4 + wave;
+        tile[lane][px] = (pix0 + px < npix) ? p.acc_cl[(pix0 + px) * p.oc_pad + oc0 + lane] : 0;
+    }
+    __syncthreads();
+    const int64_t pix = pix0 + lane;
+    if (pix >= npix) return;
+    const int64_t hw = (int64_t)p.OH * p.OW;
+    const int64_t n = pix / hw, rem = pix - n * hw;
+    int to = p.budget_to ? (int)p.budget_to[pix] : p.S;
+    to = min(to, p.s_max);
+#pragma unroll 4
+    for (int r = 0; r < 16; ++r) {
+        const int oc = oc0 + r * 4 + wave;
+        if (oc >= p.OC) break;
+        const int64_t o = (n * p.OC + oc) * hw + rem;
+        int32_t v = tile[r * 4 + wave][lane];
+        if (p.budget_from) v += p.acc[o];
+        if (p.acc) p.acc[o] = v;
+        emit(p, o, oc, v, to);
     }
 }
 
@@ -518,20 +565,21 @@ inline bool oc_lane_preferred(const LayerParams& p)
 typedef bool (*ProfileBegin)(hipStream_t, int*);
 typedef void (*ProfileEnd)(hipStream_t, int);
 
-inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t stream, ProfileBegin prof_begin,
-                          ProfileEnd prof_end)
+// benchmark overrides, read once per process (results do not depend on them)
+struct OcTuning { int max_taps = kOcMaxTaps, ppw = 0; };
+inline const OcTuning& oc_tuning()
 {
-    if (!oc_lane_supported(p)) return (int)hipErrorInvalidValue;
-    // benchmark overrides, read once per process (results do not depend on them)
-    struct Tuning { int max_taps = kOcMaxTaps, ppw = 0; };
-    static const Tuning tuning = [] {
-        Tuning t;
+    static const OcTuning tuning = [] {
+        OcTuning t;
         if (const char* v = std::getenv("PSB_OC_TAPS")) { const int n = std::atoi(v); if (n >= 1 && n <= kOcMaxTaps) t.max_taps = n; }
         if (const char* v = std::getenv("PSB_OC_PPW")) { const int n = std::atoi(v); if (n >= 1 && n <= 64) t.ppw = n; }
         return t;
     }();
-    int max_taps = tuning.max_taps;
-    constexpr int waves = kOcWaves;
+    return tuning;
+}
+
+inline int oc_lane_cus()
+{
     static int cus = 0;
     if (cus == 0) {
         int dev = 0, n = 0;
@@ -540,8 +588,42 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
             n = 256;
         cus = n;
     }
-    // resident workgroups: 160 KB of LDS hold four tiles; 512 VGPRs per lane hold four waves per SIMD
-    const int wg_per_cu = 4;
+    return cus;
+}
+
+// resident workgroups per CU: 160 KB of LDS hold four tiles; 512 VGPRs per lane hold four waves per SIMD
+constexpr int kOcWgPerCu = 4;
+
+// How the launcher cuts the tap reduction of a layer: n_chunks chunks of kc taps (at most kOcMaxTaps), as equal as
+// possible, none empty; a layer too small to give every resident workgroup a ticket gets shorter chunks (down to 16
+// taps) instead of leaving part of the chip idle.  With more than one chunk the partial sums meet in
+// LayerParams::acc_cl, which the caller provides.
+struct OcChunks { int n_chunks, kc; };
+inline OcChunks oc_lane_chunks(const LayerParams& p)
+{
+    int max_taps = oc_tuning().max_taps;
+    const int64_t n_ocb = p.oc_pad / 64;
+    const int64_t npix = (int64_t)p.N * p.OH * p.OW;
+    const int64_t pixel_groups = (npix + kOcWaves - 1) / kOcWaves;
+    OcChunks c;
+    for (;;) {
+        c.n_chunks = (p.K + max_taps - 1) / max_taps;
+        c.kc = (p.K + c.n_chunks - 1) / c.n_chunks;
+        c.n_chunks = (p.K + c.kc - 1) / c.kc;
+        if (pixel_groups * c.n_chunks * n_ocb >= (int64_t)oc_lane_cus() * kOcWgPerCu || max_taps <= 16) break;
+        max_taps /= 2;
+    }
+    return c;
+}
+
+inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t stream, ProfileBegin prof_begin,
+                          ProfileEnd prof_end)
+{
+    if (!oc_lane_supported(p)) return (int)hipErrorInvalidValue;
+    const OcTuning& tuning = oc_tuning();
+    constexpr int waves = kOcWaves;
+    const int cus = oc_lane_cus();
+    const int wg_per_cu = kOcWgPerCu;
     // one S everywhere, a whole number of generator blocks for which a specialised kernel is built (0: none)
     const bool p7 = p.prob_bits <= 7;
     const int per_block = p7 ? 16 : 4;
@@ -556,16 +638,9 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
     const int n_ocb = p.oc_pad / 64;
     const int64_t npix = (int64_t)p.N * p.OH * p.OW;
     int64_t pixel_groups = (npix + waves - 1) / waves;
-    // chunks of at most max_taps taps, as equal as possible, none empty; a layer too small to give every resident
-    // workgroup a ticket gets shorter chunks (down to 16 taps) instead of leaving part of the chip idle
-    int n_chunks, kc;
-    for (;;) {
-        n_chunks = (p.K + max_taps - 1) / max_taps;
-        kc = (p.K + n_chunks - 1) / n_chunks;
-        n_chunks = (p.K + kc - 1) / kc;
-        if (pixel_groups * n_chunks * n_ocb >= (int64_t)cus * wg_per_cu || max_taps <= 16) break;
-        max_taps /= 2;
-    }
+    const OcChunks chunks = oc_lane_chunks(p);
+    const int n_chunks = chunks.n_chunks, kc = chunks.kc;
+    if (n_chunks > 1 && !p.acc_cl) return (int)hipErrorInvalidValue;
     // Pixels per wave and ticket.  A ticket costs a draw, a restaging on small layers, three barriers and one
     // exposed activation load whatever it holds, so a ticket should hold some 10 us of sampling per wave (estimated
     // at half of the chunk's taps per pixel and 86 ns per generator call), which products of one or two calls only
@@ -586,14 +661,14 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
     pixel_groups = (npix + (int64_t)waves * ppw - 1) / ((int64_t)waves * ppw);
     const int64_t n_tickets = pixel_groups * n_chunks * n_ocb;
     if (n_tickets >= (1ll << 32) - 65536) return (int)hipErrorInvalidValue;
-    const int64_t total = npix * p.OC;
     const int64_t grid = std::min<int64_t>(n_tickets, (int64_t)cus * wg_per_cu);
 
     // the ticket counter starts at 0; partial sums of a split reduction meet in accumulators that start at 0
     {
-        const bool fill = n_chunks > 1 && !p.budget_from;
-        const int blocks = fill ? (int)std::min<int64_t>((total + 255) / 256, 8192) : 1;
-        hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(fill ? 256 : 64), 0, stream, p.acc, fill ? total : 0, sched);
+        const bool fill = n_chunks > 1;
+        const int64_t words = npix * p.oc_pad;
+        const int blocks = fill ? (int)std::min<int64_t>((words + 255) / 256, 8192) : 1;
+        hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(fill ? 256 : 64), 0, stream, p.acc_cl, fill ? words : 0, sched);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return (int)e;
     }
@@ -631,9 +706,14 @@ inline int launch_oc_lane(const LayerParams& p, uint32_t* sched, hipStream_t str
     if (timed) prof_end(stream, slot);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
-    if (n_chunks > 1 && (p.y || p.rq.x_out)) {
-        const int blocks = (int)std::min<int64_t>((total + 255) / 256, 8192);
-        hipLaunchKernelGGL(k_rescale, dim3(blocks), dim3(256), 0, stream, p);
+    if (n_chunks > 1) {
+        if ((npix + 63) / 64 > 2147483647ll) return (int)hipErrorInvalidValue;
+        const int64_t total = npix * p.OC;
+        if (total <= (1 << 20))
+            hipLaunchKernelGGL(k_rescale, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL(k_rescale_channels_last, dim3((unsigned)((npix + 63) / 64), (unsigned)n_ocb), dim3(256), 0,
+                               stream, p);
         e = hipGetLastError();
         if (e != hipSuccess) return (int)e;
     }

@@ -339,7 +339,8 @@ STATIC_MAX_OUTPUTS = 8 * 1024 * 1024
 def conv2d_requant_static(q, x, inv_step, x_out, S=None, budget_to=None, stride=(1, 1), pad=(0, 0), seed=0, layer_id=0,
                           relu=True, lo=0, hi=127, res_f32=None, res_i8=None, res_step=0.0, mult=None, bias=None, y=None):
     """psb_conv2d_requant_static: conv2d_requant without accumulators out (per-product mode) that allocates nothing;
-    the caller passes every tensor, x_out [N, OC, OH, OW] included.  At most STATIC_MAX_OUTPUTS output elements."""
+    the caller passes every tensor, x_out [N, OC, OH, OW] included.  At most STATIC_MAX_OUTPUTS output elements,
+    counted with OC rounded up to a multiple of 64."""
     g, shape = _geom(q, x, stride, pad)
     _expect_layer_io(q, shape, y=y, mult=mult, bias=bias, budget_to=budget_to, x_out=x_out, res_f32=res_f32,
                      res_i8=res_i8)

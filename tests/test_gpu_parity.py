@@ -227,6 +227,39 @@ def test_progressive_bit_exact_and_incremental(psb, orc, mapping):
     psb.set_mapping(psb.MAPPING_AUTO)
 
 
+def test_split_reduction_on_a_large_ragged_layer(psb, orc):
+    """More than 2^20 outputs, the tap reduction cut in two chunks: the partial sums meet channels-last and a tiled
+    pass turns them into [N][OC][OH][OW] accumulators and rescaled values.  100 channels (two blocks, the second
+    ragged), 11,550 pixels (not a multiple of the 64-pixel tile, images not a multiple of it either); a uniform call
+    with both outputs, then a refinement pair on budget maps."""
+    rng = np.random.default_rng(302)
+    L = _layer(rng, 2, 8, 100, (75, 77), 3, pad=1, S=4, s_max=8)
+    oh, ow = L.out_hw
+    assert 2 * 100 * oh * ow > (1 << 20)
+    psb.set_mapping(2)
+    try:
+        qo = helpers.oracle_quantize(orc, L)
+        qg = helpers.gpu_quantize(psb, L)
+        ref, over, _ = helpers.oracle_layer(orc, L, qo)
+        assert over == 0
+        mult = (rng.uniform(0.5, 2.0, size=100) * 2.0 ** qo.e_min).astype(np.float32)
+        bias = rng.standard_normal(100).astype(np.float32)
+        acc, y = helpers.gpu_layer(psb, L, qg, want_y=True, mult=mult, bias=bias)
+        assert np.array_equal(acc, ref)
+        assert np.array_equal(y, orc.rescale(ref, qo.e_min, S=4, s_max=8, mult=mult, bias=bias))
+        to = rng.choice([0, 1, 3, 4, 8], size=(2, oh, ow)).astype(np.uint8)
+        first = np.minimum(to, 3).astype(np.uint8)
+        r1, _, _ = helpers.oracle_layer(orc, L, qo, budget_to=first)
+        r2, _, _ = helpers.oracle_layer(orc, L, qo, budget_to=to)
+        a1, _ = helpers.gpu_layer(psb, L, qg, budget_to=first)
+        assert np.array_equal(a1, r1)
+        a2, y2 = helpers.gpu_layer(psb, L, qg, budget_to=to, budget_from=first, acc_in=a1, want_y=True, mult=mult, bias=bias)
+        assert np.array_equal(a2, r2)
+        assert np.array_equal(y2, orc.rescale(r2, qo.e_min, budget_to=to, s_max=8, mult=mult, bias=bias))
+    finally:
+        psb.set_mapping(psb.MAPPING_AUTO)
+
+
 def test_progressive_constant_map_equals_plain_call(psb):
     rng = np.random.default_rng(301)
     L = _layer(rng, 2, 10, 64, 6, 3, pad=1, S=8, s_max=16)

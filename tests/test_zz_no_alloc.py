@@ -58,3 +58,13 @@ def test_static_entry_point_matches_the_allocating_one():
     assert ei.value.code == psb.ERR_TOO_LARGE
     psb.conv2d_requant_static(q, x[:n - 1], 1.0, x_out[:n - 1], S=8, pad=(1, 1))      # exactly the limit
     torch.cuda.synchronize()
+    # the limit counts the channels rounded up to whole blocks of 64: 96 channels take the room of 128
+    q96 = psb.Weights(torch.from_numpy((rng.standard_normal((96, 64, 3, 3)) * 0.05).astype(np.float32)).cuda(), s_max=8)
+    rows = psb.STATIC_MAX_OUTPUTS // (128 * 256)
+    x = torch.zeros((1, 64, rows + 1, 256), dtype=torch.int8, device="cuda")
+    x_out = torch.zeros((1, 96, rows + 1, 256), dtype=torch.int8, device="cuda")
+    with pytest.raises(psb.PsbError) as ei:
+        psb.conv2d_requant_static(q96, x, 1.0, x_out, S=8, pad=(1, 1))
+    assert ei.value.code == psb.ERR_TOO_LARGE
+    psb.conv2d_requant_static(q96, x[:, :, :rows].contiguous(), 1.0, x_out[:, :, :rows].contiguous(), S=8, pad=(1, 1))
+    torch.cuda.synchronize()
