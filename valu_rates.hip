@@ -7,7 +7,7 @@
 // Output: per class, the time a SIMD needs per wave-instruction and the same in cycles.
 // These figures define the ALU roofline of bench.py.
 //
-// Build: hipcc --offload-arch=gfx950 -O3 valu_rates.hip -o valu_rates ; run: ./valu_rates [--json]
+// Build: hipcc --offload-arch=gfx950 -O3 -I paper_1904_02205_amd/csrc valu_rates.hip -o valu_rates ; run: ./valu_rates [--json]
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
