@@ -292,3 +292,14 @@ def test_window_of_the_3x3_shared_filter_kernel_covers_every_tile(psb):
     import ctypes
     assert L.psb_shared_window_slots(3, 3, ctypes.byref(gg), 3) == psb.ERR_SHAPE
     assert L.psb_shared_window_slots(0, 3, ctypes.byref(gg), 1) == psb.ERR_SHAPE
+
+
+def test_micro_benchmarks_compile(tmp_path):
+    """The two stand-alone micro-benchmarks beside bench.py build with the line build() uses."""
+    import subprocess
+    import __graft_entry__ as entry
+    for name in entry.MICRO_BENCHMARKS:
+        out = tmp_path / name
+        r = subprocess.run(entry.micro_benchmark_command(name, str(out)), capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr[-2000:]
+        assert out.exists()
