@@ -196,6 +196,85 @@ __global__ void __launch_bounds__(256) k_rate(uint32_t* out, uint32_t m, int ite
     }
 }
 
+// One generator round (two wide multiplies, four xors on their results) on the eight chains, in three instruction
+// orders: 0 = chain by chain (the "philox round" row above), 1 = the sixteen multiplies, then the 32 xors,
+// 2 = the multiplies of chain c between the xors of chain c - 1.  A mixed stream issues more slowly than its
+// parts, and the order moves it by some 10 %.
+template <int ORDER>
+__global__ void __launch_bounds__(256) k_rate_round(uint32_t* out, uint32_t m, int iters, unsigned long long* ticks)
+{
+    uint32_t a[kChains], b[kChains];
+#pragma unroll
+    for (int c = 0; c < kChains; ++c) {
+        a[c] = threadIdx.x * 2654435761u + c;
+        b[c] = blockIdx.x * 40503u + c * 7u + 1u;
+    }
+    auto mul = [&](uint64_t& p, uint32_t v) { asm volatile("v_mad_u64_u32 %0, vcc, %1, %2, 0" : "=v"(p) : "v"(v), "v"(m) : "vcc"); };
+    auto x2 = [&](uint32_t& x, uint32_t y) {
+        asm volatile("v_xor_b32_e32 %0, %1, %0" : "+v"(x) : "v"(y));
+        asm volatile("v_xor_b32_e32 %0, %1, %0" : "+v"(x) : "v"(m));
+    };
+    const unsigned long long c0 = __builtin_readcyclecounter();
+    const unsigned long long w0 = wall_clock64();
+    for (int it = 0; it < iters * kUnroll; ++it) {
+        uint64_t pa[kChains], pb[kChains];
+        if constexpr (ORDER == 0) {
+#pragma unroll
+            for (int c = 0; c < kChains; ++c) {
+                mul(pa[c], a[c]);
+                mul(pb[c], b[c]);
+                uint32_t x = (uint32_t)(pb[c] >> 32), y = (uint32_t)(pa[c] >> 32);
+                x2(x, (uint32_t)pa[c]);
+                x2(y, (uint32_t)pb[c]);
+                a[c] = x;
+                b[c] = y;
+            }
+        } else if constexpr (ORDER == 1) {
+#pragma unroll
+            for (int c = 0; c < kChains; ++c) {
+                mul(pa[c], a[c]);
+                mul(pb[c], b[c]);
+            }
+#pragma unroll
+            for (int c = 0; c < kChains; ++c) {
+                uint32_t x = (uint32_t)(pb[c] >> 32), y = (uint32_t)(pa[c] >> 32);
+                x2(x, (uint32_t)pa[c]);
+                x2(y, (uint32_t)pb[c]);
+                a[c] = x;
+                b[c] = y;
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c <= kChains; ++c) {
+                const int d = c - 1;
+                uint32_t x = 0, y = 0;
+                if (c < kChains) mul(pa[c], a[c]);
+                if (c > 0) {
+                    x = (uint32_t)(pb[d] >> 32);
+                    x2(x, (uint32_t)pa[d]);
+                }
+                if (c < kChains) mul(pb[c], b[c]);
+                if (c > 0) {
+                    y = (uint32_t)(pa[d] >> 32);
+                    x2(y, (uint32_t)pb[d]);
+                    a[d] = x;
+                    b[d] = y;
+                }
+            }
+        }
+    }
+    const unsigned long long c1 = __builtin_readcyclecounter();
+    const unsigned long long w1 = wall_clock64();
+    uint32_t r = 0;
+#pragma unroll
+    for (int c = 0; c < kChains; ++c) r ^= a[c] ^ b[c];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = r;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ticks[0] = c1 - c0;
+        ticks[1] = w1 - w0;
+    }
+}
+
 struct Result { double ns; double clock_ghz; };
 
 template <int OP>
@@ -229,6 +308,35 @@ static int run(uint32_t* out, unsigned long long* ticks_dev, int blocks, int wav
     return 0;
 }
 
+// ns per chain-round per SIMD (same operation count as the "philox round" row)
+template <int ORDER>
+static int run_round(uint32_t* out, unsigned long long* ticks_dev, int blocks, int waves_per_simd, Result* res)
+{
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    hipLaunchKernelGGL(k_rate_round<ORDER>, dim3(blocks), dim3(256), 0, 0, out, 0x9E3779B9u, 16, ticks_dev);   // warm-up
+    CHECK(hipDeviceSynchronize());
+    float best = 1e30f;
+    for (int rep = 0; rep < 5; ++rep) {
+        CHECK(hipEventRecord(e0, 0));
+        hipLaunchKernelGGL(k_rate_round<ORDER>, dim3(blocks), dim3(256), 0, 0, out, 0x9E3779B9u, kIters, ticks_dev);
+        CHECK(hipEventRecord(e1, 0));
+        CHECK(hipEventSynchronize(e1));
+        float ms = 0;
+        CHECK(hipEventElapsedTime(&ms, e0, e1));
+        if (ms < best) best = ms;
+    }
+    CHECK(hipGetLastError());
+    unsigned long long ticks[2];
+    CHECK(hipMemcpy(ticks, ticks_dev, sizeof(ticks), hipMemcpyDeviceToHost));
+    res->ns = (double)best * 1e6 / ((double)kIters * kUnroll * kChains * waves_per_simd);
+    res->clock_ghz = ticks[1] ? (double)ticks[0] / (double)ticks[1] * 0.1 : 0.0;
+    CHECK(hipEventDestroy(e0));
+    CHECK(hipEventDestroy(e1));
+    return 0;
+}
+
 template <int OP>
 static int run_all(uint32_t* out, unsigned long long* ticks, int simds, int waves_per_simd, std::vector<Result>& r)
 {
@@ -255,6 +363,16 @@ int main(int argc, char** argv)
     for (int i = 0; i < 4; ++i)
         if (run_all<0>(out, ticks, simds, wps[i], all[i])) return 2;
 
+    static const char* kOrderNames[3] = {"round, chain by chain: M M x x x x", "round, all multiplies, then all xors",
+                                         "round, multiplies of chain c between the xors of c-1"};
+    Result orders[4][3];
+    for (int i = 0; i < 4; ++i) {
+        const int blocks = simds * wps[i] / 4;
+        if (run_round<0>(out, ticks, blocks, wps[i], &orders[i][0])) return 2;
+        if (run_round<1>(out, ticks, blocks, wps[i], &orders[i][1])) return 2;
+        if (run_round<2>(out, ticks, blocks, wps[i], &orders[i][2])) return 2;
+    }
+
     if (json) {
         std::printf("{\"device\": \"%s\", \"cus\": %d, \"reported_clock_mhz\": %d, \"waves_per_simd\": [1, 2, 4, 8], \"ops\": {",
                     prop.gcnArchName, cus, prop.clockRate / 1000);
@@ -262,6 +380,10 @@ int main(int argc, char** argv)
             std::printf("%s\"%s\": {\"ns\": [%.4f, %.4f, %.4f, %.4f], \"measured_clock_ghz\": %.3f}", op ? ", " : "",
                         kNames[op], all[0][op].ns, all[1][op].ns, all[2][op].ns, all[3][op].ns, all[2][op].clock_ghz);
         }
+        std::printf("}, \"round_orders\": {");
+        for (int o = 0; o < 3; ++o)
+            std::printf("%s\"%s\": {\"ns\": [%.4f, %.4f, %.4f, %.4f], \"measured_clock_ghz\": %.3f}", o ? ", " : "",
+                        kOrderNames[o], orders[0][o].ns, orders[1][o].ns, orders[2][o].ns, orders[3][o].ns, orders[2][o].clock_ghz);
         std::printf("}}\n");
     } else {
         std::printf("device %s, %d CUs, reported clock %d MHz\n", prop.gcnArchName, cus, prop.clockRate / 1000);
@@ -270,6 +392,10 @@ int main(int argc, char** argv)
             std::printf("%-40s %7.3f %7.3f %7.3f %7.3f   clock %.3f GHz  -> %6.2f cycles\n", kNames[op], all[0][op].ns,
                         all[1][op].ns, all[2][op].ns, all[3][op].ns, all[2][op].clock_ghz,
                         all[2][op].ns * all[2][op].clock_ghz);
+        for (int o = 0; o < 3; ++o)
+            std::printf("%-52s %7.3f %7.3f %7.3f %7.3f   clock %.3f GHz  -> %6.2f cycles\n", kOrderNames[o], orders[0][o].ns,
+                        orders[1][o].ns, orders[2][o].ns, orders[3][o].ns, orders[2][o].clock_ghz,
+                        orders[2][o].ns * orders[2][o].clock_ghz);
     }
     CHECK(hipFree(out));
     CHECK(hipFree(ticks));
