@@ -46,8 +46,8 @@ struct PixelHoist {
 
 // Round keys and multipliers.  Everything here is wave-uniform and stays in scalar registers.  (An instruction
 // stream in which EVERY two-operand VALU instruction has a scalar-register source issues at half rate on gfx950 -
-// 4.2 vs 2.4 cycles per wave64 - but in this loop only 14 of 58 instructions per call have one, and copies of the
-// keys in vector registers measured no gain while costing 16 registers.)
+// 4.2 vs 2.4 cycles per wave64 - but in this loop only the key xors and the multiplies by the two constants have
+// one, and copies of the keys (16 registers) or of the two multipliers in vector registers measured no gain.)
 struct Keys {
     uint32_t k0[10], k1[10];
 };
