@@ -12,7 +12,9 @@
 //
 // The reduction over taps is split into chunks; with more than one chunk the partial
 // sums are combined with int32 atomic adds, which is exact in any order because the
-// accumulator arithmetic is modulo 2^32.
+// accumulator arithmetic is modulo 2^32.  They meet in scratch accumulators laid out
+// [N*OH*OW][OC padded to 64], where the 64 adds of a wave are consecutive words; a last
+// pass turns them into the [N][OC][OH][OW] outputs.
 //
 // Philox work saved without changing a bit of the result.  Counter = (o, k, j, layer).
 // Round 0 multiplies o and j; o is fixed per lane and pixel, j is a literal.  Round 1
