@@ -51,7 +51,9 @@ TRAFFIC_PROFILES = {("c4", "product", 23): "profiles/k_layer_oc_lane_config4.md"
                     ("c2", "product", 23): "profiles/k_layer_oc_lane_config2.md",
                     ("c3", "product", 23): "profiles/k_layer_oc_lane_config3.md",
                     ("c5", "product", 23): "profiles/k_layer_product_list_config5.md",
-                    ("c4", "shared", 23): "profiles/k_conv_shared_mfma_config4.md"}
+                    ("c4", "shared", 23): "profiles/k_conv_shared_mfma_config4.md",
+                    ("c2", "product", 4): "profiles/k_layer_oc_lane_7bit_config2_config4.md#config2",
+                    ("c4", "product", 4): "profiles/k_layer_oc_lane_7bit_config2_config4.md#config4"}
 
 # ---- ALU roofline constants (issue rates measured by valu_rates.hip) ------------------------------
 CUS, SIMDS_PER_CU, LANES_PER_SIMD_CLK, CLOCK_HZ = 256, 4, 32, 2.4e9
@@ -167,9 +169,13 @@ def count_work(L, packed, per_call=4):
 def traffic_of(workload, mode, prob_bits):
     """(bytes per launch, file) from the tracked counter summary of this workload, or (None, None)."""
     rel = TRAFFIC_PROFILES.get((workload, mode, prob_bits))
-    if rel is None or not os.path.exists(os.path.join(ROOT, rel)):
+    if rel is None:
         return None, None
-    m = re.search(r"traffic_bytes_per_launch:\s*([0-9][0-9,_]*)", open(os.path.join(ROOT, rel)).read())
+    rel, _, part = rel.partition("#")        # a summary of several workloads has one line per workload
+    if not os.path.exists(os.path.join(ROOT, rel)):
+        return None, None
+    key = "traffic_bytes_per_launch" + ("_" + part if part else "")
+    m = re.search(key + r":\s*([0-9][0-9,_]*)", open(os.path.join(ROOT, rel)).read())
     return (int(m.group(1).replace(",", "").replace("_", "")), rel) if m else (None, None)
 
 
