@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the PSB layer hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c1|c2|c3|c5|c4net] [--prob-bits 23|1..7]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c1|c2|c3|c5|c4net] [--prob-bits 23|1..7] [--per-layer]
                     [--mode product|shared] [--no-per-config] [--no-cpu-baseline]
 
 A step is one pass of the whole hot path over one batch of synthetic input that is already resident in HBM: the
@@ -209,7 +209,7 @@ def prepare(workload, args, torch, psb, dev):
         P.model.inputs = {}
     P.layers = layers
     P.per_call = 4 if args.prob_bits >= 8 else 16
-    P.calls, P.kernels, P.layer_smac = [], [], []
+    P.calls, P.kernels, P.layer_smac, P.layer_work = [], [], [], []
     P.smac = P.n_calls = P.n_prod = P.n_words = P.mfma_ops = P.mfma_plane_ops = P.smac_nz = P.smac_dense = 0.0
     for L in layers:
         w = torch.from_numpy(L.w).to(dev)
@@ -240,6 +240,7 @@ def prepare(workload, args, torch, psb, dev):
         P.smac_nz += d
         P.smac_dense += e
         P.layer_smac.append(a)
+        P.layer_work.append((b, c, f))
         P.calls.append((L, q, x, acc, y, bt))
     torch.cuda.synchronize()
     P.graph = None
@@ -322,6 +323,37 @@ def measure(P, steps, warmup, torch, psb):
             "launches_per_step": launches_per_step, "roofline": roofline}
 
 
+def per_layer(P, torch, psb, reps=5):
+    """Per-product mode: every layer of the workload on its own - sampling-kernel time (the library's HIP events),
+    its share of the ALU roofline and the time a SIMD spends per wave-level generator call."""
+    rows = []
+    for (L, q, x, acc, y, bt), smac, (calls, prods, words) in zip(P.calls, P.layer_smac, P.layer_work):
+        def call():
+            if bt is not None:
+                psb.conv2d_progressive(q, x, bt, None, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id,
+                                       acc=acc, y=y)
+            elif L.linear:
+                psb.linear(q, x.reshape(x.shape[0], -1), L.S, seed=L.seed, layer_id=L.layer_id,
+                           acc=acc.reshape(acc.shape[0], -1), y=None if y is None else y.reshape(y.shape[0], -1))
+            else:
+                psb.conv2d(q, x, L.S, stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id, acc=acc, y=y)
+        call()
+        torch.cuda.synchronize()
+        psb.profile_enable(True)
+        psb.profile_read()
+        for _ in range(reps):
+            call()
+        torch.cuda.synchronize()
+        ms, n = psb.profile_read()
+        psb.profile_enable(False)
+        kern_s = ms / max(n, 1) * 1e-3
+        rows.append({"layer": L.name, "x": list(L.x.shape), "w": list(L.w.shape), "S": L.S,
+                     "kernel_ms": kern_s * 1e3, "sampled_macs_per_s": smac / kern_s,
+                     "frac": lane_ops(calls, prods, P.prob_bits, words) / kern_s / 1e12 / PEAK_TIOPS,
+                     "ns_per_wave_call_per_simd": kern_s * 1e9 / (calls / 64 / (CUS * SIMDS_PER_CU))})
+    return rows
+
+
 def cpu_baseline(P, budget_smac=1.2e10):
     """The oracle, as it stands, on a bounded sample of the workload: for every layer of it as many randomly chosen
     output elements as an equal share of `budget_smac` sampled MACs needs (all of them if that is fewer)."""
@@ -377,6 +409,8 @@ def main():
     ap.add_argument("--no-per-config", action="store_true",
                     help="default workload only: skip the records of configurations 1, 2, 3 and 5")
     ap.add_argument("--no-y", action="store_true", help="skip the fp32 rescale output")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="per-product mode, configurations 1-5: add a record of every layer of the workload on its own")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 64 MiB device-to-device copy (reference dispatch for FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -419,6 +453,8 @@ def main():
                    "chained_pass": args.workload == "c4net" and args.mode == "shared"},
         "roofline": m["roofline"],
     }
+    if args.per_layer and args.mode == "product" and P.model is None:
+        out["per_layer"] = per_layer(P, torch, psb)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(P)
     if args.workload == "c4" and not args.no_per_config:
