@@ -176,6 +176,51 @@ def test_fused_requantisation_equals_layer_then_requantize(psb, orc, shared):
 
 # ------------------------------------------------------------------ the chained network
 
+def test_fused_requantisation_on_a_large_ragged_layer(psb, orc):
+    """The channel-lane kernel with a split tap reduction and more than 2^20 outputs: the tiled pass that turns the
+    channels-last partial sums into outputs also requantises (residual in either form, no ReLU, with and without an
+    accumulator output, with a budget map).  100 channels, 2 x 75 x 77 pixels: ragged in both directions."""
+    import torch
+    import helpers
+    from test_gpu_parity import _layer
+    rng = np.random.default_rng(78)
+    L = _layer(rng, 2, 8, 100, (75, 77), 3, pad=1, S=4, s_max=8)
+    oc = 100
+    oh, ow = L.out_hw
+    shape = (2, oc, oh, ow)
+    assert int(np.prod(shape)) > (1 << 20)
+    inv = float(np.float32(127.0 / 6.0))
+    mult = (rng.uniform(0.5, 2.0, size=oc) * 2.0 ** -6).astype(np.float32)
+    bias = rng.standard_normal(oc).astype(np.float32)
+    qo, qg = helpers.oracle_quantize(orc, L), helpers.gpu_quantize(psb, L)
+    x = torch.from_numpy(L.x).cuda()
+    res = (rng.standard_normal(shape) * 2).astype(np.float32)
+    res8 = rng.integers(0, 128, size=shape).astype(np.int8)
+    budget = rng.choice([0, 2, 4, 8], size=(2, oh, ow)).astype(np.uint8)
+    psb.set_mapping(2)
+    try:
+        for bt in (None, budget):
+            acc, _, _ = helpers.oracle_layer(orc, L, qo, budget_to=bt)
+            y = orc.rescale(acc, qo.e_min, S=None if bt is not None else L.S, s_max=L.s_max, budget_to=bt, mult=mult,
+                            bias=bias)
+            for kw_o, kw_g in ((dict(res_f32=res), dict(res_f32=torch.from_numpy(res).cuda())),
+                               (dict(res_i8=res8, res_step=np.float32(0.05)),
+                                dict(res_i8=torch.from_numpy(res8).cuda(), res_step=float(np.float32(0.05)))),
+                               (dict(relu=False, lo=-128, hi=127), dict(relu=False, lo=-128, hi=127))):
+                ref = orc.requantize(y, inv, **kw_o)
+                common = dict(S=None if bt is not None else L.S, budget_to=None if bt is None else torch.from_numpy(bt).cuda(),
+                              stride=L.stride, pad=L.pad, seed=L.seed, layer_id=L.layer_id,
+                              mult=torch.from_numpy(mult).cuda(), bias=torch.from_numpy(bias).cuda())
+                accg = torch.empty(shape, dtype=torch.int32, device="cuda")
+                got = psb.conv2d_requant(qg, x, inv, acc=accg, **common, **kw_g)
+                assert np.array_equal(accg.cpu().numpy(), acc)
+                assert np.array_equal(got.cpu().numpy(), ref), list(kw_o)
+                got2 = psb.conv2d_requant(qg, x, inv, want_acc=False, **common, **kw_g)
+                assert np.array_equal(got2.cpu().numpy(), ref), (list(kw_o), "no acc")
+    finally:
+        psb.set_mapping(psb.MAPPING_AUTO)
+
+
 def _compare(psb, orc, net, prob_bits=23, **kw):
     from paper_1904_02205_amd import network
     ref_acts, got_acts = [], []
