@@ -48,6 +48,8 @@ def test_static_entry_point_matches_the_allocating_one():
     keep.append(_case(psb, torch, rng, (64, 64, 3, 3), (1, 64, 9, 7), (2, 2), (1, 1), 8, False, 12, 2, False))
     keep.append(_case(psb, torch, rng, (128, 32, 3, 3), (2, 32, 12, 10), (1, 1), (1, 1), 0, True, 13, 3, True))
     keep.append(_case(psb, torch, rng, (64, 48, 1, 1), (3, 48, 6, 6), (1, 1), (0, 0), 4, False, 14, 4, False))
+    # more than 2^20 outputs: the tiled pass from the static partial sums to the outputs
+    keep.append(_case(psb, torch, rng, (64, 16, 3, 3), (2, 16, 102, 100), (1, 1), (1, 1), 8, False, 15, 5, True))
     # the limit is checked on the host: one output element too many launches nothing
     q = keep[0]
     n = psb.STATIC_MAX_OUTPUTS // (64 * 64 * 64) + 1
